@@ -1,0 +1,148 @@
+/*
+ * fingpt_hpc.h -- C ABI of the MI355X (gfx950) library for the factorised linear
+ * layer of FinGPT-HPC and its quantised finetuning form.
+ *
+ * Notation (row form): tokens are the M rows of X[M,K]; the factor pair is
+ * A[K,r], B[r,N] with r << K,N; H = X*A is the rank-r intermediate.  The paper
+ * writes the same layer with column vectors, y = B A x (Sec. 3.2, eq.
+ * "low_rank_layer"; Sec. 4.1 item 1 gives the row-form shapes A: n x r, B: r x n).
+ *
+ * Conventions for every entry point
+ *  - All matrices are row-major and contiguous.  Every data pointer is a DEVICE
+ *    pointer owned by the caller; the library never allocates, frees or retains
+ *    device memory.  Scratch comes from `workspace` (device pointer, 256-byte
+ *    aligned, size from fhpc_workspace_bytes); too small => FHPC_ERR_WORKSPACE
+ *    and nothing is launched.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued asynchronously; no call synchronises.  Inputs, outputs and
+ *    workspace must stay alive and untouched until the stream has passed the
+ *    call.  Outputs must not alias inputs.  Two calls that share a workspace
+ *    must be ordered on one stream.
+ *  - Shapes: M >= 1, r >= 1 arbitrary; K and N multiples of 8; data pointers
+ *    16-byte aligned; every matrix smaller than 2 GiB.  Violations return an
+ *    error code before anything is launched.
+ *  - Return value: FHPC_OK or an FHPC_ERR_* code.  Nothing throws, exits or
+ *    prints.  HIP launch failures map to FHPC_ERR_HIP.
+ *  - dA and dB are produced in fp32.  Split reductions over tokens use fp32
+ *    atomics, so their low-order bits may differ from run to run.
+ */
+#ifndef FINGPT_HPC_H
+#define FINGPT_HPC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dtype of X, A, B, Y, dY, dX, H (dA/dB are always fp32) */
+enum { FHPC_F32 = 0, FHPC_BF16 = 1 };
+
+/* storage scheme of the frozen base weight (Sec. 5.2 "Quantization": one scale
+ * per weight vector; here symmetric absmax, no zero point):
+ *  FHPC_Q_INT8_PER_CHANNEL: Wq int8 [N][K], scales fp16 [N] (vector = one output channel)
+ *  FHPC_Q_INT4_BLOCK:       Wq bytes [N][K/2], element k (even) in the low nibble and
+ *                           k+1 in the high nibble, two's complement 4-bit;
+ *                           scales fp16 [N][K/block] (vector = `block` consecutive k
+ *                           of one output channel); block must be 64. */
+enum { FHPC_Q_INT8_PER_CHANNEL = 8, FHPC_Q_INT4_BLOCK = 4 };
+
+enum {
+    FHPC_OK = 0,
+    FHPC_ERR_NULL = 1,        /* a required pointer is NULL */
+    FHPC_ERR_SHAPE = 2,       /* non-positive size, K or N not a multiple of 8, K % block != 0 */
+    FHPC_ERR_DTYPE = 3,       /* unknown dtype / qscheme */
+    FHPC_ERR_ALIGN = 4,       /* a data pointer is not 16-byte aligned (workspace: 256) */
+    FHPC_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than fhpc_workspace_bytes */
+    FHPC_ERR_UNSUPPORTED = 6, /* block != 64, matrix >= 2 GiB, ... */
+    FHPC_ERR_HIP = 7          /* a HIP call or kernel launch failed */
+};
+
+/* which entry point a workspace is sized for */
+enum { FHPC_OP_LOWRANK_FWD = 0, FHPC_OP_LOWRANK_BWD = 1, FHPC_OP_QLINEAR_FWD = 2, FHPC_OP_QLINEAR_BWD = 3 };
+
+/* Factorised linear layer, forward (Sec. 3.2 eq. low_rank_layer; Sec. 4.1 "Method 1"):
+ *   Y[M,N] = (X[M,K] * A[K,r]) * B[r,N].
+ * X, A, B, Y have `dtype`.  H_out (M x r, `dtype`), if not NULL, receives H = X*A for
+ * the backward pass.  bf16: fp32 accumulation, H rounded to bf16 between the two
+ * products.  f32: plain fp32 arithmetic throughout. */
+int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, void* H_out,
+                       int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Factorised linear layer, backward (the gradients of the layer above; the paper's
+ * forward/backward flow figure in Sec. 4.2 shows the data flow):
+ *   dH = dY * B^T;  dX[M,K] = dH * A^T (`dtype`);  dA[K,r] = X^T * dH (fp32);
+ *   dB[r,N] = H^T * dY (fp32).
+ * H_saved (M x r, `dtype`) may be NULL: H is then recomputed from X and A (the
+ * layer-local form of the recomputation of Sec. 4.2).  Any of dX, dA, dB may be NULL
+ * and is then skipped.  Outputs are overwritten. */
+int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* dY,
+                       const void* H_saved, void* dX, float* dA, float* dB,
+                       int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Finetuning layer, forward (Sec. 5.1 eq. new_linear_layer with the frozen weight
+ * stored quantised, Sec. 5.2):
+ *   Y[M,N] = X[M,K] * deq(Wq, scales)[K,N] + scaling * (X * A[K,r]) * B[r,N].
+ * X, A, B, Y, H_out are bf16.  deq(.)[k,n] = code[n][k] * scale(n, k); the product is
+ * rounded to bf16 when it enters the matrix unit.  H_out as above (unscaled X*A). */
+int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, void* Y, void* H_out,
+                        int64_t M, int64_t K, int64_t r, int64_t N,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Finetuning layer, backward; W is frozen (Sec. 5.1), so there is no dW:
+ *   dH = dY * B^T;  dX = dY * deq(W)^T + scaling * dH * A^T  (bf16);
+ *   dA = scaling * X^T * dH (fp32);  dB = scaling * (X*A)^T * dY (fp32).
+ * H_saved may be NULL (recompute).  Any of dX, dA, dB may be NULL. */
+int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, const void* dY,
+                        const void* H_saved, void* dX, float* dA, float* dB,
+                        int64_t M, int64_t K, int64_t r, int64_t N,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace the entry point `op` (FHPC_OP_*) needs for these sizes.
+ * Host-only; returns 0 for invalid arguments.  qscheme is ignored for op 0/1. */
+size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme);
+
+/* SiLU-gated product between the FFN's linears (Sec. 3.1 eq. FFN):
+ *   Z = U .* G .* sigmoid(G)            (n_elems elements of `dtype`, fp32 arithmetic)
+ *   dU = dZ .* G .* sigmoid(G);  dG = dZ .* U .* sigmoid(G) .* (1 + G .* (1 - sigmoid(G))). */
+int swiglu_fwd(const void* G, const void* U, void* Z, int64_t n_elems, int dtype, void* hip_stream);
+int swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU,
+               int64_t n_elems, int dtype, void* hip_stream);
+
+/* out = a + b elementwise (n_elems of `dtype`, fp32 add).  The FFN feeds one input to
+ * both the gate and the up projection (Sec. 3.1 eq. FFN), so its input gradient is
+ * the sum of the two projections' dX.  `out` may alias `a` or `b`. */
+int fhpc_add(const void* a, const void* b, void* out, int64_t n_elems, int dtype, void* hip_stream);
+
+/* Per-vector quantisation of a weight (Sec. 5.2: one scaling factor per vector, the
+ * vector's elements multiplied through, stored in low precision).  W is fp32 [K,N];
+ * outputs use the canonical layout above.  scale = fp16_rne(absmax / qmax) with
+ * qmax = 127 (scheme 8) or 7 (scheme 4); code = clamp(rint(w / scale), -qmax, qmax)
+ * with an fp32 divide and ties to even; a zero scale gives zero codes.  Results are
+ * bit-exact functions of W. */
+int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void* scales_out,
+                     int64_t K, int64_t N, void* hip_stream);
+
+/* Integer codes of a stored weight, q_out int8 [N][K] (scheme 8: a copy; scheme 4:
+ * sign-extended nibbles, including the code -8).  Bit-exact. */
+int qweight_unpack(const void* Wq, int qscheme, int8_t* q_out, int64_t K, int64_t N, void* hip_stream);
+
+/* Dequantised weight W_out fp32 [N][K] = code * scale (exact in fp32).  Bit-exact. */
+int qweight_dequant(const void* Wq, const void* scales, int qscheme, int block, float* W_out,
+                    int64_t K, int64_t N, void* hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* fhpc_status_string(int status);
+
+/* Library version (major * 100 + minor). */
+int fhpc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FINGPT_HPC_H */

@@ -1,0 +1,315 @@
+"""Thin Python binding of libfingpt_hpc.so (the C ABI in include/fingpt_hpc.h).
+
+Argument marshalling only: every step of the layer runs in the HIP library.
+PyTorch supplies device memory (tensors) and the current HIP stream, nothing else.
+The library must be present: there is no fallback path, and loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
+
+FHPC_F32, FHPC_BF16 = 0, 1
+FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
+FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD = 0, 1, 2, 3
+
+EXPORTS = [
+    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd",
+    "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
+    "qweight_dequant", "fhpc_add", "fhpc_status_string", "fhpc_version",
+]
+
+_lib = None
+
+
+class FhpcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, status_string(status)))
+
+
+def load_library():
+    """Load the HIP library (built in-tree by paper_2402_13533_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2402_13533_amd.build` "
+            "(there is no CPU or PyTorch fallback)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32, f32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_size_t
+    lib.lowrank_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, sz, vp]
+    lib.lowrank_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, sz, vp]
+    lib.qlinear_lowrank_fwd.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, i64, i64, i64, i64, vp, sz, vp]
+    lib.qlinear_lowrank_bwd.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp,
+                                        i64, i64, i64, i64, vp, sz, vp]
+    lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
+    lib.fhpc_workspace_bytes.restype = sz
+    lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.swiglu_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp]
+    lib.qweight_quantize.argtypes = [vp, i32, i32, vp, vp, i64, i64, vp]
+    lib.qweight_unpack.argtypes = [vp, i32, vp, i64, i64, vp]
+    lib.qweight_dequant.argtypes = [vp, vp, i32, i32, vp, i64, i64, vp]
+    lib.fhpc_add.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.fhpc_status_string.argtypes = [i32]
+    lib.fhpc_status_string.restype = C.c_char_p
+    lib.fhpc_version.restype = i32
+    for name in EXPORTS:
+        if name not in ("fhpc_workspace_bytes", "fhpc_status_string", "fhpc_version"):
+            getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().fhpc_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().fhpc_version())
+
+
+def workspace_bytes(op: int, M: int, K: int, r: int, N: int, dtype: int = FHPC_BF16, qscheme: int = 0) -> int:
+    return int(load_library().fhpc_workspace_bytes(op, M, K, r, N, dtype, qscheme))
+
+
+# ----------------------------------------------------------------------------- torch side
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return FHPC_F32
+    if t.dtype == torch.bfloat16:
+        return FHPC_BF16
+    raise TypeError("dtype must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check(t, name, shape=None, dtype=None):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s has dtype %s, expected %s" % (name, t.dtype, dtype))
+
+
+_workspaces = {}
+
+
+def get_workspace(nbytes: int, device):
+    """A cached per-device byte tensor of at least nbytes (grown on demand)."""
+    torch = _torch()
+    key = str(device)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def _ws(op, M, K, r, N, dtype, qscheme, device, workspace):
+    need = workspace_bytes(op, M, K, r, N, dtype, qscheme)
+    ws = workspace if workspace is not None else get_workspace(need, device)
+    return ws, C.c_size_t(ws.numel() * ws.element_size())
+
+
+def lowrank_linear_fwd(X, A, B, Y=None, H_out=None, save_H: bool = False, workspace=None):
+    """Y = (X A) B.  Returns Y, or (Y, H) when save_H or H_out is given."""
+    torch = _torch()
+    lib = load_library()
+    M, K = X.shape
+    r, N = B.shape
+    _check(X, "X"); _check(A, "A", (K, r), X.dtype); _check(B, "B", (r, N), X.dtype)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    if H_out is None and save_H:
+        H_out = torch.empty((M, r), dtype=X.dtype, device=X.device)
+    _check(Y, "Y", (M, N), X.dtype); _check(H_out, "H_out", (M, r), X.dtype)
+    dt = _dtype_code(X)
+    ws, wsz = _ws(FHPC_OP_LOWRANK_FWD, M, K, r, N, dt, 0, X.device, workspace)
+    rc = lib.lowrank_linear_fwd(_ptr(X), _ptr(A), _ptr(B), _ptr(Y), _ptr(H_out), M, K, r, N, dt,
+                                _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_linear_fwd")
+    return (Y, H_out) if H_out is not None else Y
+
+
+def lowrank_linear_bwd(X, A, B, dY, H_saved=None, need_dX=True, need_dA=True, need_dB=True,
+                       dX=None, dA=None, dB=None, workspace=None):
+    """Returns (dX, dA, dB) of Y = (X A) B; dA, dB are fp32."""
+    torch = _torch()
+    lib = load_library()
+    M, K = X.shape
+    r, N = B.shape
+    _check(X, "X"); _check(A, "A", (K, r), X.dtype); _check(B, "B", (r, N), X.dtype)
+    _check(dY, "dY", (M, N), X.dtype); _check(H_saved, "H_saved", (M, r), X.dtype)
+    if dX is None and need_dX:
+        dX = torch.empty((M, K), dtype=X.dtype, device=X.device)
+    if dA is None and need_dA:
+        dA = torch.empty((K, r), dtype=torch.float32, device=X.device)
+    if dB is None and need_dB:
+        dB = torch.empty((r, N), dtype=torch.float32, device=X.device)
+    _check(dX, "dX", (M, K), X.dtype); _check(dA, "dA", (K, r), torch.float32); _check(dB, "dB", (r, N), torch.float32)
+    dt = _dtype_code(X)
+    ws, wsz = _ws(FHPC_OP_LOWRANK_BWD, M, K, r, N, dt, 0, X.device, workspace)
+    rc = lib.lowrank_linear_bwd(_ptr(X), _ptr(A), _ptr(B), _ptr(dY), _ptr(H_saved), _ptr(dX), _ptr(dA), _ptr(dB),
+                                M, K, r, N, dt, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_linear_bwd")
+    return dX, dA, dB
+
+
+def _q_shapes(Wq, scales, qscheme, K, N, block):
+    torch = _torch()
+    if qscheme == FHPC_Q_INT8_PER_CHANNEL:
+        _check(Wq, "Wq", (N, K), torch.int8); _check(scales, "scales", (N,), torch.float16)
+    elif qscheme == FHPC_Q_INT4_BLOCK:
+        _check(Wq, "Wq", (N, K // 2), torch.uint8); _check(scales, "scales", (N, K // block), torch.float16)
+    else:
+        raise ValueError("qscheme must be 8 or 4")
+
+
+def qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, scaling, block=64, Y=None, H_out=None,
+                        save_H: bool = False, workspace=None):
+    """Y = X deq(Wq, scales) + scaling (X A) B (bf16)."""
+    torch = _torch()
+    lib = load_library()
+    M, K = X.shape
+    r, N = B.shape
+    bf = torch.bfloat16
+    _check(X, "X", None, bf); _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+    _q_shapes(Wq, scales, qscheme, K, N, block)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=bf, device=X.device)
+    if H_out is None and save_H:
+        H_out = torch.empty((M, r), dtype=bf, device=X.device)
+    _check(Y, "Y", (M, N), bf); _check(H_out, "H_out", (M, r), bf)
+    ws, wsz = _ws(FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, qscheme, X.device, workspace)
+    rc = lib.qlinear_lowrank_fwd(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
+                                 C.c_float(scaling), _ptr(Y), _ptr(H_out), M, K, r, N, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "qlinear_lowrank_fwd")
+    return (Y, H_out) if H_out is not None else Y
+
+
+def qlinear_lowrank_bwd(X, Wq, scales, qscheme, A, B, scaling, dY, block=64, H_saved=None,
+                        need_dX=True, need_dA=True, need_dB=True, dX=None, dA=None, dB=None, workspace=None):
+    """Returns (dX, dA, dB); the frozen W gets no gradient."""
+    torch = _torch()
+    lib = load_library()
+    M, K = X.shape
+    r, N = B.shape
+    bf = torch.bfloat16
+    _check(X, "X", None, bf); _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+    _check(dY, "dY", (M, N), bf); _check(H_saved, "H_saved", (M, r), bf)
+    _q_shapes(Wq, scales, qscheme, K, N, block)
+    if dX is None and need_dX:
+        dX = torch.empty((M, K), dtype=bf, device=X.device)
+    if dA is None and need_dA:
+        dA = torch.empty((K, r), dtype=torch.float32, device=X.device)
+    if dB is None and need_dB:
+        dB = torch.empty((r, N), dtype=torch.float32, device=X.device)
+    _check(dX, "dX", (M, K), bf); _check(dA, "dA", (K, r), torch.float32); _check(dB, "dB", (r, N), torch.float32)
+    ws, wsz = _ws(FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16, qscheme, X.device, workspace)
+    rc = lib.qlinear_lowrank_bwd(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
+                                 C.c_float(scaling), _ptr(dY), _ptr(H_saved), _ptr(dX), _ptr(dA), _ptr(dB),
+                                 M, K, r, N, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "qlinear_lowrank_bwd")
+    return dX, dA, dB
+
+
+def swiglu_fwd(G, U, Z=None):
+    torch = _torch()
+    _check(G, "G"); _check(U, "U", G.shape, G.dtype)
+    if Z is None:
+        Z = torch.empty_like(G)
+    _check(Z, "Z", G.shape, G.dtype)
+    rc = load_library().swiglu_fwd(_ptr(G), _ptr(U), _ptr(Z), G.numel(), _dtype_code(G), _stream())
+    if rc:
+        raise FhpcError(rc, "swiglu_fwd")
+    return Z
+
+
+def swiglu_bwd(G, U, dZ, dG=None, dU=None):
+    torch = _torch()
+    _check(G, "G"); _check(U, "U", G.shape, G.dtype); _check(dZ, "dZ", G.shape, G.dtype)
+    if dG is None:
+        dG = torch.empty_like(G)
+    if dU is None:
+        dU = torch.empty_like(G)
+    rc = load_library().swiglu_bwd(_ptr(G), _ptr(U), _ptr(dZ), _ptr(dG), _ptr(dU), G.numel(), _dtype_code(G), _stream())
+    if rc:
+        raise FhpcError(rc, "swiglu_bwd")
+    return dG, dU
+
+
+def fhpc_add(a, b, out=None):
+    torch = _torch()
+    _check(a, "a"); _check(b, "b", a.shape, a.dtype)
+    if out is None:
+        out = torch.empty_like(a)
+    rc = load_library().fhpc_add(_ptr(a), _ptr(b), _ptr(out), a.numel(), _dtype_code(a), _stream())
+    if rc:
+        raise FhpcError(rc, "fhpc_add")
+    return out
+
+
+def qweight_quantize(W, qscheme, block=64):
+    """W fp32 [K,N] on the device -> (Wq, scales) in the canonical layout."""
+    torch = _torch()
+    _check(W, "W", None, torch.float32)
+    K, N = W.shape
+    if qscheme == FHPC_Q_INT8_PER_CHANNEL:
+        Wq = torch.empty((N, K), dtype=torch.int8, device=W.device)
+        sc = torch.empty((N,), dtype=torch.float16, device=W.device)
+    else:
+        Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
+        sc = torch.empty((N, max(K // block, 1)), dtype=torch.float16, device=W.device)
+    rc = load_library().qweight_quantize(_ptr(W), qscheme, block, _ptr(Wq), _ptr(sc), K, N, _stream())
+    if rc:
+        raise FhpcError(rc, "qweight_quantize")
+    return Wq, sc
+
+
+def qweight_unpack(Wq, qscheme):
+    torch = _torch()
+    N = Wq.shape[0]
+    K = Wq.shape[1] * (2 if qscheme == FHPC_Q_INT4_BLOCK else 1)
+    _check(Wq, "Wq")
+    q = torch.empty((N, K), dtype=torch.int8, device=Wq.device)
+    rc = load_library().qweight_unpack(_ptr(Wq), qscheme, _ptr(q), K, N, _stream())
+    if rc:
+        raise FhpcError(rc, "qweight_unpack")
+    return q
+
+
+def qweight_dequant(Wq, scales, qscheme, block=64):
+    torch = _torch()
+    N = Wq.shape[0]
+    K = Wq.shape[1] * (2 if qscheme == FHPC_Q_INT4_BLOCK else 1)
+    _q_shapes(Wq, scales, qscheme, K, N, block)
+    out = torch.empty((N, K), dtype=torch.float32, device=Wq.device)
+    rc = load_library().qweight_dequant(_ptr(Wq), _ptr(scales), qscheme, block, _ptr(out), K, N, _stream())
+    if rc:
+        raise FhpcError(rc, "qweight_dequant")
+    return out

@@ -1,0 +1,535 @@
+// C ABI entry points: validation, workspace carving and the sequence of GEMM-core
+// launches that makes up each pass of the layer.  See include/fingpt_hpc.h for the
+// contract of every function.
+#include "../../include/fingpt_hpc.h"
+#include "gemm_bf16.h"
+#include "kernels_misc.h"
+
+using namespace fhpc;
+
+namespace {
+
+constexpr int64_t kMaxBytes = (int64_t)1 << 31;   // per-matrix limit of the 32-bit buffer offsets
+constexpr int kNumCU = 256;
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+#define FHPC_HIP(expr)                                   \
+    do {                                                 \
+        if ((expr) != hipSuccess) {                      \
+            (void)hipGetLastError();                     \
+            return FHPC_ERR_HIP;                         \
+        }                                                \
+    } while (0)
+
+// Workspace carving: a bump allocator over the caller's buffer (or a dry run that
+// only measures).
+struct Carver {
+    unsigned char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    void* take(int64_t bytes)
+    {
+        void* p = base ? base + used : nullptr;
+        used += (size_t)round_up(bytes > 0 ? bytes : 0, 256);
+        return p;
+    }
+};
+
+// Buffers an entry point may need, laid out identically by the measuring pass and the
+// real pass.
+struct Scratch {
+    void* A_p = nullptr;    // bf16 [K][rp]   zero-padded copy of A when r % 8 != 0
+    void* B_p = nullptr;    // bf16 [rp][N]
+    void* H = nullptr;      // bf16 [M][rp]
+    void* dH = nullptr;     // bf16 [M][rp]
+    float* Hf = nullptr;    // fp32 [M][rp]   split-K accumulator for the rank-r products
+    float* dA_t = nullptr;  // fp32 [K][rp]
+    float* dB_t = nullptr;  // fp32 [rp][N]
+};
+
+int64_t rank_pad(int64_t r) { return round_up(r, 8); }
+
+Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+{
+    Scratch s;
+    if (dtype == FHPC_F32) {
+        // fp32 path: H and dH in fp32, no padding
+        s.H = c.take(M * r * 4);
+        if (op == FHPC_OP_LOWRANK_BWD) s.dH = c.take(M * r * 4);
+        return s;
+    }
+    const int64_t rp = rank_pad(r);
+    const bool bwd = (op == FHPC_OP_LOWRANK_BWD || op == FHPC_OP_QLINEAR_BWD);
+    if (rp != r) {
+        s.A_p = c.take(K * rp * 2);
+        s.B_p = c.take(rp * N * 2);
+    }
+    s.H = c.take(M * rp * 2);
+    if (bwd) s.dH = c.take(M * rp * 2);
+    if (rp <= 32) s.Hf = static_cast<float*>(c.take(M * rp * 4));
+    if (bwd && rp != r) {
+        s.dA_t = static_cast<float*>(c.take(K * rp * 4));
+        s.dB_t = static_cast<float*>(c.take(rp * N * 4));
+    }
+    return s;
+}
+
+int check_common(int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    if (M < 1 || K < 1 || r < 1 || N < 1) return FHPC_ERR_SHAPE;
+    if ((K % 8) || (N % 8)) return FHPC_ERR_SHAPE;
+    if (K > ((int64_t)1 << 20) || N > ((int64_t)1 << 20) || r > ((int64_t)1 << 16)) return FHPC_ERR_UNSUPPORTED;
+    if (M > ((int64_t)1 << 30)) return FHPC_ERR_UNSUPPORTED;
+    // the GEMM core addresses each operand with 32-bit byte offsets
+    const int64_t rp = rank_pad(r);
+    const int64_t widest = (K > N ? K : N) > rp ? (K > N ? K : N) : rp;
+    if (M * widest * 2 >= kMaxBytes || K * rp * 2 >= kMaxBytes || rp * N * 2 >= kMaxBytes || K * N >= kMaxBytes)
+        return FHPC_ERR_UNSUPPORTED;
+    return FHPC_OK;
+}
+
+// Tile for an M x N output.  The narrow tiles exist only for the split (atomic)
+// rank-r products, so they are offered only when `allow_skinny`.
+int pick_tile(int64_t M, int64_t N, bool allow_skinny)
+{
+    if (allow_skinny && N <= 32) return TILE_256x32;
+    if (allow_skinny && M <= 32) return TILE_32x256;
+    const int order[4] = {TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128};
+    int best = TILE_128x128;
+    for (int t : order) {
+        int bm, bn;
+        gemm_tile_extent(t, &bm, &bn);
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+        if (tiles >= kNumCU) return t;
+    }
+    return best;
+}
+
+int64_t tile_count(int tile, int64_t M, int64_t N)
+{
+    int bm, bn;
+    gemm_tile_extent(tile, &bm, &bn);
+    return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+}
+
+// Splits of the reduction so that a small output still fills the chip.
+void pick_splits(int tile, int64_t M, int64_t N, int64_t Kred, int* splits, int* k_chunk)
+{
+    const int64_t tiles = tile_count(tile, M, N);
+    const int64_t ksteps = (Kred + 63) / 64;
+    int64_t s = (2 * kNumCU + tiles - 1) / tiles;
+    if (s > ksteps) s = ksteps;
+    if (s < 1) s = 1;
+    const int64_t steps_per = (ksteps + s - 1) / s;
+    *k_chunk = (int)(steps_per * 64);
+    *splits = (int)((ksteps + steps_per - 1) / steps_per);
+}
+
+GemmOperand operand(const void* p, int64_t ld, const void* scales = nullptr, int64_t sld = 0)
+{
+    GemmOperand o;
+    o.ptr = p;
+    o.ld = ld;
+    o.scales = scales;
+    o.scale_ld = sld;
+    return o;
+}
+
+// C[M,N] bf16 = A(KC or via a_mode) * B, whole reduction in one workgroup per tile.
+hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void* C, int64_t ldc,
+                      int64_t M, int64_t N, int64_t Kred, hipStream_t st)
+{
+    GemmArgs g = {};
+    g.a = a; g.b = b; g.c = C; g.ldc = ldc;
+    g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
+    g.alpha = 1.f; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
+    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, N, false), g, st);
+}
+
+// C[M,N] fp32 (ldc) = alpha * A * B with the reduction split across workgroups and
+// accumulated with fp32 atomics; C is zeroed first.
+hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
+                          int64_t M, int64_t N, int64_t Kred, float alpha, hipStream_t st)
+{
+    hipError_t e = launch_zero(C, M * ldc * 4, st);
+    if (e != hipSuccess) return e;
+    GemmArgs g = {};
+    g.a = a; g.b = b; g.c = C; g.ldc = ldc;
+    g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
+    g.alpha = alpha; g.mid_scale = 1.f;
+    const int tile = pick_tile(M, N, true);
+    pick_splits(tile, M, N, Kred, &g.splits, &g.k_chunk);
+    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_F32_ATOMIC, tile, g, st);
+}
+
+// Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
+// split the long reduction, accumulate in fp32, then round once to bf16.
+hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf,
+                        int64_t M, int64_t Kred, hipStream_t st)
+{
+    if (rp <= 32) {
+        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, st);
+        if (e != hipSuccess) return e;
+        return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
+    }
+    return gemm_plain(OP_KC, b_mode, a, b, P, rp, M, rp, Kred, st);
+}
+
+struct Factors {
+    const void* A;   // bf16 [K][rp]
+    const void* B;   // bf16 [rp][N]
+};
+
+// Zero-padded copies of A and B when the rank is not a multiple of 8.
+int prepare_factors(const void* A, const void* B, int64_t K, int64_t r, int64_t rp, int64_t N,
+                    const Scratch& s, hipStream_t st, Factors* f)
+{
+    if (rp == r) {
+        f->A = A;
+        f->B = B;
+        return FHPC_OK;
+    }
+    FHPC_HIP(launch_pad2d_u16(A, r, K, r, s.A_p, rp, K, st));
+    FHPC_HIP(launch_pad2d_u16(B, N, r, N, s.B_p, N, rp, st));
+    f->A = s.A_p;
+    f->B = s.B_p;
+    return FHPC_OK;
+}
+
+// dA[K][r] = alpha X^T dH and dB[r][N] = alpha H^T dY, both reductions over the M tokens.
+int weight_grads(const void* X, const void* dY, const void* H, const void* dH, float* dA, float* dB,
+                 int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha,
+                 const Scratch& s, hipStream_t st)
+{
+    if (dA) {
+        float* dst = (rp == r) ? dA : s.dA_t;
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, st));
+        if (rp != r) FHPC_HIP(launch_compact_f32(s.dA_t, rp, dA, r, K, r, 1.f, false, st));
+    }
+    if (dB) {
+        float* dst = (rp == r) ? dB : s.dB_t;
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(H, rp), operand(dY, N), dst, N, rp, N, M, alpha, st));
+        if (rp != r) FHPC_HIP(launch_compact_f32(s.dB_t, N, dB, N, r, N, 1.f, false, st));
+    }
+    return FHPC_OK;
+}
+
+int check_workspace(int op, void* ws, size_t ws_bytes, int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+{
+    Carver dry(nullptr);
+    carve(dry, op, M, K, r, N, dtype);
+    if (dry.used == 0) return FHPC_OK;
+    if (!ws || ws_bytes < dry.used) return FHPC_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return FHPC_ERR_ALIGN;
+    return FHPC_OK;
+}
+
+// ---------------- fp32 path of the factorised layer ----------------
+int lowrank_fwd_f32(const float* X, const float* A, const float* B, float* Y, float* H_out,
+                    int64_t M, int64_t K, int64_t r, int64_t N, const Scratch& s, hipStream_t st)
+{
+    float* H = H_out ? H_out : static_cast<float*>(s.H);
+    FHPC_HIP(launch_gemm_f32(X, K, 1, A, r, 1, H, r, (int)M, (int)r, (int)K, 1.f, st));
+    FHPC_HIP(launch_gemm_f32(H, r, 1, B, N, 1, Y, N, (int)M, (int)N, (int)r, 1.f, st));
+    return FHPC_OK;
+}
+
+int lowrank_bwd_f32(const float* X, const float* A, const float* B, const float* dY, const float* H_saved,
+                    float* dX, float* dA, float* dB, int64_t M, int64_t K, int64_t r, int64_t N,
+                    const Scratch& s, hipStream_t st)
+{
+    const float* H = H_saved;
+    if (!H && dB) {
+        float* Hw = static_cast<float*>(s.H);
+        FHPC_HIP(launch_gemm_f32(X, K, 1, A, r, 1, Hw, r, (int)M, (int)r, (int)K, 1.f, st));
+        H = Hw;
+    }
+    float* dH = static_cast<float*>(s.dH);
+    if (dX || dA)   // dH[m][j] = sum_n dY[m][n] B[j][n]
+        FHPC_HIP(launch_gemm_f32(dY, N, 1, B, 1, N, dH, r, (int)M, (int)r, (int)N, 1.f, st));
+    if (dX)         // dX[m][k] = sum_j dH[m][j] A[k][j]
+        FHPC_HIP(launch_gemm_f32(dH, r, 1, A, 1, r, dX, K, (int)M, (int)K, (int)r, 1.f, st));
+    if (dA)         // dA[k][j] = sum_m X[m][k] dH[m][j]
+        FHPC_HIP(launch_gemm_f32(X, 1, K, dH, r, 1, dA, r, (int)K, (int)r, (int)M, 1.f, st));
+    if (dB)         // dB[j][n] = sum_m H[m][j] dY[m][n]
+        FHPC_HIP(launch_gemm_f32(H, 1, r, dY, N, 1, dB, N, (int)r, (int)N, (int)M, 1.f, st));
+    return FHPC_OK;
+}
+
+int check_q(int qscheme, int block, int64_t K)
+{
+    if (qscheme != FHPC_Q_INT8_PER_CHANNEL && qscheme != FHPC_Q_INT4_BLOCK) return FHPC_ERR_DTYPE;
+    if (qscheme == FHPC_Q_INT4_BLOCK) {
+        if (block != 64) return FHPC_ERR_UNSUPPORTED;
+        if (K % 64) return FHPC_ERR_SHAPE;
+    }
+    return FHPC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme)
+{
+    (void)qscheme;
+    if (op < FHPC_OP_LOWRANK_FWD || op > FHPC_OP_QLINEAR_BWD) return 0;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return 0;
+    if (check_common(M, K, r, N) != FHPC_OK) return 0;
+    Carver dry(nullptr);
+    carve(dry, op, M, K, r, N, dtype);
+    return dry.used;
+}
+
+int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, void* H_out,
+                       int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
+                       void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !A || !B || !Y) return FHPC_ERR_NULL;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    int rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(Y, 16) || !aligned(H_out, 16)) return FHPC_ERR_ALIGN;
+    rc = check_workspace(FHPC_OP_LOWRANK_FWD, workspace, workspace_bytes, M, K, r, N, dtype);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    Scratch s = carve(c, FHPC_OP_LOWRANK_FWD, M, K, r, N, dtype);
+    if (dtype == FHPC_F32)
+        return lowrank_fwd_f32((const float*)X, (const float*)A, (const float*)B, (float*)Y, (float*)H_out, M, K, r, N, s, st);
+
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
+    if (rc) return rc;
+    void* H = (H_out && rp == r) ? H_out : s.H;
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, M, K, st));
+    FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st));
+    if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
+    return FHPC_OK;
+}
+
+int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* dY,
+                       const void* H_saved, void* dX, float* dA, float* dB,
+                       int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
+                       void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !A || !B || !dY) return FHPC_ERR_NULL;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    int rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(dY, 16) || !aligned(H_saved, 16) ||
+        !aligned(dX, 16) || !aligned(dA, 16) || !aligned(dB, 16))
+        return FHPC_ERR_ALIGN;
+    rc = check_workspace(FHPC_OP_LOWRANK_BWD, workspace, workspace_bytes, M, K, r, N, dtype);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    Scratch s = carve(c, FHPC_OP_LOWRANK_BWD, M, K, r, N, dtype);
+    if (dtype == FHPC_F32)
+        return lowrank_bwd_f32((const float*)X, (const float*)A, (const float*)B, (const float*)dY,
+                               (const float*)H_saved, (float*)dX, dA, dB, M, K, r, N, s, st);
+
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
+    if (rc) return rc;
+    const void* H = nullptr;
+    if (dB) {
+        if (H_saved && rp == r) {
+            H = H_saved;
+        } else if (H_saved) {
+            FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
+            H = s.H;
+        } else {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, M, K, st));
+            H = s.H;
+        }
+    }
+    if (dX || dA)
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, M, N, st));
+    if (dX)
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st));
+    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
+}
+
+int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, void* Y, void* H_out,
+                        int64_t M, int64_t K, int64_t r, int64_t N,
+                        void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !Wq || !scales || !A || !B || !Y) return FHPC_ERR_NULL;
+    int rc = check_q(qscheme, block, K);
+    if (rc) return rc;
+    rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
+        !aligned(Y, 16) || !aligned(H_out, 16))
+        return FHPC_ERR_ALIGN;
+    rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16);
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
+    if (rc) return rc;
+    void* H = (H_out && rp == r) ? H_out : s.H;
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, M, K, st));
+
+    GemmArgs g = {};
+    g.a = operand(X, K);
+    g.b = operand(Wq, K, scales, K / 64);
+    g.a2 = operand(H, rp);
+    g.b2 = operand(f.B, N);
+    g.c = Y; g.ldc = N;
+    g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
+    g.alpha = 1.f; g.mid_scale = scaling; g.splits = 1; g.k_chunk = (int)round_up(K, 64);
+    const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
+    FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_XC, OUT_BF16, pick_tile(M, N, false), g, st));
+    if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
+    return FHPC_OK;
+}
+
+int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, const void* dY,
+                        const void* H_saved, void* dX, float* dA, float* dB,
+                        int64_t M, int64_t K, int64_t r, int64_t N,
+                        void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !Wq || !scales || !A || !B || !dY) return FHPC_ERR_NULL;
+    int rc = check_q(qscheme, block, K);
+    if (rc) return rc;
+    rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
+        !aligned(dY, 16) || !aligned(H_saved, 16) || !aligned(dX, 16) || !aligned(dA, 16) || !aligned(dB, 16))
+        return FHPC_ERR_ALIGN;
+    rc = check_workspace(FHPC_OP_QLINEAR_BWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    Scratch s = carve(c, FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16);
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
+    if (rc) return rc;
+    const void* H = nullptr;
+    if (dB) {
+        if (H_saved && rp == r) {
+            H = H_saved;
+        } else if (H_saved) {
+            FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
+            H = s.H;
+        } else {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, M, K, st));
+            H = s.H;
+        }
+    }
+    if (dX || dA)
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, M, N, st));
+    if (dX) {
+        // dX[m][k] = sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
+        GemmArgs g = {};
+        g.a = operand(dY, N);
+        g.b = operand(Wq, K, scales, K / 64);
+        g.a2 = operand(s.dH, rp);
+        g.b2 = operand(f.A, rp);
+        g.c = dX; g.ldc = K;
+        g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
+        g.alpha = 1.f; g.mid_scale = scaling; g.splits = 1; g.k_chunk = (int)round_up(N, 64);
+        const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
+        FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_KC, OUT_BF16, pick_tile(M, K, false), g, st));
+    }
+    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, st);
+}
+
+int swiglu_fwd(const void* G, const void* U, void* Z, int64_t n_elems, int dtype, void* hip_stream)
+{
+    if (!G || !U || !Z) return FHPC_ERR_NULL;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    if (n_elems < 0) return FHPC_ERR_SHAPE;
+    FHPC_HIP(launch_swiglu_fwd(G, U, Z, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU,
+               int64_t n_elems, int dtype, void* hip_stream)
+{
+    if (!G || !U || !dZ || !dG || !dU) return FHPC_ERR_NULL;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    if (n_elems < 0) return FHPC_ERR_SHAPE;
+    FHPC_HIP(launch_swiglu_bwd(G, U, dZ, dG, dU, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int fhpc_add(const void* a, const void* b, void* out, int64_t n_elems, int dtype, void* hip_stream)
+{
+    if (!a || !b || !out) return FHPC_ERR_NULL;
+    if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    if (n_elems < 0) return FHPC_ERR_SHAPE;
+    FHPC_HIP(launch_add(a, b, out, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+static int check_qweight(int qscheme, int block, int64_t K, int64_t N, bool needs_block)
+{
+    if (qscheme != FHPC_Q_INT8_PER_CHANNEL && qscheme != FHPC_Q_INT4_BLOCK) return FHPC_ERR_DTYPE;
+    if (K < 1 || N < 1 || (K % 8) || (N % 8)) return FHPC_ERR_SHAPE;
+    if (qscheme == FHPC_Q_INT4_BLOCK && needs_block) {
+        if (block != 64) return FHPC_ERR_UNSUPPORTED;
+        if (K % 64) return FHPC_ERR_SHAPE;
+    }
+    return FHPC_OK;
+}
+
+int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void* scales_out,
+                     int64_t K, int64_t N, void* hip_stream)
+{
+    if (!W || !Wq_out || !scales_out) return FHPC_ERR_NULL;
+    int rc = check_qweight(qscheme, block, K, N, true);
+    if (rc) return rc;
+    FHPC_HIP(launch_quantize(W, qscheme, block, Wq_out, scales_out, K, N, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int qweight_unpack(const void* Wq, int qscheme, int8_t* q_out, int64_t K, int64_t N, void* hip_stream)
+{
+    if (!Wq || !q_out) return FHPC_ERR_NULL;
+    int rc = check_qweight(qscheme, 64, K, N, false);
+    if (rc) return rc;
+    FHPC_HIP(launch_unpack(Wq, qscheme, q_out, K, N, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int qweight_dequant(const void* Wq, const void* scales, int qscheme, int block, float* W_out,
+                    int64_t K, int64_t N, void* hip_stream)
+{
+    if (!Wq || !scales || !W_out) return FHPC_ERR_NULL;
+    int rc = check_qweight(qscheme, block, K, N, true);
+    if (rc) return rc;
+    FHPC_HIP(launch_dequant(Wq, scales, qscheme, block, W_out, K, N, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+const char* fhpc_status_string(int status)
+{
+    switch (status) {
+        case FHPC_OK: return "ok";
+        case FHPC_ERR_NULL: return "a required pointer is NULL";
+        case FHPC_ERR_SHAPE: return "invalid shape (sizes must be positive; K and N multiples of 8; K a multiple of the block)";
+        case FHPC_ERR_DTYPE: return "unknown dtype or quantisation scheme";
+        case FHPC_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes; workspace 256)";
+        case FHPC_ERR_WORKSPACE: return "workspace missing or smaller than fhpc_workspace_bytes";
+        case FHPC_ERR_UNSUPPORTED: return "unsupported configuration (block must be 64; matrices below 2 GiB)";
+        case FHPC_ERR_HIP: return "a HIP call or kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int fhpc_version(void) { return 100; }
+
+}  // extern "C"

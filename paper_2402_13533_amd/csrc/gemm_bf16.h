@@ -1,0 +1,68 @@
+// Internal interface of the bf16 MFMA GEMM core (gfx950).  Not part of the C ABI.
+//
+// One kernel family computes
+//     C[M,N] (=|+=) alpha * ( mid_scale * sum_{k<K2} A2(m,k) B2(n,k)  +  sum_{k<K} A(m,k) B(n,k) )
+// with fp32 accumulation on the matrix cores.  The optional first sum is the
+// rank-r branch of the finetuning layer riding in the same accumulators as the
+// frozen base weight's product.  Operands are described by how the element
+// (row, k) is stored, so that every product of the layer's forward and backward
+// (X*A, H*B, dY*B^T, dH*A^T, H^T*dY, X^T*dH, X*deq(W), dY*deq(W)^T) is one call.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fhpc {
+
+// Storage of an operand whose logical element is (row, k), row = output index
+// (m for the A side, n for the B side), k = reduction index.
+enum : int {
+    OP_KC = 0,     // bf16, k contiguous:   ptr[row*ld + k]
+    OP_XC = 1,     // bf16, row contiguous: ptr[k*ld + row]  (transposed while staging)
+    OP_Q8_KC = 2,  // int8 codes ptr[row*ld + k], fp16 scale[row]
+    OP_Q4_KC = 3,  // 4-bit codes, byte ptr[row*ld/2 + k/2], fp16 scale[row*scale_ld + k/64]
+    OP_Q8_XC = 4,  // int8 codes ptr[k*ld + row], fp16 scale[k]
+    OP_Q4_XC = 5,  // 4-bit codes, byte ptr[k*ld/2 + row/2], fp16 scale[k*scale_ld + row/64]
+    OP_NONE = 6
+};
+
+enum : int { OUT_BF16 = 0, OUT_F32 = 1, OUT_F32_ATOMIC = 2 };
+
+// Tile shapes (BM x BN, four 64-lane waves arranged WAVES_M x WAVES_N).
+enum : int {
+    TILE_256x256 = 0,  // 2 x 2 waves of 128 x 128
+    TILE_128x256 = 1,  // 2 x 2 waves of 64 x 128
+    TILE_256x128 = 2,  // 2 x 2 waves of 128 x 64
+    TILE_128x128 = 3,  // 2 x 2 waves of 64 x 64
+    TILE_256x32 = 4,   // 4 x 1 waves of 64 x 32   (rank-r outputs: H, dH, dA)
+    TILE_32x256 = 5,   // 1 x 4 waves of 32 x 64   (dB)
+    TILE_COUNT = 6
+};
+
+struct GemmOperand {
+    const void* ptr;
+    int64_t ld;            // leading dimension in elements (codes for quantised operands)
+    const void* scales;    // fp16 scales for quantised operands
+    int64_t scale_ld;      // scales per row of the scale array (int4 only)
+};
+
+struct GemmArgs {
+    GemmOperand a, b;      // main sum, reduction length K
+    GemmOperand a2, b2;    // optional leading sum, reduction length K2 (a rank; short)
+    void* c;
+    int64_t ldc;
+    int M, N, K, K2;
+    float alpha;
+    float mid_scale;
+    int splits;            // >1: blockIdx.z slices of k_chunk (multiple of 64); needs OUT_F32_ATOMIC
+    int k_chunk;
+};
+
+// Launches the instantiation (a_mode, b_mode, b2_mode, out_mode, tile).  a2 is always OP_KC.
+// Returns hipErrorInvalidValue when that combination is not instantiated.
+hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, int tile,
+                            const GemmArgs& args, hipStream_t stream);
+
+// Tile extents, for planning on the host.
+void gemm_tile_extent(int tile, int* bm, int* bn);
+
+}  // namespace fhpc

@@ -1,0 +1,25 @@
+// Internal launchers for the non-MFMA kernels.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fhpc {
+
+hipError_t launch_gemm_f32(const float* A, int64_t ars, int64_t acs, const float* B, int64_t brs, int64_t bcs,
+                           float* C, int64_t ldc, int M, int N, int K, float alpha, hipStream_t s);
+hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, bool bf16, hipStream_t s);
+hipError_t launch_swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
+                             bool bf16, hipStream_t s);
+hipError_t launch_add(const void* a, const void* b, void* out, int64_t n, bool bf16, hipStream_t s);
+hipError_t launch_unpack(const void* Wq, int scheme, int8_t* q, int64_t K, int64_t N, hipStream_t s);
+hipError_t launch_dequant(const void* Wq, const void* scales, int scheme, int64_t block, float* out,
+                          int64_t K, int64_t N, hipStream_t s);
+hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, void* scales,
+                           int64_t K, int64_t N, hipStream_t s);
+hipError_t launch_pad2d_u16(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src,
+                            void* dst, int64_t ld_dst, int64_t rows_dst, hipStream_t s);
+hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int64_t cols,
+                              float scale, bool to_bf16, hipStream_t s);
+hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s);
+
+}  // namespace fhpc

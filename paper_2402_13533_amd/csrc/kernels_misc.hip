@@ -1,0 +1,362 @@
+// fp32 GEMM (true fp32 arithmetic), SiLU gate, weight quantise / unpack / dequantise,
+// and the small copy / convert kernels the entry points use around the GEMM core.
+#include "kernels_misc.h"
+
+namespace fhpc {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    f32x2 v;
+    v.x = f;
+    v.y = 0.f;
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return (uint16_t)(__builtin_bit_cast(uint32_t, b) & 0xFFFFu);
+}
+
+// ---------------------------------------------------------------------------------
+// fp32 GEMM with arbitrary strides: C[m,n] = alpha * sum_k A(m,k) B(k,n),
+// A(m,k) = A[m*ars + k*acs], B(k,n) = B[k*brs + n*bcs].  64x64 tile, 16-deep steps,
+// 256 threads, each a 4x4 block of C, plain v_fma_f32 (no reduced-precision path).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int64_t ars, int64_t acs,
+                                                       const float* __restrict__ B, int64_t brs, int64_t bcs,
+                                                       float* __restrict__ C, int64_t ldc, int M, int N, int K, float alpha)
+{
+    __shared__ float sA[16][64 + 4];
+    __shared__ float sB[16][64 + 4];
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    const int tx = tid & 15, ty = tid >> 4;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int e = tid + 256 * i;
+            // A tile element (mm, kk): let the faster-varying thread index follow the contiguous stride
+            int mm, kk;
+            if (acs == 1) { kk = e & 15; mm = e >> 4; } else { mm = e & 63; kk = e >> 6; }
+            const int m = m0 + mm, k = k0 + kk;
+            sA[kk][mm] = (m < M && k < K) ? A[(int64_t)m * ars + (int64_t)k * acs] : 0.f;
+            int nn, kb;
+            if (brs == 1) { kb = e & 15; nn = e >> 4; } else { nn = e & 63; kb = e >> 6; }
+            const int n = n0 + nn, k2 = k0 + kb;
+            sB[kb][nn] = (n < N && k2 < K) ? B[(int64_t)k2 * brs + (int64_t)n * bcs] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; kk++) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) a[i] = sA[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; j++) b[j] = sB[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int m = m0 + ty * 4 + i;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int n = n0 + tx * 4 + j;
+            if (m < M && n < N) C[(int64_t)m * ldc + n] = alpha * acc[i][j];
+        }
+    }
+}
+
+hipError_t launch_gemm_f32(const float* A, int64_t ars, int64_t acs, const float* B, int64_t brs, int64_t bcs,
+                           float* C, int64_t ldc, int M, int N, int K, float alpha, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return hipSuccess;
+    dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, A, ars, acs, B, brs, bcs, C, ldc, M, N, K, alpha);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// SiLU gate (Sec. 3.1 eq. FFN): fp32 arithmetic on bf16 or fp32 storage.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void* p, int64_t i)
+{
+    if constexpr (BF16) return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(p)[i]);
+    else return reinterpret_cast<const float*>(p)[i];
+}
+template <bool BF16>
+__device__ __forceinline__ void store_elem(void* p, int64_t i, float v)
+{
+    if constexpr (BF16) reinterpret_cast<uint16_t*>(p)[i] = float_to_bf16_bits(v);
+    else reinterpret_cast<float*>(p)[i] = v;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const void* G, const void* U, void* Z, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i);
+        store_elem<BF16>(Z, i, u * g * sigmoid_f(g));
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* G, const void* U, const void* dZ,
+                                                         void* dG, void* dU, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i), dz = load_elem<BF16>(dZ, i);
+        const float sg = sigmoid_f(g);
+        store_elem<BF16>(dU, i, dz * g * sg);
+        store_elem<BF16>(dG, i, dz * u * sg * (1.f + g * (1.f - sg)));
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void add_kernel(const void* a, const void* b, void* out, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        store_elem<BF16>(out, i, load_elem<BF16>(a, i) + load_elem<BF16>(b, i));
+}
+
+static unsigned grid_for(int64_t n)
+{
+    int64_t b = (n + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
+}
+
+hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, bool bf16, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(swiglu_fwd_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, G, U, Z, n);
+    else hipLaunchKernelGGL(swiglu_fwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, Z, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_add(const void* a, const void* b, void* out, int64_t n, bool bf16, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(add_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, a, b, out, n);
+    else hipLaunchKernelGGL(add_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, a, b, out, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
+                             bool bf16, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(swiglu_bwd_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
+    else hipLaunchKernelGGL(swiglu_bwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Weight codes: unpack, dequantise, quantise (Sec. 5.2).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void unpack_int4_kernel(const uint8_t* __restrict__ p, int8_t* __restrict__ q, int64_t nbytes)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nbytes; i += stride) {
+        const int b = p[i];
+        q[2 * i] = (int8_t)__builtin_amdgcn_sbfe(b, 0, 4);
+        q[2 * i + 1] = (int8_t)__builtin_amdgcn_sbfe(b, 4, 4);
+    }
+}
+
+__global__ __launch_bounds__(256) void copy_bytes_kernel(const uint8_t* __restrict__ p, uint8_t* __restrict__ q, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) q[i] = p[i];
+}
+
+hipError_t launch_unpack(const void* Wq, int scheme, int8_t* q, int64_t K, int64_t N, hipStream_t s)
+{
+    if (scheme == 8) {
+        const int64_t n = K * N;
+        hipLaunchKernelGGL(copy_bytes_kernel, dim3(grid_for(n)), dim3(256), 0, s, (const uint8_t*)Wq, (uint8_t*)q, n);
+    } else {
+        const int64_t n = K * N / 2;
+        hipLaunchKernelGGL(unpack_int4_kernel, dim3(grid_for(n)), dim3(256), 0, s, (const uint8_t*)Wq, q, n);
+    }
+    return hipGetLastError();
+}
+
+// W_out[n][k] = code * scale, exact in fp32 (at most 8 + 11 significant bits).
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ Wq, const uint16_t* __restrict__ scales,
+                                                      int scheme, int64_t block, float* __restrict__ out, int64_t K, int64_t N)
+{
+    const int64_t total = K * N;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int64_t n = i / K, k = i % K;
+        int code;
+        float sc;
+        if (scheme == 8) {
+            code = (int8_t)Wq[i];
+            sc = (float)__builtin_bit_cast(_Float16, scales[n]);
+        } else {
+            const int b = Wq[i >> 1];
+            code = (k & 1) ? __builtin_amdgcn_sbfe(b, 4, 4) : __builtin_amdgcn_sbfe(b, 0, 4);
+            sc = (float)__builtin_bit_cast(_Float16, scales[n * (K / block) + k / block]);
+        }
+        out[i] = (float)code * sc;
+    }
+}
+
+hipError_t launch_dequant(const void* Wq, const void* scales, int scheme, int64_t block, float* out,
+                          int64_t K, int64_t N, hipStream_t s)
+{
+    hipLaunchKernelGGL(dequant_kernel, dim3(grid_for(K * N)), dim3(256), 0, s, (const uint8_t*)Wq,
+                       (const uint16_t*)scales, scheme, block, out, K, N);
+    return hipGetLastError();
+}
+
+// Quantiser.  One workgroup handles 64 output channels (columns of W[K,N]); its 256
+// threads are 64 columns x 4 k-lanes, so reads of W rows are 256-byte coalesced.
+// vec_len = K for per-channel int8, = block for 4-bit; one scale per (column, vector).
+template <int QMAX, bool PACK4>
+__global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W, uint8_t* __restrict__ Wq,
+                                                       uint16_t* __restrict__ scales, int64_t K, int64_t N, int64_t vec_len)
+{
+    __shared__ float s_max[4][64];
+    __shared__ uint8_t s_code[64][64 + 4];     // [column][k within chunk]
+    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.x * 64 + col;
+    const bool ok = n < N;
+    const int64_t nvec = K / vec_len;
+    for (int64_t v = 0; v < nvec; v++) {
+        const int64_t kb = v * vec_len;
+        float a = 0.f;
+        if (ok)
+            for (int64_t k = kl; k < vec_len; k += 4) a = fmaxf(a, fabsf(W[(kb + k) * N + n]));
+        s_max[kl][col] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(s_max[0][col], s_max[1][col]), fmaxf(s_max[2][col], s_max[3][col]));
+        const float sc32 = a / (float)QMAX;
+        const _Float16 hs = (_Float16)sc32;                 // round to nearest even
+        const float sf = (float)hs;
+        if (ok && kl == 0) scales[n * nvec + v] = __builtin_bit_cast(uint16_t, hs);
+        // codes, 64 k at a time, transposed through LDS so that stores run along k
+        for (int64_t c0 = 0; c0 < vec_len; c0 += 64) {
+            __syncthreads();
+            for (int kk = kl; kk < 64; kk += 4) {
+                int code = 0;
+                const int64_t k = c0 + kk;
+                if (ok && k < vec_len && sf != 0.f) {
+                    float t = rintf(W[(kb + k) * N + n] / sf);
+                    t = fminf(fmaxf(t, -(float)QMAX), (float)QMAX);
+                    code = (int)t;
+                }
+                s_code[col][kk] = (uint8_t)code;
+            }
+            __syncthreads();
+            // thread (row = tid/4.., piece) writes 16 codes of one column
+            const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;
+            const int64_t nn = (int64_t)blockIdx.x * 64 + r;
+            if (nn < N) {
+                const int64_t kbase = kb + c0 + piece * 16;
+                if (PACK4) {
+                    uint8_t* dst = Wq + nn * (K / 2) + kbase / 2;
+                    for (int e = 0; e < 8; e++)
+                        if (c0 + piece * 16 + 2 * e < vec_len)
+                            dst[e] = (uint8_t)((s_code[r][piece * 16 + 2 * e] & 0xF) | ((s_code[r][piece * 16 + 2 * e + 1] & 0xF) << 4));
+                } else {
+                    uint8_t* dst = Wq + nn * K + kbase;
+                    for (int e = 0; e < 16; e++)
+                        if (c0 + piece * 16 + e < vec_len) dst[e] = s_code[r][piece * 16 + e];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, void* scales,
+                           int64_t K, int64_t N, hipStream_t s)
+{
+    dim3 grid((unsigned)((N + 63) / 64));
+    if (scheme == 8)
+        hipLaunchKernelGGL((quantize_kernel<127, false>), grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N, K);
+    else
+        hipLaunchKernelGGL((quantize_kernel<7, true>), grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N, block);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Copies around the GEMM core
+// ---------------------------------------------------------------------------------
+// dst[rows_dst][ld_dst] (16-bit elements) = src[rows_src][cols_src] zero-extended.
+__global__ __launch_bounds__(256) void pad2d_u16_kernel(const uint16_t* __restrict__ src, int64_t ld_src, int64_t rows_src, int64_t cols_src,
+                                                        uint16_t* __restrict__ dst, int64_t ld_dst, int64_t rows_dst)
+{
+    const int64_t total = rows_dst * ld_dst;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int64_t r = i / ld_dst, c = i % ld_dst;
+        dst[i] = (r < rows_src && c < cols_src) ? src[r * ld_src + c] : (uint16_t)0;
+    }
+}
+
+hipError_t launch_pad2d_u16(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src,
+                            void* dst, int64_t ld_dst, int64_t rows_dst, hipStream_t s)
+{
+    const int64_t total = rows_dst * ld_dst;
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pad2d_u16_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t*)src, ld_src, rows_src, cols_src,
+                       (uint16_t*)dst, ld_dst, rows_dst);
+    return hipGetLastError();
+}
+
+// dst[rows][cols] (dense) = scale * src[rows][ld_src] (first cols columns); fp32 -> fp32 or bf16.
+template <bool TO_BF16>
+__global__ __launch_bounds__(256) void compact_f32_kernel(const float* __restrict__ src, int64_t ld_src, void* __restrict__ dst,
+                                                          int64_t ld_dst, int64_t rows, int64_t cols, float scale)
+{
+    const int64_t total = rows * cols;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int64_t r = i / cols, c = i % cols;
+        const float v = src[r * ld_src + c] * scale;
+        if constexpr (TO_BF16) reinterpret_cast<uint16_t*>(dst)[r * ld_dst + c] = float_to_bf16_bits(v);
+        else reinterpret_cast<float*>(dst)[r * ld_dst + c] = v;
+    }
+}
+
+hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int64_t cols,
+                              float scale, bool to_bf16, hipStream_t s)
+{
+    const int64_t total = rows * cols;
+    if (total <= 0) return hipSuccess;
+    if (to_bf16) hipLaunchKernelGGL(compact_f32_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, src, ld_src, dst, ld_dst, rows, cols, scale);
+    else hipLaunchKernelGGL(compact_f32_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, src, ld_src, dst, ld_dst, rows, cols, scale);
+    return hipGetLastError();
+}
+
+// Zero fill with a kernel (usable inside a captured graph, unlike a memset node).
+__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s)
+{
+    const int64_t n = bytes / 4;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(grid_for(n)), dim3(256), 0, s, (uint32_t*)p, n);
+    return hipGetLastError();
+}
+
+}  // namespace fhpc

@@ -1,0 +1,25 @@
+"""SiLU-gated FFN built from three factorised linears (Sec. 3.1 eq. FFN with every
+weight replaced by a factor pair, Sec. 3.2).  Pure sequencing of library calls."""
+from __future__ import annotations
+
+from . import fhpc_add, lowrank_linear_bwd, lowrank_linear_fwd, swiglu_bwd, swiglu_fwd
+
+
+def ffn_fwd(X, Ag, Bg, Au, Bu, Ad, Bd):
+    """Returns (Y, saved) with saved = tensors the backward pass reuses."""
+    G, Hg = lowrank_linear_fwd(X, Ag, Bg, save_H=True)
+    U, Hu = lowrank_linear_fwd(X, Au, Bu, save_H=True)
+    Z = swiglu_fwd(G, U)
+    Y, Hd = lowrank_linear_fwd(Z, Ad, Bd, save_H=True)
+    return Y, (G, U, Z, Hg, Hu, Hd)
+
+
+def ffn_bwd(X, Ag, Bg, Au, Bu, Ad, Bd, dY, saved):
+    """Returns dX and the six weight gradients (fp32)."""
+    G, U, Z, Hg, Hu, Hd = saved
+    dZ, dAd, dBd = lowrank_linear_bwd(Z, Ad, Bd, dY, H_saved=Hd)
+    dG, dU = swiglu_bwd(G, U, dZ)
+    dXg, dAg, dBg = lowrank_linear_bwd(X, Ag, Bg, dG, H_saved=Hg)
+    dXu, dAu, dBu = lowrank_linear_bwd(X, Au, Bu, dU, H_saved=Hu)
+    dX = fhpc_add(dXg, dXu, out=dXg)
+    return dX, (dAg, dBg, dAu, dBu, dAd, dBd)

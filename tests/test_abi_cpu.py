@@ -1,0 +1,84 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and validates arguments before launching anything (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2402_13533_amd as fhpc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fingpt_hpc.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = fhpc.load_library()
+    names = _declared_functions()
+    assert len(names) >= 13 and "lowrank_linear_fwd" in names and "qlinear_lowrank_bwd" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(fhpc.EXPORTS) == names
+    assert fhpc.version() >= 100
+
+
+def test_status_strings():
+    seen = {fhpc.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and fhpc.status_string(0) == "ok" and fhpc.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes_host_only():
+    wb = fhpc.workspace_bytes
+    assert wb(fhpc.FHPC_OP_LOWRANK_FWD, 16384, 4096, 512, 4096) >= 16384 * 512 * 2
+    assert wb(fhpc.FHPC_OP_LOWRANK_BWD, 16384, 4096, 512, 4096) >= 2 * 16384 * 512 * 2
+    assert wb(fhpc.FHPC_OP_QLINEAR_BWD, 4096, 4096, 8, 4096) % 256 == 0
+    assert wb(fhpc.FHPC_OP_LOWRANK_FWD, 0, 4096, 512, 4096) == 0           # invalid shape
+    assert wb(fhpc.FHPC_OP_LOWRANK_FWD, 16, 4100, 8, 4096) == 0            # K not a multiple of 8
+    assert wb(7, 16, 64, 8, 64) == 0
+    # odd rank needs padded copies of A and B
+    assert wb(fhpc.FHPC_OP_LOWRANK_FWD, 64, 64, 5, 64) > wb(fhpc.FHPC_OP_LOWRANK_FWD, 64, 64, 8, 64)
+
+
+def test_validation_precedes_launch():
+    """Error codes for bad arguments come back without touching a device (fake, aligned,
+    non-NULL addresses are never dereferenced on these paths)."""
+    lib = fhpc.load_library()
+    p = C.c_void_p(0x10000)
+    odd = C.c_void_p(0x10004)
+    nul = C.c_void_p(0)
+    ws = C.c_void_p(0x20000)
+    big = C.c_size_t(1 << 40)
+    f = lib.lowrank_linear_fwd
+    assert f(nul, p, p, p, nul, 16, 64, 8, 64, 1, ws, big, nul) == 1          # NULL X
+    assert f(p, p, p, p, nul, 16, 60, 8, 64, 1, ws, big, nul) == 2            # K % 8
+    assert f(p, p, p, p, nul, 0, 64, 8, 64, 1, ws, big, nul) == 2             # M < 1
+    assert f(p, p, p, p, nul, 16, 64, 8, 64, 5, ws, big, nul) == 3            # dtype
+    assert f(odd, p, p, p, nul, 16, 64, 8, 64, 1, ws, big, nul) == 4          # alignment
+    assert f(p, p, p, p, nul, 16, 64, 8, 64, 1, nul, C.c_size_t(0), nul) == 5  # workspace
+    assert f(p, p, p, p, nul, 16, 64, 8, 64, 1, ws, C.c_size_t(16), nul) == 5
+    assert f(p, p, p, p, nul, 1 << 28, 4096, 8, 4096, 1, ws, big, nul) == 6    # >= 2 GiB operand
+    q = lib.qlinear_lowrank_fwd
+    assert q(p, p, p, 3, 64, p, p, C.c_float(1), p, nul, 16, 64, 8, 64, ws, big, nul) == 3   # scheme
+    assert q(p, p, p, 4, 32, p, p, C.c_float(1), p, nul, 16, 64, 8, 64, ws, big, nul) == 6   # block
+    assert q(p, p, p, 4, 64, p, p, C.c_float(1), p, nul, 16, 72, 8, 64, ws, big, nul) == 2   # K % 64
+    assert q(p, nul, p, 8, 64, p, p, C.c_float(1), p, nul, 16, 64, 8, 64, ws, big, nul) == 1
+    b = lib.lowrank_linear_bwd
+    assert b(p, p, p, nul, nul, p, p, p, 16, 64, 8, 64, 1, ws, big, nul) == 1  # NULL dY
+    assert lib.swiglu_fwd(p, p, nul, 8, 1, nul) == 1
+    assert lib.swiglu_bwd(p, p, p, p, p, 8, 9, nul) == 3
+    assert lib.qweight_quantize(p, 4, 48, p, p, 64, 64, nul) == 6
+    assert lib.qweight_dequant(p, p, 5, 64, p, 64, 64, nul) == 3
+    assert lib.fhpc_add(p, p, p, -1, 1, nul) == 2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros((8, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        fhpc.lowrank_linear_fwd(x, torch.zeros((64, 8), dtype=torch.bfloat16), torch.zeros((8, 64), dtype=torch.bfloat16))

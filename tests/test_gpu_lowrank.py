@@ -1,0 +1,116 @@
+"""GPU parity of lowrank_linear_fwd / lowrank_linear_bwd against the CPU oracle on the
+same seeded inputs (element by element, relative Frobenius error per output tensor)."""
+import numpy as np
+import pytest
+
+import oracle
+from harness import TOL_BF16, TOL_F32, Bf16, from_device, lowrank_inputs, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def _fhpc():
+    import paper_2402_13533_amd as fhpc
+    return fhpc
+
+
+def _check_all(tag, got, ref, tol):
+    for name, g, r in zip(("Y", "dX", "dA", "dB"), got, ref):
+        if g is None:
+            continue
+        err = oracle.rel_fro(from_device(g), r)
+        print("%s %s rel_fro=%.3e" % (tag, name, err), flush=True)
+        assert err <= tol, (tag, name, err)
+
+
+def test_config1_fp32():
+    """Config 1: fp32, X 256x768, r = 32; tolerance 1e-5."""
+    import torch
+    fhpc = _fhpc()
+    M, K, r, N = 256, 768, 32, 768
+    X, A, B, dY = lowrank_inputs(1, M, K, r, N, bf16=False)
+    Yr, Hr = oracle.lowrank_fwd(X, A, B)
+    ref = (Yr,) + oracle.lowrank_bwd(X, A, B, dY)
+    d = lambda a: torch.from_numpy(a).cuda()
+    Xd, Ad, Bd, dYd = d(X), d(A), d(B), d(dY)
+    Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+    assert oracle.rel_fro(from_device(H), Hr) <= TOL_F32
+    dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H)
+    _check_all("c1 saved-H", (Y, dX, dA, dB), ref, TOL_F32)
+    dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd)             # recompute H
+    _check_all("c1 recompute", (None, dX, dA, dB), ref, TOL_F32)
+
+
+@pytest.mark.parametrize("M,K,r,N", [
+    (300, 320, 64, 264),     # ragged in every dimension, several tiles
+    (1, 64, 8, 72),          # a single token
+    (257, 136, 5, 200),      # rank not a multiple of 8 (padded internally)
+    (515, 1024, 16, 520),    # LoRA-sized rank: split reductions for H and dH
+    (640, 512, 96, 1032),    # rank between tile sizes
+    (1100, 768, 512, 776),   # pretraining-sized rank
+])
+def test_bf16_shapes(M, K, r, N):
+    fhpc = _fhpc()
+    X, A, B, dY = lowrank_inputs(9, M, K, r, N, tensor_base=10)
+    Yr, Hr = oracle.lowrank_fwd(X.f64, A.f64, B.f64)
+    ref = (Yr,) + oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+    assert oracle.rel_fro(from_device(H), Hr) <= TOL_BF16
+    dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H)
+    _check_all("bf16 %s saved-H" % ((M, K, r, N),), (Y, dX, dA, dB), ref, TOL_BF16)
+    Y2 = fhpc.lowrank_linear_fwd(Xd, Ad, Bd)                          # no H_out
+    # (not bit-identical to Y: a split reduction's fp32 atomics may reorder the sum)
+    assert oracle.rel_fro(from_device(Y2), Yr) <= TOL_BF16
+    dX2, dA2, dB2 = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd)          # recompute H
+    _check_all("bf16 %s recompute" % ((M, K, r, N),), (None, dX2, dA2, dB2), ref, TOL_BF16)
+
+
+def test_bf16_optional_outputs_and_canaries():
+    """NULL outputs are skipped; nothing is written outside the output tensors."""
+    import torch
+    fhpc = _fhpc()
+    M, K, r, N = 130, 72, 24, 88
+    X, A, B, dY = lowrank_inputs(9, M, K, r, N, tensor_base=20)
+    ref = oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    pad = 1024
+    big = torch.full((M * K + 2 * pad,), 7.0, dtype=torch.bfloat16, device="cuda")
+    dX = big[pad:pad + M * K].view(M, K)
+    out = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, need_dA=False, need_dB=False, dX=dX)
+    assert out[1] is None and out[2] is None
+    assert oracle.rel_fro(from_device(dX), ref[0]) <= TOL_BF16
+    assert bool((big[:pad] == 7.0).all()) and bool((big[pad + M * K:] == 7.0).all())
+    _, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, need_dX=False)
+    assert oracle.rel_fro(from_device(dA), ref[1]) <= TOL_BF16
+    assert oracle.rel_fro(from_device(dB), ref[2]) <= TOL_BF16
+
+
+def test_config2_full_size_sampled():
+    """Config 2 at full size (16384 tokens, d = 4096, r = 512), the launch configuration the
+    benchmark times.  Y and dX are checked on sampled rows (rows are independent), dA on
+    sampled columns and dB on sampled rows (column j of dA / row j of dB depends only on
+    column j of A / row j of B through the rank index, so the oracle evaluates the layer
+    restricted to those rank indices)."""
+    fhpc = _fhpc()
+    M, K, r, N = 16384, 4096, 512, 4096
+    for proj in range(4):                     # q, k, v, o: four independent calls
+        X, A, B, dY = lowrank_inputs(2, M, K, r, N, tensor_base=10 * proj)
+        Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+        Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+        dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H)
+        rows = sample_rows(M, 100 + proj)
+        Yr, _ = oracle.lowrank_fwd(X.rows(rows).f64, A.f64, B.f64)
+        dXr, _, _ = oracle.lowrank_bwd(X.rows(rows).f64, A.f64, B.f64, dY.rows(rows).f64)
+        J = np.unique(np.random.default_rng(200 + proj).integers(0, r, size=8))
+        Af, Bf = A.f64, B.f64
+        _, dAr, dBr = oracle.lowrank_bwd(X.f64, Af[:, J], Bf[J, :], dY.f64)
+        errs = {
+            "Y": oracle.rel_fro(from_device(Y)[rows], Yr),
+            "dX": oracle.rel_fro(from_device(dX)[rows], dXr),
+            "dA": oracle.rel_fro(from_device(dA)[:, J], dAr),
+            "dB": oracle.rel_fro(from_device(dB)[J, :], dBr),
+        }
+        print("c2 proj %d: %s" % (proj, {k: "%.3e" % v for k, v in errs.items()}), flush=True)
+        for k, v in errs.items():
+            assert v <= TOL_BF16, (proj, k, v)

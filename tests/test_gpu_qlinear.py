@@ -1,0 +1,170 @@
+"""GPU parity of the quantised finetuning layer and of the weight-code kernels.
+Integer / byte work is compared bit for bit; GEMM outputs by relative Frobenius error."""
+import numpy as np
+import pytest
+
+import oracle
+from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, qlinear_inputs, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def _fhpc():
+    import paper_2402_13533_amd as fhpc
+    return fhpc
+
+
+def _quantize_host(W, scheme):
+    return oracle.quantize_int8_perchannel(W) if scheme == 8 else oracle.quantize_int4_block(W, 64)
+
+
+def _to_dev(Wq, sc):
+    import torch
+    return torch.from_numpy(Wq).cuda(), f16_bits_cuda(sc)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+def test_unpack_and_dequant_bit_exact(scheme):
+    """Every byte value (so every nibble pair, including the code -8) and every int8 code."""
+    import torch
+    fhpc = _fhpc()
+    rng = np.random.default_rng(5)
+    N, K = 64, 256
+    if scheme == 4:
+        Wq = np.tile(np.arange(256, dtype=np.uint8), N * (K // 2) // 256).reshape(N, K // 2)
+        sc = rng.integers(0x0001, 0x7BFF, size=(N, K // 64)).astype(np.uint16)   # subnormals too
+    else:
+        Wq = np.tile(np.arange(256, dtype=np.uint8), N * K // 256).reshape(N, K).view(np.int8)
+        sc = rng.integers(0x0001, 0x7BFF, size=(N,)).astype(np.uint16)
+    sc.flat[0] = 0
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    q = from_device(fhpc.qweight_unpack(Wq_d, scheme))
+    q_ref = Wq if scheme == 8 else oracle.unpack_int4(Wq)
+    assert q.dtype == np.int8 and np.array_equal(q, q_ref)
+    Wd = fhpc.qweight_dequant(Wq_d, sc_d, scheme).cpu().numpy()            # fp32 [N][K]
+    Wd_ref = oracle.dequant(Wq, sc, scheme, 64).T                          # exact in fp64
+    assert np.array_equal(Wd.astype(np.float64), Wd_ref)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+def test_quantize_bit_exact(scheme):
+    import torch
+    fhpc = _fhpc()
+    from paper_2402_13533_amd import synth
+    K, N = 512, 200
+    W = synth.normal(77 + scheme, (K, N), 0.02)
+    W[:, 3] = 0.0                                    # zero vector -> zero scale and codes
+    W[5, 7] = 0.3                                    # outlier
+    # exact ties: w = (c + 0.5) * 2^-10 with absmax 127 * 2^-10 (int8) / (c + .5) * 2^-6, absmax 7 * 2^-6
+    if scheme == 8:
+        W[:, 9] = (np.arange(K) % 120 + 0.5) * 2.0 ** -10
+        W[0, 9] = 127 * 2.0 ** -10
+    else:
+        W[:, 9] = (np.arange(K) % 6 + 0.5) * 2.0 ** -6
+        W[::64, 9] = 7 * 2.0 ** -6
+    Wq_ref, sc_ref = _quantize_host(W, scheme)
+    Wq, sc = fhpc.qweight_quantize(torch.from_numpy(W).cuda(), scheme)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), sc_ref)
+    assert np.array_equal(Wq.cpu().numpy().view(Wq_ref.dtype), Wq_ref)
+
+
+def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
+    fhpc = _fhpc()
+    W, X, A, B, dY = qlinear_inputs(config, M, K, r, N, tensor_base)
+    Wq, sc = _quantize_host(W, scheme)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y, H = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)
+    dX, dA, dB = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H)
+    dX2, dA2, dB2 = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd)     # recompute H
+    if rows is None:
+        Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, s)
+        dXr, dAr, dBr = oracle.qlinear_lowrank_bwd(X.f64, Wd, A.f64, B.f64, s, dY.f64)
+        sel = slice(None)
+    else:
+        # rows of Y / dX are independent; dA, dB need every token but not the base weight
+        Yr, _ = oracle.qlinear_lowrank_fwd(X.rows(rows).f64, Wd, A.f64, B.f64, s)
+        dXr, _, _ = oracle.qlinear_lowrank_bwd(X.rows(rows).f64, Wd, A.f64, B.f64, s, dY.rows(rows).f64)
+        _, dAr, dBr = oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+        dAr, dBr = s * dAr, s * dBr
+        Hr = None
+        sel = rows
+    errs = {
+        "Y": oracle.rel_fro(from_device(Y)[sel], Yr),
+        "dX": oracle.rel_fro(from_device(dX)[sel], dXr),
+        "dA": oracle.rel_fro(from_device(dA), dAr),
+        "dB": oracle.rel_fro(from_device(dB), dBr),
+        "dX(recompute)": oracle.rel_fro(from_device(dX2)[sel], dXr),
+        "dA(recompute)": oracle.rel_fro(from_device(dA2), dAr),
+        "dB(recompute)": oracle.rel_fro(from_device(dB2), dBr),
+    }
+    if Hr is not None:
+        errs["H"] = oracle.rel_fro(from_device(H), Hr)
+    print(tag, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (tag, k, v)
+    # the low-rank branch must be visible above the tolerance-sized noise of the base
+    # product, or the test would not notice a missing branch: check it separately with
+    # the frozen weight's contribution removed in fp64
+    if rows is None and s != 0.0:
+        base = X.f64 @ Wd
+        lr_ref = Yr - base
+        lr_got = from_device(Y) - base
+        e = oracle.rel_fro(lr_got, lr_ref)
+        print(tag, "low-rank branch alone rel_fro %.3e" % e, flush=True)
+        assert e < 0.15, (tag, e)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,K,r,N", [
+    (300, 320, 8, 264),
+    (1, 64, 16, 72),
+    (515, 1024, 5, 520),      # rank padded internally
+    (260, 512, 64, 328),
+])
+def test_qlinear_shapes(scheme, M, K, r, N):
+    if scheme == 4:
+        K = (K + 63) // 64 * 64
+    _run_case("q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=30)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+def test_qlinear_scaling_zero_is_base_layer(scheme):
+    fhpc = _fhpc()
+    M, K, r, N = 200, 256, 8, 264
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 40)
+    Wq, sc = _quantize_host(W, scheme)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0)
+    assert oracle.rel_fro(from_device(Y), X.f64 @ Wd) <= TOL_BF16
+    dX, dA, dB = fhpc.qlinear_lowrank_bwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0, dY.cuda())
+    assert oracle.rel_fro(from_device(dX), dY.f64 @ Wd.T) <= TOL_BF16
+    assert not from_device(dA).any() and not from_device(dB).any()
+    # all-zero codes: the layer reduces to scaling * (X A) B, which pins the rank-r branch
+    # (and its scaling) on its own at the full tolerance
+    Wz = (np.zeros_like(Wq), sc)
+    Wz_d, scz_d = _to_dev(*Wz)
+    s = 1.5
+    Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wz_d, scz_d, scheme, A.cuda(), B.cuda(), s)
+    assert oracle.rel_fro(from_device(Y), s * oracle.lowrank_fwd(X.f64, A.f64, B.f64)[0]) <= TOL_BF16
+    dX, dA, dB = fhpc.qlinear_lowrank_bwd(X.cuda(), Wz_d, scz_d, scheme, A.cuda(), B.cuda(), s, dY.cuda())
+    for g, r_ in zip((dX, dA, dB), oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)):
+        assert oracle.rel_fro(from_device(g), s * r_) <= TOL_BF16
+
+
+def test_config4_full_size():
+    """Config 4: int8 per-channel W 4096x4096, r = 8, scaling 2, 4096 tokens (full oracle
+    for dA/dB, sampled rows for Y and dX)."""
+    M = 4096
+    _run_case("c4", 8, M, 4096, 8, 4096, 2.0, 4, rows=sample_rows(M, 4))
+
+
+def test_config5_full_size():
+    """Config 5: the seven linears of a Llama-2-13B decoder layer, 4-bit block-64 W,
+    r = 16, scaling 2, 4096 tokens."""
+    M, d, f = 4096, 5120, 13824
+    shapes = [("q", d, d), ("k", d, d), ("v", d, d), ("o", d, d), ("gate", d, f), ("up", d, f), ("down", f, d)]
+    for i, (name, K, N) in enumerate(shapes):
+        _run_case("c5 %s" % name, 4, M, K, 16, N, 2.0, 5, tensor_base=10 * i, rows=sample_rows(M, 50 + i, 128))
