@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the factorised-layer hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is
+already resident in HBM.  Default workload (config 2): forward + backward of the four
+Llama-2-7B attention projections, each factorised with r = 512, on 16384 tokens in bf16.
+Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic per launch of a kernel on a workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (summaries under profiles/); None where not yet measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--recompute", action="store_true", help="backward recomputes H instead of reading the saved copy")
+    return ap.parse_args()
+
+
+# ----------------------------------------------------------------------------- workloads
+
+def randn(shape, std, dtype, gen):
+    import torch
+    return (torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen) * std).to(dtype)
+
+
+class LowrankCall:
+    """One factorised linear: preallocated tensors, fwd and bwd through the C ABI."""
+
+    def __init__(self, fhpc, M, K, r, N, dtype, gen, recompute=False):
+        import torch
+        self.f = fhpc
+        self.M, self.K, self.r, self.N = M, K, r, N
+        self.X = randn((M, K), 1.0, dtype, gen)
+        self.dY = randn((M, N), 1.0, dtype, gen)
+        self.A = randn((K, r), K ** -0.5, dtype, gen)
+        self.B = randn((r, N), r ** -0.5, dtype, gen)
+        self.Y = torch.empty((M, N), dtype=dtype, device="cuda")
+        self.H = torch.empty((M, r), dtype=dtype, device="cuda")
+        self.dX = torch.empty((M, K), dtype=dtype, device="cuda")
+        self.dA = torch.empty((K, r), dtype=torch.float32, device="cuda")
+        self.dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+        self.recompute = recompute
+
+    def flops(self):
+        from paper_2402_13533_amd import shapes
+        return shapes.lowrank_flops(self.M, self.K, self.r, self.N)
+
+    def io_bytes(self):
+        e = self.X.element_size()
+        return e * (2 * self.M * self.K + 2 * self.M * self.N) + (e + 4) * self.r * (self.K + self.N)
+
+    def run(self):
+        self.f.lowrank_linear_fwd(self.X, self.A, self.B, Y=self.Y, H_out=self.H)
+        self.f.lowrank_linear_bwd(self.X, self.A, self.B, self.dY, H_saved=None if self.recompute else self.H,
+                                  dX=self.dX, dA=self.dA, dB=self.dB)
+
+
+class QlinearCall:
+    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False):
+        import torch
+        bf = torch.bfloat16
+        self.f = fhpc
+        self.M, self.K, self.r, self.N, self.scheme, self.s = M, K, r, N, scheme, scaling
+        W = randn((K, N), 0.02, torch.float32, gen)
+        self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)       # frozen base weight, quantised on the GPU
+        del W
+        self.X = randn((M, K), 1.0, bf, gen)
+        self.dY = randn((M, N), 1.0, bf, gen)
+        self.A = randn((K, r), K ** -0.5, bf, gen)
+        self.B = randn((r, N), 0.01, bf, gen)
+        self.Y = torch.empty((M, N), dtype=bf, device="cuda")
+        self.H = torch.empty((M, r), dtype=bf, device="cuda")
+        self.dX = torch.empty((M, K), dtype=bf, device="cuda")
+        self.dA = torch.empty((K, r), dtype=torch.float32, device="cuda")
+        self.dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+        self.recompute = recompute
+
+    def flops(self):
+        from paper_2402_13533_amd import shapes
+        return shapes.qlinear_lowrank_flops(self.M, self.K, self.r, self.N)
+
+    def io_bytes(self):
+        w = self.Wq.numel() + 2 * self.sc.numel()
+        return 2 * w + 2 * (2 * self.M * self.K + 2 * self.M * self.N) + 6 * self.r * (self.K + self.N)
+
+    def run(self):
+        f = self.f
+        f.qlinear_lowrank_fwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, Y=self.Y, H_out=self.H)
+        f.qlinear_lowrank_bwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, self.dY,
+                              H_saved=None if self.recompute else self.H, dX=self.dX, dA=self.dA, dB=self.dB)
+
+
+class FfnCall:
+    """Config 3: gate/up 4096 -> r -> 11008, SiLU gate, down 11008 -> r -> 4096, fwd + bwd."""
+
+    def __init__(self, fhpc, M, d, r, f, gen):
+        import torch
+        bf = torch.bfloat16
+        self.fh = fhpc
+        self.M, self.d, self.r, self.f = M, d, r, f
+        self.X = randn((M, d), 1.0, bf, gen)
+        self.dY = randn((M, d), 1.0, bf, gen)
+        self.W = [randn((d, r), d ** -0.5, bf, gen), randn((r, f), r ** -0.5, bf, gen),
+                  randn((d, r), d ** -0.5, bf, gen), randn((r, f), r ** -0.5, bf, gen),
+                  randn((f, r), f ** -0.5, bf, gen), randn((r, d), r ** -0.5, bf, gen)]
+
+    def flops(self):
+        from paper_2402_13533_amd import shapes
+        return 2 * shapes.lowrank_flops(self.M, self.d, self.r, self.f) + shapes.lowrank_flops(self.M, self.f, self.r, self.d)
+
+    def io_bytes(self):
+        return 2 * (4 * self.M * self.d) + 6 * 3 * self.r * (self.d + self.f)
+
+    def run(self):
+        from paper_2402_13533_amd import ffn
+        Y, saved = ffn.ffn_fwd(self.X, *self.W)
+        ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
+
+
+def build_workload(name, fhpc, recompute):
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20240213)
+    bf = torch.bfloat16
+    if name == "c1":
+        calls = [LowrankCall(fhpc, 256, 768, 32, 768, torch.float32, gen, recompute)]
+        desc = "config 1: fp32 factorised linear 256x768, r=32, fwd+bwd"
+        dtype = "f32"
+    elif name == "c2":
+        calls = [LowrankCall(fhpc, 16384, 4096, 512, 4096, bf, gen, recompute) for _ in range(4)]
+        desc = "config 2: Llama-2-7B q/k/v/o projections factorised r=512, 16384 tokens, bf16, fwd+bwd"
+        dtype = "bf16"
+    elif name == "c3":
+        calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen)]
+        desc = "config 3: Llama-2-7B SiLU-gated FFN factorised r=1024, 16384 tokens, bf16, fwd+bwd"
+        dtype = "bf16"
+    elif name == "c4":
+        calls = [QlinearCall(fhpc, 4096, 4096, 8, 4096, 8, gen, 2.0, recompute)]
+        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, 4096 tokens, bf16, fwd+bwd"
+        dtype = "bf16"
+    else:
+        d, f = 5120, 13824
+        shp = [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
+        calls = [QlinearCall(fhpc, 4096, K, 16, N, 4, gen, 2.0, recompute) for K, N in shp]
+        desc = "config 5: Llama-2-13B decoder layer, 7 linears, int4 block-64 frozen W + rank-16 branch, 4096 tokens, bf16, fwd+bwd"
+        dtype = "bf16"
+    return calls, desc, dtype
+
+
+# ----------------------------------------------------------------------------- CPU baseline
+
+def cpu_baseline(workload):
+    """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2402_13533_amd import shapes, synth
+    if workload in ("c1", "c2"):
+        K, r, N = (768, 32, 768) if workload == "c1" else (4096, 512, 4096)
+    elif workload == "c3":
+        K, r, N = 4096, 1024, 11008
+    elif workload == "c4":
+        K, r, N = 4096, 8, 4096
+    else:
+        K, r, N = 5120, 16, 5120
+    quant = workload in ("c4", "c5")
+
+    def run(M):
+        X = synth.normal(1, (M, K)).astype(np.float64)
+        dY = synth.normal(2, (M, N)).astype(np.float64)
+        A = synth.normal(3, (K, r), K ** -0.5).astype(np.float64)
+        B = synth.normal(4, (r, N), r ** -0.5).astype(np.float64)
+        if quant:
+            Wd = synth.normal(5, (K, N), 0.02).astype(np.float64)
+            t0 = time.perf_counter()
+            oracle.qlinear_lowrank_fwd(X, Wd, A, B, 2.0)
+            oracle.qlinear_lowrank_bwd(X, Wd, A, B, 2.0, dY)
+            dt = time.perf_counter() - t0
+            fl = shapes.qlinear_lowrank_flops(M, K, r, N)
+        else:
+            t0 = time.perf_counter()
+            oracle.lowrank_fwd(X, A, B)
+            oracle.lowrank_bwd(X, A, B, dY)
+            dt = time.perf_counter() - t0
+            fl = shapes.lowrank_flops(M, K, r, N)
+        return dt, fl
+
+    m0 = 64 if workload != "c1" else 256
+    dt, fl = run(m0)                                   # calibration
+    target = 15.0
+    M = m0
+    if workload != "c1":
+        M = int(min(16384, max(m0, m0 * target / max(dt, 1e-3))))
+        M = max(64, M // 64 * 64)
+        dt, fl = run(M)
+    return {
+        "value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "fp64 oracle fwd+bwd of one linear of the workload (K=%d, r=%d, N=%d) on %d token rows, %.1f s"
+                  % (K, r, N, M, dt),
+    }
+
+
+# ----------------------------------------------------------------------------- main
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus %d is not supported (the layer shards over "
+              "tokens with one all-reduce of dA/dB per step, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2402_13533_amd as fhpc
+    fhpc.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute)
+    flops = sum(c.flops() for c in calls)
+    io_bytes = sum(c.io_bytes() for c in calls)
+
+    def step():
+        for c in calls:
+            c.run()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    # second pass over the same steps with an event pair around every GEMM launch (library hook)
+    fhpc.profile_start(8192)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    recs = fhpc.profile_stop()
+    agg = {}
+    for name, ms, fl in recs:
+        a = agg.setdefault(name, [0, 0.0, 0.0])
+        a[0] += 1; a[1] += ms; a[2] += fl
+    kernels = {n: {"launches_per_step": a[0] / args.steps, "avg_ms": a[1] / a[0], "flops_per_launch": a[2] / a[0],
+                   "tflops": a[2] / a[1] / 1e9 if a[1] > 0 else None}
+               for n, a in agg.items()}
+    roofline = None
+    if agg:
+        dom = max(agg, key=lambda n: agg[n][1])
+        k = kernels[dom]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                    "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": agg[dom][1] / sum(a[1] for a in agg.values())}
+
+    out = {
+        "metric": "fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": desc, "saved_H": not args.recompute},
+        "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "io_gbs": io_bytes / (ms_per_step * 1e-3) / 1e9, "frac_hbm_peak_on_io_bytes": io_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -139,6 +139,17 @@ int qweight_dequant(const void* Wq, const void* scales, int qscheme, int block, 
 /* Static, NUL-terminated description of a status code. */
 const char* fhpc_status_string(int status);
 
+/* Diagnostic per-launch timing (off by default; not thread-safe; host-side state only).
+ * fhpc_profile_start arms a pool of `max_records` HIP event pairs; while armed, every
+ * matrix-core GEMM launch records an event before and after itself on its stream, which
+ * costs a few microseconds per launch.  fhpc_profile_stop disarms and returns the number
+ * of launches recorded.  fhpc_profile_get waits for record `index` and returns the
+ * kernel's name (NUL-terminated, truncated to name_len), its duration in milliseconds and
+ * the algorithmic flop count of that launch (bytes is reserved, 0). */
+int fhpc_profile_start(int max_records);
+int fhpc_profile_stop(void);
+int fhpc_profile_get(int index, char* name, int name_len, float* ms, double* flops, double* bytes);
+
 /* Library version (major * 100 + minor). */
 int fhpc_version(void);
 

@@ -19,7 +19,8 @@ FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_B
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
-    "qweight_dequant", "fhpc_add", "fhpc_status_string", "fhpc_version",
+    "qweight_dequant", "fhpc_add", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
+    "fhpc_status_string", "fhpc_version",
 ]
 
 _lib = None
@@ -55,6 +56,10 @@ def load_library():
     lib.qweight_unpack.argtypes = [vp, i32, vp, i64, i64, vp]
     lib.qweight_dequant.argtypes = [vp, vp, i32, i32, vp, i64, i64, vp]
     lib.fhpc_add.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.fhpc_profile_start.argtypes = [i32]
+    lib.fhpc_profile_stop.argtypes = []
+    lib.fhpc_profile_get.argtypes = [i32, C.c_char_p, i32, C.POINTER(C.c_float), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_double)]
     lib.fhpc_status_string.argtypes = [i32]
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
@@ -63,6 +68,27 @@ def load_library():
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
+
+
+def profile_start(max_records: int = 4096) -> None:
+    rc = load_library().fhpc_profile_start(max_records)
+    if rc:
+        raise FhpcError(rc, "fhpc_profile_start")
+
+
+def profile_stop():
+    """Disarm and return [(kernel name, milliseconds, flops)] for every recorded launch."""
+    lib = load_library()
+    n = lib.fhpc_profile_stop()
+    out = []
+    buf = C.create_string_buffer(64)
+    ms, fl, by = C.c_float(), C.c_double(), C.c_double()
+    for i in range(n):
+        rc = lib.fhpc_profile_get(i, buf, 64, C.byref(ms), C.byref(fl), C.byref(by))
+        if rc:
+            raise FhpcError(rc, "fhpc_profile_get")
+        out.append((buf.value.decode(), float(ms.value), float(fl.value)))
+    return out
 
 
 def status_string(status: int) -> str:

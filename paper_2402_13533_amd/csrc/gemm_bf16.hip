@@ -11,6 +11,9 @@
 // A-side tile its column operand, so a lane ends up holding 4 consecutive output
 // columns n of one output row m (16-byte fp32 / 8-byte bf16 stores).
 #include "gemm_bf16.h"
+#include "profile.h"
+
+#include <stdio.h>
 
 namespace fhpc {
 
@@ -577,7 +580,11 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s)
 {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     dim3 grid((unsigned)tiles, 1, (unsigned)(a.splits > 1 ? a.splits : 1));
+    char name[64];
+    snprintf(name, sizeof(name), "gemm_bf16<%dx%d,a%d,b%d,l%d,o%d>", BM, BN, AM, BMODE, B2, OUT);
+    const int slot = prof_begin(name, 2.0 * a.M * a.N * ((double)a.K + a.K2), 0.0, s);
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, AM, BMODE, B2, OUT>), grid, dim3(NTHREADS), 0, s, a);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 
