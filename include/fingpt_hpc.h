@@ -139,6 +139,20 @@ int qweight_dequant(const void* Wq, const void* scales, int qscheme, int block, 
 /* Static, NUL-terminated description of a status code. */
 const char* fhpc_status_string(int status);
 
+/* Diagnostic: one launch of the bf16 matrix-core GEMM that the entry points above are
+ * built from,  C[M,N] = alpha * sum_k A(m,k) B(n,k)  with fp32 accumulation.
+ * a_mode / b_mode say how element (row, k) of an operand is stored: 0 = bf16 ptr[row*ld + k],
+ * 1 = bf16 ptr[k*ld + row].  out_mode: 0 = bf16 C, 1 = fp32 C (required when splits > 1:
+ * slice s of the reduction then stores its partial sums to C + s*M*ldc, so C must hold
+ * `splits` slabs of M*ldc floats and the caller adds them).  tile: 0 = 256x256,
+ * 1 = 128x256, 2 = 256x128, 3 = 128x128, 4 = 256x32, 5 = 32x256 (the last two with out_mode 1
+ * only).  splits cuts the reduction into that many slices.  dbg must be 0 (bit 0 suppresses
+ * operand traffic, bit 1 the matrix instructions; results are then meaningless).
+ * Returns FHPC_ERR_UNSUPPORTED for a combination that is not instantiated. */
+int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_t ldb, int b_mode,
+                   void* C, int64_t ldc, int out_mode, int64_t M, int64_t N, int64_t K, float alpha,
+                   int tile, int splits, int dbg, void* hip_stream);
+
 /* Diagnostic per-launch timing (off by default; not thread-safe; host-side state only).
  * fhpc_profile_start arms a pool of `max_records` HIP event pairs; while armed, every
  * matrix-core GEMM launch records an event before and after itself on its stream, which

@@ -9,6 +9,8 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+C_float = C.c_float
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
 
@@ -19,7 +21,7 @@ FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_B
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
-    "qweight_dequant", "fhpc_add", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
+    "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
 ]
 
@@ -56,6 +58,7 @@ def load_library():
     lib.qweight_unpack.argtypes = [vp, i32, vp, i64, i64, vp]
     lib.qweight_dequant.argtypes = [vp, vp, i32, i32, vp, i64, i64, vp]
     lib.fhpc_add.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.fhpc_gemm_bf16.argtypes = [vp, i64, i32, vp, i64, i32, vp, i64, i32, i64, i64, i64, f32, i32, i32, i32, vp]
     lib.fhpc_profile_start.argtypes = [i32]
     lib.fhpc_profile_stop.argtypes = []
     lib.fhpc_profile_get.argtypes = [i32, C.c_char_p, i32, C.POINTER(C.c_float), C.POINTER(C.c_double),
@@ -298,6 +301,15 @@ def fhpc_add(a, b, out=None):
     if rc:
         raise FhpcError(rc, "fhpc_add")
     return out
+
+
+def fhpc_gemm_bf16(A, lda, a_mode, B, ldb, b_mode, C, ldc, out_mode, M, N, K, alpha=1.0, tile=0, splits=1, dbg=0):
+    """Diagnostic: one launch of the GEMM core (see the header for the argument meanings)."""
+    rc = load_library().fhpc_gemm_bf16(_ptr(A), lda, a_mode, _ptr(B), ldb, b_mode, _ptr(C), ldc, out_mode,
+                                       M, N, K, C_float(alpha), tile, splits, dbg, _stream())
+    if rc:
+        raise FhpcError(rc, "fhpc_gemm_bf16")
+    return C
 
 
 def qweight_quantize(W, qscheme, block=64):

@@ -47,9 +47,55 @@ struct Scratch {
     float* Hf = nullptr;    // fp32 [M][rp]   split-K accumulator for the rank-r products
     float* dA_t = nullptr;  // fp32 [K][rp]
     float* dB_t = nullptr;  // fp32 [rp][N]
+    float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
+
+int64_t tile_count(int tile, int64_t M, int64_t N)
+{
+    int bm, bn;
+    gemm_tile_extent(tile, &bm, &bn);
+    return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+}
+
+// How an fp32-output product whose reduction is split across workgroups is launched:
+// the largest tile that fits the output (the splits, not the tiles, fill the chip) and
+// as many slices of the reduction as it takes to occupy every compute unit.
+struct SplitPlan {
+    int tile, splits, k_chunk;
+};
+
+SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
+{
+    SplitPlan sp;
+    if (N <= 32) sp.tile = TILE_256x32;
+    else if (M <= 32) sp.tile = TILE_32x256;
+    else if (M > 128 && N > 128) sp.tile = TILE_256x256;
+    else if (M > 128) sp.tile = TILE_256x128;
+    else if (N > 128) sp.tile = TILE_128x256;
+    else sp.tile = TILE_128x128;
+    const int64_t tiles = tile_count(sp.tile, M, N);
+    const int64_t ksteps = (Kred + 63) / 64;
+    // the eight-wave tiles occupy a compute unit alone; the smaller ones run two at a time
+    const bool big = (sp.tile == TILE_256x256 || sp.tile == TILE_256x128 || sp.tile == TILE_128x256);
+    const int64_t target = big ? kNumCU : 2 * kNumCU;
+    int64_t s = (target + tiles - 1) / tiles;
+    if (s > ksteps) s = ksteps;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    const int64_t steps_per = (ksteps + s - 1) / s;
+    sp.k_chunk = (int)(steps_per * 64);
+    sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
+    return sp;
+}
+
+// Bytes of partial-sum slabs for an M x N (leading dimension ldc) product reduced over Kred.
+int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred)
+{
+    const SplitPlan sp = plan_split(M, N, Kred);
+    return sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0;
+}
 
 Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
 {
@@ -73,6 +119,18 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         s.dA_t = static_cast<float*>(c.take(K * rp * 4));
         s.dB_t = static_cast<float*>(c.take(rp * N * 4));
     }
+    // split reductions of this entry point run one after another and share the slabs
+    int64_t part = 0;
+    auto upto = [&part](int64_t b) { if (b > part) part = b; };
+    if (rp <= 32) {
+        upto(split_bytes(M, rp, rp, K));               // H  = X A
+        if (bwd) upto(split_bytes(M, rp, rp, N));      // dH = dY B^T
+    }
+    if (bwd) {
+        upto(split_bytes(K, rp, rp, M));               // dA = X^T dH
+        upto(split_bytes(rp, N, N, M));                // dB = H^T dY
+    }
+    s.part = static_cast<float*>(c.take(part));
     return s;
 }
 
@@ -107,26 +165,6 @@ int pick_tile(int64_t M, int64_t N, bool allow_skinny)
     return best;
 }
 
-int64_t tile_count(int tile, int64_t M, int64_t N)
-{
-    int bm, bn;
-    gemm_tile_extent(tile, &bm, &bn);
-    return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-}
-
-// Splits of the reduction so that a small output still fills the chip.
-void pick_splits(int tile, int64_t M, int64_t N, int64_t Kred, int* splits, int* k_chunk)
-{
-    const int64_t tiles = tile_count(tile, M, N);
-    const int64_t ksteps = (Kred + 63) / 64;
-    int64_t s = (2 * kNumCU + tiles - 1) / tiles;
-    if (s > ksteps) s = ksteps;
-    if (s < 1) s = 1;
-    const int64_t steps_per = (ksteps + s - 1) / s;
-    *k_chunk = (int)(steps_per * 64);
-    *splits = (int)((ksteps + steps_per - 1) / steps_per);
-}
-
 GemmOperand operand(const void* p, int64_t ld, const void* scales = nullptr, int64_t sld = 0)
 {
     GemmOperand o;
@@ -148,29 +186,37 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
     return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, N, false), g, st);
 }
 
-// C[M,N] fp32 (ldc) = alpha * A * B with the reduction split across workgroups and
-// accumulated with fp32 atomics; C is zeroed first.
+// C[M,N] fp32 (ldc) = alpha * A * B with the reduction split across workgroups: every
+// slice stores its partial sums to its own slab of `part` (no atomics, so the result does
+// not depend on scheduling) and a second kernel adds the slabs into C.
 hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
-                          int64_t M, int64_t N, int64_t Kred, float alpha, hipStream_t st)
+                          int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st)
 {
-    hipError_t e = launch_zero(C, M * ldc * 4, st);
-    if (e != hipSuccess) return e;
+    const SplitPlan sp = plan_split(M, N, Kred);
     GemmArgs g = {};
-    g.a = a; g.b = b; g.c = C; g.ldc = ldc;
+    g.a = a; g.b = b; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
     g.alpha = alpha; g.mid_scale = 1.f;
-    const int tile = pick_tile(M, N, true);
-    pick_splits(tile, M, N, Kred, &g.splits, &g.k_chunk);
-    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_F32_ATOMIC, tile, g, st);
+    g.splits = sp.splits; g.k_chunk = sp.k_chunk;
+    if (sp.splits == 1) {
+        g.c = C;
+        g.split_stride = 0;
+        return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_F32, sp.tile, g, st);
+    }
+    g.c = part;
+    g.split_stride = M * ldc;
+    hipError_t e = launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_F32, sp.tile, g, st);
+    if (e != hipSuccess) return e;
+    return launch_sum_slabs(part, M * ldc, sp.splits, C, st);
 }
 
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
 // split the long reduction, accumulate in fp32, then round once to bf16.
-hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf,
+hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf, float* part,
                         int64_t M, int64_t Kred, hipStream_t st)
 {
     if (rp <= 32) {
-        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, st);
+        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, st);
         if (e != hipSuccess) return e;
         return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
     }
@@ -205,12 +251,12 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
 {
     if (dA) {
         float* dst = (rp == r) ? dA : s.dA_t;
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, st));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, s.part, st));
         if (rp != r) FHPC_HIP(launch_compact_f32(s.dA_t, rp, dA, r, K, r, 1.f, false, st));
     }
     if (dB) {
         float* dst = (rp == r) ? dB : s.dB_t;
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(H, rp), operand(dY, N), dst, N, rp, N, M, alpha, st));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(H, rp), operand(dY, N), dst, N, rp, N, M, alpha, s.part, st));
         if (rp != r) FHPC_HIP(launch_compact_f32(s.dB_t, N, dB, N, r, N, 1.f, false, st));
     }
     return FHPC_OK;
@@ -305,7 +351,7 @@ int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, voi
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
-    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, M, K, st));
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
     FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st));
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
     return FHPC_OK;
@@ -344,12 +390,12 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
             FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
             H = s.H;
         } else {
-            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, M, K, st));
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, st));
             H = s.H;
         }
     }
     if (dX || dA)
-        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, M, N, st));
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX)
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st));
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
@@ -378,7 +424,7 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
-    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, M, K, st));
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
 
     GemmArgs g = {};
     g.a = operand(X, K);
@@ -425,12 +471,12 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
             FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
             H = s.H;
         } else {
-            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, M, K, st));
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, st));
             H = s.H;
         }
     }
     if (dX || dA)
-        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, M, N, st));
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX) {
         // dX[m][k] = sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};
@@ -512,6 +558,33 @@ int qweight_dequant(const void* Wq, const void* scales, int qscheme, int block, 
     int rc = check_qweight(qscheme, block, K, N, true);
     if (rc) return rc;
     FHPC_HIP(launch_dequant(Wq, scales, qscheme, block, W_out, K, N, static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_t ldb, int b_mode,
+                   void* C, int64_t ldc, int out_mode, int64_t M, int64_t N, int64_t K, float alpha,
+                   int tile, int splits, int dbg, void* hip_stream)
+{
+    if (!A || !B || !C) return FHPC_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || (K % 8) || (N % 8) || splits < 1) return FHPC_ERR_SHAPE;
+    if ((a_mode != OP_KC && a_mode != OP_XC) || (b_mode != OP_KC && b_mode != OP_XC)) return FHPC_ERR_DTYPE;
+    if (a_mode == OP_XC && (M % 8)) return FHPC_ERR_SHAPE;
+    if (M * K * 2 >= kMaxBytes || N * K * 2 >= kMaxBytes || tile < 0 || tile >= TILE_COUNT) return FHPC_ERR_UNSUPPORTED;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(C, 16)) return FHPC_ERR_ALIGN;
+    GemmArgs g = {};
+    g.a = operand(A, lda);
+    g.b = operand(B, ldb);
+    g.c = C; g.ldc = ldc;
+    g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = 0;
+    g.alpha = alpha; g.mid_scale = 1.f; g.dbg = dbg;
+    const int64_t ksteps = (K + 63) / 64;
+    const int64_t per = (ksteps + splits - 1) / splits;
+    g.k_chunk = (int)(per * 64);
+    g.splits = (int)((ksteps + per - 1) / per);
+    g.split_stride = M * ldc;
+    hipError_t e = launch_gemm_bf16(a_mode, b_mode, OP_NONE, out_mode, tile, g, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return FHPC_ERR_UNSUPPORTED;
+    FHPC_HIP(e);
     return FHPC_OK;
 }
 

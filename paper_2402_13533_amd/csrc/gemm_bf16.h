@@ -25,13 +25,15 @@ enum : int {
     OP_NONE = 6
 };
 
-enum : int { OUT_BF16 = 0, OUT_F32 = 1, OUT_F32_ATOMIC = 2 };
+// OUT_F32: fp32 C.  With a split reduction, split s writes its partial sum to
+// c + s * split_stride (plain stores, no atomics); the caller adds the slabs afterwards.
+enum : int { OUT_BF16 = 0, OUT_F32 = 1 };
 
-// Tile shapes (BM x BN, four 64-lane waves arranged WAVES_M x WAVES_N).
+// Tile shapes (BM x BN) and the wave grid that covers them.
 enum : int {
-    TILE_256x256 = 0,  // 2 x 2 waves of 128 x 128
-    TILE_128x256 = 1,  // 2 x 2 waves of 64 x 128
-    TILE_256x128 = 2,  // 2 x 2 waves of 128 x 64
+    TILE_256x256 = 0,  // 2 x 4 waves of 128 x 64
+    TILE_128x256 = 1,  // 2 x 4 waves of 64 x 64, ping-pong schedule
+    TILE_256x128 = 2,  // 4 x 2 waves of 64 x 64, ping-pong schedule
     TILE_128x128 = 3,  // 2 x 2 waves of 64 x 64
     TILE_256x32 = 4,   // 4 x 1 waves of 64 x 32   (rank-r outputs: H, dH, dA)
     TILE_32x256 = 5,   // 1 x 4 waves of 32 x 64   (dB)
@@ -53,14 +55,22 @@ struct GemmArgs {
     int M, N, K, K2;
     float alpha;
     float mid_scale;
-    int splits;            // >1: blockIdx.z slices of k_chunk (multiple of 64); needs OUT_F32_ATOMIC
+    int splits;            // >1: the reduction is cut into slices of k_chunk (multiple of 64); needs OUT_F32
     int k_chunk;
+    int64_t split_stride;  // elements between the partial-sum slabs of consecutive splits
+    int dbg;               // diagnostics: bit 0 = request no operand data (all loads out of range),
+                           // bit 1 = skip the matrix instructions.  0 in normal use.
 };
 
 // Launches the instantiation (a_mode, b_mode, b2_mode, out_mode, tile).  a2 is always OP_KC.
 // Returns hipErrorInvalidValue when that combination is not instantiated.
 hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, int tile,
                             const GemmArgs& args, hipStream_t stream);
+
+// The eight-wave ping-pong kernels (gemm_pp.hip) cover the plain bf16 products on the
+// 256x256 and 256x128 tiles; launch_gemm_bf16 routes to them unless args.dbg bit 2 is set.
+bool gemm_pp_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int tile);
+hipError_t launch_gemm_pp(int a_mode, int b_mode, int out_mode, int tile, const GemmArgs& args, hipStream_t stream);
 
 // Tile extents, for planning on the host.
 void gemm_tile_extent(int tile, int* bm, int* bn);

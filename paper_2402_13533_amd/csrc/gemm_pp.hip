@@ -1,0 +1,570 @@
+// Eight-wave "ping-pong" bf16 GEMM for gfx950 with global -> LDS loads that bypass the
+// register file (buffer_load ... lds), a ring of LDS stages, and the CDNA4 transposing LDS
+// read for operands whose output index is the contiguous one.
+//
+// Schedule.  The workgroup is two groups of four waves (one wave of each group per SIMD).
+// Time is cut into phases separated by workgroup barriers.  In odd phases group 0 reads the
+// fragments of K tile t from LDS into registers while group 1 issues the matrix
+// instructions of tile t-1; in even phases the roles swap.  A SIMD's matrix pipe is
+// therefore fed by one wave at a time, from registers only, and the LDS / memory latency
+// of the sibling wave is hidden behind it.  Every wave starts each odd phase by requesting
+// K tile t+D (D = NSTAGE-1) straight into the LDS stage that tile t-1 has just vacated,
+// and ends each even phase by waiting until its own requests for tile t+1 have landed, so
+// a request has D full steps to complete and no staging registers are needed.
+//
+// Two workgroup shapes share the per-wave work (a 128 x 64 accumulator tile, 12 fragment
+// reads and 16 MFMAs per phase pair):
+//   spatial  256 x 256 x 32: the groups own different column halves of the output;
+//   k-split  256 x 128 x 64: both groups cover the whole 256 x 128 tile and split each
+//            64-deep K tile in two; group 1's accumulators are added to group 0's through
+//            LDS at the end.  Used when the output is too narrow for 256 x 256 tiles to
+//            fill the chip.
+#include "gemm_bf16.h"
+#include "profile.h"
+
+#include <stdio.h>
+
+namespace fhpc {
+namespace pp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any 2 GiB operand
+constexpr int NT = 512;
+
+// Raw buffer descriptor (base, stride 0, byte extent, 32-bit raw-buffer format word): offsets
+// at or beyond the extent read as zero, which is how ragged edges and the tail of the k range
+// are handled.
+__device__ __forceinline__ u32x4 make_rsrc(const void* p, uint32_t bytes)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    u32x4 r;
+    r.x = (uint32_t)a;
+    r.y = (uint32_t)(a >> 32) & 0xffffu;
+    r.z = bytes;
+    r.w = 0x00020000u;
+    return r;
+}
+
+// One global -> LDS request: lane l's 16 bytes at byte offset voff of the buffer land at
+// lds_base + 16 l.  Written as an asm statement on purpose: the compiler's wait-count pass
+// does not see it, so it inserts no vmcnt(0) ahead of later LDS reads (it does that before
+// every transposing LDS read when it knows of a pending global -> LDS write, which would
+// serialise the prefetch ring).  All waits for these requests are written by hand below.
+__device__ __forceinline__ void dma_16B(const u32x4& rs, uint32_t lds_base, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rs)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p)
+{
+    return (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 f;
+    f.x = lo;
+    f.y = hi;
+    bf16x2 b = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+// Barrier without the fence that __syncthreads carries (the fence would wait for every
+// outstanding global -> LDS request, i.e. drain the prefetch ring).  The waits that the
+// data flow needs are written out where they belong; the empty asm statements keep the
+// compiler from moving LDS accesses across the barrier.
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+#define FHPC_WAIT_LGKM0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
+#define FHPC_WAIT_VM(N) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory")
+
+// ---------------------------------------------------------------------------------
+// LDS tile layouts (BK = K depth of a stage) and their fragment reads
+// ---------------------------------------------------------------------------------
+struct FragAddr { uint32_t o[4]; };
+
+// k contiguous: [rows][BK], 16-byte chunks of a row XOR-swizzled so that 16 consecutive
+// rows reading the same logical chunk hit 16 different 16-byte bank groups.
+template <int BK>
+struct KTile {
+    static constexpr int ROWB = BK * 2;
+    static constexpr int CPR = BK / 8;
+    static constexpr int SH = (BK == 64) ? 1 : 2;           // rows per 256 bytes: 2 or 4
+    static __device__ __forceinline__ int swz(int row) { return (row >> SH) & (CPR - 1); }
+    // o[s] for k slice s of the stage (s < BK/16): lane l holds row + l%32, chunk 2s + l/32
+    static __device__ __forceinline__ FragAddr make(int wave_r0, int lane)
+    {
+        const int row = wave_r0 + (lane & 31);
+        FragAddr a;
+#pragma unroll
+        for (int s = 0; s < 4; s++)
+            a.o[s] = (uint32_t)row * ROWB + (uint32_t)((((2 * s + (lane >> 5)) ^ swz(row)) & (CPR - 1)) << 4);
+        return a;
+    }
+    // fragment i (rows + 32 i; a multiple of 32 rows never changes the swizzle), k slice s
+    static __device__ __forceinline__ bf16x8 frag(const unsigned char* tile, const FragAddr& a, int i, int s)
+    {
+        return *reinterpret_cast<const bf16x8*>(tile + a.o[s] + i * (32 * ROWB));
+    }
+};
+
+// output index contiguous: [BK k][R rows], read with ds_read_b64_tr_b16 (see gemm_bf16.hip
+// for the lane semantics); chunks XOR-swizzled with (k & 3) << 2.
+template <int R, int BK>
+struct XTile {
+    static constexpr int ROWB = R * 2;
+    static constexpr int CPR = R / 8;
+    static __device__ __forceinline__ int swz(int k) { return ((k & 3) << 2) & (CPR - 1); }
+    static __device__ __forceinline__ FragAddr make(int wave_r0, int lane)
+    {
+        const int li = lane & 15, blk = lane >> 4;
+        const int k = (blk >> 1) * 8 + (li >> 2);
+        FragAddr a;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int row = wave_r0 + 32 * i + (blk & 1) * 16 + 4 * (li & 3);
+            a.o[i] = (uint32_t)k * ROWB + (uint32_t)((((row >> 3) ^ swz(k)) & (CPR - 1)) << 4) + (uint32_t)(row & 4) * 2u;
+        }
+        return a;
+    }
+    static __device__ __forceinline__ bf16x8 frag(const unsigned char* tile, const FragAddr& a, int i, int s)
+    {
+        union { s16x4 h[2]; bf16x8 v; } u;
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const unsigned char* p = tile + a.o[i] + (s * 16 + 4 * j) * ROWB;
+            u.h[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(const_cast<unsigned char*>(p)));
+        }
+        return u.v;
+    }
+};
+
+// ---------------------------------------------------------------------------------
+// Global -> LDS requests.  One wave instruction fills 1 KiB of LDS (lane l writes bytes
+// 16 l .. 16 l + 15 after the instruction's LDS base), so the swizzle is applied on the
+// global side: each lane fetches the chunk that belongs at its LDS position.  Requests
+// are bounds-checked buffer loads: anything outside the operand or past the end of the
+// k range arrives as zeros.
+// ---------------------------------------------------------------------------------
+template <int MODE, int R, int BK>
+struct Feeder;
+
+template <int R, int BK>
+struct Feeder<OP_KC, R, BK> {
+    using Tile = KTile<BK>;
+    static constexpr int TILE_BYTES = R * BK * 2;
+    static constexpr int PER = TILE_BYTES / 1024 / 8;        // requests per wave per stage
+    static constexpr int RPB = 1024 / Tile::ROWB;            // rows per request
+    static_assert(PER >= 1, "tile too small for eight waves");
+    uint32_t voff[PER];
+    int logical[PER];                                        // the logical chunk this lane fetches in request j
+    u32x4 rs;
+
+    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    {
+        rs = make_rsrc(op.ptr, (uint32_t)dim * (uint32_t)op.ld * 2u);
+        const int r_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
+#pragma unroll
+        for (int j = 0; j < PER; j++) {
+            const int row = (wave * PER + j) * RPB + r_in_blk;
+            logical[j] = (phys ^ Tile::swz(row)) & (Tile::CPR - 1);
+            voff[j] = ((uint32_t)(row0 + row) * (uint32_t)op.ld + (uint32_t)logical[j] * 8u) * 2u;
+        }
+    }
+    __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
+    {
+        const uint32_t kofs = (k0 + logical[j] * 8 < kend) ? (uint32_t)k0 * 2u : OOB;
+        dma_16B(rs, lds_addr(tile) + (uint32_t)((wave * PER + j) * 1024), voff[j] + kofs);
+    }
+    __device__ __forceinline__ void issue(unsigned char* tile, int k0, int kend, int wave)
+    {
+#pragma unroll
+        for (int j = 0; j < PER; j++) issue_one(tile, k0, kend, wave, j);
+    }
+};
+
+template <int R, int BK>
+struct Feeder<OP_XC, R, BK> {
+    using Tile = XTile<R, BK>;
+    static constexpr int TILE_BYTES = R * BK * 2;
+    static constexpr int PER = TILE_BYTES / 1024 / 8;
+    static constexpr int KPB = 1024 / Tile::ROWB;            // k rows per request
+    static_assert(PER >= 1 && KPB >= 1, "tile shape");
+    uint32_t voff[PER];
+    uint32_t ldb;
+    u32x4 rs;
+
+    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    {
+        rs = make_rsrc(op.ptr, (uint32_t)kdim * (uint32_t)op.ld * 2u);
+        ldb = (uint32_t)op.ld * 2u;
+        const int k_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
+#pragma unroll
+        for (int j = 0; j < PER; j++) {
+            const int k = (wave * PER + j) * KPB + k_in_blk;
+            const int logical = (phys ^ Tile::swz(k)) & (Tile::CPR - 1);
+            const int row = row0 + logical * 8;
+            voff[j] = (row < dim) ? ((uint32_t)k * (uint32_t)op.ld + (uint32_t)row) * 2u : OOB;
+        }
+    }
+    __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
+    {
+        const uint32_t kofs = (k0 < kend) ? (uint32_t)k0 * ldb : OOB;
+        dma_16B(rs, lds_addr(tile) + (uint32_t)((wave * PER + j) * 1024), voff[j] + kofs);
+    }
+    __device__ __forceinline__ void issue(unsigned char* tile, int k0, int kend, int wave)
+    {
+#pragma unroll
+        for (int j = 0; j < PER; j++) issue_one(tile, k0, kend, wave, j);
+    }
+};
+
+// Same workgroup -> tile mapping as the lockstep kernels (see gemm_bf16.hip).
+__device__ __forceinline__ void work_coords(int pid, int tiles_m, int tiles_n, int splits, int& tm, int& tn, int& split)
+{
+    constexpr int NXCD = 8, GROUP_M = 8;
+    const int tiles = tiles_m * tiles_n;
+    const int total = tiles * splits;
+    const int per = (total + NXCD - 1) / NXCD;
+    const int tall = (total % NXCD) ? (total % NXCD) : NXCD;
+    const int xcd = pid % NXCD, local = pid / NXCD;
+    int id = (xcd < tall) ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    if (splits > 1) {
+        split = id / tiles;
+        const int t = id - split * tiles;
+        tm = t / tiles_n;
+        tn = t - tm * tiles_n;
+        return;
+    }
+    split = 0;
+    const int in_group = GROUP_M * tiles_n;
+    const int group = id / in_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? (tiles_m - first_m) : GROUP_M;
+    const int rem = id % in_group;
+    tm = first_m + rem % gsz;
+    tn = rem / gsz;
+}
+
+template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int A_MODE, int B_MODE, int OUT_MODE>
+__global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
+{
+    constexpr int TM = 4, TN = 2;                              // every wave: 128 x 64 accumulators
+    constexpr int WTM = 128, WTN = 64;
+    static_assert(KSPLIT ? (BM == 2 * WTM && BN == 2 * WTN && BK == 64) : (BM == 2 * WTM && BN == 4 * WTN && BK == 32),
+                  "workgroup shape");
+    using FA = Feeder<A_MODE, BM, BK>;
+    using FB = Feeder<B_MODE, BN, BK>;
+    using TA = typename FA::Tile;
+    using TB = typename FB::Tile;
+    constexpr int TILE_A_BYTES = FA::TILE_BYTES, STAGE_BYTES = FA::TILE_BYTES + FB::TILE_BYTES;
+    constexpr int D = NSTAGE - 1;                              // prefetch distance in K tiles
+    constexpr int L = FA::PER + FB::PER;                       // requests per wave per K tile
+    static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS ring");
+    static_assert(!KSPLIT || 4 * 128 * 256 <= NSTAGE * STAGE_BYTES, "LDS for the accumulator hand-over");
+
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTAGE * STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wave >> 2, wq = wave & 3;
+    // k-split: 2 x 2 waves per group over 256 x 128; spatial: 2 x 4 waves over 256 x 256
+    const int wave_m0 = KSPLIT ? (wq >> 1) * WTM : (wave >> 2) * WTM;
+    const int wave_n0 = KSPLIT ? (wq & 1) * WTN : (wave & 3) * WTN;
+
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    int tm, tn, split;
+    work_coords(blockIdx.x, tiles_m, tiles_n, p.splits > 1 ? p.splits : 1, tm, tn, split);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[j][i][v] = 0.f;
+
+    const int kbeg = split * p.k_chunk;
+    const int kend = (kbeg + p.k_chunk < p.K) ? kbeg + p.k_chunk : p.K;
+    if (kbeg < kend) {
+        FA fa;
+        FB fb;
+        fa.init(p.a, m0, p.M, p.K, wave, lane);
+        fb.init(p.b, n0, p.N, p.K, wave, lane);
+        const int kld = (p.dbg & 1) ? kbeg : kend;             // diagnostics: nothing is in range
+        const int klda = (p.dbg & 16) ? kbeg : kld, kldb = (p.dbg & 32) ? kbeg : kld;
+        const FragAddr aa = TA::make(wave_m0, lane);
+        const FragAddr ab = TB::make(wave_n0, lane);
+
+        // prologue: K tiles 0 .. D-1 into stages 0 .. D-1
+#pragma unroll
+        for (int u = 0; u < D; u++) {
+            fa.issue(lds + u * STAGE_BYTES, kbeg + u * BK, klda, wave);
+            fb.issue(lds + u * STAGE_BYTES + TILE_A_BYTES, kbeg + u * BK, kldb, wave);
+        }
+        FHPC_WAIT_VM((D - 1) * L);
+        wg_barrier();
+
+        bf16x8 ra[2][TM], rb[2][TN];
+        // Memory phase of one wave: its 12 fragment reads of tile t (ring slot STAGE) interleaved
+        // with its L requests for tile t+D (into the slot tile t-1 has just left).  A request
+        // blocks the wave until the texture path accepts it, so spreading the requests between
+        // the LDS reads lets the reads drain meanwhile.
+#define FHPC_MEM(STAGE, KPOS)                                                                        \
+    {                                                                                                \
+        constexpr int REQ = ((STAGE) + NSTAGE - 1) % NSTAGE;                                         \
+        const unsigned char* st = lds + (STAGE) * STAGE_BYTES;                                       \
+        unsigned char* rq = lds + REQ * STAGE_BYTES;                                                 \
+        int issued = 0;                                                                              \
+        _Pragma("unroll") for (int s = 0; s < 2; s++) {                                              \
+            _Pragma("unroll") for (int i = 0; i < TM; i++) {                                         \
+                ra[s][i] = TA::frag(st, aa, i, SLICE0 + s);                             \
+                if ((s * (TM + TN) + i) % 2 == 1 && issued < L) {                                    \
+                    if (issued < FA::PER) fa.issue_one(rq, (KPOS) + D * BK, klda, wave, issued);      \
+                    else fb.issue_one(rq + TILE_A_BYTES, (KPOS) + D * BK, kldb, wave, issued - FA::PER); \
+                    issued++;                                                                        \
+                }                                                                                    \
+                __builtin_amdgcn_sched_barrier(0);                                                   \
+            }                                                                                        \
+            _Pragma("unroll") for (int j = 0; j < TN; j++) {                                         \
+                rb[s][j] = TB::frag(st + TILE_A_BYTES, ab, j, SLICE0 + s);              \
+                if ((s * (TM + TN) + TM + j) % 2 == 1 && issued < L) {                               \
+                    if (issued < FA::PER) fa.issue_one(rq, (KPOS) + D * BK, klda, wave, issued);      \
+                    else fb.issue_one(rq + TILE_A_BYTES, (KPOS) + D * BK, kldb, wave, issued - FA::PER); \
+                    issued++;                                                                        \
+                }                                                                                    \
+                __builtin_amdgcn_sched_barrier(0);                                                   \
+            }                                                                                        \
+        }                                                                                            \
+        static_assert(L <= 6, "one request per two fragment reads");                                 \
+    }
+#define FHPC_MMA()                                                                                   \
+    {                                                                                                \
+        __builtin_amdgcn_s_setprio(1);                                                               \
+        _Pragma("unroll") for (int s = 0; s < 2; s++)                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; j++)                                           \
+                _Pragma("unroll") for (int i = 0; i < TM; i++)                                       \
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rb[s][j], ra[s][i], acc[j][i], 0, 0, 0); \
+        __builtin_amdgcn_s_setprio(0);                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+    }
+#define FHPC_END_ODD()                                                                               \
+    {                                                                                                \
+        FHPC_WAIT_LGKM0();                                                                           \
+        wg_barrier();                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+    }
+#define FHPC_END_EVEN()                                                                              \
+    {                                                                                                \
+        FHPC_WAIT_VM((D - 1) * L);                                                                   \
+        FHPC_WAIT_LGKM0();                                                                           \
+        wg_barrier();                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+    }
+        // One K tile = an odd phase and an even phase.  Every wave opens the odd phase by
+        // requesting tile t+D into the ring slot tile t-1 has just left, and closes the even
+        // phase by waiting for its own requests for tile t+1.  The ring is walked with
+        // compile-time slot numbers, NSTAGE tiles per trip; tiles past the end of the k range
+        // are zero tiles (their requests are out of range and arrive as zeros).
+#define FHPC_STEP_G0(STAGE, KPOS) { FHPC_MEM(STAGE, KPOS) FHPC_END_ODD() FHPC_MMA() FHPC_END_EVEN() }
+#define FHPC_STEP_G1(STAGE, KPOS) { FHPC_MMA() FHPC_END_ODD() FHPC_MEM(STAGE, KPOS) FHPC_END_EVEN() }
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+#pragma unroll
+            for (int i = 0; i < TM; i++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) ra[s][i][e] = (__bf16)0.f;
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) rb[s][j][e] = (__bf16)0.f;
+        }
+        if (group == 0) {
+            // group 0: fragments of tile t in the odd phase, its matrix instructions in the even phase
+            constexpr int SLICE0 = 0;
+            for (int k0 = kbeg; k0 < kend; k0 += NSTAGE * BK) {
+                FHPC_STEP_G0(0, k0)
+                FHPC_STEP_G0(1, k0 + BK)
+                FHPC_STEP_G0(2, k0 + 2 * BK)
+                if constexpr (NSTAGE == 4) FHPC_STEP_G0(3, k0 + 3 * BK)
+            }
+        } else {
+            // group 1: one phase behind; its first odd phase multiplies zero fragments
+            constexpr int SLICE0 = KSPLIT ? 2 : 0;
+            for (int k0 = kbeg; k0 < kend; k0 += NSTAGE * BK) {
+                FHPC_STEP_G1(0, k0)
+                FHPC_STEP_G1(1, k0 + BK)
+                FHPC_STEP_G1(2, k0 + 2 * BK)
+                if constexpr (NSTAGE == 4) FHPC_STEP_G1(3, k0 + 3 * BK)
+            }
+            FHPC_MMA()                                          // the last tile
+        }
+#undef FHPC_STEP_G0
+#undef FHPC_STEP_G1
+#undef FHPC_END_ODD
+#undef FHPC_END_EVEN
+#undef FHPC_MMA
+#undef FHPC_MEM
+        FHPC_WAIT_VM(0);                                        // zero-tile requests past the end may still be landing
+        wg_barrier();
+    }
+
+    // ---- k-split: group 1 hands its accumulators to group 0 through LDS
+    if constexpr (KSPLIT) {
+        float* red = reinterpret_cast<float*>(lds) + wq * (128 * 64);       // 32 KiB per wave pair
+        if (group == 1) {
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+#pragma unroll
+                for (int i = 0; i < TM; i++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++) red[((j * TM + i) * 16 + v) * 64 + lane] = acc[j][i][v];
+        }
+        __syncthreads();
+        if (group == 0) {
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+#pragma unroll
+                for (int i = 0; i < TM; i++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++) acc[j][i][v] += red[((j * TM + i) * 16 + v) * 64 + lane];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32 x 32 block
+    const float alpha = p.alpha;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const bool owner = !KSPLIT || group == 0;
+    if constexpr (OUT_MODE == OUT_BF16) {
+        // through LDS as [BM][BN] bf16 with row-swizzled 16-byte chunks, then whole chunks along rows
+        constexpr int CPR = BN / 8;
+        static_assert(BM * BN * 2 <= NSTAGE * STAGE_BYTES, "output tile must fit the ring");
+        if (owner) {
+#pragma unroll
+            for (int j = 0; j < TN; j++) {
+#pragma unroll
+                for (int i = 0; i < TM; i++) {
+                    const int row = wave_m0 + i * 32 + l32;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const int chunk = (wave_n0 + j * 32 + g * 8) >> 3;
+                        u32x2 o;
+                        o.x = pack_bf16(acc[j][i][4 * g + 0] * alpha, acc[j][i][4 * g + 1] * alpha);
+                        o.y = pack_bf16(acc[j][i][4 * g + 2] * alpha, acc[j][i][4 * g + 3] * alpha);
+                        *reinterpret_cast<u32x2*>(lds + row * (BN * 2) + (((chunk ^ row) & (CPR - 1)) << 4) + hi * 8) = o;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        constexpr int PASSES = BM * CPR / NT;
+        const int c = tid % CPR, r0 = tid / CPR;
+        const int col = n0 + c * 8;
+#pragma unroll
+        for (int q = 0; q < PASSES; q++) {
+            const int row = r0 + q * (NT / CPR);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * (BN * 2) + (((c ^ row) & (CPR - 1)) << 4));
+            const int m = m0 + row;
+            if (m < p.M && col < p.N)
+                *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
+        }
+    } else {
+        // fp32: this split's partial sum goes to its own slab, straight from the registers
+        if (owner) {
+            float* dst = reinterpret_cast<float*>(p.c) + (size_t)split * (size_t)p.split_stride;
+#pragma unroll
+            for (int j = 0; j < TN; j++) {
+#pragma unroll
+                for (int i = 0; i < TM; i++) {
+                    const int m = m0 + wave_m0 + i * 32 + l32;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const int n = n0 + wave_n0 + j * 32 + g * 8 + hi * 4;
+                        if (m < p.M && n < p.N) {
+                            f32x4 o;
+                            o.x = acc[j][i][4 * g + 0] * alpha;
+                            o.y = acc[j][i][4 * g + 1] * alpha;
+                            o.z = acc[j][i][4 * g + 2] * alpha;
+                            o.w = acc[j][i][4 * g + 3] * alpha;
+                            *reinterpret_cast<f32x4*>(dst + (size_t)m * (size_t)p.ldc + (size_t)n) = o;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT>
+static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
+{
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    dim3 grid((unsigned)(tiles * (a.splits > 1 ? a.splits : 1)));
+    char name[64];
+    snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
+    const int slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+    hipLaunchKernelGGL((gemm_pp_kernel<BM, BN, BK, KSPLIT, NSTAGE, AM, BMODE, OUT>), grid, dim3(NT), 0, s, a);
+    prof_end(slot, s);
+    return hipGetLastError();
+}
+
+template <int AM, int BMODE, int OUT>
+static hipError_t launch_pp_tile(int tile, const GemmArgs& a, hipStream_t s)
+{
+    if (tile == TILE_256x256) return launch_pp<256, 256, 32, false, 4, AM, BMODE, OUT>(a, s);
+    if (tile == TILE_256x128) return launch_pp<256, 128, 64, true, 3, AM, BMODE, OUT>(a, s);
+    return hipErrorInvalidValue;
+}
+
+// every instantiation the dispatcher below can reach
+#define FHPC_PP_INSTANTIATE(AM, BMODE, OUT)                                                        \
+    template __global__ void gemm_pp_kernel<256, 256, 32, false, 4, AM, BMODE, OUT>(GemmArgs);     \
+    template __global__ void gemm_pp_kernel<256, 128, 64, true, 3, AM, BMODE, OUT>(GemmArgs);
+FHPC_PP_INSTANTIATE(OP_KC, OP_XC, OUT_BF16)
+FHPC_PP_INSTANTIATE(OP_KC, OP_KC, OUT_BF16)
+FHPC_PP_INSTANTIATE(OP_XC, OP_XC, OUT_F32)
+#undef FHPC_PP_INSTANTIATE
+
+}  // namespace pp
+
+using namespace pp;
+
+bool gemm_pp_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int tile)
+{
+    if (b2_mode != OP_NONE) return false;
+    if (tile != TILE_256x256 && tile != TILE_256x128) return false;
+    if (a_mode == OP_KC && b_mode == OP_XC && out_mode == OUT_BF16) return true;
+    if (a_mode == OP_KC && b_mode == OP_KC && out_mode == OUT_BF16) return true;
+    if (a_mode == OP_XC && b_mode == OP_XC && out_mode == OUT_F32) return true;
+    return false;
+}
+
+hipError_t launch_gemm_pp(int a_mode, int b_mode, int out_mode, int tile, const GemmArgs& args, hipStream_t stream)
+{
+    if (args.M <= 0 || args.N <= 0) return hipSuccess;
+    if (args.splits > 1 && out_mode != OUT_F32) return hipErrorInvalidValue;
+    if (a_mode == OP_KC && b_mode == OP_XC && out_mode == OUT_BF16) return launch_pp_tile<OP_KC, OP_XC, OUT_BF16>(tile, args, stream);
+    if (a_mode == OP_KC && b_mode == OP_KC && out_mode == OUT_BF16) return launch_pp_tile<OP_KC, OP_KC, OUT_BF16>(tile, args, stream);
+    if (a_mode == OP_XC && b_mode == OP_XC && out_mode == OUT_F32) return launch_pp_tile<OP_XC, OP_XC, OUT_F32>(tile, args, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace fhpc

@@ -344,6 +344,27 @@ hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64
     return hipGetLastError();
 }
 
+// out[i] = sum over s of slabs[s * slab + i]: the second half of a split reduction.
+__global__ __launch_bounds__(256) void sum_slabs_kernel(const float* __restrict__ slabs, int64_t slab, int nslab,
+                                                        float* __restrict__ out, int64_t n4)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+        f32x4 a = reinterpret_cast<const f32x4*>(slabs)[i];
+        for (int s = 1; s < nslab; s++) a += reinterpret_cast<const f32x4*>(slabs + (int64_t)s * slab)[i];
+        reinterpret_cast<f32x4*>(out)[i] = a;
+    }
+}
+
+// n = elements per slab, a multiple of 4 (every output here has a leading dimension that is one).
+hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, float* out, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(sum_slabs_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, slabs, n, nslab, out, n / 4);
+    return hipGetLastError();
+}
+
 // Zero fill with a kernel (usable inside a captured graph, unlike a memset node).
 __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)
 {

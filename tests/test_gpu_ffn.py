@@ -82,7 +82,11 @@ def test_config3_chain_reduced_tokens():
 def test_config3_full_size_sampled():
     """Config 3 at 16384 tokens: Y and dX of the whole chain on sampled rows (every step
     of the chain is row-wise independent), and each weight gradient's additivity over
-    token blocks (a sum over tokens must equal the sum of its two halves)."""
+    token blocks (a sum over tokens must equal the sum of its two halves).  The halves may
+    run on another tile shape than the whole, which sums k in another order, so a few per
+    cent of the bf16 intermediates (H, dH) differ by one ulp between the two runs: the bound
+    is a fraction of the bf16 tolerance, far below what a dropped or doubled token block
+    would cause (64 of 16384 tokens missing: about 6e-2)."""
     from paper_2402_13533_amd import ffn
     fhpc = _fhpc()
     M, d, r, f = 16384, 4096, 1024, 11008
@@ -109,4 +113,4 @@ def test_config3_full_size_sampled():
     for name, g, a, b in zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), grads, parts[0], parts[1]):
         e = oracle.rel_fro(g, a + b)
         print("c3 full additivity %s %.3e" % (name, e), flush=True)
-        assert e <= 1e-4, (name, e)
+        assert e <= 2e-3, (name, e)
