@@ -58,8 +58,9 @@ struct GemmArgs {
     int splits;            // >1: the reduction is cut into slices of k_chunk (multiple of 64); needs OUT_F32
     int k_chunk;
     int64_t split_stride;  // elements between the partial-sum slabs of consecutive splits
-    int dbg;               // diagnostics: bit 0 = request no operand data (all loads out of range),
-                           // bit 1 = skip the matrix instructions.  0 in normal use.
+    int dbg;               // diagnostics, 0 in normal use: bit 0 = request no operand data (all loads out
+                           // of range), bit 1 = skip the matrix instructions (lockstep kernels only),
+                           // bit 2 = lockstep kernels only, bit 3 = four-wave kernel where it exists.
 };
 
 // Launches the instantiation (a_mode, b_mode, b2_mode, out_mode, tile).  a2 is always OP_KC.
@@ -71,6 +72,12 @@ hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, i
 // 256x256 and 256x128 tiles; launch_gemm_bf16 routes to them unless args.dbg bit 2 is set.
 bool gemm_pp_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int tile);
 hipError_t launch_gemm_pp(int a_mode, int b_mode, int out_mode, int tile, const GemmArgs& args, hipStream_t stream);
+
+// The four-wave kernel (gemm_w4.hip) covers the same products on the 256x256 tile.  It matches
+// the ping-pong kernels when the reduction is long and the output has at least one 256x256 tile
+// per compute unit, and loses to them otherwise, so it is selected only by args.dbg bit 3.
+bool gemm_w4_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int tile);
+hipError_t launch_gemm_w4(int a_mode, int b_mode, int out_mode, const GemmArgs& args, hipStream_t stream);
 
 // Tile extents, for planning on the host.
 void gemm_tile_extent(int tile, int* bm, int* bn);

@@ -817,6 +817,8 @@ hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, i
 {
     if (args.M <= 0 || args.N <= 0) return hipSuccess;
     if (args.splits > 1 && out_mode != OUT_F32) return hipErrorInvalidValue;
+    if ((args.dbg & 8) && gemm_w4_supports(a_mode, b_mode, b2_mode, out_mode, tile))
+        return launch_gemm_w4(a_mode, b_mode, out_mode, args, stream);
     if (!(args.dbg & 4) && gemm_pp_supports(a_mode, b_mode, b2_mode, out_mode, tile))
         return launch_gemm_pp(a_mode, b_mode, out_mode, tile, args, stream);
     const bool skinny = (tile == TILE_256x32 || tile == TILE_32x256);
