@@ -31,6 +31,10 @@ def parse_args():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--recompute", action="store_true", help="backward recomputes H instead of reading the saved copy")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="after the steps, launch a plain elementwise kernel that reads 256 MiB and writes 256 MiB three "
+                         "times, so that a rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE by what "
+                         "the same counters read for a known amount of traffic")
     return ap.parse_args()
 
 
@@ -283,6 +287,12 @@ def main():
         "io_gbs": io_bytes / (ms_per_step * 1e-3) / 1e9, "frac_hbm_peak_on_io_bytes": io_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roofline, "kernels": kernels,
     }
+    if args.pmc_calibration:
+        x = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))

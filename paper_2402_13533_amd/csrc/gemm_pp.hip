@@ -19,6 +19,12 @@
 //            64-deep K tile in two; group 1's accumulators are added to group 0's through
 //            LDS at the end.  Used when the output is too narrow for 256 x 256 tiles to
 //            fill the chip.
+//
+// The spatial shape runs as one workgroup per compute unit that walks over its output tiles
+// (the same XCD-aware order as a plain launch would give): before the epilogue of a tile it
+// posts the requests for the first K tiles of the next one, and the bf16 epilogue goes through
+// small wave-private LDS patches outside the ring, so those requests land while the output
+// is being stored.
 #include "gemm_bf16.h"
 #include "gemm_ring.h"
 #include "profile.h"
@@ -46,10 +52,19 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     constexpr int TILE_A_BYTES = FA::TILE_BYTES, STAGE_BYTES = FA::TILE_BYTES + FB::TILE_BYTES;
     constexpr int D = NSTAGE - 1;                              // prefetch distance in K tiles
     constexpr int L = FA::PER + FB::PER;                       // requests per wave per K tile
-    static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS ring");
-    static_assert(!KSPLIT || 4 * 128 * 256 <= NSTAGE * STAGE_BYTES, "LDS for the accumulator hand-over");
+    constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+    // bf16 output leaves through a 4 KiB LDS patch private to each writing wave, outside the ring
+    constexpr int OUT_WAVES = KSPLIT ? 4 : 8;
+    constexpr int PATCH_BYTES = 32 * WTN * 2;
+    constexpr int LDS_BYTES = RING_BYTES + (OUT_MODE == OUT_BF16 ? OUT_WAVES * PATCH_BYTES : 0);
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring and output patches");
+    static_assert(!KSPLIT || 4 * 128 * 256 <= RING_BYTES, "LDS for the accumulator hand-over");
+    // The spatial shape is launched with one workgroup per compute unit that walks over output
+    // tiles: the requests for the first K tiles of the next output tile are posted before the
+    // epilogue of the current one, so their latency hides behind the output stores.
+    constexpr bool PERSISTENT = !KSPLIT;
 
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTAGE * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -60,9 +75,39 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     const int wave_n0 = KSPLIT ? (wq & 1) * WTN : (wave & 3) * WTN;
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    int tm, tn, split;
-    work_coords(blockIdx.x, tiles_m, tiles_n, p.splits > 1 ? p.splits : 1, tm, tn, split);
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int nsplit = p.splits > 1 ? p.splits : 1;
+    const int total = tiles_m * tiles_n * nsplit;
+    const FragAddr aa = TA::make(wave_m0, lane);
+    const FragAddr ab = TB::make(wave_n0, lane);
+
+    FA fa;
+    FB fb;
+    fa.describe(p.a, p.M, p.K);
+    fb.describe(p.b, p.N, p.K);
+    int m0, n0, split, kbeg, kend, kld;
+    // coordinates of work item `pid`, its feeders, and the requests for its first D K tiles
+    auto begin_tile = [&](int pid) {
+        int tm, tn;
+        work_coords(pid, tiles_m, tiles_n, nsplit, tm, tn, split);
+        m0 = tm * BM;
+        n0 = tn * BN;
+        kbeg = split * p.k_chunk;
+        kend = (kbeg + p.k_chunk < p.K) ? kbeg + p.k_chunk : p.K;
+        kld = (p.dbg & 1) ? kbeg : kend;                       // diagnostics: nothing is in range
+        if (kbeg < kend) {
+            fa.set_tile(p.a, m0, p.M, wave, lane);
+            fb.set_tile(p.b, n0, p.N, wave, lane);
+#pragma unroll
+            for (int u = 0; u < D; u++) {
+                fa.issue(lds + u * STAGE_BYTES, kbeg + u * BK, kld, wave);
+                fb.issue(lds + u * STAGE_BYTES + TILE_A_BYTES, kbeg + u * BK, kld, wave);
+            }
+        }
+    };
+    begin_tile(blockIdx.x);
+
+    for (int pid = blockIdx.x; pid < total; pid += gridDim.x) {
+    const int out_m0 = m0, out_n0 = n0, out_split = split;
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -72,25 +117,9 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[j][i][v] = 0.f;
 
-    const int kbeg = split * p.k_chunk;
-    const int kend = (kbeg + p.k_chunk < p.K) ? kbeg + p.k_chunk : p.K;
     if (kbeg < kend) {
-        FA fa;
-        FB fb;
-        fa.init(p.a, m0, p.M, p.K, wave, lane);
-        fb.init(p.b, n0, p.N, p.K, wave, lane);
-        const int kld = (p.dbg & 1) ? kbeg : kend;             // diagnostics: nothing is in range
-        const FragAddr aa = TA::make(wave_m0, lane);
-        const FragAddr ab = TB::make(wave_n0, lane);
-
-        // prologue: K tiles 0 .. D-1 into stages 0 .. D-1
-#pragma unroll
-        for (int u = 0; u < D; u++) {
-            fa.issue(lds + u * STAGE_BYTES, kbeg + u * BK, kld, wave);
-            fb.issue(lds + u * STAGE_BYTES + TILE_A_BYTES, kbeg + u * BK, kld, wave);
-        }
-        FHPC_WAIT_VM((D - 1) * L);
-        wg_barrier();
+        FHPC_WAIT_VM((D - 1) * L);                             // (output stores of the previous tile, younger
+        wg_barrier();                                          //  than these requests, only make this wait longer)
 
         bf16x8 ra[2][TM], rb[2][TN];
         // Memory phase of one wave: its 12 fragment reads of tile t (ring slot STAGE) interleaved
@@ -195,6 +224,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
         FHPC_WAIT_VM(0);                                        // zero-tile requests past the end may still be landing
         wg_barrier();
     }
+    if (PERSISTENT && pid + (int)gridDim.x < total) begin_tile(pid + (int)gridDim.x);
 
     // ---- k-split: group 1 hands its accumulators to group 0 through LDS
     if constexpr (KSPLIT) {
@@ -216,7 +246,6 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 #pragma unroll
                     for (int v = 0; v < 16; v++) acc[j][i][v] += red[((j * TM + i) * 16 + v) * 64 + lane];
         }
-        __syncthreads();
     }
 
     // ---- epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32 x 32 block
@@ -224,50 +253,48 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     const int l32 = lane & 31, hi = lane >> 5;
     const bool owner = !KSPLIT || group == 0;
     if constexpr (OUT_MODE == OUT_BF16) {
-        // through LDS as [BM][BN] bf16 with row-swizzled 16-byte chunks, then whole chunks along rows
-        constexpr int CPR = BN / 8;
-        static_assert(BM * BN * 2 <= NSTAGE * STAGE_BYTES, "output tile must fit the ring");
+        // Each writing wave turns its tile around 32 rows at a time in its own LDS patch
+        // ([32][64] bf16, 16-byte chunks XOR-swizzled by the row) and stores whole 128-byte
+        // rows; no workgroup barrier, and the ring stays free for the next tile's requests.
         if (owner) {
+            unsigned char* patch = lds + RING_BYTES + (KSPLIT ? wq : wave) * PATCH_BYTES;
+            const int rc = lane & 7, rr = lane >> 3;
 #pragma unroll
-            for (int j = 0; j < TN; j++) {
+            for (int i = 0; i < TM; i++) {
 #pragma unroll
-                for (int i = 0; i < TM; i++) {
-                    const int row = wave_m0 + i * 32 + l32;
+                for (int j = 0; j < TN; j++) {
 #pragma unroll
                     for (int g = 0; g < 4; g++) {
-                        const int chunk = (wave_n0 + j * 32 + g * 8) >> 3;
+                        const int chunk = j * 4 + g;
                         u32x2 o;
                         o.x = pack_bf16(acc[j][i][4 * g + 0] * alpha, acc[j][i][4 * g + 1] * alpha);
                         o.y = pack_bf16(acc[j][i][4 * g + 2] * alpha, acc[j][i][4 * g + 3] * alpha);
-                        *reinterpret_cast<u32x2*>(lds + row * (BN * 2) + (((chunk ^ row) & (CPR - 1)) << 4) + hi * 8) = o;
+                        *reinterpret_cast<u32x2*>(patch + l32 * 128 + (((chunk ^ l32) & 7) << 4) + hi * 8) = o;
                     }
                 }
-            }
-        }
-        __syncthreads();
-        constexpr int PASSES = BM * CPR / NT;
-        const int c = tid % CPR, r0 = tid / CPR;
-        const int col = n0 + c * 8;
+                const int col = out_n0 + wave_n0 + rc * 8;
 #pragma unroll
-        for (int q = 0; q < PASSES; q++) {
-            const int row = r0 + q * (NT / CPR);
-            const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * (BN * 2) + (((c ^ row) & (CPR - 1)) << 4));
-            const int m = m0 + row;
-            if (m < p.M && col < p.N)
-                *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
+                for (int q = 0; q < 4; q++) {
+                    const int row = rr + 8 * q;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
+                    const int m = out_m0 + wave_m0 + i * 32 + row;
+                    if (m < p.M && col < p.N)
+                        *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
+                }
+            }
         }
     } else {
         // fp32: this split's partial sum goes to its own slab, straight from the registers
         if (owner) {
-            float* dst = reinterpret_cast<float*>(p.c) + (size_t)split * (size_t)p.split_stride;
+            float* dst = reinterpret_cast<float*>(p.c) + (size_t)out_split * (size_t)p.split_stride;
 #pragma unroll
             for (int j = 0; j < TN; j++) {
 #pragma unroll
                 for (int i = 0; i < TM; i++) {
-                    const int m = m0 + wave_m0 + i * 32 + l32;
+                    const int m = out_m0 + wave_m0 + i * 32 + l32;
 #pragma unroll
                     for (int g = 0; g < 4; g++) {
-                        const int n = n0 + wave_n0 + j * 32 + g * 8 + hi * 4;
+                        const int n = out_n0 + wave_n0 + j * 32 + g * 8 + hi * 4;
                         if (m < p.M && n < p.N) {
                             f32x4 o;
                             o.x = acc[j][i][4 * g + 0] * alpha;
@@ -281,13 +308,31 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
             }
         }
     }
+    if (!PERSISTENT) break;
+    }
+}
+
+// compute units of the current device (the persistent shape launches one workgroup on each)
+static int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n - n % 8 > 0 ? n - n % 8 : n;          // whole multiples of the eight XCDs keep the tile map aligned
+    }
+    return cached[dev];
 }
 
 template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT>
 static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    dim3 grid((unsigned)(tiles * (a.splits > 1 ? a.splits : 1)));
+    const int total = tiles * (a.splits > 1 ? a.splits : 1);
+    const int cus = compute_units();
+    dim3 grid((unsigned)((!KSPLIT && total > cus) ? cus : total));
     char name[64];
     snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
     const int slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);

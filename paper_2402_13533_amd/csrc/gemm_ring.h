@@ -24,10 +24,11 @@ constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any 2 GiB operand
 __device__ __forceinline__ u32x4 make_rsrc(const void* p, uint32_t bytes)
 {
     const uint64_t a = reinterpret_cast<uint64_t>(p);
+    // the descriptor must sit in scalar registers; the values are wave-uniform by construction
     u32x4 r;
-    r.x = (uint32_t)a;
-    r.y = (uint32_t)(a >> 32) & 0xffffu;
-    r.z = bytes;
+    r.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    r.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+    r.z = __builtin_amdgcn_readfirstlane(bytes);
     r.w = 0x00020000u;
     return r;
 }
@@ -154,9 +155,13 @@ struct Feeder<OP_KC, R, BK, NW> {
     int logical[PER];                                        // the logical chunk this lane fetches in request j
     u32x4 rs;
 
-    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    // descriptor of the whole operand (once per kernel), then the lane offsets of one output tile
+    __device__ __forceinline__ void describe(const GemmOperand& op, int dim, int kdim)
     {
         rs = make_rsrc(op.ptr, (uint32_t)dim * (uint32_t)op.ld * 2u);
+    }
+    __device__ __forceinline__ void set_tile(const GemmOperand& op, int row0, int dim, int wave, int lane)
+    {
         const int r_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
 #pragma unroll
         for (int j = 0; j < PER; j++) {
@@ -164,6 +169,11 @@ struct Feeder<OP_KC, R, BK, NW> {
             logical[j] = (phys ^ Tile::swz(row)) & (Tile::CPR - 1);
             voff[j] = ((uint32_t)(row0 + row) * (uint32_t)op.ld + (uint32_t)logical[j] * 8u) * 2u;
         }
+    }
+    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    {
+        describe(op, dim, kdim);
+        set_tile(op, row0, dim, wave, lane);
     }
     __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
     {
@@ -188,10 +198,13 @@ struct Feeder<OP_XC, R, BK, NW> {
     uint32_t ldb;
     u32x4 rs;
 
-    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    __device__ __forceinline__ void describe(const GemmOperand& op, int dim, int kdim)
     {
         rs = make_rsrc(op.ptr, (uint32_t)kdim * (uint32_t)op.ld * 2u);
         ldb = (uint32_t)op.ld * 2u;
+    }
+    __device__ __forceinline__ void set_tile(const GemmOperand& op, int row0, int dim, int wave, int lane)
+    {
         const int k_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
 #pragma unroll
         for (int j = 0; j < PER; j++) {
@@ -200,6 +213,11 @@ struct Feeder<OP_XC, R, BK, NW> {
             const int row = row0 + logical * 8;
             voff[j] = (row < dim) ? ((uint32_t)k * (uint32_t)op.ld + (uint32_t)row) * 2u : OOB;
         }
+    }
+    __device__ __forceinline__ void init(const GemmOperand& op, int row0, int dim, int kdim, int wave, int lane)
+    {
+        describe(op, dim, kdim);
+        set_tile(op, row0, dim, wave, lane);
     }
     __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
     {
