@@ -23,8 +23,9 @@
  *    error code before anything is launched.
  *  - Return value: FHPC_OK or an FHPC_ERR_* code.  Nothing throws, exits or
  *    prints.  HIP launch failures map to FHPC_ERR_HIP.
- *  - dA and dB are produced in fp32.  Split reductions over tokens use fp32
- *    atomics, so their low-order bits may differ from run to run.
+ *  - dA and dB are produced in fp32.  Reductions over tokens are cut into slices
+ *    whose partial sums go to separate slabs of the workspace and are added in a
+ *    fixed order: no atomics, results are bit-reproducible from run to run.
  */
 #ifndef FINGPT_HPC_H
 #define FINGPT_HPC_H

@@ -148,7 +148,7 @@ int check_common(int64_t M, int64_t K, int64_t r, int64_t N)
     return FHPC_OK;
 }
 
-// Tile for an M x N output.  The narrow tiles exist only for the split (atomic)
+// Tile for an M x N output.  The narrow tiles exist only for the split
 // rank-r products, so they are offered only when `allow_skinny`.
 int pick_tile(int64_t M, int64_t N, bool allow_skinny)
 {
