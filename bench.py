@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
+                         "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
+    ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
     ap.add_argument("--recompute", action="store_true", help="backward recomputes H instead of reading the saved copy")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after the steps, launch a plain elementwise kernel that reads 256 MiB and writes 256 MiB three "
@@ -86,10 +90,11 @@ class LowrankCall:
 
 
 class QlinearCall:
-    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False):
+    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False, forward_only=False):
         import torch
         bf = torch.bfloat16
         self.f = fhpc
+        self.forward_only = forward_only
         self.M, self.K, self.r, self.N, self.scheme, self.s = M, K, r, N, scheme, scaling
         W = randn((K, N), 0.02, torch.float32, gen)
         self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)       # frozen base weight, quantised on the GPU
@@ -107,15 +112,22 @@ class QlinearCall:
 
     def flops(self):
         from paper_2402_13533_amd import shapes
-        return shapes.qlinear_lowrank_flops(self.M, self.K, self.r, self.N)
+        full = shapes.qlinear_lowrank_flops(self.M, self.K, self.r, self.N)
+        if self.forward_only:
+            return 2 * self.M * self.K * self.N + 2 * self.M * self.r * (self.K + self.N)
+        return full
 
     def io_bytes(self):
-        w = self.Wq.numel() + 2 * self.sc.numel()
+        w = self.Wq.numel() * self.Wq.element_size() + 2 * self.sc.numel()
+        if self.forward_only:
+            return w + 2 * (self.M * self.K + self.M * self.N) + 2 * self.r * (self.K + self.N)
         return 2 * w + 2 * (2 * self.M * self.K + 2 * self.M * self.N) + 6 * self.r * (self.K + self.N)
 
     def run(self):
         f = self.f
         f.qlinear_lowrank_fwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, Y=self.Y, H_out=self.H)
+        if self.forward_only:
+            return
         f.qlinear_lowrank_bwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, self.dY,
                               H_saved=None if self.recompute else self.H, dX=self.dX, dA=self.dA, dB=self.dB)
 
@@ -147,7 +159,7 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute):
+def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20240213)
@@ -165,14 +177,18 @@ def build_workload(name, fhpc, recompute):
         desc = "config 3: Llama-2-7B SiLU-gated FFN factorised r=1024, 16384 tokens, bf16, fwd+bwd"
         dtype = "bf16"
     elif name == "c4":
-        calls = [QlinearCall(fhpc, 4096, 4096, 8, 4096, 8, gen, 2.0, recompute)]
-        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, 4096 tokens, bf16, fwd+bwd"
+        M = tokens or 4096
+        calls = [QlinearCall(fhpc, M, 4096, 8, 4096, 8, gen, 2.0, recompute, forward_only)]
+        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, %d tokens, bf16, %s" % (
+            M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
     else:
         d, f = 5120, 13824
         shp = [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
-        calls = [QlinearCall(fhpc, 4096, K, 16, N, 4, gen, 2.0, recompute) for K, N in shp]
-        desc = "config 5: Llama-2-13B decoder layer, 7 linears, int4 block-64 frozen W + rank-16 branch, 4096 tokens, bf16, fwd+bwd"
+        M = tokens or 4096
+        calls = [QlinearCall(fhpc, M, K, 16, N, 4, gen, 2.0, recompute, forward_only) for K, N in shp]
+        desc = "config 5: Llama-2-13B decoder layer, 7 linears, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
+            M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
     return calls, desc, dtype
 
@@ -244,7 +260,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute)
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only)
     flops = sum(c.flops() for c in calls)
     io_bytes = sum(c.io_bytes() for c in calls)
 
@@ -271,20 +287,31 @@ def main():
     torch.cuda.synchronize()
     recs = fhpc.profile_stop()
     agg = {}
-    for name, ms, fl in recs:
-        a = agg.setdefault(name, [0, 0.0, 0.0])
-        a[0] += 1; a[1] += ms; a[2] += fl
+    for name, ms, fl, by in recs:
+        a = agg.setdefault(name, [0, 0.0, 0.0, 0.0])
+        a[0] += 1; a[1] += ms; a[2] += fl; a[3] += by
     kernels = {n: {"launches_per_step": a[0] / args.steps, "avg_ms": a[1] / a[0], "flops_per_launch": a[2] / a[0],
-                   "tflops": a[2] / a[1] / 1e9 if a[1] > 0 else None}
+                   "tflops": a[2] / a[1] / 1e9 if a[1] > 0 else None,
+                   "bytes_per_launch": a[3] / a[0], "gbs": a[3] / a[1] / 1e6 if (a[1] > 0 and a[3] > 0) else None}
                for n, a in agg.items()}
     roofline = None
     if agg:
-        dom = max(agg, key=lambda n: agg[n][1])
+        # the kernel the roofline is quoted for: the streaming kernel when the run has one (few tokens),
+        # else the GEMM with the largest share of time
+        streaming = [n for n in agg if agg[n][3] > 0]
+        dom = max(streaming or agg, key=lambda n: agg[n][1])
         k = kernels[dom]
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
-                    "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": agg[dom][1] / sum(a[1] for a in agg.values())}
+        share = agg[dom][1] / sum(a[1] for a in agg.values())
+        if k["gbs"] is not None:
+            # weight-streaming kernel: algorithmic bytes (packed weight + scales + tokens + its partial sums)
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": k["gbs"] / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                        "avg_launch_ms": k["avg_ms"], "share_of_timed_kernels": share}
+        else:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                        "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": share}
 
     out = {
         "metric": "fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,

@@ -160,7 +160,8 @@ int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_
  * costs a few microseconds per launch.  fhpc_profile_stop disarms and returns the number
  * of launches recorded.  fhpc_profile_get waits for record `index` and returns the
  * kernel's name (NUL-terminated, truncated to name_len), its duration in milliseconds and
- * the algorithmic flop count of that launch (bytes is reserved, 0). */
+ * the algorithmic flop count of that launch; `bytes` is the algorithmic byte count for the
+ * weight-streaming kernels and 0 elsewhere. */
 int fhpc_profile_start(int max_records);
 int fhpc_profile_stop(void);
 int fhpc_profile_get(int index, char* name, int name_len, float* ms, double* flops, double* bytes);

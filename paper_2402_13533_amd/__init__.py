@@ -80,7 +80,7 @@ def profile_start(max_records: int = 4096) -> None:
 
 
 def profile_stop():
-    """Disarm and return [(kernel name, milliseconds, flops)] for every recorded launch."""
+    """Disarm and return [(kernel name, milliseconds, flops, bytes)] for every recorded launch."""
     lib = load_library()
     n = lib.fhpc_profile_stop()
     out = []
@@ -90,7 +90,7 @@ def profile_stop():
         rc = lib.fhpc_profile_get(i, buf, 64, C.byref(ms), C.byref(fl), C.byref(by))
         if rc:
             raise FhpcError(rc, "fhpc_profile_get")
-        out.append((buf.value.decode(), float(ms.value), float(fl.value)))
+        out.append((buf.value.decode(), float(ms.value), float(fl.value), float(by.value)))
     return out
 
 

@@ -4,6 +4,7 @@
 #include "../../include/fingpt_hpc.h"
 #include "gemm_bf16.h"
 #include "kernels_misc.h"
+#include "qskinny.h"
 
 using namespace fhpc;
 
@@ -48,6 +49,8 @@ struct Scratch {
     float* dA_t = nullptr;  // fp32 [K][rp]
     float* dB_t = nullptr;  // fp32 [rp][N]
     float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
+    float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
+    float* sk_hpart = nullptr;  //                                        partial sums of X A
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
@@ -66,15 +69,10 @@ struct SplitPlan {
     int tile, splits, k_chunk;
 };
 
-SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
+SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
 {
     SplitPlan sp;
-    if (N <= 32) sp.tile = TILE_256x32;
-    else if (M <= 32) sp.tile = TILE_32x256;
-    else if (M > 128 && N > 128) sp.tile = TILE_256x256;
-    else if (M > 128) sp.tile = TILE_256x128;
-    else if (N > 128) sp.tile = TILE_128x256;
-    else sp.tile = TILE_128x128;
+    sp.tile = tile;
     const int64_t tiles = tile_count(sp.tile, M, N);
     const int64_t ksteps = (Kred + 63) / 64;
     // the eight-wave tiles occupy a compute unit alone; the smaller ones run two at a time
@@ -87,6 +85,25 @@ SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
     const int64_t steps_per = (ksteps + s - 1) / s;
     sp.k_chunk = (int)(steps_per * 64);
     sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
+    return sp;
+}
+
+SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
+{
+    int tile;
+    if (N <= 32) tile = TILE_256x32;
+    else if (M <= 32) tile = TILE_32x256;
+    else if (M > 128 && N > 128) tile = TILE_256x256;
+    else if (M > 128) tile = TILE_256x128;
+    else if (N > 128) tile = TILE_128x256;
+    else tile = TILE_128x128;
+    SplitPlan sp = plan_split_on(tile, M, N, Kred);
+    if (tile == TILE_256x256) {
+        // Both eight-wave shapes run these products equally fast when they fill the chip; the one
+        // that needs fewer slices writes (and later re-reads) fewer partial-sum slabs.
+        const SplitPlan alt = plan_split_on(TILE_256x128, M, N, Kred);
+        if (alt.splits < sp.splits) sp = alt;
+    }
     return sp;
 }
 
@@ -104,6 +121,13 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         // fp32 path: H and dH in fp32, no padding
         s.H = c.take(M * r * 4);
         if (op == FHPC_OP_LOWRANK_BWD) s.dH = c.take(M * r * 4);
+        return s;
+    }
+    if (op == FHPC_OP_QLINEAR_FWD && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
+        // a handful of tokens: the weight-streaming kernels need only their own slabs
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
+        s.sk_part = static_cast<float*>(c.take(p.part_bytes));
+        s.sk_hpart = static_cast<float*>(c.take(p.hpart_bytes));
         return s;
     }
     const int64_t rp = rank_pad(r);
@@ -419,6 +443,11 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16);
+    if (s.sk_part) {
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
+        FHPC_HIP(launch_qskinny_fwd(X, Wq, scales, qscheme, A, B, scaling, Y, H_out, M, K, r, N, p, s.sk_part, s.sk_hpart, st));
+        return FHPC_OK;
+    }
     const int64_t rp = rank_pad(r);
     Factors f;
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);

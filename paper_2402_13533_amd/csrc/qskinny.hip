@@ -1,0 +1,406 @@
+// Weight-streaming forward of the quantised finetuning layer for a handful of tokens
+// (M <= 16):  Y = X * deq(Wq, scales) + scaling * (X * A) * B.
+//
+// At this size the layer is bound by reading the packed weight once from HBM, so the kernel
+// is built around that stream: every lane loads 16-byte pieces of its own weight row straight
+// into registers (no LDS hop for the weight), turns the codes into exact small bf16 integers
+// with a few bit operations, and feeds them to v_mfma_f32_16x16x32_bf16 against the token
+// fragments, which sit in LDS (they are the only operand that is reused).
+//
+// Code -> operand without per-element floating point:
+//   int4: nibble n (two's complement) -> u = n ^ 8 = q + 8 in [0, 15]; the bf16 pattern
+//         0x4300 | u is exactly 128 + u.
+//   int8: byte b -> u = b ^ 0x80 = q + 128 in [0, 255]; float(u) is exact in bf16.
+// The matrix instruction therefore accumulates sum_k X[m,k] * (q[n,k] + c) with c = 136 or
+// 128; a second accumulator fed with an all-ones operand gives sum_k X[m,k], and the offset
+// and the fp16 scale are applied to the fp32 sums: per 64-wide block for int4 (Sec. 5.2:
+// one scale per weight vector, here a block of 64 inputs of one output channel), once at
+// the end for int8 (one scale per output channel).  The weight is thus used unrounded.
+//
+// Work split: a workgroup of four waves owns 64 output channels (16 per wave) and one slice
+// of the reduction; slices write fp32 partial sums to slabs; a finishing kernel adds the slabs
+// and the rank-r branch and rounds to bf16.  H = X * A comes from a small kernel of its own.
+#include "qskinny.h"
+#include "profile.h"
+
+#include <hip/hip_fp16.h>
+#include <stdio.h>
+
+namespace fhpc {
+namespace skinny {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int NT = 256;
+constexpr int ROWS_WG = 64;            // output channels per workgroup
+constexpr int TOK = 16;                // token rows of the MFMA tile
+constexpr int STEP = 512;              // reduction depth per pipeline step
+constexpr int HCHUNK = 256;            // reduction depth per workgroup of the H = X A kernel
+constexpr uint32_t OOB = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// 4 x 4 transpose of 32-bit words across the four 16-lane groups of a wave: on return lane
+// group g holds in w[s] what group s held in w[g].
+__device__ __forceinline__ void transpose_groups(uint32_t (&w)[4])
+{
+    // v_permlane32_swap a, b: lanes 32..63 of a <-> lanes 0..31 of b
+    // v_permlane16_swap a, b: the odd 16-lane rows of a <-> the even rows of b
+    auto s0 = __builtin_amdgcn_permlane32_swap(w[0], w[2], false, false);
+    auto s1 = __builtin_amdgcn_permlane32_swap(w[1], w[3], false, false);
+    w[0] = s0[0]; w[2] = s0[1];
+    w[1] = s1[0]; w[3] = s1[1];
+    auto t0 = __builtin_amdgcn_permlane16_swap(w[0], w[1], false, false);
+    auto t1 = __builtin_amdgcn_permlane16_swap(w[2], w[3], false, false);
+    w[0] = t0[0]; w[1] = t0[1];
+    w[2] = t1[0]; w[3] = t1[1];
+}
+
+// eight int4 codes (one 32-bit word, element 2j in the low nibble of byte j) -> eight bf16
+// values 128 + (q + 8), element order preserved
+__device__ __forceinline__ bf16x8 int4_operand(uint32_t w)
+{
+    const uint32_t x = w ^ 0x88888888u;
+    const uint32_t lo = x & 0x0f0f0f0fu, hi = (x >> 4) & 0x0f0f0f0fu;
+    u32x4 r;
+    r.x = __builtin_amdgcn_perm(hi, lo, 0x0c040c00u) | 0x43004300u;
+    r.y = __builtin_amdgcn_perm(hi, lo, 0x0c050c01u) | 0x43004300u;
+    r.z = __builtin_amdgcn_perm(hi, lo, 0x0c060c02u) | 0x43004300u;
+    r.w = __builtin_amdgcn_perm(hi, lo, 0x0c070c03u) | 0x43004300u;
+    return as_bf16x8(r);
+}
+
+// eight int8 codes (two words) -> eight bf16 values q + 128
+__device__ __forceinline__ bf16x8 int8_operand(uint32_t w0, uint32_t w1)
+{
+    const uint32_t a = w0 ^ 0x80808080u, b = w1 ^ 0x80808080u;
+    const float f0 = (float)(a & 0xffu), f1 = (float)((a >> 8) & 0xffu), f2 = (float)((a >> 16) & 0xffu), f3 = (float)(a >> 24);
+    const float f4 = (float)(b & 0xffu), f5 = (float)((b >> 8) & 0xffu), f6 = (float)((b >> 16) & 0xffu), f7 = (float)(b >> 24);
+    // the values are integers below 256: the upper 16 bits of the fp32 pattern are the exact bf16
+    u32x4 r;
+    r.x = __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+    r.y = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x07060302u);
+    r.z = __builtin_amdgcn_perm(__float_as_uint(f5), __float_as_uint(f4), 0x07060302u);
+    r.w = __builtin_amdgcn_perm(__float_as_uint(f7), __float_as_uint(f6), 0x07060302u);
+    return as_bf16x8(r);
+}
+
+// LDS tile of the token rows for one step: [16 tokens][512 k] bf16, 16-byte chunks XOR-swizzled
+// by the token so that the 16 lanes of a group (16 tokens, same chunk) hit 16 different banks.
+__device__ __forceinline__ uint32_t x_off(int tok, int chunk) { return (uint32_t)tok * (STEP * 2) + (uint32_t)(((chunk ^ tok) & 63) << 4); }
+
+template <int SCHEME>
+__global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, const void* __restrict__ Wq,
+                                                         const void* __restrict__ scales, float* __restrict__ part,
+                                                         int M, int K, int N, int k_chunk)
+{
+    constexpr bool I4 = (SCHEME == 4);
+    constexpr int WLOADS = I4 ? 4 : 8;               // 16-byte weight loads per lane per step
+    __shared__ __attribute__((aligned(16))) unsigned char xs[2][TOK * STEP * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row_blocks = (N + ROWS_WG - 1) / ROWS_WG;
+    const int rb = blockIdx.x % row_blocks, split = blockIdx.x / row_blocks;
+    const int n0 = rb * ROWS_WG + wave * 16;
+    const int kbeg = split * k_chunk;
+    const int kend = (kbeg + k_chunk < K) ? kbeg + k_chunk : K;
+    const int steps = (kend - kbeg + STEP - 1) / STEP;
+    const int lr = lane & 15, g = lane >> 4;         // operand view: row / token lr, k group g
+
+    const int64_t row_bytes = I4 ? K / 2 : K;
+    const __amdgpu_buffer_rsrc_t rw = rsrc(Wq, (int64_t)N * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = rsrc(X, (int64_t)M * K * 2);
+    const __amdgpu_buffer_rsrc_t rsc = rsrc(scales, I4 ? (int64_t)N * (K / 64) * 2 : (int64_t)N * 2);
+    const bool row_ok = (n0 + lr) < N;
+    const uint32_t wrow = row_ok ? (uint32_t)((int64_t)(n0 + lr) * row_bytes) : OOB;
+
+    // weight pieces of one step for this lane.  int4: load u covers k = 128 u + 32 g .. + 31
+    // (16 bytes); int8: load u covers k = 64 u + 16 g .. + 15.
+    auto load_w = [&](u32x4 (&w)[WLOADS], int k0) {
+#pragma unroll
+        for (int u = 0; u < WLOADS; u++) {
+            const int k = k0 + (I4 ? 128 * u + 32 * g : 64 * u + 16 * g);
+            const uint32_t off = (k < kend) ? wrow + (uint32_t)(I4 ? k / 2 : k) : OOB;
+            w[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+        }
+    };
+    // int4 scales of one step: eight consecutive blocks of each of the four output channels this
+    // lane owns in the accumulator view (channel n0 + 4 g + v)
+    auto load_s = [&](u32x4 (&s)[4], int k0) {
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+            const int n = n0 + 4 * g + v;
+            const uint32_t off = (n < N && k0 < kend) ? (uint32_t)(((int64_t)n * (K / 64) + k0 / 64) * 2) : OOB;
+            s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, off, 0, 0);
+        }
+    };
+    // token tile of one step: 1024 chunks of 16 bytes, four per thread
+    auto load_x = [&](u32x4 (&x)[4], int k0) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
+            const int k = k0 + chunk * 8;
+            const uint32_t off = (tok < M && k < kend) ? (uint32_t)(((int64_t)tok * K + k) * 2) : OOB;
+            x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+        }
+    };
+    auto store_x = [&](const u32x4 (&x)[4], unsigned char* dst) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
+            *reinterpret_cast<u32x4*>(dst + x_off(tok, chunk)) = x[j];
+        }
+    };
+
+    u32x4 wreg[2][WLOADS];
+    u32x4 sreg[2][4];
+    u32x4 xreg[4];
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                // scaled sums (int4) / raw code sums (int8)
+    f32x4 ones_acc = {0.f, 0.f, 0.f, 0.f};           // int8: sum of X over the whole slice
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8 ones = as_bf16x8(ones_bits);
+
+    auto xfrag = [&](const unsigned char* tile, int chunk) {
+        return *reinterpret_cast<const bf16x8*>(tile + x_off(lr, chunk));
+    };
+    // one step of the reduction from registers w (and s) against the token tile
+    auto compute = [&](u32x4 (&w)[WLOADS], u32x4 (&s)[4], const unsigned char* tile) {
+        if constexpr (I4) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) {            // 128 k: two scale blocks
+                uint32_t t[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+                transpose_groups(t);                 // t[c] = codes k = 128 u + 32 c + 8 g .. + 7
+#pragma unroll
+                for (int b = 0; b < 2; b++) {
+                    f32x4 cw = zero4, cx = zero4;
+#pragma unroll
+                    for (int h = 0; h < 2; h++) {
+                        const int c = 2 * b + h;
+                        const bf16x8 xf = xfrag(tile, (128 * u + 32 * c) / 8 + g);
+                        cw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(int4_operand(t[c]), xf, cw, 0, 0, 0);
+                        cx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, cx, 0, 0, 0);
+                    }
+                    // block 2 u + b of this step: fp16 scale of channel n0 + 4 g + v
+                    const int blk = 2 * u + b;
+#pragma unroll
+                    for (int v = 0; v < 4; v++) {
+                        const uint32_t word = s[v][blk >> 1];
+                        const __half hs = __ushort_as_half((unsigned short)((blk & 1) ? (word >> 16) : (word & 0xffffu)));
+                        acc[v] += __half2float(hs) * (cw[v] - 136.f * cx[v]);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; u++) {            // 64 k: lane holds k = 64 u + 16 g .. + 15
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const bf16x8 xf = xfrag(tile, (64 * u + 16 * g + 8 * h) / 8);
+                    const bf16x8 wf = h ? int8_operand(w[u].z, w[u].w) : int8_operand(w[u].x, w[u].y);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc, 0, 0, 0);
+                    ones_acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, ones_acc, 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    if (steps > 0) {
+        load_w(wreg[0], kbeg);
+        if constexpr (I4) load_s(sreg[0], kbeg);
+        load_x(xreg, kbeg);
+        for (int t = 0; t < steps; t += 2) {
+            // even step from buffer 0
+            store_x(xreg, xs[0]);
+            if (t + 1 < steps) {
+                load_w(wreg[1], kbeg + (t + 1) * STEP);
+                if constexpr (I4) load_s(sreg[1], kbeg + (t + 1) * STEP);
+                load_x(xreg, kbeg + (t + 1) * STEP);
+            }
+            __syncthreads();
+            compute(wreg[0], sreg[0], xs[0]);
+            if (t + 1 >= steps) break;
+            // odd step from buffer 1
+            store_x(xreg, xs[1]);
+            if (t + 2 < steps) {
+                load_w(wreg[0], kbeg + (t + 2) * STEP);
+                if constexpr (I4) load_s(sreg[0], kbeg + (t + 2) * STEP);
+                load_x(xreg, kbeg + (t + 2) * STEP);
+            }
+            __syncthreads();
+            compute(wreg[1], sreg[1], xs[1]);
+        }
+    }
+
+    // accumulator view: lane holds token lr, channels n0 + 4 g + v
+    const int n = n0 + 4 * g;
+    if (lr < M && n < N) {
+        f32x4 o = acc;
+        if constexpr (!I4) {
+            // one fp16 scale per output channel, applied once
+            const unsigned short* sc = reinterpret_cast<const unsigned short*>(scales);
+#pragma unroll
+            for (int v = 0; v < 4; v++)
+                o[v] = __half2float(__ushort_as_half(sc[n + v])) * (acc[v] - 128.f * ones_acc[v]);
+        }
+        *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + lr) * N + n) = o;
+    }
+}
+
+// hpart[kc][m][j] = sum over the 256-deep chunk kc of X[m][k] A[k][j]   (fp32, m < M, j < r).
+// The chunk of X ([M][256]) and of A ([256][r]) is copied to LDS with coalesced 16-byte loads;
+// thread (m, j16) then forms the sums for the columns j = j16, j16 + 16, ...
+__global__ __launch_bounds__(NT) void hpart_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ A,
+                                                   float* __restrict__ hpart, int M, int K, int r)
+{
+    constexpr int XLD = HCHUNK + 8;                  // padded token row (bank spread)
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[TOK * XLD];
+    __shared__ __attribute__((aligned(16))) uint16_t As[HCHUNK * 64];
+    const int kc = blockIdx.x;
+    const int k0 = kc * HCHUNK;
+    const int kn = (K - k0 < HCHUNK) ? K - k0 : HCHUNK;          // K is a multiple of 8
+    for (int c = threadIdx.x; c < M * (HCHUNK / 8); c += NT) {
+        const int m = c / (HCHUNK / 8), kk = (c % (HCHUNK / 8)) * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (kk < kn) v = *reinterpret_cast<const u32x4*>(X + (int64_t)m * K + k0 + kk);
+        *reinterpret_cast<u32x4*>(Xs + m * XLD + kk) = v;
+    }
+    // A chunk: kn * r contiguous elements starting at A[k0][0]
+    const int64_t abase = (int64_t)k0 * r;
+    const int an = kn * r;
+    if ((r & 7) == 0) {
+        for (int c = threadIdx.x * 8; c < an; c += NT * 8)
+            *reinterpret_cast<u32x4*>(As + c) = *reinterpret_cast<const u32x4*>(A + abase + c);
+    } else {
+        for (int c = threadIdx.x; c < an; c += NT) As[c] = A[abase + c];
+    }
+    __syncthreads();
+    const int m = threadIdx.x >> 4, j16 = threadIdx.x & 15;
+    for (int j = j16; j < r; j += 16) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll 8
+        for (int k = 0; k + 1 < kn; k += 2) {
+            s0 = fmaf(__uint_as_float((uint32_t)Xs[m * XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
+            s1 = fmaf(__uint_as_float((uint32_t)Xs[m * XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
+        }
+        if (m < M) hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
+    }
+}
+
+// Y[m][n] = bf16( sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
+// A workgroup covers 64 channels; thread (channel c, token group q) handles tokens q, q+4, ...
+template <int RMAX>
+__global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
+                                                    const float* __restrict__ hpart, int kchunks,
+                                                    const uint16_t* __restrict__ B, float scaling,
+                                                    uint16_t* __restrict__ Y, uint16_t* __restrict__ H_out,
+                                                    int M, int N, int r)
+{
+    __shared__ float Hs[TOK * RMAX];
+    for (int o = threadIdx.x; o < M * r; o += NT) {
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;      // independent chains: the loads overlap
+        int kc = 0;
+        for (; kc + 3 < kchunks; kc += 4) {
+            s0 += hpart[(int64_t)(kc + 0) * M * r + o];
+            s1 += hpart[(int64_t)(kc + 1) * M * r + o];
+            s2 += hpart[(int64_t)(kc + 2) * M * r + o];
+            s3 += hpart[(int64_t)(kc + 3) * M * r + o];
+        }
+        for (; kc < kchunks; kc++) s0 += hpart[(int64_t)kc * M * r + o];
+        const float s = (s0 + s1) + (s2 + s3);
+        Hs[o] = s;
+        if (H_out && blockIdx.x == 0) {
+            const __bf16 hb = (__bf16)s;
+            H_out[o] = __builtin_bit_cast(uint16_t, hb);
+        }
+    }
+    __syncthreads();
+    const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+    if (n >= N) return;
+    float b[RMAX];
+#pragma unroll
+    for (int j = 0; j < RMAX; j++) b[j] = (j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
+    for (int m = threadIdx.x >> 6; m < M; m += 4) {
+        float s = 0.f;
+        for (int sp = 0; sp < splits; sp++) s += part[((int64_t)sp * M + m) * N + n];
+        float l = 0.f;
+#pragma unroll
+        for (int j = 0; j < RMAX; j++) l = fmaf(Hs[m * r + (j < r ? j : 0)], b[j], l);
+        const __bf16 yb = (__bf16)(s + scaling * l);
+        Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
+    }
+}
+
+}  // namespace skinny
+
+bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
+{
+    (void)N;
+    if (scheme != 4 && scheme != 8) return false;
+    return M >= 1 && M <= skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
+}
+
+QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
+{
+    QskinnyPlan p;
+    const int64_t row_blocks = (N + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
+    const int64_t ksteps = K / skinny::STEP;
+    // enough workgroups to put about four on every compute unit, at least one step each
+    int64_t s = (4 * (int64_t)num_cu + row_blocks - 1) / row_blocks;
+    if (s > ksteps) s = ksteps;
+    if (s < 1) s = 1;
+    const int64_t per = (ksteps + s - 1) / s;
+    p.k_chunk = (int)(per * skinny::STEP);
+    p.splits = (int)((ksteps + per - 1) / per);
+    p.kchunks = (int)((K + skinny::HCHUNK - 1) / skinny::HCHUNK);
+    p.part_bytes = (int64_t)p.splits * M * N * 4;
+    p.hpart_bytes = (int64_t)p.kchunks * M * r * 4;
+    return p;
+}
+
+hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales, int scheme, const void* A, const void* B,
+                              float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
+                              const QskinnyPlan& p, float* part, float* hpart, hipStream_t st)
+{
+    using namespace skinny;
+    const int hslot = prof_begin("qskinny_hpart", 2.0 * M * K * (double)r, 0.0, st);
+    hipLaunchKernelGGL(hpart_kernel, dim3((unsigned)p.kchunks), dim3(NT), 0, st, static_cast<const uint16_t*>(X),
+                       static_cast<const uint16_t*>(A), hpart, (int)M, (int)K, (int)r);
+    prof_end(hslot, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t row_blocks = (N + ROWS_WG - 1) / ROWS_WG;
+    const dim3 grid((unsigned)(row_blocks * p.splits));
+    const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
+    const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * (double)N,
+                                wbytes + 2.0 * M * K + 4.0 * p.splits * M * N, st);
+    if (scheme == 4)
+        hipLaunchKernelGGL(qskinny_fwd_kernel<4>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk);
+    else
+        hipLaunchKernelGGL(qskinny_fwd_kernel<8>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk);
+    prof_end(slot, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 fgrid((unsigned)((N + 63) / 64));
+    const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
+    if (r <= 16)
+        hipLaunchKernelGGL(finish_kernel<16>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
+                           static_cast<const uint16_t*>(B), scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
+                           (int)M, (int)N, (int)r);
+    else
+        hipLaunchKernelGGL(finish_kernel<64>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
+                           static_cast<const uint16_t*>(B), scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
+                           (int)M, (int)N, (int)r);
+    prof_end(fslot, st);
+    return hipGetLastError();
+}
+
+}  // namespace fhpc

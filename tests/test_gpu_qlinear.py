@@ -168,3 +168,50 @@ def test_config5_full_size():
     shapes = [("q", d, d), ("k", d, d), ("v", d, d), ("o", d, d), ("gate", d, f), ("up", d, f), ("down", f, d)]
     for i, (name, K, N) in enumerate(shapes):
         _run_case("c5 %s" % name, 4, M, K, 16, N, 2.0, 5, tensor_base=10 * i, rows=sample_rows(M, 50 + i, 128))
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,K,r,N", [
+    (1, 512, 16, 72),          # one step, one slice, ragged channel count
+    (7, 2048, 5, 200),         # odd rank, several steps
+    (16, 5120, 16, 328),       # a full token tile, ten steps
+    (3, 1024, 64, 8),          # widest rank the path takes, a single group of channels
+])
+def test_few_token_forward(scheme, M, K, r, N):
+    """M <= 16 tokens and K a multiple of 512 take the weight-streaming forward (codes turned
+    into exact small bf16 integers, offset and scale applied to the fp32 sums)."""
+    fhpc = _fhpc()
+    W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 60)
+    Wq, sc = _quantize_host(W, scheme)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Y, H = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 2.0, save_H=True)
+    Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, 2.0)
+    eY, eH = oracle.rel_fro(from_device(Y), Yr), oracle.rel_fro(from_device(H), Hr)
+    print("few tokens q%d %s: Y %.3e H %.3e" % (scheme, (M, K, r, N), eY, eH), flush=True)
+    assert eY <= TOL_BF16 and eH <= TOL_BF16
+    base = X.f64 @ Wd
+    e = oracle.rel_fro(from_device(Y) - base, Yr - base)
+    assert e < 0.15, e         # the rank-r branch is there
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+def test_few_token_forward_every_code(scheme):
+    """Random bytes as codes (so the 4-bit code -8 and the int8 code -128 occur) with random
+    positive fp16 scales, subnormals included; scaling 0 isolates the frozen weight."""
+    fhpc = _fhpc()
+    rng = np.random.default_rng(11)
+    M, K, N = 5, 1024, 136
+    if scheme == 4:
+        Wq = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+        sc = rng.integers(0x0001, 0x3C00, size=(N, K // 64)).astype(np.uint16)
+    else:
+        Wq = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+        sc = rng.integers(0x0001, 0x3C00, size=(N,)).astype(np.uint16)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    _, X, A, B, _ = qlinear_inputs(8, M, K, 8, N, 70)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0)
+    e = oracle.rel_fro(from_device(Y), X.f64 @ Wd)
+    print("few tokens q%d every code: %.3e" % (scheme, e), flush=True)
+    assert e <= TOL_BF16
