@@ -98,9 +98,10 @@ SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
     else if (N > 128) tile = TILE_128x256;
     else tile = TILE_128x128;
     SplitPlan sp = plan_split_on(tile, M, N, Kred);
-    if (tile == TILE_256x256) {
-        // Both eight-wave shapes run these products equally fast when they fill the chip; the one
-        // that needs fewer slices writes (and later re-reads) fewer partial-sum slabs.
+    if (tile == TILE_256x256 && sp.splits >= 8) {
+        // Many slices mean many partial-sum slabs to write and re-read.  The 256x128 shape needs
+        // half as many; measured, it wins from eight slices on (config 2: 4096x512 outputs over
+        // 16384 tokens) and loses below (config 3: the 256x256 kernel is 25 % faster there).
         const SplitPlan alt = plan_split_on(TILE_256x128, M, N, Kred);
         if (alt.splits < sp.splits) sp = alt;
     }
