@@ -528,6 +528,7 @@ int swiglu_fwd(const void* G, const void* U, void* Z, int64_t n_elems, int dtype
     if (!G || !U || !Z) return FHPC_ERR_NULL;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
     if (n_elems < 0) return FHPC_ERR_SHAPE;
+    if (!aligned(G, 16) || !aligned(U, 16) || !aligned(Z, 16)) return FHPC_ERR_ALIGN;
     FHPC_HIP(launch_swiglu_fwd(G, U, Z, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
     return FHPC_OK;
 }
@@ -538,6 +539,7 @@ int swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU,
     if (!G || !U || !dZ || !dG || !dU) return FHPC_ERR_NULL;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
     if (n_elems < 0) return FHPC_ERR_SHAPE;
+    if (!aligned(G, 16) || !aligned(U, 16) || !aligned(dZ, 16) || !aligned(dG, 16) || !aligned(dU, 16)) return FHPC_ERR_ALIGN;
     FHPC_HIP(launch_swiglu_bwd(G, U, dZ, dG, dU, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
     return FHPC_OK;
 }
@@ -547,6 +549,7 @@ int fhpc_add(const void* a, const void* b, void* out, int64_t n_elems, int dtype
     if (!a || !b || !out) return FHPC_ERR_NULL;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
     if (n_elems < 0) return FHPC_ERR_SHAPE;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16)) return FHPC_ERR_ALIGN;
     FHPC_HIP(launch_add(a, b, out, n_elems, dtype == FHPC_BF16, static_cast<hipStream_t>(hip_stream)));
     return FHPC_OK;
 }
@@ -568,7 +571,11 @@ int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void*
     if (!W || !Wq_out || !scales_out) return FHPC_ERR_NULL;
     int rc = check_qweight(qscheme, block, K, N, true);
     if (rc) return rc;
-    FHPC_HIP(launch_quantize(W, qscheme, block, Wq_out, scales_out, K, N, static_cast<hipStream_t>(hip_stream)));
+    // int8: the partial column maxima (ceil(K/64) * N floats, never more than the K * N code bytes)
+    // are staged in the code buffer itself; they are consumed before the first code is written
+    if (!aligned(W, 16) || !aligned(Wq_out, 16) || !aligned(scales_out, 2)) return FHPC_ERR_ALIGN;
+    FHPC_HIP(launch_quantize(W, qscheme, block, Wq_out, scales_out, K, N, static_cast<float*>(Wq_out),
+                             static_cast<hipStream_t>(hip_stream)));
     return FHPC_OK;
 }
 

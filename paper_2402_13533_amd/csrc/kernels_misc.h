@@ -14,8 +14,9 @@ hipError_t launch_add(const void* a, const void* b, void* out, int64_t n, bool b
 hipError_t launch_unpack(const void* Wq, int scheme, int8_t* q, int64_t K, int64_t N, hipStream_t s);
 hipError_t launch_dequant(const void* Wq, const void* scales, int scheme, int64_t block, float* out,
                           int64_t K, int64_t N, hipStream_t s);
+// int8: `scratch` holds ceil(K / 64) * N floats (partial column maxima); unused for the 4-bit scheme.
 hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, void* scales,
-                           int64_t K, int64_t N, hipStream_t s);
+                           int64_t K, int64_t N, float* scratch, hipStream_t s);
 hipError_t launch_pad2d_u16(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src,
                             void* dst, int64_t ld_dst, int64_t rows_dst, hipStream_t s);
 hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int64_t cols,

@@ -100,11 +100,41 @@ __device__ __forceinline__ void store_elem(void* p, int64_t i, float v)
     else reinterpret_cast<float*>(p)[i] = v;
 }
 
+// bf16 storage moves 16 bytes (8 elements) per lane per access; the last n % 8 elements are
+// handled one by one.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)
+{
+    f32x2 v;
+    v.x = lo;
+    v.y = hi;
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const void* G, const void* U, void* Z, int64_t n)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t done = 0;
+    if constexpr (BF16) {
+        const int64_t n8 = n / 8;
+        for (int64_t i = tid; i < n8; i += stride) {
+            const u32x4_t g = reinterpret_cast<const u32x4_t*>(G)[i], u = reinterpret_cast<const u32x4_t*>(U)[i];
+            u32x4_t z;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float g0 = bf16_lo(g[e]), g1 = bf16_hi(g[e]);
+                z[e] = bf16_pack(bf16_lo(u[e]) * g0 * sigmoid_f(g0), bf16_hi(u[e]) * g1 * sigmoid_f(g1));
+            }
+            reinterpret_cast<u32x4_t*>(Z)[i] = z;
+        }
+        done = n8 * 8;
+    }
+    for (int64_t i = done + tid; i < n; i += stride) {
         const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i);
         store_elem<BF16>(Z, i, u * g * sigmoid_f(g));
     }
@@ -115,7 +145,29 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* G, const vo
                                                          void* dG, void* dU, int64_t n)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t done = 0;
+    if constexpr (BF16) {
+        const int64_t n8 = n / 8;
+        for (int64_t i = tid; i < n8; i += stride) {
+            const u32x4_t g = reinterpret_cast<const u32x4_t*>(G)[i], u = reinterpret_cast<const u32x4_t*>(U)[i];
+            const u32x4_t dz = reinterpret_cast<const u32x4_t*>(dZ)[i];
+            u32x4_t og, ou;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float g0 = bf16_lo(g[e]), g1 = bf16_hi(g[e]);
+                const float s0 = sigmoid_f(g0), s1 = sigmoid_f(g1);
+                const float d0 = bf16_lo(dz[e]), d1 = bf16_hi(dz[e]);
+                ou[e] = bf16_pack(d0 * g0 * s0, d1 * g1 * s1);
+                og[e] = bf16_pack(d0 * bf16_lo(u[e]) * s0 * (1.f + g0 * (1.f - s0)),
+                                  d1 * bf16_hi(u[e]) * s1 * (1.f + g1 * (1.f - s1)));
+            }
+            reinterpret_cast<u32x4_t*>(dU)[i] = ou;
+            reinterpret_cast<u32x4_t*>(dG)[i] = og;
+        }
+        done = n8 * 8;
+    }
+    for (int64_t i = done + tid; i < n; i += stride) {
         const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i), dz = load_elem<BF16>(dZ, i);
         const float sg = sigmoid_f(g);
         store_elem<BF16>(dU, i, dz * g * sg);
@@ -127,13 +179,26 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void add_kernel(const void* a, const void* b, void* out, int64_t n)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t done = 0;
+    if constexpr (BF16) {
+        const int64_t n8 = n / 8;
+        for (int64_t i = tid; i < n8; i += stride) {
+            const u32x4_t x = reinterpret_cast<const u32x4_t*>(a)[i], y = reinterpret_cast<const u32x4_t*>(b)[i];
+            u32x4_t o;
+#pragma unroll
+            for (int e = 0; e < 4; e++) o[e] = bf16_pack(bf16_lo(x[e]) + bf16_lo(y[e]), bf16_hi(x[e]) + bf16_hi(y[e]));
+            reinterpret_cast<u32x4_t*>(out)[i] = o;
+        }
+        done = n8 * 8;
+    }
+    for (int64_t i = done + tid; i < n; i += stride)
         store_elem<BF16>(out, i, load_elem<BF16>(a, i) + load_elem<BF16>(b, i));
 }
 
 static unsigned grid_for(int64_t n)
 {
-    int64_t b = (n + 255) / 256;
+    int64_t b = (n / 8 + 255) / 256;        // one 16-byte access per thread and trip
     return (unsigned)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
 }
 
@@ -223,74 +288,142 @@ hipError_t launch_dequant(const void* Wq, const void* scales, int scheme, int64_
     return hipGetLastError();
 }
 
-// Quantiser.  One workgroup handles 64 output channels (columns of W[K,N]); its 256
-// threads are 64 columns x 4 k-lanes, so reads of W rows are 256-byte coalesced.
-// vec_len = K for per-channel int8, = block for 4-bit; one scale per (column, vector).
-template <int QMAX, bool PACK4>
-__global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W, uint8_t* __restrict__ Wq,
-                                                       uint16_t* __restrict__ scales, int64_t K, int64_t N, int64_t vec_len)
+// Quantiser (Sec. 5.2: one scale per weight vector; here symmetric absmax).  The work is cut
+// into tiles of 64 k x 64 output channels of W[K,N] so that thousands of workgroups stream W
+// at once: 256 threads = 64 columns x 4 k-lanes, rows of W read 256 bytes at a time, each
+// thread keeps its 16 values in registers.
+//   4-bit, block 64: a tile is exactly one weight vector per column: absmax, scale, codes.
+//   int8 per channel: the vector is the whole column, so the column maxima come first
+//   (absmax_tiles_kernel -> partial maxima, column_scale_kernel -> fp16 scales) and the code
+//   kernel then reads the finished scale.
+// Arithmetic per element, identical in both: scale = fp16_rne(absmax / qmax) with an fp32
+// divide; q = clamp(rint(w / float(scale)), -qmax, qmax), 0 when the scale is 0.
+constexpr int QT = 64;
+
+__device__ __forceinline__ void load_tile_column(const float* __restrict__ W, int64_t K, int64_t N, int64_t k0, int64_t n,
+                                                 int kl, float (&w)[16])
 {
-    __shared__ float s_max[4][64];
-    __shared__ uint8_t s_code[64][64 + 4];     // [column][k within chunk]
-    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
-    const int64_t n = (int64_t)blockIdx.x * 64 + col;
-    const bool ok = n < N;
-    const int64_t nvec = K / vec_len;
-    for (int64_t v = 0; v < nvec; v++) {
-        const int64_t kb = v * vec_len;
-        float a = 0.f;
-        if (ok)
-            for (int64_t k = kl; k < vec_len; k += 4) a = fmaxf(a, fabsf(W[(kb + k) * N + n]));
-        s_max[kl][col] = a;
-        __syncthreads();
-        a = fmaxf(fmaxf(s_max[0][col], s_max[1][col]), fmaxf(s_max[2][col], s_max[3][col]));
-        const float sc32 = a / (float)QMAX;
-        const _Float16 hs = (_Float16)sc32;                 // round to nearest even
-        const float sf = (float)hs;
-        if (ok && kl == 0) scales[n * nvec + v] = __builtin_bit_cast(uint16_t, hs);
-        // codes, 64 k at a time, transposed through LDS so that stores run along k
-        for (int64_t c0 = 0; c0 < vec_len; c0 += 64) {
-            __syncthreads();
-            for (int kk = kl; kk < 64; kk += 4) {
-                int code = 0;
-                const int64_t k = c0 + kk;
-                if (ok && k < vec_len && sf != 0.f) {
-                    float t = rintf(W[(kb + k) * N + n] / sf);
-                    t = fminf(fmaxf(t, -(float)QMAX), (float)QMAX);
-                    code = (int)t;
-                }
-                s_code[col][kk] = (uint8_t)code;
-            }
-            __syncthreads();
-            // thread (row = tid/4.., piece) writes 16 codes of one column
-            const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;
-            const int64_t nn = (int64_t)blockIdx.x * 64 + r;
-            if (nn < N) {
-                const int64_t kbase = kb + c0 + piece * 16;
-                if (PACK4) {
-                    uint8_t* dst = Wq + nn * (K / 2) + kbase / 2;
-                    for (int e = 0; e < 8; e++)
-                        if (c0 + piece * 16 + 2 * e < vec_len)
-                            dst[e] = (uint8_t)((s_code[r][piece * 16 + 2 * e] & 0xF) | ((s_code[r][piece * 16 + 2 * e + 1] & 0xF) << 4));
-                } else {
-                    uint8_t* dst = Wq + nn * K + kbase;
-                    for (int e = 0; e < 16; e++)
-                        if (c0 + piece * 16 + e < vec_len) dst[e] = s_code[r][piece * 16 + e];
-                }
-            }
-        }
-        __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const int64_t k = k0 + kl + 4 * i;
+        w[i] = (n < N && k < K) ? W[k * N + n] : 0.f;
     }
 }
 
-hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, void* scales,
-                           int64_t K, int64_t N, hipStream_t s)
+// codes of one tile: thread (col, kl) holds k = kl + 4 i; stored transposed so that every
+// output channel's 64 codes leave as one contiguous run
+template <int QMAX, bool PACK4>
+__device__ __forceinline__ void store_tile_codes(const float (&w)[16], float sf, uint8_t* __restrict__ Wq, int64_t K, int64_t N,
+                                                 int64_t k0, int64_t n0, uint8_t (&s_code)[QT][QT + 4])
 {
-    dim3 grid((unsigned)((N + 63) / 64));
-    if (scheme == 8)
-        hipLaunchKernelGGL((quantize_kernel<127, false>), grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N, K);
-    else
-        hipLaunchKernelGGL((quantize_kernel<7, true>), grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N, block);
+    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        int code = 0;
+        if (sf != 0.f) {
+            float t = rintf(w[i] / sf);
+            t = fminf(fmaxf(t, -(float)QMAX), (float)QMAX);
+            code = (int)t;
+        }
+        s_code[col][kl + 4 * i] = (uint8_t)code;
+    }
+    __syncthreads();
+    const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;     // 16 codes of channel n0 + r
+    const int64_t nn = n0 + r;
+    if (nn < N) {
+        const int64_t kbase = k0 + piece * 16;
+        if (PACK4) {
+            uint8_t* dst = Wq + nn * (K / 2) + kbase / 2;
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (kbase + 2 * e < K)
+                    dst[e] = (uint8_t)((s_code[r][piece * 16 + 2 * e] & 0xF) | ((s_code[r][piece * 16 + 2 * e + 1] & 0xF) << 4));
+        } else {
+            uint8_t* dst = Wq + nn * K + kbase;
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+                if (kbase + e < K) dst[e] = s_code[r][piece * 16 + e];
+        }
+    }
+}
+
+// 4-bit, block 64: grid (N / 64, K / 64)
+__global__ __launch_bounds__(256) void quantize_int4_kernel(const float* __restrict__ W, uint8_t* __restrict__ Wq,
+                                                            uint16_t* __restrict__ scales, int64_t K, int64_t N)
+{
+    __shared__ float s_max[4][QT];
+    __shared__ uint8_t s_code[QT][QT + 4];
+    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
+    const int64_t n0 = (int64_t)blockIdx.x * QT, k0 = (int64_t)blockIdx.y * QT;
+    const int64_t n = n0 + col;
+    float w[16];
+    load_tile_column(W, K, N, k0, n, kl, w);
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) a = fmaxf(a, fabsf(w[i]));
+    s_max[kl][col] = a;
+    __syncthreads();
+    a = fmaxf(fmaxf(s_max[0][col], s_max[1][col]), fmaxf(s_max[2][col], s_max[3][col]));
+    const _Float16 hs = (_Float16)(a / 7.f);                // round to nearest even
+    if (n < N && kl == 0) scales[n * (K / QT) + blockIdx.y] = __builtin_bit_cast(uint16_t, hs);
+    store_tile_codes<7, true>(w, (float)hs, Wq, K, N, k0, n0, s_code);
+}
+
+// int8 per channel, step 1: pmax[tile row][n] = max |W| over the tile's 64 k
+__global__ __launch_bounds__(256) void absmax_tiles_kernel(const float* __restrict__ W, float* __restrict__ pmax, int64_t K, int64_t N)
+{
+    __shared__ float s_max[4][QT];
+    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.x * QT + col, k0 = (int64_t)blockIdx.y * QT;
+    float w[16];
+    load_tile_column(W, K, N, k0, n, kl, w);
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) a = fmaxf(a, fabsf(w[i]));
+    s_max[kl][col] = a;
+    __syncthreads();
+    if (kl == 0 && n < N)
+        pmax[(int64_t)blockIdx.y * N + n] = fmaxf(fmaxf(s_max[0][col], s_max[1][col]), fmaxf(s_max[2][col], s_max[3][col]));
+}
+
+// step 2: scale[n] = fp16(max over tile rows / 127)
+__global__ __launch_bounds__(256) void column_scale_kernel(const float* __restrict__ pmax, int64_t rows, int64_t N, uint16_t* __restrict__ scales)
+{
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float a = 0.f;
+    for (int64_t r = 0; r < rows; r++) a = fmaxf(a, pmax[r * N + n]);
+    const _Float16 hs = (_Float16)(a / 127.f);
+    scales[n] = __builtin_bit_cast(uint16_t, hs);
+}
+
+// step 3: codes with the finished scales; grid (N / 64, K / 64)
+__global__ __launch_bounds__(256) void quantize_int8_kernel(const float* __restrict__ W, const uint16_t* __restrict__ scales,
+                                                            uint8_t* __restrict__ Wq, int64_t K, int64_t N)
+{
+    __shared__ uint8_t s_code[QT][QT + 4];
+    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
+    const int64_t n0 = (int64_t)blockIdx.x * QT, k0 = (int64_t)blockIdx.y * QT;
+    const int64_t n = n0 + col;
+    float w[16];
+    load_tile_column(W, K, N, k0, n, kl, w);
+    const float sf = (n < N) ? (float)__builtin_bit_cast(_Float16, scales[n]) : 0.f;
+    store_tile_codes<127, false>(w, sf, Wq, K, N, k0, n0, s_code);
+}
+
+// `scratch` (int8 only): (K / 64 rounded up) * N floats for the partial maxima.
+hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, void* scales,
+                           int64_t K, int64_t N, float* scratch, hipStream_t s)
+{
+    (void)block;
+    const dim3 grid((unsigned)((N + QT - 1) / QT), (unsigned)((K + QT - 1) / QT));
+    if (scheme == 4) {
+        hipLaunchKernelGGL(quantize_int4_kernel, grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(absmax_tiles_kernel, grid, dim3(256), 0, s, W, scratch, K, N);
+    hipLaunchKernelGGL(column_scale_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, scratch, (int64_t)grid.y, N, (uint16_t*)scales);
+    hipLaunchKernelGGL(quantize_int8_kernel, grid, dim3(256), 0, s, W, (const uint16_t*)scales, (uint8_t*)Wq, K, N);
     return hipGetLastError();
 }
 

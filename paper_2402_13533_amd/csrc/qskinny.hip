@@ -19,7 +19,8 @@
 //
 // Work split: a workgroup of four waves owns 64 output channels (16 per wave) and one slice
 // of the reduction; slices write fp32 partial sums to slabs; a finishing kernel adds the slabs
-// and the rank-r branch and rounds to bf16.  H = X * A comes from a small kernel of its own.
+// and the rank-r branch and rounds to bf16.  H = X * A is formed in 128-deep chunks by extra
+// workgroups appended to the same grid.
 #include "qskinny.h"
 #include "profile.h"
 
@@ -37,7 +38,7 @@ constexpr int NT = 256;
 constexpr int ROWS_WG = 64;            // output channels per workgroup
 constexpr int TOK = 16;                // token rows of the MFMA tile
 constexpr int STEP = 512;              // reduction depth per pipeline step
-constexpr int HCHUNK = 256;            // reduction depth per workgroup of the H = X A kernel
+constexpr int HCHUNK = 128;            // reduction depth per workgroup of the H = X A kernel
 constexpr uint32_t OOB = 0x80000000u;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t bytes)
@@ -96,14 +97,63 @@ __device__ __forceinline__ bf16x8 int8_operand(uint32_t w0, uint32_t w1)
 // by the token so that the 16 lanes of a group (16 tokens, same chunk) hit 16 different banks.
 __device__ __forceinline__ uint32_t x_off(int tok, int chunk) { return (uint32_t)tok * (STEP * 2) + (uint32_t)(((chunk ^ tok) & 63) << 4); }
 
+// hpart[kc][m][j] = sum over the 128-deep chunk kc of X[m][k] A[k][j]   (fp32, m < M, j < r).
+// Run by the extra workgroups at the end of the streaming kernel's grid, so that H = X A costs no
+// launch of its own.  The chunk of X ([M][128]) and of A ([128][r]) is copied to LDS with
+// coalesced loads; thread (m, j16) then forms the sums for the columns j = j16, j16 + 16, ...
+constexpr int H_XLD = HCHUNK + 8;                    // padded token row (bank spread)
+constexpr int H_LDS_BYTES = (TOK * H_XLD + HCHUNK * 64) * 2;
+__device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const uint16_t* __restrict__ X,
+                                           const uint16_t* __restrict__ A, float* __restrict__ hpart, int M, int K, int r)
+{
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* As = Xs + TOK * H_XLD;
+    const int k0 = kc * HCHUNK;
+    const int kn = (K - k0 < HCHUNK) ? K - k0 : HCHUNK;          // K is a multiple of 8
+    for (int c = threadIdx.x; c < M * (HCHUNK / 8); c += NT) {
+        const int m = c / (HCHUNK / 8), kk = (c % (HCHUNK / 8)) * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (kk < kn) v = *reinterpret_cast<const u32x4*>(X + (int64_t)m * K + k0 + kk);
+        *reinterpret_cast<u32x4*>(Xs + m * H_XLD + kk) = v;
+    }
+    // A chunk: kn * r contiguous elements starting at A[k0][0]
+    const int64_t abase = (int64_t)k0 * r;
+    const int an = kn * r;
+    if ((r & 7) == 0) {
+        for (int c = threadIdx.x * 8; c < an; c += NT * 8)
+            *reinterpret_cast<u32x4*>(As + c) = *reinterpret_cast<const u32x4*>(A + abase + c);
+    } else {
+        for (int c = threadIdx.x; c < an; c += NT) As[c] = A[abase + c];
+    }
+    __syncthreads();
+    const int m = threadIdx.x >> 4, j16 = threadIdx.x & 15;
+    for (int j = j16; j < r; j += 16) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll 8
+        for (int k = 0; k + 1 < kn; k += 2) {
+            s0 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
+            s1 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
+        }
+        if (m < M) hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
+    }
+}
+
 template <int SCHEME>
 __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, const void* __restrict__ Wq,
                                                          const void* __restrict__ scales, float* __restrict__ part,
-                                                         int M, int K, int N, int k_chunk)
+                                                         int M, int K, int N, int k_chunk,
+                                                         const void* __restrict__ A, float* __restrict__ hpart, int r, int main_grid)
 {
     constexpr bool I4 = (SCHEME == 4);
     constexpr int WLOADS = I4 ? 4 : 8;               // 16-byte weight loads per lane per step
-    __shared__ __attribute__((aligned(16))) unsigned char xs[2][TOK * STEP * 2];
+    constexpr int XS_BYTES = TOK * STEP * 2;
+    static_assert(H_LDS_BYTES <= 2 * XS_BYTES, "the H = X A workgroups reuse the token tiles' LDS");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XS_BYTES];
+    unsigned char* const xs[2] = {smem, smem + XS_BYTES};
+    if ((int)blockIdx.x >= main_grid) {
+        hpart_body(smem, (int)blockIdx.x - main_grid, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(A), hpart, M, K, r);
+        return;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -255,46 +305,6 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     }
 }
 
-// hpart[kc][m][j] = sum over the 256-deep chunk kc of X[m][k] A[k][j]   (fp32, m < M, j < r).
-// The chunk of X ([M][256]) and of A ([256][r]) is copied to LDS with coalesced 16-byte loads;
-// thread (m, j16) then forms the sums for the columns j = j16, j16 + 16, ...
-__global__ __launch_bounds__(NT) void hpart_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ A,
-                                                   float* __restrict__ hpart, int M, int K, int r)
-{
-    constexpr int XLD = HCHUNK + 8;                  // padded token row (bank spread)
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[TOK * XLD];
-    __shared__ __attribute__((aligned(16))) uint16_t As[HCHUNK * 64];
-    const int kc = blockIdx.x;
-    const int k0 = kc * HCHUNK;
-    const int kn = (K - k0 < HCHUNK) ? K - k0 : HCHUNK;          // K is a multiple of 8
-    for (int c = threadIdx.x; c < M * (HCHUNK / 8); c += NT) {
-        const int m = c / (HCHUNK / 8), kk = (c % (HCHUNK / 8)) * 8;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (kk < kn) v = *reinterpret_cast<const u32x4*>(X + (int64_t)m * K + k0 + kk);
-        *reinterpret_cast<u32x4*>(Xs + m * XLD + kk) = v;
-    }
-    // A chunk: kn * r contiguous elements starting at A[k0][0]
-    const int64_t abase = (int64_t)k0 * r;
-    const int an = kn * r;
-    if ((r & 7) == 0) {
-        for (int c = threadIdx.x * 8; c < an; c += NT * 8)
-            *reinterpret_cast<u32x4*>(As + c) = *reinterpret_cast<const u32x4*>(A + abase + c);
-    } else {
-        for (int c = threadIdx.x; c < an; c += NT) As[c] = A[abase + c];
-    }
-    __syncthreads();
-    const int m = threadIdx.x >> 4, j16 = threadIdx.x & 15;
-    for (int j = j16; j < r; j += 16) {
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll 8
-        for (int k = 0; k + 1 < kn; k += 2) {
-            s0 = fmaf(__uint_as_float((uint32_t)Xs[m * XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
-            s1 = fmaf(__uint_as_float((uint32_t)Xs[m * XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
-        }
-        if (m < M) hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
-    }
-}
-
 // Y[m][n] = bf16( sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
 // A workgroup covers 64 channels; thread (channel c, token group q) handles tokens q, q+4, ...
 template <int RMAX>
@@ -305,16 +315,36 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
                                                     int M, int N, int r)
 {
     __shared__ float Hs[TOK * RMAX];
+    // Everything this thread needs from memory is requested up front (the column of B, the slab
+    // sums of its tokens, its share of the H partial sums), so the kernel pays one memory round
+    // trip, not three.
+    const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int mq = threadIdx.x >> 6;
+    const bool live = n < N;
+    float b[RMAX];
+#pragma unroll
+    for (int j = 0; j < RMAX; j++) b[j] = (live && j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
+    float base[TOK / 4];
+#pragma unroll
+    for (int t = 0; t < TOK / 4; t++) {
+        const int m = mq + 4 * t;
+        float s = 0.f;
+        if (live && m < M)
+            for (int sp = 0; sp < splits; sp++) s += part[((int64_t)sp * M + m) * N + n];
+        base[t] = s;
+    }
     for (int o = threadIdx.x; o < M * r; o += NT) {
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;      // independent chains: the loads overlap
-        int kc = 0;
-        for (; kc + 3 < kchunks; kc += 4) {
-            s0 += hpart[(int64_t)(kc + 0) * M * r + o];
-            s1 += hpart[(int64_t)(kc + 1) * M * r + o];
-            s2 += hpart[(int64_t)(kc + 2) * M * r + o];
-            s3 += hpart[(int64_t)(kc + 3) * M * r + o];
+        float sv[16];                                       // independent chains: sixteen loads in flight
+#pragma unroll
+        for (int q = 0; q < 16; q++) sv[q] = 0.f;
+        for (int kc = 0; kc < kchunks; kc += 16) {
+#pragma unroll
+            for (int q = 0; q < 16; q++)
+                if (kc + q < kchunks) sv[q] += hpart[(int64_t)(kc + q) * M * r + o];
         }
-        for (; kc < kchunks; kc++) s0 += hpart[(int64_t)kc * M * r + o];
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; q += 4) { s0 += sv[q]; s1 += sv[q + 1]; s2 += sv[q + 2]; s3 += sv[q + 3]; }
         const float s = (s0 + s1) + (s2 + s3);
         Hs[o] = s;
         if (H_out && blockIdx.x == 0) {
@@ -323,18 +353,15 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
         }
     }
     __syncthreads();
-    const int n = blockIdx.x * 64 + (threadIdx.x & 63);
-    if (n >= N) return;
-    float b[RMAX];
+    if (!live) return;
 #pragma unroll
-    for (int j = 0; j < RMAX; j++) b[j] = (j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
-    for (int m = threadIdx.x >> 6; m < M; m += 4) {
-        float s = 0.f;
-        for (int sp = 0; sp < splits; sp++) s += part[((int64_t)sp * M + m) * N + n];
+    for (int t = 0; t < TOK / 4; t++) {
+        const int m = mq + 4 * t;
+        if (m >= M) break;
         float l = 0.f;
 #pragma unroll
         for (int j = 0; j < RMAX; j++) l = fmaf(Hs[m * r + (j < r ? j : 0)], b[j], l);
-        const __bf16 yb = (__bf16)(s + scaling * l);
+        const __bf16 yb = (__bf16)(base[t] + scaling * l);
         Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
     }
 }
@@ -371,23 +398,18 @@ hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales,
                               const QskinnyPlan& p, float* part, float* hpart, hipStream_t st)
 {
     using namespace skinny;
-    const int hslot = prof_begin("qskinny_hpart", 2.0 * M * K * (double)r, 0.0, st);
-    hipLaunchKernelGGL(hpart_kernel, dim3((unsigned)p.kchunks), dim3(NT), 0, st, static_cast<const uint16_t*>(X),
-                       static_cast<const uint16_t*>(A), hpart, (int)M, (int)K, (int)r);
-    prof_end(hslot, st);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const int64_t row_blocks = (N + ROWS_WG - 1) / ROWS_WG;
-    const dim3 grid((unsigned)(row_blocks * p.splits));
+    const int main_grid = (int)(row_blocks * p.splits);
+    const dim3 grid((unsigned)(main_grid + p.kchunks));     // streaming workgroups, then the H = X A chunks
     const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
     const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * (double)N,
                                 wbytes + 2.0 * M * K + 4.0 * p.splits * M * N, st);
     if (scheme == 4)
-        hipLaunchKernelGGL(qskinny_fwd_kernel<4>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk);
+        hipLaunchKernelGGL(qskinny_fwd_kernel<4>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk, A, hpart, (int)r, main_grid);
     else
-        hipLaunchKernelGGL(qskinny_fwd_kernel<8>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk);
+        hipLaunchKernelGGL(qskinny_fwd_kernel<8>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk, A, hpart, (int)r, main_grid);
     prof_end(slot, st);
-    e = hipGetLastError();
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 fgrid((unsigned)((N + 63) / 64));
     const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
