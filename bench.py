@@ -19,15 +19,15 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 # HBM-side traffic per launch of a kernel on a workload (fetched + written bytes), from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_c2_gemm_kernels.txt
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_c2_lowrank_gemm_kernels.txt
 # (counter units scaled by a 256 MiB read + 256 MiB write kernel in the same run); None where
 # not measured.  Algorithmic bytes of the same launches are 155-160 MB.
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "gemm_pp<256x128x64,a0,b1,o0>"): 168.0e6 + 16.8e6,    # H = X A
-    ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 93.9e6 + 134.2e6,    # Y = H B
+    ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 94.1e6 + 134.2e6,    # Y = H B
     ("c2", "gemm_pp<256x128x64,a0,b0,o0>"): 168.0e6 + 16.8e6,    # dH = dY B^T
-    ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 97.4e6 + 134.2e6,    # dX = dH A^T
-    ("c2", "gemm_pp<256x256x32,a1,b1,o1>"): 151.2e6 + 75.2e6,    # dA = X^T dH, dB = H^T dY (8 partial-sum slabs)
+    ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 98.0e6 + 134.2e6,    # dX = dH A^T
+    ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 227.2e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
 }
 
 

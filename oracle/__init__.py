@@ -186,6 +186,34 @@ def qlinear_lowrank_bwd(X, Wd, A, B, s: float, dY):
     return dX, dA, dB
 
 
+# ---------------------------------------------------------------- blend layer
+
+def blend_fwd(X, W, A, B, alpha: float):
+    """Y = alpha X W + (1 - alpha) (X A) B with W[K,N] frozen.  Returns (Y, H)."""
+    X, W, A, B = _d(X), _d(W), _d(A), _d(B)
+    M, K = X.shape
+    r, N = B.shape
+    assert W.shape == (K, N) and A.shape == (K, r)
+    H = np.empty((M, r))
+    Y = np.empty((M, N))
+    lib().orc_blend_fwd(_p(X), _p(W), _p(A), _p(B), C.c_double(alpha), _p(H), _p(Y), _i(M), _i(K), _i(r), _i(N))
+    return Y, H
+
+
+def blend_bwd(X, W, A, B, alpha: float, dY):
+    """Returns (dX, dA, dB); the frozen W gets no gradient."""
+    X, W, A, B, dY = _d(X), _d(W), _d(A), _d(B), _d(dY)
+    M, K = X.shape
+    r, N = B.shape
+    assert W.shape == (K, N) and A.shape == (K, r) and dY.shape == (M, N)
+    dX = np.empty((M, K))
+    dA = np.empty((K, r))
+    dB = np.empty((r, N))
+    lib().orc_blend_bwd(_p(X), _p(W), _p(A), _p(B), C.c_double(alpha), _p(dY), _p(dX), _p(dA), _p(dB),
+                        _i(M), _i(K), _i(r), _i(N))
+    return dX, dA, dB
+
+
 # ---------------------------------------------------------------- SiLU gate
 
 def swiglu_fwd(G, U):

@@ -308,6 +308,56 @@ void orc_qlinear_lowrank_bwd(const double *X, const double *Wd,
 }
 
 /* ------------------------------------------------------------------ */
+/* Blend of a frozen pretrained weight with the factor pair, Sec. 4.1    */
+/* item 3:  y = alpha W x + (1 - alpha) B A x,  0 <= alpha <= 1          */
+/* ------------------------------------------------------------------ */
+
+/* Row form: Y = alpha X W + (1 - alpha) (X A) B, with W[K,N] frozen. */
+void orc_blend_fwd(const double *X, const double *W,
+                   const double *A, const double *B, double alpha,
+                   double *H, double *Y,
+                   int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    double *P = (double *)malloc(sizeof(double) * (size_t)M * (size_t)N);   /* X W */
+    double *L = (double *)malloc(sizeof(double) * (size_t)M * (size_t)N);   /* (X A) B */
+    mm_nn(X, W, P, M, K, N);
+    mm_nn(X, A, H, M, K, r);
+    mm_nn(H, B, L, M, r, N);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M * N; i++) Y[i] = alpha * P[i] + (1.0 - alpha) * L[i];
+    free(P);
+    free(L);
+}
+
+/* dH = dY B^T ; dX = alpha dY W^T + (1 - alpha) dH A^T ;
+ * dA = (1 - alpha) X^T dH ; dB = (1 - alpha) (X A)^T dY.  W is frozen: no dW. */
+void orc_blend_bwd(const double *X, const double *W,
+                   const double *A, const double *B, double alpha,
+                   const double *dY, double *dX, double *dA, double *dB,
+                   int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    double *H  = (double *)malloc(sizeof(double) * (size_t)M * (size_t)r);
+    double *dH = (double *)malloc(sizeof(double) * (size_t)M * (size_t)r);
+    double *P  = (double *)malloc(sizeof(double) * (size_t)M * (size_t)K);   /* dY W^T */
+    double *T  = (double *)malloc(sizeof(double) * (size_t)M * (size_t)K);   /* dH A^T */
+    const double beta = 1.0 - alpha;
+    mm_nn(X, A, H, M, K, r);
+    mm_nt(dY, B, dH, M, N, r);
+    mm_nt(dY, W, P, M, N, K);
+    mm_nt(dH, A, T, M, r, K);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M * K; i++) dX[i] = alpha * P[i] + beta * T[i];
+    mm_tn(X, dH, dA, M, K, r);
+    mm_tn(H, dY, dB, M, r, N);
+    for (int64_t i = 0; i < K * r; i++) dA[i] *= beta;
+    for (int64_t i = 0; i < r * N; i++) dB[i] *= beta;
+    free(H);
+    free(dH);
+    free(P);
+    free(T);
+}
+
+/* ------------------------------------------------------------------ */
 /* SiLU-gated product between the FFN's linears, Sec. 3.1 eq. FFN       */
 /* ------------------------------------------------------------------ */
 
