@@ -104,6 +104,25 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Blend of a frozen pretrained weight with the factor pair (Sec. 4.1 item 3:
+ * y = alpha W x + (1 - alpha) B A x, 0 <= alpha <= 1, W frozen), with W stored quantised as above:
+ *   Y = alpha * X * deq(Wq, scales) + (1 - alpha) * (X * A) * B
+ * Arguments, layouts, workspace (FHPC_OP_QLINEAR_FWD / _BWD sizes) and error behaviour are those of
+ * qlinear_lowrank_fwd / _bwd with `alpha` in place of `scaling`; alpha outside [0, 1] (or NaN)
+ * returns FHPC_ERR_SHAPE.  alpha = 0 runs the factorised layer alone and never reads Wq. */
+int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                      const void* A, const void* B, float alpha, void* Y, void* H_out,
+                      int64_t M, int64_t K, int64_t r, int64_t N,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*   dX = alpha * dY * deq(W)^T + (1 - alpha) * (dY * B^T) * A^T;
+ *   dA = (1 - alpha) * X^T * (dY * B^T);   dB = (1 - alpha) * (X * A)^T * dY;   no dW. */
+int qlinear_blend_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                      const void* A, const void* B, float alpha, const void* dY,
+                      const void* H_saved, void* dX, float* dA, float* dB,
+                      int64_t M, int64_t K, int64_t r, int64_t N,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of workspace the entry point `op` (FHPC_OP_*) needs for these sizes.
  * Host-only; returns 0 for invalid arguments.  qscheme is ignored for op 0/1. */
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme);

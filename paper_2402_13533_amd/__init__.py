@@ -19,7 +19,7 @@ FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD = 0, 1, 2, 3
 
 EXPORTS = [
-    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd",
+    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
@@ -50,6 +50,8 @@ def load_library():
     lib.qlinear_lowrank_fwd.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, i64, i64, i64, i64, vp, sz, vp]
     lib.qlinear_lowrank_bwd.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp,
                                         i64, i64, i64, i64, vp, sz, vp]
+    lib.qlinear_blend_fwd.argtypes = lib.qlinear_lowrank_fwd.argtypes
+    lib.qlinear_blend_bwd.argtypes = lib.qlinear_lowrank_bwd.argtypes
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
     lib.fhpc_workspace_bytes.restype = sz
     lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -218,7 +220,7 @@ def _q_shapes(Wq, scales, qscheme, K, N, block):
 
 
 def qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, scaling, block=64, Y=None, H_out=None,
-                        save_H: bool = False, workspace=None):
+                        save_H: bool = False, workspace=None, _entry="qlinear_lowrank_fwd"):
     """Y = X deq(Wq, scales) + scaling (X A) B (bf16)."""
     torch = _torch()
     lib = load_library()
@@ -233,15 +235,16 @@ def qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, scaling, block=64, Y=None,
         H_out = torch.empty((M, r), dtype=bf, device=X.device)
     _check(Y, "Y", (M, N), bf); _check(H_out, "H_out", (M, r), bf)
     ws, wsz = _ws(FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, qscheme, X.device, workspace)
-    rc = lib.qlinear_lowrank_fwd(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
-                                 C.c_float(scaling), _ptr(Y), _ptr(H_out), M, K, r, N, _ptr(ws), wsz, _stream())
+    rc = getattr(lib, _entry)(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
+                              C.c_float(scaling), _ptr(Y), _ptr(H_out), M, K, r, N, _ptr(ws), wsz, _stream())
     if rc:
-        raise FhpcError(rc, "qlinear_lowrank_fwd")
+        raise FhpcError(rc, _entry)
     return (Y, H_out) if H_out is not None else Y
 
 
 def qlinear_lowrank_bwd(X, Wq, scales, qscheme, A, B, scaling, dY, block=64, H_saved=None,
-                        need_dX=True, need_dA=True, need_dB=True, dX=None, dA=None, dB=None, workspace=None):
+                        need_dX=True, need_dA=True, need_dB=True, dX=None, dA=None, dB=None, workspace=None,
+                        _entry="qlinear_lowrank_bwd"):
     """Returns (dX, dA, dB); the frozen W gets no gradient."""
     torch = _torch()
     lib = load_library()
@@ -259,12 +262,22 @@ def qlinear_lowrank_bwd(X, Wq, scales, qscheme, A, B, scaling, dY, block=64, H_s
         dB = torch.empty((r, N), dtype=torch.float32, device=X.device)
     _check(dX, "dX", (M, K), bf); _check(dA, "dA", (K, r), torch.float32); _check(dB, "dB", (r, N), torch.float32)
     ws, wsz = _ws(FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16, qscheme, X.device, workspace)
-    rc = lib.qlinear_lowrank_bwd(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
-                                 C.c_float(scaling), _ptr(dY), _ptr(H_saved), _ptr(dX), _ptr(dA), _ptr(dB),
-                                 M, K, r, N, _ptr(ws), wsz, _stream())
+    rc = getattr(lib, _entry)(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
+                              C.c_float(scaling), _ptr(dY), _ptr(H_saved), _ptr(dX), _ptr(dA), _ptr(dB),
+                              M, K, r, N, _ptr(ws), wsz, _stream())
     if rc:
-        raise FhpcError(rc, "qlinear_lowrank_bwd")
+        raise FhpcError(rc, _entry)
     return dX, dA, dB
+
+
+def qlinear_blend_fwd(X, Wq, scales, qscheme, A, B, alpha, **kw):
+    """Y = alpha X deq(Wq, scales) + (1 - alpha) (X A) B (bf16); keywords as qlinear_lowrank_fwd."""
+    return qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, alpha, _entry="qlinear_blend_fwd", **kw)
+
+
+def qlinear_blend_bwd(X, Wq, scales, qscheme, A, B, alpha, dY, **kw):
+    """(dX, dA, dB) of the blend layer; keywords as qlinear_lowrank_bwd."""
+    return qlinear_lowrank_bwd(X, Wq, scales, qscheme, A, B, alpha, dY, _entry="qlinear_blend_bwd", **kw)
 
 
 def swiglu_fwd(G, U, Z=None):

@@ -202,12 +202,12 @@ GemmOperand operand(const void* p, int64_t ld, const void* scales = nullptr, int
 
 // C[M,N] bf16 = A(KC or via a_mode) * B, whole reduction in one workgroup per tile.
 hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void* C, int64_t ldc,
-                      int64_t M, int64_t N, int64_t Kred, hipStream_t st)
+                      int64_t M, int64_t N, int64_t Kred, hipStream_t st, float alpha = 1.f)
 {
     GemmArgs g = {};
     g.a = a; g.b = b; g.c = C; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
-    g.alpha = 1.f; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
+    g.alpha = alpha; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
     return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, N, false), g, st);
 }
 
@@ -426,10 +426,12 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
 }
 
-int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
-                        const void* A, const void* B, float scaling, void* Y, void* H_out,
-                        int64_t M, int64_t K, int64_t r, int64_t N,
-                        void* workspace, size_t workspace_bytes, void* hip_stream)
+// Y = base_scale * X deq(W) + scaling * (X A) B: the finetuning layer (base_scale 1) and the blend
+// layer (base_scale alpha, scaling 1 - alpha) share everything else.
+static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                            const void* A, const void* B, float base_scale, float scaling, void* Y, void* H_out,
+                            int64_t M, int64_t K, int64_t r, int64_t N,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!X || !Wq || !scales || !A || !B || !Y) return FHPC_ERR_NULL;
     int rc = check_q(qscheme, block, K);
@@ -446,7 +448,7 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
     Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16);
     if (s.sk_part) {
         const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
-        FHPC_HIP(launch_qskinny_fwd(X, Wq, scales, qscheme, A, B, scaling, Y, H_out, M, K, r, N, p, s.sk_part, s.sk_hpart, st));
+        FHPC_HIP(launch_qskinny_fwd(X, Wq, scales, qscheme, A, B, base_scale, scaling, Y, H_out, M, K, r, N, p, s.sk_part, s.sk_hpart, st));
         return FHPC_OK;
     }
     const int64_t rp = rank_pad(r);
@@ -456,25 +458,50 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
     void* H = (H_out && rp == r) ? H_out : s.H;
     FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
 
-    GemmArgs g = {};
-    g.a = operand(X, K);
-    g.b = operand(Wq, K, scales, K / 64);
-    g.a2 = operand(H, rp);
-    g.b2 = operand(f.B, N);
-    g.c = Y; g.ldc = N;
-    g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
-    g.alpha = 1.f; g.mid_scale = scaling; g.splits = 1; g.k_chunk = (int)round_up(K, 64);
-    const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
-    FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_XC, OUT_BF16, pick_tile(M, N, false), g, st));
+    if (base_scale == 0.f) {
+        // nothing of the frozen weight is left: the factorised layer alone
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st, scaling));
+    } else {
+        // the kernel forms alpha * (mid_scale * H B + X deq(W))
+        GemmArgs g = {};
+        g.a = operand(X, K);
+        g.b = operand(Wq, K, scales, K / 64);
+        g.a2 = operand(H, rp);
+        g.b2 = operand(f.B, N);
+        g.c = Y; g.ldc = N;
+        g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(K, 64);
+        const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
+        FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_XC, OUT_BF16, pick_tile(M, N, false), g, st));
+    }
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
     return FHPC_OK;
 }
 
-int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
-                        const void* A, const void* B, float scaling, const void* dY,
-                        const void* H_saved, void* dX, float* dA, float* dB,
+int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, void* Y, void* H_out,
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, Y, H_out, M, K, r, N,
+                            workspace, workspace_bytes, hip_stream);
+}
+
+int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                      const void* A, const void* B, float alpha, void* Y, void* H_out,
+                      int64_t M, int64_t K, int64_t r, int64_t N,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!(alpha >= 0.f && alpha <= 1.f)) return FHPC_ERR_SHAPE;
+    return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, alpha, 1.f - alpha, Y, H_out, M, K, r, N,
+                            workspace, workspace_bytes, hip_stream);
+}
+
+static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                            const void* A, const void* B, float base_scale, float scaling, const void* dY,
+                            const void* H_saved, void* dX, float* dA, float* dB,
+                            int64_t M, int64_t K, int64_t r, int64_t N,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!X || !Wq || !scales || !A || !B || !dY) return FHPC_ERR_NULL;
     int rc = check_q(qscheme, block, K);
@@ -507,8 +534,10 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
     }
     if (dX || dA)
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
-    if (dX) {
-        // dX[m][k] = sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
+    if (dX && base_scale == 0.f) {
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st, scaling));
+    } else if (dX) {
+        // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};
         g.a = operand(dY, N);
         g.b = operand(Wq, K, scales, K / 64);
@@ -516,11 +545,32 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
         g.b2 = operand(f.A, rp);
         g.c = dX; g.ldc = K;
         g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
-        g.alpha = 1.f; g.mid_scale = scaling; g.splits = 1; g.k_chunk = (int)round_up(N, 64);
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(N, 64);
         const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
         FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_KC, OUT_BF16, pick_tile(M, K, false), g, st));
     }
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, st);
+}
+
+int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                        const void* A, const void* B, float scaling, const void* dY,
+                        const void* H_saved, void* dX, float* dA, float* dB,
+                        int64_t M, int64_t K, int64_t r, int64_t N,
+                        void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return qlinear_bwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, dY, H_saved, dX, dA, dB, M, K, r, N,
+                            workspace, workspace_bytes, hip_stream);
+}
+
+int qlinear_blend_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                      const void* A, const void* B, float alpha, const void* dY,
+                      const void* H_saved, void* dX, float* dA, float* dB,
+                      int64_t M, int64_t K, int64_t r, int64_t N,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!(alpha >= 0.f && alpha <= 1.f)) return FHPC_ERR_SHAPE;
+    return qlinear_bwd_impl(X, Wq, scales, qscheme, block, A, B, alpha, 1.f - alpha, dY, H_saved, dX, dA, dB, M, K, r, N,
+                            workspace, workspace_bytes, hip_stream);
 }
 
 int swiglu_fwd(const void* G, const void* U, void* Z, int64_t n_elems, int dtype, void* hip_stream)

@@ -17,10 +17,10 @@ struct QskinnyPlan {
 bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu);
 
-// Y[M,N] bf16 = X deq(Wq) + scaling (X A) B;  H_out (M x r bf16) optional.  A is [K][r], B is [r][N]
+// Y[M,N] bf16 = base_scale X deq(Wq) + scaling (X A) B;  H_out (M x r bf16) optional.  A is [K][r], B is [r][N]
 // (unpadded).  part and hpart are scratch of the plan's sizes.
 hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales, int scheme, const void* A, const void* B,
-                              float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
+                              float base_scale, float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
                               const QskinnyPlan& p, float* part, float* hpart, hipStream_t st);
 
 }  // namespace fhpc

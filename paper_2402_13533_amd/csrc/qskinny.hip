@@ -1,5 +1,5 @@
 // Weight-streaming forward of the quantised finetuning layer for a handful of tokens
-// (M <= 16):  Y = X * deq(Wq, scales) + scaling * (X * A) * B.
+// (M <= 16):  Y = base_scale * X * deq(Wq, scales) + scaling * (X * A) * B.
 //
 // At this size the layer is bound by reading the packed weight once from HBM, so the kernel
 // is built around that stream: every lane loads 16-byte pieces of its own weight row straight
@@ -305,12 +305,12 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     }
 }
 
-// Y[m][n] = bf16( sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
+// Y[m][n] = bf16( base_scale * sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
 // A workgroup covers 64 channels; thread (channel c, token group q) handles tokens q, q+4, ...
 template <int RMAX>
 __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
                                                     const float* __restrict__ hpart, int kchunks,
-                                                    const uint16_t* __restrict__ B, float scaling,
+                                                    const uint16_t* __restrict__ B, float base_scale, float scaling,
                                                     uint16_t* __restrict__ Y, uint16_t* __restrict__ H_out,
                                                     int M, int N, int r)
 {
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
         float l = 0.f;
 #pragma unroll
         for (int j = 0; j < RMAX; j++) l = fmaf(Hs[m * r + (j < r ? j : 0)], b[j], l);
-        const __bf16 yb = (__bf16)(base[t] + scaling * l);
+        const __bf16 yb = (__bf16)(base_scale * base[t] + scaling * l);
         Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
     }
 }
@@ -394,7 +394,7 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
 }
 
 hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales, int scheme, const void* A, const void* B,
-                              float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
+                              float base_scale, float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
                               const QskinnyPlan& p, float* part, float* hpart, hipStream_t st)
 {
     using namespace skinny;
@@ -415,11 +415,11 @@ hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales,
     const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
     if (r <= 16)
         hipLaunchKernelGGL(finish_kernel<16>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
-                           static_cast<const uint16_t*>(B), scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
+                           static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
                            (int)M, (int)N, (int)r);
     else
         hipLaunchKernelGGL(finish_kernel<64>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
-                           static_cast<const uint16_t*>(B), scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
+                           static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
                            (int)M, (int)N, (int)r);
     prof_end(fslot, st);
     return hipGetLastError();

@@ -215,3 +215,46 @@ def test_few_token_forward_every_code(scheme):
     e = oracle.rel_fro(from_device(Y), X.f64 @ Wd)
     print("few tokens q%d every code: %.3e" % (scheme, e), flush=True)
     assert e <= TOL_BF16
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("alpha", [1.0, 0.7, 0.25, 0.0])
+def test_blend_layer(scheme, alpha):
+    """Y = alpha X deq(W) + (1 - alpha) (X A) B with W frozen, forward and backward; alpha = 1 is
+    the frozen layer alone (dA = dB = 0), alpha = 0 the factorised layer alone."""
+    fhpc = _fhpc()
+    M, K, r, N = 300, 320, 24, 264
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 80)
+    B = Bf16.normal(8123, (r, N), r ** -0.5)                 # a branch as large as the base term
+    Wq, sc = _quantize_host(W * 50.0, scheme)               # base weight of comparable magnitude
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y, H = fhpc.qlinear_blend_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, alpha, save_H=True)
+    dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, alpha, dYd, H_saved=H)
+    Yr, Hr = oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)
+    dXr, dAr, dBr = oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
+    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
+            "dX": oracle.rel_fro(from_device(dX), dXr)}
+    if alpha < 1.0:
+        errs["dA"] = oracle.rel_fro(from_device(dA), dAr)
+        errs["dB"] = oracle.rel_fro(from_device(dB), dBr)
+    else:
+        assert not from_device(dA).any() and not from_device(dB).any()
+    print("blend q%d alpha %.2f" % (scheme, alpha), {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+
+
+def test_blend_layer_few_tokens_and_alpha_range():
+    fhpc = _fhpc()
+    M, K, r, N = 4, 1024, 16, 200
+    W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 90)
+    Wq, sc = _quantize_host(W, 4)
+    Wd = oracle.dequant(Wq, sc, 4, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Y = fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), 0.4)
+    assert oracle.rel_fro(from_device(Y), oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, 0.4)[0]) <= TOL_BF16
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(fhpc.FhpcError):
+            fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), bad)
