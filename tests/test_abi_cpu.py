@@ -75,6 +75,12 @@ def test_validation_precedes_launch():
     assert lib.qweight_quantize(p, 4, 48, p, p, 64, 64, nul) == 6
     assert lib.qweight_dequant(p, p, 5, 64, p, 64, 64, nul) == 3
     assert lib.fhpc_add(p, p, p, -1, 1, nul) == 2
+    assert lib.fhpc_add(p, odd, p, 8, 1, nul) == 4
+    assert lib.swiglu_fwd(p, p, odd, 8, 1, nul) == 4
+    bl = lib.qlinear_blend_fwd
+    assert bl(p, p, p, 8, 64, p, p, C.c_float(1.5), p, nul, 16, 64, 8, 64, ws, big, nul) == 2      # alpha > 1
+    assert bl(p, p, p, 8, 64, p, p, C.c_float(float("nan")), p, nul, 16, 64, 8, 64, ws, big, nul) == 2
+    assert bl(p, p, p, 8, 64, p, p, C.c_float(0.5), p, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5
 
 
 def test_binding_refuses_cpu_tensors():
