@@ -178,8 +178,10 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
         dtype = "bf16"
     elif name == "c4":
         M = tokens or 4096
-        calls = [QlinearCall(fhpc, M, 4096, 8, 4096, 8, gen, 2.0, recompute, forward_only)]
-        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, %d tokens, bf16, %s" % (
+        # four independent copies of the layer (own W, X, dY), run back to back: one copy's buffers
+        # (0.17 GB) would sit in the 256 MB Infinity Cache from step to step
+        calls = [QlinearCall(fhpc, M, 4096, 8, 4096, 8, gen, 2.0, recompute, forward_only) for _ in range(4)]
+        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, %d tokens, bf16, %s, 4 buffer sets per step" % (
             M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
     else:

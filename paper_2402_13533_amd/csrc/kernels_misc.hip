@@ -198,14 +198,20 @@ __global__ __launch_bounds__(256) void add_kernel(const void* a, const void* b, 
 
 static unsigned grid_for(int64_t n)
 {
-    int64_t b = (n / 8 + 255) / 256;        // one 16-byte access per thread and trip
+    int64_t b = (n + 255) / 256;            // one element per thread and trip
     return (unsigned)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
+}
+
+// for the kernels that move 8 bf16 elements (16 bytes) per thread and trip
+static unsigned grid_for8(int64_t n, bool bf16)
+{
+    return grid_for(bf16 ? (n + 7) / 8 : n);
 }
 
 hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, bool bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    if (bf16) hipLaunchKernelGGL(swiglu_fwd_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, G, U, Z, n);
+    if (bf16) hipLaunchKernelGGL(swiglu_fwd_kernel<true>, dim3(grid_for8(n, true)), dim3(256), 0, s, G, U, Z, n);
     else hipLaunchKernelGGL(swiglu_fwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, Z, n);
     return hipGetLastError();
 }
@@ -213,7 +219,7 @@ hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, b
 hipError_t launch_add(const void* a, const void* b, void* out, int64_t n, bool bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    if (bf16) hipLaunchKernelGGL(add_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, a, b, out, n);
+    if (bf16) hipLaunchKernelGGL(add_kernel<true>, dim3(grid_for8(n, true)), dim3(256), 0, s, a, b, out, n);
     else hipLaunchKernelGGL(add_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, a, b, out, n);
     return hipGetLastError();
 }
@@ -222,7 +228,7 @@ hipError_t launch_swiglu_bwd(const void* G, const void* U, const void* dZ, void*
                              bool bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    if (bf16) hipLaunchKernelGGL(swiglu_bwd_kernel<true>, dim3(grid_for(n)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
+    if (bf16) hipLaunchKernelGGL(swiglu_bwd_kernel<true>, dim3(grid_for8(n, true)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
     else hipLaunchKernelGGL(swiglu_bwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
     return hipGetLastError();
 }
