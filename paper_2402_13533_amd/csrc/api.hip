@@ -214,9 +214,13 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
 // C[M,N] fp32 (ldc) = alpha * A * B with the reduction split across workgroups: every
 // slice stores its partial sums to its own slab of `part` (no atomics, so the result does
 // not depend on scheduling) and a second kernel adds the slabs into C.
+// With `bf16_out` (dense, ldc == N) and more than one slice, the slab sum writes bf16 there and C is
+// left alone: *wrote_bf16 tells the caller which happened.
 hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
-                          int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st)
+                          int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st,
+                          void* bf16_out = nullptr, bool* wrote_bf16 = nullptr)
 {
+    if (wrote_bf16) *wrote_bf16 = false;
     const SplitPlan sp = plan_split(M, N, Kred);
     GemmArgs g = {};
     g.a = a; g.b = b; g.ldc = ldc;
@@ -232,7 +236,11 @@ hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, 
     g.split_stride = M * ldc;
     hipError_t e = launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_F32, sp.tile, g, st);
     if (e != hipSuccess) return e;
-    return launch_sum_slabs(part, M * ldc, sp.splits, C, st);
+    if (bf16_out && wrote_bf16) {
+        *wrote_bf16 = true;
+        return launch_sum_slabs(part, M * ldc, sp.splits, bf16_out, true, st);
+    }
+    return launch_sum_slabs(part, M * ldc, sp.splits, C, false, st);
 }
 
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
@@ -241,8 +249,9 @@ hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64
                         int64_t M, int64_t Kred, hipStream_t st)
 {
     if (rp <= 32) {
-        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, st);
-        if (e != hipSuccess) return e;
+        bool done = false;
+        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, st, P, &done);
+        if (e != hipSuccess || done) return e;
         return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
     }
     return gemm_plain(OP_KC, b_mode, a, b, P, rp, M, rp, Kred, st);

@@ -21,7 +21,8 @@ hipError_t launch_pad2d_u16(const void* src, int64_t ld_src, int64_t rows_src, i
                             void* dst, int64_t ld_dst, int64_t rows_dst, hipStream_t s);
 hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int64_t cols,
                               float scale, bool to_bf16, hipStream_t s);
-hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, float* out, hipStream_t s);
+// out: fp32, or bf16 when to_bf16 (n a multiple of 4)
+hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out, bool to_bf16, hipStream_t s);
 hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s);
 
 }  // namespace fhpc

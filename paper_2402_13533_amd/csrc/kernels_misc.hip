@@ -483,9 +483,43 @@ hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64
     return hipGetLastError();
 }
 
-// out[i] = sum over s of slabs[s * slab + i]: the second half of a split reduction.
+// out[i] = sum over s of slabs[s * slab + i]: the second half of a split reduction.  A workgroup
+// covers 64 float4 outputs with four groups of threads, group g adding the slabs g, g+4, ...; the
+// four partial sums are then added in group order through LDS, so the result is the same from run
+// to run.  Output fp32, or bf16 for the rank-r intermediates that feed the next product.
+template <bool TO_BF16>
 __global__ __launch_bounds__(256) void sum_slabs_kernel(const float* __restrict__ slabs, int64_t slab, int nslab,
-                                                        float* __restrict__ out, int64_t n4)
+                                                        void* __restrict__ out, int64_t n4)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+    __shared__ f32x4 red[3][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int64_t base = (int64_t)blockIdx.x * 64; base < n4; base += (int64_t)gridDim.x * 64) {
+        const int64_t i = base + lane;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+        if (i < n4)
+            for (int s = g; s < nslab; s += 4) a += reinterpret_cast<const f32x4*>(slabs + (int64_t)s * slab)[i];
+        if (g > 0) red[g - 1][lane] = a;
+        __syncthreads();
+        if (g == 0 && i < n4) {
+            a = ((a + red[0][lane]) + red[1][lane]) + red[2][lane];
+            if constexpr (TO_BF16) {
+                u32x2_t o;
+                o.x = bf16_pack(a.x, a.y);
+                o.y = bf16_pack(a.z, a.w);
+                reinterpret_cast<u32x2_t*>(out)[i] = o;
+            } else {
+                reinterpret_cast<f32x4*>(out)[i] = a;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Large outputs with few slabs: one thread per float4 output adds its slabs in order.
+__global__ __launch_bounds__(256) void sum_slabs_wide_kernel(const float* __restrict__ slabs, int64_t slab, int nslab,
+                                                             float* __restrict__ out, int64_t n4)
 {
     typedef __attribute__((ext_vector_type(4))) float f32x4;
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -497,10 +531,19 @@ __global__ __launch_bounds__(256) void sum_slabs_kernel(const float* __restrict_
 }
 
 // n = elements per slab, a multiple of 4 (every output here has a leading dimension that is one).
-hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, float* out, hipStream_t s)
+hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out, bool to_bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(sum_slabs_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, slabs, n, nslab, out, n / 4);
+    const int64_t n4 = n / 4;
+    if (!to_bf16 && nslab <= 8 && n4 >= 65536) {
+        // enough independent outputs to fill the chip with one thread each
+        hipLaunchKernelGGL(sum_slabs_wide_kernel, dim3(grid_for(n4)), dim3(256), 0, s, slabs, n, nslab, (float*)out, n4);
+        return hipGetLastError();
+    }
+    int64_t blocks = (n4 + 63) / 64;
+    if (blocks > 16384) blocks = 16384;
+    if (to_bf16) hipLaunchKernelGGL(sum_slabs_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
+    else hipLaunchKernelGGL(sum_slabs_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
     return hipGetLastError();
 }
 
