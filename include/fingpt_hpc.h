@@ -49,6 +49,10 @@ enum { FHPC_F32 = 0, FHPC_BF16 = 1 };
  *                           of one output channel); block must be 64. */
 enum { FHPC_Q_INT8_PER_CHANNEL = 8, FHPC_Q_INT4_BLOCK = 4 };
 
+/* blend entry points only: the frozen weight is not quantised: W bf16 [K][N] row-major in the
+ * `Wq` argument, `scales` and `block` ignored (scales may be NULL) */
+enum { FHPC_W_BF16 = 16 };
+
 enum {
     FHPC_OK = 0,
     FHPC_ERR_NULL = 1,        /* a required pointer is NULL */
@@ -109,7 +113,8 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
  *   Y = alpha * X * deq(Wq, scales) + (1 - alpha) * (X * A) * B
  * Arguments, layouts, workspace (FHPC_OP_QLINEAR_FWD / _BWD sizes) and error behaviour are those of
  * qlinear_lowrank_fwd / _bwd with `alpha` in place of `scaling`; alpha outside [0, 1] (or NaN)
- * returns FHPC_ERR_SHAPE.  alpha = 0 runs the factorised layer alone and never reads Wq. */
+ * returns FHPC_ERR_SHAPE.  alpha = 0 runs the factorised layer alone and never reads Wq.
+ * qscheme may also be FHPC_W_BF16: the pretrained weight kept in bf16, W[K,N] row-major. */
 int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
                       const void* A, const void* B, float alpha, void* Y, void* H_out,
                       int64_t M, int64_t K, int64_t r, int64_t N,

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
 
 FHPC_F32, FHPC_BF16 = 0, 1
 FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
+FHPC_W_BF16 = 16          # blend entry points only: dense bf16 W[K,N] in place of Wq, scales None
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD = 0, 1, 2, 3
 
 EXPORTS = [
@@ -215,8 +216,12 @@ def _q_shapes(Wq, scales, qscheme, K, N, block):
         _check(Wq, "Wq", (N, K), torch.int8); _check(scales, "scales", (N,), torch.float16)
     elif qscheme == FHPC_Q_INT4_BLOCK:
         _check(Wq, "Wq", (N, K // 2), torch.uint8); _check(scales, "scales", (N, K // block), torch.float16)
+    elif qscheme == FHPC_W_BF16:
+        _check(Wq, "W", (K, N), torch.bfloat16)
+        if scales is not None:
+            raise ValueError("a dense bf16 weight has no scales")
     else:
-        raise ValueError("qscheme must be 8 or 4")
+        raise ValueError("qscheme must be 8, 4 or FHPC_W_BF16")
 
 
 def qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, scaling, block=64, Y=None, H_out=None,

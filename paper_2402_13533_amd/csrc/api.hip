@@ -115,7 +115,7 @@ int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred)
     return sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0;
 }
 
-Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, bool quantised = true)
 {
     Scratch s;
     if (dtype == FHPC_F32) {
@@ -124,7 +124,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         if (op == FHPC_OP_LOWRANK_BWD) s.dH = c.take(M * r * 4);
         return s;
     }
-    if (op == FHPC_OP_QLINEAR_FWD && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
+    if (op == FHPC_OP_QLINEAR_FWD && quantised && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
         // a handful of tokens: the weight-streaming kernels need only their own slabs
         const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
         s.sk_part = static_cast<float*>(c.take(p.part_bytes));
@@ -296,10 +296,11 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
     return FHPC_OK;
 }
 
-int check_workspace(int op, void* ws, size_t ws_bytes, int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+int check_workspace(int op, void* ws, size_t ws_bytes, int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
+                    bool quantised = true)
 {
     Carver dry(nullptr);
-    carve(dry, op, M, K, r, N, dtype);
+    carve(dry, op, M, K, r, N, dtype, quantised);
     if (dry.used == 0) return FHPC_OK;
     if (!ws || ws_bytes < dry.used) return FHPC_ERR_WORKSPACE;
     if (!aligned(ws, 256)) return FHPC_ERR_ALIGN;
@@ -354,12 +355,11 @@ extern "C" {
 
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme)
 {
-    (void)qscheme;
     if (op < FHPC_OP_LOWRANK_FWD || op > FHPC_OP_QLINEAR_BWD) return 0;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return 0;
     if (check_common(M, K, r, N) != FHPC_OK) return 0;
     Carver dry(nullptr);
-    carve(dry, op, M, K, r, N, dtype);
+    carve(dry, op, M, K, r, N, dtype, qscheme != FHPC_W_BF16);
     return dry.used;
 }
 
@@ -442,19 +442,21 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
                             int64_t M, int64_t K, int64_t r, int64_t N,
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!X || !Wq || !scales || !A || !B || !Y) return FHPC_ERR_NULL;
-    int rc = check_q(qscheme, block, K);
+    const bool dense = (qscheme == FHPC_W_BF16);          // blend layer with an unquantised frozen weight
+    if (!X || !Wq || (!scales && !dense) || !A || !B || !Y) return FHPC_ERR_NULL;
+    int rc = dense ? FHPC_OK : check_q(qscheme, block, K);
     if (rc) return rc;
     rc = check_common(M, K, r, N);
     if (rc) return rc;
+    if (dense && K * N * 2 >= kMaxBytes) return FHPC_ERR_UNSUPPORTED;
     if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
         !aligned(Y, 16) || !aligned(H_out, 16))
         return FHPC_ERR_ALIGN;
-    rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16);
+    rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
-    Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16);
+    Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, !dense);
     if (s.sk_part) {
         const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
         FHPC_HIP(launch_qskinny_fwd(X, Wq, scales, qscheme, A, B, base_scale, scaling, Y, H_out, M, K, r, N, p, s.sk_part, s.sk_hpart, st));
@@ -474,13 +476,13 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
         // the kernel forms alpha * (mid_scale * H B + X deq(W))
         GemmArgs g = {};
         g.a = operand(X, K);
-        g.b = operand(Wq, K, scales, K / 64);
+        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: W[K][N], element (n, k) at k*N + n
         g.a2 = operand(H, rp);
         g.b2 = operand(f.B, N);
         g.c = Y; g.ldc = N;
         g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
         g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(K, 64);
-        const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
+        const int b_mode = dense ? OP_XC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
         FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_XC, OUT_BF16, pick_tile(M, N, false), g, st));
     }
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
@@ -492,6 +494,7 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    if (qscheme == FHPC_W_BF16) return FHPC_ERR_DTYPE;      // the finetuning layer's weight is quantised
     return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, Y, H_out, M, K, r, N,
                             workspace, workspace_bytes, hip_stream);
 }
@@ -512,11 +515,13 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
                             int64_t M, int64_t K, int64_t r, int64_t N,
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!X || !Wq || !scales || !A || !B || !dY) return FHPC_ERR_NULL;
-    int rc = check_q(qscheme, block, K);
+    const bool dense = (qscheme == FHPC_W_BF16);
+    if (!X || !Wq || (!scales && !dense) || !A || !B || !dY) return FHPC_ERR_NULL;
+    int rc = dense ? FHPC_OK : check_q(qscheme, block, K);
     if (rc) return rc;
     rc = check_common(M, K, r, N);
     if (rc) return rc;
+    if (dense && K * N * 2 >= kMaxBytes) return FHPC_ERR_UNSUPPORTED;
     if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
         !aligned(dY, 16) || !aligned(H_saved, 16) || !aligned(dX, 16) || !aligned(dA, 16) || !aligned(dB, 16))
         return FHPC_ERR_ALIGN;
@@ -549,13 +554,13 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};
         g.a = operand(dY, N);
-        g.b = operand(Wq, K, scales, K / 64);
+        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: element (k, n) at k*N + n
         g.a2 = operand(s.dH, rp);
         g.b2 = operand(f.A, rp);
         g.c = dX; g.ldc = K;
         g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
         g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(N, 64);
-        const int b_mode = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
+        const int b_mode = dense ? OP_KC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
         FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_KC, OUT_BF16, pick_tile(M, K, false), g, st));
     }
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, st);
@@ -567,6 +572,7 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    if (qscheme == FHPC_W_BF16) return FHPC_ERR_DTYPE;
     return qlinear_bwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, dY, H_saved, dX, dA, dB, M, K, r, N,
                             workspace, workspace_bytes, hip_stream);
 }

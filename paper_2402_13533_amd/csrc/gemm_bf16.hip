@@ -838,6 +838,9 @@ hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, i
     FHPC_CASE(OP_KC, OP_Q4_KC, OP_XC, OUT_BF16)
     FHPC_CASE(OP_KC, OP_Q8_XC, OP_KC, OUT_BF16)         // dX = dY deq(W)^T + s dH A^T
     FHPC_CASE(OP_KC, OP_Q4_XC, OP_KC, OUT_BF16)
+    // blend layer with a dense bf16 frozen weight W[K][N]
+    FHPC_CASE(OP_KC, OP_XC, OP_XC, OUT_BF16)            // Y  = alpha X W + (1 - alpha) H B
+    FHPC_CASE(OP_KC, OP_KC, OP_KC, OUT_BF16)            // dX = alpha dY W^T + (1 - alpha) dH A^T
     // rank-r (skinny) products of the finetuning layer
     FHPC_SKINNY(OP_KC, OP_XC, OUT_F32)                  // H  = X A      (split over K)
     FHPC_SKINNY(OP_KC, OP_KC, OUT_F32)                  // dH = dY B^T   (split over N)

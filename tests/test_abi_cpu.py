@@ -81,6 +81,8 @@ def test_validation_precedes_launch():
     assert bl(p, p, p, 8, 64, p, p, C.c_float(1.5), p, nul, 16, 64, 8, 64, ws, big, nul) == 2      # alpha > 1
     assert bl(p, p, p, 8, 64, p, p, C.c_float(float("nan")), p, nul, 16, 64, 8, 64, ws, big, nul) == 2
     assert bl(p, p, p, 8, 64, p, p, C.c_float(0.5), p, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5
+    assert bl(p, p, nul, 16, 0, p, p, C.c_float(0.5), p, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5  # dense W: no scales needed
+    assert q(p, p, nul, 16, 0, p, p, C.c_float(1), p, nul, 16, 64, 8, 64, ws, big, nul) == 3              # not for the finetuning layer
 
 
 def test_binding_refuses_cpu_tensors():

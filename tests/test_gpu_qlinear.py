@@ -258,3 +258,28 @@ def test_blend_layer_few_tokens_and_alpha_range():
     for bad in (-0.1, 1.5, float("nan")):
         with pytest.raises(fhpc.FhpcError):
             fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), bad)
+
+
+@pytest.mark.parametrize("M", [300, 5])
+def test_blend_layer_dense_weight(M):
+    """The blend layer with the pretrained weight kept in bf16 (no quantisation): W[K,N] row-major in
+    place of the packed codes.  M = 5 checks that the few-token weight-streaming path is not taken
+    for an unquantised weight."""
+    fhpc = _fhpc()
+    K, r, N, alpha = 512, 24, 264, 0.6
+    _, X, A, _, dY = qlinear_inputs(8, M, K, r, N, 95)
+    B = Bf16.normal(8124, (r, N), r ** -0.5)
+    W = Bf16.normal(8125, (K, N), K ** -0.5)
+    Xd, Wd_, Ad, Bd, dYd = X.cuda(), W.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y, H = fhpc.qlinear_blend_fwd(Xd, Wd_, None, fhpc.FHPC_W_BF16, Ad, Bd, alpha, save_H=True)
+    dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, Wd_, None, fhpc.FHPC_W_BF16, Ad, Bd, alpha, dYd, H_saved=H)
+    Yr, Hr = oracle.blend_fwd(X.f64, W.f64, A.f64, B.f64, alpha)
+    dXr, dAr, dBr = oracle.blend_bwd(X.f64, W.f64, A.f64, B.f64, alpha, dY.f64)
+    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
+            "dX": oracle.rel_fro(from_device(dX), dXr), "dA": oracle.rel_fro(from_device(dA), dAr),
+            "dB": oracle.rel_fro(from_device(dB), dBr)}
+    print("blend dense M=%d" % M, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+    with pytest.raises(fhpc.FhpcError):          # the finetuning layer itself takes quantised weights only
+        fhpc.qlinear_lowrank_fwd(Xd, Wd_, None, fhpc.FHPC_W_BF16, Ad, Bd, 2.0)
