@@ -42,6 +42,9 @@ def parse_args():
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
                          "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
     ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (removes the host's launch cost; "
+                         "meant for the few-token runs, where a step is a handful of microsecond-scale kernels)")
     ap.add_argument("--recompute", action="store_true", help="backward recomputes H instead of reading the saved copy")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after the steps, launch a plain elementwise kernel that reads 256 MiB and writes 256 MiB three "
@@ -273,10 +276,20 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    timed = step
+    if args.graph:
+        # the library only enqueues kernels on the current stream (no allocation, no memset), so a
+        # step can be captured as it is
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        timed = graph.replay
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        step()
+        timed()
     e1.record()
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
@@ -319,7 +332,7 @@ def main():
         "metric": "fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": desc, "saved_H": not args.recompute},
+        "config": {"workload": desc, "saved_H": not args.recompute, "hip_graph": bool(args.graph)},
         "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "io_gbs": io_bytes / (ms_per_step * 1e-3) / 1e9, "frac_hbm_peak_on_io_bytes": io_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roofline, "kernels": kernels,

@@ -333,23 +333,47 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
             for (int sp = 0; sp < splits; sp++) s += part[((int64_t)sp * M + m) * N + n];
         base[t] = s;
     }
-    for (int o = threadIdx.x; o < M * r; o += NT) {
-        float sv[16];                                       // independent chains: sixteen loads in flight
-#pragma unroll
-        for (int q = 0; q < 16; q++) sv[q] = 0.f;
-        for (int kc = 0; kc < kchunks; kc += 16) {
-#pragma unroll
-            for (int q = 0; q < 16; q++)
-                if (kc + q < kchunks) sv[q] += hpart[(int64_t)(kc + q) * M * r + o];
+    // H = sum of the chunk partial sums, all 256 threads sharing the loads: thread (o, g) adds the
+    // chunks g, g + G, ... of output o, then the G group sums are added in group order (the same
+    // order every run)
+    __shared__ float Hg[NT];
+    const int outs = M * r;
+    if (outs <= NT / 2) {
+        const int G = NT / outs;                            // groups of chunks
+        const int o = threadIdx.x % outs, g = threadIdx.x / outs;
+        float s = 0.f;
+        if (g < G)
+            for (int kc = g; kc < kchunks; kc += G) s += hpart[(int64_t)kc * outs + o];
+        Hg[threadIdx.x] = s;
+        __syncthreads();
+        if (threadIdx.x < outs) {
+            float t = 0.f;
+            for (int q = 0; q < G; q++) t += Hg[q * outs + threadIdx.x];
+            Hs[threadIdx.x] = t;
+            if (H_out && blockIdx.x == 0) {
+                const __bf16 hb = (__bf16)t;
+                H_out[threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
+            }
         }
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    } else {
+        for (int o = threadIdx.x; o < outs; o += NT) {
+            float sv[8];                                    // eight loads in flight per trip
 #pragma unroll
-        for (int q = 0; q < 16; q += 4) { s0 += sv[q]; s1 += sv[q + 1]; s2 += sv[q + 2]; s3 += sv[q + 3]; }
-        const float s = (s0 + s1) + (s2 + s3);
-        Hs[o] = s;
-        if (H_out && blockIdx.x == 0) {
-            const __bf16 hb = (__bf16)s;
-            H_out[o] = __builtin_bit_cast(uint16_t, hb);
+            for (int q = 0; q < 8; q++) sv[q] = 0.f;
+            for (int kc = 0; kc < kchunks; kc += 8) {
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    const int c = (kc + q < kchunks) ? kc + q : kc;     // (a repeated, in-range chunk, weighted 0)
+                    const float v = hpart[(int64_t)c * outs + o];
+                    sv[q] += (kc + q < kchunks) ? v : 0.f;
+                }
+            }
+            const float t = ((sv[0] + sv[1]) + (sv[2] + sv[3])) + ((sv[4] + sv[5]) + (sv[6] + sv[7]));
+            Hs[o] = t;
+            if (H_out && blockIdx.x == 0) {
+                const __bf16 hb = (__bf16)t;
+                H_out[o] = __builtin_bit_cast(uint16_t, hb);
+            }
         }
     }
     __syncthreads();

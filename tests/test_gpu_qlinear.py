@@ -283,3 +283,29 @@ def test_blend_layer_dense_weight(M):
         assert v <= TOL_BF16, (k, v)
     with pytest.raises(fhpc.FhpcError):          # the finetuning layer itself takes quantised weights only
         fhpc.qlinear_lowrank_fwd(Xd, Wd_, None, fhpc.FHPC_W_BF16, Ad, Bd, 2.0)
+
+
+def test_few_token_forward_in_a_hip_graph():
+    """The few-token forward enqueues kernels only, so a caller can capture it in a HIP graph: three
+    replays, with eager work and synchronisations in between, must each reproduce the eager result."""
+    import torch
+    fhpc = _fhpc()
+    M, K, r, N = 8, 2048, 16, 328
+    W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 97)
+    Wq, sc = _quantize_host(W, 4)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd = X.cuda(), A.cuda(), B.cuda()
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    eager = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, 4, Ad, Bd, 2.0).clone()      # also sizes the cached workspace
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, 4, Ad, Bd, 2.0, Y=Y)
+    for rep in range(3):
+        Y.zero_()
+        other = fhpc.qlinear_lowrank_fwd(Xd * 0.5, Wq_d, sc_d, 4, Ad, Bd, 2.0)    # eager work on the same workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, eager), rep
+        assert not torch.equal(other, eager)
