@@ -214,6 +214,24 @@ def blend_bwd(X, W, A, B, alpha: float, dY):
     return dX, dA, dB
 
 
+# ---------------------------------------------------------------- merged weight
+
+def merge(W, A, B, s: float = 1.0):
+    """W' = W + s A B (W[K,N] or None, A[K,r], B[r,N]).  Returns W'[K,N]."""
+    A, B = _d(A), _d(B)
+    K, r = A.shape
+    N = B.shape[1]
+    assert B.shape[0] == r
+    Wp = np.empty((K, N))
+    if W is None:
+        lib().orc_merge(None, _p(A), _p(B), C.c_double(s), _p(Wp), _i(K), _i(r), _i(N))
+    else:
+        W = _d(W)
+        assert W.shape == (K, N)
+        lib().orc_merge(_p(W), _p(A), _p(B), C.c_double(s), _p(Wp), _i(K), _i(r), _i(N))
+    return Wp
+
+
 # ---------------------------------------------------------------- SiLU gate
 
 def swiglu_fwd(G, U):

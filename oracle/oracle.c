@@ -358,6 +358,26 @@ void orc_blend_bwd(const double *X, const double *W,
 }
 
 /* ------------------------------------------------------------------ */
+/* Adapted weight materialised for inference, Sec. 5.1 (eq.             */
+/* new_linear_layer: W' = W + Delta W, Delta W the product of the pair) */
+/* ------------------------------------------------------------------ */
+
+/* Row form: Wp[K,N] = W[K,N] + s * A[K,r] B[r,N]; the paper's case is s = 1.
+ * W may be NULL (then Wp = s A B: the dense weight a factor pair stands for). */
+void orc_merge(const double *W, const double *A, const double *B, double s,
+               double *Wp, int64_t K, int64_t r, int64_t N)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < K; k++) {
+        for (int64_t n = 0; n < N; n++) {
+            double d = 0.0;
+            for (int64_t j = 0; j < r; j++) d += A[k * r + j] * B[j * N + n];
+            Wp[k * N + n] = (W ? W[k * N + n] : 0.0) + s * d;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* SiLU-gated product between the FFN's linears, Sec. 3.1 eq. FFN       */
 /* ------------------------------------------------------------------ */
 

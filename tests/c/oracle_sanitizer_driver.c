@@ -19,6 +19,7 @@ void orc_qlinear_lowrank_fwd(const double *, const double *, const double *, con
 void orc_qlinear_lowrank_bwd(const double *, const double *, const double *, const double *, double, const double *, double *, double *, double *, int64_t, int64_t, int64_t, int64_t);
 void orc_blend_fwd(const double *, const double *, const double *, const double *, double, double *, double *, int64_t, int64_t, int64_t, int64_t);
 void orc_blend_bwd(const double *, const double *, const double *, const double *, double, const double *, double *, double *, double *, int64_t, int64_t, int64_t, int64_t);
+void orc_merge(const double *, const double *, const double *, double, double *, int64_t, int64_t, int64_t);
 void orc_swiglu_fwd(const double *, const double *, double *, int64_t);
 void orc_swiglu_bwd(const double *, const double *, const double *, double *, double *, int64_t);
 int orc_num_threads(void);
@@ -62,6 +63,11 @@ int main(void)
     orc_blend_fwd(X, Wd, A, B, 0.3, H, Y, M, K, r, N);
     orc_blend_bwd(X, Wd, A, B, 0.3, dY, dX, dA, dB, M, K, r, N);
     acc += sum(Y, M * N) + sum(dA, K * r);
+    double *Wp = dvec(K * N);
+    orc_merge(Wd, A, B, 0.5, Wp, K, r, N);
+    acc += sum(Wp, K * N);
+    orc_merge(NULL, A, B, 1.0, Wp, K, r, N);
+    acc += sum(Wp, K * N);
 
     uint8_t bytes[256];
     int8_t codes[512];
@@ -79,7 +85,7 @@ int main(void)
     acc += orc_f32_to_f16(65504.0f) + orc_f32_to_f16(1e-8f) + orc_f32_to_f16(-0.0f);
 
     free(X); free(A); free(B); free(dY); free(H); free(Y); free(dX); free(dA); free(dB);
-    free(W); free(q8); free(s8); free(q4); free(s4); free(Wd);
+    free(W); free(q8); free(s8); free(q4); free(s4); free(Wd); free(Wp);
     free(G); free(U); free(dZ); free(Z); free(dG); free(dU);
     printf("threads %d checksum %.6f\n", orc_num_threads(), acc);
     return 0;
