@@ -49,7 +49,7 @@ enum { FHPC_F32 = 0, FHPC_BF16 = 1 };
  *                           of one output channel); block must be 64. */
 enum { FHPC_Q_INT8_PER_CHANNEL = 8, FHPC_Q_INT4_BLOCK = 4 };
 
-/* blend entry points only: the frozen weight is not quantised: W bf16 [K][N] row-major in the
+/* blend and merge entry points only: the frozen weight is not quantised: W bf16 [K][N] row-major in the
  * `Wq` argument, `scales` and `block` ignored (scales may be NULL) */
 enum { FHPC_W_BF16 = 16 };
 
@@ -65,7 +65,8 @@ enum {
 };
 
 /* which entry point a workspace is sized for */
-enum { FHPC_OP_LOWRANK_FWD = 0, FHPC_OP_LOWRANK_BWD = 1, FHPC_OP_QLINEAR_FWD = 2, FHPC_OP_QLINEAR_BWD = 3 };
+enum { FHPC_OP_LOWRANK_FWD = 0, FHPC_OP_LOWRANK_BWD = 1, FHPC_OP_QLINEAR_FWD = 2, FHPC_OP_QLINEAR_BWD = 3,
+       FHPC_OP_MERGE = 4 };
 
 /* Factorised linear layer, forward (Sec. 3.2 eq. low_rank_layer; Sec. 4.1 "Method 1"):
  *   Y[M,N] = (X[M,K] * A[K,r]) * B[r,N].
@@ -129,7 +130,8 @@ int qlinear_blend_bwd(const void* X, const void* Wq, const void* scales, int qsc
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace the entry point `op` (FHPC_OP_*) needs for these sizes.
- * Host-only; returns 0 for invalid arguments.  qscheme is ignored for op 0/1. */
+ * Host-only; returns 0 for invalid arguments (and for FHPC_OP_MERGE when it needs none).  qscheme is
+ * ignored for op 0/1/4; M and dtype are ignored for op 4. */
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme);
 
 /* SiLU-gated product between the FFN's linears (Sec. 3.1 eq. FFN):
@@ -152,6 +154,20 @@ int fhpc_add(const void* a, const void* b, void* out, int64_t n_elems, int dtype
  * bit-exact functions of W. */
 int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void* scales_out,
                      int64_t K, int64_t N, void* hip_stream);
+
+/* Adapted weight materialised once for inference (Sec. 5.1, eq. new_linear_layer: W' = W + Delta W,
+ * Delta W the product of the factor pair):
+ *   W_out[K,N] = deq(W)[K,N] + scaling * A[K,r] * B[r,N]          (the paper's case: scaling = 1)
+ * W is the frozen weight in the storage `qscheme` names: FHPC_W_BF16 (bf16 [K][N], scales ignored) or one
+ * of the quantised layouts above with its fp16 `scales`.  W == NULL means no base weight: W_out is then
+ * the dense weight the factor pair stands for.  A, B are bf16; W_out is row-major [K][N] of `out_dtype`
+ * (FHPC_F32 or FHPC_BF16) and must not alias W.  The product is accumulated in fp32, the base weight
+ * (exact in fp32) is added in fp32 and the sum is rounded once.  To keep the merged weight quantised,
+ * write fp32 and pass it to qweight_quantize.  Workspace: FHPC_OP_MERGE (zero bytes, and workspace may
+ * be NULL, when r is a multiple of 8). */
+int lowrank_merge(const void* W, const void* scales, int qscheme, int block, const void* A, const void* B,
+                  float scaling, void* W_out, int out_dtype, int64_t K, int64_t r, int64_t N,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Integer codes of a stored weight, q_out int8 [N][K] (scheme 8: a copy; scheme 4:
  * sign-extended nibbles, including the code -8).  Bit-exact. */

@@ -16,11 +16,11 @@ LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
 
 FHPC_F32, FHPC_BF16 = 0, 1
 FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
-FHPC_W_BF16 = 16          # blend entry points only: dense bf16 W[K,N] in place of Wq, scales None
-FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD = 0, 1, 2, 3
+FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N] in place of Wq, scales None
+FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd",
+    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
@@ -53,6 +53,7 @@ def load_library():
                                         i64, i64, i64, i64, vp, sz, vp]
     lib.qlinear_blend_fwd.argtypes = lib.qlinear_lowrank_fwd.argtypes
     lib.qlinear_blend_bwd.argtypes = lib.qlinear_lowrank_bwd.argtypes
+    lib.lowrank_merge.argtypes = [vp, vp, i32, i32, vp, vp, f32, vp, i32, i64, i64, i64, vp, sz, vp]
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
     lib.fhpc_workspace_bytes.restype = sz
     lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -345,6 +346,32 @@ def qweight_quantize(W, qscheme, block=64):
     if rc:
         raise FhpcError(rc, "qweight_quantize")
     return Wq, sc
+
+
+def lowrank_merge(W, scales, qscheme, A, B, scaling=1.0, block=64, out_dtype=None, W_out=None, workspace=None):
+    """W' [K,N] = deq(W) + scaling A B.  W: None, a bf16 [K,N] tensor (qscheme FHPC_W_BF16) or a
+    quantised weight with its scales; out_dtype torch.float32 or torch.bfloat16 (default)."""
+    torch = _torch()
+    lib = load_library()
+    K, r = A.shape
+    N = B.shape[1]
+    bf = torch.bfloat16
+    _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+    if W is not None:
+        _q_shapes(W, scales, qscheme, K, N, block)
+    if W_out is None:
+        W_out = torch.empty((K, N), dtype=out_dtype or bf, device=A.device)
+    _check(W_out, "W_out", (K, N))
+    need = workspace_bytes(FHPC_OP_MERGE, 1, K, r, N)
+    ws = None
+    if need:
+        ws = workspace if workspace is not None else get_workspace(need, A.device)
+    wsz = C.c_size_t(0 if ws is None else ws.numel() * ws.element_size())
+    rc = lib.lowrank_merge(_ptr(W), _ptr(scales), qscheme, block, _ptr(A), _ptr(B), float(scaling), _ptr(W_out),
+                           _dtype_code(W_out), K, r, N, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_merge")
+    return W_out
 
 
 def qweight_unpack(Wq, qscheme):

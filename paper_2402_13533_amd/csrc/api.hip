@@ -4,6 +4,7 @@
 #include "../../include/fingpt_hpc.h"
 #include "gemm_bf16.h"
 #include "kernels_misc.h"
+#include "merge.h"
 #include "qskinny.h"
 
 using namespace fhpc;
@@ -355,6 +356,11 @@ extern "C" {
 
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme)
 {
+    if (op == FHPC_OP_MERGE) {
+        // a zero-padded copy of A when the rank is not a multiple of 8; M, dtype and qscheme are ignored
+        if (check_common(1, K, r, N) != FHPC_OK) return 0;
+        return (r % 8) ? (size_t)round_up(K * rank_pad(r) * 2, 256) : 0;
+    }
     if (op < FHPC_OP_LOWRANK_FWD || op > FHPC_OP_QLINEAR_BWD) return 0;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return 0;
     if (check_common(M, K, r, N) != FHPC_OK) return 0;
@@ -641,6 +647,43 @@ int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void*
     if (!aligned(W, 16) || !aligned(Wq_out, 16) || !aligned(scales_out, 2)) return FHPC_ERR_ALIGN;
     FHPC_HIP(launch_quantize(W, qscheme, block, Wq_out, scales_out, K, N, static_cast<float*>(Wq_out),
                              static_cast<hipStream_t>(hip_stream)));
+    return FHPC_OK;
+}
+
+int lowrank_merge(const void* W, const void* scales, int qscheme, int block, const void* A, const void* B,
+                  float scaling, void* W_out, int out_dtype, int64_t K, int64_t r, int64_t N,
+                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!A || !B || !W_out) return FHPC_ERR_NULL;
+    if (out_dtype != FHPC_F32 && out_dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+    int rc = check_common(1, K, r, N);
+    if (rc) return rc;
+    int w_kind = 0;
+    if (W) {
+        if (qscheme == FHPC_W_BF16) {
+            w_kind = 1;
+        } else {
+            rc = check_q(qscheme, block, K);
+            if (rc) return rc;
+            if (!scales) return FHPC_ERR_NULL;
+            if (!aligned(scales, 2)) return FHPC_ERR_ALIGN;
+            w_kind = (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+        }
+        if (!aligned(W, 16)) return FHPC_ERR_ALIGN;
+    }
+    if (K * N * 4 >= kMaxBytes) return FHPC_ERR_UNSUPPORTED;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(W_out, 16)) return FHPC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t rp = rank_pad(r);
+    const void* Ap = A;
+    if (rp != r) {
+        const size_t need = (size_t)round_up(K * rp * 2, 256);
+        if (!workspace || workspace_bytes < need) return FHPC_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+        FHPC_HIP(launch_pad2d_u16(A, r, K, r, workspace, rp, K, st));
+        Ap = workspace;
+    }
+    FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
     return FHPC_OK;
 }
 

@@ -83,6 +83,20 @@ def test_validation_precedes_launch():
     assert bl(p, p, p, 8, 64, p, p, C.c_float(0.5), p, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5
     assert bl(p, p, nul, 16, 0, p, p, C.c_float(0.5), p, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5  # dense W: no scales needed
     assert q(p, p, nul, 16, 0, p, p, C.c_float(1), p, nul, 16, 64, 8, 64, ws, big, nul) == 3              # not for the finetuning layer
+    mg = lib.lowrank_merge
+    one = C.c_float(1)
+    assert mg(p, p, 8, 64, nul, p, one, p, 1, 64, 8, 64, nul, C.c_size_t(0), nul) == 1            # NULL A
+    assert mg(p, nul, 8, 64, p, p, one, p, 1, 64, 8, 64, nul, C.c_size_t(0), nul) == 1            # quantised W without scales
+    assert mg(p, p, 8, 64, p, p, one, p, 7, 64, 8, 64, nul, C.c_size_t(0), nul) == 3              # out dtype
+    assert mg(p, p, 5, 64, p, p, one, p, 1, 64, 8, 64, nul, C.c_size_t(0), nul) == 3              # scheme
+    assert mg(p, p, 4, 64, p, p, one, p, 1, 72, 8, 64, nul, C.c_size_t(0), nul) == 2              # K % 64 (4-bit)
+    assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 8, 60, nul, C.c_size_t(0), nul) == 2              # N % 8
+    assert mg(p, p, 8, 64, p, p, one, odd, 1, 64, 8, 64, nul, C.c_size_t(0), nul) == 4            # alignment
+    assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, nul, C.c_size_t(0), nul) == 5              # odd rank needs a workspace
+    assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, ws, C.c_size_t(64), nul) == 5
+    assert mg(p, p, 8, 64, p, p, one, p, 1, 1 << 16, 8, 1 << 16, nul, C.c_size_t(0), nul) == 6    # >= 2 GiB
+    assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 8, 64) == 0
+    assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 64 * 8 * 2
 
 
 def test_binding_refuses_cpu_tensors():
