@@ -50,11 +50,16 @@ struct Scratch {
     float* dA_t = nullptr;  // fp32 [K][rp]
     float* dB_t = nullptr;  // fp32 [rp][N]
     float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
+    float* Yf = nullptr;    // fp32 [M][N]    factorised layer, few tokens: unsplit second product
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
+
+// The factorised layer's forward for at most one 32-row tile of tokens is bound by reading A and
+// B once: its products are then spread over the chip by splitting their reductions.
+bool few_tokens(int64_t M) { return M <= 32; }
 
 int64_t tile_count(int tile, int64_t M, int64_t N)
 {
@@ -139,6 +144,14 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         s.B_p = c.take(rp * N * 2);
     }
     s.H = c.take(M * rp * 2);
+    if (op == FHPC_OP_LOWRANK_FWD && few_tokens(M)) {
+        // both products run as split reductions on the 32-row tile
+        s.Hf = static_cast<float*>(c.take(M * rp * 4));
+        s.Yf = static_cast<float*>(c.take(M * N * 4));
+        const int64_t p1 = split_bytes(M, rp, rp, K), p2 = split_bytes(M, N, N, rp);
+        s.part = static_cast<float*>(c.take(p1 > p2 ? p1 : p2));
+        return s;
+    }
     if (bwd) s.dH = c.take(M * rp * 2);
     if (rp <= 32) s.Hf = static_cast<float*>(c.take(M * rp * 4));
     if (bwd && rp != r) {
@@ -391,8 +404,17 @@ int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, voi
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
-    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
-    FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st));
+    if (few_tokens(M)) {
+        bool done = false;
+        FHPC_HIP(gemm_split_f32(OP_KC, OP_XC, operand(X, K), operand(f.A, rp), s.Hf, rp, M, rp, K, 1.f, s.part, st, H, &done));
+        if (!done) FHPC_HIP(launch_compact_f32(s.Hf, rp, H, rp, M, rp, 1.f, true, st));
+        done = false;
+        FHPC_HIP(gemm_split_f32(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), s.Yf, N, M, N, rp, 1.f, s.part, st, Y, &done));
+        if (!done) FHPC_HIP(launch_compact_f32(s.Yf, N, Y, N, M, N, 1.f, true, st));
+    } else {
+        FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st));
+    }
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
     return FHPC_OK;
 }

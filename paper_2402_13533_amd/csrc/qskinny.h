@@ -13,7 +13,7 @@ struct QskinnyPlan {
     int64_t hpart_bytes;   // kchunks * M * r * 4
 };
 
-// M <= 16 tokens, r <= 64, K a multiple of 512, scheme 4 (block 64) or 8.
+// M <= 64 tokens, r <= 64, K a multiple of 512, scheme 4 (block 64) or 8.
 bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu);
 

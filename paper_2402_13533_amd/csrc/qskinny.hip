@@ -1,5 +1,5 @@
 // Weight-streaming forward of the quantised finetuning layer for a handful of tokens
-// (M <= 16):  Y = base_scale * X * deq(Wq, scales) + scaling * (X * A) * B.
+// (M <= 64, in tiles of 16):  Y = base_scale * X * deq(Wq, scales) + scaling * (X * A) * B.
 //
 // At this size the layer is bound by reading the packed weight once from HBM, so the kernel
 // is built around that stream: every lane loads 16-byte pieces of its own weight row straight
@@ -102,12 +102,13 @@ __device__ __forceinline__ uint32_t x_off(int tok, int chunk) { return (uint32_t
 // launch of its own.  The chunk of X ([M][128]) and of A ([128][r]) is copied to LDS with
 // coalesced loads; thread (m, j16) then forms the sums for the columns j = j16, j16 + 16, ...
 constexpr int H_XLD = HCHUNK + 8;                    // padded token row (bank spread)
-constexpr int H_LDS_BYTES = (TOK * H_XLD + HCHUNK * 64) * 2;
+constexpr int h_lds_bytes(int toks) { return (toks * H_XLD + HCHUNK * 64) * 2; }
+template <int TOKS>
 __device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const uint16_t* __restrict__ X,
                                            const uint16_t* __restrict__ A, float* __restrict__ hpart, int M, int K, int r)
 {
     uint16_t* Xs = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* As = Xs + TOK * H_XLD;
+    uint16_t* As = Xs + TOKS * H_XLD;
     const int k0 = kc * HCHUNK;
     const int kn = (K - k0 < HCHUNK) ? K - k0 : HCHUNK;          // K is a multiple of 8
     for (int c = threadIdx.x; c < M * (HCHUNK / 8); c += NT) {
@@ -126,19 +127,21 @@ __device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const ui
         for (int c = threadIdx.x; c < an; c += NT) As[c] = A[abase + c];
     }
     __syncthreads();
-    const int m = threadIdx.x >> 4, j16 = threadIdx.x & 15;
-    for (int j = j16; j < r; j += 16) {
-        float s0 = 0.f, s1 = 0.f;
+    const int j16 = threadIdx.x & 15;
+    for (int m = threadIdx.x >> 4; m < M; m += 16) {
+        for (int j = j16; j < r; j += 16) {
+            float s0 = 0.f, s1 = 0.f;
 #pragma unroll 8
-        for (int k = 0; k + 1 < kn; k += 2) {
-            s0 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
-            s1 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
+            for (int k = 0; k + 1 < kn; k += 2) {
+                s0 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
+                s1 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
+            }
+            hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
         }
-        if (m < M) hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
     }
 }
 
-template <int SCHEME>
+template <int SCHEME, int TT>
 __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, const void* __restrict__ Wq,
                                                          const void* __restrict__ scales, float* __restrict__ part,
                                                          int M, int K, int N, int k_chunk,
@@ -146,12 +149,14 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 {
     constexpr bool I4 = (SCHEME == 4);
     constexpr int WLOADS = I4 ? 4 : 8;               // 16-byte weight loads per lane per step
-    constexpr int XS_BYTES = TOK * STEP * 2;
-    static_assert(H_LDS_BYTES <= 2 * XS_BYTES, "the H = X A workgroups reuse the token tiles' LDS");
+    constexpr int TOKS = TOK * TT;                   // token rows this instantiation covers
+    constexpr int XS_BYTES = TOKS * STEP * 2;
+    constexpr int XL = 4 * TT;                       // 16-byte token pieces per thread per step
+    static_assert(h_lds_bytes(TOKS) <= 2 * XS_BYTES, "the H = X A workgroups reuse the token tiles' LDS");
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XS_BYTES];
     unsigned char* const xs[2] = {smem, smem + XS_BYTES};
     if ((int)blockIdx.x >= main_grid) {
-        hpart_body(smem, (int)blockIdx.x - main_grid, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(A), hpart, M, K, r);
+        hpart_body<TOKS>(smem, (int)blockIdx.x - main_grid, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(A), hpart, M, K, r);
         return;
     }
 
@@ -192,19 +197,19 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
             s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, off, 0, 0);
         }
     };
-    // token tile of one step: 1024 chunks of 16 bytes, four per thread
-    auto load_x = [&](u32x4 (&x)[4], int k0) {
+    // token tile of one step: 64 chunks of 16 bytes per token, 4 TT per thread
+    auto load_x = [&](u32x4 (&x)[XL], int k0) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
+        for (int j = 0; j < XL; j++) {
             const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
             const int k = k0 + chunk * 8;
             const uint32_t off = (tok < M && k < kend) ? (uint32_t)(((int64_t)tok * K + k) * 2) : OOB;
             x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
         }
     };
-    auto store_x = [&](const u32x4 (&x)[4], unsigned char* dst) {
+    auto store_x = [&](const u32x4 (&x)[XL], unsigned char* dst) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
+        for (int j = 0; j < XL; j++) {
             const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
             *reinterpret_cast<u32x4*>(dst + x_off(tok, chunk)) = x[j];
         }
@@ -212,15 +217,17 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 
     u32x4 wreg[2][WLOADS];
     u32x4 sreg[2][4];
-    u32x4 xreg[4];
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};                // scaled sums (int4) / raw code sums (int8)
-    f32x4 ones_acc = {0.f, 0.f, 0.f, 0.f};           // int8: sum of X over the whole slice
+    u32x4 xreg[XL];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[TT];                                   // scaled sums (int4) / raw code sums (int8), per token tile
+    f32x4 ones_acc[TT];                              // int8: sum of X over the whole slice
+#pragma unroll
+    for (int tt = 0; tt < TT; tt++) acc[tt] = ones_acc[tt] = zero4;
     u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = as_bf16x8(ones_bits);
 
-    auto xfrag = [&](const unsigned char* tile, int chunk) {
-        return *reinterpret_cast<const bf16x8*>(tile + x_off(lr, chunk));
+    auto xfrag = [&](const unsigned char* tile, int tt, int chunk) {
+        return *reinterpret_cast<const bf16x8*>(tile + x_off(TOK * tt + lr, chunk));
     };
     // one step of the reduction from registers w (and s) against the token tile
     auto compute = [&](u32x4 (&w)[WLOADS], u32x4 (&s)[4], const unsigned char* tile) {
@@ -231,13 +238,19 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                 transpose_groups(t);                 // t[c] = codes k = 128 u + 32 c + 8 g .. + 7
 #pragma unroll
                 for (int b = 0; b < 2; b++) {
-                    f32x4 cw = zero4, cx = zero4;
+                    f32x4 cw[TT], cx[TT];
+#pragma unroll
+                    for (int tt = 0; tt < TT; tt++) cw[tt] = cx[tt] = zero4;
 #pragma unroll
                     for (int h = 0; h < 2; h++) {
                         const int c = 2 * b + h;
-                        const bf16x8 xf = xfrag(tile, (128 * u + 32 * c) / 8 + g);
-                        cw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(int4_operand(t[c]), xf, cw, 0, 0, 0);
-                        cx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, cx, 0, 0, 0);
+                        const bf16x8 wf = int4_operand(t[c]);
+#pragma unroll
+                        for (int tt = 0; tt < TT; tt++) {
+                            const bf16x8 xf = xfrag(tile, tt, (128 * u + 32 * c) / 8 + g);
+                            cw[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, cw[tt], 0, 0, 0);
+                            cx[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, cx[tt], 0, 0, 0);
+                        }
                     }
                     // block 2 u + b of this step: fp16 scale of channel n0 + 4 g + v
                     const int blk = 2 * u + b;
@@ -245,7 +258,9 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                     for (int v = 0; v < 4; v++) {
                         const uint32_t word = s[v][blk >> 1];
                         const __half hs = __ushort_as_half((unsigned short)((blk & 1) ? (word >> 16) : (word & 0xffffu)));
-                        acc[v] += __half2float(hs) * (cw[v] - 136.f * cx[v]);
+                        const float sc = __half2float(hs);
+#pragma unroll
+                        for (int tt = 0; tt < TT; tt++) acc[tt][v] += sc * (cw[tt][v] - 136.f * cx[tt][v]);
                     }
                 }
             }
@@ -254,10 +269,13 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
             for (int u = 0; u < 8; u++) {            // 64 k: lane holds k = 64 u + 16 g .. + 15
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
-                    const bf16x8 xf = xfrag(tile, (64 * u + 16 * g + 8 * h) / 8);
                     const bf16x8 wf = h ? int8_operand(w[u].z, w[u].w) : int8_operand(w[u].x, w[u].y);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc, 0, 0, 0);
-                    ones_acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, ones_acc, 0, 0, 0);
+#pragma unroll
+                    for (int tt = 0; tt < TT; tt++) {
+                        const bf16x8 xf = xfrag(tile, tt, (64 * u + 16 * g + 8 * h) / 8);
+                        acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[tt], 0, 0, 0);
+                        ones_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, ones_acc[tt], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -290,23 +308,35 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         }
     }
 
-    // accumulator view: lane holds token lr, channels n0 + 4 g + v
+    // accumulator view: lane holds token 16 tt + lr, channels n0 + 4 g + v
     const int n = n0 + 4 * g;
-    if (lr < M && n < N) {
-        f32x4 o = acc;
+    if (n < N) {
+        float ch_scale[4] = {1.f, 1.f, 1.f, 1.f};
         if constexpr (!I4) {
             // one fp16 scale per output channel, applied once
             const unsigned short* sc = reinterpret_cast<const unsigned short*>(scales);
 #pragma unroll
-            for (int v = 0; v < 4; v++)
-                o[v] = __half2float(__ushort_as_half(sc[n + v])) * (acc[v] - 128.f * ones_acc[v]);
+            for (int v = 0; v < 4; v++) ch_scale[v] = __half2float(__ushort_as_half(sc[n + v]));
         }
-        *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + lr) * N + n) = o;
+#pragma unroll
+        for (int tt = 0; tt < TT; tt++) {
+            const int m = TOK * tt + lr;
+            if (m >= M) continue;
+            f32x4 o = acc[tt];
+            if constexpr (!I4) {
+#pragma unroll
+                for (int v = 0; v < 4; v++) o[v] = ch_scale[v] * (acc[tt][v] - 128.f * ones_acc[tt][v]);
+            }
+            *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + m) * N + n) = o;
+        }
     }
 }
 
 // Y[m][n] = bf16( base_scale * sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
-// A workgroup covers 64 channels; thread (channel c, token group q) handles tokens q, q+4, ...
+// A workgroup covers 64 channels x 4 tokens, one output per thread (blockIdx.y picks the token group).
+// Everything a thread needs from memory is requested up front (its column of B, its slab values,
+// its share of the H partial sums), so the kernel pays one memory round trip, not three.
+constexpr int FTOK = 4;
 template <int RMAX>
 __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
                                                     const float* __restrict__ hpart, int kchunks,
@@ -314,80 +344,60 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
                                                     uint16_t* __restrict__ Y, uint16_t* __restrict__ H_out,
                                                     int M, int N, int r)
 {
-    __shared__ float Hs[TOK * RMAX];
-    // Everything this thread needs from memory is requested up front (the column of B, the slab
-    // sums of its tokens, its share of the H partial sums), so the kernel pays one memory round
-    // trip, not three.
+    __shared__ float Hs[FTOK * RMAX];
+    __shared__ float Hg[NT];
     const int n = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int mq = threadIdx.x >> 6;
-    const bool live = n < N;
+    const int m0 = blockIdx.y * FTOK;
+    const int m = m0 + (threadIdx.x >> 6);
+    const bool live = n < N && m < M;
     float b[RMAX];
 #pragma unroll
     for (int j = 0; j < RMAX; j++) b[j] = (live && j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
-    float base[TOK / 4];
-#pragma unroll
-    for (int t = 0; t < TOK / 4; t++) {
-        const int m = mq + 4 * t;
-        float s = 0.f;
-        if (live && m < M)
-            for (int sp = 0; sp < splits; sp++) s += part[((int64_t)sp * M + m) * N + n];
-        base[t] = s;
-    }
-    // H = sum of the chunk partial sums, all 256 threads sharing the loads: thread (o, g) adds the
-    // chunks g, g + G, ... of output o, then the G group sums are added in group order (the same
-    // order every run)
-    __shared__ float Hg[NT];
-    const int outs = M * r;
-    if (outs <= NT / 2) {
-        const int G = NT / outs;                            // groups of chunks
+    float base = 0.f;
+    if (live)
+        for (int sp = 0; sp < splits; sp++) base += part[((int64_t)sp * M + m) * N + n];
+    // H of this group's tokens = sum of the chunk partial sums, all 256 threads sharing the loads:
+    // thread (o, g) adds the chunks g, g + G, ... of output o, then the G group sums are added in
+    // group order (the same order every run).  The tokens of a group are consecutive, so their
+    // outputs are contiguous in a chunk: hpart[kc][m0 * r + o].
+    const int toks = (M - m0 < FTOK) ? M - m0 : FTOK;
+    const int outs = toks * r;                              // at most 4 RMAX <= 256
+    const int64_t chunk = (int64_t)M * r;
+    const float* hp = hpart + (int64_t)m0 * r;
+    const int G = NT / outs;
+    {
         const int o = threadIdx.x % outs, g = threadIdx.x / outs;
-        float s = 0.f;
-        if (g < G)
-            for (int kc = g; kc < kchunks; kc += G) s += hpart[(int64_t)kc * outs + o];
-        Hg[threadIdx.x] = s;
-        __syncthreads();
-        if (threadIdx.x < outs) {
-            float t = 0.f;
-            for (int q = 0; q < G; q++) t += Hg[q * outs + threadIdx.x];
-            Hs[threadIdx.x] = t;
-            if (H_out && blockIdx.x == 0) {
-                const __bf16 hb = (__bf16)t;
-                H_out[threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
-            }
-        }
-    } else {
-        for (int o = threadIdx.x; o < outs; o += NT) {
-            float sv[8];                                    // eight loads in flight per trip
+        float sv[4] = {0.f, 0.f, 0.f, 0.f};                 // four loads in flight per trip
+        if (g < G) {
+            for (int kc = g; kc < kchunks; kc += 4 * G) {
 #pragma unroll
-            for (int q = 0; q < 8; q++) sv[q] = 0.f;
-            for (int kc = 0; kc < kchunks; kc += 8) {
-#pragma unroll
-                for (int q = 0; q < 8; q++) {
-                    const int c = (kc + q < kchunks) ? kc + q : kc;     // (a repeated, in-range chunk, weighted 0)
-                    const float v = hpart[(int64_t)c * outs + o];
-                    sv[q] += (kc + q < kchunks) ? v : 0.f;
+                for (int q = 0; q < 4; q++) {
+                    const int c = kc + q * G;
+                    const float v = hp[(int64_t)(c < kchunks ? c : kc) * chunk + o];    // (a repeated, in-range chunk, weighted 0)
+                    sv[q] += (c < kchunks) ? v : 0.f;
                 }
             }
-            const float t = ((sv[0] + sv[1]) + (sv[2] + sv[3])) + ((sv[4] + sv[5]) + (sv[6] + sv[7]));
-            Hs[o] = t;
-            if (H_out && blockIdx.x == 0) {
-                const __bf16 hb = (__bf16)t;
-                H_out[o] = __builtin_bit_cast(uint16_t, hb);
-            }
+        }
+        Hg[threadIdx.x] = (sv[0] + sv[1]) + (sv[2] + sv[3]);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < outs) {
+        float t = 0.f;
+        for (int q = 0; q < G; q++) t += Hg[q * outs + threadIdx.x];
+        Hs[threadIdx.x] = t;
+        if (H_out && blockIdx.x == 0) {
+            const __bf16 hb = (__bf16)t;
+            H_out[(int64_t)m0 * r + threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
         }
     }
     __syncthreads();
     if (!live) return;
+    const int ml = m - m0;
+    float l = 0.f;
 #pragma unroll
-    for (int t = 0; t < TOK / 4; t++) {
-        const int m = mq + 4 * t;
-        if (m >= M) break;
-        float l = 0.f;
-#pragma unroll
-        for (int j = 0; j < RMAX; j++) l = fmaf(Hs[m * r + (j < r ? j : 0)], b[j], l);
-        const __bf16 yb = (__bf16)(base_scale * base[t] + scaling * l);
-        Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
-    }
+    for (int j = 0; j < RMAX; j++) l = fmaf(Hs[ml * r + (j < r ? j : 0)], b[j], l);
+    const __bf16 yb = (__bf16)(base_scale * base + scaling * l);
+    Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
 }
 
 }  // namespace skinny
@@ -396,7 +406,7 @@ bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
 {
     (void)N;
     if (scheme != 4 && scheme != 8) return false;
-    return M >= 1 && M <= skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
+    return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
 }
 
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
@@ -404,8 +414,10 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
     QskinnyPlan p;
     const int64_t row_blocks = (N + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
     const int64_t ksteps = K / skinny::STEP;
-    // enough workgroups to put about four on every compute unit, at least one step each
-    int64_t s = (4 * (int64_t)num_cu + row_blocks - 1) / row_blocks;
+    // enough workgroups to fill the compute units as far as the token tiles' LDS lets them share one
+    // (four workgroups with 16 tokens, two with 32, one with 64), at least one step each
+    const int64_t per_cu = (M <= 16) ? 4 : (M <= 32) ? 2 : 1;
+    int64_t s = (per_cu * (int64_t)num_cu + row_blocks - 1) / row_blocks;
     if (s > ksteps) s = ksteps;
     if (s < 1) s = 1;
     const int64_t per = (ksteps + s - 1) / s;
@@ -428,23 +440,27 @@ hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales,
     const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
     const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * (double)N,
                                 wbytes + 2.0 * M * K + 4.0 * p.splits * M * N, st);
-    if (scheme == 4)
-        hipLaunchKernelGGL(qskinny_fwd_kernel<4>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk, A, hpart, (int)r, main_grid);
-    else
-        hipLaunchKernelGGL(qskinny_fwd_kernel<8>, grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, p.k_chunk, A, hpart, (int)r, main_grid);
+#define FHPC_MAIN(SCHEME, TT)                                                                                       \
+    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT>), grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, \
+                       p.k_chunk, A, hpart, (int)r, main_grid)
+    const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
+    if (scheme == 4) {
+        if (tt == 1) FHPC_MAIN(4, 1); else if (tt == 2) FHPC_MAIN(4, 2); else FHPC_MAIN(4, 4);
+    } else {
+        if (tt == 1) FHPC_MAIN(8, 1); else if (tt == 2) FHPC_MAIN(8, 2); else FHPC_MAIN(8, 4);
+    }
+#undef FHPC_MAIN
     prof_end(slot, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 fgrid((unsigned)((N + 63) / 64));
+    const dim3 fgrid((unsigned)((N + 63) / 64), (unsigned)((M + FTOK - 1) / FTOK));
     const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
-    if (r <= 16)
-        hipLaunchKernelGGL(finish_kernel<16>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
-                           static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
-                           (int)M, (int)N, (int)r);
-    else
-        hipLaunchKernelGGL(finish_kernel<64>, fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,
-                           static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y), static_cast<uint16_t*>(H_out),
-                           (int)M, (int)N, (int)r);
+#define FHPC_FINISH(RMAX)                                                                                           \
+    hipLaunchKernelGGL((finish_kernel<RMAX>), fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,              \
+                       static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y),             \
+                       static_cast<uint16_t*>(H_out), (int)M, (int)N, (int)r)
+    if (r <= 16) FHPC_FINISH(16); else FHPC_FINISH(64);
+#undef FHPC_FINISH
     prof_end(fslot, st);
     return hipGetLastError();
 }

@@ -66,6 +66,25 @@ def test_bf16_shapes(M, K, r, N):
     _check_all("bf16 %s recompute" % ((M, K, r, N),), (None, dX2, dA2, dB2), ref, TOL_BF16)
 
 
+@pytest.mark.parametrize("M,K,r,N", [
+    (1, 4096, 512, 4096),    # one token at the pretraining configuration's layer
+    (16, 1024, 128, 776),
+    (32, 520, 5, 264),       # odd rank, ragged reduction
+    (7, 768, 24, 72),
+])
+def test_bf16_few_tokens_forward(M, K, r, N):
+    """At most 32 tokens: both products of the forward run as split reductions on a 32-row tile."""
+    fhpc = _fhpc()
+    X, A, B, _ = lowrank_inputs(9, M, K, r, N, tensor_base=30)
+    Yr, Hr = oracle.lowrank_fwd(X.f64, A.f64, B.f64)
+    Y, H = fhpc.lowrank_linear_fwd(X.cuda(), A.cuda(), B.cuda(), save_H=True)
+    eY, eH = oracle.rel_fro(from_device(Y), Yr), oracle.rel_fro(from_device(H), Hr)
+    print("few tokens %s: Y %.3e H %.3e" % ((M, K, r, N), eY, eH), flush=True)
+    assert eY <= TOL_BF16 and eH <= TOL_BF16
+    Y2 = fhpc.lowrank_linear_fwd(X.cuda(), A.cuda(), B.cuda())
+    assert np.array_equal(from_device(Y2), from_device(Y))
+
+
 def test_bf16_optional_outputs_and_canaries():
     """NULL outputs are skipped; nothing is written outside the output tensors."""
     import torch

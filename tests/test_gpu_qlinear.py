@@ -176,9 +176,13 @@ def test_config5_full_size():
     (7, 2048, 5, 200),         # odd rank, several steps
     (16, 5120, 16, 328),       # a full token tile, ten steps
     (3, 1024, 64, 8),          # widest rank the path takes, a single group of channels
+    (17, 1536, 16, 136),       # two token tiles, the second nearly empty
+    (32, 1024, 8, 264),        # two full token tiles
+    (33, 2048, 24, 72),        # four token tiles, two of them empty but for one token
+    (64, 4096, 16, 520),       # the most tokens the path takes
 ])
 def test_few_token_forward(scheme, M, K, r, N):
-    """M <= 16 tokens and K a multiple of 512 take the weight-streaming forward (codes turned
+    """M <= 64 tokens and K a multiple of 512 take the weight-streaming forward (codes turned
     into exact small bf16 integers, offset and scale applied to the fp32 sums)."""
     fhpc = _fhpc()
     W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 60)
