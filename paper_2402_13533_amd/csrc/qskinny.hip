@@ -12,10 +12,12 @@
 //         0x4300 | u is exactly 128 + u.
 //   int8: byte b -> u = b ^ 0x80 = q + 128 in [0, 255]; float(u) is exact in bf16.
 // The matrix instruction therefore accumulates sum_k X[m,k] * (q[n,k] + c) with c = 136 or
-// 128; a second accumulator fed with an all-ones operand gives sum_k X[m,k], and the offset
-// and the fp16 scale are applied to the fp32 sums: per 64-wide block for int4 (Sec. 5.2:
-// one scale per weight vector, here a block of 64 inputs of one output channel), once at
-// the end for int8 (one scale per output channel).  The weight is thus used unrounded.
+// 128.  The offset is taken out again on the matrix unit: for int4 a second instruction with a
+// constant operand -136 adds sum_k X[m,k] * (-136) into the same accumulator; for int8 a
+// second accumulator fed with an all-ones operand gives sum_k X[m,k], subtracted at the end.
+// The fp16 scale is applied to the fp32 sums: per 64-wide block for int4 (Sec. 5.2: one scale
+// per weight vector, here a block of 64 inputs of one output channel), once at the end for
+// int8 (one scale per output channel).  The weight is thus used unrounded.
 //
 // Work split: a workgroup of four waves owns 64 output channels (16 per wave) and one slice
 // of the reduction; slices write fp32 partial sums to slabs; a finishing kernel adds the slabs
@@ -25,6 +27,7 @@
 #include "profile.h"
 
 #include <hip/hip_fp16.h>
+#include <type_traits>
 #include <stdio.h>
 
 namespace fhpc {
@@ -65,17 +68,32 @@ __device__ __forceinline__ void transpose_groups(uint32_t (&w)[4])
 }
 
 // eight int4 codes (one 32-bit word, element 2j in the low nibble of byte j) -> eight bf16
-// values 128 + (q + 8), element order preserved
+// values 128 + (q + 8).  The even and the odd nibbles are isolated as bytes (u = n ^ 8), and one
+// byte permute per result word interleaves two of them with the constant byte 0x43, so the
+// operand's k order is 0 2 4 6 1 3 5 7; the token tile is stored in the same order
+// (x_even_odd_order).
 __device__ __forceinline__ bf16x8 int4_operand(uint32_t w)
 {
-    const uint32_t x = w ^ 0x88888888u;
-    const uint32_t lo = x & 0x0f0f0f0fu, hi = (x >> 4) & 0x0f0f0f0fu;
+    const uint32_t lo = (w & 0x0f0f0f0fu) ^ 0x08080808u;            // u of elements 0 2 4 6
+    const uint32_t hi = ((w >> 4) & 0x0f0f0f0fu) ^ 0x08080808u;     // u of elements 1 3 5 7
+    const uint32_t c43 = 0x43434343u;
     u32x4 r;
-    r.x = __builtin_amdgcn_perm(hi, lo, 0x0c040c00u) | 0x43004300u;
-    r.y = __builtin_amdgcn_perm(hi, lo, 0x0c050c01u) | 0x43004300u;
-    r.z = __builtin_amdgcn_perm(hi, lo, 0x0c060c02u) | 0x43004300u;
-    r.w = __builtin_amdgcn_perm(hi, lo, 0x0c070c03u) | 0x43004300u;
+    r.x = __builtin_amdgcn_perm(c43, lo, 0x04010400u);
+    r.y = __builtin_amdgcn_perm(c43, lo, 0x04030402u);
+    r.z = __builtin_amdgcn_perm(c43, hi, 0x04010400u);
+    r.w = __builtin_amdgcn_perm(c43, hi, 0x04030402u);
     return as_bf16x8(r);
+}
+
+// eight consecutive bf16 (four words) -> the order 0 2 4 6 1 3 5 7
+__device__ __forceinline__ u32x4 x_even_odd_order(u32x4 v)
+{
+    u32x4 r;
+    r.x = __builtin_amdgcn_perm(v.y, v.x, 0x05040100u);
+    r.y = __builtin_amdgcn_perm(v.w, v.z, 0x05040100u);
+    r.z = __builtin_amdgcn_perm(v.y, v.x, 0x07060302u);
+    r.w = __builtin_amdgcn_perm(v.w, v.z, 0x07060302u);
+    return r;
 }
 
 // eight int8 codes (two words) -> eight bf16 values q + 128
@@ -179,7 +197,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 
     // weight pieces of one step for this lane.  int4: load u covers k = 128 u + 32 g .. + 31
     // (16 bytes); int8: load u covers k = 64 u + 16 g .. + 15.
-    auto load_w = [&](u32x4 (&w)[WLOADS], int k0) {
+    auto load_w = [&](u32x4 (&w)[WLOADS], int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < WLOADS; u++) {
             const int k = k0 + (I4 ? 128 * u + 32 * g : 64 * u + 16 * g);
@@ -189,7 +207,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     };
     // int4 scales of one step: eight consecutive blocks of each of the four output channels this
     // lane owns in the accumulator view (channel n0 + 4 g + v)
-    auto load_s = [&](u32x4 (&s)[4], int k0) {
+    auto load_s = [&](u32x4 (&s)[4], int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int v = 0; v < 4; v++) {
             const int n = n0 + 4 * g + v;
@@ -198,7 +216,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         }
     };
     // token tile of one step: 64 chunks of 16 bytes per token, 4 TT per thread
-    auto load_x = [&](u32x4 (&x)[XL], int k0) {
+    auto load_x = [&](u32x4 (&x)[XL], int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < XL; j++) {
             const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
@@ -207,16 +225,16 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
             x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
         }
     };
-    auto store_x = [&](const u32x4 (&x)[XL], unsigned char* dst) {
+    auto store_x = [&](const u32x4 (&x)[XL], unsigned char* dst) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < XL; j++) {
             const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
-            *reinterpret_cast<u32x4*>(dst + x_off(tok, chunk)) = x[j];
+            *reinterpret_cast<u32x4*>(dst + x_off(tok, chunk)) = I4 ? x_even_odd_order(x[j]) : x[j];
         }
     };
 
-    u32x4 wreg[2][WLOADS];
-    u32x4 sreg[2][4];
+    u32x4 wreg[3][WLOADS];                           // weights of the steps t, t + 1, t + 2
+    u32x4 sreg[3][4];
     u32x4 xreg[XL];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     f32x4 acc[TT];                                   // scaled sums (int4) / raw code sums (int8), per token tile
@@ -225,12 +243,14 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     for (int tt = 0; tt < TT; tt++) acc[tt] = ones_acc[tt] = zero4;
     u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = as_bf16x8(ones_bits);
+    u32x4 moff_bits = {0xc308c308u, 0xc308c308u, 0xc308c308u, 0xc308c308u};     // bf16(-136) x 8
+    const bf16x8 minus_offset = as_bf16x8(moff_bits);
 
-    auto xfrag = [&](const unsigned char* tile, int tt, int chunk) {
+    auto xfrag = [&](const unsigned char* tile, int tt, int chunk) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8*>(tile + x_off(TOK * tt + lr, chunk));
     };
     // one step of the reduction from registers w (and s) against the token tile
-    auto compute = [&](u32x4 (&w)[WLOADS], u32x4 (&s)[4], const unsigned char* tile) {
+    auto compute = [&](u32x4 (&w)[WLOADS], u32x4 (&s)[4], const unsigned char* tile) __attribute__((always_inline)) {
         if constexpr (I4) {
 #pragma unroll
             for (int u = 0; u < 4; u++) {            // 128 k: two scale blocks
@@ -238,9 +258,10 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                 transpose_groups(t);                 // t[c] = codes k = 128 u + 32 c + 8 g .. + 7
 #pragma unroll
                 for (int b = 0; b < 2; b++) {
-                    f32x4 cw[TT], cx[TT];
+                    // sum over the block of X (q + 136) and of X (-136), in one accumulator
+                    f32x4 cw[TT];
 #pragma unroll
-                    for (int tt = 0; tt < TT; tt++) cw[tt] = cx[tt] = zero4;
+                    for (int tt = 0; tt < TT; tt++) cw[tt] = zero4;
 #pragma unroll
                     for (int h = 0; h < 2; h++) {
                         const int c = 2 * b + h;
@@ -249,7 +270,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                         for (int tt = 0; tt < TT; tt++) {
                             const bf16x8 xf = xfrag(tile, tt, (128 * u + 32 * c) / 8 + g);
                             cw[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, cw[tt], 0, 0, 0);
-                            cx[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, xf, cx[tt], 0, 0, 0);
+                            cw[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(minus_offset, xf, cw[tt], 0, 0, 0);
                         }
                     }
                     // block 2 u + b of this step: fp16 scale of channel n0 + 4 g + v
@@ -260,7 +281,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                         const __half hs = __ushort_as_half((unsigned short)((blk & 1) ? (word >> 16) : (word & 0xffffu)));
                         const float sc = __half2float(hs);
 #pragma unroll
-                        for (int tt = 0; tt < TT; tt++) acc[tt][v] += sc * (cw[tt][v] - 136.f * cx[tt][v]);
+                        for (int tt = 0; tt < TT; tt++) acc[tt][v] += sc * cw[tt][v];
                     }
                 }
             }
@@ -281,30 +302,52 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         }
     };
 
+    // Step t computes from weight registers t % (DEPTH + 1) and token tile t % 2.  Its requests: the token
+    // rows of step t + 1 first, then the weights of step t + DEPTH, so that the wait for the token
+    // rows at the top of the next step leaves the weight requests in flight (loads return in
+    // order).  (Measured: DEPTH 2 costs a third of the resident waves and is slower.)
+    constexpr int DEPTH = 1;
+    auto step = [&](auto WB, auto XB, int t) __attribute__((always_inline)) {
+        constexpr int wb = decltype(WB)::value, xb = decltype(XB)::value, wn = (wb + DEPTH) % (DEPTH + 1);
+        store_x(xreg, xs[xb]);
+        if (t + 1 < steps) load_x(xreg, kbeg + (t + 1) * STEP);
+        if (t + DEPTH < steps) {
+            load_w(wreg[wn], kbeg + (t + DEPTH) * STEP);
+            if constexpr (I4) load_s(sreg[wn], kbeg + (t + DEPTH) * STEP);
+        }
+        __syncthreads();
+        compute(wreg[wb], sreg[wb], xs[xb]);
+    };
     if (steps > 0) {
+        load_x(xreg, kbeg);
         load_w(wreg[0], kbeg);
         if constexpr (I4) load_s(sreg[0], kbeg);
-        load_x(xreg, kbeg);
-        for (int t = 0; t < steps; t += 2) {
-            // even step from buffer 0
-            store_x(xreg, xs[0]);
-            if (t + 1 < steps) {
-                load_w(wreg[1], kbeg + (t + 1) * STEP);
-                if constexpr (I4) load_s(sreg[1], kbeg + (t + 1) * STEP);
-                load_x(xreg, kbeg + (t + 1) * STEP);
+        if (DEPTH == 2 && steps > 1) {
+            load_w(wreg[1], kbeg + STEP);
+            if constexpr (I4) load_s(sreg[1], kbeg + STEP);
+        }
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        if constexpr (DEPTH == 1) {
+            for (int t = 0; t < steps; t += 2) {
+                step(I0{}, I0{}, t);
+                if (t + 1 >= steps) break;
+                step(I1{}, I1{}, t + 1);
             }
-            __syncthreads();
-            compute(wreg[0], sreg[0], xs[0]);
+        } else
+        for (int t = 0; t < steps; t += 6) {
+            step(I0{}, I0{}, t);
             if (t + 1 >= steps) break;
-            // odd step from buffer 1
-            store_x(xreg, xs[1]);
-            if (t + 2 < steps) {
-                load_w(wreg[0], kbeg + (t + 2) * STEP);
-                if constexpr (I4) load_s(sreg[0], kbeg + (t + 2) * STEP);
-                load_x(xreg, kbeg + (t + 2) * STEP);
-            }
-            __syncthreads();
-            compute(wreg[1], sreg[1], xs[1]);
+            step(I1{}, I1{}, t + 1);
+            if (t + 2 >= steps) break;
+            step(I2{}, I0{}, t + 2);
+            if (t + 3 >= steps) break;
+            step(I0{}, I1{}, t + 3);
+            if (t + 4 >= steps) break;
+            step(I1{}, I0{}, t + 4);
+            if (t + 5 >= steps) break;
+            step(I2{}, I1{}, t + 5);
         }
     }
 
@@ -414,10 +457,11 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
     QskinnyPlan p;
     const int64_t row_blocks = (N + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
     const int64_t ksteps = K / skinny::STEP;
-    // enough workgroups to fill the compute units as far as the token tiles' LDS lets them share one
-    // (four workgroups with 16 tokens, two with 32, one with 64), at least one step each
-    const int64_t per_cu = (M <= 16) ? 4 : (M <= 32) ? 2 : 1;
-    int64_t s = (per_cu * (int64_t)num_cu + row_blocks - 1) / row_blocks;
+    // One round of workgroups: as many as are resident at once (registers and the token tiles' LDS
+    // allow three per compute unit with 16 tokens, two with 32, one with 64) and no more, so that
+    // no second, partly filled round follows; at least one step each.
+    const int64_t per_cu = (M <= 16) ? 3 : (M <= 32) ? 2 : 1;
+    int64_t s = per_cu * (int64_t)num_cu / row_blocks;
     if (s > ksteps) s = ksteps;
     if (s < 1) s = 1;
     const int64_t per = (ksteps + s - 1) / s;
