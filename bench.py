@@ -6,7 +6,7 @@ already resident in HBM.  Default workload (config 2): forward + backward of the
 Llama-2-7B attention projections, each factorised with r = 512, on 16384 tokens in bf16.
 Prints ONE JSON line (see README for the fields).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|merge]
 """
 from __future__ import annotations
 
@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "merge"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0,
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
@@ -135,6 +135,32 @@ class QlinearCall:
                               H_saved=None if self.recompute else self.H, dX=self.dX, dA=self.dA, dB=self.dB)
 
 
+class MergeCall:
+    """W' = deq(Wq) + scaling A B written as bf16: the adapted weight materialised for inference."""
+
+    def __init__(self, fhpc, K, r, N, scheme, gen, scaling=2.0):
+        import torch
+        bf = torch.bfloat16
+        self.f = fhpc
+        self.K, self.r, self.N, self.scheme, self.s = K, r, N, scheme, scaling
+        W = randn((K, N), 0.02, torch.float32, gen)
+        self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)
+        del W
+        self.A = randn((K, r), K ** -0.5, bf, gen)
+        self.B = randn((r, N), 0.01, bf, gen)
+        self.out = torch.empty((K, N), dtype=bf, device="cuda")
+
+    def flops(self):
+        return 2 * self.K * self.N * self.r
+
+    def io_bytes(self):
+        return (self.Wq.numel() * self.Wq.element_size() + 2 * self.sc.numel() + 2 * self.K * self.N
+                + 2 * self.r * (self.K + self.N))
+
+    def run(self):
+        self.f.lowrank_merge(self.Wq, self.sc, self.scheme, self.A, self.B, self.s, W_out=self.out)
+
+
 class FfnCall:
     """Config 3: gate/up 4096 -> r -> 11008, SiLU gate, down 11008 -> r -> 4096, fwd + bwd."""
 
@@ -186,6 +212,12 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
         calls = [QlinearCall(fhpc, M, 4096, 8, 4096, 8, gen, 2.0, recompute, forward_only) for _ in range(4)]
         desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, %d tokens, bf16, %s, 4 buffer sets per step" % (
             M, "fwd" if forward_only else "fwd+bwd")
+        dtype = "bf16"
+    elif name == "merge":
+        d, f = 5120, 13824
+        shp = [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
+        calls = [MergeCall(fhpc, K, 16, N, 4, gen) for K, N in shp]
+        desc = "merged weights of config 5's decoder layer: 7 x (int4 block-64 W + 2 A B, rank 16) -> bf16"
         dtype = "bf16"
     else:
         d, f = 5120, 13824
@@ -328,8 +360,11 @@ def main():
                         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                         "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": share}
 
+    metric, value, unit = "fwd+bwd TFLOP/s", tflops, "TFLOP/s"
+    if args.workload == "merge":       # a streaming pass: quoted in bytes moved
+        metric, value, unit = "merge GB/s", io_bytes / (ms_per_step * 1e-3) / 1e9, "GB/s"
     out = {
-        "metric": "fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": desc, "saved_H": not args.recompute, "hip_graph": bool(args.graph)},
@@ -343,7 +378,7 @@ def main():
         for _ in range(3):
             torch.add(x, 1.0, out=y)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload != "merge":
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))
 

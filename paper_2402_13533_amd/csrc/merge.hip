@@ -3,13 +3,20 @@
 //     W_out[K,N] = deq(W)[K,N] + scaling * A[K,r] * B[r,N]
 //
 // One pass over the weight: the kernel is bound by reading W once and writing W_out once; the
-// rank-r product is a short matrix-core loop (reduction length r) per 128 x 128 tile of the
-// output.  Per tile: (1) the thread's share of the base weight is requested first and stays in
-// registers while (2) the r-loop runs on 32-deep slices of A and B double-buffered in LDS
-// (global -> LDS requests, transposing LDS reads for B); (3) scaling * A B goes to LDS as an
-// fp32 tile (over the operand buffers); a quantised base weight, stored channel-major, is
-// dequantised and added there, which transposes it on the way; (4) rows of the tile are
-// streamed out 16 or 32 bytes per lane, adding a bf16 base weight on the way.
+// rank-r product is a short matrix-core loop (reduction length r) per 64 x 128 tile of the
+// output, on 32-deep slices of A and B double-buffered in LDS (global -> LDS requests,
+// transposing LDS reads for B).
+//
+// The matrix instruction is oriented so that a lane ends up with columns of the output and groups
+// of four consecutive rows k; one half-wave swap per register pair then gives every lane ONE
+// column (lane = column, 64 columns per wave) and 32 consecutive rows.  That is exactly how a
+// quantised base weight is stored (channel-major: the codes of one output channel are contiguous
+// in k), so a lane loads the 32 codes of its channel once and adds them with no transposition
+// anywhere; code * scale is exact in fp32 and the sum is rounded once.  Along a row the 64 lanes
+// hold 64 consecutive columns: an fp32 store instruction writes 256 contiguous bytes; bf16 moves
+// as 32-bit words of two adjacent columns (neighbouring lanes trade one value each), two rows of
+// 128 bytes per instruction, and a bf16 base weight is loaded the same way.  The base weight of
+// the tile is requested before the r-loop and stays in registers meanwhile.
 #include "merge.h"
 #include "gemm_ring.h"
 #include "profile.h"
@@ -20,7 +27,7 @@ namespace mrg {
 using namespace ring;
 
 constexpr int NT = 256;
-constexpr int TK = 128, TN = 128, BK = 32;
+constexpr int TK = 64, TN = 128, BK = 32;     // output tile (rows of W' x columns), rank slice
 enum : int { W_NONE = 0, W_BF16 = 1, W_INT8 = 2, W_INT4 = 3 };
 
 struct MergeArgs {
@@ -33,15 +40,15 @@ struct MergeArgs {
     int r_rows;            // rows of B that exist
 };
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
-
-// fp32 tile in LDS, [TK][TN], 16-byte chunks of a row XOR-swizzled with the row so that the 32
-// rows a wave writes at one column land in 32 different chunks
-__device__ __forceinline__ uint32_t t_off(int row, int col)
+// value of the lane with the other parity in the same pair (lanes 2 m and 2 m + 1)
+__device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t x)
 {
-    return (uint32_t)row * (TN * 4) + (uint32_t)((((col >> 2) ^ row) & 31) << 4) + (uint32_t)(col & 3) * 4u;
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1 /* quad_perm 1 0 3 2 */, 0xf, 0xf, true);
 }
+
+// Row that a lane addresses when rows q (even) and q + 1 are moved as one 32-bit word of two
+// adjacent columns: even lanes take row q, odd lanes row q + 1.
+__device__ __forceinline__ int pair_row(int kw, int q, int lane) { return kw + q + (lane & 1); }
 
 template <int WMODE, bool OUT_F32>
 __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
@@ -52,64 +59,56 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     using TB = typename FB::Tile;
     constexpr int TILE_A_BYTES = FA::TILE_BYTES, STAGE_BYTES = FA::TILE_BYTES + FB::TILE_BYTES;
     constexpr int L = FA::PER + FB::PER;
-    constexpr int LDS_BYTES = TK * TN * 4;
-    static_assert(2 * STAGE_BYTES <= LDS_BYTES, "operand stages live under the output tile");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_k0 = (wave >> 1) * 64;
-    const int wave_n0 = (wave & 1) * 64;
+    const int wave_k0 = (wave >> 1) * 32;                      // the wave's 32 rows ...
+    const int wave_n0 = (wave & 1) * 64;                       // ... and two blocks of 32 columns
     const int tiles_n = (p.N + TN - 1) / TN;
     const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
     const int k0 = tk * TK, n0 = tn * TN;
+    const int kw = k0 + wave_k0;                               // first row of the wave
+    // accumulator register v of block j: row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n0 + wave_n0 + 32 j + lane % 32
 
-    // ---- (1) base weight of this tile, requested before anything else
-    // bf16: row-major, the same 8-column pieces the thread streams out in (4)
-    // quantised: channel n0 + tid/2, k half tid%2 (64 codes)
-    constexpr int PASSES = TK * (TN / 8) / NT;                 // 8 rows of 16 per thread
-    const int oc = tid & 15, orow = tid >> 4;                   // output piece: cols 8 oc.., rows orow + 16 q
-    u32x4 wreg[WMODE == W_BF16 ? PASSES : 1];
-    u32x2 q8[WMODE == W_INT8 ? 8 : 1];
-    u32x4 q4[WMODE == W_INT4 ? 2 : 1];
+    // ---- base weight of the wave's 32 x 64 block, requested before anything else, in the layout the
+    // epilogue works in: lane = column n0 + wave_n0 + lane, 32 rows kw .. kw + 31
+    const int n = n0 + wave_n0 + lane;
+    uint32_t wb[WMODE == W_BF16 ? 16 : 1];                     // bf16 pairs, one word per two rows (see pair_row)
+    u32x2 q8[WMODE == W_INT8 ? 4 : 1];                         // codes k = kw + 8 i .. + 7 of the lane's channel
+    u32x4 q4 = {0u, 0u, 0u, 0u};                               // codes k = kw .. kw + 31
     float wscale = 0.f;
-    const int qn = n0 + (tid >> 1), qk = k0 + (tid & 1) * 64;
     if constexpr (WMODE == W_BF16) {
 #pragma unroll
-        for (int q = 0; q < PASSES; q++) {
-            const int k = k0 + orow + 16 * q, n = n0 + oc * 8;
-            wreg[q] = (u32x4){0u, 0u, 0u, 0u};
+        for (int q = 0; q < 16; q++) {
+            const int k = pair_row(kw, 2 * q, lane);
+            wb[q] = 0u;
             if (k < p.K && n < p.N)
-                wreg[q] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.W) + (size_t)k * (size_t)p.N + (size_t)n);
+                wb[q] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(p.W) + (size_t)k * (size_t)p.N + (size_t)(n & ~1));
         }
     } else if constexpr (WMODE == W_INT8) {
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            q8[j] = (u32x2){0u, 0u};
-            if (qn < p.N && qk + 8 * j < p.K)
-                q8[j] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(p.W) + (size_t)qn * (size_t)p.K + (size_t)(qk + 8 * j));
+        for (int i = 0; i < 4; i++) {
+            q8[i] = (u32x2){0u, 0u};
+            if (n < p.N && kw + 8 * i < p.K)
+                q8[i] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(p.W) + (size_t)n * (size_t)p.K + (size_t)(kw + 8 * i));
         }
-        if (qn < p.N) wscale = (float)__builtin_bit_cast(_Float16, p.scales[qn]);
+        if (n < p.N) wscale = (float)__builtin_bit_cast(_Float16, p.scales[n]);
     } else if constexpr (WMODE == W_INT4) {
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            q4[j] = (u32x4){0u, 0u, 0u, 0u};
-            if (qn < p.N && qk + 32 * j < p.K)
-                q4[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(p.W) + ((size_t)qn * (size_t)p.K + (size_t)(qk + 32 * j)) / 2);
+        if (n < p.N && kw < p.K) {
+            q4 = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(p.W) + ((size_t)n * (size_t)p.K + (size_t)kw) / 2);
+            wscale = (float)__builtin_bit_cast(_Float16, p.scales[(size_t)n * (size_t)(p.K / 64) + (size_t)(kw / 64)]);
         }
-        if (qn < p.N && qk < p.K) wscale = (float)__builtin_bit_cast(_Float16, p.scales[(size_t)qn * (size_t)(p.K / 64) + (size_t)(qk / 64)]);
     }
 
-    // ---- (2) acc[j][i]: lane holds (A B)[k][n .. n+3] for k = wave_k0 + 32 i + lane % 32
-    f32x16 acc[2][2];
+    // ---- acc[j] = (A B) block: rows from the A tile, columns from the B tile
+    f32x16 acc[2];
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
-        for (int i = 0; i < 2; i++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) acc[j][i][v] = 0.f;
+        for (int v = 0; v < 16; v++) acc[j][v] = 0.f;
     {
         FA fa;
         FB fb;
@@ -130,89 +129,61 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
             wg_barrier();
 #pragma unroll
             for (int s = 0; s < BK / 16; s++) {
-                bf16x8 ra[2], rb[2];
+                const bf16x8 ra = TA::frag(cur, aa, 0, s);
 #pragma unroll
-                for (int i = 0; i < 2; i++) ra[i] = TA::frag(cur, aa, i, s);
-#pragma unroll
-                for (int j = 0; j < 2; j++) rb[j] = TB::frag(cur + TILE_A_BYTES, ab, j, s);
-#pragma unroll
-                for (int j = 0; j < 2; j++)
-#pragma unroll
-                    for (int i = 0; i < 2; i++)
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rb[j], ra[i], acc[j][i], 0, 0, 0);
+                for (int j = 0; j < 2; j++) {
+                    const bf16x8 rb = TB::frag(cur + TILE_A_BYTES, ab, j, s);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra, rb, acc[j], 0, 0, 0);
+                }
             }
             FHPC_WAIT_LGKM0();
             wg_barrier();
             stage ^= 1;
         }
         FHPC_WAIT_VM(0);        // the last trip's requests (past the end of the rank: zeros) still land in LDS
-        wg_barrier();
     }
 
-    // ---- (3) scaling * A B -> fp32 tile
-    const int l32 = lane & 31, hi = lane >> 5;
+    // ---- rows[q]: row kw + q of the wave's block, lane = column.  One half-wave swap per register
+    // pair turns (block 0 | block 1) x (rows of the lower | upper lanes) into (row | row + 4) x 64 columns.
+    float rows[32];
 #pragma unroll
-    for (int j = 0; j < 2; j++)
-#pragma unroll
-        for (int i = 0; i < 2; i++) {
-            const int row = wave_k0 + 32 * i + l32;
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                f32x4 o;
-                o.x = acc[j][i][4 * g + 0] * p.scaling;
-                o.y = acc[j][i][4 * g + 1] * p.scaling;
-                o.z = acc[j][i][4 * g + 2] * p.scaling;
-                o.w = acc[j][i][4 * g + 3] * p.scaling;
-                *reinterpret_cast<f32x4*>(lds + t_off(row, wave_n0 + 32 * j + 8 * g + 4 * hi)) = o;
-            }
-        }
-    __syncthreads();
-    if constexpr (WMODE == W_INT8 || WMODE == W_INT4) {
-        // element (k, n) of the tile belongs to exactly one thread here: code * scale is exact in
-        // fp32, the sum is rounded once
-        const int col = tid >> 1, rbase = (tid & 1) * 64;
-#pragma unroll
-        for (int e = 0; e < 64; e++) {
-            int code;
-            if constexpr (WMODE == W_INT8) {
-                const uint32_t w = (e & 4) ? q8[e >> 3].y : q8[e >> 3].x;
-                code = __builtin_amdgcn_sbfe((int)w, 8 * (e & 3), 8);
-            } else {
-                const u32x4 v = q4[e >> 5];
-                const uint32_t w = ((e >> 3) & 3) == 0 ? v.x : ((e >> 3) & 3) == 1 ? v.y : ((e >> 3) & 3) == 2 ? v.z : v.w;
-                code = __builtin_amdgcn_sbfe((int)w, 4 * (e & 7), 4);
-            }
-            float* t = reinterpret_cast<float*>(lds + t_off(rbase + e, col));
-            *t += (float)code * wscale;
-        }
-        __syncthreads();
+    for (int v = 0; v < 16; v++) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, acc[0][v] * p.scaling),
+                                                         __builtin_bit_cast(uint32_t, acc[1][v] * p.scaling), false, false);
+        rows[8 * (v / 4) + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[0]);
+        rows[8 * (v / 4) + 4 + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[1]);
     }
-
-    // ---- (4) rows out
 #pragma unroll
-    for (int q = 0; q < PASSES; q++) {
-        const int row = orow + 16 * q;
-        const int k = k0 + row, n = n0 + oc * 8;
-        f32x4 lo = *reinterpret_cast<const f32x4*>(lds + t_off(row, oc * 8));
-        f32x4 hi4 = *reinterpret_cast<const f32x4*>(lds + t_off(row, oc * 8 + 4));
+    for (int q = 0; q < 32; q += 2) {
+        float o0 = rows[q], o1 = rows[q + 1];
         if constexpr (WMODE == W_BF16) {
-            const u32x4 w = wreg[q];
-            lo.x += bf16_lo(w.x); lo.y += bf16_hi(w.x); lo.z += bf16_lo(w.y); lo.w += bf16_hi(w.y);
-            hi4.x += bf16_lo(w.z); hi4.y += bf16_hi(w.z); hi4.z += bf16_lo(w.w); hi4.w += bf16_hi(w.w);
+            // the word holds this lane's column and its neighbour's for one of the two rows; the
+            // neighbour holds the other row: swap the halves that belong to each other
+            const uint32_t dw = wb[q / 2];
+            const uint32_t got = swap_with_neighbour((lane & 1) ? (dw & 0xffffu) : (dw >> 16));
+            o0 += __builtin_bit_cast(float, ((lane & 1) ? got : (dw & 0xffffu)) << 16);
+            o1 += __builtin_bit_cast(float, ((lane & 1) ? (dw >> 16) : got) << 16);
+        } else if constexpr (WMODE == W_INT8) {
+            const uint32_t w = (q & 4) ? q8[q / 8].y : q8[q / 8].x;
+            o0 += (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4), 8) * wscale;      // (the builtin's result type is unsigned)
+            o1 += (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4) + 8, 8) * wscale;
+        } else if constexpr (WMODE == W_INT4) {
+            const uint32_t d = (q / 8 == 0) ? q4.x : (q / 8 == 1) ? q4.y : (q / 8 == 2) ? q4.z : q4.w;
+            o0 += (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8), 4) * wscale;
+            o1 += (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8) + 4, 4) * wscale;
         }
-        if (k < p.K && n < p.N) {
-            if constexpr (OUT_F32) {
-                float* dst = reinterpret_cast<float*>(p.out) + (size_t)k * (size_t)p.N + (size_t)n;
-                *reinterpret_cast<f32x4*>(dst) = lo;
-                *reinterpret_cast<f32x4*>(dst + 4) = hi4;
-            } else {
-                u32x4 o;
-                o.x = pack_bf16(lo.x, lo.y);
-                o.y = pack_bf16(lo.z, lo.w);
-                o.z = pack_bf16(hi4.x, hi4.y);
-                o.w = pack_bf16(hi4.z, hi4.w);
-                *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.out) + (size_t)k * (size_t)p.N + (size_t)n) = o;
-            }
+        if constexpr (OUT_F32) {
+            const int k = kw + q;
+            if (k < p.K && n < p.N) reinterpret_cast<float*>(p.out)[(size_t)k * (size_t)p.N + (size_t)n] = o0;
+            if (k + 1 < p.K && n < p.N) reinterpret_cast<float*>(p.out)[(size_t)(k + 1) * (size_t)p.N + (size_t)n] = o1;
+        } else {
+            // bf16: two columns per 32-bit store.  An even lane stores (n, n + 1) of row q, its odd
+            // neighbour (n - 1, n) of row q + 1: each instruction writes two rows of 128 bytes.
+            const float got = __builtin_bit_cast(float, swap_with_neighbour(__builtin_bit_cast(uint32_t, (lane & 1) ? o0 : o1)));
+            const uint32_t word = (lane & 1) ? pack_bf16(got, o1) : pack_bf16(o0, got);
+            const int k = pair_row(kw, q, lane);
+            if (k < p.K && n < p.N)
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + (size_t)k * (size_t)p.N + (size_t)(n & ~1)) = word;
         }
     }
 }
