@@ -28,6 +28,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("c2", "gemm_pp<256x128x64,a0,b0,o0>"): 168.0e6 + 16.8e6,    # dH = dY B^T
     ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 98.0e6 + 134.2e6,    # dX = dH A^T
     ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 227.2e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
+    # profiles/bench_merge_c5_int4_to_bf16.txt: mean over the layer's seven weights (algorithmic 115.1 MB)
+    ("merge", "merge<int4>"): 37.8e6 + 90.6e6,
 }
 
 
@@ -42,6 +44,8 @@ def parse_args():
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
                          "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
     ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
+    ap.add_argument("--shape", default="", help="c4/c5 only: K,N of a single frozen weight in place of the configuration's "
+                                                "(large weights show the streaming kernel's rate beyond the fixed launch cost)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (removes the host's launch cost; "
                          "meant for the few-token runs, where a step is a handful of microsecond-scale kernels)")
@@ -188,7 +192,7 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
+def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None):
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20240213)
@@ -209,9 +213,10 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
         M = tokens or 4096
         # four independent copies of the layer (own W, X, dY), run back to back: one copy's buffers
         # (0.17 GB) would sit in the 256 MB Infinity Cache from step to step
-        calls = [QlinearCall(fhpc, M, 4096, 8, 4096, 8, gen, 2.0, recompute, forward_only) for _ in range(4)]
-        desc = "config 4: int8 per-channel frozen W 4096x4096 + rank-8 branch, %d tokens, bf16, %s, 4 buffer sets per step" % (
-            M, "fwd" if forward_only else "fwd+bwd")
+        K, N = shape or (4096, 4096)
+        calls = [QlinearCall(fhpc, M, K, 8, N, 8, gen, 2.0, recompute, forward_only) for _ in range(1 if shape else 4)]
+        desc = "config 4: int8 per-channel frozen W %dx%d + rank-8 branch, %d tokens, bf16, %s, %d buffer set(s) per step" % (
+            K, N, M, "fwd" if forward_only else "fwd+bwd", len(calls))
         dtype = "bf16"
     elif name == "merge":
         d, f = 5120, 13824
@@ -221,11 +226,11 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False):
         dtype = "bf16"
     else:
         d, f = 5120, 13824
-        shp = [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
+        shp = [shape] if shape else [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
         M = tokens or 4096
         calls = [QlinearCall(fhpc, M, K, 16, N, 4, gen, 2.0, recompute, forward_only) for K, N in shp]
-        desc = "config 5: Llama-2-13B decoder layer, 7 linears, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
-            M, "fwd" if forward_only else "fwd+bwd")
+        desc = "config 5: %s, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
+            "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
     return calls, desc, dtype
 
@@ -297,7 +302,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only)
+    shape = tuple(int(v) for v in args.shape.split(",")) if args.shape else None
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape)
     flops = sum(c.flops() for c in calls)
     io_bytes = sum(c.io_bytes() for c in calls)
 
