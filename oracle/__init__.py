@@ -232,6 +232,23 @@ def merge(W, A, B, s: float = 1.0):
     return Wp
 
 
+# ---------------------------------------------------------------- factor pair from a pretrained weight
+
+def lowrank_factorize(W, r: int):
+    """Rank-r factor pair of a pretrained weight (Sec. 4.1 item 2: W is decomposed into A[K,r] and
+    B[r,N], which initialise the factorised layer).  The paper names no algorithm; the reading taken
+    here is the best rank-r approximation in the Frobenius norm, i.e. the singular value
+    decomposition W = U S V^T cut after the r largest singular values, with the factors balanced:
+    A = U_r S_r^(1/2), B = S_r^(1/2) V_r^T.  numpy's LAPACK SVD serves as the step.
+    Returns (A, B, s) with s all singular values, largest first."""
+    W = _d(W)
+    K, N = W.shape
+    assert 1 <= r <= min(K, N)
+    U, s, Vt = np.linalg.svd(W, full_matrices=False)
+    root = np.sqrt(s[:r])
+    return U[:, :r] * root[None, :], root[:, None] * Vt[:r, :], s
+
+
 # ---------------------------------------------------------------- SiLU gate
 
 def swiglu_fwd(G, U):

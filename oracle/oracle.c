@@ -20,7 +20,8 @@
  * Pins: every function below is pinned by tests/test_oracle_*.py (association
  * identity, gradient identities, finite differences, adjoint test, numpy fp64
  * cross-check, hand-built exact quantisation cases, exhaustive nibble table).
- * No function here is "parity unpinned".
+ * No function here is "parity unpinned".  (The rank-r factorisation of a pretrained weight, which
+ * needs a singular value decomposition, lives in the Python wrapper and uses numpy's.)
  */
 #include <math.h>
 #include <stdint.h>
