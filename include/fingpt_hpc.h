@@ -66,7 +66,7 @@ enum {
 
 /* which entry point a workspace is sized for */
 enum { FHPC_OP_LOWRANK_FWD = 0, FHPC_OP_LOWRANK_BWD = 1, FHPC_OP_QLINEAR_FWD = 2, FHPC_OP_QLINEAR_BWD = 3,
-       FHPC_OP_MERGE = 4 };
+       FHPC_OP_MERGE = 4, FHPC_OP_DECOMPOSE = 5 };
 
 /* Factorised linear layer, forward (Sec. 3.2 eq. low_rank_layer; Sec. 4.1 "Method 1"):
  *   Y[M,N] = (X[M,K] * A[K,r]) * B[r,N].
@@ -131,7 +131,7 @@ int qlinear_blend_bwd(const void* X, const void* Wq, const void* scales, int qsc
 
 /* Bytes of workspace the entry point `op` (FHPC_OP_*) needs for these sizes.
  * Host-only; returns 0 for invalid arguments (and for FHPC_OP_MERGE when it needs none).  qscheme is
- * ignored for op 0/1/4; M and dtype are ignored for op 4. */
+ * ignored for op 0/1/4/5; M and dtype are ignored for op 4/5. */
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme);
 
 /* SiLU-gated product between the FFN's linears (Sec. 3.1 eq. FFN):
@@ -168,6 +168,23 @@ int qweight_quantize(const float* W, int qscheme, int block, void* Wq_out, void*
 int lowrank_merge(const void* W, const void* scales, int qscheme, int block, const void* A, const void* B,
                   float scaling, void* W_out, int out_dtype, int64_t K, int64_t r, int64_t N,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Factor pair from a pretrained weight (Sec. 4.1 item 2: W is decomposed into A[K,r] and B[r,N], which
+ * initialise the factorised layer; Sec. 4.2 "weight decomposition in parallel": the same-shape weights of
+ * different decoder layers are handled by one call, `batch` of them stored back to back).  The paper
+ * names no algorithm.  Here: randomised subspace iteration on the matrix cores,
+ *   Y = W Omega;  repeat power_iters times { Z = W^T Y, orthonormalise Z, Y = W Z };  A = orthonormalised Y;
+ *   B = (A^T A)^-1 A^T W   (the least-squares fit for this A, so that A B is the projection of W on span A),
+ * with the orthonormalisation done by matrix products only (polynomial iterations on the Gram matrix).
+ * W: bf16 [batch][K][N];  Omega: bf16 [N][r], a random test matrix from the caller (standard normal
+ * entries; the same one serves every weight of the batch);  A_out: bf16 [batch][K][r], columns orthonormal
+ * up to bf16 rounding;  B_out: bf16 [batch][r][N].  With power_iters around 2 the error |W - A B|_F is
+ * within a few per cent of the best rank-r approximation's for spectra that decay, and equal to it up to
+ * rounding when W has rank r.  r must be a multiple of 8 and at most min(K, N) (else FHPC_ERR_UNSUPPORTED);
+ * 0 <= power_iters <= 16.  Workspace: FHPC_OP_DECOMPOSE (M, dtype, qscheme ignored). */
+int lowrank_decompose(const void* W, const void* Omega, int power_iters, void* A_out, void* B_out,
+                      int64_t K, int64_t r, int64_t N, int64_t batch,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Integer codes of a stored weight, q_out int8 [N][K] (scheme 8: a copy; scheme 4:
  * sign-extended nibbles, including the code -8).  Bit-exact. */

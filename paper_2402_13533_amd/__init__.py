@@ -17,10 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
 FHPC_F32, FHPC_BF16 = 0, 1
 FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
 FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N] in place of Wq, scales None
-FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE = 0, 1, 2, 3, 4
+FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE, FHPC_OP_DECOMPOSE = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
-    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge",
+    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
@@ -54,6 +54,7 @@ def load_library():
     lib.qlinear_blend_fwd.argtypes = lib.qlinear_lowrank_fwd.argtypes
     lib.qlinear_blend_bwd.argtypes = lib.qlinear_lowrank_bwd.argtypes
     lib.lowrank_merge.argtypes = [vp, vp, i32, i32, vp, vp, f32, vp, i32, i64, i64, i64, vp, sz, vp]
+    lib.lowrank_decompose.argtypes = [vp, vp, i32, vp, vp, i64, i64, i64, i64, vp, sz, vp]
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
     lib.fhpc_workspace_bytes.restype = sz
     lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -372,6 +373,32 @@ def lowrank_merge(W, scales, qscheme, A, B, scaling=1.0, block=64, out_dtype=Non
     if rc:
         raise FhpcError(rc, "lowrank_merge")
     return W_out
+
+
+def lowrank_decompose(W, r, Omega=None, power_iters=2, seed=0, workspace=None):
+    """Rank-r factor pair (A, B) of a pretrained weight W (bf16 [K,N] or a batch [L,K,N]).  Omega: the
+    bf16 [N,r] random test matrix; drawn here from `seed` (standard normal) when not given."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    batched = W.dim() == 3
+    L = W.shape[0] if batched else 1
+    K, N = W.shape[-2], W.shape[-1]
+    _check(W, "W", None, bf)
+    if Omega is None:
+        g = torch.Generator(device=W.device)
+        g.manual_seed(seed)
+        Omega = torch.randn((N, r), device=W.device, dtype=torch.float32, generator=g).to(bf)
+    _check(Omega, "Omega", (N, r), bf)
+    A = torch.empty((L, K, r) if batched else (K, r), dtype=bf, device=W.device)
+    B = torch.empty((L, r, N) if batched else (r, N), dtype=bf, device=W.device)
+    need = workspace_bytes(FHPC_OP_DECOMPOSE, 1, K, r, N)
+    ws = workspace if workspace is not None else get_workspace(need, W.device)
+    rc = lib.lowrank_decompose(_ptr(W), _ptr(Omega), int(power_iters), _ptr(A), _ptr(B), K, r, N, L,
+                               _ptr(ws), C.c_size_t(ws.numel() * ws.element_size()), _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_decompose")
+    return A, B
 
 
 def qweight_unpack(Wq, qscheme):

@@ -353,6 +353,111 @@ int lowrank_bwd_f32(const float* X, const float* A, const float* B, const float*
     return FHPC_OK;
 }
 
+// ---------------- rank-r factor pair of a pretrained weight ----------------
+// Everything is a matrix product on the bf16 matrix cores plus r x r elementwise kernels.
+struct DecompScratch {
+    void* Yb;      // bf16 [K][r]
+    void* Zb;      // bf16 [N][r]
+    void* Qt;      // bf16 [max(K,N)][r]   orthonormalised Z
+    float* F;      // fp32 [max(K,N)][r]   unsplit fp32 output before rounding
+    float* G;      // fp32 [r][r]
+    void* Gb;      // bf16 [r][r]
+    void* G2b;     // bf16 [r][r]
+    void* Sb;      // bf16 [r][r]
+    float* Mf[6];  // fp32 [r][r] each: the r x r iteration of orthonormalise
+    float* T;      // fp32 [r][N]
+    void* Tb;      // bf16 [r][N]
+    void* Cb;      // bf16 [r][N]
+    float* part;   // partial-sum slabs of the split reductions
+};
+
+DecompScratch carve_decompose(Carver& c, int64_t K, int64_t r, int64_t N)
+{
+    DecompScratch d;
+    const int64_t R = K > N ? K : N;
+    d.Yb = c.take(K * r * 2);
+    d.Zb = c.take(N * r * 2);
+    d.Qt = c.take(R * r * 2);
+    d.F = static_cast<float*>(c.take(R * r * 4));
+    d.G = static_cast<float*>(c.take(r * r * 4));
+    d.Gb = c.take(r * r * 2);
+    d.G2b = c.take(r * r * 2);
+    d.Sb = c.take(r * r * 2);
+    for (int i = 0; i < 6; i++) d.Mf[i] = static_cast<float*>(c.take(r * r * 4));
+    d.T = static_cast<float*>(c.take(r * N * 4));
+    d.Tb = c.take(r * N * 2);
+    d.Cb = c.take(r * N * 2);
+    int64_t part = split_bytes(r, r, r, R);            // Gram matrices
+    const int64_t p2 = split_bytes(N, r, r, K);        // Z = W^T Y
+    const int64_t p3 = split_bytes(r, N, N, K);        // T = A^T W
+    if (p2 > part) part = p2;
+    if (p3 > part) part = p3;
+    d.part = static_cast<float*>(c.take(part));
+    return d;
+}
+
+// P[M][n] (bf16, dense) = sum_k a(m,k) b(j,k) with both operands stored reduction-major
+int product_tn_bf16(GemmOperand a, GemmOperand b, void* P, int64_t M, int64_t n, int64_t Kred, const DecompScratch& d, hipStream_t st)
+{
+    bool done = false;
+    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, b, d.F, n, M, n, Kred, 1.f, d.part, st, P, &done));
+    if (!done) FHPC_HIP(launch_compact_f32(d.F, n, P, n, M, n, 1.f, true, st));
+    return FHPC_OK;
+}
+
+// fp32 r x r product C = A B (transpose_a: C = A^T B): fp32 operands and accumulation on the matrix cores
+hipError_t small_mm(const float* A, bool transpose_a, const float* B, float* C, int64_t r, hipStream_t st)
+{
+    return launch_mm_f32(A, transpose_a, r, B, r, C, r, r, r, r, st);
+}
+
+// Columns of Y[R][r] (bf16) replaced by an orthonormal basis of their span: out = Y M with an r x r
+// matrix M built by products only.  The iteration  Q <- Q (a I + b G + c G^2),  G = Q^T Q,  is run on M
+// alone: with G0 = Y^T Y (one product over the long dimension, fp32) the Gram matrix of Q = Y M is
+// M^T G0 M, so every step costs r x r products in fp32 and Y is touched twice in all (G0 and the final
+// Y M).  That matters for accuracy, not only for time: Q rounded to bf16 after every step would drift out
+// of the span of Y by 2^-9 per step, and the error of the factor pair is exactly that drift.
+// `quintic` steps use coefficients that lift small singular values fast (they settle in about
+// [0.7, 1.15] instead of converging), then `cubic` steps (1.5, -0.5) converge to 1 quadratically from
+// there.  The first step divides by the Frobenius norm (trace of G0) so that no singular value starts
+// above 1.
+int orthonormalise(const void* Y, void* out, int64_t R, int64_t r, int quintic, int cubic, const DecompScratch& d, hipStream_t st)
+{
+    float* const G0 = d.G;
+    float* M = d.Mf[0];
+    float* Mn = d.Mf[1];
+    float* const P = d.Mf[2];
+    float* const Gi = d.Mf[3];
+    float* const G2 = d.Mf[4];
+    float* const S = d.Mf[5];
+    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(Y, r), operand(Y, r), G0, r, r, r, R, 1.f, d.part, st));
+    for (int i = 0; i < quintic + cubic; i++) {
+        const bool first = (i == 0), q5 = (i < quintic);
+        const float* g = G0;
+        if (!first) {
+            FHPC_HIP(small_mm(G0, false, M, P, r, st));            // P = G0 M
+            FHPC_HIP(small_mm(M, true, P, Gi, r, st));             // Gi = M^T G0 M
+            g = Gi;
+        }
+        float* dst = first ? M : S;                                 // the first step's polynomial is M itself
+        if (q5) {
+            // the first step works on G0 / trace: Gi = that, G2 its square
+            if (first) FHPC_HIP(launch_gram_poly(G0, nullptr, Gi, false, r, 0.f, 1.f, 0.f, 1, st));
+            FHPC_HIP(small_mm(first ? Gi : g, false, first ? Gi : g, G2, r, st));
+            FHPC_HIP(launch_gram_poly(g, G2, dst, false, r, 3.4445f, -4.7750f, 2.0315f, first ? 2 : 0, st));
+        } else {
+            FHPC_HIP(launch_gram_poly(g, nullptr, dst, false, r, 1.5f, -0.5f, 0.f, first ? 2 : 0, st));
+        }
+        if (!first) {
+            FHPC_HIP(small_mm(M, false, S, Mn, r, st));            // M <- M S
+            float* t = M; M = Mn; Mn = t;
+        }
+    }
+    FHPC_HIP(launch_compact_f32(M, r, d.Sb, r, r, r, 1.f, true, st));
+    FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(Y, r), operand(d.Sb, r), out, r, R, r, r, st));
+    return FHPC_OK;
+}
+
 int check_q(int qscheme, int block, int64_t K)
 {
     if (qscheme != FHPC_Q_INT8_PER_CHANNEL && qscheme != FHPC_Q_INT4_BLOCK) return FHPC_ERR_DTYPE;
@@ -369,6 +474,12 @@ extern "C" {
 
 size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme)
 {
+    if (op == FHPC_OP_DECOMPOSE) {
+        if (check_common(1, K, r, N) != FHPC_OK || (r % 8) || r > K || r > N) return 0;
+        Carver dry(nullptr);
+        carve_decompose(dry, K, r, N);
+        return dry.used;
+    }
     if (op == FHPC_OP_MERGE) {
         // a zero-padded copy of A when the rank is not a multiple of 8; M, dtype and qscheme are ignored
         if (check_common(1, K, r, N) != FHPC_OK) return 0;
@@ -706,6 +817,57 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
         Ap = workspace;
     }
     FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
+    return FHPC_OK;
+}
+
+int lowrank_decompose(const void* W, const void* Omega, int power_iters, void* A_out, void* B_out,
+                      int64_t K, int64_t r, int64_t N, int64_t batch,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!W || !Omega || !A_out || !B_out) return FHPC_ERR_NULL;
+    int rc = check_common(1, K, r, N);
+    if (rc) return rc;
+    if (batch < 1 || power_iters < 0 || power_iters > 16) return FHPC_ERR_SHAPE;
+    if ((r % 8) || r > K || r > N) return FHPC_ERR_UNSUPPORTED;
+    if (K * N * 2 >= kMaxBytes) return FHPC_ERR_UNSUPPORTED;
+    if (!aligned(W, 16) || !aligned(Omega, 16) || !aligned(A_out, 16) || !aligned(B_out, 16)) return FHPC_ERR_ALIGN;
+    Carver dry(nullptr);
+    carve_decompose(dry, K, r, N);
+    if (!workspace || workspace_bytes < dry.used) return FHPC_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    const DecompScratch d = carve_decompose(c, K, r, N);
+    constexpr int kQuintic = 8, kCubic = 3;
+    for (int64_t l = 0; l < batch; l++) {
+        const void* Wl = static_cast<const uint16_t*>(W) + l * K * N;
+        void* Al = static_cast<uint16_t*>(A_out) + l * K * r;
+        void* Bl = static_cast<uint16_t*>(B_out) + l * r * N;
+        const GemmOperand w = operand(Wl, N);
+        // Y = W Omega, then `power_iters` rounds of  Z = W^T Y, orthonormalise, Y = W Z
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(Omega, r), d.Yb, r, K, r, N, st));
+        for (int it = 0; it < power_iters; it++) {
+            rc = product_tn_bf16(w, operand(d.Yb, r), d.Zb, N, r, K, d, st);
+            if (rc) return rc;
+            rc = orthonormalise(d.Zb, d.Qt, N, r, kQuintic, kCubic, d, st);
+            if (rc) return rc;
+            FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(d.Qt, r), d.Yb, r, K, r, N, st));
+        }
+        rc = orthonormalise(d.Yb, Al, K, r, kQuintic, kCubic, d, st);                           // A = the basis, as it is used below
+        if (rc) return rc;
+        // B = (A^T A)^-1 A^T W, the least-squares fit given this very A.  G = A^T A = I + E with E small, so
+        // G^-1 - I = -E + E^2 - E^3 (+ ...) and B = T + (G^-1 - I) T with T = A^T W.
+        const GemmOperand a = operand(Al, r);
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, w, d.T, N, r, N, K, 1.f, d.part, st));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, a, d.G, r, r, r, K, 1.f, d.part, st));
+        FHPC_HIP(launch_gram_poly(d.G, nullptr, d.Gb, true, r, -1.f, 1.f, 0.f, 0, st));        // Gb = E = G - I
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Gb, r), d.G2b, r, r, r, r, st));   // E^2
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.G2b, r), operand(d.Gb, r), d.Sb, r, r, r, r, st));   // E^3
+        FHPC_HIP(launch_neumann(d.G, d.G2b, d.Sb, d.Gb, r, st));                               // Gb = -E + E^2 - E^3
+        FHPC_HIP(launch_compact_f32(d.T, N, d.Tb, N, r, N, 1.f, true, st));
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Tb, N), d.Cb, N, r, N, r, st));
+        FHPC_HIP(launch_add_f32_bf16(d.T, d.Cb, Bl, r * N, st));
+    }
     return FHPC_OK;
 }
 

@@ -23,6 +23,13 @@ hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64
                               float scale, bool to_bf16, hipStream_t s);
 // out: fp32, or bf16 when to_bf16 (n a multiple of 4)
 hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out, bool to_bf16, hipStream_t s);
+// C = A' B in fp32 on the matrix cores, A' = A or A^T; dimensions multiples of 4, rows 16-byte aligned
+hipError_t launch_mm_f32(const float* A, bool transpose_a, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                         int64_t M, int64_t N, int64_t K, hipStream_t s);
+// r x r helpers of the rank-r factorisation (see kernels_misc.hip)
+hipError_t launch_gram_poly(const float* G, const float* G2, void* out, bool to_bf16, int64_t r, float a, float b, float c, int mode, hipStream_t s);
+hipError_t launch_neumann(const float* G, const void* E2, const void* E3, void* out, int64_t r, hipStream_t s);
+hipError_t launch_add_f32_bf16(const float* a, const void* b, void* out, int64_t n, hipStream_t s);
 hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s);
 
 }  // namespace fhpc

@@ -554,6 +554,151 @@ __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p,
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
+// ---------------------------------------------------------------------------------
+// Small r x r helpers of the rank-r factorisation (iterations that orthonormalise a tall matrix
+// with matrix products only: every step is "Gram matrix -> polynomial of it -> product").
+// ---------------------------------------------------------------------------------
+
+// C[M][N] = A' B in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation),
+// A' = A (M x K, row-major) or A^T (A is K x M), B is K x N; all dimensions multiples of 4, rows 16-byte
+// aligned.  Workgroup tile 64 x 64, one 32 x 32 block per wave, 32-deep steps staged in LDS with the
+// reduction index outermost so that the 32 lanes of an operand read are 32 consecutive floats.
+constexpr int MMF_T = 64, MMF_K = 32, MMF_LD = MMF_T + 4;
+template <bool TRANSPOSE_A>
+__global__ __launch_bounds__(256) void mm_f32_kernel(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
+                                                     float* __restrict__ C, int ldc, int M, int N, int K)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef __attribute__((ext_vector_type(16))) float f32x16;
+    __shared__ float As[MMF_K][MMF_LD];
+    __shared__ float Bs[MMF_K][MMF_LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * MMF_T, n0 = blockIdx.x * MMF_T;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    for (int k0 = 0; k0 < K; k0 += MMF_K) {
+        // 64 x 32 floats of each operand: 512 pieces of four, two per thread
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int p = tid + 256 * j;
+            f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (TRANSPOSE_A) {
+                const int k = p >> 4, m = (p & 15) * 4;                 // A[k][m .. m+3]
+                if (k0 + k < K && m0 + m < M) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(k0 + k) * lda + m0 + m);
+                *reinterpret_cast<f32x4*>(&As[k][m]) = a;
+            } else {
+                const int m = p >> 3, k = (p & 7) * 4;                  // A[m][k .. k+3]
+                if (m0 + m < M && k0 + k < K) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(m0 + m) * lda + k0 + k);
+                As[k][m] = a.x; As[k + 1][m] = a.y; As[k + 2][m] = a.z; As[k + 3][m] = a.w;
+            }
+            const int kb = p >> 4, n = (p & 15) * 4;                    // B[k][n .. n+3]
+            if (k0 + kb < K && n0 + n < N) b = *reinterpret_cast<const f32x4*>(B + (int64_t)(k0 + kb) * ldb + n0 + n);
+            *reinterpret_cast<f32x4*>(&Bs[kb][n]) = b;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < MMF_K; kk += 2) {
+            const float a = As[kk + (lane >> 5)][wm + (lane & 31)];
+            const float b = Bs[kk + (lane >> 5)][wn + (lane & 31)];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    const int n = n0 + wn + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+        const int m = m0 + wm + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+        if (m < M && n < N) C[(int64_t)m * ldc + n] = acc[v];
+    }
+}
+
+hipError_t launch_mm_f32(const float* A, bool transpose_a, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                         int64_t M, int64_t N, int64_t K, hipStream_t s)
+{
+    const dim3 grid((unsigned)((N + MMF_T - 1) / MMF_T), (unsigned)((M + MMF_T - 1) / MMF_T));
+    if (transpose_a) hipLaunchKernelGGL(mm_f32_kernel<true>, grid, dim3(256), 0, s, A, (int)lda, B, (int)ldb, C, (int)ldc, (int)M, (int)N, (int)K);
+    else hipLaunchKernelGGL(mm_f32_kernel<false>, grid, dim3(256), 0, s, A, (int)lda, B, (int)ldb, C, (int)ldc, (int)M, (int)N, (int)K);
+    return hipGetLastError();
+}
+
+// trace of an r x r fp32 matrix, summed by one workgroup in a fixed order
+__device__ __forceinline__ float block_trace(const float* __restrict__ G, int r)
+{
+    __shared__ float red[256];
+    float t = 0.f;
+    for (int i = threadIdx.x; i < r; i += 256) t += G[(int64_t)i * r + i];
+    red[threadIdx.x] = t;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    return red[0];
+}
+
+// out = post * (a I + b * pre * G + c * G2), fp32 or bf16.  mode 0: pre = post = 1.  mode 1: pre = 1 / trace(G),
+// post = 1.  mode 2: pre = 1 / trace(G), post = sqrt(pre) (the first step of an iteration on a matrix
+// Q that has not been scaled: Q / |Q|_F has the Gram matrix G / trace(G)).  G2 (fp32) may be NULL.
+template <bool TO_BF16>
+__global__ __launch_bounds__(256) void gram_poly_kernel(const float* __restrict__ G, const float* __restrict__ G2,
+                                                        void* __restrict__ out, int r, float a, float b, float c, int mode)
+{
+    float pre = 1.f, post = 1.f;
+    if (mode) {
+        const float t = block_trace(G, r);
+        pre = (t > 0.f) ? 1.f / t : 0.f;
+        if (mode == 2) post = sqrtf(pre);
+    }
+    const int64_t total = (int64_t)r * r;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        float v = b * pre * G[i];
+        if (G2) v += c * G2[i];
+        if (i / r == i % r) v += a;
+        if constexpr (TO_BF16) reinterpret_cast<uint16_t*>(out)[i] = float_to_bf16_bits(post * v);
+        else reinterpret_cast<float*>(out)[i] = post * v;
+    }
+}
+
+hipError_t launch_gram_poly(const float* G, const float* G2, void* out, bool to_bf16, int64_t r, float a, float b, float c, int mode, hipStream_t s)
+{
+    if (to_bf16) hipLaunchKernelGGL(gram_poly_kernel<true>, dim3(grid_for(r * r)), dim3(256), 0, s, G, G2, out, (int)r, a, b, c, mode);
+    else hipLaunchKernelGGL(gram_poly_kernel<false>, dim3(grid_for(r * r)), dim3(256), 0, s, G, G2, out, (int)r, a, b, c, mode);
+    return hipGetLastError();
+}
+
+// out (bf16) = -(G - I) + E2 - E3: the first terms of the inverse of G = I + E around the identity, minus I
+__global__ __launch_bounds__(256) void neumann_kernel(const float* __restrict__ G, const uint16_t* __restrict__ E2,
+                                                      const uint16_t* __restrict__ E3, uint16_t* __restrict__ out, int r)
+{
+    const int64_t total = (int64_t)r * r;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const float e = G[i] - ((i / r == i % r) ? 1.f : 0.f);
+        out[i] = float_to_bf16_bits(-e + bf16_bits_to_float(E2[i]) - bf16_bits_to_float(E3[i]));
+    }
+}
+
+hipError_t launch_neumann(const float* G, const void* E2, const void* E3, void* out, int64_t r, hipStream_t s)
+{
+    hipLaunchKernelGGL(neumann_kernel, dim3(grid_for(r * r)), dim3(256), 0, s, G, (const uint16_t*)E2, (const uint16_t*)E3, (uint16_t*)out, (int)r);
+    return hipGetLastError();
+}
+
+// out (bf16) = a (fp32) + b (bf16)
+__global__ __launch_bounds__(256) void add_f32_bf16_kernel(const float* __restrict__ a, const uint16_t* __restrict__ b,
+                                                           uint16_t* __restrict__ out, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        out[i] = float_to_bf16_bits(a[i] + bf16_bits_to_float(b[i]));
+}
+
+hipError_t launch_add_f32_bf16(const float* a, const void* b, void* out, int64_t n, hipStream_t s)
+{
+    hipLaunchKernelGGL(add_f32_bf16_kernel, dim3(grid_for(n)), dim3(256), 0, s, a, (const uint16_t*)b, (uint16_t*)out, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s)
 {
     const int64_t n = bytes / 4;

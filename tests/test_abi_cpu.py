@@ -95,6 +95,17 @@ def test_validation_precedes_launch():
     assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, nul, C.c_size_t(0), nul) == 5              # odd rank needs a workspace
     assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, ws, C.c_size_t(64), nul) == 5
     assert mg(p, p, 8, 64, p, p, one, p, 1, 1 << 16, 8, 1 << 16, nul, C.c_size_t(0), nul) == 6    # >= 2 GiB
+    dc = lib.lowrank_decompose
+    assert dc(p, nul, 2, p, p, 64, 8, 64, 1, ws, big, nul) == 1                                   # NULL Omega
+    assert dc(p, p, 2, p, p, 64, 8, 60, 1, ws, big, nul) == 2                                     # N % 8
+    assert dc(p, p, 99, p, p, 64, 8, 64, 1, ws, big, nul) == 2                                    # power_iters
+    assert dc(p, p, 2, p, p, 64, 8, 64, 0, ws, big, nul) == 2                                     # batch
+    assert dc(p, p, 2, p, p, 64, 12, 64, 1, ws, big, nul) == 6                                    # rank not a multiple of 8
+    assert dc(p, p, 2, p, p, 64, 72, 64, 1, ws, big, nul) == 6                                    # rank above min(K, N)
+    assert dc(p, p, 2, odd, p, 64, 8, 64, 1, ws, big, nul) == 4
+    assert dc(p, p, 2, p, p, 64, 8, 64, 1, ws, C.c_size_t(1024), nul) == 5
+    assert fhpc.workspace_bytes(fhpc.FHPC_OP_DECOMPOSE, 1, 4096, 512, 4096) > 3 * 4096 * 512 * 2
+    assert fhpc.workspace_bytes(fhpc.FHPC_OP_DECOMPOSE, 1, 64, 12, 64) == 0
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 8, 64) == 0
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 64 * 8 * 2
 
