@@ -349,10 +349,9 @@ def main():
                for n, a in agg.items()}
     roofline = None
     if agg:
-        # the kernel the roofline is quoted for: the streaming kernel when the run has one (few tokens),
-        # else the GEMM with the largest share of time
-        streaming = [n for n in agg if agg[n][3] > 0]
-        dom = max(streaming or agg, key=lambda n: agg[n][1])
+        # the kernel the roofline is quoted for: the one with the largest share of the timed kernels'
+        # time (a GEMM, quoted in TFLOP/s, or a streaming kernel, quoted in GB/s on its algorithmic bytes)
+        dom = max(agg, key=lambda n: agg[n][1])
         k = kernels[dom]
         share = agg[dom][1] / sum(a[1] for a in agg.values())
         if k["gbs"] is not None:

@@ -51,11 +51,19 @@ struct Scratch {
     float* dB_t = nullptr;  // fp32 [rp][N]
     float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
     float* Yf = nullptr;    // fp32 [M][N]    factorised layer, few tokens: unsplit second product
+    void* Wm = nullptr;     // bf16 [K][N]    base_scale * deq(W) + scaling * A B, many tokens (see many_tokens)
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
+
+// With many tokens the frozen-weight product dominates the finetuning layer, and the plain bf16 kernels
+// (operands through global -> LDS requests) run it about 1.5 times faster than the kernels that
+// dequantise the weight in their load path.  One pass that writes  base_scale * deq(W) + scaling * A B
+// as bf16 [K][N] costs what about 600 token rows of that product cost, and removes the rank-r branch
+// from the big product as well (W' x = W x + s B A x, Sec. 5.1).  288 GB of HBM make room for it.
+bool many_tokens(int64_t M) { return M >= 1024; }
 
 // The factorised layer's forward for at most one 32-row tile of tokens is bound by reading A and
 // B once: its products are then spread over the chip by splitting their reductions.
@@ -139,6 +147,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     const int64_t rp = rank_pad(r);
     const bool bwd = (op == FHPC_OP_LOWRANK_BWD || op == FHPC_OP_QLINEAR_BWD);
+    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && many_tokens(M)) s.Wm = c.take(K * N * 2);
     if (rp != r) {
         s.A_p = c.take(K * rp * 2);
         s.B_p = c.take(rp * N * 2);
@@ -187,19 +196,36 @@ int check_common(int64_t M, int64_t K, int64_t r, int64_t N)
     return FHPC_OK;
 }
 
-// Tile for an M x N output.  The narrow tiles exist only for the split
-// rank-r products, so they are offered only when `allow_skinny`.
+// Tile for an M x N output.  The narrow tiles exist only for the split rank-r products, so they are
+// offered only when `allow_skinny`.  Among the four large tiles the choice follows the time the launch
+// should take: rounds of resident workgroups x tile area x a per-flop penalty of the smaller shapes
+// (measured on 4096-token products: 256x128 about 5 % behind 256x256 per flop, 128x256 25 %, 128x128
+// 50 %; the 128x128 kernel runs two workgroups per compute unit).  What it decides in practice: an
+// output of 320 tiles of 256x256 (4096 tokens x 5120 channels) would run two rounds, the second a
+// quarter full; as 640 tiles of 256x128 it runs 2.5 (measured 196 against 217 microseconds).
 int pick_tile(int64_t M, int64_t N, bool allow_skinny)
 {
     if (allow_skinny && N <= 32) return TILE_256x32;
     if (allow_skinny && M <= 32) return TILE_32x256;
     const int order[4] = {TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128};
+    const double penalty[4] = {1.0, 1.05, 1.25, 1.5};
+    const int per_cu[4] = {1, 1, 1, 2};
+    // only shapes that give every compute unit a tile compete; an output too small for that takes the
+    // smallest tile
     int best = TILE_128x128;
-    for (int t : order) {
+    double best_cost = -1.0;
+    for (int i = 0; i < 4; i++) {
         int bm, bn;
-        gemm_tile_extent(t, &bm, &bn);
+        gemm_tile_extent(order[i], &bm, &bn);
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-        if (tiles >= kNumCU) return t;
+        if (tiles < kNumCU) continue;
+        const int64_t slots = (int64_t)kNumCU * per_cu[i];
+        const int64_t rounds = (tiles + slots - 1) / slots;
+        const double cost = (double)rounds * bm * bn * per_cu[i] * penalty[i];      // co-resident workgroups share the unit
+        if (best_cost < 0.0 || cost < best_cost) {
+            best = order[i];
+            best_cost = cost;
+        }
     }
     return best;
 }
@@ -606,6 +632,17 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
+    const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+    if (s.Wm && base_scale != 0.f) {
+        // many tokens: one plain product with the merged weight; H only if the caller wants it
+        FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(X, K), operand(s.Wm, N), Y, N, M, N, K, st));
+        if (H_out) {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
+            if (rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
+        }
+        return FHPC_OK;
+    }
     FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
 
     if (base_scale == 0.f) {
@@ -685,10 +722,16 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
             H = s.H;
         }
     }
-    if (dX || dA)
+    const bool merged_dx = (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
+    if (dA || (dX && !merged_dx))
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX && base_scale == 0.f) {
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st, scaling));
+    } else if (dX && merged_dx) {
+        // many tokens: dX = dY W'^T with the merged weight W' = base_scale deq(W) + scaling A B
+        const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+        FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(s.Wm, N), dX, K, M, K, N, st));
     } else if (dX) {
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};
@@ -816,7 +859,7 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
         FHPC_HIP(launch_pad2d_u16(A, r, K, r, workspace, rp, K, st));
         Ap = workspace;
     }
-    FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
+    FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, 1.f, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
     return FHPC_OK;
 }
 

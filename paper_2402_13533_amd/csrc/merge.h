@@ -5,10 +5,10 @@
 
 namespace fhpc {
 
-// out[K][N] (fp32 or bf16) = base + scaling * A B.  w_kind: 0 = no base weight, 1 = bf16 W[K][N],
+// out[K][N] (fp32 or bf16) = base_scale * base + scaling * A B.  w_kind: 0 = no base weight, 1 = bf16 W[K][N],
 // 2 = int8 codes [N][K] + fp16 scale per channel, 3 = 4-bit codes [N][K/2] + fp16 scale per 64 k.
 // A is bf16 [K][lda] with lda a multiple of 8 (columns r .. lda-1 zero), B bf16 [r][N].
 hipError_t launch_merge(const void* W, const void* scales, int w_kind, const void* A, int64_t lda, const void* B,
-                        float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s);
+                        float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s);
 
 }  // namespace fhpc

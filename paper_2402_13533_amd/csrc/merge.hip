@@ -36,6 +36,7 @@ struct MergeArgs {
     GemmOperand a, b;      // A[K][ld] (rank index contiguous), B[r][N]
     void* out;
     float scaling;
+    float base_scale;      // factor on the base weight (1 for the merged weight of Sec. 5.1; alpha for the blend layer)
     int K, N, r;           // r: rank rounded up to a multiple of 8 (the copy of A is zero-padded)
     int r_rows;            // rows of B that exist
 };
@@ -95,11 +96,11 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
             if (n < p.N && kw + 8 * i < p.K)
                 q8[i] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(p.W) + (size_t)n * (size_t)p.K + (size_t)(kw + 8 * i));
         }
-        if (n < p.N) wscale = (float)__builtin_bit_cast(_Float16, p.scales[n]);
+        if (n < p.N) wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[n]);
     } else if constexpr (WMODE == W_INT4) {
         if (n < p.N && kw < p.K) {
             q4 = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(p.W) + ((size_t)n * (size_t)p.K + (size_t)kw) / 2);
-            wscale = (float)__builtin_bit_cast(_Float16, p.scales[(size_t)n * (size_t)(p.K / 64) + (size_t)(kw / 64)]);
+            wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[(size_t)n * (size_t)(p.K / 64) + (size_t)(kw / 64)]);
         }
     }
 
@@ -161,8 +162,8 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
             // neighbour holds the other row: swap the halves that belong to each other
             const uint32_t dw = wb[q / 2];
             const uint32_t got = swap_with_neighbour((lane & 1) ? (dw & 0xffffu) : (dw >> 16));
-            o0 += __builtin_bit_cast(float, ((lane & 1) ? got : (dw & 0xffffu)) << 16);
-            o1 += __builtin_bit_cast(float, ((lane & 1) ? (dw >> 16) : got) << 16);
+            o0 = fmaf(p.base_scale, __builtin_bit_cast(float, ((lane & 1) ? got : (dw & 0xffffu)) << 16), o0);
+            o1 = fmaf(p.base_scale, __builtin_bit_cast(float, ((lane & 1) ? (dw >> 16) : got) << 16), o1);
         } else if constexpr (WMODE == W_INT8) {
             const uint32_t w = (q & 4) ? q8[q / 8].y : q8[q / 8].x;
             o0 += (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4), 8) * wscale;      // (the builtin's result type is unsigned)
@@ -203,7 +204,7 @@ static hipError_t launch(const MergeArgs& a, double w_bytes, hipStream_t s)
 }  // namespace mrg
 
 hipError_t launch_merge(const void* W, const void* scales, int w_kind, const void* A, int64_t lda, const void* B,
-                        float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s)
+                        float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s)
 {
     using namespace mrg;
     MergeArgs a;
@@ -213,6 +214,7 @@ hipError_t launch_merge(const void* W, const void* scales, int w_kind, const voi
     a.b = GemmOperand{B, N, nullptr, 0};
     a.out = out;
     a.scaling = scaling;
+    a.base_scale = base_scale;
     a.K = (int)K;
     a.N = (int)N;
     a.r = (int)lda;

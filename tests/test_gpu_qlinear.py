@@ -118,12 +118,28 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
 
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("M,K,r,N", [
+    (1024, 320, 8, 264),      # the first token count on the merged-weight route
+    (1100, 384, 5, 520),      # ragged in every dimension, rank padded internally
+    (1300, 576, 40, 136),
+])
+def test_qlinear_many_tokens(scheme, M, K, r, N):
+    """From 1024 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
+    products with it (forward and backward, saved and recomputed H, as above)."""
+    if scheme == 4:
+        K = (K + 63) // 64 * 64
+    _run_case("many q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=40)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,K,r,N", [
     (300, 320, 8, 264),
     (1, 64, 16, 72),
     (515, 1024, 5, 520),      # rank padded internally
     (260, 512, 64, 328),
 ])
 def test_qlinear_shapes(scheme, M, K, r, N):
+    """Below 1024 tokens: the weight is dequantised in the GEMM's operand load path and the rank-r
+    branch rides in the same accumulators."""
     if scheme == 4:
         K = (K + 63) // 64 * 64
     _run_case("q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=30)
@@ -223,11 +239,13 @@ def test_few_token_forward_every_code(scheme):
 
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("alpha", [1.0, 0.7, 0.25, 0.0])
-def test_blend_layer(scheme, alpha):
+@pytest.mark.parametrize("M", [300, 1040])
+def test_blend_layer(scheme, alpha, M):
     """Y = alpha X deq(W) + (1 - alpha) (X A) B with W frozen, forward and backward; alpha = 1 is
-    the frozen layer alone (dA = dB = 0), alpha = 0 the factorised layer alone."""
+    the frozen layer alone (dA = dB = 0), alpha = 0 the factorised layer alone.  Both routes (below
+    and from 1024 tokens)."""
     fhpc = _fhpc()
-    M, K, r, N = 300, 320, 24, 264
+    K, r, N = 320, 24, 264
     W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 80)
     B = Bf16.normal(8123, (r, N), r ** -0.5)                 # a branch as large as the base term
     Wq, sc = _quantize_host(W * 50.0, scheme)               # base weight of comparable magnitude
@@ -264,7 +282,7 @@ def test_blend_layer_few_tokens_and_alpha_range():
             fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), bad)
 
 
-@pytest.mark.parametrize("M", [300, 5])
+@pytest.mark.parametrize("M", [300, 5, 1056])
 def test_blend_layer_dense_weight(M):
     """The blend layer with the pretrained weight kept in bf16 (no quantisation): W[K,N] row-major in
     place of the packed codes.  M = 5 checks that the few-token weight-streaming path is not taken
