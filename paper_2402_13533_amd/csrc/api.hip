@@ -379,6 +379,13 @@ int lowrank_bwd_f32(const float* X, const float* A, const float* B, const float*
     return FHPC_OK;
 }
 
+size_t merge_workspace(int64_t K, int64_t r, int64_t N)
+{
+    (void)N;
+    const int64_t rp = rank_pad(r);
+    return (rp != r) ? (size_t)round_up(K * rp * 2, 256) : 0;      // a zero-padded copy of A
+}
+
 // ---------------- rank-r factor pair of a pretrained weight ----------------
 // Everything is a matrix product on the bf16 matrix cores plus r x r elementwise kernels.
 struct DecompScratch {
@@ -509,7 +516,7 @@ size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, 
     if (op == FHPC_OP_MERGE) {
         // a zero-padded copy of A when the rank is not a multiple of 8; M, dtype and qscheme are ignored
         if (check_common(1, K, r, N) != FHPC_OK) return 0;
-        return (r % 8) ? (size_t)round_up(K * rank_pad(r) * 2, 256) : 0;
+        return merge_workspace(K, r, N);
     }
     if (op < FHPC_OP_LOWRANK_FWD || op > FHPC_OP_QLINEAR_BWD) return 0;
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return 0;
@@ -852,8 +859,8 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int64_t rp = rank_pad(r);
     const void* Ap = A;
-    if (rp != r) {
-        const size_t need = (size_t)round_up(K * rp * 2, 256);
+    const size_t need = merge_workspace(K, r, N);
+    if (need) {
         if (!workspace || workspace_bytes < need) return FHPC_ERR_WORKSPACE;
         if (!aligned(workspace, 256)) return FHPC_ERR_ALIGN;
         FHPC_HIP(launch_pad2d_u16(A, r, K, r, workspace, rp, K, st));

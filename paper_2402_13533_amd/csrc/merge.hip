@@ -47,9 +47,120 @@ __device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t x)
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1 /* quad_perm 1 0 3 2 */, 0xf, 0xf, true);
 }
 
-// Row that a lane addresses when rows q (even) and q + 1 are moved as one 32-bit word of two
-// adjacent columns: even lanes take row q, odd lanes row q + 1.
-__device__ __forceinline__ int pair_row(int kw, int q, int lane) { return kw + q + (lane & 1); }
+// Buffer descriptors of the output and of a bf16 base weight: stores and loads then take a 32-bit lane
+// offset plus a scalar row offset, a lane whose column does not exist is parked at an offset the range
+// check drops, and rows past the end are skipped by a scalar branch (they come in whole pairs), so the
+// epilogue spends no vector instructions on addresses or bounds.
+constexpr uint32_t MRG_OOB = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_rsrc(const void* ptr, int K, int N, int elt)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(ptr), 0, K * N * elt, 0x00020000);
+}
+
+// The base weight of a wave's 32 x 64 block in the layout the epilogue works in: lane = column n,
+// 32 rows kw .. kw + 31.
+template <int WMODE>
+struct BaseRegs {
+    uint32_t wb[WMODE == W_BF16 ? 16 : 1];     // bf16 pairs, one word per two rows (even lanes: row 2 q, odd lanes: row 2 q + 1)
+    u32x2 q8[WMODE == W_INT8 ? 4 : 1];         // codes k = kw + 8 i .. + 7 of the lane's channel
+    u32x4 q4;                                  // codes k = kw .. kw + 31
+    float wscale;                              // base_scale * fp16 scale of the lane's channel (and block)
+};
+
+template <int WMODE>
+__device__ __forceinline__ void load_base(BaseRegs<WMODE>& b, const MergeArgs& p, int kw, int n, int lane)
+{
+    b.q4 = (u32x4){0u, 0u, 0u, 0u};
+    b.wscale = 0.f;
+    if constexpr (WMODE == W_BF16) {
+        // the column pair (n & ~1, + 1) of row 2 q (even lanes) or 2 q + 1 (odd lanes); rows past the end
+        // and parked lanes read as zero
+        const __amdgpu_buffer_rsrc_t rw = matrix_rsrc(p.W, p.K, p.N, 2);
+        const uint32_t lane_off = (n < p.N) ? (uint32_t)((kw + (lane & 1)) * p.N + (n & ~1)) * 2u : MRG_OOB;
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            b.wb[q] = 0u;
+            if (kw + 2 * q < p.K) b.wb[q] = __builtin_amdgcn_raw_buffer_load_b32(rw, lane_off, 2 * q * p.N * 2, 0);     // uniform
+        }
+    } else if constexpr (WMODE == W_INT8) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            b.q8[i] = (u32x2){0u, 0u};
+            if (n < p.N && kw + 8 * i < p.K)
+                b.q8[i] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(p.W) + (size_t)n * (size_t)p.K + (size_t)(kw + 8 * i));
+        }
+        if (n < p.N) b.wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[n]);
+    } else if constexpr (WMODE == W_INT4) {
+        if (n < p.N && kw < p.K) {
+            b.q4 = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(p.W) + ((size_t)n * (size_t)p.K + (size_t)kw) / 2);
+            b.wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[(size_t)n * (size_t)(p.K / 64) + (size_t)(kw / 64)]);
+        }
+    }
+}
+
+// out = base_scale * base + scaling * acc for the wave's 32 x 64 block, straight from the accumulators
+// (acc[j]: register v holds row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n_block + 32 j + lane % 32).
+template <int WMODE, bool OUT_F32>
+__device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRegs<WMODE>& b, const MergeArgs& p, int kw, int n, int lane)
+{
+    // rows[q]: row kw + q, lane = column.  One half-wave swap per register pair turns
+    // (block 0 | block 1) x (rows of the lower | upper lanes) into (row | row + 4) x 64 columns.
+    float rows[32];
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+        // (the products are fresh registers for the swap, which exchanges in place; accumulators passed to it
+        // directly came back wrong)
+        const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, acc[0][v] * p.scaling),
+                                                         __builtin_bit_cast(uint32_t, acc[1][v] * p.scaling), false, false);
+        rows[8 * (v / 4) + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[0]);
+        rows[8 * (v / 4) + 4 + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[1]);
+    }
+    const __amdgpu_buffer_rsrc_t ro = matrix_rsrc(p.out, p.K, p.N, OUT_F32 ? 4 : 2);
+    const int rows_valid = p.K - kw;               // rows of this block that exist (scalar)
+    const int rowbytes = p.N * (OUT_F32 ? 4 : 2);
+    const bool odd = lane & 1;
+    // fp32: the lane's own column, rows q and q + 1 in turn.  bf16: the column pair (n & ~1, + 1) of row
+    // q (even lanes) or q + 1 (odd lanes), see below.
+    const uint32_t lane_off = (n < p.N) ? (OUT_F32 ? (uint32_t)(kw * p.N + n) * 4u
+                                                    : (uint32_t)((kw + (odd ? 1 : 0)) * p.N + (n & ~1)) * 2u) : MRG_OOB;
+    // bf16 halves of (own, neighbour) words recombined by one byte permute: even lanes keep their low
+    // half and take the neighbour's low half on top, odd lanes take the neighbour's high half below their own
+    const uint32_t pick = odd ? 0x03020706u : 0x05040100u;
+#pragma unroll
+    for (int q = 0; q < 32; q += 2) {
+        float base0 = 0.f, base1 = 0.f;
+        if constexpr (WMODE == W_BF16) {
+            // the word holds this lane's column and its neighbour's for one of the two rows; the
+            // neighbour holds the other row: swap the halves that belong to each other
+            const uint32_t dw = b.wb[q / 2];
+            const uint32_t got = swap_with_neighbour(odd ? (dw & 0xffffu) : (dw >> 16));
+            base0 = p.base_scale * __builtin_bit_cast(float, (odd ? got : (dw & 0xffffu)) << 16);
+            base1 = p.base_scale * __builtin_bit_cast(float, (odd ? (dw >> 16) : got) << 16);
+        } else if constexpr (WMODE == W_INT8) {
+            const uint32_t w = (q & 4) ? b.q8[q / 8].y : b.q8[q / 8].x;
+            base0 = (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4), 8) * b.wscale;      // (the builtin's result type is unsigned)
+            base1 = (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4) + 8, 8) * b.wscale;
+        } else if constexpr (WMODE == W_INT4) {
+            const uint32_t d = (q / 8 == 0) ? b.q4.x : (q / 8 == 1) ? b.q4.y : (q / 8 == 2) ? b.q4.z : b.q4.w;
+            base0 = (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8), 4) * b.wscale;
+            base1 = (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8) + 4, 4) * b.wscale;
+        }
+        const float o0 = rows[q] + base0;
+        const float o1 = rows[q + 1] + base1;
+        if (q >= rows_valid) continue;             // uniform: K is a multiple of 8, a row pair is in or out as one
+        if constexpr (OUT_F32) {
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o0), ro, lane_off, q * rowbytes, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o1), ro, lane_off, (q + 1) * rowbytes, 0);
+        } else {
+            // bf16: two columns per 32-bit store.  An even lane stores (n, n + 1) of row q, its odd
+            // neighbour (n - 1, n) of row q + 1: each instruction writes two rows of 128 bytes.
+            const uint32_t own = pack_bf16(o0, o1);                          // (row q, row q + 1) of this column
+            const uint32_t nb = swap_with_neighbour(own);                    // the same of the neighbour's column
+            const uint32_t word = __builtin_amdgcn_perm(nb, own, pick);
+            __builtin_amdgcn_raw_buffer_store_b32(word, ro, lane_off, q * rowbytes, 0);
+        }
+    }
+}
 
 template <int WMODE, bool OUT_F32>
 __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
@@ -74,35 +185,10 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     const int kw = k0 + wave_k0;                               // first row of the wave
     // accumulator register v of block j: row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n0 + wave_n0 + 32 j + lane % 32
 
-    // ---- base weight of the wave's 32 x 64 block, requested before anything else, in the layout the
-    // epilogue works in: lane = column n0 + wave_n0 + lane, 32 rows kw .. kw + 31
+    // ---- base weight of the wave's 32 x 64 block, requested before anything else
     const int n = n0 + wave_n0 + lane;
-    uint32_t wb[WMODE == W_BF16 ? 16 : 1];                     // bf16 pairs, one word per two rows (see pair_row)
-    u32x2 q8[WMODE == W_INT8 ? 4 : 1];                         // codes k = kw + 8 i .. + 7 of the lane's channel
-    u32x4 q4 = {0u, 0u, 0u, 0u};                               // codes k = kw .. kw + 31
-    float wscale = 0.f;
-    if constexpr (WMODE == W_BF16) {
-#pragma unroll
-        for (int q = 0; q < 16; q++) {
-            const int k = pair_row(kw, 2 * q, lane);
-            wb[q] = 0u;
-            if (k < p.K && n < p.N)
-                wb[q] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(p.W) + (size_t)k * (size_t)p.N + (size_t)(n & ~1));
-        }
-    } else if constexpr (WMODE == W_INT8) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            q8[i] = (u32x2){0u, 0u};
-            if (n < p.N && kw + 8 * i < p.K)
-                q8[i] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(p.W) + (size_t)n * (size_t)p.K + (size_t)(kw + 8 * i));
-        }
-        if (n < p.N) wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[n]);
-    } else if constexpr (WMODE == W_INT4) {
-        if (n < p.N && kw < p.K) {
-            q4 = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(p.W) + ((size_t)n * (size_t)p.K + (size_t)kw) / 2);
-            wscale = p.base_scale * (float)__builtin_bit_cast(_Float16, p.scales[(size_t)n * (size_t)(p.K / 64) + (size_t)(kw / 64)]);
-        }
-    }
+    BaseRegs<WMODE> base;
+    load_base<WMODE>(base, p, kw, n, lane);
 
     // ---- acc[j] = (A B) block: rows from the A tile, columns from the B tile
     f32x16 acc[2];
@@ -144,49 +230,7 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
         FHPC_WAIT_VM(0);        // the last trip's requests (past the end of the rank: zeros) still land in LDS
     }
 
-    // ---- rows[q]: row kw + q of the wave's block, lane = column.  One half-wave swap per register
-    // pair turns (block 0 | block 1) x (rows of the lower | upper lanes) into (row | row + 4) x 64 columns.
-    float rows[32];
-#pragma unroll
-    for (int v = 0; v < 16; v++) {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, acc[0][v] * p.scaling),
-                                                         __builtin_bit_cast(uint32_t, acc[1][v] * p.scaling), false, false);
-        rows[8 * (v / 4) + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[0]);
-        rows[8 * (v / 4) + 4 + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[1]);
-    }
-#pragma unroll
-    for (int q = 0; q < 32; q += 2) {
-        float o0 = rows[q], o1 = rows[q + 1];
-        if constexpr (WMODE == W_BF16) {
-            // the word holds this lane's column and its neighbour's for one of the two rows; the
-            // neighbour holds the other row: swap the halves that belong to each other
-            const uint32_t dw = wb[q / 2];
-            const uint32_t got = swap_with_neighbour((lane & 1) ? (dw & 0xffffu) : (dw >> 16));
-            o0 = fmaf(p.base_scale, __builtin_bit_cast(float, ((lane & 1) ? got : (dw & 0xffffu)) << 16), o0);
-            o1 = fmaf(p.base_scale, __builtin_bit_cast(float, ((lane & 1) ? (dw >> 16) : got) << 16), o1);
-        } else if constexpr (WMODE == W_INT8) {
-            const uint32_t w = (q & 4) ? q8[q / 8].y : q8[q / 8].x;
-            o0 += (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4), 8) * wscale;      // (the builtin's result type is unsigned)
-            o1 += (float)(int)__builtin_amdgcn_sbfe((int)w, 8 * (q % 4) + 8, 8) * wscale;
-        } else if constexpr (WMODE == W_INT4) {
-            const uint32_t d = (q / 8 == 0) ? q4.x : (q / 8 == 1) ? q4.y : (q / 8 == 2) ? q4.z : q4.w;
-            o0 += (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8), 4) * wscale;
-            o1 += (float)(int)__builtin_amdgcn_sbfe((int)d, 4 * (q % 8) + 4, 4) * wscale;
-        }
-        if constexpr (OUT_F32) {
-            const int k = kw + q;
-            if (k < p.K && n < p.N) reinterpret_cast<float*>(p.out)[(size_t)k * (size_t)p.N + (size_t)n] = o0;
-            if (k + 1 < p.K && n < p.N) reinterpret_cast<float*>(p.out)[(size_t)(k + 1) * (size_t)p.N + (size_t)n] = o1;
-        } else {
-            // bf16: two columns per 32-bit store.  An even lane stores (n, n + 1) of row q, its odd
-            // neighbour (n - 1, n) of row q + 1: each instruction writes two rows of 128 bytes.
-            const float got = __builtin_bit_cast(float, swap_with_neighbour(__builtin_bit_cast(uint32_t, (lane & 1) ? o0 : o1)));
-            const uint32_t word = (lane & 1) ? pack_bf16(got, o1) : pack_bf16(o0, got);
-            const int k = pair_row(kw, q, lane);
-            if (k < p.K && n < p.N)
-                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + (size_t)k * (size_t)p.N + (size_t)(n & ~1)) = word;
-        }
-    }
+    store_block<WMODE, OUT_F32>(acc, base, p, kw, n, lane);
 }
 
 template <int WMODE, bool OUT_F32>
@@ -220,12 +264,20 @@ hipError_t launch_merge(const void* W, const void* scales, int w_kind, const voi
     a.r = (int)lda;
     a.r_rows = (int)r;
     const double kn = (double)K * (double)N;
-    switch (w_kind) {
-    case W_NONE: return out_f32 ? launch<W_NONE, true>(a, 0.0, s) : launch<W_NONE, false>(a, 0.0, s);
-    case W_BF16: return out_f32 ? launch<W_BF16, true>(a, 2.0 * kn, s) : launch<W_BF16, false>(a, 2.0 * kn, s);
-    case W_INT8: return out_f32 ? launch<W_INT8, true>(a, kn + 2.0 * N, s) : launch<W_INT8, false>(a, kn + 2.0 * N, s);
-    case W_INT4: return out_f32 ? launch<W_INT4, true>(a, 0.5 * kn + kn / 32.0, s) : launch<W_INT4, false>(a, 0.5 * kn + kn / 32.0, s);
-    }
+    const double wbytes[4] = {0.0, 2.0 * kn, kn + 2.0 * N, 0.5 * kn + kn / 32.0};
+    if (w_kind < 0 || w_kind > 3) return hipErrorInvalidValue;
+#define FHPC_MERGE_CASE(KIND, F32)                                                                               \
+    if (w_kind == KIND && out_f32 == F32)                                                                        \
+        return launch<KIND, F32>(a, wbytes[KIND], s);
+    FHPC_MERGE_CASE(W_NONE, true)
+    FHPC_MERGE_CASE(W_NONE, false)
+    FHPC_MERGE_CASE(W_BF16, true)
+    FHPC_MERGE_CASE(W_BF16, false)
+    FHPC_MERGE_CASE(W_INT8, true)
+    FHPC_MERGE_CASE(W_INT8, false)
+    FHPC_MERGE_CASE(W_INT4, true)
+    FHPC_MERGE_CASE(W_INT4, false)
+#undef FHPC_MERGE_CASE
     return hipErrorInvalidValue;
 }
 

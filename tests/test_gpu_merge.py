@@ -32,7 +32,7 @@ def _base(kind, K, N, seed):
 
 @pytest.mark.parametrize("out", ["f32", "bf16"])
 @pytest.mark.parametrize("kind", ["none", "bf16", "int8", "int4"])
-@pytest.mark.parametrize("r", [8, 5, 72])
+@pytest.mark.parametrize("r", [8, 5, 24, 40, 72])
 def test_merge_small_ragged(kind, out, r):
     """Three tiles each way with ragged tails; ranks below one slice, not a multiple of 8, and over
     several slices."""
@@ -54,6 +54,28 @@ def test_merge_small_ragged(kind, out, r):
         # element by element: fp32 accumulation of exact products, one rounding of the sum with the base
         bound = 1e-6 * (np.abs(Wd if Wd is not None else 0.0) + abs(s) * (np.abs(A.f64) @ np.abs(B.f64))) + 1e-12
         assert np.all(np.abs(from_device(got) - ref) <= bound)
+
+
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("kind,K", [("none", 328), ("bf16", 328), ("int8", 328), ("int4", 320), ("none", 8)])
+def test_merge_ragged_rows_stay_inside_the_output(kind, K, out):
+    """Row counts that end inside a 32-row block: the output sits in the middle of a larger buffer of
+    sentinels, which must come back untouched on both sides."""
+    import torch
+    fhpc = _fhpc()
+    N, r = 136, 16
+    Wd, W_dev, sc_dev, scheme = _base(kind, K, N, 700 + K)
+    A = Bf16.normal(701, (K, r), 0.05)
+    B = Bf16.normal(702, (r, N), 0.05)
+    dt = torch.float32 if out == "f32" else torch.bfloat16
+    pad = 64 * N
+    buf = torch.full((K * N + 2 * pad,), 77.0, dtype=dt, device="cuda")
+    W_out = buf[pad:pad + K * N].view(K, N)
+    fhpc.lowrank_merge(W_dev, sc_dev, scheme, A.cuda(), B.cuda(), 1.0, W_out=W_out)
+    torch.cuda.synchronize()
+    assert bool((buf[:pad] == 77.0).all()) and bool((buf[pad + K * N:] == 77.0).all())
+    err = oracle.rel_fro(from_device(W_out), oracle.merge(Wd, A.f64, B.f64, 1.0))
+    assert err <= (TOL_F32 if out == "f32" else TOL_BF16)
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
