@@ -4,7 +4,7 @@
 A step is one pass of the whole hot path over one batch of synthetic input that is
 already resident in HBM.  Default workload (config 2): forward + backward of the four
 Llama-2-7B attention projections, each factorised with r = 512, on 16384 tokens in bf16.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|merge]
 """
@@ -293,7 +293,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus %d is not supported (the layer shards over "
-              "tokens with one all-reduce of dA/dB per step, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "tokens with one all-reduce of dA/dB per step)" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2402_13533_amd as fhpc
