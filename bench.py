@@ -44,6 +44,9 @@ def parse_args():
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
                          "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
     ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
+    ap.add_argument("--shared-x", action="store_true",
+                    help="c5 with --tokens and --forward-only: the q/k/v and the gate/up projections read one X each "
+                         "and go through the shared-X entry point (one call per group: qkv, o, gate+up, down)")
     ap.add_argument("--shape", default="", help="c4/c5 only: K,N of a single frozen weight in place of the configuration's "
                                                 "(large weights show the streaming kernel's rate beyond the fixed launch cost)")
     ap.add_argument("--graph", action="store_true",
@@ -139,6 +142,26 @@ class QlinearCall:
                               H_saved=None if self.recompute else self.H, dX=self.dX, dA=self.dA, dB=self.dB)
 
 
+class SharedXCall:
+    """Several quantised projections of one X through qlinear_lowrank_fwd_shared_x (forward only)."""
+
+    def __init__(self, fhpc, calls):
+        self.f = fhpc
+        self.calls = calls
+        self.X = calls[0].X
+        self.scheme = calls[0].scheme
+        self.weights = [(c.Wq, c.sc, c.A, c.B, c.s) for c in calls]
+
+    def flops(self):
+        return sum(c.flops() for c in self.calls)
+
+    def io_bytes(self):
+        return sum(c.io_bytes() for c in self.calls) - 2 * self.X.numel() * (len(self.calls) - 1)
+
+    def run(self):
+        self.f.qlinear_lowrank_fwd_shared_x(self.X, self.weights, self.scheme)
+
+
 class MergeCall:
     """W' = deq(Wq) + scaling A B written as bf16: the adapted weight materialised for inference."""
 
@@ -192,7 +215,7 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None):
+def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False):
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20240213)
@@ -232,6 +255,12 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         desc = "config 5: %s, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
             "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
+    if shared_x:
+        if name != "c5" or not forward_only or shape:
+            raise SystemExit("--shared-x goes with --workload c5 --forward-only")
+        q, k, v, o, gate, up, down = calls
+        calls = [SharedXCall(fhpc, [q, k, v]), o, SharedXCall(fhpc, [gate, up]), down]
+        desc += ", q/k/v and gate/up through the shared-X call"
     return calls, desc, dtype
 
 
@@ -303,7 +332,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     shape = tuple(int(v) for v in args.shape.split(",")) if args.shape else None
-    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape)
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape, args.shared_x)
     flops = sum(c.flops() for c in calls)
     io_bytes = sum(c.io_bytes() for c in calls)
 

@@ -109,6 +109,29 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Finetuning layer, forward, for several weights that read the same X: the q, k, v projections of a
+ * decoder layer, or its gate and up projections (Sec. 3.1 lists them; Sec. 4.2 batches same-shape work).
+ * `weights` is a HOST array of `count` descriptors whose pointers are device pointers laid out as for
+ * qlinear_lowrank_fwd; K, r, the storage scheme and M are shared, N and scaling are per weight.  Each
+ * Y is its own dense [M][N] matrix.  Result: exactly what `count` calls of qlinear_lowrank_fwd give up
+ * to summation order.  With at most 64 tokens (and up to four weights, r <= 64, K a multiple of 512)
+ * all weights go through one pair of launches, which is the point: such a call is bound by launch
+ * latency, not by the weight stream.  Otherwise the weights are processed one after another.
+ * Workspace: fhpc_workspace_bytes_shared_x (host-only; 0 for invalid arguments). */
+typedef struct {
+    const void* Wq;        /* quantised weight, device */
+    const void* scales;    /* fp16 scales, device */
+    const void* A;         /* bf16 [K][r], device */
+    const void* B;         /* bf16 [r][N], device */
+    void* Y;               /* bf16 [M][N], device */
+    void* H_out;           /* bf16 [M][r], device, or NULL */
+    int64_t N;
+    float scaling;
+} fhpc_qlinear_weight;
+int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weights, int count, int qscheme, int block,
+                                 int64_t M, int64_t K, int64_t r, void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t fhpc_workspace_bytes_shared_x(const int64_t* N, int count, int64_t M, int64_t K, int64_t r, int qscheme);
+
 /* Blend of a frozen pretrained weight with the factor pair (Sec. 4.1 item 3:
  * y = alpha W x + (1 - alpha) B A x, 0 <= alpha <= 1, W frozen), with W stored quantised as above:
  *   Y = alpha * X * deq(Wq, scales) + (1 - alpha) * (X * A) * B

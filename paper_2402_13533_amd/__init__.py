@@ -20,13 +20,19 @@ FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N]
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE, FHPC_OP_DECOMPOSE = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
-    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose",
+    "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose", "qlinear_lowrank_fwd_shared_x", "fhpc_workspace_bytes_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
 ]
 
 _lib = None
+
+
+class QlinearWeight(C.Structure):
+    """fhpc_qlinear_weight of the C header."""
+    _fields_ = [("Wq", C.c_void_p), ("scales", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p), ("Y", C.c_void_p),
+                ("H_out", C.c_void_p), ("N", C.c_int64), ("scaling", C.c_float)]
 
 
 class FhpcError(RuntimeError):
@@ -55,6 +61,9 @@ def load_library():
     lib.qlinear_blend_bwd.argtypes = lib.qlinear_lowrank_bwd.argtypes
     lib.lowrank_merge.argtypes = [vp, vp, i32, i32, vp, vp, f32, vp, i32, i64, i64, i64, vp, sz, vp]
     lib.lowrank_decompose.argtypes = [vp, vp, i32, vp, vp, i64, i64, i64, i64, vp, sz, vp]
+    lib.qlinear_lowrank_fwd_shared_x.argtypes = [vp, C.POINTER(QlinearWeight), i32, i32, i32, i64, i64, i64, vp, sz, vp]
+    lib.fhpc_workspace_bytes_shared_x.argtypes = [C.POINTER(i64), i32, i64, i64, i64, i32]
+    lib.fhpc_workspace_bytes_shared_x.restype = sz
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
     lib.fhpc_workspace_bytes.restype = sz
     lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -72,7 +81,7 @@ def load_library():
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
     for name in EXPORTS:
-        if name not in ("fhpc_workspace_bytes", "fhpc_status_string", "fhpc_version"):
+        if name not in ("fhpc_workspace_bytes", "fhpc_workspace_bytes_shared_x", "fhpc_status_string", "fhpc_version"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -347,6 +356,38 @@ def qweight_quantize(W, qscheme, block=64):
     if rc:
         raise FhpcError(rc, "qweight_quantize")
     return Wq, sc
+
+
+def qlinear_lowrank_fwd_shared_x(X, weights, qscheme, block=64, save_H: bool = False, workspace=None):
+    """Forward of several finetuning layers that read the same X.  weights: a list of
+    (Wq, scales, A, B, scaling) tuples.  Returns the list of Y (or of (Y, H) when save_H)."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    M, K = X.shape
+    _check(X, "X", None, bf)
+    count = len(weights)
+    arr = (QlinearWeight * count)()
+    outs = []
+    Ns = (C.c_int64 * count)()
+    r = weights[0][2].shape[1]
+    for j, (Wq, sc, A, B, scaling) in enumerate(weights):
+        N = B.shape[1]
+        _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+        _q_shapes(Wq, sc, qscheme, K, N, block)
+        Y = torch.empty((M, N), dtype=bf, device=X.device)
+        H = torch.empty((M, r), dtype=bf, device=X.device) if save_H else None
+        arr[j] = QlinearWeight(Wq.data_ptr(), sc.data_ptr(), A.data_ptr(), B.data_ptr(), Y.data_ptr(),
+                               0 if H is None else H.data_ptr(), N, float(scaling))
+        Ns[j] = N
+        outs.append((Y, H) if save_H else Y)
+    need = int(lib.fhpc_workspace_bytes_shared_x(Ns, count, M, K, r, qscheme))
+    ws = workspace if workspace is not None else get_workspace(need, X.device)
+    rc = lib.qlinear_lowrank_fwd_shared_x(_ptr(X), arr, count, qscheme, block, M, K, r, _ptr(ws),
+                                          C.c_size_t(ws.numel() * ws.element_size()), _stream())
+    if rc:
+        raise FhpcError(rc, "qlinear_lowrank_fwd_shared_x")
+    return outs
 
 
 def lowrank_merge(W, scales, qscheme, A, B, scaling=1.0, block=64, out_dtype=None, W_out=None, workspace=None):

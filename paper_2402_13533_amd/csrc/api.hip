@@ -140,7 +140,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     if (op == FHPC_OP_QLINEAR_FWD && quantised && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
         // a handful of tokens: the weight-streaming kernels need only their own slabs
-        const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
+        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, kNumCU);
         s.sk_part = static_cast<float*>(c.take(p.part_bytes));
         s.sk_hpart = static_cast<float*>(c.take(p.hpart_bytes));
         return s;
@@ -630,8 +630,9 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, !dense);
     if (s.sk_part) {
-        const QskinnyPlan p = qskinny_plan(M, K, r, N, kNumCU);
-        FHPC_HIP(launch_qskinny_fwd(X, Wq, scales, qscheme, A, B, base_scale, scaling, Y, H_out, M, K, r, N, p, s.sk_part, s.sk_hpart, st));
+        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, kNumCU);
+        const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};
+        FHPC_HIP(launch_qskinny_fwd(X, &job, 1, qscheme, M, K, r, p, s.sk_part, s.sk_hpart, st));
         return FHPC_OK;
     }
     const int64_t rp = rank_pad(r);
@@ -680,6 +681,80 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
     if (qscheme == FHPC_W_BF16) return FHPC_ERR_DTYPE;      // the finetuning layer's weight is quantised
     return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, Y, H_out, M, K, r, N,
                             workspace, workspace_bytes, hip_stream);
+}
+
+// workspace of the shared-X forward: the single-weight need of every weight (the fallback runs them one
+// after another in the same workspace) and, when the weight-streaming kernels take all of them at
+// once, that launch's slabs
+static size_t shared_x_workspace(const int64_t* N, int count, int64_t M, int64_t K, int64_t r, int qscheme)
+{
+    size_t need = 0;
+    for (int j = 0; j < count; j++) {
+        Carver dry(nullptr);
+        carve(dry, FHPC_OP_QLINEAR_FWD, M, K, r, N[j], FHPC_BF16, true);
+        if (dry.used > need) need = dry.used;
+    }
+    if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, kNumCU);
+        const size_t fused = (size_t)round_up(p.part_bytes, 256) + (size_t)round_up(p.hpart_bytes, 256);
+        if (fused > need) need = fused;
+    }
+    return need;
+}
+
+size_t fhpc_workspace_bytes_shared_x(const int64_t* N, int count, int64_t M, int64_t K, int64_t r, int qscheme)
+{
+    if (!N || count < 1 || count > 64) return 0;
+    for (int j = 0; j < count; j++)
+        if (check_common(M, K, r, N[j]) != FHPC_OK) return 0;
+    return shared_x_workspace(N, count, M, K, r, qscheme);
+}
+
+int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weights, int count, int qscheme, int block,
+                                 int64_t M, int64_t K, int64_t r, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !weights) return FHPC_ERR_NULL;
+    if (count < 1 || count > 64) return FHPC_ERR_SHAPE;
+    int rc = check_q(qscheme, block, K);
+    if (rc) return rc;
+    int64_t N[64];
+    for (int j = 0; j < count; j++) {
+        const fhpc_qlinear_weight& w = weights[j];
+        if (!w.Wq || !w.scales || !w.A || !w.B || !w.Y) return FHPC_ERR_NULL;
+        rc = check_common(M, K, r, w.N);
+        if (rc) return rc;
+        if (!aligned(w.Wq, 16) || !aligned(w.scales, 16) || !aligned(w.A, 16) || !aligned(w.B, 16) || !aligned(w.Y, 16) ||
+            !aligned(w.H_out, 16))
+            return FHPC_ERR_ALIGN;
+        N[j] = w.N;
+    }
+    if (!aligned(X, 16)) return FHPC_ERR_ALIGN;
+    const size_t need = shared_x_workspace(N, count, M, K, r, qscheme);
+    if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
+        // few tokens: every weight in one pair of launches
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, kNumCU);
+        Carver c(workspace);
+        float* part = static_cast<float*>(c.take(p.part_bytes));
+        float* hpart = static_cast<float*>(c.take(p.hpart_bytes));
+        QskinnyJob jobs[QSKINNY_MAX_JOBS];
+        for (int j = 0; j < count; j++) {
+            const fhpc_qlinear_weight& w = weights[j];
+            jobs[j] = QskinnyJob{w.Wq, w.scales, w.A, w.B, w.Y, w.H_out, w.N, 1.f, w.scaling};
+        }
+        FHPC_HIP(launch_qskinny_fwd(X, jobs, count, qscheme, M, K, r, p, part, hpart, st));
+        return FHPC_OK;
+    }
+    // otherwise: the single-weight path, one weight after another on the stream
+    for (int j = 0; j < count; j++) {
+        const fhpc_qlinear_weight& w = weights[j];
+        rc = qlinear_fwd_impl(X, w.Wq, w.scales, qscheme, block, w.A, w.B, 1.f, w.scaling, w.Y, w.H_out, M, K, r, w.N,
+                              workspace, workspace_bytes, hip_stream);
+        if (rc) return rc;
+    }
+    return FHPC_OK;
 }
 
 int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,

@@ -44,6 +44,47 @@ constexpr int STEP = 512;              // reduction depth per pipeline step
 constexpr int HCHUNK = 128;            // reduction depth per workgroup of the H = X A kernel
 constexpr uint32_t OOB = 0x80000000u;
 
+// Up to four weights that share X (the q/k/v or the gate/up projections of a decoder layer) go through
+// one launch: their 64-channel row blocks are numbered one after the other (rb0[j] = first block of
+// weight j, rb0[count] = all), and a workgroup finds its weight from its block number.
+struct SkinnyJobs {
+    const void* Wq[QSKINNY_MAX_JOBS];
+    const void* scales[QSKINNY_MAX_JOBS];
+    const void* A[QSKINNY_MAX_JOBS];
+    const void* B[QSKINNY_MAX_JOBS];
+    void* Y[QSKINNY_MAX_JOBS];
+    void* H_out[QSKINNY_MAX_JOBS];
+    int N[QSKINNY_MAX_JOBS];
+    int rb0[QSKINNY_MAX_JOBS + 1];
+    float base_scale[QSKINNY_MAX_JOBS];
+    float scaling[QSKINNY_MAX_JOBS];
+    int count;
+};
+
+__device__ __forceinline__ int job_of_block(const SkinnyJobs& jb, int rb)
+{
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < QSKINNY_MAX_JOBS; i++) j += (i < jb.count && rb >= jb.rb0[i]) ? 1 : 0;
+    return j;
+}
+__device__ __forceinline__ int pick_rb0(const SkinnyJobs& jb, int j)
+{
+    int v = jb.rb0[0];
+#pragma unroll
+    for (int i = 1; i < QSKINNY_MAX_JOBS; i++) v = (j == i) ? jb.rb0[i] : v;
+    return v;
+}
+// element j of a small array in the kernel arguments, j uniform: a chain of selects, no indexed memory
+template <typename T>
+__device__ __forceinline__ T pick(const T (&a)[QSKINNY_MAX_JOBS], int j)
+{
+    T v = a[0];
+#pragma unroll
+    for (int i = 1; i < QSKINNY_MAX_JOBS; i++) v = (j == i) ? a[i] : v;
+    return v;
+}
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -160,10 +201,9 @@ __device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const ui
 }
 
 template <int SCHEME, int TT>
-__global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, const void* __restrict__ Wq,
-                                                         const void* __restrict__ scales, float* __restrict__ part,
-                                                         int M, int K, int N, int k_chunk,
-                                                         const void* __restrict__ A, float* __restrict__ hpart, int r, int main_grid)
+__global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, SkinnyJobs jb, float* __restrict__ part,
+                                                         int M, int K, int k_chunk, float* __restrict__ hpart, int r,
+                                                         int kchunks, int main_grid)
 {
     constexpr bool I4 = (SCHEME == 4);
     constexpr int WLOADS = I4 ? 4 : 8;               // 16-byte weight loads per lane per step
@@ -174,15 +214,24 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XS_BYTES];
     unsigned char* const xs[2] = {smem, smem + XS_BYTES};
     if ((int)blockIdx.x >= main_grid) {
-        hpart_body<TOKS>(smem, (int)blockIdx.x - main_grid, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(A), hpart, M, K, r);
+        // the H = X A chunks: kchunks workgroups per weight
+        const int idx = (int)blockIdx.x - main_grid, hj = idx / kchunks, kc = idx - hj * kchunks;
+        hpart_body<TOKS>(smem, kc, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(pick(jb.A, hj)),
+                         hpart + (int64_t)hj * kchunks * M * r, M, K, r);
         return;
     }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int row_blocks = (N + ROWS_WG - 1) / ROWS_WG;
+    const int row_blocks = jb.rb0[jb.count];                   // of all weights together
     const int rb = blockIdx.x % row_blocks, split = blockIdx.x / row_blocks;
-    const int n0 = rb * ROWS_WG + wave * 16;
+    const int job = job_of_block(jb, rb);
+    const int N = pick(jb.N, job);
+    const void* const Wq = pick(jb.Wq, job);
+    const void* const scales = pick(jb.scales, job);
+    const int n0 = (rb - pick_rb0(jb, job)) * ROWS_WG + wave * 16;      // channel within its weight
+    const int ncomb0 = rb * ROWS_WG + wave * 16;                       // column in the combined slabs
+    const int ld_part = row_blocks * ROWS_WG;
     const int kbeg = split * k_chunk;
     const int kend = (kbeg + k_chunk < K) ? kbeg + k_chunk : K;
     const int steps = (kend - kbeg + STEP - 1) / STEP;
@@ -370,7 +419,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 #pragma unroll
                 for (int v = 0; v < 4; v++) o[v] = ch_scale[v] * (acc[tt][v] - 128.f * ones_acc[tt][v]);
             }
-            *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + m) * N + n) = o;
+            *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + m) * ld_part + ncomb0 + 4 * g) = o;
         }
     }
 }
@@ -382,14 +431,23 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 constexpr int FTOK = 4;
 template <int RMAX>
 __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
-                                                    const float* __restrict__ hpart, int kchunks,
-                                                    const uint16_t* __restrict__ B, float base_scale, float scaling,
-                                                    uint16_t* __restrict__ Y, uint16_t* __restrict__ H_out,
-                                                    int M, int N, int r)
+                                                    const float* __restrict__ hpart_all, int kchunks,
+                                                    SkinnyJobs jb, int M, int r)
 {
     __shared__ float Hs[FTOK * RMAX];
     __shared__ float Hg[NT];
-    const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int rb = blockIdx.x;                                 // 64-channel block in the combined numbering
+    const int job = job_of_block(jb, rb);
+    const int N = pick(jb.N, job);
+    const uint16_t* const B = static_cast<const uint16_t*>(pick(jb.B, job));
+    uint16_t* const Y = static_cast<uint16_t*>(pick(jb.Y, job));
+    uint16_t* const H_out = static_cast<uint16_t*>(pick(jb.H_out, job));
+    const float base_scale = pick(jb.base_scale, job), scaling = pick(jb.scaling, job);
+    const float* const hpart = hpart_all + (int64_t)job * kchunks * M * r;
+    const bool first_block = (rb == pick_rb0(jb, job));
+    const int ld_part = jb.rb0[jb.count] * 64;
+    const int ncomb = rb * 64 + (threadIdx.x & 63);
+    const int n = (rb - pick_rb0(jb, job)) * 64 + (threadIdx.x & 63);
     const int m0 = blockIdx.y * FTOK;
     const int m = m0 + (threadIdx.x >> 6);
     const bool live = n < N && m < M;
@@ -398,7 +456,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
     for (int j = 0; j < RMAX; j++) b[j] = (live && j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
     float base = 0.f;
     if (live)
-        for (int sp = 0; sp < splits; sp++) base += part[((int64_t)sp * M + m) * N + n];
+        for (int sp = 0; sp < splits; sp++) base += part[((int64_t)sp * M + m) * ld_part + ncomb];
     // H of this group's tokens = sum of the chunk partial sums, all 256 threads sharing the loads:
     // thread (o, g) adds the chunks g, g + G, ... of output o, then the G group sums are added in
     // group order (the same order every run).  The tokens of a group are consecutive, so their
@@ -428,7 +486,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
         float t = 0.f;
         for (int q = 0; q < G; q++) t += Hg[q * outs + threadIdx.x];
         Hs[threadIdx.x] = t;
-        if (H_out && blockIdx.x == 0) {
+        if (H_out && first_block) {
             const __bf16 hb = (__bf16)t;
             H_out[(int64_t)m0 * r + threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
         }
@@ -452,10 +510,11 @@ bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
     return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
 }
 
-QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
+QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int count, int num_cu)
 {
     QskinnyPlan p;
-    const int64_t row_blocks = (N + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
+    int64_t row_blocks = 0;
+    for (int j = 0; j < count; j++) row_blocks += (N[j] + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
     const int64_t ksteps = K / skinny::STEP;
     // One round of workgroups: as many as are resident at once (registers and the token tiles' LDS
     // allow three per compute unit with 16 tokens, two with 32, one with 64) and no more, so that
@@ -468,25 +527,40 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, int64_t N, int num_cu)
     p.k_chunk = (int)(per * skinny::STEP);
     p.splits = (int)((ksteps + per - 1) / per);
     p.kchunks = (int)((K + skinny::HCHUNK - 1) / skinny::HCHUNK);
-    p.part_bytes = (int64_t)p.splits * M * N * 4;
-    p.hpart_bytes = (int64_t)p.kchunks * M * r * 4;
+    p.row_blocks = (int)row_blocks;
+    p.part_bytes = (int64_t)p.splits * M * row_blocks * skinny::ROWS_WG * 4;
+    p.hpart_bytes = (int64_t)count * p.kchunks * M * r * 4;
     return p;
 }
 
-hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales, int scheme, const void* A, const void* B,
-                              float base_scale, float scaling, void* Y, void* H_out, int64_t M, int64_t K, int64_t r, int64_t N,
+hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, int scheme, int64_t M, int64_t K, int64_t r,
                               const QskinnyPlan& p, float* part, float* hpart, hipStream_t st)
 {
     using namespace skinny;
-    const int64_t row_blocks = (N + ROWS_WG - 1) / ROWS_WG;
-    const int main_grid = (int)(row_blocks * p.splits);
-    const dim3 grid((unsigned)(main_grid + p.kchunks));     // streaming workgroups, then the H = X A chunks
-    const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
-    const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * (double)N,
-                                wbytes + 2.0 * M * K + 4.0 * p.splits * M * N, st);
+    if (count < 1 || count > QSKINNY_MAX_JOBS) return hipErrorInvalidValue;
+    SkinnyJobs jb = {};
+    jb.count = count;
+    double wbytes = 0.0, nsum = 0.0;
+    int rb = 0;
+    for (int j = 0; j < QSKINNY_MAX_JOBS; j++) {
+        const QskinnyJob& q = jobs[j < count ? j : 0];          // unused slots repeat the first weight
+        jb.Wq[j] = q.Wq; jb.scales[j] = q.scales; jb.A[j] = q.A; jb.B[j] = q.B; jb.Y[j] = q.Y; jb.H_out[j] = q.H_out;
+        jb.N[j] = (int)q.N; jb.base_scale[j] = q.base_scale; jb.scaling[j] = q.scaling;
+        jb.rb0[j] = rb;
+        if (j < count) {
+            rb += (int)((q.N + ROWS_WG - 1) / ROWS_WG);
+            wbytes += (scheme == 4) ? (double)q.N * K / 2 + (double)q.N * (K / 64) * 2 : (double)q.N * K + (double)q.N * 2;
+            nsum += (double)q.N;
+        }
+    }
+    for (int j = count; j <= QSKINNY_MAX_JOBS; j++) jb.rb0[j] = rb;
+    const int main_grid = rb * p.splits;
+    const dim3 grid((unsigned)(main_grid + count * p.kchunks));     // streaming workgroups, then the H = X A chunks
+    const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * nsum,
+                                wbytes + 2.0 * M * K + 4.0 * p.splits * M * nsum, st);
 #define FHPC_MAIN(SCHEME, TT)                                                                                       \
-    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT>), grid, dim3(NT), 0, st, X, Wq, scales, part, (int)M, (int)K, (int)N, \
-                       p.k_chunk, A, hpart, (int)r, main_grid)
+    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT>), grid, dim3(NT), 0, st, X, jb, part, (int)M, (int)K,        \
+                       p.k_chunk, hpart, (int)r, p.kchunks, main_grid)
     const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
     if (scheme == 4) {
         if (tt == 1) FHPC_MAIN(4, 1); else if (tt == 2) FHPC_MAIN(4, 2); else FHPC_MAIN(4, 4);
@@ -497,12 +571,10 @@ hipError_t launch_qskinny_fwd(const void* X, const void* Wq, const void* scales,
     prof_end(slot, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 fgrid((unsigned)((N + 63) / 64), (unsigned)((M + FTOK - 1) / FTOK));
+    const dim3 fgrid((unsigned)rb, (unsigned)((M + FTOK - 1) / FTOK));
     const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
-#define FHPC_FINISH(RMAX)                                                                                           \
-    hipLaunchKernelGGL((finish_kernel<RMAX>), fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks,              \
-                       static_cast<const uint16_t*>(B), base_scale, scaling, static_cast<uint16_t*>(Y),             \
-                       static_cast<uint16_t*>(H_out), (int)M, (int)N, (int)r)
+#define FHPC_FINISH(RMAX) \
+    hipLaunchKernelGGL((finish_kernel<RMAX>), fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks, jb, (int)M, (int)r)
     if (r <= 16) FHPC_FINISH(16); else FHPC_FINISH(64);
 #undef FHPC_FINISH
     prof_end(fslot, st);

@@ -95,6 +95,16 @@ def test_validation_precedes_launch():
     assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, nul, C.c_size_t(0), nul) == 5              # odd rank needs a workspace
     assert mg(p, p, 8, 64, p, p, one, p, 1, 64, 5, 64, ws, C.c_size_t(64), nul) == 5
     assert mg(p, p, 8, 64, p, p, one, p, 1, 1 << 16, 8, 1 << 16, nul, C.c_size_t(0), nul) == 6    # >= 2 GiB
+    sx = lib.qlinear_lowrank_fwd_shared_x
+    wts = (fhpc.QlinearWeight * 2)(fhpc.QlinearWeight(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0, 64, 1.0),
+                                   fhpc.QlinearWeight(0x10000, 0x10000, 0x10000, 0x10000, 0, 0, 64, 1.0))
+    assert sx(p, wts, 2, 8, 64, 4, 512, 8, ws, big, nul) == 1                                     # second weight has no Y
+    assert sx(p, wts, 0, 8, 64, 4, 512, 8, ws, big, nul) == 2                                     # count
+    assert sx(p, wts, 1, 5, 64, 4, 512, 8, ws, big, nul) == 3                                     # scheme
+    assert sx(p, wts, 1, 8, 64, 4, 512, 8, nul, C.c_size_t(0), nul) == 5                          # workspace
+    ns = (C.c_int64 * 2)(64, 128)
+    assert lib.fhpc_workspace_bytes_shared_x(ns, 2, 4, 512, 8, 8) >= 4 * 192 * 4
+    assert lib.fhpc_workspace_bytes_shared_x(ns, 0, 4, 512, 8, 8) == 0
     dc = lib.lowrank_decompose
     assert dc(p, nul, 2, p, p, 64, 8, 64, 1, ws, big, nul) == 1                                   # NULL Omega
     assert dc(p, p, 2, p, p, 64, 8, 60, 1, ws, big, nul) == 2                                     # N % 8

@@ -216,6 +216,34 @@ def test_few_token_forward(scheme, M, K, r, N):
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M", [1, 16, 40, 100])
+def test_shared_x_forward(scheme, M):
+    """Three projections that read the same X (widths as with grouped key/value heads, one of them not a
+    multiple of 64) in one call: up to 64 tokens they share one pair of launches, at 100 tokens the call
+    runs them one after another.  Every output against the oracle's single layer."""
+    fhpc = _fhpc()
+    K, r = 1024, 16
+    widths = (520, 136, 200)
+    X = Bf16.normal(6100, (M, K), 1.0)
+    weights, refs = [], []
+    for j, N in enumerate(widths):
+        W, _, A, B, _ = qlinear_inputs(8, 8, K, r, N, 110 + 10 * j)
+        Wq, sc = _quantize_host(W, scheme)
+        Wq_d, sc_d = _to_dev(Wq, sc)
+        s = 2.0 - 0.5 * j
+        weights.append((Wq_d, sc_d, A.cuda(), B.cuda(), s))
+        refs.append(oracle.qlinear_lowrank_fwd(X.f64, oracle.dequant(Wq, sc, scheme, 64), A.f64, B.f64, s))
+    outs = fhpc.qlinear_lowrank_fwd_shared_x(X.cuda(), weights, scheme, save_H=True)
+    for j, ((Y, H), (Yr, Hr)) in enumerate(zip(outs, refs)):
+        eY, eH = oracle.rel_fro(from_device(Y), Yr), oracle.rel_fro(from_device(H), Hr)
+        print("shared X q%d M=%d weight %d: Y %.3e H %.3e" % (scheme, M, j, eY, eH), flush=True)
+        assert eY <= TOL_BF16 and eH <= TOL_BF16
+    plain = fhpc.qlinear_lowrank_fwd_shared_x(X.cuda(), weights, scheme)
+    for j in range(len(widths)):
+        assert np.array_equal(from_device(plain[j]), from_device(outs[j][0]))
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
 def test_few_token_forward_every_code(scheme):
     """Random bytes as codes (so the 4-bit code -8 and the int8 code -128 occur) with random
     positive fp16 scales, subnormals included; scaling 0 isolates the frozen weight."""
