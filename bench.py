@@ -21,7 +21,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side traffic per launch of a kernel on a workload (fetched + written bytes), from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_c2_lowrank_gemm_kernels.txt
 # (counter units scaled by a 256 MiB read + 256 MiB write kernel in the same run); None where
-# not measured.  Algorithmic bytes of the same launches are 155-160 MB.
+# not measured.  Algorithmic bytes of the config 2 launches are 155-160 MB.
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "gemm_pp<256x128x64,a0,b1,o0>"): 168.0e6 + 16.8e6,    # H = X A
     ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 94.1e6 + 134.2e6,    # Y = H B
@@ -29,7 +29,18 @@ MEASURED_TRAFFIC_BYTES = {
     ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 98.0e6 + 134.2e6,    # dX = dH A^T
     ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 227.2e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
     # profiles/bench_merge_c5_int4_to_bf16.txt: mean over the layer's seven weights (algorithmic 115.1 MB)
-    ("merge", "merge<int4>"): 37.8e6 + 90.6e6,
+    ("merge", "merge<int4>"): 38.6e6 + 90.6e6,
+    # profiles/bench_c3_ffn_kernels.txt: means over the launches of a step (they differ in shape)
+    ("c3", "gemm_pp<256x256x32,a0,b1,o0>"): 375.8e6 + 159.4e6,
+    ("c3", "gemm_pp<256x256x32,a0,b0,o0>"): 375.7e6 + 121.6e6,
+    ("c3", "gemm_pp<256x256x32,a1,b1,o1>"): 734.2e6 + 82.6e6,
+    # profiles/bench_c4_int8_qlinear_kernels.txt (algorithmic 100.7 MB: X, the merged weight, Y)
+    ("c4", "gemm_pp<256x256x32,a0,b1,o0>"): 201.5e6 + 33.6e6,
+    ("c4", "gemm_pp<256x256x32,a0,b0,o0>"): 201.5e6 + 33.6e6,
+    # profiles/bench_c5_int4_qlinear_kernels.txt: means over the seven linears (algorithmic 132 MB read, 62 / 52 MB
+    # written): the 256x128 launch order gives each XCD's L2 a panel it cannot hold
+    ("c5", "gemm_pp<256x128x64,a0,b1,o0>"): 1021.9e6 + 62.3e6,
+    ("c5", "gemm_pp<256x128x64,a0,b0,o0>"): 1082.4e6 + 52.1e6,
 }
 
 
