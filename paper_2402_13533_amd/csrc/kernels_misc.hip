@@ -559,57 +559,54 @@ __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p,
 // with matrix products only: every step is "Gram matrix -> polynomial of it -> product").
 // ---------------------------------------------------------------------------------
 
-// C[M][N] = A' B in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation),
+// C[M][N] = A' B in fp32 on the matrix cores (v_mfma_f32_16x16x4_f32: fp32 operands, fp32 accumulation),
 // A' = A (M x K, row-major) or A^T (A is K x M), B is K x N; all dimensions multiples of 4, rows 16-byte
-// aligned.  Workgroup tile 64 x 64, one 32 x 32 block per wave, 32-deep steps staged in LDS with the
-// reduction index outermost so that the 32 lanes of an operand read are 32 consecutive floats.
-constexpr int MMF_T = 64, MMF_K = 32, MMF_LD = MMF_T + 4;
+// aligned.  The matrices here are a few hundred rows, so the tile is small on purpose: a workgroup covers
+// 32 x 32 of the output with one 16 x 16 block per wave (a 512 x 512 product is then 1024 waves, one per
+// SIMD of the chip, instead of 256 that each work four times as long).  32-deep steps are staged in LDS
+// with the reduction index outermost, so that the 16 lanes of an operand read are consecutive floats; the
+// row stride of 48 floats keeps the four k rows of one read on different banks.
+constexpr int MMF_T = 32, MMF_K = 32, MMF_LD = 48;
 template <bool TRANSPOSE_A>
 __global__ __launch_bounds__(256) void mm_f32_kernel(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
                                                      float* __restrict__ C, int ldc, int M, int N, int K)
 {
     typedef __attribute__((ext_vector_type(4))) float f32x4;
-    typedef __attribute__((ext_vector_type(16))) float f32x16;
-    __shared__ float As[MMF_K][MMF_LD];
-    __shared__ float Bs[MMF_K][MMF_LD];
+    __shared__ __attribute__((aligned(16))) float As[MMF_K][MMF_LD];
+    __shared__ __attribute__((aligned(16))) float Bs[MMF_K][MMF_LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.y * MMF_T, n0 = blockIdx.x * MMF_T;
-    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
-    f32x16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    const int wm = (wave >> 1) * 16, wn = (wave & 1) * 16;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < K; k0 += MMF_K) {
-        // 64 x 32 floats of each operand: 512 pieces of four, two per thread
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            const int p = tid + 256 * j;
-            f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (TRANSPOSE_A) {
-                const int k = p >> 4, m = (p & 15) * 4;                 // A[k][m .. m+3]
-                if (k0 + k < K && m0 + m < M) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(k0 + k) * lda + m0 + m);
-                *reinterpret_cast<f32x4*>(&As[k][m]) = a;
-            } else {
-                const int m = p >> 3, k = (p & 7) * 4;                  // A[m][k .. k+3]
-                if (m0 + m < M && k0 + k < K) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(m0 + m) * lda + k0 + k);
-                As[k][m] = a.x; As[k + 1][m] = a.y; As[k + 2][m] = a.z; As[k + 3][m] = a.w;
-            }
-            const int kb = p >> 4, n = (p & 15) * 4;                    // B[k][n .. n+3]
-            if (k0 + kb < K && n0 + n < N) b = *reinterpret_cast<const f32x4*>(B + (int64_t)(k0 + kb) * ldb + n0 + n);
-            *reinterpret_cast<f32x4*>(&Bs[kb][n]) = b;
+        // 32 x 32 floats of each operand: 256 pieces of four, one per thread
+        f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (TRANSPOSE_A) {
+            const int k = tid >> 3, m = (tid & 7) * 4;                      // A[k][m .. m+3]
+            if (k0 + k < K && m0 + m < M) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(k0 + k) * lda + m0 + m);
+            *reinterpret_cast<f32x4*>(&As[k][m]) = a;
+        } else {
+            const int m = tid >> 3, k = (tid & 7) * 4;                      // A[m][k .. k+3]
+            if (m0 + m < M && k0 + k < K) a = *reinterpret_cast<const f32x4*>(A + (int64_t)(m0 + m) * lda + k0 + k);
+            As[k][m] = a.x; As[k + 1][m] = a.y; As[k + 2][m] = a.z; As[k + 3][m] = a.w;
         }
+        const int kb = tid >> 3, n = (tid & 7) * 4;                         // B[k][n .. n+3]
+        if (k0 + kb < K && n0 + n < N) b = *reinterpret_cast<const f32x4*>(B + (int64_t)(k0 + kb) * ldb + n0 + n);
+        *reinterpret_cast<f32x4*>(&Bs[kb][n]) = b;
         __syncthreads();
 #pragma unroll
-        for (int kk = 0; kk < MMF_K; kk += 2) {
-            const float a = As[kk + (lane >> 5)][wm + (lane & 31)];
-            const float b = Bs[kk + (lane >> 5)][wn + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        for (int kk = 0; kk < MMF_K; kk += 4) {
+            const float av = As[kk + (lane >> 4)][wm + (lane & 15)];
+            const float bv = Bs[kk + (lane >> 4)][wn + (lane & 15)];
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
         }
         __syncthreads();
     }
-    const int n = n0 + wn + (lane & 31);
+    // lane holds column wn + lane % 16, rows wm + 4 (lane / 16) .. + 3
+    const int n = n0 + wn + (lane & 15);
 #pragma unroll
-    for (int v = 0; v < 16; v++) {
-        const int m = m0 + wm + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+    for (int v = 0; v < 4; v++) {
+        const int m = m0 + wm + 4 * (lane >> 4) + v;
         if (m < M && n < N) C[(int64_t)m * ldc + n] = acc[v];
     }
 }
