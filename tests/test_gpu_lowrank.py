@@ -133,3 +133,19 @@ def test_config2_full_size_sampled():
         print("c2 proj %d: %s" % (proj, {k: "%.3e" % v for k, v in errs.items()}), flush=True)
         for k, v in errs.items():
             assert v <= TOL_BF16, (proj, k, v)
+
+
+@pytest.mark.parametrize("M", [1, 40, 300])
+def test_bf16_rank_one_and_three(M):
+    """Degenerate ranks: the pair is a single outer product (r = 1), and r = 3."""
+    fhpc = _fhpc()
+    for r in (1, 3):
+        K, N = 264, 136
+        X, A, B, dY = lowrank_inputs(9, M, K, r, N, tensor_base=50 + r)
+        Yr, Hr = oracle.lowrank_fwd(X.f64, A.f64, B.f64)
+        ref = (Yr,) + oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+        Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+        Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+        assert tuple(H.shape) == (M, r) and oracle.rel_fro(from_device(H), Hr) <= TOL_BF16
+        dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H)
+        _check_all("rank %d M=%d" % (r, M), (Y, dX, dA, dB), ref, TOL_BF16)

@@ -359,3 +359,49 @@ def test_few_token_forward_in_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(Y, eager), rep
         assert not torch.equal(other, eager)
+
+
+def test_many_token_step_in_a_hip_graph():
+    """Forward and backward on the merged-weight route (1024 tokens) captured in one HIP graph: the calls
+    enqueue kernels only (the merge, the products, the slab sums), so three replays, with eager work on the
+    same workspace in between, must each reproduce the eager result bit for bit."""
+    import torch
+    fhpc = _fhpc()
+    M, K, r, N = 1024, 512, 16, 264
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 98)
+    Wq, sc = _quantize_host(W, 8)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    bf = torch.bfloat16
+    Y = torch.empty((M, N), dtype=bf, device="cuda")
+    H = torch.empty((M, r), dtype=bf, device="cuda")
+    dX = torch.empty((M, K), dtype=bf, device="cuda")
+    dA = torch.empty((K, r), dtype=torch.float32, device="cuda")
+    dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+
+    def step():
+        fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, 8, Ad, Bd, 2.0, Y=Y, H_out=H)
+        fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, 8, Ad, Bd, 2.0, dYd, H_saved=H, dX=dX, dA=dA, dB=dB)
+
+    step()                                                      # also sizes the cached workspace
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (Y, dX, dA, dB)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (Y, dX, dA, dB):
+            t.zero_()
+        fhpc.qlinear_lowrank_fwd(Xd * 0.5, Wq_d, sc_d, 8, Ad, Bd, 1.0)         # eager work on the same workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((Y, dX, dA, dB), eager):
+            assert torch.equal(got, ref), rep
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M", [3, 200, 1030])
+def test_qlinear_rank_one(scheme, M):
+    """The smallest rank on each route (weight streaming, load-path dequantisation, merged weight)."""
+    _run_case("rank 1 q%d M=%d" % (scheme, M), scheme, M, 512, 1, 136, 2.0, 8, tensor_base=120)
