@@ -1,0 +1,64 @@
+"""Seeded random shapes through every layer entry point, each output against the oracle: token counts on
+both sides of every routing threshold (16, 32, 64, 1024), reductions and widths that are not tile
+multiples, ranks from 1 to beyond a tile, saved and recomputed H, all weight storages, blend factors at
+the end points and inside."""
+import numpy as np
+import pytest
+
+import oracle
+from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device
+
+pytestmark = pytest.mark.gpu
+
+TOKENS = [1, 2, 7, 16, 17, 33, 64, 65, 100, 255, 256, 300, 777, 1023, 1024, 1500, 2049]
+RANKS = [1, 2, 5, 8, 16, 24, 40, 64, 72, 100, 136]
+KINDS = ["lowrank", "q8", "q4", "blend8", "blend4", "dense"]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_shapes(seed):
+    import torch
+    import paper_2402_13533_amd as fhpc
+    from paper_2402_13533_amd import synth
+    rng = np.random.default_rng(9000 + seed)
+    pick = lambda a: a[rng.integers(len(a))]
+    for it in range(20):
+        M, r, kind = int(pick(TOKENS)), int(pick(RANKS)), pick(KINDS)
+        K = int(rng.integers(1, 24)) * 64
+        N = int(rng.integers(1, 180)) * 8
+        base = 100000 * (seed + 1) + 10 * it
+        X, dY = Bf16.normal(base, (M, K), 1.0), Bf16.normal(base + 1, (M, N), 1.0)
+        A = Bf16.normal(base + 2, (K, r), K ** -0.5)
+        B = Bf16.normal(base + 3, (r, N), r ** -0.5 if kind == "lowrank" else 0.05)
+        Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+        saved = bool(rng.random() < 0.5)
+        tag = "%s M=%d K=%d r=%d N=%d saved_H=%s" % (kind, M, K, r, N, saved)
+        if kind == "lowrank":
+            Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+            got = (Y,) + tuple(fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H if saved else None))
+            ref = (oracle.lowrank_fwd(X.f64, A.f64, B.f64)[0],) + oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+        else:
+            if kind == "dense":
+                W = Bf16.normal(base + 4, (K, N), K ** -0.5)
+                Wd, W_dev, sc_dev, scheme = W.f64, W.cuda(), None, fhpc.FHPC_W_BF16
+            else:
+                scheme = 8 if kind.endswith("8") else 4
+                Wf = synth.normal(base + 4, (K, N), 0.03)
+                Wq, sc = oracle.quantize_int8_perchannel(Wf) if scheme == 8 else oracle.quantize_int4_block(Wf, 64)
+                Wd, W_dev, sc_dev = oracle.dequant(Wq, sc, scheme, 64), torch.from_numpy(Wq).cuda(), f16_bits_cuda(sc)
+            if kind in ("q8", "q4"):
+                Y, H = fhpc.qlinear_lowrank_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, save_H=True)
+                got = (Y,) + tuple(fhpc.qlinear_lowrank_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, dYd, H_saved=H if saved else None))
+                ref = (oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, 2.0)[0],) + oracle.qlinear_lowrank_bwd(X.f64, Wd, A.f64, B.f64, 2.0, dY.f64)
+            else:
+                alpha = float(pick([0.0, 0.3, 0.9, 1.0]))
+                tag += " alpha=%.1f" % alpha
+                Y, H = fhpc.qlinear_blend_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, save_H=True)
+                got = (Y,) + tuple(fhpc.qlinear_blend_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, dYd, H_saved=H if saved else None))
+                ref = (oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)[0],) + oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
+        for name, g, rf in zip(("Y", "dX", "dA", "dB"), got, ref):
+            if np.linalg.norm(rf) > 0:
+                e = oracle.rel_fro(from_device(g), rf)
+                assert e <= TOL_BF16, (tag, name, e)
+            else:
+                assert not from_device(g).any(), (tag, name)          # alpha = 1: no gradient reaches the pair
