@@ -55,6 +55,9 @@ def parse_args():
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
                          "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
     ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
+    ap.add_argument("--premerged", action="store_true",
+                    help="c4/c5: a step merges each weight once (lowrank_merge) and passes the merged weight to the forward "
+                         "and the backward call, instead of each call merging by itself")
     ap.add_argument("--shared-x", action="store_true",
                     help="c5 with --tokens and --forward-only: the q/k/v and the gate/up projections read one X each "
                          "and go through the shared-X entry point (one call per group: qkv, o, gate+up, down)")
@@ -111,11 +114,12 @@ class LowrankCall:
 
 
 class QlinearCall:
-    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False, forward_only=False):
+    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False, forward_only=False, premerged=False):
         import torch
         bf = torch.bfloat16
         self.f = fhpc
         self.forward_only = forward_only
+        self.Wm = torch.empty((K, N), dtype=bf, device="cuda") if premerged else None
         self.M, self.K, self.r, self.N, self.scheme, self.s = M, K, r, N, scheme, scaling
         W = randn((K, N), 0.02, torch.float32, gen)
         self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)       # frozen base weight, quantised on the GPU
@@ -146,10 +150,14 @@ class QlinearCall:
 
     def run(self):
         f = self.f
-        f.qlinear_lowrank_fwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, Y=self.Y, H_out=self.H)
+        Wq, sc, scheme = self.Wq, self.sc, self.scheme
+        if self.Wm is not None:
+            f.lowrank_merge(self.Wq, self.sc, self.scheme, self.A, self.B, self.s, W_out=self.Wm)
+            Wq, sc, scheme = self.Wm, None, f.FHPC_W_MERGED
+        f.qlinear_lowrank_fwd(self.X, Wq, sc, scheme, self.A, self.B, self.s, Y=self.Y, H_out=self.H)
         if self.forward_only:
             return
-        f.qlinear_lowrank_bwd(self.X, self.Wq, self.sc, self.scheme, self.A, self.B, self.s, self.dY,
+        f.qlinear_lowrank_bwd(self.X, Wq, sc, scheme, self.A, self.B, self.s, self.dY,
                               H_saved=None if self.recompute else self.H, dX=self.dX, dA=self.dA, dB=self.dB)
 
 
@@ -226,7 +234,7 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False):
+def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False, premerged=False):
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20240213)
@@ -248,7 +256,7 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         # four independent copies of the layer (own W, X, dY), run back to back: one copy's buffers
         # (0.17 GB) would sit in the 256 MB Infinity Cache from step to step
         K, N = shape or (4096, 4096)
-        calls = [QlinearCall(fhpc, M, K, 8, N, 8, gen, 2.0, recompute, forward_only) for _ in range(1 if shape else 4)]
+        calls = [QlinearCall(fhpc, M, K, 8, N, 8, gen, 2.0, recompute, forward_only, premerged) for _ in range(1 if shape else 4)]
         desc = "config 4: int8 per-channel frozen W %dx%d + rank-8 branch, %d tokens, bf16, %s, %d buffer set(s) per step" % (
             K, N, M, "fwd" if forward_only else "fwd+bwd", len(calls))
         dtype = "bf16"
@@ -262,7 +270,7 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         d, f = 5120, 13824
         shp = [shape] if shape else [(d, d)] * 4 + [(d, f), (d, f), (f, d)]
         M = tokens or 4096
-        calls = [QlinearCall(fhpc, M, K, 16, N, 4, gen, 2.0, recompute, forward_only) for K, N in shp]
+        calls = [QlinearCall(fhpc, M, K, 16, N, 4, gen, 2.0, recompute, forward_only, premerged) for K, N in shp]
         desc = "config 5: %s, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
             "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
@@ -343,7 +351,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     shape = tuple(int(v) for v in args.shape.split(",")) if args.shape else None
-    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape, args.shared_x)
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape, args.shared_x, args.premerged)
     flops = sum(c.flops() for c in calls)
     io_bytes = sum(c.io_bytes() for c in calls)
 
@@ -412,7 +420,8 @@ def main():
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": desc, "saved_H": not args.recompute, "hip_graph": bool(args.graph)},
+        "config": {"workload": desc, "saved_H": not args.recompute, "hip_graph": bool(args.graph),
+                   "merged_once_per_step": bool(args.premerged)},
         "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "io_gbs": io_bytes / (ms_per_step * 1e-3) / 1e9, "frac_hbm_peak_on_io_bytes": io_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roofline, "kernels": kernels,

@@ -53,6 +53,13 @@ enum { FHPC_Q_INT8_PER_CHANNEL = 8, FHPC_Q_INT4_BLOCK = 4 };
  * `Wq` argument, `scales` and `block` ignored (scales may be NULL) */
 enum { FHPC_W_BF16 = 16 };
 
+/* qlinear_lowrank_fwd / _bwd only: `Wq` is not the stored weight but the merged weight W' = deq(W) + scaling * A * B
+ * as bf16 [K][N], written by lowrank_merge (bf16 output) for the SAME A, B and scaling that the call receives;
+ * `scales` and `block` are ignored.  The calls then skip their own merge: Y = X W', dX = dY W'^T, while H, dA and
+ * dB are formed from A and B as always.  A training step merges once (A and B change once per step) and passes
+ * the result to both calls; the caller answers for W' matching A, B and scaling. */
+enum { FHPC_W_MERGED = 17 };
+
 enum {
     FHPC_OK = 0,
     FHPC_ERR_NULL = 1,        /* a required pointer is NULL */

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfingpt_hpc.so")
 FHPC_F32, FHPC_BF16 = 0, 1
 FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
 FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N] in place of Wq, scales None
+FHPC_W_MERGED = 17        # qlinear_lowrank_fwd/bwd only: Wq is the bf16 [K,N] weight lowrank_merge wrote for the same A, B, scaling
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE, FHPC_OP_DECOMPOSE = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
@@ -227,7 +228,7 @@ def _q_shapes(Wq, scales, qscheme, K, N, block):
         _check(Wq, "Wq", (N, K), torch.int8); _check(scales, "scales", (N,), torch.float16)
     elif qscheme == FHPC_Q_INT4_BLOCK:
         _check(Wq, "Wq", (N, K // 2), torch.uint8); _check(scales, "scales", (N, K // block), torch.float16)
-    elif qscheme == FHPC_W_BF16:
+    elif qscheme in (FHPC_W_BF16, FHPC_W_MERGED):
         _check(Wq, "W", (K, N), torch.bfloat16)
         if scales is not None:
             raise ValueError("a dense bf16 weight has no scales")

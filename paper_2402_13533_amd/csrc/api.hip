@@ -129,7 +129,8 @@ int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred)
     return sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0;
 }
 
-Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, bool quantised = true)
+Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, bool quantised = true,
+              bool premerged = false)
 {
     Scratch s;
     if (dtype == FHPC_F32) {
@@ -147,7 +148,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     const int64_t rp = rank_pad(r);
     const bool bwd = (op == FHPC_OP_LOWRANK_BWD || op == FHPC_OP_QLINEAR_BWD);
-    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && many_tokens(M)) s.Wm = c.take(K * N * 2);
+    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && many_tokens(M) && !premerged) s.Wm = c.take(K * N * 2);
     if (rp != r) {
         s.A_p = c.take(K * rp * 2);
         s.B_p = c.take(rp * N * 2);
@@ -337,10 +338,10 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
 }
 
 int check_workspace(int op, void* ws, size_t ws_bytes, int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
-                    bool quantised = true)
+                    bool quantised = true, bool premerged = false)
 {
     Carver dry(nullptr);
-    carve(dry, op, M, K, r, N, dtype, quantised);
+    carve(dry, op, M, K, r, N, dtype, quantised, premerged);
     if (dry.used == 0) return FHPC_OK;
     if (!ws || ws_bytes < dry.used) return FHPC_ERR_WORKSPACE;
     if (!aligned(ws, 256)) return FHPC_ERR_ALIGN;
@@ -522,7 +523,7 @@ size_t fhpc_workspace_bytes(int op, int64_t M, int64_t K, int64_t r, int64_t N, 
     if (dtype != FHPC_F32 && dtype != FHPC_BF16) return 0;
     if (check_common(M, K, r, N) != FHPC_OK) return 0;
     Carver dry(nullptr);
-    carve(dry, op, M, K, r, N, dtype, qscheme != FHPC_W_BF16);
+    carve(dry, op, M, K, r, N, dtype, qscheme != FHPC_W_BF16 && qscheme != FHPC_W_MERGED, qscheme == FHPC_W_MERGED);
     return dry.used;
 }
 
@@ -614,7 +615,8 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
                             int64_t M, int64_t K, int64_t r, int64_t N,
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    const bool dense = (qscheme == FHPC_W_BF16);          // blend layer with an unquantised frozen weight
+    const bool premerged = (qscheme == FHPC_W_MERGED);    // Wq is the bf16 weight lowrank_merge wrote for this A, B, scaling
+    const bool dense = (qscheme == FHPC_W_BF16) || premerged;      // (FHPC_W_BF16: blend layer with an unquantised frozen weight)
     if (!X || !Wq || (!scales && !dense) || !A || !B || !Y) return FHPC_ERR_NULL;
     int rc = dense ? FHPC_OK : check_q(qscheme, block, K);
     if (rc) return rc;
@@ -624,11 +626,11 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
     if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
         !aligned(Y, 16) || !aligned(H_out, 16))
         return FHPC_ERR_ALIGN;
-    rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense);
+    rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense, premerged);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
-    Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, !dense);
+    Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, !dense, premerged);
     if (s.sk_part) {
         const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, kNumCU);
         const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};
@@ -641,10 +643,15 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
     const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
-    if (s.Wm && base_scale != 0.f) {
-        // many tokens: one plain product with the merged weight; H only if the caller wants it
-        FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(X, K), operand(s.Wm, N), Y, N, M, N, K, st));
+    if (premerged || (s.Wm && base_scale != 0.f)) {
+        // many tokens (or a weight merged by the caller): one plain product with the merged weight; H only if
+        // the caller wants it
+        const void* Wm = Wq;
+        if (!premerged) {
+            FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
+            Wm = s.Wm;
+        }
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(X, K), operand(Wm, N), Y, N, M, N, K, st));
         if (H_out) {
             FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
             if (rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
@@ -763,6 +770,7 @@ int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qsc
                       void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!(alpha >= 0.f && alpha <= 1.f)) return FHPC_ERR_SHAPE;
+    if (qscheme == FHPC_W_MERGED) return FHPC_ERR_DTYPE;
     return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, alpha, 1.f - alpha, Y, H_out, M, K, r, N,
                             workspace, workspace_bytes, hip_stream);
 }
@@ -773,7 +781,8 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
                             int64_t M, int64_t K, int64_t r, int64_t N,
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    const bool dense = (qscheme == FHPC_W_BF16);
+    const bool premerged = (qscheme == FHPC_W_MERGED);
+    const bool dense = (qscheme == FHPC_W_BF16) || premerged;
     if (!X || !Wq || (!scales && !dense) || !A || !B || !dY) return FHPC_ERR_NULL;
     int rc = dense ? FHPC_OK : check_q(qscheme, block, K);
     if (rc) return rc;
@@ -783,11 +792,11 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
     if (!aligned(X, 16) || !aligned(Wq, 16) || !aligned(scales, 16) || !aligned(A, 16) || !aligned(B, 16) ||
         !aligned(dY, 16) || !aligned(H_saved, 16) || !aligned(dX, 16) || !aligned(dA, 16) || !aligned(dB, 16))
         return FHPC_ERR_ALIGN;
-    rc = check_workspace(FHPC_OP_QLINEAR_BWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16);
+    rc = check_workspace(FHPC_OP_QLINEAR_BWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense, premerged);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
-    Scratch s = carve(c, FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16);
+    Scratch s = carve(c, FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16, !dense, premerged);
     const int64_t rp = rank_pad(r);
     Factors f;
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
@@ -804,16 +813,20 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
             H = s.H;
         }
     }
-    const bool merged_dx = (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
+    const bool merged_dx = premerged || (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
     if (dA || (dX && !merged_dx))
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX && base_scale == 0.f) {
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st, scaling));
     } else if (dX && merged_dx) {
         // many tokens: dX = dY W'^T with the merged weight W' = base_scale deq(W) + scaling A B
-        const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
-        FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
-        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(s.Wm, N), dX, K, M, K, N, st));
+        const void* Wm = Wq;
+        if (!premerged) {
+            const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+            FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
+            Wm = s.Wm;
+        }
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, st));
     } else if (dX) {
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};
@@ -848,6 +861,7 @@ int qlinear_blend_bwd(const void* X, const void* Wq, const void* scales, int qsc
                       void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!(alpha >= 0.f && alpha <= 1.f)) return FHPC_ERR_SHAPE;
+    if (qscheme == FHPC_W_MERGED) return FHPC_ERR_DTYPE;
     return qlinear_bwd_impl(X, Wq, scales, qscheme, block, A, B, alpha, 1.f - alpha, dY, H_saved, dX, dA, dB, M, K, r, N,
                             workspace, workspace_bytes, hip_stream);
 }

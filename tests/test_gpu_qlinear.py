@@ -405,3 +405,34 @@ def test_many_token_step_in_a_hip_graph():
 def test_qlinear_rank_one(scheme, M):
     """The smallest rank on each route (weight streaming, load-path dequantisation, merged weight)."""
     _run_case("rank 1 q%d M=%d" % (scheme, M), scheme, M, 512, 1, 136, 2.0, 8, tensor_base=120)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M", [40, 300, 1100])
+def test_premerged_weight(scheme, M):
+    """The caller merges once (lowrank_merge, bf16) and passes the result to forward and backward with
+    qscheme FHPC_W_MERGED: outputs against the oracle's layer; from 1024 tokens on they are the very bits
+    of the calls that merge by themselves (same merge kernel, same products)."""
+    import torch
+    fhpc = _fhpc()
+    K, r, N, s = 512, 24, 264, 2.0
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 130)
+    Wq, sc = _quantize_host(W, scheme)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Wm = fhpc.lowrank_merge(Wq_d, sc_d, scheme, Ad, Bd, s)
+    Y, H = fhpc.qlinear_lowrank_fwd(Xd, Wm, None, fhpc.FHPC_W_MERGED, Ad, Bd, s, save_H=True)
+    dX, dA, dB = fhpc.qlinear_lowrank_bwd(Xd, Wm, None, fhpc.FHPC_W_MERGED, Ad, Bd, s, dYd, H_saved=H)
+    Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, s)
+    ref = oracle.qlinear_lowrank_bwd(X.f64, Wd, A.f64, B.f64, s, dY.f64)
+    for name, g, rf in zip(("Y", "H", "dX", "dA", "dB"), (Y, H, dX, dA, dB), (Yr, Hr) + ref):
+        e = oracle.rel_fro(from_device(g), rf)
+        assert e <= TOL_BF16, (name, e)
+    if M >= 1024:
+        Y2, H2 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)
+        dX2, dA2, dB2 = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H2)
+        for a, b in zip((Y, H, dX, dA, dB), (Y2, H2, dX2, dA2, dB2)):
+            assert torch.equal(a, b)
+    with pytest.raises(fhpc.FhpcError):          # the blend layer does not take a merged weight
+        fhpc.qlinear_blend_fwd(Xd, Wm, None, fhpc.FHPC_W_MERGED, Ad, Bd, 0.5)
