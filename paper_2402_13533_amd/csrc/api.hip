@@ -89,9 +89,11 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
     sp.tile = tile;
     const int64_t tiles = tile_count(sp.tile, M, N);
     const int64_t ksteps = (Kred + 63) / 64;
-    // the eight-wave tiles occupy a compute unit alone; the smaller ones run two at a time
-    const bool big = (sp.tile == TILE_256x256 || sp.tile == TILE_256x128 || sp.tile == TILE_128x256);
-    const int64_t target = big ? kNumCU : 2 * kNumCU;
+    // the eight-wave tiles occupy a compute unit alone; 128x128 runs two at a time.  The skinny tiles could
+    // too, but their products are bound by streaming the long operand, and one workgroup per compute
+    // unit with twice the depth measured faster than two (4096 x 5120 -> 16: 11.4 against 14.8 microseconds)
+    // and leaves half as many slabs to add.
+    const int64_t target = (sp.tile == TILE_128x128) ? 2 * kNumCU : kNumCU;
     int64_t s = (target + tiles - 1) / tiles;
     if (s > ksteps) s = ksteps;
     if (s > 64) s = 64;
