@@ -40,7 +40,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int NT = 256;
 constexpr int ROWS_WG = 64;            // output channels per workgroup
 constexpr int TOK = 16;                // token rows of the MFMA tile
-constexpr int STEP = 512;              // reduction depth per pipeline step
+constexpr int STEP = 512;              // unit of the reduction split (and the pipeline step up to 32 tokens)
+// Reduction depth per pipeline step.  The double-buffered token tile of a step takes
+// tokens * depth * 4 bytes of LDS; with 64 tokens the shallower step lets two workgroups share a
+// compute unit, which hides more of the weight stream's latency than the deeper step does.
+constexpr int step_depth(int tt) { return tt == 4 ? 256 : 512; }
 constexpr int HCHUNK = 128;            // reduction depth per workgroup of the H = X A kernel
 constexpr uint32_t OOB = 0x80000000u;
 
@@ -152,9 +156,13 @@ __device__ __forceinline__ bf16x8 int8_operand(uint32_t w0, uint32_t w1)
     return as_bf16x8(r);
 }
 
-// LDS tile of the token rows for one step: [16 tokens][512 k] bf16, 16-byte chunks XOR-swizzled
+// LDS tile of the token rows for one step: [tokens][DEPTH k] bf16, 16-byte chunks XOR-swizzled
 // by the token so that the 16 lanes of a group (16 tokens, same chunk) hit 16 different banks.
-__device__ __forceinline__ uint32_t x_off(int tok, int chunk) { return (uint32_t)tok * (STEP * 2) + (uint32_t)(((chunk ^ tok) & 63) << 4); }
+template <int DEPTH>
+__device__ __forceinline__ uint32_t x_off(int tok, int chunk)
+{
+    return (uint32_t)tok * (DEPTH * 2) + (uint32_t)(((chunk ^ tok) & (DEPTH / 8 - 1)) << 4);
+}
 
 // hpart[kc][m][j] = sum over the 128-deep chunk kc of X[m][k] A[k][j]   (fp32, m < M, j < r).
 // Run by the extra workgroups at the end of the streaming kernel's grid, so that H = X A costs no
@@ -206,10 +214,12 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                                                          int kchunks, int main_grid)
 {
     constexpr bool I4 = (SCHEME == 4);
-    constexpr int WLOADS = I4 ? 4 : 8;               // 16-byte weight loads per lane per step
+    constexpr int SD = step_depth(TT);               // reduction depth per step
+    constexpr int WLOADS = I4 ? SD / 128 : SD / 64;  // 16-byte weight loads per lane per step
     constexpr int TOKS = TOK * TT;                   // token rows this instantiation covers
-    constexpr int XS_BYTES = TOKS * STEP * 2;
-    constexpr int XL = 4 * TT;                       // 16-byte token pieces per thread per step
+    constexpr int XS_BYTES = TOKS * SD * 2;
+    constexpr int XCH = SD / 8;                      // 16-byte pieces per token row per step
+    constexpr int XL = TOKS * XCH / NT;              // ... per thread per step
     static_assert(h_lds_bytes(TOKS) <= 2 * XS_BYTES, "the H = X A workgroups reuse the token tiles' LDS");
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XS_BYTES];
     unsigned char* const xs[2] = {smem, smem + XS_BYTES};
@@ -234,7 +244,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     const int ld_part = row_blocks * ROWS_WG;
     const int kbeg = split * k_chunk;
     const int kend = (kbeg + k_chunk < K) ? kbeg + k_chunk : K;
-    const int steps = (kend - kbeg + STEP - 1) / STEP;
+    const int steps = (kend - kbeg + SD - 1) / SD;
     const int lr = lane & 15, g = lane >> 4;         // operand view: row / token lr, k group g
 
     const int64_t row_bytes = I4 ? K / 2 : K;
@@ -254,21 +264,26 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
             w[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
         }
     };
-    // int4 scales of one step: eight consecutive blocks of each of the four output channels this
-    // lane owns in the accumulator view (channel n0 + 4 g + v)
+    // int4 scales of one step: the SD / 64 consecutive blocks of each of the four output channels
+    // this lane owns in the accumulator view (channel n0 + 4 g + v)
     auto load_s = [&](u32x4 (&s)[4], int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int v = 0; v < 4; v++) {
             const int n = n0 + 4 * g + v;
             const uint32_t off = (n < N && k0 < kend) ? (uint32_t)(((int64_t)n * (K / 64) + k0 / 64) * 2) : OOB;
-            s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, off, 0, 0);
+            if constexpr (SD == 512) {
+                s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, off, 0, 0);
+            } else {
+                const auto h = __builtin_amdgcn_raw_buffer_load_b64(rsc, off, 0, 0);
+                s[v].x = h[0]; s[v].y = h[1];
+            }
         }
     };
-    // token tile of one step: 64 chunks of 16 bytes per token, 4 TT per thread
+    // token tile of one step: XCH chunks of 16 bytes per token, XL per thread
     auto load_x = [&](u32x4 (&x)[XL], int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < XL; j++) {
-            const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
+            const int c = tid + NT * j, tok = c / XCH, chunk = c % XCH;
             const int k = k0 + chunk * 8;
             const uint32_t off = (tok < M && k < kend) ? (uint32_t)(((int64_t)tok * K + k) * 2) : OOB;
             x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
@@ -277,8 +292,8 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     auto store_x = [&](const u32x4 (&x)[XL], unsigned char* dst) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < XL; j++) {
-            const int c = tid + NT * j, tok = c >> 6, chunk = c & 63;
-            *reinterpret_cast<u32x4*>(dst + x_off(tok, chunk)) = I4 ? x_even_odd_order(x[j]) : x[j];
+            const int c = tid + NT * j, tok = c / XCH, chunk = c % XCH;
+            *reinterpret_cast<u32x4*>(dst + x_off<SD>(tok, chunk)) = I4 ? x_even_odd_order(x[j]) : x[j];
         }
     };
 
@@ -296,13 +311,13 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     const bf16x8 minus_offset = as_bf16x8(moff_bits);
 
     auto xfrag = [&](const unsigned char* tile, int tt, int chunk) __attribute__((always_inline)) {
-        return *reinterpret_cast<const bf16x8*>(tile + x_off(TOK * tt + lr, chunk));
+        return *reinterpret_cast<const bf16x8*>(tile + x_off<SD>(TOK * tt + lr, chunk));
     };
     // one step of the reduction from registers w (and s) against the token tile
     auto compute = [&](u32x4 (&w)[WLOADS], u32x4 (&s)[4], const unsigned char* tile) __attribute__((always_inline)) {
         if constexpr (I4) {
 #pragma unroll
-            for (int u = 0; u < 4; u++) {            // 128 k: two scale blocks
+            for (int u = 0; u < WLOADS; u++) {       // 128 k: two scale blocks
                 uint32_t t[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
                 transpose_groups(t);                 // t[c] = codes k = 128 u + 32 c + 8 g .. + 7
 #pragma unroll
@@ -336,7 +351,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
             }
         } else {
 #pragma unroll
-            for (int u = 0; u < 8; u++) {            // 64 k: lane holds k = 64 u + 16 g .. + 15
+            for (int u = 0; u < WLOADS; u++) {       // 64 k: lane holds k = 64 u + 16 g .. + 15
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
                     const bf16x8 wf = h ? int8_operand(w[u].z, w[u].w) : int8_operand(w[u].x, w[u].y);
@@ -359,10 +374,10 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     auto step = [&](auto WB, auto XB, int t) __attribute__((always_inline)) {
         constexpr int wb = decltype(WB)::value, xb = decltype(XB)::value, wn = (wb + DEPTH) % (DEPTH + 1);
         store_x(xreg, xs[xb]);
-        if (t + 1 < steps) load_x(xreg, kbeg + (t + 1) * STEP);
+        if (t + 1 < steps) load_x(xreg, kbeg + (t + 1) * SD);
         if (t + DEPTH < steps) {
-            load_w(wreg[wn], kbeg + (t + DEPTH) * STEP);
-            if constexpr (I4) load_s(sreg[wn], kbeg + (t + DEPTH) * STEP);
+            load_w(wreg[wn], kbeg + (t + DEPTH) * SD);
+            if constexpr (I4) load_s(sreg[wn], kbeg + (t + DEPTH) * SD);
         }
         __syncthreads();
         compute(wreg[wb], sreg[wb], xs[xb]);
@@ -372,8 +387,8 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         load_w(wreg[0], kbeg);
         if constexpr (I4) load_s(sreg[0], kbeg);
         if (DEPTH == 2 && steps > 1) {
-            load_w(wreg[1], kbeg + STEP);
-            if constexpr (I4) load_s(sreg[1], kbeg + STEP);
+            load_w(wreg[1], kbeg + SD);
+            if constexpr (I4) load_s(sreg[1], kbeg + SD);
         }
         using I0 = std::integral_constant<int, 0>;
         using I1 = std::integral_constant<int, 1>;
@@ -517,9 +532,9 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
     for (int j = 0; j < count; j++) row_blocks += (N[j] + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
     const int64_t ksteps = K / skinny::STEP;
     // One round of workgroups: as many as are resident at once (registers and the token tiles' LDS
-    // allow three per compute unit with 16 tokens, two with 32, one with 64) and no more, so that
+    // allow three per compute unit with 16 tokens, two with more) and no more, so that
     // no second, partly filled round follows; at least one step each.
-    const int64_t per_cu = (M <= 16) ? 3 : (M <= 32) ? 2 : 1;
+    const int64_t per_cu = (M <= 16) ? 3 : 2;
     int64_t s = per_cu * (int64_t)num_cu / row_blocks;
     if (s > ksteps) s = ksteps;
     if (s < 1) s = 1;
