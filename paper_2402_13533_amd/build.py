@@ -15,7 +15,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Wno-unused-command-line-argument"]
 
 
-EXTRA = {}      # per-file compiler options (none at present)
+# Per-file compiler options.  qskinny.hip: keep the matrix instructions' results in ordinary vector
+# registers; its loop scales every 64-deep block sum on the vector ALU, and with the results in
+# accumulation registers each of those values costs an extra register move (an eighth of the loop).
+EXTRA = {"qskinny.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build_library(verbose: bool = False) -> str:

@@ -96,20 +96,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t by
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// 4 x 4 transpose of 32-bit words across the four 16-lane groups of a wave: on return lane
-// group g holds in w[s] what group s held in w[g].
-__device__ __forceinline__ void transpose_groups(uint32_t (&w)[4])
+// Exchange between the two halves of a wave: lanes 0..31 keep w[0], w[1] and get the upper
+// partner's (lane + 32) w[0], w[1] in w[2], w[3]; lanes 32..63 keep w[2], w[3] and get the lower
+// partner's w[2], w[3] in w[0], w[1].
+__device__ __forceinline__ void exchange_halves(uint32_t (&w)[4])
 {
     // v_permlane32_swap a, b: lanes 32..63 of a <-> lanes 0..31 of b
-    // v_permlane16_swap a, b: the odd 16-lane rows of a <-> the even rows of b
     auto s0 = __builtin_amdgcn_permlane32_swap(w[0], w[2], false, false);
     auto s1 = __builtin_amdgcn_permlane32_swap(w[1], w[3], false, false);
     w[0] = s0[0]; w[2] = s0[1];
     w[1] = s1[0]; w[3] = s1[1];
-    auto t0 = __builtin_amdgcn_permlane16_swap(w[0], w[1], false, false);
-    auto t1 = __builtin_amdgcn_permlane16_swap(w[2], w[3], false, false);
-    w[0] = t0[0]; w[1] = t0[1];
-    w[2] = t1[0]; w[3] = t1[1];
 }
 
 // eight int4 codes (one 32-bit word, element 2j in the low nibble of byte j) -> eight bf16
@@ -254,40 +250,48 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     const bool row_ok = (n0 + lr) < N;
     const uint32_t wrow = row_ok ? (uint32_t)((int64_t)(n0 + lr) * row_bytes) : OOB;
 
+    // A step never straddles the end of the slice (K and the slice depth are multiples of 512, the
+    // step depth divides 512), so only rows and tokens need a bounds guard; it sits in the
+    // loop-invariant vector offset (an offset beyond the buffer reads as zero), and the position
+    // along k travels in the scalar offset, so the loop spends no vector instructions on addresses.
     // weight pieces of one step for this lane.  int4: load u covers k = 128 u + 32 g .. + 31
-    // (16 bytes); int8: load u covers k = 64 u + 16 g .. + 15.
+    // (16 bytes); int8: load u covers k = 64 u + 16 g .. + 15: byte 64 u + 16 g of the step either way.
+    const uint32_t wlane = row_ok ? wrow + 16u * (uint32_t)g : OOB;
     auto load_w = [&](u32x4 (&w)[WLOADS], int k0) __attribute__((always_inline)) {
+        const int sk = I4 ? k0 >> 1 : k0;
 #pragma unroll
-        for (int u = 0; u < WLOADS; u++) {
-            const int k = k0 + (I4 ? 128 * u + 32 * g : 64 * u + 16 * g);
-            const uint32_t off = (k < kend) ? wrow + (uint32_t)(I4 ? k / 2 : k) : OOB;
-            w[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
-        }
+        for (int u = 0; u < WLOADS; u++) w[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, wlane + 64u * u, sk, 0);
     };
     // int4 scales of one step: the SD / 64 consecutive blocks of each of the four output channels
     // this lane owns in the accumulator view (channel n0 + 4 g + v)
+    uint32_t srow[4];
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+        const int n = n0 + 4 * g + v;
+        srow[v] = (I4 && n < N) ? (uint32_t)((int64_t)n * (K / 64) * 2) : OOB;
+    }
     auto load_s = [&](u32x4 (&s)[4], int k0) __attribute__((always_inline)) {
+        const int sk = k0 >> 5;                      // block k0 / 64, two bytes each
 #pragma unroll
         for (int v = 0; v < 4; v++) {
-            const int n = n0 + 4 * g + v;
-            const uint32_t off = (n < N && k0 < kend) ? (uint32_t)(((int64_t)n * (K / 64) + k0 / 64) * 2) : OOB;
             if constexpr (SD == 512) {
-                s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, off, 0, 0);
+                s[v] = __builtin_amdgcn_raw_buffer_load_b128(rsc, srow[v], sk, 0);
             } else {
-                const auto h = __builtin_amdgcn_raw_buffer_load_b64(rsc, off, 0, 0);
+                const auto h = __builtin_amdgcn_raw_buffer_load_b64(rsc, srow[v], sk, 0);
                 s[v].x = h[0]; s[v].y = h[1];
             }
         }
     };
     // token tile of one step: XCH chunks of 16 bytes per token, XL per thread
+    uint32_t xlane[XL];
+#pragma unroll
+    for (int j = 0; j < XL; j++) {
+        const int c = tid + NT * j, tok = c / XCH, chunk = c % XCH;
+        xlane[j] = (tok < M) ? (uint32_t)(((int64_t)tok * K + chunk * 8) * 2) : OOB;
+    }
     auto load_x = [&](u32x4 (&x)[XL], int k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < XL; j++) {
-            const int c = tid + NT * j, tok = c / XCH, chunk = c % XCH;
-            const int k = k0 + chunk * 8;
-            const uint32_t off = (tok < M && k < kend) ? (uint32_t)(((int64_t)tok * K + k) * 2) : OOB;
-            x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
-        }
+        for (int j = 0; j < XL; j++) x[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, xlane[j], k0 * 2, 0);
     };
     auto store_x = [&](const u32x4 (&x)[XL], unsigned char* dst) __attribute__((always_inline)) {
 #pragma unroll
@@ -310,6 +314,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     u32x4 moff_bits = {0xc308c308u, 0xc308c308u, 0xc308c308u, 0xc308c308u};     // bf16(-136) x 8
     const bf16x8 minus_offset = as_bf16x8(moff_bits);
 
+    const int gchunk = 4 * (g & 1) + 2 * (g >> 1);  // int4: 16-byte chunk of this lane group's codes within a block
     auto xfrag = [&](const unsigned char* tile, int tt, int chunk) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8*>(tile + x_off<SD>(TOK * tt + lr, chunk));
     };
@@ -318,8 +323,10 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         if constexpr (I4) {
 #pragma unroll
             for (int u = 0; u < WLOADS; u++) {       // 128 k: two scale blocks
+                // t[2 b + h] = codes k = 128 u + 64 b + gk + 8 h .. + 7,  gk = 32 (g & 1) + 16 (g >> 1):
+                // the four lane groups of one matrix instruction stay inside one scale block
                 uint32_t t[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-                transpose_groups(t);                 // t[c] = codes k = 128 u + 32 c + 8 g .. + 7
+                exchange_halves(t);
 #pragma unroll
                 for (int b = 0; b < 2; b++) {
                     // sum over the block of X (q + 136) and of X (-136), in one accumulator
@@ -332,7 +339,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
                         const bf16x8 wf = int4_operand(t[c]);
 #pragma unroll
                         for (int tt = 0; tt < TT; tt++) {
-                            const bf16x8 xf = xfrag(tile, tt, (128 * u + 32 * c) / 8 + g);
+                            const bf16x8 xf = xfrag(tile, tt, 16 * u + 8 * b + h + gchunk);
                             cw[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, cw[tt], 0, 0, 0);
                             cw[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(minus_offset, xf, cw[tt], 0, 0, 0);
                         }
@@ -441,16 +448,19 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 
 // Y[m][n] = bf16( base_scale * sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
 // A workgroup covers 64 channels x 4 tokens, one output per thread (blockIdx.y picks the token group).
-// Everything a thread needs from memory is requested up front (its column of B, its slab values,
-// its share of the H partial sums), so the kernel pays one memory round trip, not three.
+// The kernel is a chain of memory round trips and little else, so everything a thread needs is
+// requested before anything is waited for: every load below has an address that is valid whatever
+// the lane's bounds say (indices are clamped, the value is dropped by a select afterwards), so
+// no load sits behind a branch, and the loops over slabs and chunks keep eight loads in flight.
 constexpr int FTOK = 4;
+constexpr int FDEPTH = 8;
 template <int RMAX>
 __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
                                                     const float* __restrict__ hpart_all, int kchunks,
                                                     SkinnyJobs jb, int M, int r)
 {
     __shared__ float Hs[FTOK * RMAX];
-    __shared__ float Hg[NT];
+    __shared__ __attribute__((aligned(16))) float Hg[4 * NT];
     const int rb = blockIdx.x;                                 // 64-channel block in the combined numbering
     const int job = job_of_block(jb, rb);
     const int N = pick(jb.N, job);
@@ -461,40 +471,85 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
     const float* const hpart = hpart_all + (int64_t)job * kchunks * M * r;
     const bool first_block = (rb == pick_rb0(jb, job));
     const int ld_part = jb.rb0[jb.count] * 64;
-    const int ncomb = rb * 64 + (threadIdx.x & 63);
+    const int ncomb = rb * 64 + (threadIdx.x & 63);            // always inside the slab's width
     const int n = (rb - pick_rb0(jb, job)) * 64 + (threadIdx.x & 63);
     const int m0 = blockIdx.y * FTOK;
     const int m = m0 + (threadIdx.x >> 6);
     const bool live = n < N && m < M;
+    const int nc = n < N ? n : N - 1, mc = m < M ? m : M - 1;
+
+    // (1) this thread's column of B
+    // (buffer loads: a row beyond r gets an offset outside the buffer and reads as zero)
+    const __amdgpu_buffer_rsrc_t rB = rsrc(B, (int64_t)r * N * 2);
     float b[RMAX];
 #pragma unroll
-    for (int j = 0; j < RMAX; j++) b[j] = (live && j < r) ? __uint_as_float((uint32_t)B[(int64_t)j * N + n] << 16) : 0.f;
-    float base = 0.f;
-    if (live)
-        for (int sp = 0; sp < splits; sp++) base += part[((int64_t)sp * M + m) * ld_part + ncomb];
-    // H of this group's tokens = sum of the chunk partial sums, all 256 threads sharing the loads:
-    // thread (o, g) adds the chunks g, g + G, ... of output o, then the G group sums are added in
-    // group order (the same order every run).  The tokens of a group are consecutive, so their
-    // outputs are contiguous in a chunk: hpart[kc][m0 * r + o].
+    for (int j = 0; j < RMAX; j++) {
+        const uint32_t off = (j < r) ? (uint32_t)(j * N + nc) * 2u : OOB;
+        b[j] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rB, off, 0, 0) << 16);
+    }
+    // (2) its slab values: the first eight requested here, summed (and any further ones fetched)
+    // after the requests of (3) are out
+    auto part_batch = [&](float (&v)[FDEPTH], int sp0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < FDEPTH; q++) {
+            const int sp = sp0 + q;
+            const float x = part[((int64_t)(sp < splits ? sp : sp0) * M + mc) * ld_part + ncomb];
+            v[q] = (sp < splits) ? x : 0.f;
+        }
+    };
+    auto sum8 = [](const auto (&v)[FDEPTH]) __attribute__((always_inline)) {
+        return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    };
+    float pv[FDEPTH];
+    part_batch(pv, 0);
+    // (3) H of this group's tokens = sum of the chunk partial sums, the 256 threads sharing the loads.
+    // The tokens of a group are consecutive, so their outputs are contiguous in a chunk:
+    // hpart[kc][m0 * r + o], o < outs.  A thread owns `vec` consecutive outputs (4 when r is a multiple
+    // of 4, which keeps 16-byte alignment; else 1) of the chunks g, g + G, ...; the G group sums
+    // are then added in group order (the same order every run).
     const int toks = (M - m0 < FTOK) ? M - m0 : FTOK;
     const int outs = toks * r;                              // at most 4 RMAX <= 256
     const int64_t chunk = (int64_t)M * r;
     const float* hp = hpart + (int64_t)m0 * r;
-    const int G = NT / outs;
+    const bool vec4 = (r & 3) == 0;
+    const int P = vec4 ? outs >> 2 : outs;                  // threads per chunk
+    const int G = NT / P;
     {
-        const int o = threadIdx.x % outs, g = threadIdx.x / outs;
-        float sv[4] = {0.f, 0.f, 0.f, 0.f};                 // four loads in flight per trip
+        const int p = threadIdx.x % P, g = threadIdx.x / P;
+        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        f32x4 sv = zero4;
         if (g < G) {
-            for (int kc = g; kc < kchunks; kc += 4 * G) {
+            if (vec4) {
+                for (int kc = g; kc < kchunks; kc += FDEPTH * G) {
+                    f32x4 v[FDEPTH];
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const int c = kc + q * G;
-                    const float v = hp[(int64_t)(c < kchunks ? c : kc) * chunk + o];    // (a repeated, in-range chunk, weighted 0)
-                    sv[q] += (c < kchunks) ? v : 0.f;
+                    for (int q = 0; q < FDEPTH; q++) {
+                        const int c = kc + q * G;
+                        const f32x4 x = *reinterpret_cast<const f32x4*>(hp + (int64_t)(c < kchunks ? c : kc) * chunk + 4 * p);
+                        v[q] = (c < kchunks) ? x : zero4;
+                    }
+                    sv += sum8(v);
                 }
+                *reinterpret_cast<f32x4*>(Hg + (g * P + p) * 4) = sv;       // Hg[g][4 p ..] of [G][outs]
+            } else {
+                for (int kc = g; kc < kchunks; kc += FDEPTH * G) {
+                    float v[FDEPTH];
+#pragma unroll
+                    for (int q = 0; q < FDEPTH; q++) {
+                        const int c = kc + q * G;
+                        const float x = hp[(int64_t)(c < kchunks ? c : kc) * chunk + p];
+                        v[q] = (c < kchunks) ? x : 0.f;
+                    }
+                    sv[0] += sum8(v);
+                }
+                Hg[g * P + p] = sv[0];                                      // Hg[g][p] of [G][outs]
             }
         }
-        Hg[threadIdx.x] = (sv[0] + sv[1]) + (sv[2] + sv[3]);
+    }
+    float base = sum8(pv);
+    for (int sp0 = FDEPTH; sp0 < splits; sp0 += FDEPTH) {
+        part_batch(pv, sp0);
+        base += sum8(pv);
     }
     __syncthreads();
     if ((int)threadIdx.x < outs) {
@@ -520,8 +575,10 @@ __global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ pa
 
 bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
 {
-    (void)N;
     if (scheme != 4 && scheme != 8) return false;
+    // the kernels address each operand with 32-bit byte offsets below 2^31
+    const int64_t lim = (int64_t)1 << 31;
+    if (N < 1 || K < 1 || N * K >= lim || 2 * r * N >= lim) return false;
     return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
 }
 
