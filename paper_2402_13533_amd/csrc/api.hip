@@ -54,6 +54,7 @@ struct Scratch {
     void* Wm = nullptr;     // bf16 [K][N]    base_scale * deq(W) + scaling * A B, many tokens (see many_tokens)
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
+    float* sk_dxpart = nullptr; // weight-streaming input gradient (few tokens): slabs of M x K
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
@@ -131,6 +132,13 @@ int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred)
     return sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0;
 }
 
+// The quantised layer's input gradient for at most 64 tokens is bound by reading the packed weight
+// once: it then comes from the weight-streaming kernel (both schemes have the same shape limits).
+bool stream_dx(int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    return qskinny_dx_supports(M, K, r, N, FHPC_Q_INT4_BLOCK) && qskinny_dx_supports(M, K, r, N, FHPC_Q_INT8_PER_CHANNEL);
+}
+
 Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, bool quantised = true,
               bool premerged = false)
 {
@@ -169,6 +177,12 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     if (bwd && rp != r) {
         s.dA_t = static_cast<float*>(c.take(K * rp * 4));
         s.dB_t = static_cast<float*>(c.take(rp * N * 4));
+    }
+    if (op == FHPC_OP_QLINEAR_BWD && quantised && stream_dx(M, K, r, N)) {
+        // a handful of tokens: dX comes from the weight-streaming kernel (sized for either scheme)
+        const int64_t b4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, kNumCU).part_bytes;
+        const int64_t b8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, kNumCU).part_bytes;
+        s.sk_dxpart = static_cast<float*>(c.take(b4 > b8 ? b4 : b8));
     }
     // split reductions of this entry point run one after another and share the slabs
     int64_t part = 0;
@@ -829,6 +843,11 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
             Wm = s.Wm;
         }
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, st));
+    } else if (dX && s.sk_dxpart) {
+        // a handful of tokens: one pass over the packed weight (slabs), then slabs + rank-r branch -> bf16
+        const QskinnyDxPlan p = qskinny_dx_plan(M, K, N, qscheme, kNumCU);
+        FHPC_HIP(launch_qskinny_dx(dY, Wq, scales, qscheme, s.dH, f.A, rp, base_scale, scaling, dX, M, K, N, p,
+                                   s.sk_dxpart, st));
     } else if (dX) {
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};

@@ -38,4 +38,24 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
 hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, int scheme, int64_t M, int64_t K, int64_t r,
                               const QskinnyPlan& p, float* part, float* hpart, hipStream_t st);
 
+// ---- input gradient dX for a handful of tokens (csrc/qskinny_dx.hip)
+struct QskinnyDxPlan {
+    int strips;            // column strips of dX: K / 256 (int4) or K / 128 (int8)
+    int token_blocks;      // blocks of 16 tokens
+    int steps_total;       // 32-row steps of the weight: ceil(N / 32)
+    int steps_per_slice;   // steps of one slice of the reduction
+    int slices;            // slices; each writes its own fp32 slab of M x K
+    int64_t part_bytes;    // slices * M * K * 4
+};
+
+// M <= 64 tokens, r <= 64, K a multiple of 256, N a multiple of 8, scheme 4 (block 64) or 8.
+bool qskinny_dx_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
+QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int num_cu);
+
+// dX[M,K] bf16 = base_scale dY deq(Wq)^T + scaling dH A^T.  dH: bf16 [M][rp], A: bf16 [K][rp], rp a multiple
+// of 8, at most 64 (both may be NULL when scaling is 0).  part is scratch of the plan's size.
+hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* dH, const void* A,
+                             int64_t rp, float base_scale, float scaling, void* dX, int64_t M, int64_t K, int64_t N,
+                             const QskinnyDxPlan& p, float* part, hipStream_t st);
+
 }  // namespace fhpc

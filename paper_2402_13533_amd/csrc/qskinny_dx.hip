@@ -1,0 +1,301 @@
+// Weight-streaming input gradient of the quantised finetuning layer for a handful of tokens
+// (M <= 64, in blocks of 16):
+//   dX[m][k] = base_scale * sum_n dY[m][n] q[n][k] scale(n, k) + scaling * sum_j dH[m][j] A[k][j],
+// the backward of Y = X deq(W) + s (X A) B with respect to X (Sec. 5.1; W is frozen, so there is no dW).
+//
+// The reduction runs over the rows n of the stored weight ([N][K] codes, k contiguous), so the
+// contraction index of the matrix instruction is the one index along which nothing is contiguous.
+// v_mfma_f32_16x16x4_f32 takes ONE contraction element per lane and register, which fits that
+// exactly: lane (i, g) loads eight bytes of row n(g) - eight int8 or sixteen int4 codes along k -
+// and instruction c of the step uses code c of every lane, so its 16 operand rows are the columns
+// k = k0 + CODES * i + c and its four contraction slots are four different rows n.  The other
+// operand is dY[m][n(g)] as fp32.  Each code position c has its own 16 x 16 accumulator
+// (CODES * 4 registers).  Codes are converted with v_cvt_f32_ubyte (after an XOR that makes them
+// unsigned) and scaled by the lane's own fp16 scale in one fma: (u - offset) * scale is exact in
+// fp32, so the weight is used unrounded and the sums are fp32 throughout.  Both schemes have the
+// scale of a lane's codes in one scalar: int8 scales belong to the row n, int4 scales to
+// (row n, block k / 64), and a lane's sixteen codes lie in one block.
+//
+// Work split: a workgroup of eight waves owns a column strip of 16 * CODES inputs k and a slice
+// of the rows n; its waves take the 32-row steps of the slice in turn and add their accumulators
+// through LDS; slices write fp32 slabs [slice][M][K]; dx_finish_kernel adds the slabs and the
+// rank-r branch and rounds to bf16.  More than 16 tokens are further workgroups (blockIdx.z) that
+// stream the same weight again (it is then served by the caches).
+#include "qskinny.h"
+#include "profile.h"
+
+#include <hip/hip_fp16.h>
+#include <stdio.h>
+#include <type_traits>
+
+namespace fhpc {
+namespace skinny_dx {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int NT = 512, WAVES = 8;
+constexpr int TOK = 16;                // tokens per workgroup (the matrix instruction's columns)
+constexpr int STEP_ROWS = 32;          // rows n per step of a wave: four lane groups x eight loads
+constexpr uint32_t OOB = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) { return __half2float(__ushort_as_half((unsigned short)h)); }
+
+// Column of the LDS reduction buffer for strip-local input k: within each run of 64 columns the
+// index is XORed with 16 * (run number), which spreads the four lane groups of a wave (whose
+// columns differ by the run) over different banks; rows are padded to an odd length for the
+// sixteen tokens.
+__device__ __forceinline__ int red_col(int kl)
+{
+    const int run = kl >> 6;
+    return (run << 6) | ((kl & 63) ^ ((run & 3) << 4));
+}
+
+template <int SCHEME>
+__global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__ dY, const void* __restrict__ Wq,
+                                                        const void* __restrict__ scales, float* __restrict__ part,
+                                                        int M, int K, int N, int steps_per_slice, int steps_total)
+{
+    constexpr bool I4 = (SCHEME == 4);
+    constexpr int CODES = I4 ? 16 : 8;               // codes in a lane's eight bytes
+    constexpr int KC = 16 * CODES;                   // inputs k per workgroup
+    constexpr int RS = KC + 1;                       // padded row of the reduction buffer
+    __shared__ float red[WAVES * TOK * RS];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int strip = blockIdx.x, slice = blockIdx.y, tb = blockIdx.z;
+    const int k0 = strip * KC + CODES * i;           // first input of this lane's codes
+    const int step_beg = slice * steps_per_slice;
+    const int step_end = (step_beg + steps_per_slice < steps_total) ? step_beg + steps_per_slice : steps_total;
+
+    const int64_t row_bytes = I4 ? K / 2 : K;
+    const __amdgpu_buffer_rsrc_t rw = rsrc(Wq, (int64_t)N * row_bytes);
+    const __amdgpu_buffer_rsrc_t rs = rsrc(scales, I4 ? (int64_t)N * (K / 64) * 2 : (int64_t)N * 2);
+    const __amdgpu_buffer_rsrc_t rd = rsrc(dY, (int64_t)M * N * 2);
+    const uint32_t wcol = (uint32_t)(I4 ? k0 / 2 : k0);          // byte of the lane's codes within a row
+    const uint32_t scol = I4 ? (uint32_t)(k0 / 64) * 2u : 0u;    // byte of the lane's block scale within a row of scales
+    const int m = tb * TOK + i;                                  // this lane's token (dY operand and accumulator column)
+    const uint32_t dyrow = (m < M) ? (uint32_t)((int64_t)m * N * 2) : OOB;
+
+    f32x4 acc[CODES];
+#pragma unroll
+    for (int c = 0; c < CODES; c++) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // What a lane reads for one step: rows n = 32 step + 8 g + s, s < 8.  N is a multiple of 8, so the
+    // eight rows are inside the weight together or not at all; what lies outside reads as zero
+    // (an offset beyond the buffer), and so does the dY chunk, which makes those rows contribute 0.
+    u32x2 wq[2][8];
+    uint32_t sc4[2][8];                              // int4: one fp16 scale per row (this lane's block)
+    u32x4 sc8[2];                                    // int8: the eight rows' fp16 scales
+    u32x4 dyq[2];                                    // dY[m][n .. n + 7] bf16
+    auto load = [&](auto BUF, int step) __attribute__((always_inline)) {
+        constexpr int b = decltype(BUF)::value;
+        const int n0 = step * STEP_ROWS + 8 * g;
+        const bool inside = n0 < N;
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const uint32_t off = inside ? (uint32_t)((int64_t)(n0 + s) * row_bytes) + wcol : OOB;
+            wq[b][s] = __builtin_amdgcn_raw_buffer_load_b64(rw, off, 0, 0);
+        }
+        if constexpr (I4) {
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const uint32_t off = inside ? (uint32_t)((int64_t)(n0 + s) * (K / 64) * 2) + scol : OOB;
+                sc4[b][s] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, off, 0, 0);
+            }
+        } else {
+            sc8[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, inside ? (uint32_t)n0 * 2u : OOB, 0, 0);
+        }
+        dyq[b] = __builtin_amdgcn_raw_buffer_load_b128(rd, (inside && m < M) ? dyrow + (uint32_t)n0 * 2u : OOB, 0, 0);
+    };
+    auto compute = [&](auto BUF) __attribute__((always_inline)) {
+        constexpr int b = decltype(BUF)::value;
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const uint32_t dword = dyq[b][s >> 1];
+            const float dy = __uint_as_float((s & 1) ? (dword & 0xffff0000u) : (dword << 16));
+            float sc;
+            if constexpr (I4) {
+                sc = half_bits_to_float(sc4[b][s]);
+            } else {
+                const uint32_t sword = sc8[b][s >> 1];
+                sc = half_bits_to_float((s & 1) ? (sword >> 16) : (sword & 0xffffu));
+            }
+            const float off = (I4 ? -8.f : -128.f) * sc;
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t w = wq[b][s][h];
+                if constexpr (I4) {
+                    // nibble ^ 8 = q + 8; byte j of `lo` is code 2 j of this word, byte j of `hi` code 2 j + 1
+                    const uint32_t u = w ^ 0x88888888u;
+                    const uint32_t lo = u & 0x0f0f0f0fu, hi = (u >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        const float f0 = fmaf((float)((lo >> (8 * j)) & 0xffu), sc, off);
+                        const float f1 = fmaf((float)((hi >> (8 * j)) & 0xffu), sc, off);
+                        acc[8 * h + 2 * j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f0, dy, acc[8 * h + 2 * j], 0, 0, 0);
+                        acc[8 * h + 2 * j + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f1, dy, acc[8 * h + 2 * j + 1], 0, 0, 0);
+                    }
+                } else {
+                    const uint32_t u = w ^ 0x80808080u;          // byte ^ 0x80 = q + 128
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        const float f = fmaf((float)((u >> (8 * j)) & 0xffu), sc, off);
+                        acc[4 * h + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f, dy, acc[4 * h + j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    };
+
+    // the waves of the workgroup take the steps of the slice in turn; two register sets, the
+    // loads of a wave's next step are out before it computes the current one
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    int step = step_beg + wave;
+    if (step < step_end) load(B0{}, step);
+    while (step < step_end) {
+        if (step + WAVES < step_end) load(B1{}, step + WAVES);
+        compute(B0{});
+        step += WAVES;
+        if (step >= step_end) break;
+        if (step + WAVES < step_end) load(B0{}, step + WAVES);
+        compute(B1{});
+        step += WAVES;
+    }
+
+    // accumulator view: lane holds token i (column) and the operand rows 4 g + v, i.e. the strip-local
+    // inputs CODES * (4 g + v) + c
+#pragma unroll
+    for (int c = 0; c < CODES; c++)
+#pragma unroll
+        for (int v = 0; v < 4; v++) red[(wave * TOK + i) * RS + red_col(CODES * (4 * g + v) + c)] = acc[c][v];
+    __syncthreads();
+    for (int o = tid; o < TOK * KC; o += NT) {
+        const int mm = o / KC, kl = o - mm * KC;
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; w++) t += red[(w * TOK + mm) * RS + red_col(kl)];
+        const int mg = tb * TOK + mm;
+        if (mg < M) part[((int64_t)slice * M + mg) * K + strip * KC + kl] = t;
+    }
+}
+
+// dX[m][k] = bf16( base_scale * sum_s part[s][m][k] + scaling * sum_j dH[m][j] A[k][j] ).
+// One output per thread (grid: 256 inputs k x one token).  dH is bf16 [M][rp], A is bf16 [K][rp],
+// rp a multiple of 8 and at most 64.  All loads are requested before the first wait: the pieces of
+// the row of A beyond rp get an offset outside the buffer and read as zero.
+constexpr int FIN_NT = 256, FIN_DEPTH = 8, FIN_RMAX = 64;
+__global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restrict__ part, int slices,
+                                                           const uint16_t* __restrict__ dH, const uint16_t* __restrict__ A,
+                                                           int rp, float base_scale, float scaling,
+                                                           uint16_t* __restrict__ dX, int M, int K)
+{
+    __shared__ float dh[FIN_RMAX];
+    const int m = blockIdx.y, k = blockIdx.x * FIN_NT + threadIdx.x;       // K is a multiple of 256
+    const bool branch = (scaling != 0.f) && dH && A;
+    float dhv = 0.f;
+    if (branch && (int)threadIdx.x < rp) dhv = __uint_as_float((uint32_t)dH[(int64_t)m * rp + threadIdx.x] << 16);
+    const __amdgpu_buffer_rsrc_t rA = rsrc(A, branch ? (int64_t)K * rp * 2 : 0);
+    u32x4 a[FIN_RMAX / 8];
+#pragma unroll
+    for (int q = 0; q < FIN_RMAX / 8; q++) {
+        const uint32_t off = (branch && 8 * q < rp) ? (uint32_t)((int64_t)k * rp + 8 * q) * 2u : OOB;
+        a[q] = __builtin_amdgcn_raw_buffer_load_b128(rA, off, 0, 0);
+    }
+    float base = 0.f;
+    for (int s0 = 0; s0 < slices; s0 += FIN_DEPTH) {
+        float v[FIN_DEPTH];
+#pragma unroll
+        for (int q = 0; q < FIN_DEPTH; q++) {
+            const int s = s0 + q;
+            const float x = part[((int64_t)(s < slices ? s : s0) * M + m) * K + k];
+            v[q] = (s < slices) ? x : 0.f;
+        }
+        base += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    }
+    if (threadIdx.x < FIN_RMAX) dh[threadIdx.x] = dhv;
+    __syncthreads();
+    float l = 0.f;
+#pragma unroll
+    for (int q = 0; q < FIN_RMAX / 8; q++) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const uint32_t word = a[q][e];
+            l = fmaf(__uint_as_float(word << 16), dh[8 * q + 2 * e], l);
+            l = fmaf(__uint_as_float(word & 0xffff0000u), dh[8 * q + 2 * e + 1], l);
+        }
+    }
+    const __bf16 o = (__bf16)(base_scale * base + scaling * l);
+    dX[(int64_t)m * K + k] = __builtin_bit_cast(uint16_t, o);
+}
+
+}  // namespace skinny_dx
+
+bool qskinny_dx_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
+{
+    if (scheme != 4 && scheme != 8) return false;
+    // the kernels address each operand with 32-bit byte offsets below 2^31
+    const int64_t lim = (int64_t)1 << 31;
+    if (N < 8 || K < 256 || (N % 8) || (K % 256)) return false;
+    if (N * K >= lim || M * N * 2 >= lim || K * 64 * 2 >= lim) return false;
+    return M >= 1 && M <= 4 * skinny_dx::TOK && r >= 1 && r <= skinny_dx::FIN_RMAX;
+}
+
+QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int num_cu)
+{
+    using namespace skinny_dx;
+    QskinnyDxPlan p;
+    const int64_t kc = (scheme == 4) ? 256 : 128;
+    // one workgroup per compute unit (registers: two waves per SIMD; int4 also by its 129 KB reduction buffer)
+    const int64_t per_cu = 1;
+    p.strips = (int)(K / kc);
+    p.token_blocks = (int)((M + TOK - 1) / TOK);
+    p.steps_total = (int)((N + STEP_ROWS - 1) / STEP_ROWS);
+    // one round of resident workgroups; a slice is at least one step for each of the eight waves
+    int64_t s = per_cu * (int64_t)num_cu / ((int64_t)p.strips * p.token_blocks);
+    const int64_t most = (p.steps_total + WAVES - 1) / WAVES;
+    if (s > most) s = most;
+    if (s < 1) s = 1;
+    p.steps_per_slice = (int)((p.steps_total + s - 1) / s);
+    p.slices = (int)((p.steps_total + p.steps_per_slice - 1) / p.steps_per_slice);
+    p.part_bytes = (int64_t)p.slices * M * K * 4;
+    return p;
+}
+
+hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* dH, const void* A,
+                             int64_t rp, float base_scale, float scaling, void* dX, int64_t M, int64_t K, int64_t N,
+                             const QskinnyDxPlan& p, float* part, hipStream_t st)
+{
+    using namespace skinny_dx;
+    if (rp > FIN_RMAX || (rp % 8)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)p.strips, (unsigned)p.slices, (unsigned)p.token_blocks);
+    const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
+    const int slot = prof_begin(scheme == 4 ? "qskinny_dx<int4>" : "qskinny_dx<int8>", 2.0 * M * K * (double)N,
+                                wbytes + 2.0 * M * N + 4.0 * p.slices * M * K, st);
+    if (scheme == 4)
+        hipLaunchKernelGGL((qskinny_dx_kernel<4>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
+                           p.steps_per_slice, p.steps_total);
+    else
+        hipLaunchKernelGGL((qskinny_dx_kernel<8>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
+                           p.steps_per_slice, p.steps_total);
+    prof_end(slot, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int fslot = prof_begin("qskinny_dx_finish", 0.0, 0.0, st);
+    hipLaunchKernelGGL(dx_finish_kernel, dim3((unsigned)(K / FIN_NT), (unsigned)M), dim3(FIN_NT), 0, st, part, p.slices,
+                       static_cast<const uint16_t*>(dH), static_cast<const uint16_t*>(A), (int)rp, base_scale, scaling,
+                       static_cast<uint16_t*>(dX), (int)M, (int)K);
+    prof_end(fslot, st);
+    return hipGetLastError();
+}
+
+}  // namespace fhpc

@@ -266,6 +266,68 @@ def test_few_token_forward_every_code(scheme):
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,K,r,N", [
+    (1, 512, 16, 72),          # one token; fewer 32-row steps than waves, the last one ragged
+    (7, 2048, 5, 200),         # odd rank (padded internally)
+    (16, 5120, 16, 328),       # a full token block, twenty column strips
+    (3, 1024, 64, 8),          # widest rank the path takes; a single group of eight rows
+    (17, 1536, 16, 136),       # two token blocks, the second with one token
+    (33, 2048, 24, 1096),      # three token blocks; several steps per wave
+    (64, 4096, 16, 520),       # the most tokens the path takes
+    (5, 256, 8, 8200),         # one column strip, many slices of the reduction
+])
+def test_few_token_step(scheme, M, K, r, N):
+    """M <= 64 tokens: forward through the weight-streaming kernel (K a multiple of 512), and the
+    input gradient through its counterpart (K a multiple of 256) that reduces over the rows of the stored weight (fp32
+    matrix instructions on exactly converted codes); dA, dB, saved and recomputed H as everywhere."""
+    _run_case("few q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=110)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
+def test_few_token_input_gradient_every_code(scheme):
+    """Random bytes as codes (the 4-bit code -8 and the int8 code -128 occur) with random positive
+    fp16 scales, subnormals included; scaling 0 isolates the frozen weight, whose product is then
+    exact up to the fp32 sums and the final rounding to bf16."""
+    fhpc = _fhpc()
+    rng = np.random.default_rng(12)
+    M, K, N = 5, 512, 136
+    if scheme == 4:
+        Wq = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+        sc = rng.integers(0x0001, 0x3C00, size=(N, K // 64)).astype(np.uint16)
+    else:
+        Wq = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+        sc = rng.integers(0x0001, 0x3C00, size=(N,)).astype(np.uint16)
+    Wd = oracle.dequant(Wq, sc, scheme, 64)
+    _, X, A, B, dY = qlinear_inputs(8, M, K, 8, N, 75)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    dX, _, _ = fhpc.qlinear_lowrank_bwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0, dY.cuda())
+    ref = dY.f64 @ Wd.T
+    e = oracle.rel_fro(from_device(dX), ref)
+    print("few tokens q%d dX every code: %.3e" % (scheme, e), flush=True)
+    assert e <= 3e-3           # one rounding of the result to bf16: 2^-9 at most per element
+
+
+def test_few_token_blend_backward():
+    """The blend layer's backward at a handful of tokens: alpha scales the frozen-weight term of dX."""
+    fhpc = _fhpc()
+    M, K, r, N = 9, 768, 16, 264
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 95)
+    for scheme in (8, 4):
+        Wq, sc = _quantize_host(W, scheme)
+        Wd = oracle.dequant(Wq, sc, scheme, 64)
+        Wq_d, sc_d = _to_dev(Wq, sc)
+        for alpha in (0.3, 1.0, 0.0):
+            dX, dA, dB = fhpc.qlinear_blend_bwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), alpha, dY.cuda())
+            dXr, dAr, dBr = oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
+            for name, got, ref in (("dX", dX, dXr), ("dA", dA, dAr), ("dB", dB, dBr)):
+                if np.linalg.norm(ref) == 0.0:
+                    assert not from_device(got).any()
+                    continue
+                e = oracle.rel_fro(from_device(got), ref)
+                assert e <= TOL_BF16, (scheme, alpha, name, e)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("alpha", [1.0, 0.7, 0.25, 0.0])
 @pytest.mark.parametrize("M", [300, 1040])
 def test_blend_layer(scheme, alpha, M):
