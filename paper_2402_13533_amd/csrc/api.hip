@@ -340,6 +340,11 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha,
                  const Scratch& s, hipStream_t st)
 {
+    if ((dA || dB) && few_token_grads_supports(M, rp)) {
+        // a handful of tokens: M-deep sums, both products in one launch
+        FHPC_HIP(launch_few_token_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
+        return FHPC_OK;
+    }
     if (dA) {
         float* dst = (rp == r) ? dA : s.dA_t;
         FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, s.part, st));

@@ -1,6 +1,7 @@
 // fp32 GEMM (true fp32 arithmetic), SiLU gate, weight quantise / unpack / dequantise,
 // and the small copy / convert kernels the entry points use around the GEMM core.
 #include "kernels_misc.h"
+#include "profile.h"
 
 namespace fhpc {
 
@@ -701,6 +702,88 @@ hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s)
     const int64_t n = bytes / 4;
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(zero_u32_kernel, dim3(grid_for(n)), dim3(256), 0, s, (uint32_t*)p, n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Rank-r weight gradients from a handful of tokens.  With M <= 64 the two products are M-deep
+// sums over outputs that are read once, far too small for the matrix-core tiles: a thread owns
+// one column c of the streamed operand U (a k for dA with U = X, an n for dB with U = dY), keeps
+// its r sums in registers and adds  U[m][c] * V[m][j]  token by token, V (dH or H, M x rp) sitting
+// in LDS as fp32 where every lane reads the same word.  The workgroups of both products share a
+// launch: the first ceil(K / 256) take dA, the rest dB.
+// ---------------------------------------------------------------------------------
+constexpr int FTG_NT = 256, FTG_MMAX = 64, FTG_RMAX = 64;
+
+template <int MT, int RP>
+__global__ __launch_bounds__(FTG_NT) void few_token_grads_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dH,
+                                                                float* __restrict__ dA, const uint16_t* __restrict__ H,
+                                                                const uint16_t* __restrict__ dY, float* __restrict__ dB,
+                                                                int M, int K, int r, int rp, int N, float alpha, int blocks_a)
+{
+    __shared__ float Vs[MT * RP];
+    const bool is_a = (int)blockIdx.x < blocks_a;
+    const uint16_t* const U = is_a ? X : dY;
+    const uint16_t* const V = is_a ? dH : H;
+    const int ld = is_a ? K : N;
+    const int c = (is_a ? (int)blockIdx.x : (int)blockIdx.x - blocks_a) * FTG_NT + (int)threadIdx.x;
+    // this thread's column of U, every token requested at once (tokens past M and columns past the
+    // end get an offset outside the buffer and read as zero)
+    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(U), 0, (int)((int64_t)M * ld * 2), 0x00020000);
+    float u[MT];
+#pragma unroll
+    for (int m = 0; m < MT; m++) {
+        const uint32_t off = (m < M && c < ld) ? (uint32_t)(((int64_t)m * ld + c) * 2) : 0x80000000u;
+        u[m] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(ru, off, 0, 0) << 16);
+    }
+    for (int e = threadIdx.x; e < MT * RP; e += FTG_NT) {
+        const int m = e / RP, j = e - m * RP;
+        Vs[e] = (m < M && j < rp) ? __uint_as_float((uint32_t)V[(int64_t)m * rp + j] << 16) : 0.f;
+    }
+    __syncthreads();
+    float acc[RP];
+#pragma unroll
+    for (int j = 0; j < RP; j++) acc[j] = 0.f;
+#pragma unroll
+    for (int m = 0; m < MT; m++) {
+#pragma unroll
+        for (int j = 0; j < RP; j++) acc[j] = fmaf(u[m], Vs[m * RP + j], acc[j]);
+    }
+    if (c >= ld) return;
+    if (is_a) {
+        float* out = dA + (int64_t)c * r;                          // dA[k][0 .. r)
+#pragma unroll
+        for (int j = 0; j < RP; j++)
+            if (j < r) out[j] = alpha * acc[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < RP; j++)
+            if (j < r) dB[(int64_t)j * N + c] = alpha * acc[j];    // dB[j][n]
+    }
+}
+
+bool few_token_grads_supports(int64_t M, int64_t rp) { return M >= 1 && M <= FTG_MMAX && rp >= 1 && rp <= FTG_RMAX; }
+
+hipError_t launch_few_token_grads(const void* X, const void* dH, float* dA, const void* H, const void* dY, float* dB,
+                                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha, hipStream_t s)
+{
+    if (!few_token_grads_supports(M, rp)) return hipErrorInvalidValue;
+    const int blocks_a = dA ? (int)((K + FTG_NT - 1) / FTG_NT) : 0;
+    const int blocks_b = dB ? (int)((N + FTG_NT - 1) / FTG_NT) : 0;
+    if (blocks_a + blocks_b == 0) return hipSuccess;
+    const dim3 grid((unsigned)(blocks_a + blocks_b));
+#define FHPC_FTG(MT, RP)                                                                                              \
+    hipLaunchKernelGGL((few_token_grads_kernel<MT, RP>), grid, dim3(FTG_NT), 0, s, static_cast<const uint16_t*>(X),   \
+                       static_cast<const uint16_t*>(dH), dA, static_cast<const uint16_t*>(H),                        \
+                       static_cast<const uint16_t*>(dY), dB, (int)M, (int)K, (int)r, (int)rp, (int)N, alpha, blocks_a)
+    const int slot = prof_begin("few_token_grads", 2.0 * M * r * (double)((dA ? K : 0) + (dB ? N : 0)), 0.0, s);
+    if (M <= 16) {
+        if (rp <= 16) FHPC_FTG(16, 16); else if (rp <= 32) FHPC_FTG(16, 32); else FHPC_FTG(16, 64);
+    } else {
+        if (rp <= 16) FHPC_FTG(64, 16); else if (rp <= 32) FHPC_FTG(64, 32); else FHPC_FTG(64, 64);
+    }
+#undef FHPC_FTG
+    prof_end(slot, s);
     return hipGetLastError();
 }
 
