@@ -4,17 +4,18 @@
 // the backward of Y = X deq(W) + s (X A) B with respect to X (Sec. 5.1; W is frozen, so there is no dW).
 //
 // The reduction runs over the rows n of the stored weight ([N][K] codes, k contiguous), so the
-// contraction index of the matrix instruction is the one index along which nothing is contiguous.
-// v_mfma_f32_16x16x4_f32 takes ONE contraction element per lane and register, which fits that
-// exactly: lane (i, g) loads eight bytes of row n(g) - eight int8 or sixteen int4 codes along k -
-// and instruction c of the step uses code c of every lane, so its 16 operand rows are the columns
-// k = k0 + CODES * i + c and its four contraction slots are four different rows n.  The other
-// operand is dY[m][n(g)] as fp32.  Each code position c has its own 16 x 16 accumulator
-// (CODES * 4 registers).  Codes are converted with v_cvt_f32_ubyte (after an XOR that makes them
-// unsigned) and scaled by the lane's own fp16 scale in one fma: (u - offset) * scale is exact in
-// fp32, so the weight is used unrounded and the sums are fp32 throughout.  Both schemes have the
-// scale of a lane's codes in one scalar: int8 scales belong to the row n, int4 scales to
-// (row n, block k / 64), and a lane's sixteen codes lie in one block.
+// contraction index of the matrix instruction is the one index along which nothing is contiguous
+// in memory.  Lane (i, g) therefore loads eight bytes - eight int8 or sixteen int4 codes along k -
+// from each of the eight rows n = n0 + 8 g + s, and builds, for every code position c, the operand
+// of v_mfma_f32_16x16x32_bf16 from code c of its eight rows: the instruction's 16 operand rows are
+// the inputs k = k0 + CODES * i + c, its 32 contraction slots the 32 rows n of the step.  The other
+// operand is the 16-byte piece dY[m][n0 + 8 g .. + 7] as it lies in memory.  Each code position has
+// its own 16 x 16 accumulator (CODES * 4 registers).  A code becomes an operand element with
+// v_cvt_f32_ubyte (after an XOR that makes it unsigned), one fma with the fp16 scale,
+// (u - offset) * scale, which is exact in fp32, and the rounding to bf16 that every product with
+// this weight applies to deq(W).  Both schemes have the scale of a lane's codes of one row in one
+// scalar: int8 scales belong to the row n, int4 scales to (row n, block k / 64), and a lane's
+// sixteen codes lie in one block.
 //
 // Work split: a workgroup of eight waves owns a column strip of 16 * CODES inputs k and a slice
 // of the rows n; its waves take the 32-row steps of the slice in turn and add their accumulators
@@ -31,6 +32,9 @@
 namespace fhpc {
 namespace skinny_dx {
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -43,6 +47,14 @@ constexpr uint32_t OOB = 0x80000000u;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, int64_t bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 f;
+    f.x = lo;
+    f.y = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) { return __half2float(__ushort_as_half((unsigned short)h)); }
@@ -100,59 +112,70 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
         constexpr int b = decltype(BUF)::value;
         const int n0 = step * STEP_ROWS + 8 * g;
         const bool inside = n0 < N;
+        const uint32_t guard = inside ? 0u : OOB;    // ORed into every offset: outside rows read as zero
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            const uint32_t off = inside ? (uint32_t)((int64_t)(n0 + s) * row_bytes) + wcol : OOB;
+            const uint32_t off = ((uint32_t)(n0 + s) * (uint32_t)row_bytes + wcol) | guard;
             wq[b][s] = __builtin_amdgcn_raw_buffer_load_b64(rw, off, 0, 0);
         }
         if constexpr (I4) {
 #pragma unroll
             for (int s = 0; s < 8; s++) {
-                const uint32_t off = inside ? (uint32_t)((int64_t)(n0 + s) * (K / 64) * 2) + scol : OOB;
+                const uint32_t off = ((uint32_t)(n0 + s) * (uint32_t)(K / 64) * 2u + scol) | guard;
                 sc4[b][s] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, off, 0, 0);
             }
         } else {
-            sc8[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, inside ? (uint32_t)n0 * 2u : OOB, 0, 0);
+            sc8[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)n0 * 2u) | guard, 0, 0);
         }
-        dyq[b] = __builtin_amdgcn_raw_buffer_load_b128(rd, (inside && m < M) ? dyrow + (uint32_t)n0 * 2u : OOB, 0, 0);
+        dyq[b] = __builtin_amdgcn_raw_buffer_load_b128(rd, (dyrow + (uint32_t)n0 * 2u) | guard, 0, 0);
     };
     auto compute = [&](auto BUF) __attribute__((always_inline)) {
         constexpr int b = decltype(BUF)::value;
+        // per row s: the lane's scale and the term that takes the unsigned code's offset out again
+        float sc[8], off[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            const uint32_t dword = dyq[b][s >> 1];
-            const float dy = __uint_as_float((s & 1) ? (dword & 0xffff0000u) : (dword << 16));
-            float sc;
             if constexpr (I4) {
-                sc = half_bits_to_float(sc4[b][s]);
+                sc[s] = half_bits_to_float(sc4[b][s]);
             } else {
                 const uint32_t sword = sc8[b][s >> 1];
-                sc = half_bits_to_float((s & 1) ? (sword >> 16) : (sword & 0xffffu));
+                sc[s] = half_bits_to_float((s & 1) ? (sword >> 16) : (sword & 0xffffu));
             }
-            const float off = (I4 ? -8.f : -128.f) * sc;
+            off[s] = (I4 ? -8.f : -128.f) * sc[s];
+        }
+        const bf16x8 dy = __builtin_bit_cast(bf16x8, dyq[b]);      // dY[m][n0 + 8 g + 0 .. 7]
+        // unsigned codes as bytes: int4 word h of row s -> lo[s][h] (codes 0 2 4 6 of the word), hi[s][h] (1 3 5 7)
+        uint32_t ub[8][2][I4 ? 2 : 1];
+#pragma unroll
+        for (int s = 0; s < 8; s++)
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t w = wq[b][s][h];
                 if constexpr (I4) {
-                    // nibble ^ 8 = q + 8; byte j of `lo` is code 2 j of this word, byte j of `hi` code 2 j + 1
-                    const uint32_t u = w ^ 0x88888888u;
-                    const uint32_t lo = u & 0x0f0f0f0fu, hi = (u >> 4) & 0x0f0f0f0fu;
-#pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        const float f0 = fmaf((float)((lo >> (8 * j)) & 0xffu), sc, off);
-                        const float f1 = fmaf((float)((hi >> (8 * j)) & 0xffu), sc, off);
-                        acc[8 * h + 2 * j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f0, dy, acc[8 * h + 2 * j], 0, 0, 0);
-                        acc[8 * h + 2 * j + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f1, dy, acc[8 * h + 2 * j + 1], 0, 0, 0);
-                    }
+                    const uint32_t u = wq[b][s][h] ^ 0x88888888u;      // nibble ^ 8 = q + 8
+                    ub[s][h][0] = u & 0x0f0f0f0fu;
+                    ub[s][h][1] = (u >> 4) & 0x0f0f0f0fu;
+                    // (opaque to the optimiser: a byte of a masked word converts with one
+                    // v_cvt_f32_ubyteN; seen through, it becomes a 4-bit field extract plus a convert)
+                    asm volatile("" : "+v"(ub[s][h][0]), "+v"(ub[s][h][1]));
                 } else {
-                    const uint32_t u = w ^ 0x80808080u;          // byte ^ 0x80 = q + 128
-#pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        const float f = fmaf((float)((u >> (8 * j)) & 0xffu), sc, off);
-                        acc[4 * h + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(f, dy, acc[4 * h + j], 0, 0, 0);
-                    }
+                    ub[s][h][0] = wq[b][s][h] ^ 0x80808080u;           // byte ^ 0x80 = q + 128
                 }
             }
+#pragma unroll
+        for (int c = 0; c < CODES; c++) {
+            // code c of the lane's eight rows -> one operand: element s = bf16((u - offset) * scale of row s)
+            const int h = I4 ? c >> 3 : c >> 2;                    // word
+            const int j = I4 ? (c & 7) >> 1 : c & 3;               // byte within the word
+            const int par = I4 ? c & 1 : 0;                        // int4: even / odd code of the byte
+            float f[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) f[s] = fmaf((float)((ub[s][h][par] >> (8 * j)) & 0xffu), sc[s], off[s]);
+            u32x4 wv;
+            wv.x = pack_bf16(f[0], f[1]);
+            wv.y = pack_bf16(f[2], f[3]);
+            wv.z = pack_bf16(f[4], f[5]);
+            wv.w = pack_bf16(f[6], f[7]);
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), dy, acc[c], 0, 0, 0);
         }
     };
 
