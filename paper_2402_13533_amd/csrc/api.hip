@@ -55,6 +55,7 @@ struct Scratch {
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
     float* sk_dxpart = nullptr; // weight-streaming input gradient (few tokens): slabs of M x K
+    float* sk_dhpart = nullptr; //                                                partial sums of dY B^T
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
@@ -183,6 +184,11 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         const int64_t b4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, kNumCU).part_bytes;
         const int64_t b8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, kNumCU).part_bytes;
         s.sk_dxpart = static_cast<float*>(c.take(b4 > b8 ? b4 : b8));
+        if (rp <= 16) {       // dH = dY B^T is then formed by the same launch, one partial sum per slice
+            const int s4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, kNumCU).slices;
+            const int s8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, kNumCU).slices;
+            s.sk_dhpart = static_cast<float*>(c.take((int64_t)(s4 > s8 ? s4 : s8) * M * rp * 4));
+        }
     }
     // split reductions of this entry point run one after another and share the slabs
     int64_t part = 0;
@@ -835,7 +841,9 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
         }
     }
     const bool merged_dx = premerged || (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
-    if (dA || (dX && !merged_dx))
+    const bool streamed_dx = dX && s.sk_dxpart && base_scale != 0.f;
+    const bool dh_on_the_way = streamed_dx && s.sk_dhpart;                        // the streaming launch forms dH itself
+    if (!dh_on_the_way && (dA || (dX && !merged_dx)))
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX && base_scale == 0.f) {
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st, scaling));
@@ -848,11 +856,12 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
             Wm = s.Wm;
         }
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, st));
-    } else if (dX && s.sk_dxpart) {
-        // a handful of tokens: one pass over the packed weight (slabs), then slabs + rank-r branch -> bf16
+    } else if (streamed_dx) {
+        // a handful of tokens: one pass over the packed weight (slabs; for r <= 16 also dH = dY B^T),
+        // then slabs + rank-r branch -> bf16, and dH for dA
         const QskinnyDxPlan p = qskinny_dx_plan(M, K, N, qscheme, kNumCU);
-        FHPC_HIP(launch_qskinny_dx(dY, Wq, scales, qscheme, s.dH, f.A, rp, base_scale, scaling, dX, M, K, N, p,
-                                   s.sk_dxpart, st));
+        FHPC_HIP(launch_qskinny_dx(dY, Wq, scales, qscheme, f.B, f.A, rp, base_scale, scaling, dX, s.dH, M, K, N, p,
+                                   s.sk_dxpart, s.sk_dhpart, st));
     } else if (dX) {
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};

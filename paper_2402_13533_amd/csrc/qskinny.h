@@ -52,10 +52,12 @@ struct QskinnyDxPlan {
 bool qskinny_dx_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int num_cu);
 
-// dX[M,K] bf16 = base_scale dY deq(Wq)^T + scaling dH A^T.  dH: bf16 [M][rp], A: bf16 [K][rp], rp a multiple
-// of 8, at most 64 (both may be NULL when scaling is 0).  part is scratch of the plan's size.
-hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* dH, const void* A,
-                             int64_t rp, float base_scale, float scaling, void* dX, int64_t M, int64_t K, int64_t N,
-                             const QskinnyDxPlan& p, float* part, hipStream_t st);
+// dX[M,K] bf16 = base_scale dY deq(Wq)^T + scaling dH A^T,  dH = dY B^T (bf16 [M][rp]).
+// With dhpart (scratch of slices * M * rp floats; rp <= 16, B: bf16 [rp][N]) dH is formed by the launch
+// itself and stored to dH (may be NULL); without it dH is an input.  A: bf16 [K][rp]; rp a multiple of 8,
+// at most 64.  part is scratch of the plan's size.
+hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* B, const void* A,
+                             int64_t rp, float base_scale, float scaling, void* dX, void* dH_out, int64_t M, int64_t K, int64_t N,
+                             const QskinnyDxPlan& p, float* part, float* dhpart, hipStream_t st);
 
 }  // namespace fhpc

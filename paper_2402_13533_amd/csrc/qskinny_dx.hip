@@ -20,8 +20,12 @@
 // Work split: a workgroup of eight waves owns a column strip of 16 * CODES inputs k and a slice
 // of the rows n; its waves take the 32-row steps of the slice in turn and add their accumulators
 // through LDS; slices write fp32 slabs [slice][M][K]; dx_finish_kernel adds the slabs and the
-// rank-r branch and rounds to bf16.  More than 16 tokens are further workgroups (blockIdx.z) that
-// stream the same weight again (it is then served by the caches).
+// rank-r branch and rounds to bf16.  More than 16 tokens are further workgroups that stream the
+// same weight again (it is then served by the caches).  dH = dY B^T (M x r), which the rank-r branch
+// and dA need, is formed on the way when r <= 16: the workgroups of the first strip also multiply
+// their dY pieces with the matching pieces of B (one more 16-byte load and one more matrix
+// instruction per step) and write dH's sums over their slices; the finish kernel adds them (and
+// stores dH as bf16 for dA).
 #include "qskinny.h"
 #include "profile.h"
 
@@ -72,7 +76,9 @@ __device__ __forceinline__ int red_col(int kl)
 template <int SCHEME>
 __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__ dY, const void* __restrict__ Wq,
                                                         const void* __restrict__ scales, float* __restrict__ part,
-                                                        int M, int K, int N, int steps_per_slice, int steps_total)
+                                                        int M, int K, int N, int steps_per_slice, int steps_total,
+                                                        int strips, int slices, int token_blocks,
+                                                        const void* __restrict__ Bf, float* __restrict__ dhpart, int rp)
 {
     constexpr bool I4 = (SCHEME == 4);
     constexpr int CODES = I4 ? 16 : 8;               // codes in a lane's eight bytes
@@ -83,7 +89,15 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, g = lane >> 4;
-    const int strip = blockIdx.x, slice = blockIdx.y, tb = blockIdx.z;
+    // Workgroup -> work item.  Consecutive workgroup numbers go to the eight XCDs in turn, each with
+    // its own L2, so item w = (number % 8) * (items / 8) + number / 8 gives every XCD a contiguous
+    // run of the list (token block fastest, then strip, then slice): the token blocks of one strip read
+    // the same codes, and neighbouring strips of one slice share the lines of int4 scales (64 blocks,
+    // i.e. 16 strips, per 128-byte line) and the dY rows.
+    const int per_xcd = (int)gridDim.x >> 3;
+    const int w = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (w >= strips * slices * token_blocks) return;             // the grid is rounded up to a multiple of 8
+    const int tb = w % token_blocks, strip = (w / token_blocks) % strips, slice = w / (token_blocks * strips);
     const int k0 = strip * KC + CODES * i;           // first input of this lane's codes
     const int step_beg = slice * steps_per_slice;
     const int step_end = (step_beg + steps_per_slice < steps_total) ? step_beg + steps_per_slice : steps_total;
@@ -96,6 +110,13 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
     const uint32_t scol = I4 ? (uint32_t)(k0 / 64) * 2u : 0u;    // byte of the lane's block scale within a row of scales
     const int m = tb * TOK + i;                                  // this lane's token (dY operand and accumulator column)
     const uint32_t dyrow = (m < M) ? (uint32_t)((int64_t)m * N * 2) : OOB;
+
+    // first strip: dH[m][j] = sum_n dY[m][n] B[j][n] over this slice beside the main sums (lane i is row j of B)
+    const bool with_dh = (strip == 0) && (dhpart != nullptr);
+    const __amdgpu_buffer_rsrc_t rb = rsrc(Bf, with_dh ? (int64_t)rp * N * 2 : 0);
+    const uint32_t brow = (with_dh && i < rp) ? (uint32_t)((int64_t)i * N * 2) : OOB;
+    f32x4 acc_dh = {0.f, 0.f, 0.f, 0.f};
+    u32x4 bq[2];
 
     f32x4 acc[CODES];
 #pragma unroll
@@ -128,6 +149,7 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
             sc8[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)n0 * 2u) | guard, 0, 0);
         }
         dyq[b] = __builtin_amdgcn_raw_buffer_load_b128(rd, (dyrow + (uint32_t)n0 * 2u) | guard, 0, 0);
+        if (with_dh) bq[b] = __builtin_amdgcn_raw_buffer_load_b128(rb, (brow + (uint32_t)n0 * 2u) | guard, 0, 0);
     };
     auto compute = [&](auto BUF) __attribute__((always_inline)) {
         constexpr int b = decltype(BUF)::value;
@@ -144,38 +166,41 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
             off[s] = (I4 ? -8.f : -128.f) * sc[s];
         }
         const bf16x8 dy = __builtin_bit_cast(bf16x8, dyq[b]);      // dY[m][n0 + 8 g + 0 .. 7]
-        // unsigned codes as bytes: int4 word h of row s -> lo[s][h] (codes 0 2 4 6 of the word), hi[s][h] (1 3 5 7)
-        uint32_t ub[8][2][I4 ? 2 : 1];
+        if (with_dh) acc_dh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[b]), dy, acc_dh, 0, 0, 0);
+        // word h of the eight rows at a time (keeps the unpacked codes of one word live, not of both)
 #pragma unroll
-        for (int s = 0; s < 8; s++)
+        for (int h = 0; h < 2; h++) {
+            // unsigned codes as bytes: int4 -> lo (codes 0 2 4 6 of the word) and hi (codes 1 3 5 7)
+            uint32_t ub[8][I4 ? 2 : 1];
 #pragma unroll
-            for (int h = 0; h < 2; h++) {
+            for (int s = 0; s < 8; s++) {
                 if constexpr (I4) {
                     const uint32_t u = wq[b][s][h] ^ 0x88888888u;      // nibble ^ 8 = q + 8
-                    ub[s][h][0] = u & 0x0f0f0f0fu;
-                    ub[s][h][1] = (u >> 4) & 0x0f0f0f0fu;
+                    ub[s][0] = u & 0x0f0f0f0fu;
+                    ub[s][1] = (u >> 4) & 0x0f0f0f0fu;
                     // (opaque to the optimiser: a byte of a masked word converts with one
                     // v_cvt_f32_ubyteN; seen through, it becomes a 4-bit field extract plus a convert)
-                    asm volatile("" : "+v"(ub[s][h][0]), "+v"(ub[s][h][1]));
+                    asm volatile("" : "+v"(ub[s][0]), "+v"(ub[s][1]));
                 } else {
-                    ub[s][h][0] = wq[b][s][h] ^ 0x80808080u;           // byte ^ 0x80 = q + 128
+                    ub[s][0] = wq[b][s][h] ^ 0x80808080u;              // byte ^ 0x80 = q + 128
                 }
             }
 #pragma unroll
-        for (int c = 0; c < CODES; c++) {
-            // code c of the lane's eight rows -> one operand: element s = bf16((u - offset) * scale of row s)
-            const int h = I4 ? c >> 3 : c >> 2;                    // word
-            const int j = I4 ? (c & 7) >> 1 : c & 3;               // byte within the word
-            const int par = I4 ? c & 1 : 0;                        // int4: even / odd code of the byte
-            float f[8];
+            for (int cc = 0; cc < CODES / 2; cc++) {
+                // code c of the lane's eight rows -> one operand: element s = bf16((u - offset) * scale of row s)
+                const int c = h * (CODES / 2) + cc;
+                const int j = I4 ? cc >> 1 : cc;                       // byte within the word
+                const int par = I4 ? cc & 1 : 0;                       // int4: even / odd code of the byte
+                float f[8];
 #pragma unroll
-            for (int s = 0; s < 8; s++) f[s] = fmaf((float)((ub[s][h][par] >> (8 * j)) & 0xffu), sc[s], off[s]);
-            u32x4 wv;
-            wv.x = pack_bf16(f[0], f[1]);
-            wv.y = pack_bf16(f[2], f[3]);
-            wv.z = pack_bf16(f[4], f[5]);
-            wv.w = pack_bf16(f[6], f[7]);
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), dy, acc[c], 0, 0, 0);
+                for (int s = 0; s < 8; s++) f[s] = fmaf((float)((ub[s][par] >> (8 * j)) & 0xffu), sc[s], off[s]);
+                u32x4 wv;
+                wv.x = pack_bf16(f[0], f[1]);
+                wv.y = pack_bf16(f[2], f[3]);
+                wv.z = pack_bf16(f[4], f[5]);
+                wv.w = pack_bf16(f[6], f[7]);
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), dy, acc[c], 0, 0, 0);
+            }
         }
     };
 
@@ -210,23 +235,42 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
         const int mg = tb * TOK + mm;
         if (mg < M) part[((int64_t)slice * M + mg) * K + strip * KC + kl] = t;
     }
+    if (with_dh) {
+        // dH of this slice: lane holds token i and the rows j = 4 g + v; added over the waves like the main sums
+        constexpr int DS = TOK + 1;
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 4; v++) red[(wave * TOK + i) * DS + 4 * g + v] = acc_dh[v];
+        __syncthreads();
+        if (tid < TOK * TOK) {
+            const int mm = tid >> 4, j = tid & 15;
+            float t = 0.f;
+#pragma unroll
+            for (int w8 = 0; w8 < WAVES; w8++) t += red[(w8 * TOK + mm) * DS + j];
+            const int mg = tb * TOK + mm;
+            if (mg < M && j < rp) dhpart[((int64_t)slice * M + mg) * rp + j] = t;
+        }
+    }
 }
 
-// dX[m][k] = bf16( base_scale * sum_s part[s][m][k] + scaling * sum_j dH[m][j] A[k][j] ).
-// One output per thread (grid: 256 inputs k x one token).  dH is bf16 [M][rp], A is bf16 [K][rp],
-// rp a multiple of 8 and at most 64.  All loads are requested before the first wait: the pieces of
-// the row of A beyond rp get an offset outside the buffer and read as zero.
+// dX[m][k] = bf16( base_scale * sum_s part[s][m][k] + scaling * sum_j dH[m][j] A[k][j] ),  dH = sum_c dhpart[c].
+// One output per thread (grid: 256 inputs k x one token).  A is bf16 [K][rp], rp a multiple of 8 and at
+// most 64.  All loads are requested before the first wait: the pieces of the row of A beyond rp get an
+// offset outside the buffer and read as zero; the chunk sums of dH are read as 16-byte pieces, thread
+// (p, g) taking piece p of the chunks g, g + G, ..., eight in flight; the workgroups of the first 256
+// inputs then also store dH[m] as bf16 (dA is formed from it afterwards).  Without dhpart, dH is an
+// input (bf16 [M][rp]).
 constexpr int FIN_NT = 256, FIN_DEPTH = 8, FIN_RMAX = 64;
 __global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restrict__ part, int slices,
-                                                           const uint16_t* __restrict__ dH, const uint16_t* __restrict__ A,
+                                                           const float* __restrict__ dhpart, int dh_chunks,
+                                                           uint16_t* __restrict__ dH, const uint16_t* __restrict__ A,
                                                            int rp, float base_scale, float scaling,
                                                            uint16_t* __restrict__ dX, int M, int K)
 {
     __shared__ float dh[FIN_RMAX];
+    __shared__ __attribute__((aligned(16))) float dg[FIN_NT * 4];
     const int m = blockIdx.y, k = blockIdx.x * FIN_NT + threadIdx.x;       // K is a multiple of 256
-    const bool branch = (scaling != 0.f) && dH && A;
-    float dhv = 0.f;
-    if (branch && (int)threadIdx.x < rp) dhv = __uint_as_float((uint32_t)dH[(int64_t)m * rp + threadIdx.x] << 16);
+    const bool branch = (scaling != 0.f) && A;
     const __amdgpu_buffer_rsrc_t rA = rsrc(A, branch ? (int64_t)K * rp * 2 : 0);
     u32x4 a[FIN_RMAX / 8];
 #pragma unroll
@@ -234,18 +278,61 @@ __global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restri
         const uint32_t off = (branch && 8 * q < rp) ? (uint32_t)((int64_t)k * rp + 8 * q) * 2u : OOB;
         a[q] = __builtin_amdgcn_raw_buffer_load_b128(rA, off, 0, 0);
     }
-    float base = 0.f;
-    for (int s0 = 0; s0 < slices; s0 += FIN_DEPTH) {
-        float v[FIN_DEPTH];
+    auto sum8 = [](const auto (&v)[FIN_DEPTH]) __attribute__((always_inline)) {
+        return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    };
+    auto part_batch = [&](float (&v)[FIN_DEPTH], int s0) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < FIN_DEPTH; q++) {
             const int s = s0 + q;
             const float x = part[((int64_t)(s < slices ? s : s0) * M + m) * K + k];
             v[q] = (s < slices) ? x : 0.f;
         }
-        base += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    };
+    float pv[FIN_DEPTH];
+    part_batch(pv, 0);
+    // dH[m][.]: chunk c holds it at dhpart[(c M + m) rp ..]
+    const int P = rp >> 2;                                      // 16-byte pieces per chunk
+    const int G = (FIN_NT / P < dh_chunks) ? FIN_NT / P : dh_chunks;   // groups that have a chunk to start from
+    {
+        const int p = threadIdx.x % P, g = threadIdx.x / P;
+        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        f32x4 sv = zero4;
+        if (dhpart && g < G) {
+            const float* src = dhpart + (int64_t)m * rp + 4 * p;
+            const int64_t stride = (int64_t)M * rp;
+            for (int c0 = g; c0 < dh_chunks; c0 += FIN_DEPTH * G) {
+                f32x4 v[FIN_DEPTH];
+#pragma unroll
+                for (int q = 0; q < FIN_DEPTH; q++) {
+                    const int c = c0 + q * G;
+                    const f32x4 x = *reinterpret_cast<const f32x4*>(src + (int64_t)(c < dh_chunks ? c : c0) * stride);
+                    v[q] = (c < dh_chunks) ? x : zero4;
+                }
+                sv += sum8(v);
+            }
+            *reinterpret_cast<f32x4*>(dg + (g * P + p) * 4) = sv;          // dg[g][4 p ..] of [G][rp]
+        }
     }
-    if (threadIdx.x < FIN_RMAX) dh[threadIdx.x] = dhv;
+    float base = sum8(pv);
+    for (int s0 = FIN_DEPTH; s0 < slices; s0 += FIN_DEPTH) {
+        part_batch(pv, s0);
+        base += sum8(pv);
+    }
+    __syncthreads();
+    if (threadIdx.x < FIN_RMAX) {
+        float t = 0.f;
+        if (dhpart && (int)threadIdx.x < rp) {
+            for (int g = 0; g < G; g++) t += dg[g * rp + threadIdx.x];     // group order: the same sum every run
+            if (blockIdx.x == 0 && dH) {
+                const __bf16 hb = (__bf16)t;
+                dH[(int64_t)m * rp + threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
+            }
+        } else if (!dhpart && dH && branch && (int)threadIdx.x < rp) {
+            t = __uint_as_float((uint32_t)dH[(int64_t)m * rp + threadIdx.x] << 16);   // formed by the caller
+        }
+        dh[threadIdx.x] = t;
+    }
     __syncthreads();
     float l = 0.f;
 #pragma unroll
@@ -294,29 +381,31 @@ QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int n
     return p;
 }
 
-hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* dH, const void* A,
-                             int64_t rp, float base_scale, float scaling, void* dX, int64_t M, int64_t K, int64_t N,
-                             const QskinnyDxPlan& p, float* part, hipStream_t st)
+hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* B, const void* A,
+                             int64_t rp, float base_scale, float scaling, void* dX, void* dH, int64_t M, int64_t K, int64_t N,
+                             const QskinnyDxPlan& p, float* part, float* dhpart, hipStream_t st)
 {
     using namespace skinny_dx;
-    if (rp > FIN_RMAX || (rp % 8)) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)p.strips, (unsigned)p.slices, (unsigned)p.token_blocks);
+    if (rp > FIN_RMAX || rp < 8 || (rp % 8)) return hipErrorInvalidValue;
+    if (dhpart && (rp > TOK || !B)) return hipErrorInvalidValue;
+    const int64_t items = (int64_t)p.strips * p.slices * p.token_blocks;
+    const dim3 grid((unsigned)((items + 7) / 8 * 8));
     const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
     const int slot = prof_begin(scheme == 4 ? "qskinny_dx<int4>" : "qskinny_dx<int8>", 2.0 * M * K * (double)N,
                                 wbytes + 2.0 * M * N + 4.0 * p.slices * M * K, st);
     if (scheme == 4)
         hipLaunchKernelGGL((qskinny_dx_kernel<4>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
-                           p.steps_per_slice, p.steps_total);
+                           p.steps_per_slice, p.steps_total, p.strips, p.slices, p.token_blocks, B, dhpart, (int)rp);
     else
         hipLaunchKernelGGL((qskinny_dx_kernel<8>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
-                           p.steps_per_slice, p.steps_total);
+                           p.steps_per_slice, p.steps_total, p.strips, p.slices, p.token_blocks, B, dhpart, (int)rp);
     prof_end(slot, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int fslot = prof_begin("qskinny_dx_finish", 0.0, 0.0, st);
     hipLaunchKernelGGL(dx_finish_kernel, dim3((unsigned)(K / FIN_NT), (unsigned)M), dim3(FIN_NT), 0, st, part, p.slices,
-                       static_cast<const uint16_t*>(dH), static_cast<const uint16_t*>(A), (int)rp, base_scale, scaling,
-                       static_cast<uint16_t*>(dX), (int)M, (int)K);
+                       dhpart, p.slices, static_cast<uint16_t*>(dH), static_cast<const uint16_t*>(A), (int)rp,
+                       base_scale, scaling, static_cast<uint16_t*>(dX), (int)M, (int)K);
     prof_end(fslot, st);
     return hipGetLastError();
 }
