@@ -860,8 +860,11 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
         // a handful of tokens: one pass over the packed weight (slabs; for r <= 16 also dH = dY B^T),
         // then slabs + rank-r branch -> bf16, and dH for dA
         const QskinnyDxPlan p = qskinny_dx_plan(M, K, N, qscheme, kNumCU);
+        QskinnyDxGrads grads = {X, H, dA, dB, r, scaling};
+        const bool grads_ride = dh_on_the_way && (dA || dB);       // dA, dB in the finish launch
         FHPC_HIP(launch_qskinny_dx(dY, Wq, scales, qscheme, f.B, f.A, rp, base_scale, scaling, dX, s.dH, M, K, N, p,
-                                   s.sk_dxpart, s.sk_dhpart, st));
+                                   s.sk_dxpart, s.sk_dhpart, grads_ride ? &grads : nullptr, st));
+        if (grads_ride) return FHPC_OK;
     } else if (dX) {
         // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
         GemmArgs g = {};

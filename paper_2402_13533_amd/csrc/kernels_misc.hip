@@ -1,6 +1,7 @@
 // fp32 GEMM (true fp32 arithmetic), SiLU gate, weight quantise / unpack / dequantise,
 // and the small copy / convert kernels the entry points use around the GEMM core.
 #include "kernels_misc.h"
+#include "few_token_grads.h"
 #include "profile.h"
 
 namespace fhpc {
@@ -713,52 +714,19 @@ hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s)
 // in LDS as fp32 where every lane reads the same word.  The workgroups of both products share a
 // launch: the first ceil(K / 256) take dA, the rest dB.
 // ---------------------------------------------------------------------------------
-constexpr int FTG_NT = 256, FTG_MMAX = 64, FTG_RMAX = 64;
-
 template <int MT, int RP>
 __global__ __launch_bounds__(FTG_NT) void few_token_grads_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dH,
                                                                 float* __restrict__ dA, const uint16_t* __restrict__ H,
                                                                 const uint16_t* __restrict__ dY, float* __restrict__ dB,
                                                                 int M, int K, int r, int rp, int N, float alpha, int blocks_a)
 {
-    __shared__ float Vs[MT * RP];
-    const bool is_a = (int)blockIdx.x < blocks_a;
-    const uint16_t* const U = is_a ? X : dY;
-    const uint16_t* const V = is_a ? dH : H;
-    const int ld = is_a ? K : N;
-    const int c = (is_a ? (int)blockIdx.x : (int)blockIdx.x - blocks_a) * FTG_NT + (int)threadIdx.x;
-    // this thread's column of U, every token requested at once (tokens past M and columns past the
-    // end get an offset outside the buffer and read as zero)
-    const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(U), 0, (int)((int64_t)M * ld * 2), 0x00020000);
-    float u[MT];
-#pragma unroll
-    for (int m = 0; m < MT; m++) {
-        const uint32_t off = (m < M && c < ld) ? (uint32_t)(((int64_t)m * ld + c) * 2) : 0x80000000u;
-        u[m] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(ru, off, 0, 0) << 16);
-    }
-    for (int e = threadIdx.x; e < MT * RP; e += FTG_NT) {
-        const int m = e / RP, j = e - m * RP;
-        Vs[e] = (m < M && j < rp) ? __uint_as_float((uint32_t)V[(int64_t)m * rp + j] << 16) : 0.f;
-    }
-    __syncthreads();
-    float acc[RP];
-#pragma unroll
-    for (int j = 0; j < RP; j++) acc[j] = 0.f;
-#pragma unroll
-    for (int m = 0; m < MT; m++) {
-#pragma unroll
-        for (int j = 0; j < RP; j++) acc[j] = fmaf(u[m], Vs[m * RP + j], acc[j]);
-    }
-    if (c >= ld) return;
-    if (is_a) {
-        float* out = dA + (int64_t)c * r;                          // dA[k][0 .. r)
-#pragma unroll
-        for (int j = 0; j < RP; j++)
-            if (j < r) out[j] = alpha * acc[j];
+    __shared__ __attribute__((aligned(16))) float Vs[MT * RP];
+    if ((int)blockIdx.x < blocks_a) {
+        const int c = (int)blockIdx.x * FTG_NT + (int)threadIdx.x;
+        few_token_grads_body<MT, RP, false>(Vs, X, K, c, M, r, alpha, dA, [&](float* v) { fill_from_bf16<MT, RP>(v, dH, M, rp); });
     } else {
-#pragma unroll
-        for (int j = 0; j < RP; j++)
-            if (j < r) dB[(int64_t)j * N + c] = alpha * acc[j];    // dB[j][n]
+        const int c = ((int)blockIdx.x - blocks_a) * FTG_NT + (int)threadIdx.x;
+        few_token_grads_body<MT, RP, true>(Vs, dY, N, c, M, r, alpha, dB, [&](float* v) { fill_from_bf16<MT, RP>(v, H, M, rp); });
     }
 }
 

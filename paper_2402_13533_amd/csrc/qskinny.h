@@ -52,12 +52,23 @@ struct QskinnyDxPlan {
 bool qskinny_dx_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int num_cu);
 
+// The rank-r weight gradients that may ride in the finish launch (only with dhpart, i.e. rp <= 16):
+// dA[K][r] = alpha X^T dH, dB[r][N] = alpha H^T dY (fp32; either may be NULL).  X: bf16 [M][K], H: bf16 [M][rp].
+struct QskinnyDxGrads {
+    const void* X;
+    const void* H;
+    float* dA;
+    float* dB;
+    int64_t r;
+    float alpha;
+};
+
 // dX[M,K] bf16 = base_scale dY deq(Wq)^T + scaling dH A^T,  dH = dY B^T (bf16 [M][rp]).
 // With dhpart (scratch of slices * M * rp floats; rp <= 16, B: bf16 [rp][N]) dH is formed by the launch
 // itself and stored to dH (may be NULL); without it dH is an input.  A: bf16 [K][rp]; rp a multiple of 8,
-// at most 64.  part is scratch of the plan's size.
+// at most 64.  part is scratch of the plan's size.  grads may be NULL.
 hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* B, const void* A,
-                             int64_t rp, float base_scale, float scaling, void* dX, void* dH_out, int64_t M, int64_t K, int64_t N,
-                             const QskinnyDxPlan& p, float* part, float* dhpart, hipStream_t st);
+                             int64_t rp, float base_scale, float scaling, void* dX, void* dH, int64_t M, int64_t K, int64_t N,
+                             const QskinnyDxPlan& p, float* part, float* dhpart, const QskinnyDxGrads* grads, hipStream_t st);
 
 }  // namespace fhpc

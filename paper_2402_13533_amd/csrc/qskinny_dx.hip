@@ -27,6 +27,7 @@
 // instruction per step) and write dH's sums over their slices; the finish kernel adds them (and
 // stores dH as bf16 for dA).
 #include "qskinny.h"
+#include "few_token_grads.h"
 #include "profile.h"
 
 #include <hip/hip_fp16.h>
@@ -261,15 +262,32 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
 // inputs then also store dH[m] as bf16 (dA is formed from it afterwards).  Without dhpart, dH is an
 // input (bf16 [M][rp]).
 constexpr int FIN_NT = 256, FIN_DEPTH = 8, FIN_RMAX = 64;
-__global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restrict__ part, int slices,
-                                                           const float* __restrict__ dhpart, int dh_chunks,
-                                                           uint16_t* __restrict__ dH, const uint16_t* __restrict__ A,
-                                                           int rp, float base_scale, float scaling,
-                                                           uint16_t* __restrict__ dX, int M, int K)
+constexpr int FIN_LDS = FIN_NT * 4 + FIN_RMAX;                             // floats: group sums, then dH[m]
+struct FinishArgs {
+    const float* part;
+    int slices;
+    const float* dhpart;
+    int dh_chunks;
+    uint16_t* dH;
+    const uint16_t* A;
+    int rp;
+    float base_scale, scaling;
+    uint16_t* dX;
+    int M, K;
+};
+// workgroup (bx, m): the 256 inputs k from 256 bx of token m
+__device__ __forceinline__ void dx_finish_body(float* smem, int bx, int m, const FinishArgs& fa)
 {
-    __shared__ float dh[FIN_RMAX];
-    __shared__ __attribute__((aligned(16))) float dg[FIN_NT * 4];
-    const int m = blockIdx.y, k = blockIdx.x * FIN_NT + threadIdx.x;       // K is a multiple of 256
+    float* const dg = smem;
+    float* const dh = smem + FIN_NT * 4;
+    const float* __restrict__ part = fa.part;
+    const float* __restrict__ dhpart = fa.dhpart;
+    uint16_t* __restrict__ dH = fa.dH;
+    const uint16_t* __restrict__ A = fa.A;
+    uint16_t* __restrict__ dX = fa.dX;
+    const int slices = fa.slices, dh_chunks = fa.dh_chunks, rp = fa.rp, M = fa.M, K = fa.K;
+    const float base_scale = fa.base_scale, scaling = fa.scaling;
+    const int k = bx * FIN_NT + threadIdx.x;                               // K is a multiple of 256
     const bool branch = (scaling != 0.f) && A;
     const __amdgpu_buffer_rsrc_t rA = rsrc(A, branch ? (int64_t)K * rp * 2 : 0);
     u32x4 a[FIN_RMAX / 8];
@@ -324,7 +342,7 @@ __global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restri
         float t = 0.f;
         if (dhpart && (int)threadIdx.x < rp) {
             for (int g = 0; g < G; g++) t += dg[g * rp + threadIdx.x];     // group order: the same sum every run
-            if (blockIdx.x == 0 && dH) {
+            if (bx == 0 && dH) {
                 const __bf16 hb = (__bf16)t;
                 dH[(int64_t)m * rp + threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
             }
@@ -346,6 +364,67 @@ __global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(const float* __restri
     }
     const __bf16 o = (__bf16)(base_scale * base + scaling * l);
     dX[(int64_t)m * K + k] = __builtin_bit_cast(uint16_t, o);
+}
+
+__global__ __launch_bounds__(FIN_NT) void dx_finish_kernel(FinishArgs fa)
+{
+    __shared__ __attribute__((aligned(16))) float smem[FIN_LDS];
+    dx_finish_body(smem, blockIdx.x, blockIdx.y, fa);
+}
+
+// The finish of dX and the rank-r weight gradients in one launch (they are independent of each other
+// once the streaming launch has written its slabs): workgroups [0, fin_blocks) finish dX, the next
+// blocks_a form dA = alpha X^T dH with dH summed in fp32 from the per-slice sums, the rest
+// dB = alpha H^T dY.  rp <= 16.
+struct GradArgs {
+    const uint16_t* X;
+    const uint16_t* H;
+    const uint16_t* dY;
+    float* dA;
+    float* dB;
+    int r, N, fin_blocks, blocks_a;
+    float alpha;
+};
+template <int MT>
+__global__ __launch_bounds__(FIN_NT) void dx_tail_kernel(FinishArgs fa, GradArgs ga)
+{
+    constexpr int RP = 16;
+    static_assert(FTG_NT == FIN_NT && MT * RP <= FIN_LDS, "shared workgroup shape and LDS");
+    __shared__ __attribute__((aligned(16))) float smem[FIN_LDS];
+    const int b = blockIdx.x;
+    if (b < ga.fin_blocks) {
+        const int per_token = fa.K / FIN_NT;
+        dx_finish_body(smem, b % per_token, b / per_token, fa);
+    } else if (b < ga.fin_blocks + ga.blocks_a) {
+        const int c = (b - ga.fin_blocks) * FIN_NT + (int)threadIdx.x;
+        few_token_grads_body<MT, RP, false>(smem, ga.X, fa.K, c, fa.M, ga.r, ga.alpha, ga.dA, [&](float* v) {
+            // v[m][j] = sum over the slices of dhpart[(s M + m) rp + j], eight loads in flight (a slice
+            // index past the end repeats an earlier, valid address and is dropped by the select)
+            for (int e = threadIdx.x; e < MT * RP; e += FIN_NT) {
+                const int m = e / RP, j = e - m * RP;
+                float t = 0.f;
+                if (m < fa.M && j < fa.rp) {
+                    const float* src = fa.dhpart + (int64_t)m * fa.rp + j;
+                    const int64_t stride = (int64_t)fa.M * fa.rp;
+                    for (int s0 = 0; s0 < fa.dh_chunks; s0 += FIN_DEPTH) {
+                        float x[FIN_DEPTH];
+#pragma unroll
+                        for (int q = 0; q < FIN_DEPTH; q++) {
+                            const int sl = s0 + q;
+                            const float y = src[(int64_t)(sl < fa.dh_chunks ? sl : s0) * stride];
+                            x[q] = (sl < fa.dh_chunks) ? y : 0.f;
+                        }
+                        t += ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+                    }
+                }
+                v[e] = t;
+            }
+        });
+    } else {
+        const int c = (b - ga.fin_blocks - ga.blocks_a) * FIN_NT + (int)threadIdx.x;
+        few_token_grads_body<MT, RP, true>(smem, ga.dY, ga.N, c, fa.M, ga.r, ga.alpha, ga.dB,
+                                           [&](float* v) { fill_from_bf16<MT, RP>(v, ga.H, fa.M, fa.rp); });
+    }
 }
 
 }  // namespace skinny_dx
@@ -383,11 +462,12 @@ QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int n
 
 hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales, int scheme, const void* B, const void* A,
                              int64_t rp, float base_scale, float scaling, void* dX, void* dH, int64_t M, int64_t K, int64_t N,
-                             const QskinnyDxPlan& p, float* part, float* dhpart, hipStream_t st)
+                             const QskinnyDxPlan& p, float* part, float* dhpart, const QskinnyDxGrads* grads, hipStream_t st)
 {
     using namespace skinny_dx;
     if (rp > FIN_RMAX || rp < 8 || (rp % 8)) return hipErrorInvalidValue;
     if (dhpart && (rp > TOK || !B)) return hipErrorInvalidValue;
+    if (grads && !dhpart) return hipErrorInvalidValue;
     const int64_t items = (int64_t)p.strips * p.slices * p.token_blocks;
     const dim3 grid((unsigned)((items + 7) / 8 * 8));
     const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
@@ -402,10 +482,27 @@ hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales,
     prof_end(slot, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    FinishArgs fa;
+    fa.part = part; fa.slices = p.slices; fa.dhpart = dhpart; fa.dh_chunks = p.slices;
+    fa.dH = static_cast<uint16_t*>(dH); fa.A = static_cast<const uint16_t*>(A); fa.rp = (int)rp;
+    fa.base_scale = base_scale; fa.scaling = scaling; fa.dX = static_cast<uint16_t*>(dX); fa.M = (int)M; fa.K = (int)K;
+    if (grads && (grads->dA || grads->dB)) {
+        GradArgs ga;
+        ga.X = static_cast<const uint16_t*>(grads->X); ga.H = static_cast<const uint16_t*>(grads->H);
+        ga.dY = static_cast<const uint16_t*>(dY); ga.dA = grads->dA; ga.dB = grads->dB;
+        ga.r = (int)grads->r; ga.N = (int)N; ga.alpha = grads->alpha;
+        ga.fin_blocks = (int)(K / FIN_NT * M);
+        ga.blocks_a = grads->dA ? (int)(K / FIN_NT) : 0;
+        const int blocks_b = grads->dB ? (int)((N + FIN_NT - 1) / FIN_NT) : 0;
+        const dim3 tgrid((unsigned)(ga.fin_blocks + ga.blocks_a + blocks_b));
+        const int tslot = prof_begin("qskinny_dx_finish+grads", 0.0, 0.0, st);
+        if (M <= 16) hipLaunchKernelGGL((dx_tail_kernel<16>), tgrid, dim3(FIN_NT), 0, st, fa, ga);
+        else hipLaunchKernelGGL((dx_tail_kernel<64>), tgrid, dim3(FIN_NT), 0, st, fa, ga);
+        prof_end(tslot, st);
+        return hipGetLastError();
+    }
     const int fslot = prof_begin("qskinny_dx_finish", 0.0, 0.0, st);
-    hipLaunchKernelGGL(dx_finish_kernel, dim3((unsigned)(K / FIN_NT), (unsigned)M), dim3(FIN_NT), 0, st, part, p.slices,
-                       dhpart, p.slices, static_cast<uint16_t*>(dH), static_cast<const uint16_t*>(A), (int)rp,
-                       base_scale, scaling, static_cast<uint16_t*>(dX), (int)M, (int)K);
+    hipLaunchKernelGGL(dx_finish_kernel, dim3((unsigned)(K / FIN_NT), (unsigned)M), dim3(FIN_NT), 0, st, fa);
     prof_end(fslot, st);
     return hipGetLastError();
 }
