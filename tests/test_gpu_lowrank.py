@@ -48,6 +48,7 @@ def test_config1_fp32():
     (515, 1024, 16, 520),    # LoRA-sized rank: split reductions for H and dH
     (640, 512, 96, 1032),    # rank between tile sizes
     (1100, 768, 512, 776),   # pretraining-sized rank
+    (48, 520, 40, 264),      # few tokens, small rank: dA and dB as token-deep sums in one launch
 ])
 def test_bf16_shapes(M, K, r, N):
     fhpc = _fhpc()

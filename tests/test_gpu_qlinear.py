@@ -307,6 +307,45 @@ def test_few_token_input_gradient_every_code(scheme):
     assert e <= TOL_BF16
 
 
+@pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,r", [(5, 8), (37, 24)])
+def test_few_token_backward_optional_outputs_and_canaries(scheme, M, r):
+    """The few-token backward writes nothing outside dX, dA, dB (r <= 16: the gradients ride in the
+    finish launch; above: in a launch of their own), skips NULL outputs, and gives the same bits
+    whichever subset is asked for."""
+    import torch
+    fhpc = _fhpc()
+    K, N = 768, 264
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 120)
+    Wq, sc = _quantize_host(W, scheme)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    pad = 512
+
+    def guarded(rows, cols, dtype):
+        big = torch.full((rows * cols + 2 * pad,), 7.0, dtype=dtype, device="cuda")
+        return big, big[pad:pad + rows * cols].view(rows, cols)
+
+    bX, dX = guarded(M, K, torch.bfloat16)
+    bA, dA = guarded(K, r, torch.float32)
+    bB, dB = guarded(r, N, torch.float32)
+    fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, dX=dX, dA=dA, dB=dB)
+    for big, n in ((bX, M * K), (bA, K * r), (bB, r * N)):
+        assert bool((big[:pad] == 7.0).all()) and bool((big[pad + n:] == 7.0).all())
+    ref = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd)
+    for got, want in zip((dX, dA, dB), ref):
+        assert torch.equal(got, want)
+    only_dx = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, need_dA=False, need_dB=False)
+    assert only_dx[1] is None and only_dx[2] is None and torch.equal(only_dx[0], ref[0])
+    no_dx = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, need_dX=False)
+    assert no_dx[0] is None
+    # without dX the gradients go through dH rounded to bf16 (the GEMM kernels), with it through fp32 sums
+    assert oracle.rel_fro(from_device(no_dx[1]), from_device(ref[1]).astype(np.float64)) <= TOL_BF16
+    assert oracle.rel_fro(from_device(no_dx[2]), from_device(ref[2]).astype(np.float64)) <= 1e-6
+    only_db = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, need_dA=False)
+    assert only_db[1] is None and torch.equal(only_db[0], ref[0]) and torch.equal(only_db[2], ref[2])
+
+
 def test_few_token_blend_backward():
     """The blend layer's backward at a handful of tokens: alpha scales the frozen-weight term of dX."""
     fhpc = _fhpc()
