@@ -49,7 +49,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "merge"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "merge", "streams"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0,
                     help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
@@ -207,6 +207,45 @@ class MergeCall:
         self.f.lowrank_merge(self.Wq, self.sc, self.scheme, self.A, self.B, self.s, W_out=self.out)
 
 
+class StreamCall:
+    """One of the pure streaming kernels of the path (no matrix work): a closure and its algorithmic bytes."""
+
+    def __init__(self, fn, nbytes):
+        self.fn, self.nbytes = fn, nbytes
+
+    def flops(self):
+        return 0
+
+    def io_bytes(self):
+        return self.nbytes
+
+    def run(self):
+        self.fn()
+
+
+def stream_calls(fhpc, gen):
+    """SiLU gate forward / backward on config 3's 16384 x 11008 activations; dequantise and quantise
+    on config 5's widest weight (5120 x 13824), both schemes."""
+    import torch
+    bf = torch.bfloat16
+    n = 16384 * 11008
+    G, U, dZ = (randn((16384, 11008), 1.0, bf, gen) for _ in range(3))
+    Z, dG, dU = (torch.empty_like(G) for _ in range(3))
+    K, N = 5120, 13824
+    W = randn((K, N), 0.02, torch.float32, gen)
+    calls = [StreamCall(lambda: fhpc.swiglu_fwd(G, U, Z=Z), 6 * n),
+             StreamCall(lambda: fhpc.swiglu_bwd(G, U, dZ, dG=dG, dU=dU), 10 * n)]
+    for scheme in (4, 8):
+        Wq, sc = fhpc.qweight_quantize(W, scheme)
+        out = torch.empty((N, K), dtype=torch.float32, device="cuda")
+        packed = Wq.numel() * Wq.element_size() + 2 * sc.numel()
+        calls.append(StreamCall(lambda Wq=Wq, sc=sc, scheme=scheme, out=out: fhpc.qweight_dequant(Wq, sc, scheme, W_out=out),
+                                packed + 4 * K * N))
+        calls.append(StreamCall(lambda Wq=Wq, sc=sc, scheme=scheme: fhpc.qweight_quantize(W, scheme, Wq_out=Wq, scales_out=sc),
+                                4 * K * N + packed))
+    return calls
+
+
 class FfnCall:
     """Config 3: gate/up 4096 -> r -> 11008, SiLU gate, down 11008 -> r -> 4096, fwd + bwd."""
 
@@ -259,6 +298,11 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         calls = [QlinearCall(fhpc, M, K, 8, N, 8, gen, 2.0, recompute, forward_only, premerged) for _ in range(1 if shape else 4)]
         desc = "config 4: int8 per-channel frozen W %dx%d + rank-8 branch, %d tokens, bf16, %s, %d buffer set(s) per step" % (
             K, N, M, "fwd" if forward_only else "fwd+bwd", len(calls))
+        dtype = "bf16"
+    elif name == "streams":
+        calls = stream_calls(fhpc, gen)
+        desc = ("streaming kernels: SiLU gate fwd/bwd on 16384x11008 bf16, dequantise and quantise of a 5120x13824 "
+                "weight (int4 block-64, int8 per-channel)")
         dtype = "bf16"
     elif name == "merge":
         d, f = 5120, 13824
@@ -414,8 +458,8 @@ def main():
                         "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": share}
 
     metric, value, unit = "fwd+bwd TFLOP/s", tflops, "TFLOP/s"
-    if args.workload == "merge":       # a streaming pass: quoted in bytes moved
-        metric, value, unit = "merge GB/s", io_bytes / (ms_per_step * 1e-3) / 1e9, "GB/s"
+    if args.workload in ("merge", "streams"):       # streaming passes: quoted in bytes moved
+        metric, value, unit = args.workload + " GB/s", io_bytes / (ms_per_step * 1e-3) / 1e9, "GB/s"
     out = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -432,7 +476,7 @@ def main():
         for _ in range(3):
             torch.add(x, 1.0, out=y)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and args.workload != "merge":
+    if not args.no_cpu_baseline and args.workload not in ("merge", "streams"):
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))
 

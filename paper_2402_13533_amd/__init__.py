@@ -342,17 +342,18 @@ def fhpc_gemm_bf16(A, lda, a_mode, B, ldb, b_mode, C, ldc, out_mode, M, N, K, al
     return C
 
 
-def qweight_quantize(W, qscheme, block=64):
-    """W fp32 [K,N] on the device -> (Wq, scales) in the canonical layout."""
+def qweight_quantize(W, qscheme, block=64, Wq_out=None, scales_out=None):
+    """W fp32 [K,N] on the device -> (Wq, scales) in the canonical layout (into Wq_out, scales_out when given)."""
     torch = _torch()
     _check(W, "W", None, torch.float32)
     K, N = W.shape
     if qscheme == FHPC_Q_INT8_PER_CHANNEL:
-        Wq = torch.empty((N, K), dtype=torch.int8, device=W.device)
-        sc = torch.empty((N,), dtype=torch.float16, device=W.device)
+        wshape, wdtype, sshape = (N, K), torch.int8, (N,)
     else:
-        Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
-        sc = torch.empty((N, max(K // block, 1)), dtype=torch.float16, device=W.device)
+        wshape, wdtype, sshape = (N, K // 2), torch.uint8, (N, max(K // block, 1))
+    Wq = Wq_out if Wq_out is not None else torch.empty(wshape, dtype=wdtype, device=W.device)
+    sc = scales_out if scales_out is not None else torch.empty(sshape, dtype=torch.float16, device=W.device)
+    _check(Wq, "Wq_out", wshape, wdtype); _check(sc, "scales_out", sshape, torch.float16)
     rc = load_library().qweight_quantize(_ptr(W), qscheme, block, _ptr(Wq), _ptr(sc), K, N, _stream())
     if rc:
         raise FhpcError(rc, "qweight_quantize")
@@ -455,12 +456,13 @@ def qweight_unpack(Wq, qscheme):
     return q
 
 
-def qweight_dequant(Wq, scales, qscheme, block=64):
+def qweight_dequant(Wq, scales, qscheme, block=64, W_out=None):
     torch = _torch()
     N = Wq.shape[0]
     K = Wq.shape[1] * (2 if qscheme == FHPC_Q_INT4_BLOCK else 1)
     _q_shapes(Wq, scales, qscheme, K, N, block)
-    out = torch.empty((N, K), dtype=torch.float32, device=Wq.device)
+    out = W_out if W_out is not None else torch.empty((N, K), dtype=torch.float32, device=Wq.device)
+    _check(out, "W_out", (N, K), torch.float32)
     rc = load_library().qweight_dequant(_ptr(Wq), _ptr(scales), qscheme, block, _ptr(out), K, N, _stream())
     if rc:
         raise FhpcError(rc, "qweight_dequant")

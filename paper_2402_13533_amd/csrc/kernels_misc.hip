@@ -213,8 +213,10 @@ static unsigned grid_for8(int64_t n, bool bf16)
 hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, bool bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
+    const int slot = prof_begin("swiglu_fwd", 0.0, 3.0 * n * (bf16 ? 2 : 4), s);
     if (bf16) hipLaunchKernelGGL(swiglu_fwd_kernel<true>, dim3(grid_for8(n, true)), dim3(256), 0, s, G, U, Z, n);
     else hipLaunchKernelGGL(swiglu_fwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, Z, n);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 
@@ -230,8 +232,10 @@ hipError_t launch_swiglu_bwd(const void* G, const void* U, const void* dZ, void*
                              bool bf16, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
+    const int slot = prof_begin("swiglu_bwd", 0.0, 5.0 * n * (bf16 ? 2 : 4), s);
     if (bf16) hipLaunchKernelGGL(swiglu_bwd_kernel<true>, dim3(grid_for8(n, true)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
     else hipLaunchKernelGGL(swiglu_bwd_kernel<false>, dim3(grid_for(n)), dim3(256), 0, s, G, U, dZ, dG, dU, n);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 
@@ -266,47 +270,84 @@ hipError_t launch_unpack(const void* Wq, int scheme, int8_t* q, int64_t K, int64
     return hipGetLastError();
 }
 
-// W_out[n][k] = code * scale, exact in fp32 (at most 8 + 11 significant bits).
+// W_out[n][k] = code * scale, exact in fp32 (at most 8 + 11 significant bits).  A thread takes eight
+// consecutive k of one row (K is a multiple of 8, and of the block for the 4-bit scheme, so the
+// eight share one scale): 4 or 8 bytes of codes in, 32 bytes out.
+template <int SCHEME>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ Wq, const uint16_t* __restrict__ scales,
-                                                      int scheme, int64_t block, float* __restrict__ out, int64_t K, int64_t N)
+                                                      int64_t block, float* __restrict__ out, int64_t K, int64_t N)
 {
-    const int64_t total = K * N;
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+    const int64_t per_row = K / 8, total = per_row * N;
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
-        const int64_t n = i / K, k = i % K;
-        int code;
+        const int64_t n = i / per_row, k = (i - n * per_row) * 8;
+        int q[8];
         float sc;
-        if (scheme == 8) {
-            code = (int8_t)Wq[i];
+        if (SCHEME == 8) {
+            const u32x2_t w = *reinterpret_cast<const u32x2_t*>(Wq + n * K + k);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                q[e] = (int)__builtin_amdgcn_sbfe(w.x, 8 * e, 8);
+                q[4 + e] = (int)__builtin_amdgcn_sbfe(w.y, 8 * e, 8);
+            }
             sc = (float)__builtin_bit_cast(_Float16, scales[n]);
         } else {
-            const int b = Wq[i >> 1];
-            code = (k & 1) ? __builtin_amdgcn_sbfe(b, 4, 4) : __builtin_amdgcn_sbfe(b, 0, 4);
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(Wq + n * (K / 2) + k / 2);
+#pragma unroll
+            for (int e = 0; e < 8; e++) q[e] = (int)__builtin_amdgcn_sbfe(w, 4 * e, 4);     // element k even in the low nibble
             sc = (float)__builtin_bit_cast(_Float16, scales[n * (K / block) + k / block]);
         }
-        out[i] = (float)code * sc;
+        f32x4_t lo = {(float)q[0] * sc, (float)q[1] * sc, (float)q[2] * sc, (float)q[3] * sc};
+        f32x4_t hi = {(float)q[4] * sc, (float)q[5] * sc, (float)q[6] * sc, (float)q[7] * sc};
+        float* dst = out + n * K + k;
+        *reinterpret_cast<f32x4_t*>(dst) = lo;
+        *reinterpret_cast<f32x4_t*>(dst + 4) = hi;
     }
 }
 
 hipError_t launch_dequant(const void* Wq, const void* scales, int scheme, int64_t block, float* out,
                           int64_t K, int64_t N, hipStream_t s)
 {
-    hipLaunchKernelGGL(dequant_kernel, dim3(grid_for(K * N)), dim3(256), 0, s, (const uint8_t*)Wq,
-                       (const uint16_t*)scales, scheme, block, out, K, N);
+    // algorithmic bytes: the packed codes and scales in, fp32 out
+    const double in_bytes = (scheme == 4) ? K * N * 0.5 + 2.0 * N * (K / block) : (double)K * N + 2.0 * N;
+    const int slot = prof_begin(scheme == 4 ? "qweight_dequant<int4>" : "qweight_dequant<int8>", 0.0, in_bytes + 4.0 * K * N, s);
+    if (scheme == 4)
+        hipLaunchKernelGGL(dequant_kernel<4>, dim3(grid_for(K * N / 8)), dim3(256), 0, s, (const uint8_t*)Wq,
+                           (const uint16_t*)scales, block, out, K, N);
+    else
+        hipLaunchKernelGGL(dequant_kernel<8>, dim3(grid_for(K * N / 8)), dim3(256), 0, s, (const uint8_t*)Wq,
+                           (const uint16_t*)scales, block, out, K, N);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 
-// Quantiser (Sec. 5.2: one scale per weight vector; here symmetric absmax).  The work is cut
-// into tiles of 64 k x 64 output channels of W[K,N] so that thousands of workgroups stream W
-// at once: 256 threads = 64 columns x 4 k-lanes, rows of W read 256 bytes at a time, each
-// thread keeps its 16 values in registers.
+// Quantiser (Sec. 5.2: one scale per weight vector; here symmetric absmax).  W is [K][N] fp32 with n
+// contiguous, the codes are [N][K] with k contiguous, so this is a transposing pass.  The work is cut
+// into tiles of 64 k x 64 output channels so that thousands of workgroups stream W at once:
+// 256 threads = 64 columns x 4 k-lanes, rows of W read 256 bytes at a time, each thread keeps its 16
+// values in registers; the codes pass through LDS and leave as 8-byte stores, 16 codes of one channel
+// per thread (with byte stores the same kernels ran at two thirds of the speed).  Small tiles on
+// purpose: a thread cannot produce a code before the whole weight vector's absmax is known, so loads and
+// arithmetic overlap only across waves, and 64-deep blocks per thread (fewer, fatter waves with wider
+// loads) measured 149-157 us against 87 us on a 5120 x 13824 weight.
 //   4-bit, block 64: a tile is exactly one weight vector per column: absmax, scale, codes.
 //   int8 per channel: the vector is the whole column, so the column maxima come first
-//   (absmax_tiles_kernel -> partial maxima, column_scale_kernel -> fp16 scales) and the code
-//   kernel then reads the finished scale.
+//   (absmax_rows_kernel -> partial maxima, column_scale_kernel -> fp16 scales) and the code
+//   kernel then reads the finished scale: two passes over W.
 // Arithmetic per element, identical in both: scale = fp16_rne(absmax / qmax) with an fp32
 // divide; q = clamp(rint(w / float(scale)), -qmax, qmax), 0 when the scale is 0.
 constexpr int QT = 64;
+
+template <int QMAX>
+__device__ __forceinline__ int quantize_code(float w, float sf)
+{
+    if (sf == 0.f) return 0;
+    float t = rintf(w / sf);
+    t = fminf(fmaxf(t, -(float)QMAX), (float)QMAX);
+    return (int)t;
+}
 
 __device__ __forceinline__ void load_tile_column(const float* __restrict__ W, int64_t K, int64_t N, int64_t k0, int64_t n,
                                                  int kl, float (&w)[16])
@@ -318,40 +359,39 @@ __device__ __forceinline__ void load_tile_column(const float* __restrict__ W, in
     }
 }
 
-// codes of one tile: thread (col, kl) holds k = kl + 4 i; stored transposed so that every
-// output channel's 64 codes leave as one contiguous run
+// codes of one tile: thread (col, kl) holds k = kl + 4 i; they pass through LDS so that thread
+// (channel r, piece) then owns 16 consecutive codes of one channel: 8 bytes packed (4-bit), or two
+// 8-byte halves (int8; K is a multiple of 8, so a half is inside the row or not at all)
 template <int QMAX, bool PACK4>
 __device__ __forceinline__ void store_tile_codes(const float (&w)[16], float sf, uint8_t* __restrict__ Wq, int64_t K, int64_t N,
-                                                 int64_t k0, int64_t n0, uint8_t (&s_code)[QT][QT + 4])
+                                                 int64_t k0, int64_t n0, uint8_t (&s_code)[QT][QT + 8])
 {
     const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        int code = 0;
-        if (sf != 0.f) {
-            float t = rintf(w[i] / sf);
-            t = fminf(fmaxf(t, -(float)QMAX), (float)QMAX);
-            code = (int)t;
-        }
-        s_code[col][kl + 4 * i] = (uint8_t)code;
-    }
+    for (int i = 0; i < 16; i++) s_code[col][kl + 4 * i] = (uint8_t)quantize_code<QMAX>(w[i], sf);
     __syncthreads();
     const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;     // 16 codes of channel n0 + r
-    const int64_t nn = n0 + r;
-    if (nn < N) {
-        const int64_t kbase = k0 + piece * 16;
-        if (PACK4) {
-            uint8_t* dst = Wq + nn * (K / 2) + kbase / 2;
+    const int64_t nn = n0 + r, kbase = k0 + piece * 16;
+    if (nn >= N) return;
+    const uint64_t lo = *reinterpret_cast<const uint64_t*>(&s_code[r][piece * 16]);
+    const uint64_t hi = *reinterpret_cast<const uint64_t*>(&s_code[r][piece * 16 + 8]);
+    if (PACK4) {
+        // element k even in the low nibble of byte k / 2
+        auto pack8 = [](uint64_t v) {                            // eight code bytes -> four packed bytes
+            uint32_t out = 0;
 #pragma unroll
-            for (int e = 0; e < 8; e++)
-                if (kbase + 2 * e < K)
-                    dst[e] = (uint8_t)((s_code[r][piece * 16 + 2 * e] & 0xF) | ((s_code[r][piece * 16 + 2 * e + 1] & 0xF) << 4));
-        } else {
-            uint8_t* dst = Wq + nn * K + kbase;
-#pragma unroll
-            for (int e = 0; e < 16; e++)
-                if (kbase + e < K) dst[e] = s_code[r][piece * 16 + e];
-        }
+            for (int e = 0; e < 4; e++) {
+                const uint32_t b0 = (uint32_t)(v >> (16 * e)) & 0xFu, b1 = (uint32_t)(v >> (16 * e + 8)) & 0xFu;
+                out |= (b0 | (b1 << 4)) << (8 * e);
+            }
+            return out;
+        };
+        if (kbase < K)                                           // K is a multiple of 64: all 16 codes or none
+            *reinterpret_cast<uint64_t*>(Wq + nn * (K / 2) + kbase / 2) = (uint64_t)pack8(lo) | ((uint64_t)pack8(hi) << 32);
+    } else {
+        uint8_t* dst = Wq + nn * K + kbase;
+        if (kbase < K) *reinterpret_cast<uint64_t*>(dst) = lo;
+        if (kbase + 8 < K) *reinterpret_cast<uint64_t*>(dst + 8) = hi;
     }
 }
 
@@ -360,7 +400,7 @@ __global__ __launch_bounds__(256) void quantize_int4_kernel(const float* __restr
                                                             uint16_t* __restrict__ scales, int64_t K, int64_t N)
 {
     __shared__ float s_max[4][QT];
-    __shared__ uint8_t s_code[QT][QT + 4];
+    __shared__ __attribute__((aligned(8))) uint8_t s_code[QT][QT + 8];
     const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * QT, k0 = (int64_t)blockIdx.y * QT;
     const int64_t n = n0 + col;
@@ -377,21 +417,26 @@ __global__ __launch_bounds__(256) void quantize_int4_kernel(const float* __restr
     store_tile_codes<7, true>(w, (float)hs, Wq, K, N, k0, n0, s_code);
 }
 
-// int8 per channel, step 1: pmax[tile row][n] = max |W| over the tile's 64 k
-__global__ __launch_bounds__(256) void absmax_tiles_kernel(const float* __restrict__ W, float* __restrict__ pmax, int64_t K, int64_t N)
+// int8 per channel, step 1: pmax[slice][n] = max |W| over the slice's 64 rows k.  Nothing is transposed
+// here, so the pass reads W the way it lies: a thread owns four neighbouring columns, a workgroup
+// 4 KB of every row of its slice (the tiled pattern of the code kernels reads cold data at about half
+// the rate of this one).  grid (ceil(N / 1024), ceil(K / 64)); N is a multiple of 8.
+__global__ __launch_bounds__(256) void absmax_rows_kernel(const float* __restrict__ W, float* __restrict__ pmax, int64_t K, int64_t N)
 {
-    __shared__ float s_max[4][QT];
-    const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
-    const int64_t n = (int64_t)blockIdx.x * QT + col, k0 = (int64_t)blockIdx.y * QT;
-    float w[16];
-    load_tile_column(W, K, N, k0, n, kl, w);
-    float a = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; i++) a = fmaxf(a, fabsf(w[i]));
-    s_max[kl][col] = a;
-    __syncthreads();
-    if (kl == 0 && n < N)
-        pmax[(int64_t)blockIdx.y * N + n] = fmaxf(fmaxf(s_max[0][col], s_max[1][col]), fmaxf(s_max[2][col], s_max[3][col]));
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const int64_t n = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4, k0 = (int64_t)blockIdx.y * QT;
+    if (n >= N) return;
+    f32x4_t a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 16
+    for (int t = 0; t < QT; t++) {
+        const int64_t k = k0 + t;
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(W + (k < K ? k : K - 1) * N + n);   // (a repeated row changes no maximum)
+        a.x = fmaxf(a.x, fabsf(v.x));
+        a.y = fmaxf(a.y, fabsf(v.y));
+        a.z = fmaxf(a.z, fabsf(v.z));
+        a.w = fmaxf(a.w, fabsf(v.w));
+    }
+    *reinterpret_cast<f32x4_t*>(pmax + (int64_t)blockIdx.y * N + n) = a;
 }
 
 // step 2: scale[n] = fp16(max over tile rows / 127)
@@ -400,7 +445,13 @@ __global__ __launch_bounds__(256) void column_scale_kernel(const float* __restri
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     float a = 0.f;
-    for (int64_t r = 0; r < rows; r++) a = fmaxf(a, pmax[r * N + n]);
+    for (int64_t r0 = 0; r0 < rows; r0 += 8) {           // eight loads in flight (a row past the end repeats row r0)
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; q++) v[q] = pmax[(r0 + q < rows ? r0 + q : r0) * N + n];
+#pragma unroll
+        for (int q = 0; q < 8; q++) a = fmaxf(a, v[q]);
+    }
     const _Float16 hs = (_Float16)(a / 127.f);
     scales[n] = __builtin_bit_cast(uint16_t, hs);
 }
@@ -409,7 +460,7 @@ __global__ __launch_bounds__(256) void column_scale_kernel(const float* __restri
 __global__ __launch_bounds__(256) void quantize_int8_kernel(const float* __restrict__ W, const uint16_t* __restrict__ scales,
                                                             uint8_t* __restrict__ Wq, int64_t K, int64_t N)
 {
-    __shared__ uint8_t s_code[QT][QT + 4];
+    __shared__ __attribute__((aligned(8))) uint8_t s_code[QT][QT + 8];
     const int col = threadIdx.x & 63, kl = threadIdx.x >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * QT, k0 = (int64_t)blockIdx.y * QT;
     const int64_t n = n0 + col;
@@ -425,13 +476,19 @@ hipError_t launch_quantize(const float* W, int scheme, int64_t block, void* Wq, 
 {
     (void)block;
     const dim3 grid((unsigned)((N + QT - 1) / QT), (unsigned)((K + QT - 1) / QT));
+    // algorithmic bytes: W once in, codes and scales out (the int8 path reads W a second time for the
+    // codes, after the column maxima; that second pass is not credited)
     if (scheme == 4) {
+        const int slot = prof_begin("qweight_quantize<int4>", 0.0, 4.0 * K * N + 0.5 * K * N + 2.0 * N * (K / 64), s);
         hipLaunchKernelGGL(quantize_int4_kernel, grid, dim3(256), 0, s, W, (uint8_t*)Wq, (uint16_t*)scales, K, N);
+        prof_end(slot, s);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(absmax_tiles_kernel, grid, dim3(256), 0, s, W, scratch, K, N);
+    const int slot = prof_begin("qweight_quantize<int8>", 0.0, 4.0 * K * N + 1.0 * K * N + 2.0 * N, s);
+    hipLaunchKernelGGL(absmax_rows_kernel, dim3((unsigned)((N + 1023) / 1024), grid.y), dim3(256), 0, s, W, scratch, K, N);
     hipLaunchKernelGGL(column_scale_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, scratch, (int64_t)grid.y, N, (uint16_t*)scales);
     hipLaunchKernelGGL(quantize_int8_kernel, grid, dim3(256), 0, s, W, (const uint16_t*)scales, (uint8_t*)Wq, K, N);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 

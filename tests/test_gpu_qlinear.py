@@ -47,11 +47,15 @@ def test_unpack_and_dequant_bit_exact(scheme):
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
-def test_quantize_bit_exact(scheme):
+@pytest.mark.parametrize("K,N", [(512, 200), (192, 72), (1088, 520)])
+def test_quantize_bit_exact(scheme, K, N):
+    """Several workgroups in both directions, ragged channel count, a last workgroup with fewer than
+    four 64-blocks; for int8 also a K that ends inside a block and inside a 16-byte piece of a code row."""
     import torch
     fhpc = _fhpc()
     from paper_2402_13533_amd import synth
-    K, N = 512, 200
+    if scheme == 8 and K == 192:
+        K = 136
     W = synth.normal(77 + scheme, (K, N), 0.02)
     W[:, 3] = 0.0                                    # zero vector -> zero scale and codes
     W[5, 7] = 0.3                                    # outlier
@@ -66,6 +70,16 @@ def test_quantize_bit_exact(scheme):
     Wq, sc = fhpc.qweight_quantize(torch.from_numpy(W).cuda(), scheme)
     assert np.array_equal(sc.cpu().numpy().view(np.uint16), sc_ref)
     assert np.array_equal(Wq.cpu().numpy().view(Wq_ref.dtype), Wq_ref)
+    # into caller buffers with sentinel bytes on both sides: nothing is written outside them
+    pad = 256
+    bw = torch.full((Wq.numel() + 2 * pad,), 0x5A, dtype=torch.uint8, device="cuda")
+    bs = torch.full((sc.numel() + 2 * pad,), 1.0, dtype=torch.float16, device="cuda")
+    Wq2 = bw[pad:pad + Wq.numel()].view(Wq.dtype).view(Wq.shape)
+    sc2 = bs[pad:pad + sc.numel()].view(sc.shape)
+    fhpc.qweight_quantize(torch.from_numpy(W).cuda(), scheme, Wq_out=Wq2, scales_out=sc2)
+    assert torch.equal(Wq2, Wq) and torch.equal(sc2, sc)
+    assert bool((bw[:pad] == 0x5A).all()) and bool((bw[pad + Wq.numel():] == 0x5A).all())
+    assert bool((bs[:pad] == 1.0).all()) and bool((bs[pad + sc.numel():] == 1.0).all())
 
 
 def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
