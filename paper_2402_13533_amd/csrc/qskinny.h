@@ -40,8 +40,9 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
 
 // ---- input gradient dX for a handful of tokens (csrc/qskinny_dx.hip)
 struct QskinnyDxPlan {
-    int strips;            // column strips of dX: K / 256 (int4) or K / 128 (int8)
-    int token_blocks;      // blocks of 16 tokens
+    int tt;                // blocks of 16 tokens that share a pass over the codes: 1 or 2
+    int strips;            // column strips of dX: K / 256 (int4 with tt = 1) or K / 128
+    int token_blocks;      // workgroups along the tokens: ceil(M / (16 tt))
     int steps_total;       // 32-row steps of the weight: ceil(N / 32)
     int steps_per_slice;   // steps of one slice of the reduction
     int slices;            // slices; each writes its own fp32 slab of M x K

@@ -20,8 +20,9 @@
 // Work split: a workgroup of eight waves owns a column strip of 16 * CODES inputs k and a slice
 // of the rows n; its waves take the 32-row steps of the slice in turn and add their accumulators
 // through LDS; slices write fp32 slabs [slice][M][K]; dx_finish_kernel adds the slabs and the
-// rank-r branch and rounds to bf16.  More than 16 tokens are further workgroups that stream the
-// same weight again (it is then served by the caches).  dH = dY B^T (M x r), which the rank-r branch
+// rank-r branch and rounds to bf16.  Two blocks of 16 tokens can share one pass over the codes
+// (template parameter TT: every operand built from the codes feeds TT matrix instructions); more
+// than 32 tokens are further workgroups that stream the same weight again (from the caches).  dH = dY B^T (M x r), which the rank-r branch
 // and dA need, is formed on the way when r <= 16: the workgroups of the first strip also multiply
 // their dY pieces with the matching pieces of B (one more 16-byte load and one more matrix
 // instruction per step) and write dH's sums over their slices; the finish kernel adds them (and
@@ -74,7 +75,12 @@ __device__ __forceinline__ int red_col(int kl)
     return (run << 6) | ((kl & 63) ^ ((run & 3) << 4));
 }
 
-template <int SCHEME>
+// TT: blocks of 16 tokens that share one pass over the codes (each operand built from the codes feeds TT
+// matrix instructions), 1 or 2.  A lane takes 16 int4 codes per row with one token block, 8 codes per row
+// otherwise (4 * TT accumulator registers per code position have to fit).
+constexpr int dx_codes(int scheme, int tt) { return (scheme == 4 && tt == 1) ? 16 : 8; }
+
+template <int SCHEME, int TT>
 __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__ dY, const void* __restrict__ Wq,
                                                         const void* __restrict__ scales, float* __restrict__ part,
                                                         int M, int K, int N, int steps_per_slice, int steps_total,
@@ -82,7 +88,9 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
                                                         const void* __restrict__ Bf, float* __restrict__ dhpart, int rp)
 {
     constexpr bool I4 = (SCHEME == 4);
-    constexpr int CODES = I4 ? 16 : 8;               // codes in a lane's eight bytes
+    constexpr int CODES = dx_codes(SCHEME, TT);      // codes of a lane per row
+    constexpr int WORDS = (I4 ? CODES / 2 : CODES) / 4;          // 32-bit words they take
+    constexpr int CPW = I4 ? 8 : 4;                  // codes per word
     constexpr int KC = 16 * CODES;                   // inputs k per workgroup
     constexpr int RS = KC + 1;                       // padded row of the reduction buffer
     __shared__ float red[WAVES * TOK * RS];
@@ -93,8 +101,8 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
     // Workgroup -> work item.  Consecutive workgroup numbers go to the eight XCDs in turn, each with
     // its own L2, so item w = (number % 8) * (items / 8) + number / 8 gives every XCD a contiguous
     // run of the list (token block fastest, then strip, then slice): the token blocks of one strip read
-    // the same codes, and neighbouring strips of one slice share the lines of int4 scales (64 blocks,
-    // i.e. 16 strips, per 128-byte line) and the dY rows.
+    // the same codes, and neighbouring strips of one slice share the lines of int4 scales (64 blocks
+    // per 128-byte line) and the dY rows.
     const int per_xcd = (int)gridDim.x >> 3;
     const int w = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (w >= strips * slices * token_blocks) return;             // the grid is rounded up to a multiple of 8
@@ -109,27 +117,33 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
     const __amdgpu_buffer_rsrc_t rd = rsrc(dY, (int64_t)M * N * 2);
     const uint32_t wcol = (uint32_t)(I4 ? k0 / 2 : k0);          // byte of the lane's codes within a row
     const uint32_t scol = I4 ? (uint32_t)(k0 / 64) * 2u : 0u;    // byte of the lane's block scale within a row of scales
-    const int m = tb * TOK + i;                                  // this lane's token (dY operand and accumulator column)
-    const uint32_t dyrow = (m < M) ? (uint32_t)((int64_t)m * N * 2) : OOB;
+    const int m0 = tb * (TOK * TT);                              // first token of this workgroup
+    uint32_t dyrow[TT];                                          // this lane's token of every block (dY operand, accumulator column)
+#pragma unroll
+    for (int t = 0; t < TT; t++) dyrow[t] = (m0 + TOK * t + i < M) ? (uint32_t)((int64_t)(m0 + TOK * t + i) * N * 2) : OOB;
 
     // first strip: dH[m][j] = sum_n dY[m][n] B[j][n] over this slice beside the main sums (lane i is row j of B)
     const bool with_dh = (strip == 0) && (dhpart != nullptr);
     const __amdgpu_buffer_rsrc_t rb = rsrc(Bf, with_dh ? (int64_t)rp * N * 2 : 0);
     const uint32_t brow = (with_dh && i < rp) ? (uint32_t)((int64_t)i * N * 2) : OOB;
-    f32x4 acc_dh = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc_dh[TT];
     u32x4 bq[2];
 
-    f32x4 acc[CODES];
+    f32x4 acc[TT][CODES];
 #pragma unroll
-    for (int c = 0; c < CODES; c++) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TT; t++) {
+        acc_dh[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < CODES; c++) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     // What a lane reads for one step: rows n = 32 step + 8 g + s, s < 8.  N is a multiple of 8, so the
     // eight rows are inside the weight together or not at all; what lies outside reads as zero
-    // (an offset beyond the buffer), and so does the dY chunk, which makes those rows contribute 0.
-    u32x2 wq[2][8];
+    // (an offset beyond the buffer), and so do the dY pieces, which makes those rows contribute 0.
+    uint32_t wq[2][8][WORDS];
     uint32_t sc4[2][8];                              // int4: one fp16 scale per row (this lane's block)
     u32x4 sc8[2];                                    // int8: the eight rows' fp16 scales
-    u32x4 dyq[2];                                    // dY[m][n .. n + 7] bf16
+    u32x4 dyq[2][TT];                                // dY[m][n .. n + 7] bf16
     auto load = [&](auto BUF, int step) __attribute__((always_inline)) {
         constexpr int b = decltype(BUF)::value;
         const int n0 = step * STEP_ROWS + 8 * g;
@@ -138,7 +152,12 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             const uint32_t off = ((uint32_t)(n0 + s) * (uint32_t)row_bytes + wcol) | guard;
-            wq[b][s] = __builtin_amdgcn_raw_buffer_load_b64(rw, off, 0, 0);
+            if constexpr (WORDS == 2) {
+                const auto v = __builtin_amdgcn_raw_buffer_load_b64(rw, off, 0, 0);
+                wq[b][s][0] = v[0]; wq[b][s][1] = v[1];
+            } else {
+                wq[b][s][0] = __builtin_amdgcn_raw_buffer_load_b32(rw, off, 0, 0);
+            }
         }
         if constexpr (I4) {
 #pragma unroll
@@ -149,7 +168,8 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
         } else {
             sc8[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((uint32_t)n0 * 2u) | guard, 0, 0);
         }
-        dyq[b] = __builtin_amdgcn_raw_buffer_load_b128(rd, (dyrow + (uint32_t)n0 * 2u) | guard, 0, 0);
+#pragma unroll
+        for (int t = 0; t < TT; t++) dyq[b][t] = __builtin_amdgcn_raw_buffer_load_b128(rd, (dyrow[t] + (uint32_t)n0 * 2u) | guard, 0, 0);
         if (with_dh) bq[b] = __builtin_amdgcn_raw_buffer_load_b128(rb, (brow + (uint32_t)n0 * 2u) | guard, 0, 0);
     };
     auto compute = [&](auto BUF) __attribute__((always_inline)) {
@@ -166,11 +186,17 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
             }
             off[s] = (I4 ? -8.f : -128.f) * sc[s];
         }
-        const bf16x8 dy = __builtin_bit_cast(bf16x8, dyq[b]);      // dY[m][n0 + 8 g + 0 .. 7]
-        if (with_dh) acc_dh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[b]), dy, acc_dh, 0, 0, 0);
-        // word h of the eight rows at a time (keeps the unpacked codes of one word live, not of both)
+        bf16x8 dy[TT];                                             // dY[m][n0 + 8 g + 0 .. 7] of every token block
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
+        for (int t = 0; t < TT; t++) dy[t] = __builtin_bit_cast(bf16x8, dyq[b][t]);
+        if (with_dh) {
+#pragma unroll
+            for (int t = 0; t < TT; t++)
+                acc_dh[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[b]), dy[t], acc_dh[t], 0, 0, 0);
+        }
+        // one word of the eight rows at a time (keeps the unpacked codes of one word live, not of all)
+#pragma unroll
+        for (int h = 0; h < WORDS; h++) {
             // unsigned codes as bytes: int4 -> lo (codes 0 2 4 6 of the word) and hi (codes 1 3 5 7)
             uint32_t ub[8][I4 ? 2 : 1];
 #pragma unroll
@@ -187,9 +213,9 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
                 }
             }
 #pragma unroll
-            for (int cc = 0; cc < CODES / 2; cc++) {
+            for (int cc = 0; cc < CPW; cc++) {
                 // code c of the lane's eight rows -> one operand: element s = bf16((u - offset) * scale of row s)
-                const int c = h * (CODES / 2) + cc;
+                const int c = h * CPW + cc;
                 const int j = I4 ? cc >> 1 : cc;                       // byte within the word
                 const int par = I4 ? cc & 1 : 0;                       // int4: even / odd code of the byte
                 float f[8];
@@ -200,7 +226,9 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
                 wv.y = pack_bf16(f[2], f[3]);
                 wv.z = pack_bf16(f[4], f[5]);
                 wv.w = pack_bf16(f[6], f[7]);
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), dy, acc[c], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TT; t++)
+                    acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), dy[t], acc[t][c], 0, 0, 0);
             }
         }
     };
@@ -221,35 +249,42 @@ __global__ __launch_bounds__(NT) void qskinny_dx_kernel(const void* __restrict__
         step += WAVES;
     }
 
-    // accumulator view: lane holds token i (column) and the operand rows 4 g + v, i.e. the strip-local
-    // inputs CODES * (4 g + v) + c
+    // accumulator view: lane holds token i (column) of each block and the operand rows 4 g + v, i.e. the
+    // strip-local inputs CODES * (4 g + v) + c.  One token block at a time through the reduction buffer.
 #pragma unroll
-    for (int c = 0; c < CODES; c++)
+    for (int t = 0; t < TT; t++) {
+        if (t > 0) __syncthreads();
 #pragma unroll
-        for (int v = 0; v < 4; v++) red[(wave * TOK + i) * RS + red_col(CODES * (4 * g + v) + c)] = acc[c][v];
-    __syncthreads();
-    for (int o = tid; o < TOK * KC; o += NT) {
-        const int mm = o / KC, kl = o - mm * KC;
-        float t = 0.f;
+        for (int c = 0; c < CODES; c++)
 #pragma unroll
-        for (int w = 0; w < WAVES; w++) t += red[(w * TOK + mm) * RS + red_col(kl)];
-        const int mg = tb * TOK + mm;
-        if (mg < M) part[((int64_t)slice * M + mg) * K + strip * KC + kl] = t;
+            for (int v = 0; v < 4; v++) red[(wave * TOK + i) * RS + red_col(CODES * (4 * g + v) + c)] = acc[t][c][v];
+        __syncthreads();
+        for (int o = tid; o < TOK * KC; o += NT) {
+            const int mm = o / KC, kl = o - mm * KC;
+            float sum = 0.f;
+#pragma unroll
+            for (int w8 = 0; w8 < WAVES; w8++) sum += red[(w8 * TOK + mm) * RS + red_col(kl)];
+            const int mg = m0 + TOK * t + mm;
+            if (mg < M) part[((int64_t)slice * M + mg) * K + strip * KC + kl] = sum;
+        }
     }
     if (with_dh) {
         // dH of this slice: lane holds token i and the rows j = 4 g + v; added over the waves like the main sums
         constexpr int DS = TOK + 1;
-        __syncthreads();
 #pragma unroll
-        for (int v = 0; v < 4; v++) red[(wave * TOK + i) * DS + 4 * g + v] = acc_dh[v];
-        __syncthreads();
-        if (tid < TOK * TOK) {
-            const int mm = tid >> 4, j = tid & 15;
-            float t = 0.f;
+        for (int t = 0; t < TT; t++) {
+            __syncthreads();
 #pragma unroll
-            for (int w8 = 0; w8 < WAVES; w8++) t += red[(w8 * TOK + mm) * DS + j];
-            const int mg = tb * TOK + mm;
-            if (mg < M && j < rp) dhpart[((int64_t)slice * M + mg) * rp + j] = t;
+            for (int v = 0; v < 4; v++) red[(wave * TOK + i) * DS + 4 * g + v] = acc_dh[t][v];
+            __syncthreads();
+            if (tid < TOK * TOK) {
+                const int mm = tid >> 4, j = tid & 15;
+                float sum = 0.f;
+#pragma unroll
+                for (int w8 = 0; w8 < WAVES; w8++) sum += red[(w8 * TOK + mm) * DS + j];
+                const int mg = m0 + TOK * t + mm;
+                if (mg < M && j < rp) dhpart[((int64_t)slice * M + mg) * rp + j] = sum;
+            }
         }
     }
 }
@@ -443,11 +478,12 @@ QskinnyDxPlan qskinny_dx_plan(int64_t M, int64_t K, int64_t N, int scheme, int n
 {
     using namespace skinny_dx;
     QskinnyDxPlan p;
-    const int64_t kc = (scheme == 4) ? 256 : 128;
-    // one workgroup per compute unit (registers: two waves per SIMD; int4 also by its 129 KB reduction buffer)
+    p.tt = (M <= TOK) ? 1 : 2;            // (four blocks per pass do not fit the registers: 600 bytes of spills per lane)
+    const int64_t kc = 16 * dx_codes(scheme, p.tt);
+    // one workgroup per compute unit (registers: two waves per SIMD; the reduction buffer is 65 or 129 KB)
     const int64_t per_cu = 1;
     p.strips = (int)(K / kc);
-    p.token_blocks = (int)((M + TOK - 1) / TOK);
+    p.token_blocks = (int)((M + TOK * p.tt - 1) / (TOK * p.tt));
     p.steps_total = (int)((N + STEP_ROWS - 1) / STEP_ROWS);
     // one round of resident workgroups; a slice is at least one step for each of the eight waves
     int64_t s = per_cu * (int64_t)num_cu / ((int64_t)p.strips * p.token_blocks);
@@ -473,12 +509,15 @@ hipError_t launch_qskinny_dx(const void* dY, const void* Wq, const void* scales,
     const double wbytes = (scheme == 4) ? (double)N * K / 2 + (double)N * (K / 64) * 2 : (double)N * K + (double)N * 2;
     const int slot = prof_begin(scheme == 4 ? "qskinny_dx<int4>" : "qskinny_dx<int8>", 2.0 * M * K * (double)N,
                                 wbytes + 2.0 * M * N + 4.0 * p.slices * M * K, st);
-    if (scheme == 4)
-        hipLaunchKernelGGL((qskinny_dx_kernel<4>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
-                           p.steps_per_slice, p.steps_total, p.strips, p.slices, p.token_blocks, B, dhpart, (int)rp);
-    else
-        hipLaunchKernelGGL((qskinny_dx_kernel<8>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N,
-                           p.steps_per_slice, p.steps_total, p.strips, p.slices, p.token_blocks, B, dhpart, (int)rp);
+#define FHPC_DX(SCHEME, TT)                                                                                                  \
+    hipLaunchKernelGGL((qskinny_dx_kernel<SCHEME, TT>), grid, dim3(NT), 0, st, dY, Wq, scales, part, (int)M, (int)K, (int)N, \
+                       p.steps_per_slice, p.steps_total, p.strips, p.slices, p.token_blocks, B, dhpart, (int)rp)
+    if (scheme == 4) {
+        if (p.tt == 1) FHPC_DX(4, 1); else FHPC_DX(4, 2);
+    } else {
+        if (p.tt == 1) FHPC_DX(8, 1); else FHPC_DX(8, 2);
+    }
+#undef FHPC_DX
     prof_end(slot, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
