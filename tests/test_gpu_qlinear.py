@@ -132,12 +132,12 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
 
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("M,K,r,N", [
-    (1024, 320, 8, 264),      # the first token count on the merged-weight route
-    (1100, 384, 5, 520),      # ragged in every dimension, rank padded internally
-    (1300, 576, 40, 136),
+    (2048, 320, 8, 264),      # the first token count on the merged-weight route
+    (2100, 384, 5, 520),      # ragged in every dimension, rank padded internally
+    (2300, 576, 40, 136),
 ])
 def test_qlinear_many_tokens(scheme, M, K, r, N):
-    """From 1024 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
+    """From 2048 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
     products with it (forward and backward, saved and recomputed H, as above)."""
     if scheme == 4:
         K = (K + 63) // 64 * 64
@@ -152,7 +152,7 @@ def test_qlinear_many_tokens(scheme, M, K, r, N):
     (260, 512, 64, 328),
 ])
 def test_qlinear_shapes(scheme, M, K, r, N):
-    """Below 1024 tokens: the weight is dequantised in the GEMM's operand load path and the rank-r
+    """Below 2048 tokens: the weight is dequantised in the GEMM's operand load path and the rank-r
     branch rides in the same accumulators."""
     if scheme == 4:
         K = (K + 63) // 64 * 64
@@ -382,11 +382,11 @@ def test_few_token_blend_backward():
 
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("alpha", [1.0, 0.7, 0.25, 0.0])
-@pytest.mark.parametrize("M", [300, 1040])
+@pytest.mark.parametrize("M", [300, 2064])
 def test_blend_layer(scheme, alpha, M):
     """Y = alpha X deq(W) + (1 - alpha) (X A) B with W frozen, forward and backward; alpha = 1 is
     the frozen layer alone (dA = dB = 0), alpha = 0 the factorised layer alone.  Both routes (below
-    and from 1024 tokens)."""
+    and from 2048 tokens)."""
     fhpc = _fhpc()
     K, r, N = 320, 24, 264
     W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 80)
@@ -425,7 +425,7 @@ def test_blend_layer_few_tokens_and_alpha_range():
             fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), bad)
 
 
-@pytest.mark.parametrize("M", [300, 5, 1056])
+@pytest.mark.parametrize("M", [300, 5, 2080])
 def test_blend_layer_dense_weight(M):
     """The blend layer with the pretrained weight kept in bf16 (no quantisation): W[K,N] row-major in
     place of the packed codes.  M = 5 checks that the few-token weight-streaming path is not taken
@@ -477,12 +477,12 @@ def test_few_token_forward_in_a_hip_graph():
 
 
 def test_many_token_step_in_a_hip_graph():
-    """Forward and backward on the merged-weight route (1024 tokens) captured in one HIP graph: the calls
+    """Forward and backward on the merged-weight route (2048 tokens) captured in one HIP graph: the calls
     enqueue kernels only (the merge, the products, the slab sums), so three replays, with eager work on the
     same workspace in between, must each reproduce the eager result bit for bit."""
     import torch
     fhpc = _fhpc()
-    M, K, r, N = 1024, 512, 16, 264
+    M, K, r, N = 2048, 512, 16, 264
     W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 98)
     Wq, sc = _quantize_host(W, 8)
     Wq_d, sc_d = _to_dev(Wq, sc)
@@ -516,17 +516,17 @@ def test_many_token_step_in_a_hip_graph():
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
-@pytest.mark.parametrize("M", [3, 200, 1030])
+@pytest.mark.parametrize("M", [3, 200, 2054])
 def test_qlinear_rank_one(scheme, M):
     """The smallest rank on each route (weight streaming, load-path dequantisation, merged weight)."""
     _run_case("rank 1 q%d M=%d" % (scheme, M), scheme, M, 512, 1, 136, 2.0, 8, tensor_base=120)
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
-@pytest.mark.parametrize("M", [40, 300, 1100])
+@pytest.mark.parametrize("M", [40, 300, 2100])
 def test_premerged_weight(scheme, M):
     """The caller merges once (lowrank_merge, bf16) and passes the result to forward and backward with
-    qscheme FHPC_W_MERGED: outputs against the oracle's layer; from 1024 tokens on they are the very bits
+    qscheme FHPC_W_MERGED: outputs against the oracle's layer; from 2048 tokens on they are the very bits
     of the calls that merge by themselves (same merge kernel, same products)."""
     import torch
     fhpc = _fhpc()
@@ -544,7 +544,7 @@ def test_premerged_weight(scheme, M):
     for name, g, rf in zip(("Y", "H", "dX", "dA", "dB"), (Y, H, dX, dA, dB), (Yr, Hr) + ref):
         e = oracle.rel_fro(from_device(g), rf)
         assert e <= TOL_BF16, (name, e)
-    if M >= 1024:
+    if M >= 2048:
         Y2, H2 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)
         dX2, dA2, dB2 = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H2)
         for a, b in zip((Y, H, dX, dA, dB), (Y2, H2, dX2, dA2, dB2)):
