@@ -476,6 +476,41 @@ def test_few_token_forward_in_a_hip_graph():
         assert not torch.equal(other, eager)
 
 
+@pytest.mark.parametrize("scheme,M,r", [(4, 12, 16), (8, 40, 24)])
+def test_few_token_step_in_a_hip_graph(scheme, M, r):
+    """Forward and backward of the few-token routes captured in one HIP graph (streaming kernels, their
+    finish kernels, the gradient sums: kernels only, slabs in the workspace, nothing cleared by a
+    memset): three replays, with eager work on the same workspace and synchronisations in between,
+    must each reproduce the eager results bit for bit."""
+    import torch
+    fhpc = _fhpc()
+    K, N = 1536, 328
+    W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 98)
+    Wq, sc = _quantize_host(W, scheme)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y0, H0 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, save_H=True)
+    eager = [t.clone() for t in (Y0,) + tuple(fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, H_saved=H0))]
+    torch.cuda.synchronize()
+    bf = torch.bfloat16
+    Y = torch.empty((M, N), dtype=bf, device="cuda"); H = torch.empty((M, r), dtype=bf, device="cuda")
+    dX = torch.empty((M, K), dtype=bf, device="cuda")
+    dA = torch.empty((K, r), dtype=torch.float32, device="cuda"); dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, Y=Y, H_out=H)
+        fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd, H_saved=H, dX=dX, dA=dA, dB=dB)
+    for rep in range(3):
+        for t in (Y, H, dX, dA, dB):
+            t.zero_()
+        fhpc.qlinear_lowrank_bwd(Xd * 0.5, Wq_d, sc_d, scheme, Ad, Bd, 2.0, dYd)       # eager work on the same workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((Y, dX, dA, dB), eager):
+            assert torch.equal(got, want), rep
+
+
 def test_many_token_step_in_a_hip_graph():
     """Forward and backward on the merged-weight route (2048 tokens) captured in one HIP graph: the calls
     enqueue kernels only (the merge, the products, the slab sums), so three replays, with eager work on the
