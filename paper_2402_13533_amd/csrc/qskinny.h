@@ -9,7 +9,7 @@ constexpr int QSKINNY_MAX_JOBS = 4;
 
 struct QskinnyPlan {
     int splits;            // slices of the reduction (each writes its own fp32 slab of M x (64 * row_blocks))
-    int k_chunk;           // reduction depth per slice, a multiple of 512
+    int k_chunk;           // reduction depth per slice, a multiple of the step depth (512, or 256)
     int kchunks;           // partial sums of H = X A, per weight
     int row_blocks;        // 64-channel blocks of all weights together
     int64_t part_bytes;    // splits * M * 64 * row_blocks * 4
@@ -29,7 +29,7 @@ struct QskinnyJob {
     float base_scale, scaling;
 };
 
-// M <= 64 tokens, r <= 64, K a multiple of 512, scheme 4 (block 64) or 8.
+// M <= 64 tokens, r <= 64, K a multiple of 256, scheme 4 (block 64) or 8.
 bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 // `count` weights (at most QSKINNY_MAX_JOBS) with output widths N[0..count) that share X, K and r
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int count, int num_cu);

@@ -40,11 +40,12 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int NT = 256;
 constexpr int ROWS_WG = 64;            // output channels per workgroup
 constexpr int TOK = 16;                // token rows of the MFMA tile
-constexpr int STEP = 512;              // unit of the reduction split (and the pipeline step up to 32 tokens)
-// Reduction depth per pipeline step.  The double-buffered token tile of a step takes
-// tokens * depth * 4 bytes of LDS; with 64 tokens the shallower step lets two workgroups share a
-// compute unit, which hides more of the weight stream's latency than the deeper step does.
-constexpr int step_depth(int tt) { return tt == 4 ? 256 : 512; }
+// Reduction depth per pipeline step: 512, or 256 (template parameter SD).  The double-buffered token
+// tile of a step takes tokens * depth * 4 bytes of LDS; with 64 tokens the shallower step lets two
+// workgroups share a compute unit, which hides more of the weight stream's latency than the deeper
+// step does.  The shallower step also serves reductions K that are a multiple of 256 but not of 512
+// (a step never straddles the end of K, so the loop needs no guard along k).
+constexpr int step_depth(int tt, int64_t K) { return (tt == 4 || (K % 512) != 0) ? 256 : 512; }
 constexpr int HCHUNK = 128;            // reduction depth per workgroup of the H = X A kernel
 constexpr uint32_t OOB = 0x80000000u;
 
@@ -204,20 +205,20 @@ __device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const ui
     }
 }
 
-template <int SCHEME, int TT>
+template <int SCHEME, int TT, int SD>
 __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, SkinnyJobs jb, float* __restrict__ part,
                                                          int M, int K, int k_chunk, float* __restrict__ hpart, int r,
                                                          int kchunks, int main_grid)
 {
     constexpr bool I4 = (SCHEME == 4);
-    constexpr int SD = step_depth(TT);               // reduction depth per step
     constexpr int WLOADS = I4 ? SD / 128 : SD / 64;  // 16-byte weight loads per lane per step
     constexpr int TOKS = TOK * TT;                   // token rows this instantiation covers
     constexpr int XS_BYTES = TOKS * SD * 2;
     constexpr int XCH = SD / 8;                      // 16-byte pieces per token row per step
     constexpr int XL = TOKS * XCH / NT;              // ... per thread per step
-    static_assert(h_lds_bytes(TOKS) <= 2 * XS_BYTES, "the H = X A workgroups reuse the token tiles' LDS");
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XS_BYTES];
+    // (the H = X A workgroups reuse the token tiles' LDS)
+    constexpr int LDS_BYTES = (2 * XS_BYTES > h_lds_bytes(TOKS)) ? 2 * XS_BYTES : h_lds_bytes(TOKS);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     unsigned char* const xs[2] = {smem, smem + XS_BYTES};
     if ((int)blockIdx.x >= main_grid) {
         // the H = X A chunks: kchunks workgroups per weight
@@ -579,7 +580,7 @@ bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
     // the kernels address each operand with 32-bit byte offsets below 2^31
     const int64_t lim = (int64_t)1 << 31;
     if (N < 1 || K < 1 || N * K >= lim || 2 * r * N >= lim) return false;
-    return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % skinny::STEP) == 0;
+    return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % 256) == 0;
 }
 
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int count, int num_cu)
@@ -587,7 +588,9 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
     QskinnyPlan p;
     int64_t row_blocks = 0;
     for (int j = 0; j < count; j++) row_blocks += (N[j] + skinny::ROWS_WG - 1) / skinny::ROWS_WG;
-    const int64_t ksteps = K / skinny::STEP;
+    const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
+    const int64_t sd = skinny::step_depth(tt, K);
+    const int64_t ksteps = K / sd;
     // One round of workgroups: as many as are resident at once (registers and the token tiles' LDS
     // allow three per compute unit with 16 tokens, two with more) and no more, so that
     // no second, partly filled round follows; at least one step each.
@@ -596,7 +599,7 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
     if (s > ksteps) s = ksteps;
     if (s < 1) s = 1;
     const int64_t per = (ksteps + s - 1) / s;
-    p.k_chunk = (int)(per * skinny::STEP);
+    p.k_chunk = (int)(per * sd);
     p.splits = (int)((ksteps + per - 1) / per);
     p.kchunks = (int)((K + skinny::HCHUNK - 1) / skinny::HCHUNK);
     p.row_blocks = (int)row_blocks;
@@ -630,14 +633,19 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
     const dim3 grid((unsigned)(main_grid + count * p.kchunks));     // streaming workgroups, then the H = X A chunks
     const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * nsum,
                                 wbytes + 2.0 * M * K + 4.0 * p.splits * M * nsum, st);
-#define FHPC_MAIN(SCHEME, TT)                                                                                       \
-    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT>), grid, dim3(NT), 0, st, X, jb, part, (int)M, (int)K,        \
+#define FHPC_MAIN(SCHEME, TT, SD)                                                                                   \
+    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT, SD>), grid, dim3(NT), 0, st, X, jb, part, (int)M, (int)K,    \
                        p.k_chunk, hpart, (int)r, p.kchunks, main_grid)
     const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
+    const bool deep = step_depth(tt, K) == 512;
     if (scheme == 4) {
-        if (tt == 1) FHPC_MAIN(4, 1); else if (tt == 2) FHPC_MAIN(4, 2); else FHPC_MAIN(4, 4);
+        if (tt == 1) { if (deep) FHPC_MAIN(4, 1, 512); else FHPC_MAIN(4, 1, 256); }
+        else if (tt == 2) { if (deep) FHPC_MAIN(4, 2, 512); else FHPC_MAIN(4, 2, 256); }
+        else FHPC_MAIN(4, 4, 256);
     } else {
-        if (tt == 1) FHPC_MAIN(8, 1); else if (tt == 2) FHPC_MAIN(8, 2); else FHPC_MAIN(8, 4);
+        if (tt == 1) { if (deep) FHPC_MAIN(8, 1, 512); else FHPC_MAIN(8, 1, 256); }
+        else if (tt == 2) { if (deep) FHPC_MAIN(8, 2, 512); else FHPC_MAIN(8, 2, 256); }
+        else FHPC_MAIN(8, 4, 256);
     }
 #undef FHPC_MAIN
     prof_end(slot, st);

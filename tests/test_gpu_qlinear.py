@@ -210,9 +210,12 @@ def test_config5_full_size():
     (32, 1024, 8, 264),        # two full token tiles
     (33, 2048, 24, 72),        # four token tiles, two of them empty but for one token
     (64, 4096, 16, 520),       # the most tokens the path takes
+    (5, 768, 16, 200),         # K a multiple of 256 only: the 256-deep step
+    (20, 1280, 8, 136),
+    (64, 2816, 16, 72),
 ])
 def test_few_token_forward(scheme, M, K, r, N):
-    """M <= 64 tokens and K a multiple of 512 take the weight-streaming forward (codes turned
+    """M <= 64 tokens and K a multiple of 256 take the weight-streaming forward (codes turned
     into exact small bf16 integers, offset and scale applied to the fp32 sums)."""
     fhpc = _fhpc()
     W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 60)
@@ -291,7 +294,7 @@ def test_few_token_forward_every_code(scheme):
     (5, 256, 8, 8200),         # one column strip, many slices of the reduction
 ])
 def test_few_token_step(scheme, M, K, r, N):
-    """M <= 64 tokens: forward through the weight-streaming kernel (K a multiple of 512), and the
+    """M <= 64 tokens: forward through the weight-streaming kernel (K a multiple of 256), and the
     input gradient through its counterpart (K a multiple of 256) that reduces over the rows of the stored weight (fp32
     matrix instructions on exactly converted codes); dA, dB, saved and recomputed H as everywhere."""
     _run_case("few q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=110)
