@@ -144,6 +144,18 @@ def test_qlinear_many_tokens(scheme, M, K, r, N):
     _run_case("many q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=40)
 
 
+@pytest.mark.parametrize("scheme,M,K,r,N", [
+    (8, 2048, 2304, 8, 4224),     # 8 x 33 tiles of 256 x 128: one tile column beyond a full round
+    (4, 2048, 2560, 16, 5120),    # 8 x 40 tiles: a quarter round beyond
+    (4, 2048, 5120, 16, 2560),    # the same remainder in the backward product (outputs along K = 5120)
+])
+def test_qlinear_many_tokens_remainder_round(scheme, M, K, r, N):
+    """Merged-weight route with outputs whose 256 x 128 tiles fill the chip once plus a fraction of a
+    round (sampled token rows against the oracle, every column)."""
+    _run_case("tail q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=130,
+              rows=sample_rows(M, 77, 96))
+
+
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("M,K,r,N", [
     (300, 320, 8, 264),
