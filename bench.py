@@ -60,7 +60,8 @@ def parse_args():
                          "and the backward call, instead of each call merging by itself")
     ap.add_argument("--shared-x", action="store_true",
                     help="c5 with --tokens and --forward-only: the q/k/v and the gate/up projections read one X each "
-                         "and go through the shared-X entry point (one call per group: qkv, o, gate+up, down)")
+                         "and go through the shared-X entry point (one call per group: qkv, o, gate+up, down); "
+                         "c2: q/k/v read one X through lowrank_linear_fwd/bwd_shared_x (fwd+bwd); c3: gate and up likewise")
     ap.add_argument("--shape", default="", help="c4/c5 only: K,N of a single frozen weight in place of the configuration's "
                                                 "(large weights show the streaming kernel's rate beyond the fixed launch cost)")
     ap.add_argument("--graph", action="store_true",
@@ -111,6 +112,41 @@ class LowrankCall:
         self.f.lowrank_linear_fwd(self.X, self.A, self.B, Y=self.Y, H_out=self.H)
         self.f.lowrank_linear_bwd(self.X, self.A, self.B, self.dY, H_saved=None if self.recompute else self.H,
                                   dX=self.dX, dA=self.dA, dB=self.dB)
+
+
+class SharedLowrankCall:
+    """g factorised linears fed by one X (q/k/v) through lowrank_linear_fwd/bwd_shared_x: X A_all is one
+    product and the input gradient one product over the g r columns of [dH_0 | ...]."""
+
+    def __init__(self, fhpc, M, K, r, N, g, gen):
+        import torch
+        bf = torch.bfloat16
+        self.f, self.lib = fhpc, fhpc.load_library()
+        self.M, self.K, self.r, self.N, self.g = M, K, r, N, g
+        self.X = randn((M, K), 1.0, bf, gen)
+        self.A_all = randn((K, g * r), K ** -0.5, bf, gen)
+        self.B = [randn((r, N), r ** -0.5, bf, gen) for _ in range(g)]
+        self.dY = [randn((M, N), 1.0, bf, gen) for _ in range(g)]
+        self.Y = [torch.empty((M, N), dtype=bf, device="cuda") for _ in range(g)]
+        self.H = torch.empty((M, g * r), dtype=bf, device="cuda")
+        self.dX = torch.empty((M, K), dtype=bf, device="cuda")
+        self.dA = torch.empty((K, g * r), dtype=torch.float32, device="cuda")
+        self.dB = [torch.empty((r, N), dtype=torch.float32, device="cuda") for _ in range(g)]
+        need = max(self.lib.fhpc_workspace_bytes_lowrank_shared_x(b, M, K, r, N, g) for b in (0, 1))
+        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+
+    def flops(self):
+        from paper_2402_13533_amd import shapes
+        return self.g * shapes.lowrank_flops(self.M, self.K, self.r, self.N)
+
+    def io_bytes(self):
+        g = self.g
+        return 2 * (2 * self.M * self.K + 2 * g * self.M * self.N) + 6 * g * self.r * (self.K + self.N)
+
+    def run(self):
+        self.f.lowrank_linear_fwd_shared_x(self.X, self.A_all, self.B, Ys=self.Y, H_all_out=self.H, workspace=self.ws)
+        self.f.lowrank_linear_bwd_shared_x(self.X, self.A_all, self.B, self.dY, H_all_saved=self.H, dX=self.dX,
+                                           dA_all=self.dA, dBs=self.dB, workspace=self.ws)
 
 
 class QlinearCall:
@@ -249,16 +285,20 @@ def stream_calls(fhpc, gen):
 class FfnCall:
     """Config 3: gate/up 4096 -> r -> 11008, SiLU gate, down 11008 -> r -> 4096, fwd + bwd."""
 
-    def __init__(self, fhpc, M, d, r, f, gen):
+    def __init__(self, fhpc, M, d, r, f, gen, shared_x=False):
         import torch
         bf = torch.bfloat16
         self.fh = fhpc
+        self.shared_x = shared_x
         self.M, self.d, self.r, self.f = M, d, r, f
         self.X = randn((M, d), 1.0, bf, gen)
         self.dY = randn((M, d), 1.0, bf, gen)
         self.W = [randn((d, r), d ** -0.5, bf, gen), randn((r, f), r ** -0.5, bf, gen),
                   randn((d, r), d ** -0.5, bf, gen), randn((r, f), r ** -0.5, bf, gen),
                   randn((f, r), f ** -0.5, bf, gen), randn((r, d), r ** -0.5, bf, gen)]
+        if shared_x:      # gate and up factors side by side: [Ag | Au]
+            Ag, Bg, Au, Bu, Ad, Bd = self.W
+            self.Ws = [torch.cat([Ag, Au], dim=1).contiguous(), Bg, Bu, Ad, Bd]
 
     def flops(self):
         from paper_2402_13533_amd import shapes
@@ -269,6 +309,10 @@ class FfnCall:
 
     def run(self):
         from paper_2402_13533_amd import ffn
+        if self.shared_x:
+            Y, saved = ffn.ffn_fwd_shared_x(self.X, *self.Ws)
+            ffn.ffn_bwd_shared_x(self.X, *self.Ws, self.dY, saved)
+            return
         Y, saved = ffn.ffn_fwd(self.X, *self.W)
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
@@ -287,8 +331,10 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         desc = "config 2: Llama-2-7B q/k/v/o projections factorised r=512, 16384 tokens, bf16, fwd+bwd"
         dtype = "bf16"
     elif name == "c3":
-        calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen)]
+        calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen, shared_x)]
         desc = "config 3: Llama-2-7B SiLU-gated FFN factorised r=1024, 16384 tokens, bf16, fwd+bwd"
+        if shared_x:
+            return calls, desc + ", gate and up through the shared-X call", "bf16"
         dtype = "bf16"
     elif name == "c4":
         M = tokens or 4096
@@ -318,9 +364,13 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         desc = "config 5: %s, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
             "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
+    if shared_x and name == "c2":
+        calls = [SharedLowrankCall(fhpc, 16384, 4096, 512, 4096, 3, gen), calls[3]]
+        desc += ", q/k/v read one X through the shared-X call (their input gradients arrive summed)"
+        return calls, desc, dtype
     if shared_x:
         if name != "c5" or not forward_only or shape:
-            raise SystemExit("--shared-x goes with --workload c5 --forward-only")
+            raise SystemExit("--shared-x goes with --workload c2 or c3, or with --workload c5 --forward-only")
         q, k, v, o, gate, up, down = calls
         calls = [SharedXCall(fhpc, [q, k, v]), o, SharedXCall(fhpc, [gate, up]), down]
         desc += ", q/k/v and gate/up through the shared-X call"

@@ -96,6 +96,33 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
                        int64_t M, int64_t K, int64_t r, int64_t N, int dtype,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* g factorised layers that read the same activations: the query, key and value projections of an
+ * attention block, or the gate and up projections of the FFN (Sec. 3.1 eqs. attention and FFN; each
+ * of them replaced by a factor pair, Sec. 4.1 "Method 1").  bf16 only.
+ *   Y_i[M,N] = (X[M,K] * A_i[K,r]) * B_i[r,N],   i = 0 .. g-1,   1 <= g <= FHPC_MAX_SHARED
+ * A_all is one bf16 matrix [K][g*r], row-major, with A_i in columns i*r .. (i+1)*r-1, so that X*A_all
+ * is a single product.  B and Y are HOST arrays of g device pointers (B_i [r][N], Y_i [M][N], bf16).
+ * H_all_out ([M][g*r] bf16, H_i = X*A_i in columns i*r ..), if not NULL, receives the intermediate for
+ * the backward pass.  r must be a multiple of 8 (FHPC_ERR_UNSUPPORTED otherwise); every other rule
+ * of lowrank_linear_fwd applies with g*r as the rank.  Results equal g calls of lowrank_linear_fwd.
+ * Workspace: fhpc_workspace_bytes_lowrank_shared_x (host-only; 0 for invalid arguments). */
+#define FHPC_MAX_SHARED 8
+int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* const* B, void* const* Y, void* H_all_out,
+                                int64_t M, int64_t K, int64_t r, int64_t N, int g,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of the g layers above:
+ *   dH_i = dY_i * B_i^T;   dX[M,K] = sum_i dH_i * A_i^T  (bf16; one product over the g*r columns of
+ *   [dH_0 | ... | dH_g-1], the per-layer input gradients are never formed);
+ *   dA_all[K][g*r] = X^T * [dH_0 | ...] (fp32, dA_i in columns i*r ..);   dB_i[r,N] = H_i^T * dY_i (fp32).
+ * dY and dB are HOST arrays of g device pointers.  H_all_saved may be NULL (H is recomputed).  dX,
+ * dA_all, dB (the array) and any dB[i] may be NULL and are then skipped.  Outputs are overwritten. */
+int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* const* B, const void* const* dY,
+                                const void* H_all_saved, void* dX, float* dA_all, float* const* dB,
+                                int64_t M, int64_t K, int64_t r, int64_t N, int g,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t fhpc_workspace_bytes_lowrank_shared_x(int backward, int64_t M, int64_t K, int64_t r, int64_t N, int g);
+
 /* Finetuning layer, forward (Sec. 5.1 eq. new_linear_layer with the frozen weight
  * stored quantised, Sec. 5.2):
  *   Y[M,N] = X[M,K] * deq(Wq, scales)[K,N] + scaling * (X * A[K,r]) * B[r,N].

@@ -22,6 +22,7 @@ FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_B
 
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose", "qlinear_lowrank_fwd_shared_x", "fhpc_workspace_bytes_shared_x",
+    "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version",
@@ -65,6 +66,11 @@ def load_library():
     lib.qlinear_lowrank_fwd_shared_x.argtypes = [vp, C.POINTER(QlinearWeight), i32, i32, i32, i64, i64, i64, vp, sz, vp]
     lib.fhpc_workspace_bytes_shared_x.argtypes = [C.POINTER(i64), i32, i64, i64, i64, i32]
     lib.fhpc_workspace_bytes_shared_x.restype = sz
+    pp = C.POINTER(vp)
+    lib.lowrank_linear_fwd_shared_x.argtypes = [vp, vp, pp, pp, vp, i64, i64, i64, i64, i32, vp, sz, vp]
+    lib.lowrank_linear_bwd_shared_x.argtypes = [vp, vp, pp, pp, vp, vp, vp, pp, i64, i64, i64, i64, i32, vp, sz, vp]
+    lib.fhpc_workspace_bytes_lowrank_shared_x.argtypes = [i32, i64, i64, i64, i64, i32]
+    lib.fhpc_workspace_bytes_lowrank_shared_x.restype = sz
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
     lib.fhpc_workspace_bytes.restype = sz
     lib.swiglu_fwd.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -82,7 +88,8 @@ def load_library():
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
     for name in EXPORTS:
-        if name not in ("fhpc_workspace_bytes", "fhpc_workspace_bytes_shared_x", "fhpc_status_string", "fhpc_version"):
+        if name not in ("fhpc_workspace_bytes", "fhpc_workspace_bytes_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
+                        "fhpc_status_string", "fhpc_version"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -220,6 +227,85 @@ def lowrank_linear_bwd(X, A, B, dY, H_saved=None, need_dX=True, need_dA=True, ne
     if rc:
         raise FhpcError(rc, "lowrank_linear_bwd")
     return dX, dA, dB
+
+
+def _ptr_array(tensors):
+    """Host array of device pointers (None entries become NULL)."""
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None else t.data_ptr()
+    return arr
+
+
+def _shared_ws(backward, M, K, r, N, g, device, workspace):
+    torch = _torch()
+    need = int(load_library().fhpc_workspace_bytes_lowrank_shared_x(int(backward), M, K, r, N, g))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel()
+
+
+def lowrank_linear_fwd_shared_x(X, A_all, Bs, Ys=None, H_all_out=None, save_H: bool = False, workspace=None):
+    """Y_i = (X A_i) B_i for the g factor pairs whose A_i sit side by side in A_all [K][g r] (bf16).
+    Returns the list of Y_i, or (list, H_all) when save_H or H_all_out is given."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    M, K = X.shape
+    g = len(Bs)
+    r, N = Bs[0].shape
+    _check(X, "X", None, bf); _check(A_all, "A_all", (K, g * r), bf)
+    for B in Bs:
+        _check(B, "B", (r, N), bf)
+    if Ys is None:
+        Ys = [torch.empty((M, N), dtype=bf, device=X.device) for _ in range(g)]
+    for Y in Ys:
+        _check(Y, "Y", (M, N), bf)
+    if H_all_out is None and save_H:
+        H_all_out = torch.empty((M, g * r), dtype=bf, device=X.device)
+    _check(H_all_out, "H_all_out", (M, g * r), bf)
+    ws, wsz = _shared_ws(False, M, K, r, N, g, X.device, workspace)
+    rc = lib.lowrank_linear_fwd_shared_x(_ptr(X), _ptr(A_all), _ptr_array(Bs), _ptr_array(Ys), _ptr(H_all_out),
+                                         M, K, r, N, g, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_linear_fwd_shared_x")
+    return (Ys, H_all_out) if H_all_out is not None else Ys
+
+
+def lowrank_linear_bwd_shared_x(X, A_all, Bs, dYs, H_all_saved=None, need_dX=True, need_dA=True, need_dB=True,
+                                dX=None, dA_all=None, dBs=None, workspace=None):
+    """Returns (dX, dA_all, [dB_i]) of the g layers of lowrank_linear_fwd_shared_x; dA_all, dB_i are fp32.
+    need_dB may be a list of g flags; dX, dA_all, dBs (a list, None entries skipped) take preallocated outputs."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    M, K = X.shape
+    g = len(Bs)
+    r, N = Bs[0].shape
+    _check(X, "X", None, bf); _check(A_all, "A_all", (K, g * r), bf); _check(H_all_saved, "H_all_saved", (M, g * r), bf)
+    if len(dYs) != g:
+        raise ValueError("one dY per factor pair")
+    for B, dY in zip(Bs, dYs):
+        _check(B, "B", (r, N), bf); _check(dY, "dY", (M, N), bf)
+    flags = list(need_dB) if isinstance(need_dB, (list, tuple)) else [bool(need_dB)] * g
+    if dX is None and need_dX:
+        dX = torch.empty((M, K), dtype=bf, device=X.device)
+    dA = dA_all
+    if dA is None and need_dA:
+        dA = torch.empty((K, g * r), dtype=torch.float32, device=X.device)
+    if dBs is None:
+        dBs = [torch.empty((r, N), dtype=torch.float32, device=X.device) if f else None for f in flags]
+    flags = [b is not None for b in dBs]
+    _check(dX, "dX", (M, K), bf); _check(dA, "dA_all", (K, g * r), torch.float32)
+    for b in dBs:
+        _check(b, "dB", (r, N), torch.float32)
+    ws, wsz = _shared_ws(True, M, K, r, N, g, X.device, workspace)
+    rc = lib.lowrank_linear_bwd_shared_x(_ptr(X), _ptr(A_all), _ptr_array(Bs), _ptr_array(dYs), _ptr(H_all_saved),
+                                         _ptr(dX), _ptr(dA), _ptr_array(dBs) if any(flags) else None,
+                                         M, K, r, N, g, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_linear_bwd_shared_x")
+    return dX, dA, dBs
 
 
 def _q_shapes(Wq, scales, qscheme, K, N, block):

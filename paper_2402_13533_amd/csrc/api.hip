@@ -637,6 +637,136 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
 }
 
+// ---- g factorised layers on one X ------------------------------------------------------------------
+// The first factors sit side by side in A_all [K][g r], so X A_all is one product g r wide, and the
+// input gradient  sum_i dH_i A_i^T  is one product over the g r columns of dH_all = [dH_0 | ... ]: the
+// g partial dX never exist and X is read once per pass instead of g times.
+
+struct SharedScratch {
+    void* H = nullptr;      // bf16 [M][g r]
+    void* dH = nullptr;     // bf16 [M][g r]
+    float* Pf = nullptr;    // fp32 [M][max(r, g r) when <= 32]  split accumulator of a narrow product
+    float* part = nullptr;  // slabs of the split reductions
+};
+
+static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int64_t r, int64_t N, int g)
+{
+    SharedScratch s;
+    const int64_t R = r * g;
+    s.H = c.take(M * R * 2);
+    if (bwd) s.dH = c.take(M * R * 2);
+    if (r <= 32) s.Pf = static_cast<float*>(c.take(M * (R <= 32 ? R : r) * 4));
+    int64_t part = 0;
+    auto upto = [&part](int64_t b) { if (b > part) part = b; };
+    if (R <= 32) upto(split_bytes(M, R, R, K));        // H_all = X A_all
+    if (bwd) {
+        if (r <= 32) upto(split_bytes(M, r, r, N));    // dH_i = dY_i B_i^T
+        upto(split_bytes(K, R, R, M));                 // dA_all = X^T dH_all
+        upto(split_bytes(r, N, N, M));                 // dB_i = H_i^T dY_i
+    }
+    s.part = static_cast<float*>(c.take(part));
+    return s;
+}
+
+static int check_shared(int64_t M, int64_t K, int64_t r, int64_t N, int g)
+{
+    if (g < 1 || g > FHPC_MAX_SHARED) return FHPC_ERR_SHAPE;
+    int rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (r % 8) return FHPC_ERR_UNSUPPORTED;            // the column blocks of A_all and H_all must start 16-byte aligned
+    return check_common(M, K, r * g, N);
+}
+
+size_t fhpc_workspace_bytes_lowrank_shared_x(int backward, int64_t M, int64_t K, int64_t r, int64_t N, int g)
+{
+    if (check_shared(M, K, r, N, g) != FHPC_OK) return 0;
+    Carver dry(nullptr);
+    carve_shared(dry, backward != 0, M, K, r, N, g);
+    return dry.used;
+}
+
+// P[M][r] (bf16, row stride ldp) = L * R^(b_mode) over Kred; a product at most 32 wide splits its reduction.
+static hipError_t narrow_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t r,
+                                 float* Pf, float* part, int64_t M, int64_t Kred, hipStream_t st)
+{
+    if (r > 32) return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, r, Kred, st);
+    hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, r, M, r, Kred, 1.f, part, st);
+    if (e != hipSuccess) return e;
+    return launch_compact_f32(Pf, r, P, ldp, M, r, 1.f, true, st);
+}
+
+// column `col` of a row-major bf16 matrix
+static inline void* bf16_col(const void* p, int64_t col)
+{
+    return const_cast<uint16_t*>(static_cast<const uint16_t*>(p)) + col;
+}
+
+int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* const* B, void* const* Y, void* H_all_out,
+                                int64_t M, int64_t K, int64_t r, int64_t N, int g,
+                                void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !A_all || !B || !Y) return FHPC_ERR_NULL;
+    int rc = check_shared(M, K, r, N, g);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(A_all, 16) || !aligned(H_all_out, 16)) return FHPC_ERR_ALIGN;
+    for (int i = 0; i < g; i++) {
+        if (!B[i] || !Y[i]) return FHPC_ERR_NULL;
+        if (!aligned(B[i], 16) || !aligned(Y[i], 16)) return FHPC_ERR_ALIGN;
+    }
+    const size_t need = fhpc_workspace_bytes_lowrank_shared_x(0, M, K, r, N, g);
+    if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    const SharedScratch s = carve_shared(c, false, M, K, r, N, g);
+    const int64_t R = r * g;
+    void* H = H_all_out ? H_all_out : s.H;
+    FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, st));
+    for (int i = 0; i < g; i++)
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, M, N, r, st));
+    return FHPC_OK;
+}
+
+int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* const* B, const void* const* dY,
+                                const void* H_all_saved, void* dX, float* dA_all, float* const* dB,
+                                int64_t M, int64_t K, int64_t r, int64_t N, int g,
+                                void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !A_all || !B || !dY) return FHPC_ERR_NULL;
+    int rc = check_shared(M, K, r, N, g);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(A_all, 16) || !aligned(H_all_saved, 16) || !aligned(dX, 16) || !aligned(dA_all, 16))
+        return FHPC_ERR_ALIGN;
+    bool any_dB = false;
+    for (int i = 0; i < g; i++) {
+        if (!B[i] || !dY[i]) return FHPC_ERR_NULL;
+        if (!aligned(B[i], 16) || !aligned(dY[i], 16) || (dB && !aligned(dB[i], 16))) return FHPC_ERR_ALIGN;
+        any_dB = any_dB || (dB && dB[i]);
+    }
+    const size_t need = fhpc_workspace_bytes_lowrank_shared_x(1, M, K, r, N, g);
+    if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Carver c(workspace);
+    const SharedScratch s = carve_shared(c, true, M, K, r, N, g);
+    const int64_t R = r * g;
+    const void* H = H_all_saved;
+    if (any_dB && !H) {
+        FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), s.H, R, R, s.Pf, s.part, M, K, st));
+        H = s.H;
+    }
+    if (dX || dA_all) {
+        for (int i = 0; i < g; i++)
+            FHPC_HIP(narrow_product(OP_KC, operand(dY[i], N), operand(B[i], N), bf16_col(s.dH, i * r), R, r, s.Pf, s.part, M, N, st));
+    }
+    if (dX) FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, M, K, R, st));
+    if (dA_all) FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(s.dH, R), dA_all, R, K, R, M, 1.f, s.part, st));
+    for (int i = 0; i < g && any_dB; i++)
+        if (dB[i])
+            FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(bf16_col(H, i * r), R), operand(dY[i], N), dB[i], N, r, N, M, 1.f, s.part, st));
+    return FHPC_OK;
+}
+
 // Y = base_scale * X deq(W) + scaling * (X A) B: the finetuning layer (base_scale 1) and the blend
 // layer (base_scale alpha, scaling 1 - alpha) share everything else.
 static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, int qscheme, int block,

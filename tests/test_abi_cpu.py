@@ -105,6 +105,20 @@ def test_validation_precedes_launch():
     ns = (C.c_int64 * 2)(64, 128)
     assert lib.fhpc_workspace_bytes_shared_x(ns, 2, 4, 512, 8, 8) >= 4 * 192 * 4
     assert lib.fhpc_workspace_bytes_shared_x(ns, 0, 4, 512, 8, 8) == 0
+    lf, lb, lw = lib.lowrank_linear_fwd_shared_x, lib.lowrank_linear_bwd_shared_x, lib.fhpc_workspace_bytes_lowrank_shared_x
+    two = (C.c_void_p * 2)(0x10000, 0x10000)
+    gap = (C.c_void_p * 2)(0x10000, None)
+    assert lf(p, p, two, gap, nul, 256, 512, 8, 64, 2, ws, big, nul) == 1                         # second layer has no Y
+    assert lf(p, p, two, two, nul, 256, 512, 8, 64, 0, ws, big, nul) == 2                         # g
+    assert lf(p, p, two, two, nul, 256, 512, 8, 64, 9, ws, big, nul) == 2
+    assert lf(p, p, two, two, nul, 256, 512, 12, 64, 2, ws, big, nul) == 6                        # rank not a multiple of 8
+    assert lf(odd, p, two, two, nul, 256, 512, 8, 64, 2, ws, big, nul) == 4
+    assert lf(p, p, two, two, nul, 256, 512, 8, 64, 2, nul, C.c_size_t(0), nul) == 5
+    assert lb(p, p, two, gap, nul, p, p, two, 256, 512, 8, 64, 2, ws, big, nul) == 1              # second layer has no dY
+    assert lb(p, p, two, two, nul, p, p, None, 256, 512, 8, 64, 2, nul, C.c_size_t(0), nul) == 5
+    assert lw(0, 256, 512, 8, 64, 2) >= 256 * 16 * 2
+    assert lw(1, 256, 512, 8, 64, 2) > lw(0, 256, 512, 8, 64, 2)
+    assert lw(1, 256, 512, 12, 64, 2) == 0 and lw(1, 256, 512, 8, 64, 9) == 0
     dc = lib.lowrank_decompose
     assert dc(p, nul, 2, p, p, 64, 8, 64, 1, ws, big, nul) == 1                                   # NULL Omega
     assert dc(p, p, 2, p, p, 64, 8, 60, 1, ws, big, nul) == 2                                     # N % 8

@@ -79,6 +79,29 @@ def test_config3_chain_reduced_tokens():
         assert v <= TOL_BF16, (k, v)
 
 
+def test_config3_chain_shared_x():
+    """The same chain with the gate and up factors side by side (one X A product, one input-gradient
+    product): every output against the full oracle; dA of gate and up arrive as the two column blocks."""
+    import numpy as np
+    from paper_2402_13533_amd import ffn
+    M, d, r, f = 320, 4096, 1024, 11008
+    X, dY, W = _ffn_inputs(M, d, r, f)
+    Yr, dXr, gr = _oracle_ffn(X.f64, dY.f64, W)
+    Ag, Bg, Au, Bu, Ad, Bd = W
+    A_gu = Bf16(np.concatenate([Ag.bits, Au.bits], axis=1)).cuda()
+    Wd = [A_gu, Bg.cuda(), Bu.cuda(), Ad.cuda(), Bd.cuda()]
+    Y, saved = ffn.ffn_fwd_shared_x(X.cuda(), *Wd)
+    dX, (dA_gu, dBg, dBu, dAd, dBd) = ffn.ffn_bwd_shared_x(X.cuda(), *Wd, dY.cuda(), saved)
+    dA_gu = from_device(dA_gu)
+    got = {"Y": from_device(Y), "dX": from_device(dX), "dAg": dA_gu[:, :r], "dBg": from_device(dBg),
+           "dAu": dA_gu[:, r:], "dBu": from_device(dBu), "dAd": from_device(dAd), "dBd": from_device(dBd)}
+    ref = dict(zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), gr), Y=Yr, dX=dXr)
+    errs = {k: oracle.rel_fro(got[k], ref[k]) for k in got}
+    print("c3 chain shared-x M=%d:" % M, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+
+
 def test_config3_full_size_sampled():
     """Config 3 at 16384 tokens: Y and dX of the whole chain on sampled rows (every step
     of the chain is row-wise independent), and each weight gradient's additivity over

@@ -174,3 +174,98 @@ def test_results_are_bit_reproducible_from_run_to_run():
         for a, b in zip(first, run()):
             assert torch.equal(a, b)
     assert np.isfinite(filler)
+
+
+def _shared_inputs(M, K, r, N, g, base):
+    """g factor pairs on one X: (X, [A_i], [B_i], [dY_i]) with the usual distributions."""
+    X = None
+    As, Bs, dYs = [], [], []
+    for i in range(g):
+        Xi, A, B, dY = lowrank_inputs(9, M, K, r, N, tensor_base=base + 4 * i)
+        X = Xi if X is None else X
+        As.append(A); Bs.append(B); dYs.append(dY)
+    return X, As, Bs, dYs
+
+
+@pytest.mark.parametrize("M,K,r,N,g", [
+    (300, 320, 64, 264, 3),      # q/k/v, rank above the split threshold, ragged everywhere
+    (515, 1024, 16, 520, 2),     # gate/up at a LoRA-sized rank: every narrow product splits its reduction
+    (257, 136, 8, 200, 3),       # g r = 24
+    (640, 512, 24, 1032, 3),     # r <= 32 < g r: dH_i split, X A_all whole
+    (1100, 768, 128, 776, 2),
+    (1, 64, 8, 72, 2),           # a single token
+    (130, 264, 40, 136, 1),      # g = 1 is the plain layer
+    (96, 128, 8, 64, 8),         # the most layers one call takes
+])
+def test_shared_x_factorised_layers(M, K, r, N, g):
+    """lowrank_linear_fwd/bwd_shared_x against g runs of the oracle: dX is the sum of the layers' input
+    gradients, dA_all and H_all hold the layers' blocks side by side."""
+    import torch
+    fhpc = _fhpc()
+    X, As, Bs, dYs = _shared_inputs(M, K, r, N, g, base=60)
+    Yr, Hr, dXr, dAr, dBr = [], [], np.zeros((M, K)), [], []
+    for A, B, dY in zip(As, Bs, dYs):
+        y, h = oracle.lowrank_fwd(X.f64, A.f64, B.f64)
+        dx, da, db = oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
+        Yr.append(y); Hr.append(h); dXr += dx; dAr.append(da); dBr.append(db)
+    Hr, dAr = np.concatenate(Hr, axis=1), np.concatenate(dAr, axis=1)
+    A_all = Bf16(np.concatenate([A.bits for A in As], axis=1)).cuda()
+    Xd, Bd, dYd = X.cuda(), [B.cuda() for B in Bs], [dY.cuda() for dY in dYs]
+    tag = "shared-x %s" % ((M, K, r, N, g),)
+
+    def check(name, got, ref):
+        err = oracle.rel_fro(from_device(got), ref)
+        print("%s %s rel_fro=%.3e" % (tag, name, err), flush=True)
+        assert err <= TOL_BF16, (tag, name, err)
+
+    Ys, H = fhpc.lowrank_linear_fwd_shared_x(Xd, A_all, Bd, save_H=True)
+    check("H_all", H, Hr)
+    for i in range(g):
+        check("Y%d" % i, Ys[i], Yr[i])
+    Ys2 = fhpc.lowrank_linear_fwd_shared_x(Xd, A_all, Bd)                 # H kept in the workspace
+    for i in range(g):
+        check("Y%d (no H_out)" % i, Ys2[i], Yr[i])
+    dX, dA, dBs = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, H_all_saved=H)
+    check("dX", dX, dXr); check("dA_all", dA, dAr)
+    for i in range(g):
+        check("dB%d" % i, dBs[i], dBr[i])
+    # recomputed H; one dB left out; then weight gradients only, then the input gradient only
+    flags = [i != 0 for i in range(g)]
+    dX2, dA2, dBs2 = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, need_dB=flags)
+    check("dX (recompute)", dX2, dXr); check("dA_all (recompute)", dA2, dAr)
+    assert dBs2[0] is None
+    for i in range(1, g):
+        check("dB%d (recompute)" % i, dBs2[i], dBr[i])
+    dX3, dA3, dBs3 = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, H_all_saved=H, need_dX=False)
+    assert dX3 is None
+    check("dA_all (no dX)", dA3, dAr)
+    dX4, dA4, dBs4 = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, need_dA=False, need_dB=False)
+    assert dA4 is None and all(b is None for b in dBs4)
+    check("dX (alone)", dX4, dXr)
+    torch.cuda.synchronize()
+
+
+def test_shared_x_matches_the_single_layer_calls():
+    """The layers' outputs and weight gradients of the shared call are those of the single-layer entry
+    point on the same operands (same kernels, same reduction order: identical bits where the product
+    has the same shape, i.e. Y_i and dB_i)."""
+    import torch
+    fhpc = _fhpc()
+    M, K, r, N, g = 520, 512, 64, 264, 3
+    X, As, Bs, dYs = _shared_inputs(M, K, r, N, g, base=90)
+    A_all = Bf16(np.concatenate([A.bits for A in As], axis=1)).cuda()
+    Xd, Bd, dYd = X.cuda(), [B.cuda() for B in Bs], [dY.cuda() for dY in dYs]
+    Ys, H = fhpc.lowrank_linear_fwd_shared_x(Xd, A_all, Bd, save_H=True)
+    dX, dA, dBs = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, H_all_saved=H)
+    dX_sum = np.zeros((M, K))
+    for i in range(g):
+        Ad = As[i].cuda()
+        Y1, H1 = fhpc.lowrank_linear_fwd(Xd, Ad, Bd[i], save_H=True)
+        dX1, dA1, dB1 = fhpc.lowrank_linear_bwd(Xd, Ad, Bd[i], dYd[i], H_saved=H1)
+        assert oracle.rel_fro(from_device(H[:, i * r:(i + 1) * r].contiguous()), from_device(H1)) <= 1e-6
+        assert oracle.rel_fro(from_device(Ys[i]), from_device(Y1)) <= 1e-6
+        assert oracle.rel_fro(from_device(dBs[i]), from_device(dB1)) <= 1e-6
+        assert oracle.rel_fro(from_device(dA[:, i * r:(i + 1) * r].contiguous()), from_device(dA1)) <= 1e-5
+        dX_sum += from_device(dX1)
+    assert oracle.rel_fro(from_device(dX), dX_sum) <= TOL_BF16
+    torch.cuda.synchronize()
