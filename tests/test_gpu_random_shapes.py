@@ -62,3 +62,41 @@ def test_random_shapes(seed):
                 assert e <= TOL_BF16, (tag, name, e)
             else:
                 assert not from_device(g).any(), (tag, name)          # alpha = 1: no gradient reaches the pair
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_random_shapes_shared_x(seed):
+    """Seeded random shapes through lowrank_linear_fwd/bwd_shared_x (g layers on one X): every output
+    against g runs of the oracle, the input gradient against their sum."""
+    import paper_2402_13533_amd as fhpc
+    rng = np.random.default_rng(9500 + seed)
+    pick = lambda a: a[rng.integers(len(a))]
+    for it in range(12):
+        M = int(pick(TOKENS))
+        r = int(pick([8, 16, 24, 32, 40, 64, 136]))
+        g = int(pick([1, 2, 3, 4, 8]))
+        K = int(rng.integers(1, 24)) * 64
+        N = int(rng.integers(1, 120)) * 8
+        base = 500000 * (seed + 1) + 40 * it
+        saved = bool(rng.random() < 0.5)
+        tag = "shared-x M=%d K=%d r=%d N=%d g=%d saved_H=%s" % (M, K, r, N, g, saved)
+        X = Bf16.normal(base, (M, K), 1.0)
+        As = [Bf16.normal(base + 1 + 3 * i, (K, r), K ** -0.5) for i in range(g)]
+        Bs = [Bf16.normal(base + 2 + 3 * i, (r, N), r ** -0.5) for i in range(g)]
+        dYs = [Bf16.normal(base + 3 + 3 * i, (M, N), 1.0) for i in range(g)]
+        Xd = X.cuda()
+        A_all = Bf16(np.concatenate([A.bits for A in As], axis=1)).cuda()
+        Bd, dYd = [B.cuda() for B in Bs], [dY.cuda() for dY in dYs]
+        Ys, H = fhpc.lowrank_linear_fwd_shared_x(Xd, A_all, Bd, save_H=True)
+        dX, dA, dBs = fhpc.lowrank_linear_bwd_shared_x(Xd, A_all, Bd, dYd, H_all_saved=H if saved else None)
+        dA = from_device(dA)
+        dX_ref = np.zeros((M, K))
+        for i in range(g):
+            y = oracle.lowrank_fwd(X.f64, As[i].f64, Bs[i].f64)[0]
+            dx, da, db = oracle.lowrank_bwd(X.f64, As[i].f64, Bs[i].f64, dYs[i].f64)
+            dX_ref += dx
+            for name, got, rf in (("Y", from_device(Ys[i]), y), ("dA", dA[:, i * r:(i + 1) * r], da), ("dB", from_device(dBs[i]), db)):
+                e = oracle.rel_fro(got, rf)
+                assert e <= TOL_BF16, (tag, name, i, e)
+        e = oracle.rel_fro(from_device(dX), dX_ref)
+        assert e <= TOL_BF16, (tag, "dX", e)
