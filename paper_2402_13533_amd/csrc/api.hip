@@ -50,7 +50,6 @@ struct Scratch {
     float* dA_t = nullptr;  // fp32 [K][rp]
     float* dB_t = nullptr;  // fp32 [rp][N]
     float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
-    float* Yf = nullptr;    // fp32 [M][N]    factorised layer, few tokens: unsplit second product
     void* Wm = nullptr;     // bf16 [K][N]    base_scale * deq(W) + scaling * A B, many tokens (see many_tokens)
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
@@ -59,6 +58,7 @@ struct Scratch {
 };
 
 int64_t rank_pad(int64_t r) { return round_up(r, 8); }
+
 
 // With many tokens the frozen-weight product dominates the finetuning layer, and the plain bf16 kernels
 // (operands through global -> LDS requests) run it about 1.5 times faster than the kernels that
@@ -69,9 +69,6 @@ int64_t rank_pad(int64_t r) { return round_up(r, 8); }
 // 13B decoder layer in int4, a whole step is faster this way from somewhere between 1536 and 2048 tokens.
 bool many_tokens(int64_t M) { return M >= 2048; }
 
-// The factorised layer's forward for at most one 32-row tile of tokens is bound by reading A and
-// B once: its products are then spread over the chip by splitting their reductions.
-bool few_tokens(int64_t M) { return M <= 32; }
 
 int64_t tile_count(int tile, int64_t M, int64_t N)
 {
@@ -108,11 +105,12 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
     return sp;
 }
 
-SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
+// `rows32`: 32-row tiles whatever M is (the only fp32-output shape of the products X A, H B, dY B^T, dH A^T)
+SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred, bool rows32 = false)
 {
     int tile;
     if (N <= 32) tile = TILE_256x32;
-    else if (M <= 32) tile = TILE_32x256;
+    else if (M <= 32 || rows32) tile = TILE_32x256;
     else if (M > 128 && N > 128) tile = TILE_256x256;
     else if (M > 128) tile = TILE_256x128;
     else if (N > 128) tile = TILE_128x256;
@@ -129,10 +127,31 @@ SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred)
 }
 
 // Bytes of partial-sum slabs for an M x N (leading dimension ldc) product reduced over Kred.
-int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred)
+int64_t split_bytes(int64_t M, int64_t N, int64_t ldc, int64_t Kred, bool rows32 = false)
 {
-    const SplitPlan sp = plan_split(M, N, Kred);
+    const SplitPlan sp = plan_split(M, N, Kred, rows32);
     return sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0;
+}
+
+// A bf16 product M x Nout whose plain launch would put tiles on fewer than half of the compute units,
+// while its reduction is long, is bound by streaming the long operand through those few units: it runs
+// as a split reduction on 32-row tiles instead, as many slices as fill the chip, and the slab sum
+// rounds to bf16.  Measured on one factorised layer 4096 -> 512 -> 4096, forward: 64 tokens 52 -> 28
+// microseconds, 256 tokens 53 -> 30, 1024 tokens 54 -> 47; 11008 -> 1024 -> 4096 at 64 tokens 125 -> 30.
+// (Outputs at most 32 wide have their own split shape, see rank_product.)
+bool split_pays(int64_t M, int64_t Nout, int64_t Kred)
+{
+    if (Nout <= 32) return false;
+    if (M > 32) {
+        const int64_t tiles = ((M + 127) / 128) * ((Nout + 127) / 128);
+        if (2 * tiles > kNumCU || Kred < 256) return false;
+    }
+    return plan_split(M, Nout, Kred, true).splits > 1;
+}
+
+int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
+{
+    return split_pays(M, Nout, Kred) ? split_bytes(M, Nout, Nout, Kred, true) : 0;
 }
 
 // The quantised layer's input gradient for at most 64 tokens is bound by reading the packed weight
@@ -167,14 +186,6 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         s.B_p = c.take(rp * N * 2);
     }
     s.H = c.take(M * rp * 2);
-    if (op == FHPC_OP_LOWRANK_FWD && few_tokens(M)) {
-        // both products run as split reductions on the 32-row tile
-        s.Hf = static_cast<float*>(c.take(M * rp * 4));
-        s.Yf = static_cast<float*>(c.take(M * N * 4));
-        const int64_t p1 = split_bytes(M, rp, rp, K), p2 = split_bytes(M, N, N, rp);
-        s.part = static_cast<float*>(c.take(p1 > p2 ? p1 : p2));
-        return s;
-    }
     if (bwd) s.dH = c.take(M * rp * 2);
     if (rp <= 32) s.Hf = static_cast<float*>(c.take(M * rp * 4));
     if (bwd && rp != r) {
@@ -198,7 +209,12 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     if (rp <= 32) {
         upto(split_bytes(M, rp, rp, K));               // H  = X A
         if (bwd) upto(split_bytes(M, rp, rp, N));      // dH = dY B^T
+    } else {
+        upto(product_part_bytes(M, rp, K));
+        if (bwd) upto(product_part_bytes(M, rp, N));
     }
+    if (op == FHPC_OP_LOWRANK_FWD) upto(product_part_bytes(M, N, rp));     // Y  = H B
+    if (op == FHPC_OP_LOWRANK_BWD) upto(product_part_bytes(M, K, rp));     // dX = dH A^T
     if (bwd) {
         upto(split_bytes(K, rp, rp, M));               // dA = X^T dH
         upto(split_bytes(rp, N, N, M));                // dB = H^T dY
@@ -283,10 +299,10 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
 // left alone: *wrote_bf16 tells the caller which happened.
 hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
                           int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st,
-                          void* bf16_out = nullptr, bool* wrote_bf16 = nullptr)
+                          void* bf16_out = nullptr, bool* wrote_bf16 = nullptr, bool rows32 = false)
 {
     if (wrote_bf16) *wrote_bf16 = false;
-    const SplitPlan sp = plan_split(M, N, Kred);
+    const SplitPlan sp = plan_split(M, N, Kred, rows32);
     GemmArgs g = {};
     g.a = a; g.b = b; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
@@ -308,6 +324,19 @@ hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, 
     return launch_sum_slabs(part, M * ldc, sp.splits, C, false, st);
 }
 
+// P[M][Nout] (bf16, row stride ldp) = L * R, L with k contiguous: the plain launch, or the split reduction on
+// 32-row tiles when that pays (split_pays) and P is dense.
+hipError_t product_bf16(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t Nout,
+                        int64_t M, int64_t Kred, float* part, hipStream_t st)
+{
+    if (ldp == Nout && split_pays(M, Nout, Kred)) {
+        bool done = false;
+        // more than one slice (split_pays), so the slab sum writes P and no fp32 output is touched
+        return gemm_split_f32(OP_KC, b_mode, a, b, nullptr, Nout, M, Nout, Kred, 1.f, part, st, P, &done, true);
+    }
+    return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, Nout, Kred, st);
+}
+
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
 // split the long reduction, accumulate in fp32, then round once to bf16.
 hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf, float* part,
@@ -319,7 +348,7 @@ hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64
         if (e != hipSuccess || done) return e;
         return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
     }
-    return gemm_plain(OP_KC, b_mode, a, b, P, rp, M, rp, Kred, st);
+    return product_bf16(b_mode, a, b, P, rp, rp, M, Kred, part, st);
 }
 
 struct Factors {
@@ -578,17 +607,8 @@ int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, voi
     rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
     if (rc) return rc;
     void* H = (H_out && rp == r) ? H_out : s.H;
-    if (few_tokens(M)) {
-        bool done = false;
-        FHPC_HIP(gemm_split_f32(OP_KC, OP_XC, operand(X, K), operand(f.A, rp), s.Hf, rp, M, rp, K, 1.f, s.part, st, H, &done));
-        if (!done) FHPC_HIP(launch_compact_f32(s.Hf, rp, H, rp, M, rp, 1.f, true, st));
-        done = false;
-        FHPC_HIP(gemm_split_f32(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), s.Yf, N, M, N, rp, 1.f, s.part, st, Y, &done));
-        if (!done) FHPC_HIP(launch_compact_f32(s.Yf, N, Y, N, M, N, 1.f, true, st));
-    } else {
-        FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st));
-    }
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
+    FHPC_HIP(product_bf16(OP_XC, operand(H, rp), operand(f.B, N), Y, N, N, M, rp, s.part, st));
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
     return FHPC_OK;
 }
@@ -633,7 +653,7 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
     if (dX || dA)
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
     if (dX)
-        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st));
+        FHPC_HIP(product_bf16(OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, K, M, rp, s.part, st));
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
 }
 
@@ -658,9 +678,11 @@ static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int
     if (r <= 32) s.Pf = static_cast<float*>(c.take(M * (R <= 32 ? R : r) * 4));
     int64_t part = 0;
     auto upto = [&part](int64_t b) { if (b > part) part = b; };
-    if (R <= 32) upto(split_bytes(M, R, R, K));        // H_all = X A_all
+    upto(R <= 32 ? split_bytes(M, R, R, K) : product_part_bytes(M, R, K));      // H_all = X A_all
+    if (!bwd) upto(product_part_bytes(M, N, r));       // Y_i = H_i B_i
     if (bwd) {
-        if (r <= 32) upto(split_bytes(M, r, r, N));    // dH_i = dY_i B_i^T
+        upto(product_part_bytes(M, K, R));             // dX = dH_all A_all^T
+        if (r <= 32) upto(split_bytes(M, r, r, N));    // dH_i = dY_i B_i^T (a column block: never the 32-row split)
         upto(split_bytes(K, R, R, M));                 // dA_all = X^T dH_all
         upto(split_bytes(r, N, N, M));                 // dB_i = H_i^T dY_i
     }
@@ -689,7 +711,7 @@ size_t fhpc_workspace_bytes_lowrank_shared_x(int backward, int64_t M, int64_t K,
 static hipError_t narrow_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t r,
                                  float* Pf, float* part, int64_t M, int64_t Kred, hipStream_t st)
 {
-    if (r > 32) return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, r, Kred, st);
+    if (r > 32) return product_bf16(b_mode, a, b, P, ldp, r, M, Kred, part, st);
     hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, r, M, r, Kred, 1.f, part, st);
     if (e != hipSuccess) return e;
     return launch_compact_f32(Pf, r, P, ldp, M, r, 1.f, true, st);
@@ -723,7 +745,7 @@ int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* co
     void* H = H_all_out ? H_all_out : s.H;
     FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, st));
     for (int i = 0; i < g; i++)
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, M, N, r, st));
+        FHPC_HIP(product_bf16(OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, N, M, r, s.part, st));
     return FHPC_OK;
 }
 
@@ -759,7 +781,7 @@ int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* co
         for (int i = 0; i < g; i++)
             FHPC_HIP(narrow_product(OP_KC, operand(dY[i], N), operand(B[i], N), bf16_col(s.dH, i * r), R, r, s.Pf, s.part, M, N, st));
     }
-    if (dX) FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, M, K, R, st));
+    if (dX) FHPC_HIP(product_bf16(OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, K, M, R, s.part, st));
     if (dA_all) FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(s.dH, R), dA_all, R, K, R, M, 1.f, s.part, st));
     for (int i = 0; i < g && any_dB; i++)
         if (dB[i])

@@ -246,9 +246,10 @@ def test_shared_x_factorised_layers(M, K, r, N, g):
 
 
 def test_shared_x_matches_the_single_layer_calls():
-    """The layers' outputs and weight gradients of the shared call are those of the single-layer entry
-    point on the same operands (same kernels, same reduction order: identical bits where the product
-    has the same shape, i.e. Y_i and dB_i)."""
+    """The layers' outputs and weight gradients of the shared call against those of the single-layer entry
+    point on the same operands, GPU against GPU.  The wide products of the shared call may run on another
+    tile shape or another split of the reduction than the narrow ones, which sums in another order, so a
+    few per cent of the bf16 values differ by one ulp: the bound is a fraction of the bf16 tolerance."""
     import torch
     fhpc = _fhpc()
     M, K, r, N, g = 520, 512, 64, 264, 3
@@ -262,10 +263,10 @@ def test_shared_x_matches_the_single_layer_calls():
         Ad = As[i].cuda()
         Y1, H1 = fhpc.lowrank_linear_fwd(Xd, Ad, Bd[i], save_H=True)
         dX1, dA1, dB1 = fhpc.lowrank_linear_bwd(Xd, Ad, Bd[i], dYd[i], H_saved=H1)
-        assert oracle.rel_fro(from_device(H[:, i * r:(i + 1) * r].contiguous()), from_device(H1)) <= 1e-6
-        assert oracle.rel_fro(from_device(Ys[i]), from_device(Y1)) <= 1e-6
-        assert oracle.rel_fro(from_device(dBs[i]), from_device(dB1)) <= 1e-6
-        assert oracle.rel_fro(from_device(dA[:, i * r:(i + 1) * r].contiguous()), from_device(dA1)) <= 1e-5
+        assert oracle.rel_fro(from_device(H[:, i * r:(i + 1) * r].contiguous()), from_device(H1)) <= 2e-3
+        assert oracle.rel_fro(from_device(Ys[i]), from_device(Y1)) <= 2e-3
+        assert oracle.rel_fro(from_device(dBs[i]), from_device(dB1)) <= 2e-3
+        assert oracle.rel_fro(from_device(dA[:, i * r:(i + 1) * r].contiguous()), from_device(dA1)) <= 2e-3
         dX_sum += from_device(dX1)
     assert oracle.rel_fro(from_device(dX), dX_sum) <= TOL_BF16
     torch.cuda.synchronize()
