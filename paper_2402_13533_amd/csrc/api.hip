@@ -154,6 +154,37 @@ int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
     return split_pays(M, Nout, Kred) ? split_bytes(M, Nout, Nout, Kred, true) : 0;
 }
 
+// The products of the finetuning and blend layers that dequantise the frozen weight in their load path
+// (65 .. 2047 tokens) read that weight once per row of 128-wide output tiles: with few tiles the launch is
+// bound by streaming the weight through few compute units.  Its reduction is then cut into slices of at
+// least 512, as many as fit the chip at once (two workgroups of this tile per compute unit: one slice more
+// and a second, nearly empty round of workgroups costs more than the slices gain); the rank-r phase stays
+// with slice 0 and a slab sum writes the bf16 output.  Measured on a 4-bit 5120 x 5120 weight: 65 tokens
+// 76 -> 34 microseconds forward and 96 -> 49 backward, 256 tokens 86 -> 47 and 101 -> 63.
+SplitPlan plan_fused_split(int64_t M, int64_t Nout, int64_t Kred)
+{
+    SplitPlan sp;
+    sp.tile = TILE_128x128;
+    sp.splits = 1;
+    sp.k_chunk = (int)round_up(Kred, 64);
+    const int64_t tiles = tile_count(TILE_128x128, M, Nout);
+    const int64_t ksteps = (Kred + 63) / 64;
+    int64_t s = (2 * kNumCU) / tiles;
+    if (s > ksteps / 8) s = ksteps / 8;
+    if (s > 16) s = 16;
+    if (s < 2) return sp;
+    const int64_t steps_per = (ksteps + s - 1) / s;
+    sp.k_chunk = (int)(steps_per * 64);
+    sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
+    return sp;
+}
+
+int64_t fused_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
+{
+    const SplitPlan sp = plan_fused_split(M, Nout, Kred);
+    return sp.splits > 1 ? (int64_t)sp.splits * M * Nout * 4 : 0;
+}
+
 // The quantised layer's input gradient for at most 64 tokens is bound by reading the packed weight
 // once: it then comes from the weight-streaming kernel (both schemes have the same shape limits).
 bool stream_dx(int64_t M, int64_t K, int64_t r, int64_t N)
@@ -213,6 +244,8 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         upto(product_part_bytes(M, rp, K));
         if (bwd) upto(product_part_bytes(M, rp, N));
     }
+    if (op == FHPC_OP_QLINEAR_FWD) upto(fused_part_bytes(M, N, K));        // Y  = X deq(W) + s H B
+    if (op == FHPC_OP_QLINEAR_BWD) upto(fused_part_bytes(M, K, N));        // dX = dY deq(W)^T + s dH A^T
     if (op == FHPC_OP_LOWRANK_FWD) upto(product_part_bytes(M, N, rp));     // Y  = H B
     if (op == FHPC_OP_LOWRANK_BWD) upto(product_part_bytes(M, K, rp));     // dX = dH A^T
     if (bwd) {
@@ -349,6 +382,27 @@ hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64
         return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
     }
     return product_bf16(b_mode, a, b, P, rp, rp, M, Kred, part, st);
+}
+
+// C[M][Nout] (bf16, dense) = g.alpha * (g.mid_scale * A2 B2 + A deq(B)): whole, or split over the reduction
+hipError_t fused_product(int b_mode, int b2_mode, GemmArgs g, void* C, int64_t M, int64_t Nout, int64_t Kred,
+                         float* part, hipStream_t st)
+{
+    const SplitPlan sp = plan_fused_split(M, Nout, Kred);
+    g.ldc = Nout;
+    if (sp.splits == 1) {
+        g.c = C;
+        g.splits = 1;
+        g.k_chunk = (int)round_up(Kred, 64);
+        return launch_gemm_bf16(OP_KC, b_mode, b2_mode, OUT_BF16, pick_tile(M, Nout, false), g, st);
+    }
+    g.c = part;
+    g.splits = sp.splits;
+    g.k_chunk = sp.k_chunk;
+    g.split_stride = M * Nout;
+    hipError_t e = launch_gemm_bf16(OP_KC, b_mode, b2_mode, OUT_F32, TILE_128x128, g, st);
+    if (e != hipSuccess) return e;
+    return launch_sum_slabs(part, M * Nout, sp.splits, C, true, st);
 }
 
 struct Factors {
@@ -851,11 +905,10 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
         g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: W[K][N], element (n, k) at k*N + n
         g.a2 = operand(H, rp);
         g.b2 = operand(f.B, N);
-        g.c = Y; g.ldc = N;
         g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
-        g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(K, 64);
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
         const int b_mode = dense ? OP_XC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
-        FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_XC, OUT_BF16, pick_tile(M, N, false), g, st));
+        FHPC_HIP(fused_product(b_mode, OP_XC, g, Y, M, N, K, s.part, st));
     }
     if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
     return FHPC_OK;
@@ -1026,11 +1079,10 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
         g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: element (k, n) at k*N + n
         g.a2 = operand(s.dH, rp);
         g.b2 = operand(f.A, rp);
-        g.c = dX; g.ldc = K;
         g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
-        g.alpha = base_scale; g.mid_scale = scaling / base_scale; g.splits = 1; g.k_chunk = (int)round_up(N, 64);
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
         const int b_mode = dense ? OP_KC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
-        FHPC_HIP(launch_gemm_bf16(OP_KC, b_mode, OP_KC, OUT_BF16, pick_tile(M, K, false), g, st));
+        FHPC_HIP(fused_product(b_mode, OP_KC, g, dX, M, K, N, s.part, st));
     }
     return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, st);
 }

@@ -172,6 +172,46 @@ def test_qlinear_shapes(scheme, M, K, r, N):
 
 
 @pytest.mark.parametrize("scheme", [8, 4])
+@pytest.mark.parametrize("M,K,r,N", [
+    (200, 1536, 16, 1032),    # 3 slices of 512 forward (N ragged), 2 slices backward
+    (65, 2048, 8, 1160),      # the first token count past the weight-streaming kernels
+    (700, 1024, 40, 1096),    # 6 x 9 tiles, 2 slices; rank above 32
+])
+def test_qlinear_split_reduction(scheme, M, K, r, N):
+    """65 .. 2047 tokens with few output tiles and a long reduction: the dequantising product is cut into
+    slices of the reduction (fp32 slabs, the rank-r phase in slice 0, slab sum to bf16)."""
+    _run_case("split q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=150)
+
+
+@pytest.mark.parametrize("kind", ["q4", "q8", "dense"])
+def test_blend_layer_split_reduction(kind):
+    """The blend layer on the same route (slices of the reduction), quantised and dense bf16 weight."""
+    fhpc = _fhpc()
+    M, K, r, N, alpha = 200, 1536, 24, 1032, 0.6
+    W, X, A, _, dY = qlinear_inputs(8, M, K, r, N, 160)
+    B = Bf16.normal(8126, (r, N), r ** -0.5)
+    if kind == "dense":
+        Wb = Bf16.normal(8127, (K, N), K ** -0.5)
+        Wd, W_dev, sc_dev, scheme = Wb.f64, Wb.cuda(), None, fhpc.FHPC_W_BF16
+    else:
+        scheme = int(kind[1])
+        Wq, sc = _quantize_host(W * 50.0, scheme)
+        Wd = oracle.dequant(Wq, sc, scheme, 64)
+        W_dev, sc_dev = _to_dev(Wq, sc)
+    Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
+    Y, H = fhpc.qlinear_blend_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, save_H=True)
+    dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, dYd, H_saved=H)
+    Yr, Hr = oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)
+    dXr, dAr, dBr = oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
+    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
+            "dX": oracle.rel_fro(from_device(dX), dXr), "dA": oracle.rel_fro(from_device(dA), dAr),
+            "dB": oracle.rel_fro(from_device(dB), dBr)}
+    print("blend split %s" % kind, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+
+
+@pytest.mark.parametrize("scheme", [8, 4])
 def test_qlinear_scaling_zero_is_base_layer(scheme):
     fhpc = _fhpc()
     M, K, r, N = 200, 256, 8, 264
