@@ -52,9 +52,10 @@ def parse_args():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "merge", "streams"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0,
-                    help="c4/c5 only: override the 4096 tokens (the weight-streaming regime is tokens <= 64; the "
-                         "JSON line then quotes GB/s on the algorithmic bytes as the value to read)")
-    ap.add_argument("--forward-only", action="store_true", help="c4/c5 only: time the forward call alone")
+                    help="c2/c4/c5: override the configuration's token count (c4/c5: the weight-streaming regime is tokens <= 64, "
+                         "the JSON line then quotes GB/s on the algorithmic bytes as the value to read; c2: 48 independent "
+                         "layers per step below 4096 tokens)")
+    ap.add_argument("--forward-only", action="store_true", help="c2/c4/c5: time the forward call alone")
     ap.add_argument("--premerged", action="store_true",
                     help="c4/c5: a step merges each weight once (lowrank_merge) and passes the merged weight to the forward "
                          "and the backward call, instead of each call merging by itself")
@@ -85,9 +86,10 @@ def randn(shape, std, dtype, gen):
 class LowrankCall:
     """One factorised linear: preallocated tensors, fwd and bwd through the C ABI."""
 
-    def __init__(self, fhpc, M, K, r, N, dtype, gen, recompute=False):
+    def __init__(self, fhpc, M, K, r, N, dtype, gen, recompute=False, forward_only=False):
         import torch
         self.f = fhpc
+        self.forward_only = forward_only
         self.M, self.K, self.r, self.N = M, K, r, N
         self.X = randn((M, K), 1.0, dtype, gen)
         self.dY = randn((M, N), 1.0, dtype, gen)
@@ -102,14 +104,20 @@ class LowrankCall:
 
     def flops(self):
         from paper_2402_13533_amd import shapes
+        if self.forward_only:
+            return 2 * self.M * self.r * (self.K + self.N)
         return shapes.lowrank_flops(self.M, self.K, self.r, self.N)
 
     def io_bytes(self):
         e = self.X.element_size()
+        if self.forward_only:
+            return e * (self.M * self.K + self.M * self.N) + e * self.r * (self.K + self.N)
         return e * (2 * self.M * self.K + 2 * self.M * self.N) + (e + 4) * self.r * (self.K + self.N)
 
     def run(self):
         self.f.lowrank_linear_fwd(self.X, self.A, self.B, Y=self.Y, H_out=self.H)
+        if self.forward_only:
+            return
         self.f.lowrank_linear_bwd(self.X, self.A, self.B, self.dY, H_saved=None if self.recompute else self.H,
                                   dX=self.dX, dA=self.dA, dB=self.dB)
 
@@ -327,8 +335,13 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         desc = "config 1: fp32 factorised linear 256x768, r=32, fwd+bwd"
         dtype = "f32"
     elif name == "c2":
-        calls = [LowrankCall(fhpc, 16384, 4096, 512, 4096, bf, gen, recompute) for _ in range(4)]
-        desc = "config 2: Llama-2-7B q/k/v/o projections factorised r=512, 16384 tokens, bf16, fwd+bwd"
+        M = tokens or 16384
+        # at a reduced token count the factor pairs (8.4 MB each) would sit in the 256 MB Infinity Cache from step
+        # to step: 48 independent layers then stand for the 4, so that the weights come from HBM
+        copies = 4 if M >= 4096 else 48
+        calls = [LowrankCall(fhpc, M, 4096, 512, 4096, bf, gen, recompute, forward_only) for _ in range(copies)]
+        desc = "config 2: Llama-2-7B q/k/v/o projections factorised r=512, %d tokens, bf16, %s%s" % (
+            M, "fwd" if forward_only else "fwd+bwd", "" if copies == 4 else ", %d independent layers per step" % copies)
         dtype = "bf16"
     elif name == "c3":
         calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen, shared_x)]
@@ -365,6 +378,8 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
             "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
     if shared_x and name == "c2":
+        if tokens or forward_only:
+            raise SystemExit("--shared-x on c2 runs the configuration's 16384 tokens, forward and backward")
         calls = [SharedLowrankCall(fhpc, 16384, 4096, 512, 4096, 3, gen), calls[3]]
         desc += ", q/k/v read one X through the shared-X call (their input gradients arrive summed)"
         return calls, desc, dtype

@@ -431,9 +431,10 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha,
                  const Scratch& s, hipStream_t st)
 {
-    if ((dA || dB) && few_token_grads_supports(M, rp)) {
-        // a handful of tokens: M-deep sums, both products in one launch
-        FHPC_HIP(launch_few_token_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
+    // a handful of tokens: M-deep sums, both products in one launch of the vector-ALU kernel, until the sums
+    // over the tokens outweigh writing the outputs once
+    if ((dA || dB) && token_outer_supports(M) && (M <= 32 || rp * (K + N) <= ((int64_t)8 << 20))) {
+        FHPC_HIP(launch_token_outer_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
         return FHPC_OK;
     }
     if (dA) {

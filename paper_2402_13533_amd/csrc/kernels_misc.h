@@ -33,9 +33,9 @@ hipError_t launch_add_f32_bf16(const float* a, const void* b, void* out, int64_t
 hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s);
 // Rank-r weight gradients from at most 64 tokens, both in one launch (either output may be NULL):
 //   dA[k][j] = alpha sum_m X[m][k] dH[m][j]  (fp32 [K][r]),   dB[j][n] = alpha sum_m H[m][j] dY[m][n]  (fp32 [r][N]).
-// X [M][K], dY [M][N], dH and H [M][rp] are bf16; r <= rp <= 64.
-bool few_token_grads_supports(int64_t M, int64_t rp);
-hipError_t launch_few_token_grads(const void* X, const void* dH, float* dA, const void* H, const void* dY, float* dB,
-                                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha, hipStream_t s);
+// X [M][K], dY [M][N], dH and H [M][rp] are bf16; any rank; tiles of the outputs, a 4 x 4 patch per thread.
+bool token_outer_supports(int64_t M);
+hipError_t launch_token_outer_grads(const void* X, const void* dH, float* dA, const void* H, const void* dY, float* dB,
+                                    int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha, hipStream_t s);
 
 }  // namespace fhpc

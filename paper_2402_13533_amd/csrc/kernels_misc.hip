@@ -1,7 +1,6 @@
 // fp32 GEMM (true fp32 arithmetic), SiLU gate, weight quantise / unpack / dequantise,
 // and the small copy / convert kernels the entry points use around the GEMM core.
 #include "kernels_misc.h"
-#include "few_token_grads.h"
 #include "profile.h"
 
 namespace fhpc {
@@ -764,50 +763,102 @@ hipError_t launch_zero(void* p, int64_t bytes, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------
-// Rank-r weight gradients from a handful of tokens.  With M <= 64 the two products are M-deep
-// sums over outputs that are read once, far too small for the matrix-core tiles: a thread owns
-// one column c of the streamed operand U (a k for dA with U = X, an n for dB with U = dY), keeps
-// its r sums in registers and adds  U[m][c] * V[m][j]  token by token, V (dH or H, M x rp) sitting
-// in LDS as fp32 where every lane reads the same word.  The workgroups of both products share a
-// launch: the first ceil(K / 256) take dA, the rest dB.
+// Rank-r weight gradients from at most 64 tokens:
+//   out[a][b] = alpha * sum_m U[m][a] V[m][b]      (dA: U = X, V = dH;  dB: U = H, V = dY)
+// are M-deep sums, far too shallow for the matrix-core tiles, over fp32 outputs that are written once
+// (and at a large rank bound by that).  A workgroup owns a 32 x 128 tile of the output,
+// stages the tokens' 32 + 128 operand values as fp32 in LDS and every thread sums a 4 x 4 patch over
+// the tokens; rows leave as 16-byte stores, 512 contiguous bytes per 32 lanes.  The tiles of both
+// products share a launch.
 // ---------------------------------------------------------------------------------
-template <int MT, int RP>
-__global__ __launch_bounds__(FTG_NT) void few_token_grads_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dH,
-                                                                float* __restrict__ dA, const uint16_t* __restrict__ H,
-                                                                const uint16_t* __restrict__ dY, float* __restrict__ dB,
-                                                                int M, int K, int r, int rp, int N, float alpha, int blocks_a)
+constexpr int TOG_NT = 256, TOG_A = 32, TOG_B = 128, TOG_M = 64;
+
+struct TokenOuterJob {
+    const uint16_t* U;   // bf16 [M][ldu]
+    const uint16_t* V;   // bf16 [M][ldv]
+    float* out;          // fp32 [na][ldo], columns < nb written
+    int ldu, ldv, ldo, na, nb, tiles_b, tiles;
+};
+
+__global__ __launch_bounds__(TOG_NT) void token_outer_kernel(TokenOuterJob j0, TokenOuterJob j1, int M, float alpha)
 {
-    __shared__ __attribute__((aligned(16))) float Vs[MT * RP];
-    if ((int)blockIdx.x < blocks_a) {
-        const int c = (int)blockIdx.x * FTG_NT + (int)threadIdx.x;
-        few_token_grads_body<MT, RP, false>(Vs, X, K, c, M, r, alpha, dA, [&](float* v) { fill_from_bf16<MT, RP>(v, dH, M, rp); });
-    } else {
-        const int c = ((int)blockIdx.x - blocks_a) * FTG_NT + (int)threadIdx.x;
-        few_token_grads_body<MT, RP, true>(Vs, dY, N, c, M, r, alpha, dB, [&](float* v) { fill_from_bf16<MT, RP>(v, H, M, rp); });
+    __shared__ __attribute__((aligned(16))) float Us[TOG_M][TOG_A];
+    __shared__ __attribute__((aligned(16))) float Vs[TOG_M][TOG_B];
+    const bool first = (int)blockIdx.x < j0.tiles;
+    const TokenOuterJob j = first ? j0 : j1;
+    const int t = first ? (int)blockIdx.x : (int)blockIdx.x - j0.tiles;
+    const int a0 = (t / j.tiles_b) * TOG_A, b0 = (t % j.tiles_b) * TOG_B;
+    const int tid = threadIdx.x;
+    // stage: 4 bf16 (8 bytes) per request; leading dimensions and tile origins are multiples of 8
+    for (int e = tid; e < TOG_M * (TOG_A / 4); e += TOG_NT) {
+        const int m = e / (TOG_A / 4), q = (e % (TOG_A / 4)) * 4;
+        uint2 w = make_uint2(0u, 0u);
+        if (m < M && a0 + q < j.ldu) w = *reinterpret_cast<const uint2*>(j.U + (int64_t)m * j.ldu + a0 + q);
+        Us[m][q + 0] = __uint_as_float(w.x << 16); Us[m][q + 1] = __uint_as_float(w.x & 0xFFFF0000u);
+        Us[m][q + 2] = __uint_as_float(w.y << 16); Us[m][q + 3] = __uint_as_float(w.y & 0xFFFF0000u);
+    }
+    for (int e = tid; e < TOG_M * (TOG_B / 4); e += TOG_NT) {
+        const int m = e / (TOG_B / 4), q = (e % (TOG_B / 4)) * 4;
+        uint2 w = make_uint2(0u, 0u);
+        if (m < M && b0 + q < j.ldv) w = *reinterpret_cast<const uint2*>(j.V + (int64_t)m * j.ldv + b0 + q);
+        Vs[m][q + 0] = __uint_as_float(w.x << 16); Vs[m][q + 1] = __uint_as_float(w.x & 0xFFFF0000u);
+        Vs[m][q + 2] = __uint_as_float(w.y << 16); Vs[m][q + 3] = __uint_as_float(w.y & 0xFFFF0000u);
+    }
+    __syncthreads();
+    const int tx = tid & 31, ty = tid >> 5;      // 4 columns from tx, 4 rows from ty
+    float acc[4][4] = {};
+    const int mt = (M + 3) & ~3;                 // (rows past M hold zeros)
+#pragma unroll 4
+    for (int m = 0; m < mt; m++) {
+        const float4 u = *reinterpret_cast<const float4*>(&Us[m][ty * 4]);
+        const float4 v = *reinterpret_cast<const float4*>(&Vs[m][tx * 4]);
+        const float uu[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            acc[i][0] = fmaf(uu[i], v.x, acc[i][0]);
+            acc[i][1] = fmaf(uu[i], v.y, acc[i][1]);
+            acc[i][2] = fmaf(uu[i], v.z, acc[i][2]);
+            acc[i][3] = fmaf(uu[i], v.w, acc[i][3]);
+        }
+    }
+    const int b = b0 + tx * 4;
+    const bool vec = (j.ldo % 4) == 0 && b + 4 <= j.nb;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int a = a0 + ty * 4 + i;
+        if (a >= j.na) continue;
+        float* dst = j.out + (int64_t)a * j.ldo + b;
+        if (vec) {
+            *reinterpret_cast<float4*>(dst) = make_float4(alpha * acc[i][0], alpha * acc[i][1], alpha * acc[i][2], alpha * acc[i][3]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                if (b + c < j.nb) dst[c] = alpha * acc[i][c];
+        }
     }
 }
 
-bool few_token_grads_supports(int64_t M, int64_t rp) { return M >= 1 && M <= FTG_MMAX && rp >= 1 && rp <= FTG_RMAX; }
+bool token_outer_supports(int64_t M) { return M >= 1 && M <= TOG_M; }
 
-hipError_t launch_few_token_grads(const void* X, const void* dH, float* dA, const void* H, const void* dY, float* dB,
-                                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha, hipStream_t s)
+hipError_t launch_token_outer_grads(const void* X, const void* dH, float* dA, const void* H, const void* dY, float* dB,
+                                    int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha, hipStream_t s)
 {
-    if (!few_token_grads_supports(M, rp)) return hipErrorInvalidValue;
-    const int blocks_a = dA ? (int)((K + FTG_NT - 1) / FTG_NT) : 0;
-    const int blocks_b = dB ? (int)((N + FTG_NT - 1) / FTG_NT) : 0;
-    if (blocks_a + blocks_b == 0) return hipSuccess;
-    const dim3 grid((unsigned)(blocks_a + blocks_b));
-#define FHPC_FTG(MT, RP)                                                                                              \
-    hipLaunchKernelGGL((few_token_grads_kernel<MT, RP>), grid, dim3(FTG_NT), 0, s, static_cast<const uint16_t*>(X),   \
-                       static_cast<const uint16_t*>(dH), dA, static_cast<const uint16_t*>(H),                        \
-                       static_cast<const uint16_t*>(dY), dB, (int)M, (int)K, (int)r, (int)rp, (int)N, alpha, blocks_a)
-    const int slot = prof_begin("few_token_grads", 2.0 * M * r * (double)((dA ? K : 0) + (dB ? N : 0)), 0.0, s);
-    if (M <= 16) {
-        if (rp <= 16) FHPC_FTG(16, 16); else if (rp <= 32) FHPC_FTG(16, 32); else FHPC_FTG(16, 64);
-    } else {
-        if (rp <= 16) FHPC_FTG(64, 16); else if (rp <= 32) FHPC_FTG(64, 32); else FHPC_FTG(64, 64);
-    }
-#undef FHPC_FTG
+    if (!token_outer_supports(M)) return hipErrorInvalidValue;
+    auto job = [](const void* U, int64_t ldu, const void* V, int64_t ldv, float* out, int64_t ldo, int64_t na, int64_t nb) {
+        TokenOuterJob j = {};
+        if (!out) return j;
+        j.U = static_cast<const uint16_t*>(U); j.V = static_cast<const uint16_t*>(V); j.out = out;
+        j.ldu = (int)ldu; j.ldv = (int)ldv; j.ldo = (int)ldo; j.na = (int)na; j.nb = (int)nb;
+        j.tiles_b = (int)((nb + TOG_B - 1) / TOG_B);
+        j.tiles = (int)((na + TOG_A - 1) / TOG_A) * j.tiles_b;
+        return j;
+    };
+    const TokenOuterJob ja = job(X, K, dH, rp, dA, r, K, r);      // dA[k][j] = sum_m X[m][k] dH[m][j]
+    const TokenOuterJob jb = job(H, rp, dY, N, dB, N, r, N);      // dB[j][n] = sum_m H[m][j] dY[m][n]
+    if (ja.tiles + jb.tiles == 0) return hipSuccess;
+    const int slot = prof_begin("token_outer_grads", 2.0 * M * r * (double)((dA ? K : 0) + (dB ? N : 0)),
+                                4.0 * r * (double)((dA ? K : 0) + (dB ? N : 0)), s);
+    hipLaunchKernelGGL(token_outer_kernel, dim3((unsigned)(ja.tiles + jb.tiles)), dim3(TOG_NT), 0, s, ja, jb, (int)M, alpha);
     prof_end(slot, s);
     return hipGetLastError();
 }

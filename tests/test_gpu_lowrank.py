@@ -49,6 +49,9 @@ def test_config1_fp32():
     (640, 512, 96, 1032),    # rank between tile sizes
     (1100, 768, 512, 776),   # pretraining-sized rank
     (48, 520, 40, 264),      # few tokens, small rank: dA and dB as token-deep sums in one launch
+    (64, 1032, 512, 776),    # few tokens, large rank: dA and dB as tiles of outer-product sums
+    (33, 328, 77, 264),      # the same with a rank that is padded (dA rows not 16-byte aligned)
+    (1, 264, 130, 520),
 ])
 def test_bf16_shapes(M, K, r, N):
     fhpc = _fhpc()
