@@ -21,19 +21,21 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side traffic per launch of a kernel on a workload (fetched + written bytes), from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_c2_lowrank_gemm_kernels.txt
 # (counter units scaled by a 256 MiB read + 256 MiB write kernel in the same run); None where
-# not measured.  Algorithmic bytes of the config 2 launches are 155-160 MB.
+# not measured.  Means over the launches of a step: the q/k/v group's wide products and the o projection's
+# share a kernel.  Algorithmic bytes of a 68.7 GFLOP launch of config 2 are 155-160 MB.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2", "gemm_pp<256x128x64,a0,b1,o0>"): 168.0e6 + 16.8e6,    # H = X A
-    ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 94.1e6 + 134.2e6,    # Y = H B
+    ("c2", "gemm_pp<256x128x64,a0,b1,o0>"): 335.7e6 + 33.6e6,    # H = X A (o), H_all = X A_all (q/k/v)
+    ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 95.2e6 + 134.2e6,    # Y = H B
     ("c2", "gemm_pp<256x128x64,a0,b0,o0>"): 168.0e6 + 16.8e6,    # dH = dY B^T
-    ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 98.0e6 + 134.2e6,    # dX = dH A^T
-    ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 227.2e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
+    ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 201.0e6 + 134.2e6,   # dX = dH A^T (o), dX = dH_all A_all^T (q/k/v)
+    ("c2", "gemm_pp<256x256x32,a1,b1,o1>"): 414.0e6 + 76.3e6,    # dA_all = X^T dH_all
+    ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 262.4e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
     # profiles/bench_merge_c5_int4_to_bf16.txt: mean over the layer's seven weights (algorithmic 115.1 MB)
     ("merge", "merge<int4>"): 38.6e6 + 90.6e6,
     # profiles/bench_c3_ffn_kernels.txt: means over the launches of a step (they differ in shape)
-    ("c3", "gemm_pp<256x256x32,a0,b1,o0>"): 375.8e6 + 159.4e6,
-    ("c3", "gemm_pp<256x256x32,a0,b0,o0>"): 375.7e6 + 121.6e6,
-    ("c3", "gemm_pp<256x256x32,a1,b1,o1>"): 734.2e6 + 82.6e6,
+    ("c3", "gemm_pp<256x256x32,a0,b1,o0>"): 451.5e6 + 191.3e6,
+    ("c3", "gemm_pp<256x256x32,a0,b0,o0>"): 450.3e6 + 119.1e6,
+    ("c3", "gemm_pp<256x256x32,a1,b1,o1>"): 881.0e6 + 81.8e6,
     # profiles/bench_c4_int8_qlinear_kernels.txt (algorithmic 100.7 MB: X, the merged weight, Y)
     ("c4", "gemm_pp<256x256x32,a0,b1,o0>"): 201.5e6 + 33.6e6,
     ("c4", "gemm_pp<256x256x32,a0,b0,o0>"): 201.5e6 + 33.6e6,
@@ -59,10 +61,14 @@ def parse_args():
     ap.add_argument("--premerged", action="store_true",
                     help="c4/c5: a step merges each weight once (lowrank_merge) and passes the merged weight to the forward "
                          "and the backward call, instead of each call merging by itself")
+    ap.add_argument("--independent-x", action="store_true",
+                    help="c2: four independent projections, each with its own X (default: q/k/v read one X through "
+                         "lowrank_linear_fwd/bwd_shared_x, as in an attention block; o has its own input); c3: gate and up "
+                         "as two single-layer calls and an add of their input gradients (default: one shared-X call)")
     ap.add_argument("--shared-x", action="store_true",
                     help="c5 with --tokens and --forward-only: the q/k/v and the gate/up projections read one X each "
                          "and go through the shared-X entry point (one call per group: qkv, o, gate+up, down); "
-                         "c2: q/k/v read one X through lowrank_linear_fwd/bwd_shared_x (fwd+bwd); c3: gate and up likewise")
+                         "c2, c3: the default (see --independent-x)")
     ap.add_argument("--shape", default="", help="c4/c5 only: K,N of a single frozen weight in place of the configuration's "
                                                 "(large weights show the streaming kernel's rate beyond the fixed launch cost)")
     ap.add_argument("--graph", action="store_true",
@@ -325,7 +331,8 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False, premerged=False):
+def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False, premerged=False,
+                   independent_x=False):
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20240213)
@@ -339,15 +346,23 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         # at a reduced token count the factor pairs (8.4 MB each) would sit in the 256 MB Infinity Cache from step
         # to step: 48 independent layers then stand for the 4, so that the weights come from HBM
         copies = 4 if M >= 4096 else 48
-        calls = [LowrankCall(fhpc, M, 4096, 512, 4096, bf, gen, recompute, forward_only) for _ in range(copies)]
         desc = "config 2: Llama-2-7B q/k/v/o projections factorised r=512, %d tokens, bf16, %s%s" % (
             M, "fwd" if forward_only else "fwd+bwd", "" if copies == 4 else ", %d independent layers per step" % copies)
         dtype = "bf16"
+        if shared_x and (tokens or forward_only or recompute or independent_x):
+            raise SystemExit("--shared-x on c2 runs the configuration's 16384 tokens, forward and backward, saved H")
+        if not (tokens or forward_only or recompute or independent_x):
+            # an attention block: q, k and v read the same X (their input gradients arrive summed), o its own input
+            calls = [SharedLowrankCall(fhpc, M, 4096, 512, 4096, 3, gen), LowrankCall(fhpc, M, 4096, 512, 4096, bf, gen)]
+            return calls, desc + ", q/k/v read one X through the shared-X call", dtype
+        calls = [LowrankCall(fhpc, M, 4096, 512, 4096, bf, gen, recompute, forward_only) for _ in range(copies)]
+        if independent_x:
+            desc += ", four independent inputs"
+        return calls, desc, dtype
     elif name == "c3":
-        calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen, shared_x)]
+        calls = [FfnCall(fhpc, 16384, 4096, 1024, 11008, gen, not independent_x)]
         desc = "config 3: Llama-2-7B SiLU-gated FFN factorised r=1024, 16384 tokens, bf16, fwd+bwd"
-        if shared_x:
-            return calls, desc + ", gate and up through the shared-X call", "bf16"
+        return calls, desc + (", gate and up as single-layer calls" if independent_x else ", gate and up through the shared-X call"), "bf16"
         dtype = "bf16"
     elif name == "c4":
         M = tokens or 4096
@@ -377,15 +392,9 @@ def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=No
         desc = "config 5: %s, int4 block-64 frozen W + rank-16 branch, %d tokens, bf16, %s" % (
             "one linear %dx%d" % shape if shape else "Llama-2-13B decoder layer, 7 linears", M, "fwd" if forward_only else "fwd+bwd")
         dtype = "bf16"
-    if shared_x and name == "c2":
-        if tokens or forward_only:
-            raise SystemExit("--shared-x on c2 runs the configuration's 16384 tokens, forward and backward")
-        calls = [SharedLowrankCall(fhpc, 16384, 4096, 512, 4096, 3, gen), calls[3]]
-        desc += ", q/k/v read one X through the shared-X call (their input gradients arrive summed)"
-        return calls, desc, dtype
     if shared_x:
         if name != "c5" or not forward_only or shape:
-            raise SystemExit("--shared-x goes with --workload c2 or c3, or with --workload c5 --forward-only")
+            raise SystemExit("--shared-x goes with --workload c5 --forward-only (c2 and c3 use their shared-X calls by default)")
         q, k, v, o, gate, up, down = calls
         calls = [SharedXCall(fhpc, [q, k, v]), o, SharedXCall(fhpc, [gate, up]), down]
         desc += ", q/k/v and gate/up through the shared-X call"
@@ -460,7 +469,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     shape = tuple(int(v) for v in args.shape.split(",")) if args.shape else None
-    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape, args.shared_x, args.premerged)
+    calls, desc, dtype = build_workload(args.workload, fhpc, args.recompute, args.tokens, args.forward_only, shape, args.shared_x, args.premerged,
+                                       args.independent_x)
     flops = sum(c.flops() for c in calls)
     io_bytes = sum(c.io_bytes() for c in calls)
 
