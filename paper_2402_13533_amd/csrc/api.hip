@@ -155,24 +155,38 @@ int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
 }
 
 // The products of the finetuning and blend layers that dequantise the frozen weight in their load path
-// (65 .. 2047 tokens) read that weight once per row of 128-wide output tiles: with few tiles the launch is
-// bound by streaming the weight through few compute units.  Its reduction is then cut into slices of at
-// least 512, as many as fit the chip at once (two workgroups of this tile per compute unit: one slice more
-// and a second, nearly empty round of workgroups costs more than the slices gain); the rank-r phase stays
-// with slice 0 and a slab sum writes the bf16 output.  Measured on a 4-bit 5120 x 5120 weight: 65 tokens
-// 76 -> 34 microseconds forward and 96 -> 49 backward, 256 tokens 86 -> 47 and 101 -> 63.
+// (65 .. 2047 tokens) read that weight once per row of output tiles: with few tiles the launch is bound by
+// streaming the weight through few compute units.  Its reduction is then cut into slices of at least 512,
+// as many as fit the chip at once (one slice more and a second, nearly empty round of workgroups costs more
+// than the slices gain); the rank-r phase stays with slice 0 and a slab sum writes the bf16 output.
+// Up to 256 tiles of 128 x 128 (two workgroups per compute unit) that tile is used; a larger output of at
+// most 128 tiles of 256 x 256 (one workgroup per compute unit) takes those.  Measured on a 4-bit
+// 5120 x 5120 weight: 65 tokens 76 -> 34 microseconds forward and 96 -> 49 backward, 256 tokens 86 -> 47 and
+// 101 -> 63, 1024 tokens (80 tiles of 256 x 256, 3 slices) 107 -> 91 and 133 -> 108.
 SplitPlan plan_fused_split(int64_t M, int64_t Nout, int64_t Kred)
 {
     SplitPlan sp;
     sp.tile = TILE_128x128;
     sp.splits = 1;
     sp.k_chunk = (int)round_up(Kred, 64);
-    const int64_t tiles = tile_count(TILE_128x128, M, Nout);
     const int64_t ksteps = (Kred + 63) / 64;
-    int64_t s = (2 * kNumCU) / tiles;
+    const int64_t small = tile_count(TILE_128x128, M, Nout), large = tile_count(TILE_256x256, M, Nout);
+    int64_t s;
+    if (small <= kNumCU) {
+        s = (2 * kNumCU) / small;
+    } else {
+        s = kNumCU / large;
+        sp.tile = TILE_256x256;
+    }
     if (s > ksteps / 8) s = ksteps / 8;
     if (s > 16) s = 16;
     if (s < 2) return sp;
+    // two slices of a short reduction on the large tile do not pay for their slabs (4096 x 4096 at 1536 and
+    // 2047 tokens: 86 against 79 and 99 against 89 microseconds unsplit); three do, and so do two of a long one
+    if (sp.tile == TILE_256x256 && s == 2 && Kred < 8192) {
+        sp.tile = TILE_128x128;
+        return sp;
+    }
     const int64_t steps_per = (ksteps + s - 1) / s;
     sp.k_chunk = (int)(steps_per * 64);
     sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
@@ -400,7 +414,7 @@ hipError_t fused_product(int b_mode, int b2_mode, GemmArgs g, void* C, int64_t M
     g.splits = sp.splits;
     g.k_chunk = sp.k_chunk;
     g.split_stride = M * Nout;
-    hipError_t e = launch_gemm_bf16(OP_KC, b_mode, b2_mode, OUT_F32, TILE_128x128, g, st);
+    hipError_t e = launch_gemm_bf16(OP_KC, b_mode, b2_mode, OUT_F32, sp.tile, g, st);
     if (e != hipSuccess) return e;
     return launch_sum_slabs(part, M * Nout, sp.splits, C, true, st);
 }

@@ -841,17 +841,13 @@ hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, i
     // blend layer with a dense bf16 frozen weight W[K][N]
     FHPC_CASE(OP_KC, OP_XC, OP_XC, OUT_BF16)            // Y  = alpha X W + (1 - alpha) H B
     FHPC_CASE(OP_KC, OP_KC, OP_KC, OUT_BF16)            // dX = alpha dY W^T + (1 - alpha) dH A^T
-    // the same four (and the dense pair) with the reduction split over workgroups: fp32 slabs, 128x128 tile only
-#define FHPC_SPLIT128(BMODE, B2)                                                                            \
-    if (a_mode == OP_KC && b_mode == BMODE && b2_mode == B2 && out_mode == OUT_F32 && tile == TILE_128x128) \
-        return launch_one<128, 128, 2, 2, OP_KC, BMODE, B2, OUT_F32, (BMODE == OP_KC || BMODE == OP_XC) ? 2 : 1, false>(args, stream);
-    FHPC_SPLIT128(OP_Q8_KC, OP_XC)
-    FHPC_SPLIT128(OP_Q4_KC, OP_XC)
-    FHPC_SPLIT128(OP_Q8_XC, OP_KC)
-    FHPC_SPLIT128(OP_Q4_XC, OP_KC)
-    FHPC_SPLIT128(OP_XC, OP_XC)
-    FHPC_SPLIT128(OP_KC, OP_KC)
-#undef FHPC_SPLIT128
+    // the same four (and the dense pair) with the reduction split over workgroups: fp32 slabs
+    FHPC_CASE(OP_KC, OP_Q8_KC, OP_XC, OUT_F32)
+    FHPC_CASE(OP_KC, OP_Q4_KC, OP_XC, OUT_F32)
+    FHPC_CASE(OP_KC, OP_Q8_XC, OP_KC, OUT_F32)
+    FHPC_CASE(OP_KC, OP_Q4_XC, OP_KC, OUT_F32)
+    FHPC_CASE(OP_KC, OP_XC, OP_XC, OUT_F32)
+    FHPC_CASE(OP_KC, OP_KC, OP_KC, OUT_F32)
     // rank-r (skinny) products of the finetuning layer
     FHPC_SKINNY(OP_KC, OP_XC, OUT_F32)                  // H  = X A      (split over K)
     FHPC_SKINNY(OP_KC, OP_KC, OUT_F32)                  // dH = dY B^T   (split over N)

@@ -176,6 +176,7 @@ def test_qlinear_shapes(scheme, M, K, r, N):
     (200, 1536, 16, 1032),    # 3 slices of 512 forward (N ragged), 2 slices backward
     (65, 2048, 8, 1160),      # the first token count past the weight-streaming kernels
     (700, 1024, 40, 1096),    # 6 x 9 tiles, 2 slices; rank above 32
+    (1100, 1536, 16, 4200),   # forward: more than 256 tiles of 128 x 128, so 5 x 17 tiles of 256 x 256 in 3 slices
 ])
 def test_qlinear_split_reduction(scheme, M, K, r, N):
     """65 .. 2047 tokens with few output tiles and a long reduction: the dequantising product is cut into
