@@ -104,7 +104,9 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
  * is a single product.  B and Y are HOST arrays of g device pointers (B_i [r][N], Y_i [M][N], bf16).
  * H_all_out ([M][g*r] bf16, H_i = X*A_i in columns i*r ..), if not NULL, receives the intermediate for
  * the backward pass.  r must be a multiple of 8 (FHPC_ERR_UNSUPPORTED otherwise); every other rule
- * of lowrank_linear_fwd applies with g*r as the rank.  Results equal g calls of lowrank_linear_fwd.
+ * of lowrank_linear_fwd applies with g*r as the rank.  Results are those of g calls of lowrank_linear_fwd up
+ * to the rounding of H (the wide product may sum its reduction in another order).  The pointer arrays are
+ * read during the call only.
  * Workspace: fhpc_workspace_bytes_lowrank_shared_x (host-only; 0 for invalid arguments). */
 #define FHPC_MAX_SHARED 8
 int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* const* B, void* const* Y, void* H_all_out,
