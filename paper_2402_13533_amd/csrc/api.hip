@@ -67,7 +67,7 @@ int64_t rank_pad(int64_t r) { return round_up(r, 8); }
 // from the big product as well (W' x = W x + s B A x, Sec. 5.1).  288 GB of HBM make room for it.
 // The forward and the backward call each merge for themselves; measured on 4096 x 4096 int8 and on a
 // 13B decoder layer in int4, a whole step is faster this way from somewhere between 1536 and 2048 tokens.
-bool many_tokens(int64_t M) { return M >= 2048; }
+bool many_tokens(int op, int64_t M, int64_t K, int64_t N);
 
 
 int64_t tile_count(int tile, int64_t M, int64_t N)
@@ -199,6 +199,39 @@ int64_t fused_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
     return sp.splits > 1 ? (int64_t)sp.splits * M * Nout * 4 : 0;
 }
 
+// How much of the chip the dequantising product M x Nout keeps busy: the share of workgroup slots its best
+// launch fills over its rounds, times the per-flop standing of that tile shape (see pick_tile).
+static double dequant_route_fill(int64_t M, int64_t Nout, int64_t Kred)
+{
+    const SplitPlan sp = plan_fused_split(M, Nout, Kred);
+    if (sp.splits > 1) {
+        const bool small = (sp.tile == TILE_128x128);
+        return (double)(tile_count(sp.tile, M, Nout) * sp.splits) / (double)((small ? 2 : 1) * kNumCU);
+    }
+    const int tiles[4] = {TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128};
+    const double standing[4] = {1.0, 0.95, 0.8, 0.67};
+    double best = 0.0;
+    for (int i = 0; i < 4; i++) {
+        const int64_t n = tile_count(tiles[i], M, Nout), slots = (i == 3 ? 2 : 1) * kNumCU;
+        const double f = (double)n / (double)(((n + slots - 1) / slots) * slots) * standing[i];
+        if (f > best) best = f;
+    }
+    return best;
+}
+
+// From 2048 tokens on the finetuning and blend layers merge the weight and run plain products (see above).
+// Between 1024 and 2047 tokens they do so when the dequantising product would leave much of the chip idle
+// for want of a tile shape that fits: 1664 tokens x 5120 channels are 280 tiles of 256 x 128, two rounds
+// with the second a tenth full (config 5's layer at 1664 tokens: 3937 microseconds per step that way,
+// 3225 merged; at 1536 tokens, 240 tiles, 2712 against 3003).
+bool many_tokens(int op, int64_t M, int64_t K, int64_t N)
+{
+    if (M >= 2048) return true;
+    if (M < 1024) return false;
+    const bool fwd = (op == FHPC_OP_QLINEAR_FWD);
+    return dequant_route_fill(M, fwd ? N : K, fwd ? K : N) < 0.7;
+}
+
 // The quantised layer's input gradient for at most 64 tokens is bound by reading the packed weight
 // once: it then comes from the weight-streaming kernel (both schemes have the same shape limits).
 bool stream_dx(int64_t M, int64_t K, int64_t r, int64_t N)
@@ -225,7 +258,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     const int64_t rp = rank_pad(r);
     const bool bwd = (op == FHPC_OP_LOWRANK_BWD || op == FHPC_OP_QLINEAR_BWD);
-    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && many_tokens(M) && !premerged) s.Wm = c.take(K * N * 2);
+    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && !premerged && many_tokens(op, M, K, N)) s.Wm = c.take(K * N * 2);
     if (rp != r) {
         s.A_p = c.take(K * rp * 2);
         s.B_p = c.take(rp * N * 2);
