@@ -149,8 +149,38 @@ bool split_pays(int64_t M, int64_t Nout, int64_t Kred)
     return plan_split(M, Nout, Kred, true).splits > 1;
 }
 
+// From 256 tokens on, an output that gives at most a quarter of the compute units a 256 x 128 tile, with a
+// reduction of 1024 or more, takes the large request-fed tiles for its slices instead (slices of at least
+// 512): one factorised layer 4096 -> 512 -> 4096 at 2048 tokens, forward 55 -> 43 microseconds and backward
+// 107 -> 96 against the 32-row tiles; at 4096 tokens, where X A is 64 tiles in 4 slices, 69 -> 56 and
+// 136 -> 125 against 128 unsplit tiles of 128 x 128.  At 8192 tokens (128 tiles) the slices and their slab
+// sum take longer than the small tiles do: 54 + 8 against 57 microseconds.
+SplitPlan plan_large_split(int64_t M, int64_t Nout, int64_t Kred)
+{
+    SplitPlan sp = plan_split(M, Nout, Kred);
+    const int64_t ksteps = (Kred + 63) / 64;
+    if (sp.k_chunk < 512) {
+        // fewer slices, each 512 deep at least
+        const int64_t s = ksteps / 8 > 0 ? ksteps / 8 : 1;
+        const int64_t steps_per = (ksteps + s - 1) / s;
+        sp.k_chunk = (int)(steps_per * 64);
+        sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
+    }
+    return sp;
+}
+
+bool large_split_pays(int64_t M, int64_t Nout, int64_t Kred)
+{
+    if (M < 256 || Nout <= 128 || Kred < 1024) return false;
+    if (4 * tile_count(TILE_256x128, M, Nout) > kNumCU) return false;
+    const SplitPlan sp = plan_large_split(M, Nout, Kred);
+    // (with fewer workgroups than half the compute units the 32-row tiles do better)
+    return sp.splits > 1 && 2 * sp.splits * tile_count(sp.tile, M, Nout) >= kNumCU;
+}
+
 int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
 {
+    if (large_split_pays(M, Nout, Kred)) return (int64_t)plan_large_split(M, Nout, Kred).splits * M * Nout * 4;
     return split_pays(M, Nout, Kred) ? split_bytes(M, Nout, Nout, Kred, true) : 0;
 }
 
@@ -379,10 +409,11 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
 // left alone: *wrote_bf16 tells the caller which happened.
 hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
                           int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st,
-                          void* bf16_out = nullptr, bool* wrote_bf16 = nullptr, bool rows32 = false)
+                          void* bf16_out = nullptr, bool* wrote_bf16 = nullptr, bool rows32 = false,
+                          const SplitPlan* plan = nullptr)
 {
     if (wrote_bf16) *wrote_bf16 = false;
-    const SplitPlan sp = plan_split(M, N, Kred, rows32);
+    const SplitPlan sp = plan ? *plan : plan_split(M, N, Kred, rows32);
     GemmArgs g = {};
     g.a = a; g.b = b; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
@@ -409,10 +440,13 @@ hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, 
 hipError_t product_bf16(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t Nout,
                         int64_t M, int64_t Kred, float* part, hipStream_t st)
 {
-    if (ldp == Nout && split_pays(M, Nout, Kred)) {
+    const bool large = large_split_pays(M, Nout, Kred);
+    if (ldp == Nout && (large || split_pays(M, Nout, Kred))) {
         bool done = false;
-        // more than one slice (split_pays), so the slab sum writes P and no fp32 output is touched
-        return gemm_split_f32(OP_KC, b_mode, a, b, nullptr, Nout, M, Nout, Kred, 1.f, part, st, P, &done, true);
+        // more than one slice (checked by both rules), so the slab sum writes P and no fp32 output is touched
+        const SplitPlan lp = large ? plan_large_split(M, Nout, Kred) : SplitPlan();
+        return gemm_split_f32(OP_KC, b_mode, a, b, nullptr, Nout, M, Nout, Kred, 1.f, part, st, P, &done, !large,
+                              large ? &lp : nullptr);
     }
     return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, Nout, Kred, st);
 }

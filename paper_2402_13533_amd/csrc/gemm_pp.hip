@@ -356,6 +356,8 @@ static hipError_t launch_pp_tile(int tile, const GemmArgs& a, hipStream_t s)
 FHPC_PP_INSTANTIATE(OP_KC, OP_XC, OUT_BF16)
 FHPC_PP_INSTANTIATE(OP_KC, OP_KC, OUT_BF16)
 FHPC_PP_INSTANTIATE(OP_XC, OP_XC, OUT_F32)
+FHPC_PP_INSTANTIATE(OP_KC, OP_XC, OUT_F32)      // H = X A, Y = H B with the reduction split (fp32 slabs)
+FHPC_PP_INSTANTIATE(OP_KC, OP_KC, OUT_F32)      // dH = dY B^T, dX = dH A^T likewise
 #undef FHPC_PP_INSTANTIATE
 
 }  // namespace pp
@@ -369,6 +371,7 @@ bool gemm_pp_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int til
     if (a_mode == OP_KC && b_mode == OP_XC && out_mode == OUT_BF16) return true;
     if (a_mode == OP_KC && b_mode == OP_KC && out_mode == OUT_BF16) return true;
     if (a_mode == OP_XC && b_mode == OP_XC && out_mode == OUT_F32) return true;
+    if (a_mode == OP_KC && (b_mode == OP_XC || b_mode == OP_KC) && out_mode == OUT_F32) return true;
     return false;
 }
 
@@ -379,6 +382,8 @@ hipError_t launch_gemm_pp(int a_mode, int b_mode, int out_mode, int tile, const 
     if (a_mode == OP_KC && b_mode == OP_XC && out_mode == OUT_BF16) return launch_pp_tile<OP_KC, OP_XC, OUT_BF16>(tile, args, stream);
     if (a_mode == OP_KC && b_mode == OP_KC && out_mode == OUT_BF16) return launch_pp_tile<OP_KC, OP_KC, OUT_BF16>(tile, args, stream);
     if (a_mode == OP_XC && b_mode == OP_XC && out_mode == OUT_F32) return launch_pp_tile<OP_XC, OP_XC, OUT_F32>(tile, args, stream);
+    if (a_mode == OP_KC && b_mode == OP_XC && out_mode == OUT_F32) return launch_pp_tile<OP_KC, OP_XC, OUT_F32>(tile, args, stream);
+    if (a_mode == OP_KC && b_mode == OP_KC && out_mode == OUT_F32) return launch_pp_tile<OP_KC, OP_KC, OUT_F32>(tile, args, stream);
     return hipErrorInvalidValue;
 }
 

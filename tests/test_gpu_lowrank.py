@@ -52,6 +52,8 @@ def test_config1_fp32():
     (64, 1032, 512, 776),    # few tokens, large rank: dA and dB as tiles of outer-product sums
     (33, 328, 77, 264),      # the same with a rank that is padded (dA rows not 16-byte aligned)
     (1, 264, 130, 520),
+    (4000, 2048, 512, 2056), # X A and dY B^T: 64 tiles of 256 x 128 (ragged last row), reductions cut into 4 slices on the large tiles
+    (1300, 8192, 520, 264),  # X A: 6 x 3 tiles of 256 x 256 in 16 slices of 512
 ])
 def test_bf16_shapes(M, K, r, N):
     fhpc = _fhpc()
