@@ -354,33 +354,22 @@ int check_common(int64_t M, int64_t K, int64_t r, int64_t N)
 // 50 %; the 128x128 kernel runs two workgroups per compute unit).  What it decides in practice: an
 // output of 320 tiles of 256x256 (4096 tokens x 5120 channels) would run two rounds, the second a
 // quarter full; as 640 tiles of 256x128 it runs 2.5 (measured 196 against 217 microseconds).
-int pick_tile(int64_t M, int64_t N, bool allow_skinny, bool partial_rounds = false)
+int pick_tile(int64_t M, int64_t N, bool allow_skinny)
 {
     if (allow_skinny && N <= 32) return TILE_256x32;
     if (allow_skinny && M <= 32) return TILE_32x256;
     const int order[4] = {TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128};
     const double penalty[4] = {1.0, 1.05, 1.25, 1.5};
-    const int per_cu[4] = {1, 1, 1, 2};
-    // only shapes that give every compute unit a tile compete; an output too small for that takes the
-    // smallest tile
     int best = TILE_128x128;
     double best_cost = -1.0;
     for (int i = 0; i < 4; i++) {
         int bm, bn;
         gemm_tile_extent(order[i], &bm, &bn);
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-        double cost;
-        if (partial_rounds) {
-            // the plain products: what the busiest compute unit has to work through, whether its tiles come one
-            // after the other or share it; a shape that leaves some units without a tile may still be the fastest
-            // (12288 x 512: 192 tiles of 256 x 128 in 75 microseconds against 384 of 128 x 128 in 85)
-            cost = (double)((tiles + kNumCU - 1) / kNumCU) * bm * bn * penalty[i];
-        } else {
-            if (tiles < kNumCU) continue;
-            const int64_t slots = (int64_t)kNumCU * per_cu[i];
-            const int64_t rounds = (tiles + slots - 1) / slots;
-            cost = (double)rounds * bm * bn * per_cu[i] * penalty[i];      // co-resident workgroups share the unit
-        }
+        // what the busiest compute unit has to work through, whether its tiles come one after the other or
+        // share it (128 x 128 runs two at a time); a shape that leaves some units without a tile may still be
+        // the fastest (12288 x 512: 192 tiles of 256 x 128 in 75 microseconds against 384 of 128 x 128 in 85)
+        const double cost = (double)((tiles + kNumCU - 1) / kNumCU) * bm * bn * penalty[i];
         if (best_cost < 0.0 || cost < best_cost) {
             best = order[i];
             best_cost = cost;
@@ -407,7 +396,7 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
     g.a = a; g.b = b; g.c = C; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
     g.alpha = alpha; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
-    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, N, false, true), g, st);
+    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, N, false), g, st);
 }
 
 // C[M,N] fp32 (ldc) = alpha * A * B with the reduction split across workgroups: every
