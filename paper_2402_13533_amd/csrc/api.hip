@@ -66,7 +66,7 @@ int64_t rank_pad(int64_t r) { return round_up(r, 8); }
 // as bf16 [K][N] costs what about 600 token rows of that product cost, and removes the rank-r branch
 // from the big product as well (W' x = W x + s B A x, Sec. 5.1).  288 GB of HBM make room for it.
 // The forward and the backward call each merge for themselves; measured on 4096 x 4096 int8 and on a
-// 13B decoder layer in int4, a whole step is faster this way from somewhere between 1536 and 2048 tokens.
+// 13B decoder layer in int4, a whole step is faster this way from about 1152 tokens on.
 bool many_tokens(int op, int64_t M, int64_t K, int64_t N);
 
 
@@ -249,14 +249,14 @@ static double dequant_route_fill(int64_t M, int64_t Nout, int64_t Kred)
     return best;
 }
 
-// From 2048 tokens on the finetuning and blend layers merge the weight and run plain products (see above).
-// Between 1024 and 2047 tokens they do so when the dequantising product would leave much of the chip idle
-// for want of a tile shape that fits: 1664 tokens x 5120 channels are 280 tiles of 256 x 128, two rounds
-// with the second a tenth full (config 5's layer at 1664 tokens: 3937 microseconds per step that way,
-// 3225 merged; at 1536 tokens, 240 tiles, 2712 against 3003).
+// From 1152 tokens on the finetuning and blend layers merge the weight and run plain products (see above):
+// config 5's layer per step at 1280 / 1536 tokens 2478 / 2620 microseconds merged against 2557 / 2708
+// dequantising, config 4's 656 against 705 at 1152; at 1024 tokens the dequantising route with its reduction
+// in slices is ahead (1944 against 2157).  Between 1024 and 1151 tokens the layers merge only when the
+// dequantising product would leave much of the chip idle for want of a tile shape that fits.
 bool many_tokens(int op, int64_t M, int64_t K, int64_t N)
 {
-    if (M >= 2048) return true;
+    if (M >= 1152) return true;
     if (M < 1024) return false;
     const bool fwd = (op == FHPC_OP_QLINEAR_FWD);
     return dequant_route_fill(M, fwd ? N : K, fwd ? K : N) < 0.7;

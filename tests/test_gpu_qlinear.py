@@ -132,12 +132,13 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
 
 @pytest.mark.parametrize("scheme", [8, 4])
 @pytest.mark.parametrize("M,K,r,N", [
-    (2048, 320, 8, 264),      # the first token count on the merged-weight route
+    (1152, 320, 8, 264),      # the first token count on the merged-weight route
+    (2048, 320, 8, 264),
     (2100, 384, 5, 520),      # ragged in every dimension, rank padded internally
     (2300, 576, 40, 136),
 ])
 def test_qlinear_many_tokens(scheme, M, K, r, N):
-    """From 2048 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
+    """From 1152 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
     products with it (forward and backward, saved and recomputed H, as above)."""
     if scheme == 4:
         K = (K + 63) // 64 * 64
@@ -162,9 +163,10 @@ def test_qlinear_many_tokens_remainder_round(scheme, M, K, r, N):
     (1, 64, 16, 72),
     (515, 1024, 5, 520),      # rank padded internally
     (260, 512, 64, 328),
+    (1151, 512, 8, 264),      # the last token count on this route
 ])
 def test_qlinear_shapes(scheme, M, K, r, N):
-    """Below 2048 tokens: the weight is dequantised in the GEMM's operand load path and the rank-r
+    """Below 1152 tokens: the weight is dequantised in the GEMM's operand load path and the rank-r
     branch rides in the same accumulators."""
     if scheme == 4:
         K = (K + 63) // 64 * 64
@@ -179,7 +181,7 @@ def test_qlinear_shapes(scheme, M, K, r, N):
     (1100, 1536, 16, 4200),   # forward: more than 256 tiles of 128 x 128, so 5 x 17 tiles of 256 x 256 in 3 slices
 ])
 def test_qlinear_split_reduction(scheme, M, K, r, N):
-    """65 .. 2047 tokens with few output tiles and a long reduction: the dequantising product is cut into
+    """65 .. 1151 tokens with few output tiles and a long reduction: the dequantising product is cut into
     slices of the reduction (fp32 slabs, the rank-r phase in slice 0, slab sum to bf16)."""
     _run_case("split q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=150)
 
@@ -442,7 +444,7 @@ def test_few_token_blend_backward():
 def test_blend_layer(scheme, alpha, M):
     """Y = alpha X deq(W) + (1 - alpha) (X A) B with W frozen, forward and backward; alpha = 1 is
     the frozen layer alone (dA = dB = 0), alpha = 0 the factorised layer alone.  Both routes (below
-    and from 2048 tokens)."""
+    and from 1152 tokens)."""
     fhpc = _fhpc()
     K, r, N = 320, 24, 264
     W, X, A, B, dY = qlinear_inputs(8, M, K, r, N, 80)
@@ -617,7 +619,7 @@ def test_qlinear_rank_one(scheme, M):
 @pytest.mark.parametrize("M", [40, 300, 2100])
 def test_premerged_weight(scheme, M):
     """The caller merges once (lowrank_merge, bf16) and passes the result to forward and backward with
-    qscheme FHPC_W_MERGED: outputs against the oracle's layer; from 2048 tokens on they are the very bits
+    qscheme FHPC_W_MERGED: outputs against the oracle's layer; from 1152 tokens on they are the very bits
     of the calls that merge by themselves (same merge kernel, same products)."""
     import torch
     fhpc = _fhpc()
@@ -635,7 +637,7 @@ def test_premerged_weight(scheme, M):
     for name, g, rf in zip(("Y", "H", "dX", "dA", "dB"), (Y, H, dX, dA, dB), (Yr, Hr) + ref):
         e = oracle.rel_fro(from_device(g), rf)
         assert e <= TOL_BF16, (name, e)
-    if M >= 2048:
+    if M >= 1152:
         Y2, H2 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)
         dX2, dA2, dB2 = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H2)
         for a, b in zip((Y, H, dX, dA, dB), (Y2, H2, dX2, dA2, dB2)):

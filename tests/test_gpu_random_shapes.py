@@ -1,5 +1,5 @@
 """Seeded random shapes through every layer entry point, each output against the oracle: token counts on
-both sides of every routing threshold (16, 32, 64, 2048), reductions and widths that are not tile
+both sides of every routing threshold (16, 32, 64, 1152), reductions and widths that are not tile
 multiples, ranks from 1 to beyond a tile, saved and recomputed H, all weight storages, blend factors at
 the end points and inside."""
 import numpy as np
@@ -10,7 +10,7 @@ from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device
 
 pytestmark = pytest.mark.gpu
 
-TOKENS = [1, 2, 7, 16, 17, 33, 64, 65, 100, 255, 256, 300, 777, 1024, 2047, 2048, 2500]
+TOKENS = [1, 2, 7, 16, 17, 33, 64, 65, 100, 255, 256, 300, 777, 1024, 1151, 1152, 2048, 2500]
 RANKS = [1, 2, 5, 8, 16, 24, 40, 64, 72, 100, 136]
 KINDS = ["lowrank", "q8", "q4", "blend8", "blend4", "dense"]
 
