@@ -185,7 +185,7 @@ int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
 }
 
 // The products of the finetuning and blend layers that dequantise the frozen weight in their load path
-// (65 .. 2047 tokens) read that weight once per row of output tiles: with few tiles the launch is bound by
+// (65 .. 1151 tokens) read that weight once per row of output tiles: with few tiles the launch is bound by
 // streaming the weight through few compute units.  Its reduction is then cut into slices of at least 512,
 // as many as fit the chip at once (one slice more and a second, nearly empty round of workgroups costs more
 // than the slices gain); the rank-r phase stays with slice 0 and a slab sum writes the bf16 output.
