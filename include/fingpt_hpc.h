@@ -173,7 +173,9 @@ size_t fhpc_workspace_bytes_shared_x(const int64_t* N, int count, int64_t M, int
  *   Y = alpha * X * deq(Wq, scales) + (1 - alpha) * (X * A) * B
  * Arguments, layouts, workspace (FHPC_OP_QLINEAR_FWD / _BWD sizes) and error behaviour are those of
  * qlinear_lowrank_fwd / _bwd with `alpha` in place of `scaling`; alpha outside [0, 1] (or NaN)
- * returns FHPC_ERR_SHAPE.  alpha = 0 runs the factorised layer alone and never reads Wq.
+ * returns FHPC_ERR_SHAPE.  alpha = 0 gives the factorised layer alone; with more than 64 tokens Wq is then
+ * never read, with at most 64 the forward still streams Wq and its scales and multiplies them by 0, so the
+ * scales must be finite there.
  * qscheme may also be FHPC_W_BF16: the pretrained weight kept in bf16, W[K,N] row-major. */
 int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
                       const void* A, const void* B, float alpha, void* Y, void* H_out,
@@ -263,8 +265,9 @@ const char* fhpc_status_string(int status);
  * slice s of the reduction then stores its partial sums to C + s*M*ldc, so C must hold
  * `splits` slabs of M*ldc floats and the caller adds them).  tile: 0 = 256x256,
  * 1 = 128x256, 2 = 256x128, 3 = 128x128, 4 = 256x32, 5 = 32x256 (the last two with out_mode 1
- * only).  splits cuts the reduction into that many slices.  dbg must be 0 (bit 0 suppresses
- * operand traffic, bit 1 the matrix instructions; results are then meaningless).
+ * only).  splits cuts the reduction into that many slices.  dbg chooses among the kernels that
+ * cover a tile, for their parity tests: 0 = the one the entry points use, 4 = the register-staged
+ * lockstep kernel, 8 = the four-wave kernel (256x256 only); other bits are ignored.
  * Returns FHPC_ERR_UNSUPPORTED for a combination that is not instantiated. */
 int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_t ldb, int b_mode,
                    void* C, int64_t ldc, int out_mode, int64_t M, int64_t N, int64_t K, float alpha,
@@ -281,6 +284,19 @@ int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_
 int fhpc_profile_start(int max_records);
 int fhpc_profile_stop(void);
 int fhpc_profile_get(int index, char* name, int name_len, float* ms, double* flops, double* bytes);
+
+/* Host-only test hook (needs no GPU, touches no memory): walks the launch sequence of an entry point for
+ * these sizes without launching anything and reports, in bytes, the largest partial-sum area any of its
+ * split reductions would use (*planned) and what the workspace layout reserves for them (*reserved).
+ * The calls themselves refuse, with FHPC_ERR_WORKSPACE, a launch whose slabs would not fit; this hook lets
+ * a test show on the CPU that planned <= reserved over a grid of shapes.
+ * call: FHPC_OP_LOWRANK_FWD .. FHPC_OP_QLINEAR_BWD, FHPC_OP_DECOMPOSE, FHPC_PLAN_SHARED_FWD / _BWD (the
+ * shared-X calls of the factorised layer, g layers).  outputs: bit 0 = dX wanted (forward calls: H_out given),
+ * bit 1 = dA, bit 2 = dB, bit 3 = H_saved given.  base_scale: 1 for the finetuning layer, alpha for the blend
+ * layer.  dtype, qscheme, g are ignored where the call has no such argument.  Returns a status code. */
+enum { FHPC_PLAN_SHARED_FWD = 16, FHPC_PLAN_SHARED_BWD = 17 };
+int fhpc_plan_slab_bytes(int call, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme, int g,
+                         int outputs, float base_scale, int64_t* planned, int64_t* reserved);
 
 /* Library version (major * 100 + minor). */
 int fhpc_version(void);

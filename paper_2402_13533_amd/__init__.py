@@ -19,13 +19,14 @@ FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
 FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N] in place of Wq, scales None
 FHPC_W_MERGED = 17        # qlinear_lowrank_fwd/bwd only: Wq is the bf16 [K,N] weight lowrank_merge wrote for the same A, B, scaling
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE, FHPC_OP_DECOMPOSE = 0, 1, 2, 3, 4, 5
+FHPC_PLAN_SHARED_FWD, FHPC_PLAN_SHARED_BWD = 16, 17
 
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose", "qlinear_lowrank_fwd_shared_x", "fhpc_workspace_bytes_shared_x",
     "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
-    "fhpc_status_string", "fhpc_version",
+    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes",
 ]
 
 _lib = None
@@ -84,6 +85,7 @@ def load_library():
     lib.fhpc_profile_stop.argtypes = []
     lib.fhpc_profile_get.argtypes = [i32, C.c_char_p, i32, C.POINTER(C.c_float), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
+    lib.fhpc_plan_slab_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32, i32, i32, f32, C.POINTER(i64), C.POINTER(i64)]
     lib.fhpc_status_string.argtypes = [i32]
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
@@ -122,6 +124,15 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(load_library().fhpc_version())
+
+
+def plan_slab_bytes(call: int, M: int, K: int, r: int, N: int, dtype: int = FHPC_BF16, qscheme: int = 0, g: int = 1,
+                    outputs: int = 7, base_scale: float = 1.0):
+    """Host-only test hook: (status, planned, reserved) partial-sum bytes of an entry point's launch sequence."""
+    planned, reserved = C.c_int64(0), C.c_int64(0)
+    rc = load_library().fhpc_plan_slab_bytes(call, M, K, r, N, dtype, qscheme, g, outputs, C_float(base_scale),
+                                             C.byref(planned), C.byref(reserved))
+    return int(rc), int(planned.value), int(reserved.value)
 
 
 def workspace_bytes(op: int, M: int, K: int, r: int, N: int, dtype: int = FHPC_BF16, qscheme: int = 0) -> int:
@@ -167,9 +178,10 @@ _workspaces = {}
 
 
 def get_workspace(nbytes: int, device):
-    """A cached per-device byte tensor of at least nbytes (grown on demand)."""
+    """A cached byte tensor of at least nbytes (grown on demand), one per device and stream: calls that share a
+    workspace must be ordered on one stream."""
     torch = _torch()
-    key = str(device)
+    key = (str(device), int(torch.cuda.current_stream(device).cuda_stream))
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

@@ -12,17 +12,42 @@ using namespace fhpc;
 namespace {
 
 constexpr int64_t kMaxBytes = (int64_t)1 << 31;   // per-matrix limit of the 32-bit buffer offsets
-constexpr int kNumCU = 256;
+// compute units of the current device: every plan below is sized for it
+inline int num_cu() { return compute_units(); }
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-#define FHPC_HIP(expr)                                   \
-    do {                                                 \
-        if ((expr) != hipSuccess) {                      \
-            (void)hipGetLastError();                     \
-            return FHPC_ERR_HIP;                         \
-        }                                                \
+// (hipErrorOutOfMemory is what the launch helpers below return when a split reduction asks for more
+// partial-sum slabs than the workspace reserves: reported as a workspace error, nothing was launched for it)
+#define FHPC_HIP(expr)                                                               \
+    do {                                                                             \
+        const hipError_t fhpc_e_ = (expr);                                           \
+        if (fhpc_e_ != hipSuccess) {                                                 \
+            (void)hipGetLastError();                                                 \
+            return fhpc_e_ == hipErrorOutOfMemory ? FHPC_ERR_WORKSPACE : FHPC_ERR_HIP; \
+        }                                                                            \
+    } while (0)
+
+// One pass over an entry point's launch sequence: the real one (launch on `st`; a split reduction whose
+// slabs would not fit behind Scratch::part fails instead of writing past it) or a dry one (launch
+// nothing, record the largest slab area any launch of the sequence asks for).
+struct Run {
+    hipStream_t st = nullptr;
+    bool dry = false;
+    int64_t part_cap = 0;        // bytes reserved for partial-sum slabs
+    int64_t part_need = 0;       // dry pass: the most any launch asked for
+    // true when `bytes` of slabs may be used (always in a dry pass, which only records)
+    bool claim(int64_t bytes)
+    {
+        if (bytes > part_need) part_need = bytes;
+        return dry || bytes <= part_cap;
+    }
+};
+// a launch that uses no slabs: skipped in a dry pass
+#define FHPC_LAUNCH(run, expr)                \
+    do {                                      \
+        if (!(run).dry) FHPC_HIP(expr);       \
     } while (0)
 
 // Workspace carving: a bump allocator over the caller's buffer (or a dry run that
@@ -30,10 +55,12 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 struct Carver {
     unsigned char* base;
     size_t used = 0;
-    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    // a measuring pass (p == NULL) hands out addresses from a fake base: never dereferenced, but non-null, so
+    // that code which asks "was this region carved" takes the same route as the real pass
+    explicit Carver(void* p) : base(p ? static_cast<unsigned char*>(p) : reinterpret_cast<unsigned char*>((uintptr_t)1 << 20)) {}
     void* take(int64_t bytes)
     {
-        void* p = base ? base + used : nullptr;
+        void* p = bytes > 0 ? base + used : nullptr;
         used += (size_t)round_up(bytes > 0 ? bytes : 0, 256);
         return p;
     }
@@ -50,6 +77,7 @@ struct Scratch {
     float* dA_t = nullptr;  // fp32 [K][rp]
     float* dB_t = nullptr;  // fp32 [rp][N]
     float* part = nullptr;  // fp32 partial sums of a split reduction, one slab per split
+    int64_t part_bytes = 0; // what is reserved behind `part`
     void* Wm = nullptr;     // bf16 [K][N]    base_scale * deq(W) + scaling * A B, many tokens (see many_tokens)
     float* sk_part = nullptr;   // weight-streaming forward (few tokens): slabs of M x N
     float* sk_hpart = nullptr;  //                                        partial sums of X A
@@ -94,7 +122,7 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
     // too, but their products are bound by streaming the long operand, and one workgroup per compute
     // unit with twice the depth measured faster than two (4096 x 5120 -> 16: 11.4 against 14.8 microseconds)
     // and leaves half as many slabs to add.
-    const int64_t target = (sp.tile == TILE_128x128) ? 2 * kNumCU : kNumCU;
+    const int64_t target = (sp.tile == TILE_128x128) ? 2 * num_cu() : num_cu();
     int64_t s = (target + tiles - 1) / tiles;
     if (s > ksteps) s = ksteps;
     if (s > 64) s = 64;
@@ -144,7 +172,7 @@ bool split_pays(int64_t M, int64_t Nout, int64_t Kred)
     if (Nout <= 32) return false;
     if (M > 32) {
         const int64_t tiles = ((M + 127) / 128) * ((Nout + 127) / 128);
-        if (2 * tiles > kNumCU || Kred < 256) return false;
+        if (2 * tiles > num_cu() || Kred < 256) return false;
     }
     return plan_split(M, Nout, Kred, true).splits > 1;
 }
@@ -172,10 +200,10 @@ SplitPlan plan_large_split(int64_t M, int64_t Nout, int64_t Kred)
 bool large_split_pays(int64_t M, int64_t Nout, int64_t Kred)
 {
     if (M < 256 || Nout <= 128 || Kred < 1024) return false;
-    if (4 * tile_count(TILE_256x128, M, Nout) > kNumCU) return false;
+    if (4 * tile_count(TILE_256x128, M, Nout) > num_cu()) return false;
     const SplitPlan sp = plan_large_split(M, Nout, Kred);
     // (with fewer workgroups than half the compute units the 32-row tiles do better)
-    return sp.splits > 1 && 2 * sp.splits * tile_count(sp.tile, M, Nout) >= kNumCU;
+    return sp.splits > 1 && 2 * sp.splits * tile_count(sp.tile, M, Nout) >= num_cu();
 }
 
 int64_t product_part_bytes(int64_t M, int64_t Nout, int64_t Kred)
@@ -202,10 +230,10 @@ SplitPlan plan_fused_split(int64_t M, int64_t Nout, int64_t Kred)
     const int64_t ksteps = (Kred + 63) / 64;
     const int64_t small = tile_count(TILE_128x128, M, Nout), large = tile_count(TILE_256x256, M, Nout);
     int64_t s;
-    if (small <= kNumCU) {
-        s = (2 * kNumCU) / small;
+    if (small <= num_cu()) {
+        s = (2 * num_cu()) / small;
     } else {
-        s = kNumCU / large;
+        s = num_cu() / large;
         sp.tile = TILE_256x256;
     }
     if (s > ksteps / 8) s = ksteps / 8;
@@ -236,13 +264,13 @@ static double dequant_route_fill(int64_t M, int64_t Nout, int64_t Kred)
     const SplitPlan sp = plan_fused_split(M, Nout, Kred);
     if (sp.splits > 1) {
         const bool small = (sp.tile == TILE_128x128);
-        return (double)(tile_count(sp.tile, M, Nout) * sp.splits) / (double)((small ? 2 : 1) * kNumCU);
+        return (double)(tile_count(sp.tile, M, Nout) * sp.splits) / (double)((small ? 2 : 1) * num_cu());
     }
     const int tiles[4] = {TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128};
     const double standing[4] = {1.0, 0.95, 0.8, 0.67};
     double best = 0.0;
     for (int i = 0; i < 4; i++) {
-        const int64_t n = tile_count(tiles[i], M, Nout), slots = (i == 3 ? 2 : 1) * kNumCU;
+        const int64_t n = tile_count(tiles[i], M, Nout), slots = (i == 3 ? 2 : 1) * num_cu();
         const double f = (double)n / (double)(((n + slots - 1) / slots) * slots) * standing[i];
         if (f > best) best = f;
     }
@@ -281,7 +309,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     if (op == FHPC_OP_QLINEAR_FWD && quantised && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
         // a handful of tokens: the weight-streaming kernels need only their own slabs
-        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, kNumCU);
+        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
         s.sk_part = static_cast<float*>(c.take(p.part_bytes));
         s.sk_hpart = static_cast<float*>(c.take(p.hpart_bytes));
         return s;
@@ -302,12 +330,12 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     if (op == FHPC_OP_QLINEAR_BWD && quantised && stream_dx(M, K, r, N)) {
         // a handful of tokens: dX comes from the weight-streaming kernel (sized for either scheme)
-        const int64_t b4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, kNumCU).part_bytes;
-        const int64_t b8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, kNumCU).part_bytes;
+        const int64_t b4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, num_cu()).part_bytes;
+        const int64_t b8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, num_cu()).part_bytes;
         s.sk_dxpart = static_cast<float*>(c.take(b4 > b8 ? b4 : b8));
         if (rp <= 16) {       // dH = dY B^T is then formed by the same launch, one partial sum per slice
-            const int s4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, kNumCU).slices;
-            const int s8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, kNumCU).slices;
+            const int s4 = qskinny_dx_plan(M, K, N, FHPC_Q_INT4_BLOCK, num_cu()).slices;
+            const int s8 = qskinny_dx_plan(M, K, N, FHPC_Q_INT8_PER_CHANNEL, num_cu()).slices;
             s.sk_dhpart = static_cast<float*>(c.take((int64_t)(s4 > s8 ? s4 : s8) * M * rp * 4));
         }
     }
@@ -330,6 +358,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
         upto(split_bytes(rp, N, N, M));                // dB = H^T dY
     }
     s.part = static_cast<float*>(c.take(part));
+    s.part_bytes = part;
     return s;
 }
 
@@ -369,7 +398,7 @@ int pick_tile(int64_t M, int64_t N, bool allow_skinny)
         // what the busiest compute unit has to work through, whether its tiles come one after the other or
         // share it (128 x 128 runs two at a time); a shape that leaves some units without a tile may still be
         // the fastest (12288 x 512: 192 tiles of 256 x 128 in 75 microseconds against 384 of 128 x 128 in 85)
-        const double cost = (double)((tiles + kNumCU - 1) / kNumCU) * bm * bn * penalty[i];
+        const double cost = (double)((tiles + num_cu() - 1) / num_cu()) * bm * bn * penalty[i];
         if (best_cost < 0.0 || cost < best_cost) {
             best = order[i];
             best_cost = cost;
@@ -390,8 +419,10 @@ GemmOperand operand(const void* p, int64_t ld, const void* scales = nullptr, int
 
 // C[M,N] bf16 = A(KC or via a_mode) * B, whole reduction in one workgroup per tile.
 hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void* C, int64_t ldc,
-                      int64_t M, int64_t N, int64_t Kred, hipStream_t st, float alpha = 1.f)
+                      int64_t M, int64_t N, int64_t Kred, Run& run, float alpha = 1.f)
 {
+    if (run.dry) return hipSuccess;
+    hipStream_t st = run.st;
     GemmArgs g = {};
     g.a = a; g.b = b; g.c = C; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
@@ -405,12 +436,18 @@ hipError_t gemm_plain(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void
 // With `bf16_out` (dense, ldc == N) and more than one slice, the slab sum writes bf16 there and C is
 // left alone: *wrote_bf16 tells the caller which happened.
 hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, float* C, int64_t ldc,
-                          int64_t M, int64_t N, int64_t Kred, float alpha, float* part, hipStream_t st,
+                          int64_t M, int64_t N, int64_t Kred, float alpha, float* part, Run& run,
                           void* bf16_out = nullptr, bool* wrote_bf16 = nullptr, bool rows32 = false,
                           const SplitPlan* plan = nullptr)
 {
     if (wrote_bf16) *wrote_bf16 = false;
     const SplitPlan sp = plan ? *plan : plan_split(M, N, Kred, rows32);
+    if (!run.claim(sp.splits > 1 ? (int64_t)sp.splits * M * ldc * 4 : 0)) return hipErrorOutOfMemory;
+    if (run.dry) {
+        if (wrote_bf16) *wrote_bf16 = (sp.splits > 1 && bf16_out);
+        return hipSuccess;
+    }
+    hipStream_t st = run.st;
     GemmArgs g = {};
     g.a = a; g.b = b; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)Kred; g.K2 = 0;
@@ -435,38 +472,41 @@ hipError_t gemm_split_f32(int a_mode, int b_mode, GemmOperand a, GemmOperand b, 
 // P[M][Nout] (bf16, row stride ldp) = L * R, L with k contiguous: the plain launch, or the split reduction on
 // 32-row tiles when that pays (split_pays) and P is dense.
 hipError_t product_bf16(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t Nout,
-                        int64_t M, int64_t Kred, float* part, hipStream_t st)
+                        int64_t M, int64_t Kred, float* part, Run& run)
 {
     const bool large = large_split_pays(M, Nout, Kred);
     if (ldp == Nout && (large || split_pays(M, Nout, Kred))) {
         bool done = false;
         // more than one slice (checked by both rules), so the slab sum writes P and no fp32 output is touched
         const SplitPlan lp = large ? plan_large_split(M, Nout, Kred) : SplitPlan();
-        return gemm_split_f32(OP_KC, b_mode, a, b, nullptr, Nout, M, Nout, Kred, 1.f, part, st, P, &done, !large,
+        return gemm_split_f32(OP_KC, b_mode, a, b, nullptr, Nout, M, Nout, Kred, 1.f, part, run, P, &done, !large,
                               large ? &lp : nullptr);
     }
-    return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, Nout, Kred, st);
+    return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, Nout, Kred, run);
 }
 
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
 // split the long reduction, accumulate in fp32, then round once to bf16.
 hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf, float* part,
-                        int64_t M, int64_t Kred, hipStream_t st)
+                        int64_t M, int64_t Kred, Run& run)
 {
     if (rp <= 32) {
         bool done = false;
-        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, st, P, &done);
-        if (e != hipSuccess || done) return e;
-        return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, st);
+        hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, run, P, &done);
+        if (e != hipSuccess || done || run.dry) return e;
+        return launch_compact_f32(Pf, rp, P, rp, M, rp, 1.f, true, run.st);
     }
-    return product_bf16(b_mode, a, b, P, rp, rp, M, Kred, part, st);
+    return product_bf16(b_mode, a, b, P, rp, rp, M, Kred, part, run);
 }
 
 // C[M][Nout] (bf16, dense) = g.alpha * (g.mid_scale * A2 B2 + A deq(B)): whole, or split over the reduction
 hipError_t fused_product(int b_mode, int b2_mode, GemmArgs g, void* C, int64_t M, int64_t Nout, int64_t Kred,
-                         float* part, hipStream_t st)
+                         float* part, Run& run)
 {
     const SplitPlan sp = plan_fused_split(M, Nout, Kred);
+    if (!run.claim(sp.splits > 1 ? (int64_t)sp.splits * M * Nout * 4 : 0)) return hipErrorOutOfMemory;
+    if (run.dry) return hipSuccess;
+    hipStream_t st = run.st;
     g.ldc = Nout;
     if (sp.splits == 1) {
         g.c = C;
@@ -490,15 +530,15 @@ struct Factors {
 
 // Zero-padded copies of A and B when the rank is not a multiple of 8.
 int prepare_factors(const void* A, const void* B, int64_t K, int64_t r, int64_t rp, int64_t N,
-                    const Scratch& s, hipStream_t st, Factors* f)
+                    const Scratch& s, Run& run, Factors* f)
 {
     if (rp == r) {
         f->A = A;
         f->B = B;
         return FHPC_OK;
     }
-    FHPC_HIP(launch_pad2d_u16(A, r, K, r, s.A_p, rp, K, st));
-    FHPC_HIP(launch_pad2d_u16(B, N, r, N, s.B_p, N, rp, st));
+    FHPC_LAUNCH(run, launch_pad2d_u16(A, r, K, r, s.A_p, rp, K, run.st));
+    FHPC_LAUNCH(run, launch_pad2d_u16(B, N, r, N, s.B_p, N, rp, run.st));
     f->A = s.A_p;
     f->B = s.B_p;
     return FHPC_OK;
@@ -507,23 +547,24 @@ int prepare_factors(const void* A, const void* B, int64_t K, int64_t r, int64_t 
 // dA[K][r] = alpha X^T dH and dB[r][N] = alpha H^T dY, both reductions over the M tokens.
 int weight_grads(const void* X, const void* dY, const void* H, const void* dH, float* dA, float* dB,
                  int64_t M, int64_t K, int64_t r, int64_t rp, int64_t N, float alpha,
-                 const Scratch& s, hipStream_t st)
+                 const Scratch& s, Run& run)
 {
+    hipStream_t st = run.st;
     // a handful of tokens: M-deep sums, both products in one launch of the vector-ALU kernel, until the sums
     // over the tokens outweigh writing the outputs once
     if ((dA || dB) && token_outer_supports(M) && (M <= 32 || rp * (K + N) <= ((int64_t)8 << 20))) {
-        FHPC_HIP(launch_token_outer_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
+        FHPC_LAUNCH(run, launch_token_outer_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
         return FHPC_OK;
     }
     if (dA) {
         float* dst = (rp == r) ? dA : s.dA_t;
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, s.part, st));
-        if (rp != r) FHPC_HIP(launch_compact_f32(s.dA_t, rp, dA, r, K, r, 1.f, false, st));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(dH, rp), dst, rp, K, rp, M, alpha, s.part, run));
+        if (rp != r) FHPC_LAUNCH(run, launch_compact_f32(s.dA_t, rp, dA, r, K, r, 1.f, false, st));
     }
     if (dB) {
         float* dst = (rp == r) ? dB : s.dB_t;
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(H, rp), operand(dY, N), dst, N, rp, N, M, alpha, s.part, st));
-        if (rp != r) FHPC_HIP(launch_compact_f32(s.dB_t, N, dB, N, r, N, 1.f, false, st));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(H, rp), operand(dY, N), dst, N, rp, N, M, alpha, s.part, run));
+        if (rp != r) FHPC_LAUNCH(run, launch_compact_f32(s.dB_t, N, dB, N, r, N, 1.f, false, st));
     }
     return FHPC_OK;
 }
@@ -541,8 +582,10 @@ int check_workspace(int op, void* ws, size_t ws_bytes, int64_t M, int64_t K, int
 
 // ---------------- fp32 path of the factorised layer ----------------
 int lowrank_fwd_f32(const float* X, const float* A, const float* B, float* Y, float* H_out,
-                    int64_t M, int64_t K, int64_t r, int64_t N, const Scratch& s, hipStream_t st)
+                    int64_t M, int64_t K, int64_t r, int64_t N, const Scratch& s, Run& run)
 {
+    if (run.dry) return FHPC_OK;
+    hipStream_t st = run.st;
     float* H = H_out ? H_out : static_cast<float*>(s.H);
     FHPC_HIP(launch_gemm_f32(X, K, 1, A, r, 1, H, r, (int)M, (int)r, (int)K, 1.f, st));
     FHPC_HIP(launch_gemm_f32(H, r, 1, B, N, 1, Y, N, (int)M, (int)N, (int)r, 1.f, st));
@@ -551,8 +594,10 @@ int lowrank_fwd_f32(const float* X, const float* A, const float* B, float* Y, fl
 
 int lowrank_bwd_f32(const float* X, const float* A, const float* B, const float* dY, const float* H_saved,
                     float* dX, float* dA, float* dB, int64_t M, int64_t K, int64_t r, int64_t N,
-                    const Scratch& s, hipStream_t st)
+                    const Scratch& s, Run& run)
 {
+    if (run.dry) return FHPC_OK;
+    hipStream_t st = run.st;
     const float* H = H_saved;
     if (!H && dB) {
         float* Hw = static_cast<float*>(s.H);
@@ -594,6 +639,7 @@ struct DecompScratch {
     void* Tb;      // bf16 [r][N]
     void* Cb;      // bf16 [r][N]
     float* part;   // partial-sum slabs of the split reductions
+    int64_t part_bytes;
 };
 
 DecompScratch carve_decompose(Carver& c, int64_t K, int64_t r, int64_t N)
@@ -612,21 +658,26 @@ DecompScratch carve_decompose(Carver& c, int64_t K, int64_t r, int64_t N)
     d.T = static_cast<float*>(c.take(r * N * 4));
     d.Tb = c.take(r * N * 2);
     d.Cb = c.take(r * N * 2);
-    int64_t part = split_bytes(r, r, r, R);            // Gram matrices
+    // Gram matrices over K (of Y, of A) and over N (of Z): the slice count is not monotone in the reduction
+    // length, so each is sized for itself
+    int64_t part = split_bytes(r, r, r, K);
+    const int64_t p1 = split_bytes(r, r, r, N);
     const int64_t p2 = split_bytes(N, r, r, K);        // Z = W^T Y
     const int64_t p3 = split_bytes(r, N, N, K);        // T = A^T W
+    if (p1 > part) part = p1;
     if (p2 > part) part = p2;
     if (p3 > part) part = p3;
     d.part = static_cast<float*>(c.take(part));
+    d.part_bytes = part;
     return d;
 }
 
 // P[M][n] (bf16, dense) = sum_k a(m,k) b(j,k) with both operands stored reduction-major
-int product_tn_bf16(GemmOperand a, GemmOperand b, void* P, int64_t M, int64_t n, int64_t Kred, const DecompScratch& d, hipStream_t st)
+int product_tn_bf16(GemmOperand a, GemmOperand b, void* P, int64_t M, int64_t n, int64_t Kred, const DecompScratch& d, Run& run)
 {
     bool done = false;
-    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, b, d.F, n, M, n, Kred, 1.f, d.part, st, P, &done));
-    if (!done) FHPC_HIP(launch_compact_f32(d.F, n, P, n, M, n, 1.f, true, st));
+    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, b, d.F, n, M, n, Kred, 1.f, d.part, run, P, &done));
+    if (!done) FHPC_LAUNCH(run, launch_compact_f32(d.F, n, P, n, M, n, 1.f, true, run.st));
     return FHPC_OK;
 }
 
@@ -646,8 +697,9 @@ hipError_t small_mm(const float* A, bool transpose_a, const float* B, float* C, 
 // [0.7, 1.15] instead of converging), then `cubic` steps (1.5, -0.5) converge to 1 quadratically from
 // there.  The first step divides by the Frobenius norm (trace of G0) so that no singular value starts
 // above 1.
-int orthonormalise(const void* Y, void* out, int64_t R, int64_t r, int quintic, int cubic, const DecompScratch& d, hipStream_t st)
+int orthonormalise(const void* Y, void* out, int64_t R, int64_t r, int quintic, int cubic, const DecompScratch& d, Run& run)
 {
+    hipStream_t st = run.st;
     float* const G0 = d.G;
     float* M = d.Mf[0];
     float* Mn = d.Mf[1];
@@ -655,31 +707,31 @@ int orthonormalise(const void* Y, void* out, int64_t R, int64_t r, int quintic, 
     float* const Gi = d.Mf[3];
     float* const G2 = d.Mf[4];
     float* const S = d.Mf[5];
-    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(Y, r), operand(Y, r), G0, r, r, r, R, 1.f, d.part, st));
+    FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(Y, r), operand(Y, r), G0, r, r, r, R, 1.f, d.part, run));
     for (int i = 0; i < quintic + cubic; i++) {
         const bool first = (i == 0), q5 = (i < quintic);
         const float* g = G0;
         if (!first) {
-            FHPC_HIP(small_mm(G0, false, M, P, r, st));            // P = G0 M
-            FHPC_HIP(small_mm(M, true, P, Gi, r, st));             // Gi = M^T G0 M
+            FHPC_LAUNCH(run, small_mm(G0, false, M, P, r, st));            // P = G0 M
+            FHPC_LAUNCH(run, small_mm(M, true, P, Gi, r, st));             // Gi = M^T G0 M
             g = Gi;
         }
         float* dst = first ? M : S;                                 // the first step's polynomial is M itself
         if (q5) {
             // the first step works on G0 / trace: Gi = that, G2 its square
-            if (first) FHPC_HIP(launch_gram_poly(G0, nullptr, Gi, false, r, 0.f, 1.f, 0.f, 1, st));
-            FHPC_HIP(small_mm(first ? Gi : g, false, first ? Gi : g, G2, r, st));
-            FHPC_HIP(launch_gram_poly(g, G2, dst, false, r, 3.4445f, -4.7750f, 2.0315f, first ? 2 : 0, st));
+            if (first) FHPC_LAUNCH(run, launch_gram_poly(G0, nullptr, Gi, false, r, 0.f, 1.f, 0.f, 1, st));
+            FHPC_LAUNCH(run, small_mm(first ? Gi : g, false, first ? Gi : g, G2, r, st));
+            FHPC_LAUNCH(run, launch_gram_poly(g, G2, dst, false, r, 3.4445f, -4.7750f, 2.0315f, first ? 2 : 0, st));
         } else {
-            FHPC_HIP(launch_gram_poly(g, nullptr, dst, false, r, 1.5f, -0.5f, 0.f, first ? 2 : 0, st));
+            FHPC_LAUNCH(run, launch_gram_poly(g, nullptr, dst, false, r, 1.5f, -0.5f, 0.f, first ? 2 : 0, st));
         }
         if (!first) {
-            FHPC_HIP(small_mm(M, false, S, Mn, r, st));            // M <- M S
+            FHPC_LAUNCH(run, small_mm(M, false, S, Mn, r, st));            // M <- M S
             float* t = M; M = Mn; Mn = t;
         }
     }
-    FHPC_HIP(launch_compact_f32(M, r, d.Sb, r, r, r, 1.f, true, st));
-    FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(Y, r), operand(d.Sb, r), out, r, R, r, r, st));
+    FHPC_LAUNCH(run, launch_compact_f32(M, r, d.Sb, r, r, r, 1.f, true, st));
+    FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(Y, r), operand(d.Sb, r), out, r, R, r, r, run));
     return FHPC_OK;
 }
 
@@ -691,6 +743,55 @@ int check_q(int qscheme, int block, int64_t K)
         if (K % 64) return FHPC_ERR_SHAPE;
     }
     return FHPC_OK;
+}
+
+// ---------------- launch sequences of the entry points ----------------
+// Each takes validated arguments and the carved scratch, and is walked either for real or dry (see Run).
+
+int seq_lowrank_fwd(Run& run, const Scratch& s, const void* X, const void* A, const void* B, void* Y, void* H_out,
+                    int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+{
+    if (dtype == FHPC_F32)
+        return lowrank_fwd_f32((const float*)X, (const float*)A, (const float*)B, (float*)Y, (float*)H_out, M, K, r, N, s, run);
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    int rc = prepare_factors(A, B, K, r, rp, N, s, run, &f);
+    if (rc) return rc;
+    void* H = (H_out && rp == r) ? H_out : s.H;
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, run));
+    FHPC_HIP(product_bf16(OP_XC, operand(H, rp), operand(f.B, N), Y, N, N, M, rp, s.part, run));
+    if (H_out && rp != r) FHPC_LAUNCH(run, launch_pad2d_u16(H, rp, M, r, H_out, r, M, run.st));
+    return FHPC_OK;
+}
+
+int seq_lowrank_bwd(Run& run, const Scratch& s, const void* X, const void* A, const void* B, const void* dY,
+                    const void* H_saved, void* dX, float* dA, float* dB,
+                    int64_t M, int64_t K, int64_t r, int64_t N, int dtype)
+{
+    if (dtype == FHPC_F32)
+        return lowrank_bwd_f32((const float*)X, (const float*)A, (const float*)B, (const float*)dY,
+                               (const float*)H_saved, (float*)dX, dA, dB, M, K, r, N, s, run);
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    int rc = prepare_factors(A, B, K, r, rp, N, s, run, &f);
+    if (rc) return rc;
+    const void* H = nullptr;
+    if (dB) {
+        if (H_saved && rp == r) {
+            H = H_saved;
+        } else if (H_saved) {
+            FHPC_LAUNCH(run, launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, run.st));
+            H = s.H;
+        } else {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, run));
+            H = s.H;
+        }
+    }
+    if (dX || dA)
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, run));
+    if (dX)
+        FHPC_HIP(product_bf16(OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, K, M, rp, s.part, run));
+    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, run);
 }
 
 }  // namespace
@@ -729,21 +830,12 @@ int lowrank_linear_fwd(const void* X, const void* A, const void* B, void* Y, voi
     if (!aligned(X, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(Y, 16) || !aligned(H_out, 16)) return FHPC_ERR_ALIGN;
     rc = check_workspace(FHPC_OP_LOWRANK_FWD, workspace, workspace_bytes, M, K, r, N, dtype);
     if (rc) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_LOWRANK_FWD, M, K, r, N, dtype);
-    if (dtype == FHPC_F32)
-        return lowrank_fwd_f32((const float*)X, (const float*)A, (const float*)B, (float*)Y, (float*)H_out, M, K, r, N, s, st);
-
-    const int64_t rp = rank_pad(r);
-    Factors f;
-    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
-    if (rc) return rc;
-    void* H = (H_out && rp == r) ? H_out : s.H;
-    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
-    FHPC_HIP(product_bf16(OP_XC, operand(H, rp), operand(f.B, N), Y, N, N, M, rp, s.part, st));
-    if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
-    return FHPC_OK;
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_lowrank_fwd(run, s, X, A, B, Y, H_out, M, K, r, N, dtype);
 }
 
 int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* dY,
@@ -760,34 +852,12 @@ int lowrank_linear_bwd(const void* X, const void* A, const void* B, const void* 
         return FHPC_ERR_ALIGN;
     rc = check_workspace(FHPC_OP_LOWRANK_BWD, workspace, workspace_bytes, M, K, r, N, dtype);
     if (rc) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_LOWRANK_BWD, M, K, r, N, dtype);
-    if (dtype == FHPC_F32)
-        return lowrank_bwd_f32((const float*)X, (const float*)A, (const float*)B, (const float*)dY,
-                               (const float*)H_saved, (float*)dX, dA, dB, M, K, r, N, s, st);
-
-    const int64_t rp = rank_pad(r);
-    Factors f;
-    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
-    if (rc) return rc;
-    const void* H = nullptr;
-    if (dB) {
-        if (H_saved && rp == r) {
-            H = H_saved;
-        } else if (H_saved) {
-            FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
-            H = s.H;
-        } else {
-            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, st));
-            H = s.H;
-        }
-    }
-    if (dX || dA)
-        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
-    if (dX)
-        FHPC_HIP(product_bf16(OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, K, M, rp, s.part, st));
-    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, st);
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_lowrank_bwd(run, s, X, A, B, dY, H_saved, dX, dA, dB, M, K, r, N, dtype);
 }
 
 // ---- g factorised layers on one X ------------------------------------------------------------------
@@ -800,6 +870,7 @@ struct SharedScratch {
     void* dH = nullptr;     // bf16 [M][g r]
     float* Pf = nullptr;    // fp32 [M][max(r, g r) when <= 32]  split accumulator of a narrow product
     float* part = nullptr;  // slabs of the split reductions
+    int64_t part_bytes = 0;
 };
 
 static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int64_t r, int64_t N, int g)
@@ -815,11 +886,15 @@ static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int
     if (!bwd) upto(product_part_bytes(M, N, r));       // Y_i = H_i B_i
     if (bwd) {
         upto(product_part_bytes(M, K, R));             // dX = dH_all A_all^T
-        if (r <= 32) upto(split_bytes(M, r, r, N));    // dH_i = dY_i B_i^T (a column block: never the 32-row split)
+        // dH_i = dY_i B_i^T: at most 32 wide it splits its reduction; wider, it is a column block of dH_all and
+        // runs unsplit, except for g = 1, where the block is the whole (dense) matrix and may take the 32-row split
+        if (r <= 32) upto(split_bytes(M, r, r, N));
+        else if (g == 1) upto(product_part_bytes(M, r, N));
         upto(split_bytes(K, R, R, M));                 // dA_all = X^T dH_all
         upto(split_bytes(r, N, N, M));                 // dB_i = H_i^T dY_i
     }
     s.part = static_cast<float*>(c.take(part));
+    s.part_bytes = part;
     return s;
 }
 
@@ -842,18 +917,51 @@ size_t fhpc_workspace_bytes_lowrank_shared_x(int backward, int64_t M, int64_t K,
 
 // P[M][r] (bf16, row stride ldp) = L * R^(b_mode) over Kred; a product at most 32 wide splits its reduction.
 static hipError_t narrow_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t ldp, int64_t r,
-                                 float* Pf, float* part, int64_t M, int64_t Kred, hipStream_t st)
+                                 float* Pf, float* part, int64_t M, int64_t Kred, Run& run)
 {
-    if (r > 32) return product_bf16(b_mode, a, b, P, ldp, r, M, Kred, part, st);
-    hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, r, M, r, Kred, 1.f, part, st);
-    if (e != hipSuccess) return e;
-    return launch_compact_f32(Pf, r, P, ldp, M, r, 1.f, true, st);
+    if (r > 32) return product_bf16(b_mode, a, b, P, ldp, r, M, Kred, part, run);
+    hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, r, M, r, Kred, 1.f, part, run);
+    if (e != hipSuccess || run.dry) return e;
+    return launch_compact_f32(Pf, r, P, ldp, M, r, 1.f, true, run.st);
 }
 
 // column `col` of a row-major bf16 matrix
 static inline void* bf16_col(const void* p, int64_t col)
 {
     return const_cast<uint16_t*>(static_cast<const uint16_t*>(p)) + col;
+}
+
+static int seq_shared_fwd(Run& run, const SharedScratch& s, const void* X, const void* A_all, const void* const* B,
+                          void* const* Y, void* H_all_out, int64_t M, int64_t K, int64_t r, int64_t N, int g)
+{
+    const int64_t R = r * g;
+    void* H = H_all_out ? H_all_out : s.H;
+    FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, run));
+    for (int i = 0; i < g; i++)
+        FHPC_HIP(product_bf16(OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, N, M, r, s.part, run));
+    return FHPC_OK;
+}
+
+static int seq_shared_bwd(Run& run, const SharedScratch& s, const void* X, const void* A_all, const void* const* B,
+                          const void* const* dY, const void* H_all_saved, void* dX, float* dA_all, float* const* dB,
+                          bool any_dB, int64_t M, int64_t K, int64_t r, int64_t N, int g)
+{
+    const int64_t R = r * g;
+    const void* H = H_all_saved;
+    if (any_dB && !H) {
+        FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), s.H, R, R, s.Pf, s.part, M, K, run));
+        H = s.H;
+    }
+    if (dX || dA_all) {
+        for (int i = 0; i < g; i++)
+            FHPC_HIP(narrow_product(OP_KC, operand(dY[i], N), operand(B[i], N), bf16_col(s.dH, i * r), R, r, s.Pf, s.part, M, N, run));
+    }
+    if (dX) FHPC_HIP(product_bf16(OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, K, M, R, s.part, run));
+    if (dA_all) FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(s.dH, R), dA_all, R, K, R, M, 1.f, s.part, run));
+    for (int i = 0; i < g && any_dB; i++)
+        if (dB[i])
+            FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(bf16_col(H, i * r), R), operand(dY[i], N), dB[i], N, r, N, M, 1.f, s.part, run));
+    return FHPC_OK;
 }
 
 int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* const* B, void* const* Y, void* H_all_out,
@@ -871,15 +979,12 @@ int lowrank_linear_fwd_shared_x(const void* X, const void* A_all, const void* co
     const size_t need = fhpc_workspace_bytes_lowrank_shared_x(0, M, K, r, N, g);
     if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     const SharedScratch s = carve_shared(c, false, M, K, r, N, g);
-    const int64_t R = r * g;
-    void* H = H_all_out ? H_all_out : s.H;
-    FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, st));
-    for (int i = 0; i < g; i++)
-        FHPC_HIP(product_bf16(OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, N, M, r, s.part, st));
-    return FHPC_OK;
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_shared_fwd(run, s, X, A_all, B, Y, H_all_out, M, K, r, N, g);
 }
 
 int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* const* B, const void* const* dY,
@@ -901,24 +1006,66 @@ int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* co
     const size_t need = fhpc_workspace_bytes_lowrank_shared_x(1, M, K, r, N, g);
     if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     const SharedScratch s = carve_shared(c, true, M, K, r, N, g);
-    const int64_t R = r * g;
-    const void* H = H_all_saved;
-    if (any_dB && !H) {
-        FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), s.H, R, R, s.Pf, s.part, M, K, st));
-        H = s.H;
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_shared_bwd(run, s, X, A_all, B, dY, H_all_saved, dX, dA_all, dB, any_dB, M, K, r, N, g);
+}
+
+// Y = base_scale * X deq(W) + scaling * (X A) B
+static int seq_qlinear_fwd(Run& run, const Scratch& s, const void* X, const void* Wq, const void* scales, int qscheme,
+                           const void* A, const void* B, float base_scale, float scaling, void* Y, void* H_out,
+                           int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    const bool premerged = (qscheme == FHPC_W_MERGED);
+    const bool dense = (qscheme == FHPC_W_BF16) || premerged;
+    if (s.sk_part) {
+        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
+        const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};
+        FHPC_LAUNCH(run, launch_qskinny_fwd(X, &job, 1, qscheme, M, K, r, p, s.sk_part, s.sk_hpart, run.st));
+        return FHPC_OK;
     }
-    if (dX || dA_all) {
-        for (int i = 0; i < g; i++)
-            FHPC_HIP(narrow_product(OP_KC, operand(dY[i], N), operand(B[i], N), bf16_col(s.dH, i * r), R, r, s.Pf, s.part, M, N, st));
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    int rc = prepare_factors(A, B, K, r, rp, N, s, run, &f);
+    if (rc) return rc;
+    void* H = (H_out && rp == r) ? H_out : s.H;
+    const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+    if (premerged || (s.Wm && base_scale != 0.f)) {
+        // many tokens (or a weight merged by the caller): one plain product with the merged weight; H only if
+        // the caller wants it
+        const void* Wm = Wq;
+        if (!premerged) {
+            FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st));
+            Wm = s.Wm;
+        }
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(X, K), operand(Wm, N), Y, N, M, N, K, run));
+        if (H_out) {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, run));
+            if (rp != r) FHPC_LAUNCH(run, launch_pad2d_u16(H, rp, M, r, H_out, r, M, run.st));
+        }
+        return FHPC_OK;
     }
-    if (dX) FHPC_HIP(product_bf16(OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, K, M, R, s.part, st));
-    if (dA_all) FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(s.dH, R), dA_all, R, K, R, M, 1.f, s.part, st));
-    for (int i = 0; i < g && any_dB; i++)
-        if (dB[i])
-            FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(bf16_col(H, i * r), R), operand(dY[i], N), dB[i], N, r, N, M, 1.f, s.part, st));
+    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, run));
+
+    if (base_scale == 0.f) {
+        // nothing of the frozen weight is left: the factorised layer alone
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, run, scaling));
+    } else {
+        // the kernel forms alpha * (mid_scale * H B + X deq(W))
+        GemmArgs g = {};
+        g.a = operand(X, K);
+        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: W[K][N], element (n, k) at k*N + n
+        g.a2 = operand(H, rp);
+        g.b2 = operand(f.B, N);
+        g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
+        const int b_mode = dense ? OP_XC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
+        FHPC_HIP(fused_product(b_mode, OP_XC, g, Y, M, N, K, s.part, run));
+    }
+    if (H_out && rp != r) FHPC_LAUNCH(run, launch_pad2d_u16(H, rp, M, r, H_out, r, M, run.st));
     return FHPC_OK;
 }
 
@@ -942,55 +1089,12 @@ static int qlinear_fwd_impl(const void* X, const void* Wq, const void* scales, i
         return FHPC_ERR_ALIGN;
     rc = check_workspace(FHPC_OP_QLINEAR_FWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense, premerged);
     if (rc) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, !dense, premerged);
-    if (s.sk_part) {
-        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, kNumCU);
-        const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};
-        FHPC_HIP(launch_qskinny_fwd(X, &job, 1, qscheme, M, K, r, p, s.sk_part, s.sk_hpart, st));
-        return FHPC_OK;
-    }
-    const int64_t rp = rank_pad(r);
-    Factors f;
-    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
-    if (rc) return rc;
-    void* H = (H_out && rp == r) ? H_out : s.H;
-    const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
-    if (premerged || (s.Wm && base_scale != 0.f)) {
-        // many tokens (or a weight merged by the caller): one plain product with the merged weight; H only if
-        // the caller wants it
-        const void* Wm = Wq;
-        if (!premerged) {
-            FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
-            Wm = s.Wm;
-        }
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(X, K), operand(Wm, N), Y, N, M, N, K, st));
-        if (H_out) {
-            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
-            if (rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
-        }
-        return FHPC_OK;
-    }
-    FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), H, rp, s.Hf, s.part, M, K, st));
-
-    if (base_scale == 0.f) {
-        // nothing of the frozen weight is left: the factorised layer alone
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(H, rp), operand(f.B, N), Y, N, M, N, rp, st, scaling));
-    } else {
-        // the kernel forms alpha * (mid_scale * H B + X deq(W))
-        GemmArgs g = {};
-        g.a = operand(X, K);
-        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: W[K][N], element (n, k) at k*N + n
-        g.a2 = operand(H, rp);
-        g.b2 = operand(f.B, N);
-        g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = (int)rp;
-        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
-        const int b_mode = dense ? OP_XC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_KC : OP_Q4_KC;
-        FHPC_HIP(fused_product(b_mode, OP_XC, g, Y, M, N, K, s.part, st));
-    }
-    if (H_out && rp != r) FHPC_HIP(launch_pad2d_u16(H, rp, M, r, H_out, r, M, st));
-    return FHPC_OK;
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_qlinear_fwd(run, s, X, Wq, scales, qscheme, A, B, base_scale, scaling, Y, H_out, M, K, r, N);
 }
 
 int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
@@ -1015,7 +1119,7 @@ static size_t shared_x_workspace(const int64_t* N, int count, int64_t M, int64_t
         if (dry.used > need) need = dry.used;
     }
     if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
-        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, kNumCU);
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, num_cu());
         const size_t fused = (size_t)round_up(p.part_bytes, 256) + (size_t)round_up(p.hpart_bytes, 256);
         if (fused > need) need = fused;
     }
@@ -1055,7 +1159,7 @@ int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weigh
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
         // few tokens: every weight in one pair of launches
-        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, kNumCU);
+        const QskinnyPlan p = qskinny_plan(M, K, r, N, count, num_cu());
         Carver c(workspace);
         float* part = static_cast<float*>(c.take(p.part_bytes));
         float* hpart = static_cast<float*>(c.take(p.hpart_bytes));
@@ -1088,6 +1192,70 @@ int qlinear_blend_fwd(const void* X, const void* Wq, const void* scales, int qsc
                             workspace, workspace_bytes, hip_stream);
 }
 
+// dX = base_scale * dY deq(W)^T + scaling * dH A^T, dA = scaling X^T dH, dB = scaling H^T dY
+static int seq_qlinear_bwd(Run& run, const Scratch& s, const void* X, const void* Wq, const void* scales, int qscheme,
+                           const void* A, const void* B, float base_scale, float scaling, const void* dY,
+                           const void* H_saved, void* dX, float* dA, float* dB,
+                           int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    const bool premerged = (qscheme == FHPC_W_MERGED);
+    const bool dense = (qscheme == FHPC_W_BF16) || premerged;
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    int rc = prepare_factors(A, B, K, r, rp, N, s, run, &f);
+    if (rc) return rc;
+    const void* H = nullptr;
+    if (dB) {
+        if (H_saved && rp == r) {
+            H = H_saved;
+        } else if (H_saved) {
+            FHPC_LAUNCH(run, launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, run.st));
+            H = s.H;
+        } else {
+            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, run));
+            H = s.H;
+        }
+    }
+    const bool merged_dx = premerged || (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
+    const bool streamed_dx = dX && s.sk_dxpart && base_scale != 0.f;
+    const bool dh_on_the_way = streamed_dx && s.sk_dhpart;                        // the streaming launch forms dH itself
+    if (!dh_on_the_way && (dA || (dX && !merged_dx)))
+        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, run));
+    if (dX && base_scale == 0.f) {
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, run, scaling));
+    } else if (dX && merged_dx) {
+        // many tokens: dX = dY W'^T with the merged weight W' = base_scale deq(W) + scaling A B
+        const void* Wm = Wq;
+        if (!premerged) {
+            const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+            FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st));
+            Wm = s.Wm;
+        }
+        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, run));
+    } else if (streamed_dx) {
+        // a handful of tokens: one pass over the packed weight (slabs; for r <= 16 also dH = dY B^T),
+        // then slabs + rank-r branch -> bf16, and dH for dA
+        const QskinnyDxPlan p = qskinny_dx_plan(M, K, N, qscheme, num_cu());
+        QskinnyDxGrads grads = {X, H, dA, dB, r, scaling};
+        const bool grads_ride = dh_on_the_way && (dA || dB);       // dA, dB in the finish launch
+        FHPC_LAUNCH(run, launch_qskinny_dx(dY, Wq, scales, qscheme, f.B, f.A, rp, base_scale, scaling, dX, s.dH, M, K, N, p,
+                                   s.sk_dxpart, s.sk_dhpart, grads_ride ? &grads : nullptr, run.st));
+        if (grads_ride) return FHPC_OK;
+    } else if (dX) {
+        // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
+        GemmArgs g = {};
+        g.a = operand(dY, N);
+        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: element (k, n) at k*N + n
+        g.a2 = operand(s.dH, rp);
+        g.b2 = operand(f.A, rp);
+        g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
+        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
+        const int b_mode = dense ? OP_KC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
+        FHPC_HIP(fused_product(b_mode, OP_KC, g, dX, M, K, N, s.part, run));
+    }
+    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, run);
+}
+
 static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, int qscheme, int block,
                             const void* A, const void* B, float base_scale, float scaling, const void* dY,
                             const void* H_saved, void* dX, float* dA, float* dB,
@@ -1107,63 +1275,12 @@ static int qlinear_bwd_impl(const void* X, const void* Wq, const void* scales, i
         return FHPC_ERR_ALIGN;
     rc = check_workspace(FHPC_OP_QLINEAR_BWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16, !dense, premerged);
     if (rc) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     Scratch s = carve(c, FHPC_OP_QLINEAR_BWD, M, K, r, N, FHPC_BF16, !dense, premerged);
-    const int64_t rp = rank_pad(r);
-    Factors f;
-    rc = prepare_factors(A, B, K, r, rp, N, s, st, &f);
-    if (rc) return rc;
-    const void* H = nullptr;
-    if (dB) {
-        if (H_saved && rp == r) {
-            H = H_saved;
-        } else if (H_saved) {
-            FHPC_HIP(launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, st));
-            H = s.H;
-        } else {
-            FHPC_HIP(rank_product(OP_XC, operand(X, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, st));
-            H = s.H;
-        }
-    }
-    const bool merged_dx = premerged || (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
-    const bool streamed_dx = dX && s.sk_dxpart && base_scale != 0.f;
-    const bool dh_on_the_way = streamed_dx && s.sk_dhpart;                        // the streaming launch forms dH itself
-    if (!dh_on_the_way && (dA || (dX && !merged_dx)))
-        FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, st));
-    if (dX && base_scale == 0.f) {
-        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, st, scaling));
-    } else if (dX && merged_dx) {
-        // many tokens: dX = dY W'^T with the merged weight W' = base_scale deq(W) + scaling A B
-        const void* Wm = Wq;
-        if (!premerged) {
-            const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
-            FHPC_HIP(launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, st));
-            Wm = s.Wm;
-        }
-        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, st));
-    } else if (streamed_dx) {
-        // a handful of tokens: one pass over the packed weight (slabs; for r <= 16 also dH = dY B^T),
-        // then slabs + rank-r branch -> bf16, and dH for dA
-        const QskinnyDxPlan p = qskinny_dx_plan(M, K, N, qscheme, kNumCU);
-        QskinnyDxGrads grads = {X, H, dA, dB, r, scaling};
-        const bool grads_ride = dh_on_the_way && (dA || dB);       // dA, dB in the finish launch
-        FHPC_HIP(launch_qskinny_dx(dY, Wq, scales, qscheme, f.B, f.A, rp, base_scale, scaling, dX, s.dH, M, K, N, p,
-                                   s.sk_dxpart, s.sk_dhpart, grads_ride ? &grads : nullptr, st));
-        if (grads_ride) return FHPC_OK;
-    } else if (dX) {
-        // dX[m][k] = base_scale * sum_n dY[m][n] deq(W)[k][n] + scaling * sum_j dH[m][j] A[k][j]
-        GemmArgs g = {};
-        g.a = operand(dY, N);
-        g.b = dense ? operand(Wq, N) : operand(Wq, K, scales, K / 64);      // dense: element (k, n) at k*N + n
-        g.a2 = operand(s.dH, rp);
-        g.b2 = operand(f.A, rp);
-        g.M = (int)M; g.N = (int)K; g.K = (int)N; g.K2 = (int)rp;
-        g.alpha = base_scale; g.mid_scale = scaling / base_scale;
-        const int b_mode = dense ? OP_KC : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? OP_Q8_XC : OP_Q4_XC;
-        FHPC_HIP(fused_product(b_mode, OP_KC, g, dX, M, K, N, s.part, st));
-    }
-    return weight_grads(X, dY, H, s.dH, dA, dB, M, K, r, rp, N, scaling, s, st);
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_qlinear_bwd(run, s, X, Wq, scales, qscheme, A, B, base_scale, scaling, dY, H_saved, dX, dA, dB, M, K, r, N);
 }
 
 int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int qscheme, int block,
@@ -1282,6 +1399,45 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
     return FHPC_OK;
 }
 
+static int seq_decompose(Run& run, const DecompScratch& d, const void* W, const void* Omega, int power_iters,
+                         void* A_out, void* B_out, int64_t K, int64_t r, int64_t N, int64_t batch)
+{
+    hipStream_t st = run.st;
+    int rc;
+    constexpr int kQuintic = 8, kCubic = 3;
+    for (int64_t l = 0; l < batch; l++) {
+        const void* Wl = static_cast<const uint16_t*>(W) + l * K * N;
+        void* Al = static_cast<uint16_t*>(A_out) + l * K * r;
+        void* Bl = static_cast<uint16_t*>(B_out) + l * r * N;
+        const GemmOperand w = operand(Wl, N);
+        // Y = W Omega, then `power_iters` rounds of  Z = W^T Y, orthonormalise, Y = W Z
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(Omega, r), d.Yb, r, K, r, N, run));
+        for (int it = 0; it < power_iters; it++) {
+            rc = product_tn_bf16(w, operand(d.Yb, r), d.Zb, N, r, K, d, run);
+            if (rc) return rc;
+            rc = orthonormalise(d.Zb, d.Qt, N, r, kQuintic, kCubic, d, run);
+            if (rc) return rc;
+            FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(d.Qt, r), d.Yb, r, K, r, N, run));
+        }
+        rc = orthonormalise(d.Yb, Al, K, r, kQuintic, kCubic, d, run);                           // A = the basis, as it is used below
+        if (rc) return rc;
+        // B = (A^T A)^-1 A^T W, the least-squares fit given this very A.  G = A^T A = I + E with E small, so
+        // G^-1 - I = -E + E^2 - E^3 (+ ...) and B = T + (G^-1 - I) T with T = A^T W.
+        const GemmOperand a = operand(Al, r);
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, w, d.T, N, r, N, K, 1.f, d.part, run));
+        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, a, d.G, r, r, r, K, 1.f, d.part, run));
+        FHPC_LAUNCH(run, launch_gram_poly(d.G, nullptr, d.Gb, true, r, -1.f, 1.f, 0.f, 0, st));        // Gb = E = G - I
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Gb, r), d.G2b, r, r, r, r, run));   // E^2
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.G2b, r), operand(d.Gb, r), d.Sb, r, r, r, r, run));   // E^3
+        FHPC_LAUNCH(run, launch_neumann(d.G, d.G2b, d.Sb, d.Gb, r, st));                               // Gb = -E + E^2 - E^3
+        FHPC_LAUNCH(run, launch_compact_f32(d.T, N, d.Tb, N, r, N, 1.f, true, st));
+        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Tb, N), d.Cb, N, r, N, r, run));
+        FHPC_LAUNCH(run, launch_add_f32_bf16(d.T, d.Cb, Bl, r * N, st));
+    }
+    return FHPC_OK;
+}
+
+
 int lowrank_decompose(const void* W, const void* Omega, int power_iters, void* A_out, void* B_out,
                       int64_t K, int64_t r, int64_t N, int64_t batch,
                       void* workspace, size_t workspace_bytes, void* hip_stream)
@@ -1297,40 +1453,12 @@ int lowrank_decompose(const void* W, const void* Omega, int power_iters, void* A
     carve_decompose(dry, K, r, N);
     if (!workspace || workspace_bytes < dry.used) return FHPC_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return FHPC_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Carver c(workspace);
     const DecompScratch d = carve_decompose(c, K, r, N);
-    constexpr int kQuintic = 8, kCubic = 3;
-    for (int64_t l = 0; l < batch; l++) {
-        const void* Wl = static_cast<const uint16_t*>(W) + l * K * N;
-        void* Al = static_cast<uint16_t*>(A_out) + l * K * r;
-        void* Bl = static_cast<uint16_t*>(B_out) + l * r * N;
-        const GemmOperand w = operand(Wl, N);
-        // Y = W Omega, then `power_iters` rounds of  Z = W^T Y, orthonormalise, Y = W Z
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(Omega, r), d.Yb, r, K, r, N, st));
-        for (int it = 0; it < power_iters; it++) {
-            rc = product_tn_bf16(w, operand(d.Yb, r), d.Zb, N, r, K, d, st);
-            if (rc) return rc;
-            rc = orthonormalise(d.Zb, d.Qt, N, r, kQuintic, kCubic, d, st);
-            if (rc) return rc;
-            FHPC_HIP(gemm_plain(OP_KC, OP_XC, w, operand(d.Qt, r), d.Yb, r, K, r, N, st));
-        }
-        rc = orthonormalise(d.Yb, Al, K, r, kQuintic, kCubic, d, st);                           // A = the basis, as it is used below
-        if (rc) return rc;
-        // B = (A^T A)^-1 A^T W, the least-squares fit given this very A.  G = A^T A = I + E with E small, so
-        // G^-1 - I = -E + E^2 - E^3 (+ ...) and B = T + (G^-1 - I) T with T = A^T W.
-        const GemmOperand a = operand(Al, r);
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, w, d.T, N, r, N, K, 1.f, d.part, st));
-        FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, a, a, d.G, r, r, r, K, 1.f, d.part, st));
-        FHPC_HIP(launch_gram_poly(d.G, nullptr, d.Gb, true, r, -1.f, 1.f, 0.f, 0, st));        // Gb = E = G - I
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Gb, r), d.G2b, r, r, r, r, st));   // E^2
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.G2b, r), operand(d.Gb, r), d.Sb, r, r, r, r, st));   // E^3
-        FHPC_HIP(launch_neumann(d.G, d.G2b, d.Sb, d.Gb, r, st));                               // Gb = -E + E^2 - E^3
-        FHPC_HIP(launch_compact_f32(d.T, N, d.Tb, N, r, N, 1.f, true, st));
-        FHPC_HIP(gemm_plain(OP_KC, OP_XC, operand(d.Gb, r), operand(d.Tb, N), d.Cb, N, r, N, r, st));
-        FHPC_HIP(launch_add_f32_bf16(d.T, d.Cb, Bl, r * N, st));
-    }
-    return FHPC_OK;
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = d.part_bytes;
+    return seq_decompose(run, d, W, Omega, power_iters, A_out, B_out, K, r, N, batch);
 }
 
 int qweight_unpack(const void* Wq, int qscheme, int8_t* q_out, int64_t K, int64_t N, void* hip_stream)
@@ -1367,7 +1495,12 @@ int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_
     g.b = operand(B, ldb);
     g.c = C; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)K; g.K2 = 0;
-    g.alpha = alpha; g.mid_scale = 1.f; g.dbg = dbg;
+    g.alpha = alpha; g.mid_scale = 1.f;
+#ifdef FHPC_DIAG
+    g.dbg = dbg;
+#else
+    g.dbg = dbg & 12;
+#endif
     const int64_t ksteps = (K + 63) / 64;
     const int64_t per = (ksteps + splits - 1) / splits;
     g.k_chunk = (int)(per * 64);
@@ -1377,6 +1510,64 @@ int fhpc_gemm_bf16(const void* A, int64_t lda, int a_mode, const void* B, int64_
     if (e == hipErrorInvalidValue) return FHPC_ERR_UNSUPPORTED;
     FHPC_HIP(e);
     return FHPC_OK;
+}
+
+int fhpc_plan_slab_bytes(int call, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme, int g,
+                         int outputs, float base_scale, int64_t* planned, int64_t* reserved)
+{
+    if (!planned || !reserved) return FHPC_ERR_NULL;
+    // addresses that are never dereferenced: the dry pass launches nothing
+    void* const fake = reinterpret_cast<void*>((uintptr_t)1 << 21);
+    float* const ffake = static_cast<float*>(fake);
+    void* const o0 = (outputs & 1) ? fake : nullptr;
+    float* const o1 = (outputs & 2) ? ffake : nullptr;
+    float* const o2 = (outputs & 4) ? ffake : nullptr;
+    const void* const hs = (outputs & 8) ? fake : nullptr;
+    Run run;
+    run.dry = true;
+    Carver c(nullptr);
+    int rc = FHPC_ERR_SHAPE;
+    if (call >= FHPC_OP_LOWRANK_FWD && call <= FHPC_OP_QLINEAR_BWD) {
+        rc = check_common(M, K, r, N);
+        if (rc) return rc;
+        if (dtype != FHPC_F32 && dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+        const bool premerged = (qscheme == FHPC_W_MERGED), dense = premerged || (qscheme == FHPC_W_BF16);
+        const bool q = (call == FHPC_OP_QLINEAR_FWD || call == FHPC_OP_QLINEAR_BWD);
+        if (q) {
+            if (dtype != FHPC_BF16) return FHPC_ERR_DTYPE;
+            rc = dense ? FHPC_OK : check_q(qscheme, 64, K);
+            if (rc) return rc;
+        }
+        const Scratch s = q ? carve(c, call, M, K, r, N, FHPC_BF16, !dense, premerged) : carve(c, call, M, K, r, N, dtype);
+        *reserved = s.part_bytes;
+        if (call == FHPC_OP_LOWRANK_FWD) rc = seq_lowrank_fwd(run, s, fake, fake, fake, fake, o0, M, K, r, N, dtype);
+        else if (call == FHPC_OP_LOWRANK_BWD) rc = seq_lowrank_bwd(run, s, fake, fake, fake, fake, hs, o0, o1, o2, M, K, r, N, dtype);
+        else if (call == FHPC_OP_QLINEAR_FWD)
+            rc = seq_qlinear_fwd(run, s, fake, fake, fake, qscheme, fake, fake, base_scale, 1.f, fake, o0, M, K, r, N);
+        else
+            rc = seq_qlinear_bwd(run, s, fake, fake, fake, qscheme, fake, fake, base_scale, 1.f, fake, hs, o0, o1, o2, M, K, r, N);
+    } else if (call == FHPC_OP_DECOMPOSE) {
+        rc = check_common(1, K, r, N);
+        if (rc) return rc;
+        if ((r % 8) || r > K || r > N) return FHPC_ERR_UNSUPPORTED;
+        const DecompScratch d = carve_decompose(c, K, r, N);
+        *reserved = d.part_bytes;
+        rc = seq_decompose(run, d, fake, fake, 1, fake, fake, K, r, N, 1);
+    } else if (call == FHPC_PLAN_SHARED_FWD || call == FHPC_PLAN_SHARED_BWD) {
+        rc = check_shared(M, K, r, N, g);
+        if (rc) return rc;
+        const bool bwd = (call == FHPC_PLAN_SHARED_BWD);
+        const SharedScratch s = carve_shared(c, bwd, M, K, r, N, g);
+        *reserved = s.part_bytes;
+        const void* in[FHPC_MAX_SHARED];
+        void* out[FHPC_MAX_SHARED];
+        float* dB[FHPC_MAX_SHARED];
+        for (int i = 0; i < g; i++) { in[i] = fake; out[i] = fake; dB[i] = o2; }
+        rc = bwd ? seq_shared_bwd(run, s, fake, fake, in, in, hs, o0, o1, dB, o2 != nullptr, M, K, r, N, g)
+                 : seq_shared_fwd(run, s, fake, fake, in, out, o0, M, K, r, N, g);
+    }
+    *planned = run.part_need;
+    return rc;
 }
 
 const char* fhpc_status_string(int status)

@@ -58,10 +58,19 @@ struct GemmArgs {
     int splits;            // >1: the reduction is cut into slices of k_chunk (multiple of 64); needs OUT_F32
     int k_chunk;
     int64_t split_stride;  // elements between the partial-sum slabs of consecutive splits
-    int dbg;               // diagnostics, 0 in normal use: bit 0 = request no operand data (all loads out
-                           // of range), bit 1 = skip the matrix instructions (lockstep kernels only),
-                           // bit 2 = lockstep kernels only, bit 3 = four-wave kernel where it exists.
+    int dbg;               // kernel choice for tests, 0 in normal use: bit 2 = lockstep kernels only, bit 3 =
+                           // four-wave kernel where it exists.  A build with -DFHPC_DIAG also honours bit 0
+                           // (request no operand data) and bit 1 (skip the matrix instructions, lockstep only).
 };
+
+// The diagnostic bits cost a scalar compare per K tile in the hot loops, so the product build folds them away.
+#ifdef FHPC_DIAG
+#define FHPC_DBG_NO_LOADS(p) (((p).dbg & 1) != 0)
+#define FHPC_DBG_NO_MMA(p) (((p).dbg & 2) != 0)
+#else
+#define FHPC_DBG_NO_LOADS(p) false
+#define FHPC_DBG_NO_MMA(p) false
+#endif
 
 // Launches the instantiation (a_mode, b_mode, b2_mode, out_mode, tile).  a2 is always OP_KC.
 // Returns hipErrorInvalidValue when that combination is not instantiated.
@@ -78,6 +87,10 @@ hipError_t launch_gemm_pp(int a_mode, int b_mode, int out_mode, int tile, const 
 // per compute unit, and loses to them otherwise, so it is selected only by args.dbg bit 3.
 bool gemm_w4_supports(int a_mode, int b_mode, int b2_mode, int out_mode, int tile);
 hipError_t launch_gemm_w4(int a_mode, int b_mode, int out_mode, const GemmArgs& args, hipStream_t stream);
+
+// Compute units of the current device in whole multiples of 8 (256 if no device answers): what the
+// planner and the persistent launches size themselves for.
+int compute_units();
 
 // Tile extents, for planning on the host.
 void gemm_tile_extent(int tile, int* bm, int* bn);

@@ -590,8 +590,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
             typename SB::Regs rb[2];
             sa.init(p.a, m0, p.M, p.K, tid);
             sb.init(p.b, n0, p.N, p.K, tid);
-            const int kld = (p.dbg & 1) ? kbeg : kend;      // diagnostics: nothing is in range
-            const bool do_mma = !(p.dbg & 2);
+            const int kld = FHPC_DBG_NO_LOADS(p) ? kbeg : kend;      // diagnostics: nothing is in range
+            const bool do_mma = !FHPC_DBG_NO_MMA(p);
             const FragAddr fa_addr = SA::Layout::make(wave_m0, lane);
             const FragAddr fb_addr = SB::Layout::make(wave_n0, lane);
             const int group = __builtin_amdgcn_readfirstlane(wave >> 2);
@@ -653,8 +653,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
         typename SB::Regs rb[PF];
         sa.init(p.a, m0, p.M, p.K, tid);
         sb.init(p.b, n0, p.N, p.K, tid);
-        const int kld = (p.dbg & 1) ? kbeg : kend;      // diagnostics: nothing is in range
-        const bool do_mma = !(p.dbg & 2);
+        const int kld = FHPC_DBG_NO_LOADS(p) ? kbeg : kend;      // diagnostics: nothing is in range
+        const bool do_mma = !FHPC_DBG_NO_MMA(p);
         sa.issue(kbeg, kld, ra[0]);
         sb.issue(kbeg, kld, rb[0]);
         if constexpr (PF == 2) {
@@ -771,9 +771,12 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s)
 {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     dim3 grid((unsigned)(tiles * (a.splits > 1 ? a.splits : 1)));
-    char name[64];
-    snprintf(name, sizeof(name), "gemm_bf16<%dx%d,w%d,a%d,b%d,l%d,o%d>", BM, BN, WM * WN, AM, BMODE, B2, OUT);
-    const int slot = prof_begin(name, 2.0 * a.M * a.N * ((double)a.K + a.K2), 0.0, s);
+    int slot = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof(name), "gemm_bf16<%dx%d,w%d,a%d,b%d,l%d,o%d>", BM, BN, WM * WN, AM, BMODE, B2, OUT);
+        slot = prof_begin(name, 2.0 * a.M * a.N * ((double)a.K + a.K2), 0.0, s);
+    }
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, AM, BMODE, B2, OUT, PF, PP>), grid, dim3(WM * WN * 64), 0, s, a);
     prof_end(slot, s);
     return hipGetLastError();

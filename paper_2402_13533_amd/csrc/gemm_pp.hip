@@ -93,7 +93,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
         n0 = tn * BN;
         kbeg = split * p.k_chunk;
         kend = (kbeg + p.k_chunk < p.K) ? kbeg + p.k_chunk : p.K;
-        kld = (p.dbg & 1) ? kbeg : kend;                       // diagnostics: nothing is in range
+        kld = FHPC_DBG_NO_LOADS(p) ? kbeg : kend;                       // diagnostics: nothing is in range
         if (kbeg < kend) {
             fa.set_tile(p.a, m0, p.M, wave, lane);
             fb.set_tile(p.b, n0, p.N, wave, lane);
@@ -312,8 +312,11 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     }
 }
 
-// compute units of the current device (the persistent shape launches one workgroup on each)
-static int compute_units()
+}  // namespace pp
+
+// compute units of the current device, rounded down to whole multiples of the eight XCDs (256 when no
+// device can be asked: the planner also sizes workspaces on hosts without a GPU)
+int compute_units()
 {
     static int cached[64] = {0};
     int dev = 0;
@@ -326,6 +329,8 @@ static int compute_units()
     return cached[dev];
 }
 
+namespace pp {
+
 template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT>
 static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 {
@@ -333,9 +338,12 @@ static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
     const int total = tiles * (a.splits > 1 ? a.splits : 1);
     const int cus = compute_units();
     dim3 grid((unsigned)((!KSPLIT && total > cus) ? cus : total));
-    char name[64];
-    snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
-    const int slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+    int slot = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
+        slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+    }
     hipLaunchKernelGGL((gemm_pp_kernel<BM, BN, BK, KSPLIT, NSTAGE, AM, BMODE, OUT>), grid, dim3(NT), 0, s, a);
     prof_end(slot, s);
     return hipGetLastError();

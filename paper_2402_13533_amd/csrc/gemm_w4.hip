@@ -70,7 +70,7 @@ __global__ __launch_bounds__(NT) void gemm_w4_kernel(GemmArgs p)
         FB fb;
         fa.init(p.a, m0, p.M, p.K, wave, lane);
         fb.init(p.b, n0, p.N, p.K, wave, lane);
-        const int kld = (p.dbg & 1) ? kbeg : kend;             // diagnostics: nothing is in range
+        const int kld = FHPC_DBG_NO_LOADS(p) ? kbeg : kend;             // diagnostics: nothing is in range
         const FragAddr aa = TA::make(wave_m0, lane);
         const FragAddr ab = TB::make(wave_n0, lane);
 
@@ -218,9 +218,12 @@ static hipError_t launch_w4(const GemmArgs& a, hipStream_t s)
 {
     const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     dim3 grid((unsigned)(tiles * (a.splits > 1 ? a.splits : 1)));
-    char name[64];
-    snprintf(name, sizeof(name), "gemm_w4<256x256x32,a%d,b%d,o%d>", AM, BMODE, OUT);
-    const int slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+    int slot = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof(name), "gemm_w4<256x256x32,a%d,b%d,o%d>", AM, BMODE, OUT);
+        slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+    }
     hipLaunchKernelGGL((gemm_w4_kernel<NS, AM, BMODE, OUT>), grid, dim3(NT), 0, s, a);
     prof_end(slot, s);
     return hipGetLastError();

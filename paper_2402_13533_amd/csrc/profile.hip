@@ -19,6 +19,8 @@ int g_count = 0;
 bool g_on = false;
 }  // namespace
 
+bool prof_on() { return g_on; }
+
 int prof_begin(const char* name, double flops, double bytes, hipStream_t s)
 {
     if (!g_on || g_count >= (int)g_pool.size()) return -1;
