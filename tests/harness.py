@@ -45,6 +45,27 @@ def from_device(t) -> np.ndarray:
     return t.numpy()
 
 
+def parity_err(got, ref, tol=TOL_BF16, what=""):
+    """Relative Frobenius error of a result against the oracle's, in fp64; also asserts, element by element,
+    |got - ref| <= 2^-7 |ref| + 10 tol rms(ref): the norm alone would let a single garbage element of a large
+    output through (typical element errors are a fifth of tol rms(ref), so this is some twenty deviations out),
+    and that nothing is NaN or infinite."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), (what, "non-finite values")
+    diff = np.abs(got - ref)
+    den = np.linalg.norm(ref.ravel())
+    num = np.linalg.norm(diff.ravel())
+    rms = den / np.sqrt(max(ref.size, 1))
+    over = diff - (2.0 ** -7 * np.abs(ref) + 10.0 * tol * rms)
+    if over.size and over.max() > 0:
+        i = np.unravel_index(int(np.argmax(over)), over.shape)
+        raise AssertionError("%s: element %s off by %.3e (got %.6g, ref %.6g, bound %.3e; %d elements beyond their bound)"
+                             % (what, i, diff[i], got[i], ref[i], diff[i] - over[i], int((over > 0).sum())))
+    return float(num / den) if den > 0 else float(num)
+
+
 def f16_bits_cuda(bits: np.ndarray):
     import torch
     return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16)).cuda()

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import Bf16, from_device
+from harness import Bf16, from_device, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -54,7 +54,7 @@ def _check(W, r, power_iters, slack, seed=5):
     assert err >= opt * (1 - 1e-9) - ROUNDING                                   # nothing beats the optimum
     assert np.max(np.abs(A.T @ A - np.eye(r))) <= 2e-2                          # orthonormal up to bf16 rounding
     fit = np.linalg.lstsq(A, Wd, rcond=None)[0]                                 # the least-squares B for this A
-    assert oracle.rel_fro(B, fit) <= 5e-3
+    assert parity_err(B, fit) <= 5e-3
     return A, B
 
 

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, TOL_F32, Bf16, from_device, sample_rows
+from harness import TOL_BF16, TOL_F32, Bf16, from_device, sample_rows, parity_err
 from paper_2402_13533_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -35,7 +35,7 @@ def test_swiglu_elementwise():
     # fp32 storage
     Gf, Uf = synth.normal(904, (4099,), 2.0), synth.normal(905, (4099,), 1.0)
     Zf = fhpc.swiglu_fwd(torch.from_numpy(Gf).cuda(), torch.from_numpy(Uf).cuda())
-    assert oracle.rel_fro(from_device(Zf), oracle.swiglu_fwd(Gf, Uf)) <= TOL_F32
+    assert parity_err(from_device(Zf), oracle.swiglu_fwd(Gf, Uf)) <= TOL_F32
 
 
 def _ffn_inputs(M, d, r, f, base=0):
@@ -71,9 +71,9 @@ def test_config3_chain_reduced_tokens():
     Wd = [w.cuda() for w in W]
     Y, saved = ffn.ffn_fwd(X.cuda(), *Wd)
     dX, grads = ffn.ffn_bwd(X.cuda(), *Wd, dY.cuda(), saved)
-    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "dX": oracle.rel_fro(from_device(dX), dXr)}
+    errs = {"Y": parity_err(from_device(Y), Yr), "dX": parity_err(from_device(dX), dXr)}
     for name, g, r_ in zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), grads, gr):
-        errs[name] = oracle.rel_fro(from_device(g), r_)
+        errs[name] = parity_err(from_device(g), r_)
     print("c3 chain M=%d:" % M, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= TOL_BF16, (k, v)
@@ -96,44 +96,82 @@ def test_config3_chain_shared_x():
     got = {"Y": from_device(Y), "dX": from_device(dX), "dAg": dA_gu[:, :r], "dBg": from_device(dBg),
            "dAu": dA_gu[:, r:], "dBu": from_device(dBu), "dAd": from_device(dAd), "dBd": from_device(dBd)}
     ref = dict(zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), gr), Y=Yr, dX=dXr)
-    errs = {k: oracle.rel_fro(got[k], ref[k]) for k in got}
+    errs = {k: parity_err(got[k], ref[k]) for k in got}
     print("c3 chain shared-x M=%d:" % M, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= TOL_BF16, (k, v)
 
 
-def test_config3_full_size_sampled():
-    """Config 3 at 16384 tokens: Y and dX of the whole chain on sampled rows (every step
-    of the chain is row-wise independent), and each weight gradient's additivity over
-    token blocks (a sum over tokens must equal the sum of its two halves).  The halves may
-    run on another tile shape than the whole, which sums k in another order, so a few per
-    cent of the bf16 intermediates (H, dH) differ by one ulp between the two runs: the bound
-    is a fraction of the bf16 tolerance, far below what a dropped or doubled token block
-    would cause (64 of 16384 tokens missing: about 6e-2)."""
+def _oracle_ffn_full_size(X, dY, W, rows, J):
+    """The oracle's chain on every token (G, U, Z, dZ, dG, dU in fp64), then: Y and dX on the token rows `rows`, and
+    each weight gradient restricted to the rank indices J (column j of dA and row j of dB depend on the pair only
+    through column j of A and row j of B, so the oracle runs the layer restricted to those indices).
+    dZ = (dY Bd^T) Ad^T is the factorised layer's forward with the transposed pair."""
+    Ag, Bg, Au, Bu, Ad, Bd = [w.f64 for w in W]
+    Xf, dYf = X.f64, dY.f64
+    G, _ = oracle.lowrank_fwd(Xf, Ag, Bg)
+    U, _ = oracle.lowrank_fwd(Xf, Au, Bu)
+    Z = oracle.swiglu_fwd(G, U)
+    dZ, _ = oracle.lowrank_fwd(dYf, np.ascontiguousarray(Bd.T), np.ascontiguousarray(Ad.T))
+    dG, dU = oracle.swiglu_bwd(G, U, dZ)
+    del dZ
+    Y, _ = oracle.lowrank_fwd(Z[rows], Ad, Bd)
+    dXg, _, _ = oracle.lowrank_bwd(Xf[rows], Ag, Bg, dG[rows])
+    dXu, _, _ = oracle.lowrank_bwd(Xf[rows], Au, Bu, dU[rows])
+    sub = lambda A, B: (np.ascontiguousarray(A[:, J]), np.ascontiguousarray(B[J, :]))
+    _, dAg, dBg = oracle.lowrank_bwd(Xf, *sub(Ag, Bg), dG)
+    _, dAu, dBu = oracle.lowrank_bwd(Xf, *sub(Au, Bu), dU)
+    _, dAd, dBd = oracle.lowrank_bwd(Z, *sub(Ad, Bd), dYf)
+    return Y, dXg + dXu, {"dAg": dAg, "dBg": dBg, "dAu": dAu, "dBu": dBu, "dAd": dAd, "dBd": dBd}
+
+
+_full_size_cache = {}
+
+
+def _config3_full_size_case():
+    """Inputs and oracle results of the full-size test, computed once for both routes (the fp64 chain over
+    16384 tokens is about a minute of host time)."""
+    if not _full_size_cache:
+        M, d, r, f = 16384, 4096, 1024, 11008
+        X, dY, W = _ffn_inputs(M, d, r, f, base=20)
+        rows = sample_rows(M, 33, 128)
+        J = np.unique(np.random.default_rng(34).integers(0, r, size=6))
+        print("c3 full size: oracle chain on %d tokens ..." % M, flush=True)
+        _full_size_cache["case"] = (X, dY, W, rows, J, _oracle_ffn_full_size(X, dY, W, rows, J))
+        print("c3 full size: oracle done", flush=True)
+    return _full_size_cache["case"]
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("shared_x", [False, True])
+def test_config3_full_size_sampled(shared_x):
+    """Config 3 at 16384 tokens, as separate gate / up calls and through the shared-X chain the benchmark times:
+    Y and dX of the whole chain on sampled rows (every step of the chain is row-wise independent) and all six
+    weight gradients on sampled rank indices, against the oracle run on every token."""
     from paper_2402_13533_amd import ffn
-    fhpc = _fhpc()
-    M, d, r, f = 16384, 4096, 1024, 11008
-    X, dY, W = _ffn_inputs(M, d, r, f, base=20)
-    Wd = [w.cuda() for w in W]
+    r = 1024
+    X, dY, W, rows, J, (Yr, dXr, gr) = _config3_full_size_case()
+    Ag, Bg, Au, Bu, Ad, Bd = W
     Xd, dYd = X.cuda(), dY.cuda()
-    Y, saved = ffn.ffn_fwd(Xd, *Wd)
-    dX, grads = ffn.ffn_bwd(Xd, *Wd, dYd, saved)
-    rows = sample_rows(M, 33, 128)
-    Yr, dXr, _ = _oracle_ffn(X.rows(rows).f64, dY.rows(rows).f64, W)
-    eY = oracle.rel_fro(from_device(Y)[rows], Yr)
-    eX = oracle.rel_fro(from_device(dX)[rows], dXr)
-    print("c3 full: Y %.3e dX %.3e" % (eY, eX), flush=True)
-    assert eY <= TOL_BF16 and eX <= TOL_BF16
-    grads = [from_device(g) for g in grads]
-    del Y, dX, saved
-    h = M // 2
-    parts = []
-    for lo in (0, h):
-        Yh, sv = ffn.ffn_fwd(Xd[lo:lo + h].contiguous(), *Wd)
-        _, gh = ffn.ffn_bwd(Xd[lo:lo + h].contiguous(), *Wd, dYd[lo:lo + h].contiguous(), sv)
-        parts.append([from_device(g) for g in gh])
-        del Yh, sv, gh
-    for name, g, a, b in zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), grads, parts[0], parts[1]):
-        e = oracle.rel_fro(g, a + b)
-        print("c3 full additivity %s %.3e" % (name, e), flush=True)
-        assert e <= 2e-3, (name, e)
+    if shared_x:
+        A_gu = Bf16(np.concatenate([Ag.bits, Au.bits], axis=1)).cuda()
+        Wd = [A_gu, Bg.cuda(), Bu.cuda(), Ad.cuda(), Bd.cuda()]
+        Y, saved = ffn.ffn_fwd_shared_x(Xd, *Wd)
+        dX, (dA_gu, dBg, dBu, dAd, dBd) = ffn.ffn_bwd_shared_x(Xd, *Wd, dYd, saved)
+        dA_gu = from_device(dA_gu)
+        grads = {"dAg": dA_gu[:, :r], "dBg": from_device(dBg), "dAu": dA_gu[:, r:], "dBu": from_device(dBu),
+                 "dAd": from_device(dAd), "dBd": from_device(dBd)}
+    else:
+        Wd = [w.cuda() for w in W]
+        Y, saved = ffn.ffn_fwd(Xd, *Wd)
+        dX, g6 = ffn.ffn_bwd(Xd, *Wd, dYd, saved)
+        grads = dict(zip(("dAg", "dBg", "dAu", "dBu", "dAd", "dBd"), [from_device(g) for g in g6]))
+    Y, dX = from_device(Y)[rows], from_device(dX)[rows]
+    del saved
+    errs = {"Y": parity_err(Y, Yr, what="Y"), "dX": parity_err(dX, dXr, what="dX")}
+    for name, ref in gr.items():
+        got = grads[name][:, J] if name.startswith("dA") else grads[name][J, :]
+        errs[name] = parity_err(got, ref, what=name)
+    print("c3 full shared_x=%s: %s" % (shared_x, {k: "%.3e" % v for k, v in errs.items()}), flush=True)
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)

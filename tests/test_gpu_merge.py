@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, TOL_F32, Bf16, f16_bits_cuda, from_device, sample_rows
+from harness import TOL_BF16, TOL_F32, Bf16, f16_bits_cuda, from_device, sample_rows, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -48,7 +48,7 @@ def test_merge_small_ragged(kind, out, r):
                              out_dtype=torch.float32 if out == "f32" else torch.bfloat16)
     torch.cuda.synchronize()
     assert tuple(got.shape) == (K, N)
-    err = oracle.rel_fro(from_device(got), ref)
+    err = parity_err(from_device(got), ref)
     assert err <= (TOL_F32 if out == "f32" else TOL_BF16), (kind, out, r, err)
     if out == "f32":
         # element by element: fp32 accumulation of exact products, one rounding of the sum with the base
@@ -74,7 +74,7 @@ def test_merge_ragged_rows_stay_inside_the_output(kind, K, out):
     fhpc.lowrank_merge(W_dev, sc_dev, scheme, A.cuda(), B.cuda(), 1.0, W_out=W_out)
     torch.cuda.synchronize()
     assert bool((buf[:pad] == 77.0).all()) and bool((buf[pad + K * N:] == 77.0).all())
-    err = oracle.rel_fro(from_device(W_out), oracle.merge(Wd, A.f64, B.f64, 1.0))
+    err = parity_err(from_device(W_out), oracle.merge(Wd, A.f64, B.f64, 1.0))
     assert err <= (TOL_F32 if out == "f32" else TOL_BF16)
 
 
@@ -113,7 +113,7 @@ def test_merge_full_size_sampled_rows(kind, K, N, r):
     ref = oracle.merge(None if Wd is None else Wd[idx], A.f64[idx], B.f64, s)
     for dt, tol in ((torch.float32, TOL_F32), (torch.bfloat16, TOL_BF16)):
         got = fhpc.lowrank_merge(W_dev, sc_dev, scheme, A.cuda(), B.cuda(), s, out_dtype=dt)
-        err = oracle.rel_fro(from_device(got[torch.from_numpy(idx).cuda()]), ref)
+        err = parity_err(from_device(got[torch.from_numpy(idx).cuda()]), ref)
         assert err <= tol, (kind, dt, err)
 
 
@@ -133,7 +133,7 @@ def test_merged_weight_reproduces_the_adapted_layer():
     Y_merged = fhpc.qlinear_blend_fwd(X.cuda(), Wm, None, fhpc.FHPC_W_BF16, A.cuda(), B.cuda(), 1.0)
     Y_ref, _ = oracle.qlinear_lowrank_fwd(X.f64, oracle.dequant(Wq, sc, 4, 64), A.f64, B.f64, s)
     # two roundings to bf16 on the merged route (the weight, then the output)
-    assert oracle.rel_fro(from_device(Y_merged), Y_ref) <= 2 * TOL_BF16
+    assert parity_err(from_device(Y_merged), Y_ref) <= 2 * TOL_BF16
 
 
 @pytest.mark.parametrize("scheme", [8, 4])

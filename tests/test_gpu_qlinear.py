@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, qlinear_inputs, sample_rows
+from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, qlinear_inputs, sample_rows, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -105,16 +105,16 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
         Hr = None
         sel = rows
     errs = {
-        "Y": oracle.rel_fro(from_device(Y)[sel], Yr),
-        "dX": oracle.rel_fro(from_device(dX)[sel], dXr),
-        "dA": oracle.rel_fro(from_device(dA), dAr),
-        "dB": oracle.rel_fro(from_device(dB), dBr),
-        "dX(recompute)": oracle.rel_fro(from_device(dX2)[sel], dXr),
-        "dA(recompute)": oracle.rel_fro(from_device(dA2), dAr),
-        "dB(recompute)": oracle.rel_fro(from_device(dB2), dBr),
+        "Y": parity_err(from_device(Y)[sel], Yr),
+        "dX": parity_err(from_device(dX)[sel], dXr),
+        "dA": parity_err(from_device(dA), dAr),
+        "dB": parity_err(from_device(dB), dBr),
+        "dX(recompute)": parity_err(from_device(dX2)[sel], dXr),
+        "dA(recompute)": parity_err(from_device(dA2), dAr),
+        "dB(recompute)": parity_err(from_device(dB2), dBr),
     }
     if Hr is not None:
-        errs["H"] = oracle.rel_fro(from_device(H), Hr)
+        errs["H"] = parity_err(from_device(H), Hr)
     print(tag, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= TOL_BF16, (tag, k, v)
@@ -206,9 +206,9 @@ def test_blend_layer_split_reduction(kind):
     dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, dYd, H_saved=H)
     Yr, Hr = oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)
     dXr, dAr, dBr = oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
-    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
-            "dX": oracle.rel_fro(from_device(dX), dXr), "dA": oracle.rel_fro(from_device(dA), dAr),
-            "dB": oracle.rel_fro(from_device(dB), dBr)}
+    errs = {"Y": parity_err(from_device(Y), Yr), "H": parity_err(from_device(H), Hr),
+            "dX": parity_err(from_device(dX), dXr), "dA": parity_err(from_device(dA), dAr),
+            "dB": parity_err(from_device(dB), dBr)}
     print("blend split %s" % kind, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= TOL_BF16, (k, v)
@@ -223,9 +223,9 @@ def test_qlinear_scaling_zero_is_base_layer(scheme):
     Wd = oracle.dequant(Wq, sc, scheme, 64)
     Wq_d, sc_d = _to_dev(Wq, sc)
     Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0)
-    assert oracle.rel_fro(from_device(Y), X.f64 @ Wd) <= TOL_BF16
+    assert parity_err(from_device(Y), X.f64 @ Wd) <= TOL_BF16
     dX, dA, dB = fhpc.qlinear_lowrank_bwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0, dY.cuda())
-    assert oracle.rel_fro(from_device(dX), dY.f64 @ Wd.T) <= TOL_BF16
+    assert parity_err(from_device(dX), dY.f64 @ Wd.T) <= TOL_BF16
     assert not from_device(dA).any() and not from_device(dB).any()
     # all-zero codes: the layer reduces to scaling * (X A) B, which pins the rank-r branch
     # (and its scaling) on its own at the full tolerance
@@ -233,10 +233,10 @@ def test_qlinear_scaling_zero_is_base_layer(scheme):
     Wz_d, scz_d = _to_dev(*Wz)
     s = 1.5
     Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wz_d, scz_d, scheme, A.cuda(), B.cuda(), s)
-    assert oracle.rel_fro(from_device(Y), s * oracle.lowrank_fwd(X.f64, A.f64, B.f64)[0]) <= TOL_BF16
+    assert parity_err(from_device(Y), s * oracle.lowrank_fwd(X.f64, A.f64, B.f64)[0]) <= TOL_BF16
     dX, dA, dB = fhpc.qlinear_lowrank_bwd(X.cuda(), Wz_d, scz_d, scheme, A.cuda(), B.cuda(), s, dY.cuda())
     for g, r_ in zip((dX, dA, dB), oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)):
-        assert oracle.rel_fro(from_device(g), s * r_) <= TOL_BF16
+        assert parity_err(from_device(g), s * r_) <= TOL_BF16
 
 
 def test_config4_full_size():
@@ -279,7 +279,7 @@ def test_few_token_forward(scheme, M, K, r, N):
     Wq_d, sc_d = _to_dev(Wq, sc)
     Y, H = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 2.0, save_H=True)
     Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, 2.0)
-    eY, eH = oracle.rel_fro(from_device(Y), Yr), oracle.rel_fro(from_device(H), Hr)
+    eY, eH = parity_err(from_device(Y), Yr), parity_err(from_device(H), Hr)
     print("few tokens q%d %s: Y %.3e H %.3e" % (scheme, (M, K, r, N), eY, eH), flush=True)
     assert eY <= TOL_BF16 and eH <= TOL_BF16
     base = X.f64 @ Wd
@@ -307,7 +307,7 @@ def test_shared_x_forward(scheme, M):
         refs.append(oracle.qlinear_lowrank_fwd(X.f64, oracle.dequant(Wq, sc, scheme, 64), A.f64, B.f64, s))
     outs = fhpc.qlinear_lowrank_fwd_shared_x(X.cuda(), weights, scheme, save_H=True)
     for j, ((Y, H), (Yr, Hr)) in enumerate(zip(outs, refs)):
-        eY, eH = oracle.rel_fro(from_device(Y), Yr), oracle.rel_fro(from_device(H), Hr)
+        eY, eH = parity_err(from_device(Y), Yr), parity_err(from_device(H), Hr)
         print("shared X q%d M=%d weight %d: Y %.3e H %.3e" % (scheme, M, j, eY, eH), flush=True)
         assert eY <= TOL_BF16 and eH <= TOL_BF16
     plain = fhpc.qlinear_lowrank_fwd_shared_x(X.cuda(), weights, scheme)
@@ -332,7 +332,7 @@ def test_few_token_forward_every_code(scheme):
     _, X, A, B, _ = qlinear_inputs(8, M, K, 8, N, 70)
     Wq_d, sc_d = _to_dev(Wq, sc)
     Y = fhpc.qlinear_lowrank_fwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0)
-    e = oracle.rel_fro(from_device(Y), X.f64 @ Wd)
+    e = parity_err(from_device(Y), X.f64 @ Wd)
     print("few tokens q%d every code: %.3e" % (scheme, e), flush=True)
     assert e <= TOL_BF16
 
@@ -374,7 +374,7 @@ def test_few_token_input_gradient_every_code(scheme):
     Wq_d, sc_d = _to_dev(Wq, sc)
     dX, _, _ = fhpc.qlinear_lowrank_bwd(X.cuda(), Wq_d, sc_d, scheme, A.cuda(), B.cuda(), 0.0, dY.cuda())
     ref = dY.f64 @ Wd.T
-    e = oracle.rel_fro(from_device(dX), ref)
+    e = parity_err(from_device(dX), ref)
     print("few tokens q%d dX every code: %.3e" % (scheme, e), flush=True)
     assert e <= TOL_BF16
 
@@ -434,7 +434,7 @@ def test_few_token_blend_backward():
                 if np.linalg.norm(ref) == 0.0:
                     assert not from_device(got).any()
                     continue
-                e = oracle.rel_fro(from_device(got), ref)
+                e = parity_err(from_device(got), ref)
                 assert e <= TOL_BF16, (scheme, alpha, name, e)
 
 
@@ -457,11 +457,11 @@ def test_blend_layer(scheme, alpha, M):
     dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, alpha, dYd, H_saved=H)
     Yr, Hr = oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)
     dXr, dAr, dBr = oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
-    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
-            "dX": oracle.rel_fro(from_device(dX), dXr)}
+    errs = {"Y": parity_err(from_device(Y), Yr), "H": parity_err(from_device(H), Hr),
+            "dX": parity_err(from_device(dX), dXr)}
     if alpha < 1.0:
-        errs["dA"] = oracle.rel_fro(from_device(dA), dAr)
-        errs["dB"] = oracle.rel_fro(from_device(dB), dBr)
+        errs["dA"] = parity_err(from_device(dA), dAr)
+        errs["dB"] = parity_err(from_device(dB), dBr)
     else:
         assert not from_device(dA).any() and not from_device(dB).any()
     print("blend q%d alpha %.2f" % (scheme, alpha), {k: "%.3e" % v for k, v in errs.items()}, flush=True)
@@ -477,7 +477,7 @@ def test_blend_layer_few_tokens_and_alpha_range():
     Wd = oracle.dequant(Wq, sc, 4, 64)
     Wq_d, sc_d = _to_dev(Wq, sc)
     Y = fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), 0.4)
-    assert oracle.rel_fro(from_device(Y), oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, 0.4)[0]) <= TOL_BF16
+    assert parity_err(from_device(Y), oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, 0.4)[0]) <= TOL_BF16
     for bad in (-0.1, 1.5, float("nan")):
         with pytest.raises(fhpc.FhpcError):
             fhpc.qlinear_blend_fwd(X.cuda(), Wq_d, sc_d, 4, A.cuda(), B.cuda(), bad)
@@ -498,9 +498,9 @@ def test_blend_layer_dense_weight(M):
     dX, dA, dB = fhpc.qlinear_blend_bwd(Xd, Wd_, None, fhpc.FHPC_W_BF16, Ad, Bd, alpha, dYd, H_saved=H)
     Yr, Hr = oracle.blend_fwd(X.f64, W.f64, A.f64, B.f64, alpha)
     dXr, dAr, dBr = oracle.blend_bwd(X.f64, W.f64, A.f64, B.f64, alpha, dY.f64)
-    errs = {"Y": oracle.rel_fro(from_device(Y), Yr), "H": oracle.rel_fro(from_device(H), Hr),
-            "dX": oracle.rel_fro(from_device(dX), dXr), "dA": oracle.rel_fro(from_device(dA), dAr),
-            "dB": oracle.rel_fro(from_device(dB), dBr)}
+    errs = {"Y": parity_err(from_device(Y), Yr), "H": parity_err(from_device(H), Hr),
+            "dX": parity_err(from_device(dX), dXr), "dA": parity_err(from_device(dA), dAr),
+            "dB": parity_err(from_device(dB), dBr)}
     print("blend dense M=%d" % M, {k: "%.3e" % v for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= TOL_BF16, (k, v)
@@ -635,7 +635,7 @@ def test_premerged_weight(scheme, M):
     Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, s)
     ref = oracle.qlinear_lowrank_bwd(X.f64, Wd, A.f64, B.f64, s, dY.f64)
     for name, g, rf in zip(("Y", "H", "dX", "dA", "dB"), (Y, H, dX, dA, dB), (Yr, Hr) + ref):
-        e = oracle.rel_fro(from_device(g), rf)
+        e = parity_err(from_device(g), rf)
         assert e <= TOL_BF16, (name, e)
     if M >= 1152:
         Y2, H2 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device
+from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -58,7 +58,7 @@ def test_random_shapes(seed):
                 ref = (oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)[0],) + oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
         for name, g, rf in zip(("Y", "dX", "dA", "dB"), got, ref):
             if np.linalg.norm(rf) > 0:
-                e = oracle.rel_fro(from_device(g), rf)
+                e = parity_err(from_device(g), rf)
                 assert e <= TOL_BF16, (tag, name, e)
             else:
                 assert not from_device(g).any(), (tag, name)          # alpha = 1: no gradient reaches the pair
@@ -96,7 +96,7 @@ def test_random_shapes_shared_x(seed):
             dx, da, db = oracle.lowrank_bwd(X.f64, As[i].f64, Bs[i].f64, dYs[i].f64)
             dX_ref += dx
             for name, got, rf in (("Y", from_device(Ys[i]), y), ("dA", dA[:, i * r:(i + 1) * r], da), ("dB", from_device(dBs[i]), db)):
-                e = oracle.rel_fro(got, rf)
+                e = parity_err(got, rf)
                 assert e <= TOL_BF16, (tag, name, i, e)
-        e = oracle.rel_fro(from_device(dX), dX_ref)
+        e = parity_err(from_device(dX), dX_ref)
         assert e <= TOL_BF16, (tag, "dX", e)
