@@ -135,6 +135,21 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
                         int64_t M, int64_t K, int64_t r, int64_t N,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* qlinear_lowrank_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, layouts, results (bit
+ * for bit) and status codes as qlinear_lowrank_fwd, without the workspace pair: scratch comes from a fixed
+ * array of FHPC_NOALLOC_SCRATCH_BYTES in device memory that belongs to the library (one per GPU, held until the
+ * process ends).  The call allocates nothing and frees nothing.  Sizes whose workspace need
+ * (fhpc_workspace_bytes(FHPC_OP_QLINEAR_FWD, ...)) exceeds the array return FHPC_ERR_WORKSPACE before anything
+ * is launched; every token count up to 64 on the weights of a 13B decoder layer needs 8 MiB or less.
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU (different streams, different
+ * threads) race on it; calls ordered on one stream do not.  The first call on a device looks the array's
+ * address up, which is not a capturable operation: make one call on the device before capturing. */
+#define FHPC_NOALLOC_SCRATCH_BYTES (16u << 20)
+int qlinear_lowrank_fwd_noalloc(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                                const void* A, const void* B, float scaling, void* Y, void* H_out,
+                                int64_t M, int64_t K, int64_t r, int64_t N, void* hip_stream);
+
 /* Finetuning layer, backward; W is frozen (Sec. 5.1), so there is no dW:
  *   dH = dY * B^T;  dX = dY * deq(W)^T + scaling * dH * A^T  (bf16);
  *   dA = scaling * X^T * dH (fp32);  dB = scaling * (X*A)^T * dY (fp32).

@@ -26,7 +26,7 @@ EXPORTS = [
     "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
-    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes",
+    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc",
 ]
 
 _lib = None
@@ -61,6 +61,7 @@ def load_library():
     lib.qlinear_lowrank_bwd.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp,
                                         i64, i64, i64, i64, vp, sz, vp]
     lib.qlinear_blend_fwd.argtypes = lib.qlinear_lowrank_fwd.argtypes
+    lib.qlinear_lowrank_fwd_noalloc.argtypes = [vp, vp, vp, i32, i32, vp, vp, f32, vp, vp, i64, i64, i64, i64, vp]
     lib.qlinear_blend_bwd.argtypes = lib.qlinear_lowrank_bwd.argtypes
     lib.lowrank_merge.argtypes = [vp, vp, i32, i32, vp, vp, f32, vp, i32, i64, i64, i64, vp, sz, vp]
     lib.lowrank_decompose.argtypes = [vp, vp, i32, vp, vp, i64, i64, i64, i64, vp, sz, vp]
@@ -354,6 +355,26 @@ def qlinear_lowrank_fwd(X, Wq, scales, qscheme, A, B, scaling, block=64, Y=None,
                               C.c_float(scaling), _ptr(Y), _ptr(H_out), M, K, r, N, _ptr(ws), wsz, _stream())
     if rc:
         raise FhpcError(rc, _entry)
+    return (Y, H_out) if H_out is not None else Y
+
+
+FHPC_NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def qlinear_lowrank_fwd_noalloc(X, Wq, scales, qscheme, A, B, scaling, Y, H_out=None, block=64):
+    """qlinear_lowrank_fwd without a workspace: the library's fixed scratch array serves.  Nothing is allocated here
+    either, so Y (and H_out, if wanted) must be passed in."""
+    torch = _torch()
+    M, K = X.shape
+    r, N = B.shape
+    bf = torch.bfloat16
+    _check(X, "X", None, bf); _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+    _q_shapes(Wq, scales, qscheme, K, N, block)
+    _check(Y, "Y", (M, N), bf); _check(H_out, "H_out", (M, r), bf)
+    rc = load_library().qlinear_lowrank_fwd_noalloc(_ptr(X), _ptr(Wq), _ptr(scales), qscheme, block, _ptr(A), _ptr(B),
+                                                    C.c_float(scaling), _ptr(Y), _ptr(H_out), M, K, r, N, _stream())
+    if rc:
+        raise FhpcError(rc, "qlinear_lowrank_fwd_noalloc")
     return (Y, H_out) if H_out is not None else Y
 
 

@@ -7,6 +7,8 @@
 #include "merge.h"
 #include "qskinny.h"
 
+#include <atomic>
+
 using namespace fhpc;
 
 namespace {
@@ -1107,6 +1109,56 @@ int qlinear_lowrank_fwd(const void* X, const void* Wq, const void* scales, int q
                             workspace, workspace_bytes, hip_stream);
 }
 
+// ---- the same forward for callers that cannot allocate --------------------------------------------
+// The workspace is a fixed array in device memory that belongs to the library: every GPU the library runs on
+// holds its own copy, at its own address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; what the kernels get is the address looked up once per device.
+static __device__ __align__(256) unsigned char scratch[FHPC_NOALLOC_SCRATCH_BYTES];
+
+// address of `scratch` on the current device (looked up on the first call on that device)
+static int noalloc_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> addr[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FHPC_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return FHPC_ERR_UNSUPPORTED;
+    void* p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // (two threads that race here look up the same address)
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return FHPC_ERR_HIP;
+        }
+        addr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return FHPC_OK;
+}
+
+int qlinear_lowrank_fwd_noalloc(const void* X, const void* Wq, const void* scales, int qscheme, int block,
+                                const void* A, const void* B, float scaling, void* Y, void* H_out,
+                                int64_t M, int64_t K, int64_t r, int64_t N, void* hip_stream)
+{
+    if (qscheme == FHPC_W_BF16) return FHPC_ERR_DTYPE;
+    if (!X || !Wq || !A || !B || !Y) return FHPC_ERR_NULL;
+    int rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    // what the call would carve, before anything else: a size beyond the fixed array is refused here
+    const size_t need = fhpc_workspace_bytes(FHPC_OP_QLINEAR_FWD, M, K, r, N, FHPC_BF16, qscheme);
+    if (need > (size_t)FHPC_NOALLOC_SCRATCH_BYTES) return FHPC_ERR_WORKSPACE;
+    void* ws = nullptr;
+    rc = noalloc_scratch(&ws);
+    if (rc) return rc;
+    // every region the sequence reads is written earlier in the same call (slabs, H, the merged weight), so
+    // nothing needs clearing between calls; the calls only must not overlap on one GPU
+    return qlinear_fwd_impl(X, Wq, scales, qscheme, block, A, B, 1.f, scaling, Y, H_out, M, K, r, N,
+                            ws, (size_t)FHPC_NOALLOC_SCRATCH_BYTES, hip_stream);
+}
+
 // workspace of the shared-X forward: the single-weight need of every weight (the fallback runs them one
 // after another in the same workspace) and, when the weight-streaming kernels take all of them at
 // once, that launch's slabs
@@ -1578,7 +1630,7 @@ const char* fhpc_status_string(int status)
         case FHPC_ERR_SHAPE: return "invalid shape (sizes must be positive; K and N multiples of 8; K a multiple of the block)";
         case FHPC_ERR_DTYPE: return "unknown dtype or quantisation scheme";
         case FHPC_ERR_ALIGN: return "pointer not sufficiently aligned (16 bytes; workspace 256)";
-        case FHPC_ERR_WORKSPACE: return "workspace missing or smaller than fhpc_workspace_bytes";
+        case FHPC_ERR_WORKSPACE: return "workspace missing or smaller than fhpc_workspace_bytes (the entry point without a workspace argument: the sizes need more than its fixed scratch array)";
         case FHPC_ERR_UNSUPPORTED: return "unsupported configuration (block must be 64; matrices below 2 GiB)";
         case FHPC_ERR_HIP: return "a HIP call or kernel launch failed";
         default: return "unknown status";
