@@ -4,9 +4,11 @@
 A step is one pass of the whole hot path over one batch of synthetic input that is
 already resident in HBM.  Default workload (config 2): forward + backward of the four
 Llama-2-7B attention projections, each factorised with r = 512, on 16384 tokens in bf16.
-Prints ONE JSON line.
+Prints ONE JSON line: the headline workload (value, roofline of its dominant kernel, CPU baseline) and, unless
+--only-headline, every other configuration, the few-token sweep of the quantised layers (the metric's GB/s half)
+and the measured peaks of this GPU.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|merge]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|merge|streams] [--only-headline]
 """
 from __future__ import annotations
 
@@ -17,33 +19,36 @@ import time
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+METRIC = "fwd+bwd TFLOP/s (% bf16 MFMA peak); quantised-path GB/s (% HBM peak)"
 
-# HBM-side traffic per launch of a kernel on a workload (fetched + written bytes), from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_c2_lowrank_gemm_kernels.txt
-# (counter units scaled by a 256 MiB read + 256 MiB write kernel in the same run); None where
-# not measured.  Means over the launches of a step: the q/k/v group's wide products and the o projection's
-# share a kernel.  Algorithmic bytes of a 68.7 GFLOP launch of config 2 are 155-160 MB.
-MEASURED_TRAFFIC_BYTES = {
-    ("c2", "gemm_pp<256x128x64,a0,b1,o0>"): 335.7e6 + 33.6e6,    # H = X A (o), H_all = X A_all (q/k/v)
-    ("c2", "gemm_pp<256x256x32,a0,b1,o0>"): 95.2e6 + 134.2e6,    # Y = H B
-    ("c2", "gemm_pp<256x128x64,a0,b0,o0>"): 168.0e6 + 16.8e6,    # dH = dY B^T
-    ("c2", "gemm_pp<256x256x32,a0,b0,o0>"): 201.0e6 + 134.2e6,   # dX = dH A^T (o), dX = dH_all A_all^T (q/k/v)
-    ("c2", "gemm_pp<256x256x32,a1,b1,o1>"): 414.0e6 + 76.3e6,    # dA_all = X^T dH_all
-    ("c2", "gemm_pp<256x128x64,a1,b1,o1>"): 262.4e6 + 34.6e6,    # dA = X^T dH, dB = H^T dY (4 partial-sum slabs)
-    # profiles/bench_merge_c5_int4_to_bf16.txt: mean over the layer's seven weights (algorithmic 115.1 MB)
-    ("merge", "merge<int4>"): 38.6e6 + 90.6e6,
-    # profiles/bench_c3_ffn_kernels.txt: means over the launches of a step (they differ in shape)
-    ("c3", "gemm_pp<256x256x32,a0,b1,o0>"): 451.5e6 + 191.3e6,
-    ("c3", "gemm_pp<256x256x32,a0,b0,o0>"): 450.3e6 + 119.1e6,
-    ("c3", "gemm_pp<256x256x32,a1,b1,o1>"): 881.0e6 + 81.8e6,
-    # profiles/bench_c4_int8_qlinear_kernels.txt (algorithmic 100.7 MB: X, the merged weight, Y)
-    ("c4", "gemm_pp<256x256x32,a0,b1,o0>"): 201.5e6 + 33.6e6,
-    ("c4", "gemm_pp<256x256x32,a0,b0,o0>"): 201.5e6 + 33.6e6,
-    # profiles/bench_c5_int4_qlinear_kernels.txt: means over the seven linears (algorithmic 132 MB read, 62 / 52 MB
-    # written): the 256x128 launch order gives each XCD's L2 a panel it cannot hold
-    ("c5", "gemm_pp<256x128x64,a0,b1,o0>"): 1021.9e6 + 62.3e6,
-    ("c5", "gemm_pp<256x128x64,a0,b0,o0>"): 1082.4e6 + 52.1e6,
-}
+
+def profiled_traffic(workload, kernel):
+    """HBM-side bytes per launch (fetched + written) of `kernel` on `workload`, read from the committed rocprofv3
+    --pmc summary of the same command (profiles/bench_<workload>_*.txt, section "HBM-side traffic counters"), and
+    the file it came from; (None, None) when no summary lists the kernel.  The bench never measures this itself:
+    hardware counters need the profiler."""
+    import glob
+    import os
+    import re
+    m = re.match(r"gemm_pp<(\d+)x(\d+)x(\d+),a(\d),b(\d),o(\d)(,p)?>", kernel)
+    if m:
+        bm, bn, bk, a, b, o = (int(v) for v in m.groups()[:6])
+        pat = re.compile(r"gemm_pp_kernel<%d, %d, %d, [^>]*?%d, %d, %d>" % (bm, bn, bk, a, b, o))
+    else:
+        pat = re.compile(re.escape(kernel.split("<")[0]))
+    here = os.path.dirname(os.path.abspath(__file__))
+    for path in sorted(glob.glob(os.path.join(here, "profiles", "bench_%s_*.txt" % workload))):
+        in_table = False
+        for line in open(path):
+            if line.startswith("== "):
+                in_table = "HBM-side traffic" in line
+            elif in_table and pat.search(line):
+                cols = line.split()
+                try:
+                    return (float(cols[-2]) + float(cols[-1])) * 1e6, os.path.relpath(path, here)
+                except ValueError:
+                    pass
+    return None, None
 
 
 def parse_args():
@@ -53,6 +58,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "merge", "streams"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-headline", dest="all_configs", action="store_false",
+                    help="time the chosen workload alone (profiler runs); by default the line also carries every other "
+                         "configuration, the few-token sweep of the quantised layers and the measured peaks")
     ap.add_argument("--tokens", type=int, default=0,
                     help="c2/c4/c5: override the configuration's token count (c4/c5: the weight-streaming regime is tokens <= 64, "
                          "the JSON line then quotes GB/s on the algorithmic bytes as the value to read; c2: 48 independent "
@@ -163,21 +171,35 @@ class SharedLowrankCall:
                                            dA_all=self.dA, dBs=self.dB, workspace=self.ws)
 
 
+class QlinearWeights:
+    """A frozen weight quantised on the GPU and its factor pair (shared by calls at several token counts)."""
+
+    def __init__(self, fhpc, K, r, N, scheme, gen):
+        import torch
+        self.K, self.r, self.N, self.scheme = K, r, N, scheme
+        W = randn((K, N), 0.02, torch.float32, gen)
+        self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)
+        del W
+        self.A = randn((K, r), K ** -0.5, torch.bfloat16, gen)
+        self.B = randn((r, N), 0.01, torch.bfloat16, gen)
+
+    def packed_bytes(self):
+        return self.Wq.numel() * self.Wq.element_size() + 2 * self.sc.numel()
+
+
 class QlinearCall:
-    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False, forward_only=False, premerged=False):
+    def __init__(self, fhpc, M, K, r, N, scheme, gen, scaling=2.0, recompute=False, forward_only=False, premerged=False,
+                 weights=None):
         import torch
         bf = torch.bfloat16
         self.f = fhpc
         self.forward_only = forward_only
         self.Wm = torch.empty((K, N), dtype=bf, device="cuda") if premerged else None
         self.M, self.K, self.r, self.N, self.scheme, self.s = M, K, r, N, scheme, scaling
-        W = randn((K, N), 0.02, torch.float32, gen)
-        self.Wq, self.sc = fhpc.qweight_quantize(W, scheme)       # frozen base weight, quantised on the GPU
-        del W
+        w = weights if weights is not None else QlinearWeights(fhpc, K, r, N, scheme, gen)
+        self.Wq, self.sc, self.A, self.B = w.Wq, w.sc, w.A, w.B       # frozen base weight, quantised on the GPU
         self.X = randn((M, K), 1.0, bf, gen)
         self.dY = randn((M, N), 1.0, bf, gen)
-        self.A = randn((K, r), K ** -0.5, bf, gen)
-        self.B = randn((r, N), 0.01, bf, gen)
         self.Y = torch.empty((M, N), dtype=bf, device="cuda")
         self.H = torch.empty((M, r), dtype=bf, device="cuda")
         self.dX = torch.empty((M, K), dtype=bf, device="cuda")
@@ -331,7 +353,7 @@ class FfnCall:
         ffn.ffn_bwd(self.X, *self.W, self.dY, saved)
 
 
-def build_workload(name, fhpc, recompute, tokens=0, forward_only=False, shape=None, shared_x=False, premerged=False,
+def build_workload(name, fhpc, recompute=False, tokens=0, forward_only=False, shape=None, shared_x=False, premerged=False,
                    independent_x=False):
     import torch
     gen = torch.Generator(device="cuda")
@@ -453,6 +475,185 @@ def cpu_baseline(workload):
     }
 
 
+# ----------------------------------------------------------------------------- timing
+
+def time_steps(step, steps, warmup, graph=False):
+    """W untimed warm-up steps, then K timed steps bracketed by synchronisation; an event after every step gives
+    the per-step durations.  Returns (mean, median, min) in milliseconds; the mean is first event to last."""
+    import statistics
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    timed = step
+    if graph:
+        # the library only enqueues kernels on the current stream (no allocation, no memset), so a
+        # step can be captured as it is
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        timed = g.replay
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        timed()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return ev[0].elapsed_time(ev[steps]) / steps, statistics.median(per), min(per)
+
+
+def kernel_profile(fhpc, step, steps, workload):
+    """A second pass over the same steps with the library's event pair around every launch (on the launch stream):
+    per-kernel averages, and the roofline object of the kernel with the largest share of the time."""
+    import torch
+    fhpc.profile_start(8192)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    recs = fhpc.profile_stop()
+    agg = {}
+    for name, ms, fl, by in recs:
+        a = agg.setdefault(name, [0, 0.0, 0.0, 0.0])
+        a[0] += 1; a[1] += ms; a[2] += fl; a[3] += by
+    kernels = {n: {"launches_per_step": a[0] / steps, "avg_ms": a[1] / a[0], "flops_per_launch": a[2] / a[0],
+                   "tflops": a[2] / a[1] / 1e9 if a[1] > 0 else None,
+                   "bytes_per_launch": a[3] / a[0], "gbs": a[3] / a[1] / 1e6 if (a[1] > 0 and a[3] > 0) else None}
+               for n, a in agg.items()}
+    roofline = None
+    if agg:
+        dom = max(agg, key=lambda n: agg[n][1])
+        k = kernels[dom]
+        share = agg[dom][1] / sum(a[1] for a in agg.values())
+        traffic, source = profiled_traffic(workload, dom)
+        if k["gbs"] is not None:
+            # weight-streaming kernel: algorithmic bytes (packed weight + scales + tokens + its partial sums)
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": k["gbs"] / PEAK_HBM_GBS, "traffic": traffic, "traffic_source": source,
+                        "avg_launch_ms": k["avg_ms"], "share_of_timed_kernels": share}
+        else:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic,
+                        "traffic_source": source, "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": share}
+    return kernels, roofline
+
+
+def measured_peaks(fhpc):
+    """What this GPU delivers with no kernel design in the way: the matrix cores fed from registers (zero operands,
+    and random operands, under which the chip lowers its clock) and a streaming copy / read of 1 GiB."""
+    import torch
+    dev = "cuda"
+    out = {"bf16_mfma_tflops": {"spec": PEAK_BF16_TFLOPS}, "hbm_gbs": {"spec": PEAK_HBM_GBS}}
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    seeds = {"registers_only_zero_operands": torch.zeros(256, dtype=torch.int32, device=dev),
+             "registers_only_random_operands": torch.randn(512, device=dev).to(torch.bfloat16).view(torch.int32)}
+    for name, seed in seeds.items():
+        best = 0.0
+        for _ in range(3):
+            fhpc.probe_mfma(seed, cus, 2000)                      # warm
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = fhpc.probe_mfma(seed, 4 * cus, 20000)            # about 1 ms of matrix instructions per SIMD
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out["bf16_mfma_tflops"][name] = best
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    best = 0.0
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        n = fhpc.probe_copy(src, dst)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    out["hbm_gbs"]["copy_1GiB_read_plus_write"] = best
+    del src, dst
+    return out
+
+
+def summarise(calls, ms_mean, ms_median, ms_min, desc, dtype):
+    flops = sum(c.flops() for c in calls)
+    io = sum(c.io_bytes() for c in calls)
+    d = {"workload": desc, "dtype": dtype, "ms_per_step": ms_mean, "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+         "io_gbs": io / (ms_mean * 1e-3) / 1e9, "frac_hbm_peak_on_io_bytes": io / (ms_mean * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if flops:
+        d["tflops"] = flops / (ms_mean * 1e-3) / 1e12
+        d["tflops_at_median"] = flops / (ms_median * 1e-3) / 1e12
+        d["frac_bf16_mfma_peak"] = d["tflops"] / PEAK_BF16_TFLOPS
+    return d
+
+
+def other_configs(fhpc, headline, independent_x):
+    """Every configuration beside the headline one, each timed on a few steps (they are not the quoted value)."""
+    import gc
+    import torch
+    plan = [("c1", {}, 200, 20), ("c2", {}, 8, 2), ("c2_independent_x", {"independent_x": True}, 8, 2), ("c3", {}, 5, 2),
+            ("c4", {}, 8, 2), ("c5", {}, 5, 2)]
+    out = {}
+    for key, kw, steps, warmup in plan:
+        name = key.split("_")[0]
+        if key == headline and not independent_x:
+            continue
+        calls, desc, dtype = build_workload(name, fhpc, False, **kw)
+
+        def step():
+            for c in calls:
+                c.run()
+        out[key] = summarise(calls, *time_steps(step, steps, warmup), desc, dtype)
+        out[key]["steps"] = steps
+        del calls, step
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
+def quantised_stream(fhpc):
+    """The regime in which the quantised layers are bound by reading their packed weights: configurations 4 and 5 at
+    1, 16 and 64 tokens, forward alone and forward + backward.  A step is the configuration's layer (one int8 linear;
+    the seven int4 linears of a decoder layer); the steps rotate through independent copies of the weights, more than
+    512 MB in all, so that the 256 MB Infinity Cache cannot serve them.  GB/s is on the algorithmic bytes
+    (packed codes + scales once per pass over the weight, tokens in and out, the factor pair and its gradients)."""
+    import gc
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20240214)
+    d, f = 5120, 13824
+    layers = {"c4": ([(4096, 4096)], 8, 8, 32), "c5": ([(d, d)] * 4 + [(d, f), (d, f), (f, d)], 16, 4, 4)}
+    rows = []
+    for cfg, (shapes_, r, scheme, copies) in layers.items():
+        weights = [[QlinearWeights(fhpc, K, r, N, scheme, gen) for K, N in shapes_] for _ in range(copies)]
+        packed = sum(w.packed_bytes() for w in weights[0]) * copies
+        for M in (1, 16, 64):
+            for fwd_only in (True, False):
+                sets = [[QlinearCall(fhpc, M, w.K, r, w.N, scheme, gen, 2.0, False, fwd_only, weights=w) for w in ws]
+                        for ws in weights]
+                state = {"i": 0}
+
+                def step():
+                    for c in sets[state["i"] % copies]:
+                        c.run()
+                    state["i"] += 1
+                mean, med, mn = time_steps(step, 40, 8)
+                io = sum(c.io_bytes() for c in sets[0])
+                rows.append({"config": cfg, "tokens": M, "pass": "fwd" if fwd_only else "fwd+bwd", "ms_per_step": mean,
+                             "ms_per_step_median": med, "ms_per_step_min": mn, "algorithmic_bytes": io,
+                             "gbs": io / (mean * 1e-3) / 1e9, "frac_hbm_peak": io / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                del sets, step
+        rows[-1]["weight_copies"] = copies
+        rows[-1]["packed_weight_bytes_all_copies"] = packed
+        del weights
+        gc.collect()
+        torch.cuda.empty_cache()
+    best = max(rows, key=lambda r_: r_["gbs"])
+    return {"note": "configs 4 and 5 at 1/16/64 tokens: HBM-bound regime of the quantised layers; one step = the "
+                    "configuration's layer, weights rotating through > 512 MB of independent copies",
+            "peak_gbs": PEAK_HBM_GBS, "best_gbs": best["gbs"], "best_frac_hbm_peak": best["frac_hbm_peak"], "rows": rows}
+
+
 # ----------------------------------------------------------------------------- main
 
 def main():
@@ -478,66 +679,17 @@ def main():
         for c in calls:
             c.run()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    timed = step
-    if args.graph:
-        # the library only enqueues kernels on the current stream (no allocation, no memset), so a
-        # step can be captured as it is
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        graph.replay()
-        torch.cuda.synchronize()
-        timed = graph.replay
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        timed()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step, ms_median, ms_min = time_steps(step, args.steps, args.warmup, args.graph)
     tflops = flops / (ms_per_step * 1e-3) / 1e12
+    kernels, roofline = kernel_profile(fhpc, step, args.steps, args.workload)
 
-    # second pass over the same steps with an event pair around every GEMM launch (library hook)
-    fhpc.profile_start(8192)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    recs = fhpc.profile_stop()
-    agg = {}
-    for name, ms, fl, by in recs:
-        a = agg.setdefault(name, [0, 0.0, 0.0, 0.0])
-        a[0] += 1; a[1] += ms; a[2] += fl; a[3] += by
-    kernels = {n: {"launches_per_step": a[0] / args.steps, "avg_ms": a[1] / a[0], "flops_per_launch": a[2] / a[0],
-                   "tflops": a[2] / a[1] / 1e9 if a[1] > 0 else None,
-                   "bytes_per_launch": a[3] / a[0], "gbs": a[3] / a[1] / 1e6 if (a[1] > 0 and a[3] > 0) else None}
-               for n, a in agg.items()}
-    roofline = None
-    if agg:
-        # the kernel the roofline is quoted for: the one with the largest share of the timed kernels'
-        # time (a GEMM, quoted in TFLOP/s, or a streaming kernel, quoted in GB/s on its algorithmic bytes)
-        dom = max(agg, key=lambda n: agg[n][1])
-        k = kernels[dom]
-        share = agg[dom][1] / sum(a[1] for a in agg.values())
-        if k["gbs"] is not None:
-            # weight-streaming kernel: algorithmic bytes (packed weight + scales + tokens + its partial sums)
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": k["gbs"] / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
-                        "avg_launch_ms": k["avg_ms"], "share_of_timed_kernels": share}
-        else:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
-                        "avg_launch_ms": k["avg_ms"], "share_of_gemm_time": share}
-
-    metric, value, unit = "fwd+bwd TFLOP/s", tflops, "TFLOP/s"
+    metric, value, unit = METRIC, tflops, "TFLOP/s"
     if args.workload in ("merge", "streams"):       # streaming passes: quoted in bytes moved
         metric, value, unit = args.workload + " GB/s", io_bytes / (ms_per_step * 1e-3) / 1e9, "GB/s"
     out = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_median": ms_median,
+        "ms_per_step_min": ms_min, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": desc, "saved_H": not args.recompute, "hip_graph": bool(args.graph),
                    "merged_once_per_step": bool(args.premerged)},
@@ -551,6 +703,16 @@ def main():
         for _ in range(3):
             torch.add(x, 1.0, out=y)
         torch.cuda.synchronize()
+    plain = not (args.tokens or args.forward_only or shape or args.shared_x or args.premerged or args.graph or args.recompute)
+    if args.all_configs and plain and args.workload in ("c1", "c2", "c3", "c4", "c5"):
+        # the other half of the metric and the other configurations, in the same line
+        del calls
+        torch.cuda.empty_cache()
+        out["peaks_measured"] = measured_peaks(fhpc)
+        out["configs"] = other_configs(fhpc, args.workload, args.independent_x)
+        out["quantised_stream"] = quantised_stream(fhpc)
+        out["quantised_path_gbs"] = out["quantised_stream"]["best_gbs"]
+        out["quantised_path_frac_hbm_peak"] = out["quantised_stream"]["best_frac_hbm_peak"]
     if not args.no_cpu_baseline and args.workload not in ("merge", "streams"):
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))

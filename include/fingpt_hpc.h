@@ -300,6 +300,16 @@ int fhpc_profile_start(int max_records);
 int fhpc_profile_stop(void);
 int fhpc_profile_get(int index, char* name, int name_len, float* ms, double* flops, double* bytes);
 
+/* Measurement probes: what this GPU delivers with no kernel design in the way, for a benchmark that quotes its
+ * kernels against measured ceilings beside the published ones.
+ * fhpc_probe_mfma: `workgroups` x 4 waves each issue iters * 8 v_mfma_f32_32x32x16_bf16 back to back from
+ * registers, with no memory traffic; seed (device, 256 x uint32) holds the operand words of a wave (all zero, or
+ * random bf16 pairs: the matrix pipes' clock under load depends on the data).  *flops (host) receives the
+ * flop count of the launch.  sink (device, workgroups * 256 floats) may be NULL.
+ * fhpc_probe_copy: dst[0 .. bytes) = src[0 .. bytes), 16 bytes per lane; bytes a multiple of 16. */
+int fhpc_probe_mfma(const void* seed, int workgroups, int iters, float* sink, double* flops, void* hip_stream);
+int fhpc_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
+
 /* Host-only test hook (needs no GPU, touches no memory): walks the launch sequence of an entry point for
  * these sizes without launching anything and reports, in bytes, the largest partial-sum area any of its
  * split reductions would use (*planned) and what the workspace layout reserves for them (*reserved).

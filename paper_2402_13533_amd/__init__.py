@@ -26,7 +26,7 @@ EXPORTS = [
     "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
-    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc",
+    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc", "fhpc_probe_mfma", "fhpc_probe_copy",
 ]
 
 _lib = None
@@ -87,6 +87,8 @@ def load_library():
     lib.fhpc_profile_get.argtypes = [i32, C.c_char_p, i32, C.POINTER(C.c_float), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double)]
     lib.fhpc_plan_slab_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32, i32, i32, f32, C.POINTER(i64), C.POINTER(i64)]
+    lib.fhpc_probe_mfma.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
+    lib.fhpc_probe_copy.argtypes = [vp, vp, i64, vp]
     lib.fhpc_status_string.argtypes = [i32]
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
@@ -117,6 +119,24 @@ def profile_stop():
             raise FhpcError(rc, "fhpc_profile_get")
         out.append((buf.value.decode(), float(ms.value), float(fl.value), float(by.value)))
     return out
+
+
+def probe_mfma(seed, workgroups: int, iters: int) -> float:
+    """Enqueue the register-only matrix-core loop on the current stream; returns the launch's flop count."""
+    fl = C.c_double(0.0)
+    rc = load_library().fhpc_probe_mfma(_ptr(seed), workgroups, iters, None, C.byref(fl), _stream())
+    if rc:
+        raise FhpcError(rc, "fhpc_probe_mfma")
+    return float(fl.value)
+
+
+def probe_copy(src, dst) -> int:
+    """Enqueue the streaming copy dst = src on the current stream; returns the bytes copied."""
+    n = src.numel() * src.element_size()
+    rc = load_library().fhpc_probe_copy(_ptr(src), _ptr(dst), n, _stream())
+    if rc:
+        raise FhpcError(rc, "fhpc_probe_copy")
+    return n
 
 
 def status_string(status: int) -> str:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfingpt_hpc.so")
-SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_pp.hip", "gemm_w4.hip", "kernels_misc.hip", "merge.hip", "qskinny.hip", "qskinny_dx.hip", "profile.hip"]
+SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_pp.hip", "gemm_w4.hip", "kernels_misc.hip", "merge.hip", "qskinny.hip", "qskinny_dx.hip", "profile.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -175,6 +175,18 @@ struct Feeder<OP_KC, R, BK, NW> {
         describe(op, dim, kdim);
         set_tile(op, row0, dim, wave, lane);
     }
+    // request j of the tile that starts at row `row0`, its lane offset formed on the spot (for the few
+    // requests a kernel makes on behalf of another output tile than the one set_tile was called for)
+    __device__ __forceinline__ void issue_one_for(const GemmOperand& op, int row0, int dim, unsigned char* tile, int k0,
+                                                  int kend, int wave, int lane, int j)
+    {
+        const int r_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
+        const int row = (wave * PER + j) * RPB + r_in_blk;
+        const int lg = (phys ^ Tile::swz(row)) & (Tile::CPR - 1);
+        const uint32_t vo = ((uint32_t)(row0 + row) * (uint32_t)op.ld + (uint32_t)lg * 8u) * 2u;
+        const uint32_t kofs = (k0 + lg * 8 < kend) ? (uint32_t)k0 * 2u : OOB;
+        dma_16B(rs, lds_addr(tile) + (uint32_t)((wave * PER + j) * 1024), vo + kofs);
+    }
     __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
     {
         const uint32_t kofs = (k0 + logical[j] * 8 < kend) ? (uint32_t)k0 * 2u : OOB;
@@ -218,6 +230,17 @@ struct Feeder<OP_XC, R, BK, NW> {
     {
         describe(op, dim, kdim);
         set_tile(op, row0, dim, wave, lane);
+    }
+    __device__ __forceinline__ void issue_one_for(const GemmOperand& op, int row0, int dim, unsigned char* tile, int k0,
+                                                  int kend, int wave, int lane, int j)
+    {
+        const int k_in_blk = lane / Tile::CPR, phys = lane % Tile::CPR;
+        const int k = (wave * PER + j) * KPB + k_in_blk;
+        const int lg = (phys ^ Tile::swz(k)) & (Tile::CPR - 1);
+        const int row = row0 + lg * 8;
+        const uint32_t vo = (row < dim) ? ((uint32_t)k * (uint32_t)op.ld + (uint32_t)row) * 2u : OOB;
+        const uint32_t kofs = (k0 < kend) ? (uint32_t)k0 * ldb : OOB;
+        dma_16B(rs, lds_addr(tile) + (uint32_t)((wave * PER + j) * 1024), vo + kofs);
     }
     __device__ __forceinline__ void issue_one(unsigned char* tile, int k0, int kend, int wave, int j)
     {
