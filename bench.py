@@ -155,7 +155,7 @@ class SharedLowrankCall:
         self.dA = torch.empty((K, g * r), dtype=torch.float32, device="cuda")
         self.dB = [torch.empty((r, N), dtype=torch.float32, device="cuda") for _ in range(g)]
         need = max(self.lib.fhpc_workspace_bytes_lowrank_shared_x(b, M, K, r, N, g) for b in (0, 1))
-        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        self.ws = torch.zeros(max(need, 256), dtype=torch.uint8, device="cuda")      # (the header must start out zero)
 
     def flops(self):
         from paper_2402_13533_amd import shapes
@@ -637,11 +637,21 @@ def quantised_stream(fhpc):
                     for c in sets[state["i"] % copies]:
                         c.run()
                     state["i"] += 1
-                mean, med, mn = time_steps(step, 40, 8)
                 io = sum(c.io_bytes() for c in sets[0])
-                rows.append({"config": cfg, "tokens": M, "pass": "fwd" if fwd_only else "fwd+bwd", "ms_per_step": mean,
-                             "ms_per_step_median": med, "ms_per_step_min": mn, "algorithmic_bytes": io,
-                             "gbs": io / (mean * 1e-3) / 1e9, "frac_hbm_peak": io / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                # eager launches from this process, then the same steps replayed from a HIP graph (one graph holds a
+                # step on every copy of the weights; a serving loop would replay such a graph), which takes the
+                # host's launch cost out
+                for launch in ("eager", "hip_graph"):
+                    if launch == "eager":
+                        mean, med, mn = time_steps(step, 40, 8)
+                    else:
+                        def all_copies():
+                            for _ in range(copies):
+                                step()
+                        mean, med, mn = (t / copies for t in time_steps(all_copies, 10, 2, graph=True))
+                    rows.append({"config": cfg, "tokens": M, "pass": "fwd" if fwd_only else "fwd+bwd", "launch": launch,
+                                 "ms_per_step": mean, "ms_per_step_median": med, "ms_per_step_min": mn, "algorithmic_bytes": io,
+                                 "gbs": io / (mean * 1e-3) / 1e9, "frac_hbm_peak": io / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
                 del sets, step
         rows[-1]["weight_copies"] = copies
         rows[-1]["packed_weight_bytes_all_copies"] = packed

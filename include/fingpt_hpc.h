@@ -12,7 +12,13 @@
  *    pointer owned by the caller; the library never allocates, frees or retains
  *    device memory.  Scratch comes from `workspace` (device pointer, 256-byte
  *    aligned, size from fhpc_workspace_bytes); too small => FHPC_ERR_WORKSPACE
- *    and nothing is launched.
+ *    and nothing is launched.  Every workspace layout begins with a header of
+ *    FHPC_WORKSPACE_HEADER_BYTES that holds arrival counters of the weight-streaming
+ *    launches (a launch's last workgroup to reach a block of outputs finishes it).  The
+ *    header must be ZERO when a buffer is first handed to the library (clear the buffer
+ *    once after allocating it); every call leaves the header zero again, so a buffer
+ *    can be reused from call to call, by any entry point, without clearing, also under
+ *    HIP graph replay.  The rest of a workspace may hold anything.
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued asynchronously; no call synchronises.  Inputs, outputs and
  *    workspace must stay alive and untouched until the stream has passed the
@@ -25,7 +31,7 @@
  *    prints.  HIP launch failures map to FHPC_ERR_HIP.
  *  - dA and dB are produced in fp32.  Reductions over tokens are cut into slices
  *    whose partial sums go to separate slabs of the workspace and are added in a
- *    fixed order: no atomics, results are bit-reproducible from run to run.
+ *    fixed order: no floating-point atomics, results are bit-reproducible from run to run.
  */
 #ifndef FINGPT_HPC_H
 #define FINGPT_HPC_H
@@ -36,6 +42,8 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+#define FHPC_WORKSPACE_HEADER_BYTES 16384
 
 /* dtype of X, A, B, Y, dY, dX, H (dA/dB are always fp32) */
 enum { FHPC_F32 = 0, FHPC_BF16 = 1 };

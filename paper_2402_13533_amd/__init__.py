@@ -205,7 +205,8 @@ def get_workspace(nbytes: int, device):
     key = (str(device), int(torch.cuda.current_stream(device).cuda_stream))
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        # zero once: the library keeps the workspace header (arrival counters) zero from call to call
+        ws = torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
         _workspaces[key] = ws
     return ws
 
@@ -274,7 +275,7 @@ def _shared_ws(backward, M, K, r, N, g, device, workspace):
     torch = _torch()
     need = int(load_library().fhpc_workspace_bytes_lowrank_shared_x(int(backward), M, K, r, N, g))
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+        workspace = torch.zeros(max(need, 256), dtype=torch.uint8, device=device)
     return workspace, workspace.numel()
 
 

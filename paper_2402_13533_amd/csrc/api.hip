@@ -16,6 +16,7 @@ namespace {
 constexpr int64_t kMaxBytes = (int64_t)1 << 31;   // per-matrix limit of the 32-bit buffer offsets
 // compute units of the current device: every plan below is sized for it
 inline int num_cu() { return compute_units(); }
+static_assert(QSKINNY_HEADER_BYTES == FHPC_WORKSPACE_HEADER_BYTES, "the header size is part of the ABI");
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -71,6 +72,7 @@ struct Carver {
 // Buffers an entry point may need, laid out identically by the measuring pass and the
 // real pass.
 struct Scratch {
+    uint32_t* header = nullptr; // first QSKINNY_HEADER_BYTES of every workspace: arrival counters, zero between calls
     void* A_p = nullptr;    // bf16 [K][rp]   zero-padded copy of A when r % 8 != 0
     void* B_p = nullptr;    // bf16 [rp][N]
     void* H = nullptr;      // bf16 [M][rp]
@@ -303,6 +305,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
               bool premerged = false)
 {
     Scratch s;
+    s.header = static_cast<uint32_t*>(c.take(QSKINNY_HEADER_BYTES));
     if (dtype == FHPC_F32) {
         // fp32 path: H and dH in fp32, no padding
         s.H = c.take(M * r * 4);
@@ -622,7 +625,8 @@ size_t merge_workspace(int64_t K, int64_t r, int64_t N)
 {
     (void)N;
     const int64_t rp = rank_pad(r);
-    return (rp != r) ? (size_t)round_up(K * rp * 2, 256) : 0;      // a zero-padded copy of A
+    // a zero-padded copy of A, behind the header every workspace starts with
+    return (rp != r) ? (size_t)QSKINNY_HEADER_BYTES + (size_t)round_up(K * rp * 2, 256) : 0;
 }
 
 // ---------------- rank-r factor pair of a pretrained weight ----------------
@@ -647,6 +651,7 @@ struct DecompScratch {
 DecompScratch carve_decompose(Carver& c, int64_t K, int64_t r, int64_t N)
 {
     DecompScratch d;
+    (void)c.take(QSKINNY_HEADER_BYTES);                // every workspace starts with the header (unused here)
     const int64_t R = K > N ? K : N;
     d.Yb = c.take(K * r * 2);
     d.Zb = c.take(N * r * 2);
@@ -879,6 +884,7 @@ static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int
 {
     SharedScratch s;
     const int64_t R = r * g;
+    (void)c.take(QSKINNY_HEADER_BYTES);                // every workspace starts with the header (unused here)
     s.H = c.take(M * R * 2);
     if (bwd) s.dH = c.take(M * R * 2);
     if (r <= 32) s.Pf = static_cast<float*>(c.take(M * (R <= 32 ? R : r) * 4));
@@ -1026,7 +1032,7 @@ static int seq_qlinear_fwd(Run& run, const Scratch& s, const void* X, const void
     if (s.sk_part) {
         const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
         const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};
-        FHPC_LAUNCH(run, launch_qskinny_fwd(X, &job, 1, qscheme, M, K, r, p, s.sk_part, s.sk_hpart, run.st));
+        FHPC_LAUNCH(run, launch_qskinny_fwd(X, &job, 1, qscheme, M, K, r, p, s.sk_part, s.sk_hpart, s.header, run.st));
         return FHPC_OK;
     }
     const int64_t rp = rank_pad(r);
@@ -1172,7 +1178,7 @@ static size_t shared_x_workspace(const int64_t* N, int count, int64_t M, int64_t
     }
     if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
         const QskinnyPlan p = qskinny_plan(M, K, r, N, count, num_cu());
-        const size_t fused = (size_t)round_up(p.part_bytes, 256) + (size_t)round_up(p.hpart_bytes, 256);
+        const size_t fused = (size_t)QSKINNY_HEADER_BYTES + (size_t)round_up(p.part_bytes, 256) + (size_t)round_up(p.hpart_bytes, 256);
         if (fused > need) need = fused;
     }
     return need;
@@ -1213,6 +1219,7 @@ int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weigh
         // few tokens: every weight in one pair of launches
         const QskinnyPlan p = qskinny_plan(M, K, r, N, count, num_cu());
         Carver c(workspace);
+        uint32_t* header = static_cast<uint32_t*>(c.take(QSKINNY_HEADER_BYTES));
         float* part = static_cast<float*>(c.take(p.part_bytes));
         float* hpart = static_cast<float*>(c.take(p.hpart_bytes));
         QskinnyJob jobs[QSKINNY_MAX_JOBS];
@@ -1220,7 +1227,7 @@ int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weigh
             const fhpc_qlinear_weight& w = weights[j];
             jobs[j] = QskinnyJob{w.Wq, w.scales, w.A, w.B, w.Y, w.H_out, w.N, 1.f, w.scaling};
         }
-        FHPC_HIP(launch_qskinny_fwd(X, jobs, count, qscheme, M, K, r, p, part, hpart, st));
+        FHPC_HIP(launch_qskinny_fwd(X, jobs, count, qscheme, M, K, r, p, part, hpart, header, st));
         return FHPC_OK;
     }
     // otherwise: the single-weight path, one weight after another on the stream
@@ -1444,8 +1451,9 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
     if (need) {
         if (!workspace || workspace_bytes < need) return FHPC_ERR_WORKSPACE;
         if (!aligned(workspace, 256)) return FHPC_ERR_ALIGN;
-        FHPC_HIP(launch_pad2d_u16(A, r, K, r, workspace, rp, K, st));
-        Ap = workspace;
+        void* const Apad = static_cast<unsigned char*>(workspace) + QSKINNY_HEADER_BYTES;
+        FHPC_HIP(launch_pad2d_u16(A, r, K, r, Apad, rp, K, st));
+        Ap = Apad;
     }
     FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, 1.f, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
     return FHPC_OK;

@@ -13,7 +13,7 @@ struct QskinnyPlan {
     int kchunks;           // partial sums of H = X A, per weight
     int row_blocks;        // 64-channel blocks of all weights together
     int64_t part_bytes;    // splits * M * 64 * row_blocks * 4
-    int64_t hpart_bytes;   // count * kchunks * M * r * 4
+    int64_t hpart_bytes;   // count * (kchunks + 1) * M * r * 4: the chunk sums, then H
 };
 
 // One weight of a launch: Y[M,N] bf16 = base_scale X deq(Wq) + scaling (X A) B;  H_out (M x r bf16) optional.
@@ -34,9 +34,13 @@ bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme);
 // `count` weights (at most QSKINNY_MAX_JOBS) with output widths N[0..count) that share X, K and r
 QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int count, int num_cu);
 
-// All weights in one launch pair.  part and hpart are scratch of the plan's sizes.
+// Words of the workspace header (QSKINNY_HEADER_BYTES at the start of every workspace) that the weight-streaming
+// launches use as arrival counters.  They must be zero when a launch starts and are zero again when it ends.
+constexpr int QSKINNY_HEADER_BYTES = 16384;
+
+// All weights in one launch.  part and hpart are scratch of the plan's sizes; tickets is the workspace header.
 hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, int scheme, int64_t M, int64_t K, int64_t r,
-                              const QskinnyPlan& p, float* part, float* hpart, hipStream_t st);
+                              const QskinnyPlan& p, float* part, float* hpart, uint32_t* tickets, hipStream_t st);
 
 // ---- input gradient dX for a handful of tokens (csrc/qskinny_dx.hip)
 struct QskinnyDxPlan {

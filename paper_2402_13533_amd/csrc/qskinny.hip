@@ -20,15 +20,21 @@
 // int8 (one scale per output channel).  The weight is thus used unrounded.
 //
 // Work split: a workgroup of four waves owns 64 output channels (16 per wave) and one slice
-// of the reduction; slices write fp32 partial sums to slabs; a finishing kernel adds the slabs
-// and the rank-r branch and rounds to bf16.  H = X * A is formed in 128-deep chunks by extra
-// workgroups appended to the same grid.
+// of the reduction; slices write fp32 partial sums to slabs.  H = X * A is formed in 128-deep
+// chunks by extra workgroups at the head of the same grid (the last of them to arrive adds the
+// chunks up and raises a flag).  There is one launch: the slice that is the last to arrive at a
+// 64-channel block (a ticket counter per block in the workspace header) adds the slabs and the
+// rank-r branch and rounds to bf16.  It looks at H's flag a bounded number of times and
+// otherwise forms H itself, in the same order of sums, so that no wave ever waits without an
+// end and the result does not depend on which happened.  Every counter and flag is put back
+// to zero by the launch itself: nothing has to be cleared between launches.
 #include "qskinny.h"
 #include "profile.h"
 
 #include <hip/hip_fp16.h>
 #include <type_traits>
 #include <stdio.h>
+#include <stdlib.h>
 
 namespace fhpc {
 namespace skinny {
@@ -38,6 +44,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int NT = 256;
+#ifdef FHPC_TRACE
+__device__ unsigned long long g_qtrace[2048 * 8];
+#define QTS(slot) do { if (threadIdx.x == 0 && blockIdx.x < 2048) g_qtrace[blockIdx.x * 8 + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define QTS(slot) do { } while (0)
+#endif
 constexpr int ROWS_WG = 64;            // output channels per workgroup
 constexpr int TOK = 16;                // token rows of the MFMA tile
 // Reduction depth per pipeline step: 512, or 256 (template parameter SD).  The double-buffered token
@@ -161,6 +173,19 @@ __device__ __forceinline__ uint32_t x_off(int tok, int chunk)
     return (uint32_t)tok * (DEPTH * 2) + (uint32_t)(((chunk ^ tok) & (DEPTH / 8 - 1)) << 4);
 }
 
+// Data that one workgroup writes and another reads within the launch (slabs, chunk sums of H, H) moves with
+// device-scope accesses: a store goes through to the level all compute units share and a load comes from there,
+// instruction by instruction.  (Ordinary accesses would need a device-scope fence on either side, which writes
+// back and invalidates a whole L2 on this chip: measured, that made a launch 8 to 50 times slower.)
+__device__ __forceinline__ void shared_store(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float shared_load(const float* p)
+{
+    return __hip_atomic_load(const_cast<float*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // hpart[kc][m][j] = sum over the 128-deep chunk kc of X[m][k] A[k][j]   (fp32, m < M, j < r).
 // Run by the extra workgroups at the end of the streaming kernel's grid, so that H = X A costs no
 // launch of its own.  The chunk of X ([M][128]) and of A ([128][r]) is copied to LDS with
@@ -200,15 +225,162 @@ __device__ __forceinline__ void hpart_body(unsigned char* smem, int kc, const ui
                 s0 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k] << 16), __uint_as_float((uint32_t)As[k * r + j] << 16), s0);
                 s1 = fmaf(__uint_as_float((uint32_t)Xs[m * H_XLD + k + 1] << 16), __uint_as_float((uint32_t)As[(k + 1) * r + j] << 16), s1);
             }
-            hpart[((int64_t)kc * M + m) * r + j] = s0 + s1;
+            shared_store(hpart + ((int64_t)kc * M + m) * r + j, s0 + s1);
         }
     }
 }
 
+// Arrival at a counter in the workspace header.  Every thread waits until its own shared_stores have been
+// acknowledged, the workgroup meets, and one thread draws the ticket (the number of earlier arrivals).  The
+// workgroup that draws the last ticket may shared_load what all earlier arrivals stored.
+__device__ __forceinline__ uint32_t arrive(uint32_t* counter, uint32_t* s_ticket)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0) *s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t t = *s_ticket;
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return t;
+}
+
+// The 64-channel block rb is complete (all slices' slabs and H are in memory): Y = bf16(base_scale * sum of the slabs
+// + scaling * H B) for its channels and every token.  One workgroup; thread (c = tid % 64, tg = tid / 64) takes
+// channel c and the tokens tg, tg + 4, ...  H (fp32, [M][r]) is staged in LDS.  The rank-r sums come first, sixteen
+// ranks of the thread's column of B in registers at a time, and wait in LDS ([M][64]) for the slab sums: few
+// registers, so that this tail does not lower the occupancy the streaming loop was planned for.
+__device__ __forceinline__ void finish_block(unsigned char* smem, int rb, const SkinnyJobs& jb, const float* __restrict__ part,
+                                             int splits, const float* __restrict__ hsum_all, const uint32_t* hready, int poll_limit,
+                                             const uint16_t* __restrict__ X, int K, int M, int r)
+{
+    float* Hs = reinterpret_cast<float*>(smem);                 // [M][r], at most 64 x 64 floats
+    const int job = job_of_block(jb, rb);
+    const int N = pick(jb.N, job);
+    const uint16_t* const B = static_cast<const uint16_t*>(pick(jb.B, job));
+    uint16_t* const Y = static_cast<uint16_t*>(pick(jb.Y, job));
+    const float base_scale = pick(jb.base_scale, job), scaling = pick(jb.scaling, job);
+    const float* const hsum = hsum_all + (int64_t)job * M * r;
+    const int ld_part = jb.rb0[jb.count] * ROWS_WG;
+    const int c = threadIdx.x & 63, tg = threadIdx.x >> 6;
+    const int ncomb = rb * ROWS_WG + c;
+    const int n = (rb - pick_rb0(jb, job)) * ROWS_WG + c;
+    const int nc = n < N ? n : N - 1;
+    const __amdgpu_buffer_rsrc_t rB = rsrc(B, (int64_t)r * N * 2);
+    auto slab_batch = [&](float (&v)[8], int m, int sp0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 8; q++) {
+            const int sp = sp0 + q;
+            const float x = shared_load(part + ((int64_t)(sp < splits ? sp : sp0) * M + m) * ld_part + ncomb);
+            v[q] = (sp < splits) ? x : 0.f;
+        }
+    };
+    auto sum8 = [](const float (&v)[8]) __attribute__((always_inline)) {
+        return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    };
+    // the first tokens' slab values and the first sixteen ranks of B's column are requested before anything waits
+    float v[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; u++) slab_batch(v[u], (tg + 4 * u < M) ? tg + 4 * u : tg, 0);
+    float b0[16];
+#pragma unroll
+    for (int j = 0; j < 16; j++) {                               // (a row beyond r reads as zero)
+        const uint32_t off = (j < r) ? (uint32_t)(j * N + nc) * 2u : OOB;
+        b0[j] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rB, off, 0, 0) << 16);
+    }
+    // H is formed by the workgroups at the head of the grid, which wait for nobody, so it is normally complete
+    // long before a block's last slice arrives; one thread looks at the weight's flag, a bounded number of times.
+    __shared__ uint32_t s_ready;
+    if (threadIdx.x == 0) {
+        uint32_t ok = 0;
+        for (int polls = 0; polls <= poll_limit && !ok; polls++) {
+            ok = __hip_atomic_load(const_cast<uint32_t*>(hready + job), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!ok) __builtin_amdgcn_s_sleep(8);
+        }
+        s_ready = ok;
+    }
+    __syncthreads();
+    if (s_ready) {
+        for (int i = threadIdx.x; i < M * r; i += NT) Hs[i] = shared_load(hsum + i);
+    } else {
+        // Not complete within the bound (never seen; it is what lets every wave end whatever the order in which
+        // the hardware starts workgroups): this workgroup forms H itself, with the very sums and the very
+        // order of the chunk workgroups, so the result is the same bits.
+        const uint16_t* const A = static_cast<const uint16_t*>(pick(jb.A, job));
+        for (int i = threadIdx.x; i < M * r; i += NT) {
+            const int m = i / r, j = i - m * r;
+            float t = 0.f;
+            for (int k0 = 0; k0 < K; k0 += HCHUNK) {
+                const int kn = (K - k0 < HCHUNK) ? K - k0 : HCHUNK;
+                float s0 = 0.f, s1 = 0.f;
+                for (int k = 0; k + 1 < kn; k += 2) {
+                    s0 = fmaf(__uint_as_float((uint32_t)X[(int64_t)m * K + k0 + k] << 16), __uint_as_float((uint32_t)A[(int64_t)(k0 + k) * r + j] << 16), s0);
+                    s1 = fmaf(__uint_as_float((uint32_t)X[(int64_t)m * K + k0 + k + 1] << 16), __uint_as_float((uint32_t)A[(int64_t)(k0 + k + 1) * r + j] << 16), s1);
+                }
+                t += s0 + s1;
+            }
+            Hs[i] = t;
+        }
+    }
+    __syncthreads();
+    // Four of the thread's tokens at a time, so that their slab values are all in flight together (the work is a
+    // chain of memory round trips and little else).
+    for (int mb = tg; mb < M; mb += 16) {
+        if (mb != tg) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) slab_batch(v[u], (mb + 4 * u < M) ? mb + 4 * u : mb, 0);
+        }
+        float l[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int j0 = 0; j0 < r; j0 += 16) {
+            float b[16];
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                if (j0 == 0) {
+                    b[j] = b0[j];
+                } else {
+                    const uint32_t off = (j0 + j < r) ? (uint32_t)((j0 + j) * N + nc) * 2u : OOB;
+                    b[j] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rB, off, 0, 0) << 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int m = (mb + 4 * u < M) ? mb + 4 * u : mb;
+#pragma unroll
+                for (int j = 0; j < 16; j++) l[u] = fmaf(Hs[m * r + (j0 + j < r ? j0 + j : 0)], b[j], l[u]);
+            }
+        }
+        float base[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) base[u] = sum8(v[u]);
+        for (int sp0 = 8; sp0 < splits; sp0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) slab_batch(v[u], (mb + 4 * u < M) ? mb + 4 * u : mb, sp0);
+#pragma unroll
+            for (int u = 0; u < 4; u++) base[u] += sum8(v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int m = mb + 4 * u;
+            if (n < N && m < M) {
+                const __bf16 yb = (__bf16)(base_scale * base[u] + scaling * l[u]);
+                Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
+            }
+        }
+    }
+    __syncthreads();                                            // Hs is reused if this workgroup finishes another block
+}
+
+// Header words: one ticket per 64-channel block; then, per weight, an arrival counter for the chunks of H = X A and
+// a flag that H is complete; then the number of finished blocks of the launch.
+constexpr int TICKETS = 4080;
+constexpr int HCOUNT = TICKETS, HREADY = TICKETS + QSKINNY_MAX_JOBS, DONE = TICKETS + 2 * QSKINNY_MAX_JOBS;
+static_assert((DONE + 1) * 4 <= QSKINNY_HEADER_BYTES, "header words");
+
 template <int SCHEME, int TT, int SD>
 __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, SkinnyJobs jb, float* __restrict__ part,
                                                          int M, int K, int k_chunk, float* __restrict__ hpart, int r,
-                                                         int kchunks, int main_grid)
+                                                         int kchunks, int head_grid, int splits, uint32_t* __restrict__ tickets,
+                                                         float* __restrict__ hsum, int poll_limit)
 {
     constexpr bool I4 = (SCHEME == 4);
     constexpr int WLOADS = I4 ? SD / 128 : SD / 64;  // 16-byte weight loads per lane per step
@@ -219,19 +391,77 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     // (the H = X A workgroups reuse the token tiles' LDS)
     constexpr int LDS_BYTES = (2 * XS_BYTES > h_lds_bytes(TOKS)) ? 2 * XS_BYTES : h_lds_bytes(TOKS);
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+    static_assert(LDS_BYTES >= 64 * 64 * 4, "the finish stages H ([M][r] fp32) in the same LDS");
     unsigned char* const xs[2] = {smem, smem + XS_BYTES};
-    if ((int)blockIdx.x >= main_grid) {
-        // the H = X A chunks: kchunks workgroups per weight
-        const int idx = (int)blockIdx.x - main_grid, hj = idx / kchunks, kc = idx - hj * kchunks;
-        hpart_body<TOKS>(smem, kc, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(pick(jb.A, hj)),
-                         hpart + (int64_t)hj * kchunks * M * r, M, K, r);
+    __shared__ uint32_t s_ticket;
+    const int row_blocks = jb.rb0[jb.count];                   // of all weights together
+    // a 64-channel block counts its `splits` slices
+    const uint32_t last_ticket = (uint32_t)(splits - 1);
+    // One thread, after a block is finished or a weight's flag is set: the last of these events of the launch
+    // (row_blocks + count of them) puts the remaining header words back to zero.  By then every block has been
+    // finished, so every workgroup has arrived and nobody reads the flags any more.
+    auto done = [&]() __attribute__((always_inline)) {
+        if (__hip_atomic_fetch_add(tickets + DONE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(row_blocks + jb.count - 1)) {
+            __hip_atomic_store(tickets + DONE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int j = 0; j < QSKINNY_MAX_JOBS; j++)
+                __hip_atomic_store(tickets + HREADY + j, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    auto finish = [&](int rb) __attribute__((always_inline)) {
+        finish_block(smem, rb, jb, part, splits, hsum, tickets + HREADY, poll_limit, static_cast<const uint16_t*>(X), K, M, r);
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(tickets + rb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            done();
+        }
+    };
+    QTS(0);
+    if ((int)blockIdx.x < head_grid) {
+        // the H = X A chunks: kchunks workgroups per weight, at the head of the grid so that they start first
+        const int idx = (int)blockIdx.x, hj = idx / kchunks, kc = idx - hj * kchunks;
+        float* const hp = hpart + (int64_t)hj * kchunks * M * r;
+        hpart_body<TOKS>(smem, kc, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(pick(jb.A, hj)), hp, M, K, r);
+        QTS(1);
+        if (arrive(tickets + HCOUNT + hj, &s_ticket) != (uint32_t)(kchunks - 1)) return;
+        QTS(2);
+        // the last chunk of this weight: H = the sum of the chunks, in chunk order (the same order every run)
+        uint16_t* const H_out = static_cast<uint16_t*>(pick(jb.H_out, hj));
+        float* const hs = hsum + (int64_t)hj * M * r;
+        for (int i = threadIdx.x; i < M * r; i += NT) {
+            float t = 0.f;
+            for (int c0 = 0; c0 < kchunks; c0 += 48) {         // 48 loads in flight, added in chunk order
+                float v[48];
+#pragma unroll
+                for (int q = 0; q < 48; q++) {
+                    const int c = c0 + q;
+                    const float x = shared_load(hp + (int64_t)(c < kchunks ? c : c0) * M * r + i);
+                    v[q] = (c < kchunks) ? x : 0.f;
+                }
+#pragma unroll
+                for (int q = 0; q < 48; q++) t += v[q];
+            }
+            shared_store(hs + i, t);
+            if (H_out) {
+                const __bf16 hb = (__bf16)t;
+                H_out[i] = __builtin_bit_cast(uint16_t, hb);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0) __hip_atomic_store(tickets + HCOUNT + hj, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        QTS(3);
+        // H is in memory: the flag the blocks' finishers look at
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(tickets + HREADY + hj, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            done();
+        }
+        QTS(4);
         return;
     }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int row_blocks = jb.rb0[jb.count];                   // of all weights together
-    const int rb = blockIdx.x % row_blocks, split = blockIdx.x / row_blocks;
+    const int wg = (int)blockIdx.x - head_grid;
+    const int rb = wg % row_blocks, split = wg / row_blocks;
     const int job = job_of_block(jb, rb);
     const int N = pick(jb.N, job);
     const void* const Wq = pick(jb.Wq, job);
@@ -423,6 +653,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         }
     }
 
+    QTS(1);
     // accumulator view: lane holds token 16 tt + lr, channels n0 + 4 g + v
     const int n = n0 + 4 * g;
     if (n < N) {
@@ -442,137 +673,27 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 #pragma unroll
                 for (int v = 0; v < 4; v++) o[v] = ch_scale[v] * (acc[tt][v] - 128.f * ones_acc[tt][v]);
             }
-            *reinterpret_cast<f32x4*>(part + ((int64_t)split * M + m) * ld_part + ncomb0 + 4 * g) = o;
+            float* const dst = part + ((int64_t)split * M + m) * ld_part + ncomb0 + 4 * g;
+#pragma unroll
+            for (int v = 0; v < 4; v++) shared_store(dst + v, o[v]);
         }
     }
-}
-
-// Y[m][n] = bf16( base_scale * sum_s part[s][m][n] + scaling * sum_j H[m][j] B[j][n] ),  H = sum_kc hpart[kc].
-// A workgroup covers 64 channels x 4 tokens, one output per thread (blockIdx.y picks the token group).
-// The kernel is a chain of memory round trips and little else, so everything a thread needs is
-// requested before anything is waited for: every load below has an address that is valid whatever
-// the lane's bounds say (indices are clamped, the value is dropped by a select afterwards), so
-// no load sits behind a branch, and the loops over slabs and chunks keep eight loads in flight.
-constexpr int FTOK = 4;
-constexpr int FDEPTH = 8;
-template <int RMAX>
-__global__ __launch_bounds__(NT) void finish_kernel(const float* __restrict__ part, int splits,
-                                                    const float* __restrict__ hpart_all, int kchunks,
-                                                    SkinnyJobs jb, int M, int r)
-{
-    __shared__ float Hs[FTOK * RMAX];
-    __shared__ __attribute__((aligned(16))) float Hg[4 * NT];
-    const int rb = blockIdx.x;                                 // 64-channel block in the combined numbering
-    const int job = job_of_block(jb, rb);
-    const int N = pick(jb.N, job);
-    const uint16_t* const B = static_cast<const uint16_t*>(pick(jb.B, job));
-    uint16_t* const Y = static_cast<uint16_t*>(pick(jb.Y, job));
-    uint16_t* const H_out = static_cast<uint16_t*>(pick(jb.H_out, job));
-    const float base_scale = pick(jb.base_scale, job), scaling = pick(jb.scaling, job);
-    const float* const hpart = hpart_all + (int64_t)job * kchunks * M * r;
-    const bool first_block = (rb == pick_rb0(jb, job));
-    const int ld_part = jb.rb0[jb.count] * 64;
-    const int ncomb = rb * 64 + (threadIdx.x & 63);            // always inside the slab's width
-    const int n = (rb - pick_rb0(jb, job)) * 64 + (threadIdx.x & 63);
-    const int m0 = blockIdx.y * FTOK;
-    const int m = m0 + (threadIdx.x >> 6);
-    const bool live = n < N && m < M;
-    const int nc = n < N ? n : N - 1, mc = m < M ? m : M - 1;
-
-    // (1) this thread's column of B
-    // (buffer loads: a row beyond r gets an offset outside the buffer and reads as zero)
-    const __amdgpu_buffer_rsrc_t rB = rsrc(B, (int64_t)r * N * 2);
-    float b[RMAX];
-#pragma unroll
-    for (int j = 0; j < RMAX; j++) {
-        const uint32_t off = (j < r) ? (uint32_t)(j * N + nc) * 2u : OOB;
-        b[j] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rB, off, 0, 0) << 16);
-    }
-    // (2) its slab values: the first eight requested here, summed (and any further ones fetched)
-    // after the requests of (3) are out
-    auto part_batch = [&](float (&v)[FDEPTH], int sp0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < FDEPTH; q++) {
-            const int sp = sp0 + q;
-            const float x = part[((int64_t)(sp < splits ? sp : sp0) * M + mc) * ld_part + ncomb];
-            v[q] = (sp < splits) ? x : 0.f;
-        }
-    };
-    auto sum8 = [](const auto (&v)[FDEPTH]) __attribute__((always_inline)) {
-        return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
-    };
-    float pv[FDEPTH];
-    part_batch(pv, 0);
-    // (3) H of this group's tokens = sum of the chunk partial sums, the 256 threads sharing the loads.
-    // The tokens of a group are consecutive, so their outputs are contiguous in a chunk:
-    // hpart[kc][m0 * r + o], o < outs.  A thread owns `vec` consecutive outputs (4 when r is a multiple
-    // of 4, which keeps 16-byte alignment; else 1) of the chunks g, g + G, ...; the G group sums
-    // are then added in group order (the same order every run).
-    const int toks = (M - m0 < FTOK) ? M - m0 : FTOK;
-    const int outs = toks * r;                              // at most 4 RMAX <= 256
-    const int64_t chunk = (int64_t)M * r;
-    const float* hp = hpart + (int64_t)m0 * r;
-    const bool vec4 = (r & 3) == 0;
-    const int P = vec4 ? outs >> 2 : outs;                  // threads per chunk
-    const int G = NT / P;
-    {
-        const int p = threadIdx.x % P, g = threadIdx.x / P;
-        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-        f32x4 sv = zero4;
-        if (g < G) {
-            if (vec4) {
-                for (int kc = g; kc < kchunks; kc += FDEPTH * G) {
-                    f32x4 v[FDEPTH];
-#pragma unroll
-                    for (int q = 0; q < FDEPTH; q++) {
-                        const int c = kc + q * G;
-                        const f32x4 x = *reinterpret_cast<const f32x4*>(hp + (int64_t)(c < kchunks ? c : kc) * chunk + 4 * p);
-                        v[q] = (c < kchunks) ? x : zero4;
-                    }
-                    sv += sum8(v);
-                }
-                *reinterpret_cast<f32x4*>(Hg + (g * P + p) * 4) = sv;       // Hg[g][4 p ..] of [G][outs]
-            } else {
-                for (int kc = g; kc < kchunks; kc += FDEPTH * G) {
-                    float v[FDEPTH];
-#pragma unroll
-                    for (int q = 0; q < FDEPTH; q++) {
-                        const int c = kc + q * G;
-                        const float x = hp[(int64_t)(c < kchunks ? c : kc) * chunk + p];
-                        v[q] = (c < kchunks) ? x : 0.f;
-                    }
-                    sv[0] += sum8(v);
-                }
-                Hg[g * P + p] = sv[0];                                      // Hg[g][p] of [G][outs]
-            }
-        }
-    }
-    float base = sum8(pv);
-    for (int sp0 = FDEPTH; sp0 < splits; sp0 += FDEPTH) {
-        part_batch(pv, sp0);
-        base += sum8(pv);
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < outs) {
-        float t = 0.f;
-        for (int q = 0; q < G; q++) t += Hg[q * outs + threadIdx.x];
-        Hs[threadIdx.x] = t;
-        if (H_out && first_block) {
-            const __bf16 hb = (__bf16)t;
-            H_out[(int64_t)m0 * r + threadIdx.x] = __builtin_bit_cast(uint16_t, hb);
-        }
-    }
-    __syncthreads();
-    if (!live) return;
-    const int ml = m - m0;
-    float l = 0.f;
-#pragma unroll
-    for (int j = 0; j < RMAX; j++) l = fmaf(Hs[ml * r + (j < r ? j : 0)], b[j], l);
-    const __bf16 yb = (__bf16)(base_scale * base + scaling * l);
-    Y[(int64_t)m * N + n] = __builtin_bit_cast(uint16_t, yb);
+    // the last of this block's slices to arrive finishes it
+    QTS(3);
+    const bool last = arrive(tickets + rb, &s_ticket) == last_ticket;
+    QTS(4);
+    if (last) finish(rb);
+    QTS(5);
 }
 
 }  // namespace skinny
+
+#ifdef FHPC_TRACE
+extern "C" int fhpc_debug_read_qts(unsigned long long* out, int n)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(skinny::g_qtrace), sizeof(unsigned long long) * (size_t)n);
+}
+#endif
 
 bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
 {
@@ -580,6 +701,7 @@ bool qskinny_supports(int64_t M, int64_t K, int64_t r, int64_t N, int scheme)
     // the kernels address each operand with 32-bit byte offsets below 2^31
     const int64_t lim = (int64_t)1 << 31;
     if (N < 1 || K < 1 || N * K >= lim || 2 * r * N >= lim) return false;
+    if ((N + skinny::ROWS_WG - 1) / skinny::ROWS_WG > skinny::TICKETS / QSKINNY_MAX_JOBS) return false;   // tickets in the header
     return M >= 1 && M <= 4 * skinny::TOK && r >= 1 && r <= 64 && (K % 256) == 0;
 }
 
@@ -595,7 +717,9 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
     // allow three per compute unit with 16 tokens, two with more) and no more, so that
     // no second, partly filled round follows; at least one step each.
     const int64_t per_cu = (M <= 16) ? 3 : 2;
-    int64_t s = per_cu * (int64_t)num_cu / row_blocks;
+    // (the chunks of H = X A run at the head of the same grid and hold slots of that round meanwhile)
+    const int64_t hchunks = (int64_t)count * ((K + skinny::HCHUNK - 1) / skinny::HCHUNK);
+    int64_t s = (per_cu * (int64_t)num_cu - hchunks) / row_blocks;
     if (s > ksteps) s = ksteps;
     if (s < 1) s = 1;
     const int64_t per = (ksteps + s - 1) / s;
@@ -604,12 +728,12 @@ QskinnyPlan qskinny_plan(int64_t M, int64_t K, int64_t r, const int64_t* N, int 
     p.kchunks = (int)((K + skinny::HCHUNK - 1) / skinny::HCHUNK);
     p.row_blocks = (int)row_blocks;
     p.part_bytes = (int64_t)p.splits * M * row_blocks * skinny::ROWS_WG * 4;
-    p.hpart_bytes = (int64_t)count * p.kchunks * M * r * 4;
+    p.hpart_bytes = (int64_t)count * (p.kchunks + 1) * M * r * 4;          // the chunks, then H itself ([count][M][r])
     return p;
 }
 
 hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, int scheme, int64_t M, int64_t K, int64_t r,
-                              const QskinnyPlan& p, float* part, float* hpart, hipStream_t st)
+                              const QskinnyPlan& p, float* part, float* hpart, uint32_t* tickets, hipStream_t st)
 {
     using namespace skinny;
     if (count < 1 || count > QSKINNY_MAX_JOBS) return hipErrorInvalidValue;
@@ -629,13 +753,19 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
         }
     }
     for (int j = count; j <= QSKINNY_MAX_JOBS; j++) jb.rb0[j] = rb;
-    const int main_grid = rb * p.splits;
-    const dim3 grid((unsigned)(main_grid + count * p.kchunks));     // streaming workgroups, then the H = X A chunks
+    if (rb > TICKETS) return hipErrorInvalidValue;
+    const int head_grid = count * p.kchunks;                       // the H = X A chunks first, then the streaming workgroups
+    const dim3 grid((unsigned)(head_grid + rb * p.splits));
+    float* const hsum = hpart + (int64_t)count * p.kchunks * M * r;
+    // how often a finisher looks at H's flag before it forms H itself (about a microsecond a look); the
+    // environment variable is for the test that forces that path (a negative value: never look)
+    int poll_limit = 8192;
+    if (const char* e = getenv("FHPC_H_POLLS")) poll_limit = atoi(e);
     const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * nsum,
-                                wbytes + 2.0 * M * K + 4.0 * p.splits * M * nsum, st);
+                                wbytes + 2.0 * M * K + 4.0 * p.splits * M * nsum + 2.0 * M * nsum, st);
 #define FHPC_MAIN(SCHEME, TT, SD)                                                                                   \
     hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT, SD>), grid, dim3(NT), 0, st, X, jb, part, (int)M, (int)K,    \
-                       p.k_chunk, hpart, (int)r, p.kchunks, main_grid)
+                       p.k_chunk, hpart, (int)r, p.kchunks, head_grid, p.splits, tickets, hsum, poll_limit)
     const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
     const bool deep = step_depth(tt, K) == 512;
     if (scheme == 4) {
@@ -649,15 +779,6 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
     }
 #undef FHPC_MAIN
     prof_end(slot, st);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const dim3 fgrid((unsigned)rb, (unsigned)((M + FTOK - 1) / FTOK));
-    const int fslot = prof_begin("qskinny_finish", 0.0, 0.0, st);
-#define FHPC_FINISH(RMAX) \
-    hipLaunchKernelGGL((finish_kernel<RMAX>), fgrid, dim3(NT), 0, st, part, p.splits, hpart, p.kchunks, jb, (int)M, (int)r)
-    if (r <= 16) FHPC_FINISH(16); else FHPC_FINISH(64);
-#undef FHPC_FINISH
-    prof_end(fslot, st);
     return hipGetLastError();
 }
 

@@ -131,7 +131,7 @@ def test_validation_precedes_launch():
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_DECOMPOSE, 1, 4096, 512, 4096) > 3 * 4096 * 512 * 2
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_DECOMPOSE, 1, 64, 12, 64) == 0
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 8, 64) == 0
-    assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 64 * 8 * 2                  # a padded A
+    assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 16384 + 64 * 8 * 2          # the header, then a padded A
 
 
 def test_binding_refuses_cpu_tensors():

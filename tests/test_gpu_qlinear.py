@@ -534,6 +534,39 @@ def test_few_token_forward_in_a_hip_graph():
         assert not torch.equal(other, eager)
 
 
+@pytest.mark.parametrize("scheme,M,r", [(4, 16, 16), (8, 37, 40), (4, 64, 5)])
+def test_few_token_forward_when_the_finisher_forms_H_itself(scheme, M, r):
+    """The one-launch forward: a block's finisher normally reads H = X A from the workgroups at the head of the
+    grid; if their flag does not come up within its bound it forms H itself, in the same order of sums.  The
+    environment variable makes every finisher take that path: the output must be the same bits, the workspace
+    header must be left zero either way, and a later ordinary call must still be right."""
+    import os
+    import torch
+    fhpc = _fhpc()
+    K, N = 2304, 328
+    W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 99)
+    Wq, sc = _quantize_host(W, scheme)
+    Wq_d, sc_d = _to_dev(Wq, sc)
+    Xd, Ad, Bd = X.cuda(), A.cuda(), B.cuda()
+    need = fhpc.workspace_bytes(fhpc.FHPC_OP_QLINEAR_FWD, M, K, r, N, fhpc.FHPC_BF16, scheme)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    Y0, H0 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, save_H=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:16384].count_nonzero()) == 0
+    Yr, _ = oracle.qlinear_lowrank_fwd(X.f64, oracle.dequant(Wq, sc, scheme, 64), A.f64, B.f64, 2.0)
+    assert parity_err(from_device(Y0), Yr) <= TOL_BF16
+    os.environ["FHPC_H_POLLS"] = "-1"
+    try:
+        Y1, H1 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, save_H=True, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["FHPC_H_POLLS"]
+    assert torch.equal(Y1, Y0) and torch.equal(H1, H0)
+    assert int(ws[:16384].count_nonzero()) == 0
+    Y2 = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, 2.0, workspace=ws)
+    assert torch.equal(Y2, Y0)
+
+
 @pytest.mark.parametrize("scheme,M,r", [(4, 12, 16), (8, 40, 24)])
 def test_few_token_step_in_a_hip_graph(scheme, M, r):
     """Forward and backward of the few-token routes captured in one HIP graph (streaming kernels, their
