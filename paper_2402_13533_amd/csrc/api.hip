@@ -131,6 +131,27 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
     if (s > ksteps) s = ksteps;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
+    if ((sp.tile == TILE_256x256 || sp.tile == TILE_256x128) && tiles < target && ksteps >= 16) {
+        // The eight-wave tiles run one workgroup per compute unit, so what a launch takes is the number of
+        // rounds its tiles x slices need times the depth of a slice, plus a fixed part per round (ring fill,
+        // fp32 epilogue) and the slabs it writes and the slab sum reads.  The rule above can leave a second
+        // round nearly empty (96 tiles in 3 slices: 288 items, 235 microseconds for 4096 x 1536 over 16384
+        // tokens; in 5 slices two full rounds of shorter slices); take the cheapest count instead.
+        // Units: 64-deep steps of a 256 x 256 tile (about 1.5 microseconds each).
+        const double tile_steps = (sp.tile == TILE_256x256) ? 1.0 : 0.5;
+        const double fixed_steps = 5.0;                                     // per round
+        const double slab_steps = (double)M * (double)N * 8.0 / 4.0e12 / 1.5e-6;   // one slab written and read at 4 TB/s
+        double best = -1.0;
+        for (int64_t c = 1; c <= 64 && c <= ksteps / 8; c++) {
+            const int64_t rounds = (tiles * c + target - 1) / target;
+            const int64_t per = (ksteps + c - 1) / c;
+            const double cost = (double)rounds * ((double)per * tile_steps + fixed_steps) + (c > 1 ? (double)c * slab_steps : 0.0);
+            if (best < 0.0 || cost < best) {
+                best = cost;
+                s = c;
+            }
+        }
+    }
     const int64_t steps_per = (ksteps + s - 1) / s;
     sp.k_chunk = (int)(steps_per * 64);
     sp.splits = (int)((ksteps + steps_per - 1) / steps_per);
