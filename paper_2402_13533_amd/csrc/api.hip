@@ -901,6 +901,8 @@ struct SharedScratch {
     int64_t part_bytes = 0;
 };
 
+static bool groupable_f32(int64_t M, int64_t N, int64_t Kred, int g);
+
 static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int64_t r, int64_t N, int g)
 {
     SharedScratch s;
@@ -920,7 +922,8 @@ static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int
         if (r <= 32) upto(split_bytes(M, r, r, N));
         else if (g == 1) upto(product_part_bytes(M, r, N));
         upto(split_bytes(K, R, R, M));                 // dA_all = X^T dH_all
-        upto(split_bytes(r, N, N, M));                 // dB_i = H_i^T dY_i
+        // dB_i = H_i^T dY_i: one product's slabs, or all g products' when they go out in one launch
+        upto((groupable_f32(r, N, M, g) ? g : 1) * split_bytes(r, N, N, M));
     }
     s.part = static_cast<float*>(c.take(part));
     s.part_bytes = part;
@@ -960,12 +963,78 @@ static inline void* bf16_col(const void* p, int64_t col)
     return const_cast<uint16_t*>(static_cast<const uint16_t*>(p)) + col;
 }
 
+// The g same-shaped products of a shared-X call (Y_i = H_i B_i, dH_i = dY_i B_i^T, dB_i = H_i^T dY_i) in one launch of
+// the request-fed kernels: one ramp and one tail instead of g, and the workgroups of the persistent shape run on
+// from one product into the next.  Whether that is possible for a product shape: unsplit bf16 output, or fp32
+// output (split or not), on the tiles those kernels serve.
+static bool groupable_bf16(int b_mode, int64_t M, int64_t Nout, int64_t ldp, int64_t Kred, int g)
+{
+    if (g < 2 || g > GEMM_MAX_GROUPS) return false;
+    if (ldp == Nout && (large_split_pays(M, Nout, Kred) || split_pays(M, Nout, Kred))) return false;
+    return gemm_pp_supports(OP_KC, b_mode, OP_NONE, OUT_BF16, pick_tile(M, Nout, false));
+}
+
+// P_i[M][Nout] (bf16, row stride ldp) = a_i * b_i^(b_mode), i < g; a_i has k contiguous
+static hipError_t grouped_bf16(int b_mode, const GemmOperand* a, const GemmOperand* b, void* const* P, int64_t ldp,
+                               int64_t Nout, int64_t M, int64_t Kred, int g, Run& run)
+{
+    if (run.dry) return hipSuccess;
+    GemmArgs ga = {};
+    ga.a = a[0]; ga.b = b[0]; ga.c = P[0]; ga.ldc = ldp;
+    ga.M = (int)M; ga.N = (int)Nout; ga.K = (int)Kred; ga.K2 = 0;
+    ga.alpha = 1.f; ga.mid_scale = 1.f; ga.splits = 1; ga.k_chunk = (int)round_up(Kred, 64);
+    ga.groups = g;
+    for (int i = 0; i < g; i++) { ga.ga[i] = a[i].ptr; ga.gb[i] = b[i].ptr; ga.gc[i] = P[i]; }
+    return launch_gemm_bf16(OP_KC, b_mode, OP_NONE, OUT_BF16, pick_tile(M, Nout, false), ga, run.st);
+}
+
+// C_i[M][N] (fp32, dense) = a_i^T-type products reduced over Kred (both operands reduction-major), i < g: the g
+// split reductions in one launch, slabs of product i behind those of product i - 1, then the g slab sums.
+static bool groupable_f32(int64_t M, int64_t N, int64_t Kred, int g)
+{
+    if (g < 2 || g > GEMM_MAX_GROUPS) return false;
+    return gemm_pp_supports(OP_XC, OP_XC, OP_NONE, OUT_F32, plan_split(M, N, Kred).tile);
+}
+
+static hipError_t grouped_split_f32(const GemmOperand* a, const GemmOperand* b, float* const* C, int64_t M, int64_t N,
+                                    int64_t Kred, float* part, int g, Run& run)
+{
+    const SplitPlan sp = plan_split(M, N, Kred);
+    const int64_t slab_area = sp.splits > 1 ? (int64_t)sp.splits * M * N : 0;      // floats per product
+    if (!run.claim((int64_t)g * slab_area * 4)) return hipErrorOutOfMemory;
+    if (run.dry) return hipSuccess;
+    GemmArgs ga = {};
+    ga.a = a[0]; ga.b = b[0]; ga.ldc = N;
+    ga.M = (int)M; ga.N = (int)N; ga.K = (int)Kred; ga.K2 = 0;
+    ga.alpha = 1.f; ga.mid_scale = 1.f; ga.splits = sp.splits; ga.k_chunk = sp.k_chunk;
+    ga.split_stride = sp.splits > 1 ? M * N : 0;
+    ga.groups = g;
+    for (int i = 0; i < g; i++) {
+        ga.ga[i] = a[i].ptr; ga.gb[i] = b[i].ptr;
+        ga.gc[i] = sp.splits > 1 ? static_cast<void*>(part + (int64_t)i * slab_area) : static_cast<void*>(C[i]);
+    }
+    ga.c = ga.gc[0];
+    hipError_t e = launch_gemm_bf16(OP_XC, OP_XC, OP_NONE, OUT_F32, sp.tile, ga, run.st);
+    if (e != hipSuccess || sp.splits == 1) return e;
+    for (int i = 0; i < g; i++) {
+        e = launch_sum_slabs(part + (int64_t)i * slab_area, M * N, sp.splits, C[i], false, run.st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 static int seq_shared_fwd(Run& run, const SharedScratch& s, const void* X, const void* A_all, const void* const* B,
                           void* const* Y, void* H_all_out, int64_t M, int64_t K, int64_t r, int64_t N, int g)
 {
     const int64_t R = r * g;
     void* H = H_all_out ? H_all_out : s.H;
     FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, run));
+    if (groupable_bf16(OP_XC, M, N, N, r, g)) {
+        GemmOperand a[GEMM_MAX_GROUPS], b[GEMM_MAX_GROUPS];
+        for (int i = 0; i < g; i++) { a[i] = operand(bf16_col(H, i * r), R); b[i] = operand(B[i], N); }
+        FHPC_HIP(grouped_bf16(OP_XC, a, b, Y, N, N, M, r, g, run));
+        return FHPC_OK;
+    }
     for (int i = 0; i < g; i++)
         FHPC_HIP(product_bf16(OP_XC, operand(bf16_col(H, i * r), R), operand(B[i], N), Y[i], N, N, M, r, s.part, run));
     return FHPC_OK;
@@ -981,12 +1050,25 @@ static int seq_shared_bwd(Run& run, const SharedScratch& s, const void* X, const
         FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), s.H, R, R, s.Pf, s.part, M, K, run));
         H = s.H;
     }
-    if (dX || dA_all) {
+    if ((dX || dA_all) && r > 32 && groupable_bf16(OP_KC, M, r, R, N, g)) {
+        GemmOperand a[GEMM_MAX_GROUPS], b[GEMM_MAX_GROUPS];
+        void* P[GEMM_MAX_GROUPS];
+        for (int i = 0; i < g; i++) { a[i] = operand(dY[i], N); b[i] = operand(B[i], N); P[i] = bf16_col(s.dH, i * r); }
+        FHPC_HIP(grouped_bf16(OP_KC, a, b, P, R, r, M, N, g, run));
+    } else if (dX || dA_all) {
         for (int i = 0; i < g; i++)
             FHPC_HIP(narrow_product(OP_KC, operand(dY[i], N), operand(B[i], N), bf16_col(s.dH, i * r), R, r, s.Pf, s.part, M, N, run));
     }
     if (dX) FHPC_HIP(product_bf16(OP_KC, operand(s.dH, R), operand(A_all, R), dX, K, K, M, R, s.part, run));
     if (dA_all) FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(X, K), operand(s.dH, R), dA_all, R, K, R, M, 1.f, s.part, run));
+    bool all_dB = any_dB;
+    for (int i = 0; i < g && all_dB; i++) all_dB = dB[i] != nullptr;
+    if (all_dB && groupable_f32(r, N, M, g)) {
+        GemmOperand a[GEMM_MAX_GROUPS], b[GEMM_MAX_GROUPS];
+        for (int i = 0; i < g; i++) { a[i] = operand(bf16_col(H, i * r), R); b[i] = operand(dY[i], N); }
+        FHPC_HIP(grouped_split_f32(a, b, dB, r, N, M, s.part, g, run));
+        return FHPC_OK;
+    }
     for (int i = 0; i < g && any_dB; i++)
         if (dB[i])
             FHPC_HIP(gemm_split_f32(OP_XC, OP_XC, operand(bf16_col(H, i * r), R), operand(dY[i], N), dB[i], N, r, N, M, 1.f, s.part, run));

@@ -40,6 +40,8 @@ enum : int {
     TILE_COUNT = 6
 };
 
+constexpr int GEMM_MAX_GROUPS = 8;
+
 struct GemmOperand {
     const void* ptr;
     int64_t ld;            // leading dimension in elements (codes for quantised operands)
@@ -58,6 +60,13 @@ struct GemmArgs {
     int splits;            // >1: the reduction is cut into slices of k_chunk (multiple of 64); needs OUT_F32
     int k_chunk;
     int64_t split_stride;  // elements between the partial-sum slabs of consecutive splits
+    // groups > 1 (request-fed kernels only): that many independent products of the same shape, layout and
+    // leading dimensions in one launch; product i takes its operand and output addresses from ga[i], gb[i],
+    // gc[i] (a.ptr, b.ptr and c are then unused).  With a split reduction, gc[i] is product i's slab area.
+    int groups;
+    const void* ga[GEMM_MAX_GROUPS];
+    const void* gb[GEMM_MAX_GROUPS];
+    void* gc[GEMM_MAX_GROUPS];
     int dbg;               // kernel choice for tests, 0 in normal use: bit 2 = lockstep kernels only, bit 3 =
                            // four-wave kernel where it exists.  A build with -DFHPC_DIAG also honours bit 0
                            // (request no operand data) and bit 1 (skip the matrix instructions, lockstep only).

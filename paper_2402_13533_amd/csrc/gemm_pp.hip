@@ -90,7 +90,9 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int nsplit = p.splits > 1 ? p.splits : 1;
-    const int total = tiles_m * tiles_n * nsplit;
+    const int per_product = tiles_m * tiles_n * nsplit;
+    const int ngroups = p.groups > 1 ? p.groups : 1;
+    const int total = per_product * ngroups;
     const FragAddr aa = TA::make(wave_m0, lane);
     const FragAddr ab = TB::make(wave_n0, lane);
 
@@ -99,11 +101,13 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     FB fb;
     fa.describe(p.a, p.M, p.K);
     fb.describe(p.b, p.N, p.K);
-    struct Item { int m0, n0, split, kbeg, kend, kld; };
+    struct Item { int m0, n0, split, kbeg, kend, kld, grp; };
     Item cur = {}, nxt = {};                                   // (nxt is read, unused, when no item follows)
     auto item_of = [&](int pid, Item& it) {
         int tm, tn;
-        work_coords(pid, tiles_m, tiles_n, nsplit, tm, tn, it.split);
+        const int id = xcd_contiguous(pid, total);
+        it.grp = id / per_product;
+        item_coords(id - it.grp * per_product, tiles_m, tiles_n, nsplit, tm, tn, it.split);
         it.m0 = tm * BM;
         it.n0 = tn * BN;
         it.kbeg = it.split * p.k_chunk;
@@ -136,7 +140,16 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 
     for (int pid = blockIdx.x; pid < total; pid += gridDim.x) {
     const int out_m0 = cur.m0, out_n0 = cur.n0, out_split = cur.split;
+    void* const out_c = (p.groups > 1) ? p.gc[cur.grp] : p.c;
     const int kbeg = cur.kbeg, kend = cur.kend, kld = cur.kld;
+    if (p.groups > 1) {
+        // this item's product: its operands' descriptors (the lane offsets do not depend on the base address)
+        GemmOperand ga = p.a, gb = p.b;
+        ga.ptr = p.ga[cur.grp];
+        gb.ptr = p.gb[cur.grp];
+        fa.describe(ga, p.M, p.K);
+        fb.describe(gb, p.N, p.K);
+    }
     if (kbeg < kend) {
         fa.set_tile(p.a, cur.m0, p.M, wave, lane);
         fb.set_tile(p.b, cur.n0, p.N, wave, lane);
@@ -146,7 +159,8 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     if (has_next) item_of(pid + (int)gridDim.x, nxt);
     // whole trips: the first k position past this item's loop
     const int kpad = kbeg + (kend - kbeg + NSTAGE * BK - 1) / (NSTAGE * BK) * (NSTAGE * BK);
-    const bool chain = has_next && kbeg < kend && nxt.kbeg < nxt.kend;
+    // (the successor's requests use this item's operand descriptors: no chaining into another product)
+    const bool chain = has_next && kbeg < kend && nxt.kbeg < nxt.kend && nxt.grp == cur.grp;
     const int nk0 = nxt.kbeg - kpad;                          // successor's k position = loop position + nk0
 
     f32x16 acc[TN][TM];
@@ -355,7 +369,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 #pragma unroll
                         for (int v = 0; v < 16; v++) acc[j][i][v] *= alpha;
             }
-            const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(p.c, 0, (int)((uint32_t)p.M * (uint32_t)p.ldc * 2u), 0x00020000);
+            const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(out_c, 0, (int)((uint32_t)p.M * (uint32_t)p.ldc * 2u), 0x00020000);
             const uint32_t ldc_b = (uint32_t)p.ldc * 2u;
             const uint32_t lane_off = (uint32_t)(wave_m0 + rr) * ldc_b + (uint32_t)(wave_n0 + rc * 8) * 2u;
             const uint32_t tile_off = (uint32_t)out_m0 * ldc_b + (uint32_t)out_n0 * 2u;
@@ -385,7 +399,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
                         u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
                         if (q & 1) v = u32x4{v.z, v.w, v.x, v.y};
 #ifdef FHPC_DIAG
-                        if (p.dbg & 32) { if (v.x == 0x12345678u && v.y == 0x9abcdef0u) reinterpret_cast<u32x4*>(p.c)[0] = v; continue; }
+                        if (p.dbg & 32) { if (v.x == 0x12345678u && v.y == 0x9abcdef0u) reinterpret_cast<u32x4*>(out_c)[0] = v; continue; }
 #endif
                         const uint32_t soff = __builtin_amdgcn_readfirstlane(tile_off + (uint32_t)(i * 32 + 8 * q) * ldc_b);
                         __builtin_amdgcn_raw_buffer_store_b128(v, rs_c, lane_off, soff, 0);
@@ -399,7 +413,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
                         if (q & 1) v = u32x4{v.z, v.w, v.x, v.y};
                         const int m = out_m0 + wave_m0 + i * 32 + row;
                         if (m < p.M && col < p.N)
-                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
+                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out_c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
                     }
                 }
             }
@@ -407,7 +421,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     } else {
         // fp32: this split's partial sum goes to its own slab, straight from the registers
         if (owner) {
-            float* dst = reinterpret_cast<float*>(p.c) + (size_t)out_split * (size_t)p.split_stride;
+            float* dst = reinterpret_cast<float*>(out_c) + (size_t)out_split * (size_t)p.split_stride;
 #pragma unroll
             for (int j = 0; j < TN; j++) {
 #pragma unroll
@@ -459,14 +473,14 @@ template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, in
 static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    const int total = tiles * (a.splits > 1 ? a.splits : 1);
+    const int total = tiles * (a.splits > 1 ? a.splits : 1) * (a.groups > 1 ? a.groups : 1);
     const int cus = compute_units();
     dim3 grid((unsigned)((!KSPLIT && total > cus) ? cus : total));
     int slot = -1;
     if (prof_on()) {
         char name[64];
         snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
-        slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K, 0.0, s);
+        slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K * (a.groups > 1 ? a.groups : 1), 0.0, s);
     }
     hipLaunchKernelGGL((gemm_pp_kernel<BM, BN, BK, KSPLIT, NSTAGE, AM, BMODE, OUT>), grid, dim3(NT), 0, s, a);
     prof_end(slot, s);

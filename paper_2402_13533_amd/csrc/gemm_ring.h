@@ -254,21 +254,35 @@ struct Feeder<OP_XC, R, BK, NW> {
     }
 };
 
-// Same workgroup -> tile mapping as the lockstep kernels (see gemm_bf16.hip).
-__device__ __forceinline__ void work_coords(int pid, int tiles_m, int tiles_n, int splits, int& tm, int& tn, int& split)
+// Workgroup -> work item.  pid % 8 is the XCD a workgroup lands on (hardware round-robin), so every XCD gets a
+// contiguous range of item numbers: the workgroups resident on an XCD then share operand tiles in its L2.
+__device__ __forceinline__ int xcd_contiguous(int pid, int total)
 {
-    constexpr int NXCD = 8, GROUP_M = 8;
-    const int tiles = tiles_m * tiles_n;
-    const int total = tiles * splits;
+    constexpr int NXCD = 8;
     const int per = (total + NXCD - 1) / NXCD;
     const int tall = (total % NXCD) ? (total % NXCD) : NXCD;
     const int xcd = pid % NXCD, local = pid / NXCD;
-    int id = (xcd < tall) ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    return (xcd < tall) ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+}
+
+// Item number within one product -> (slice of the reduction, tile row, tile column).
+__device__ __forceinline__ void item_coords(int id, int tiles_m, int tiles_n, int splits, int& tm, int& tn, int& split)
+{
+    constexpr int GROUP_M = 8;
+    const int tiles = tiles_m * tiles_n;
     if (splits > 1) {
+        // Split-major, and within a slice the shorter tile dimension runs fastest: the tiles that read the same
+        // panel of the larger operand (all row tiles of one column tile when there are more column tiles, and
+        // the other way round) then sit in one XCD's contiguous range and the panel is fetched once.
         split = id / tiles;
         const int t = id - split * tiles;
-        tm = t / tiles_n;
-        tn = t - tm * tiles_n;
+        if (tiles_n > tiles_m) {
+            tn = t / tiles_m;
+            tm = t - tn * tiles_m;
+        } else {
+            tm = t / tiles_n;
+            tn = t - tm * tiles_n;
+        }
         return;
     }
     split = 0;
@@ -279,6 +293,12 @@ __device__ __forceinline__ void work_coords(int pid, int tiles_m, int tiles_n, i
     const int rem = id % in_group;
     tm = first_m + rem % gsz;
     tn = rem / gsz;
+}
+
+// Same workgroup -> tile mapping as the lockstep kernels (see gemm_bf16.hip).
+__device__ __forceinline__ void work_coords(int pid, int tiles_m, int tiles_n, int splits, int& tm, int& tn, int& split)
+{
+    item_coords(xcd_contiguous(pid, tiles_m * tiles_n * splits), tiles_m, tiles_n, splits, tm, tn, split);
 }
 
 }  // namespace ring
