@@ -102,6 +102,31 @@ def test_config3_chain_shared_x():
         assert v <= TOL_BF16, (k, v)
 
 
+def test_config3_chain_error_spread_over_seeds():
+    """The chain's error is a sum over millions of independent roundings (every stored intermediate is bf16:
+    H_gate/up, G, U, Z, H_down, Y on the way forward; dH_down, dZ, dG, dU, dH_gate/up, dX on the way back), so its
+    relative Frobenius norm depends on how many roundings the chain has, hardly on the data: over six seeds
+    the values agree to a few per cent, and the worst keeps the distance to the tolerance that the first has."""
+    import numpy as np
+    from paper_2402_13533_amd import ffn
+    M, d, r, f = 320, 4096, 1024, 11008
+    seen = {"Y": [], "dX": []}
+    for seed in range(6):
+        X, dY, W = _ffn_inputs(M, d, r, f, base=100 * (seed + 1))
+        Yr, dXr, _ = _oracle_ffn(X.f64, dY.f64, W, want_weight_grads=False)
+        Ag, Bg, Au, Bu, Ad, Bd = W
+        A_gu = Bf16(np.concatenate([Ag.bits, Au.bits], axis=1)).cuda()
+        Wd = [A_gu, Bg.cuda(), Bu.cuda(), Ad.cuda(), Bd.cuda()]
+        Y, saved = ffn.ffn_fwd_shared_x(X.cuda(), *Wd)
+        dX, _ = ffn.ffn_bwd_shared_x(X.cuda(), *Wd, dY.cuda(), saved)
+        seen["Y"].append(parity_err(from_device(Y), Yr))
+        seen["dX"].append(parity_err(from_device(dX), dXr))
+        print("c3 chain seed %d: Y %.3e dX %.3e" % (seed, seen["Y"][-1], seen["dX"][-1]), flush=True)
+    for k, v in seen.items():
+        assert max(v) <= TOL_BF16, (k, v)
+        assert (max(v) - min(v)) <= 0.05 * min(v), (k, v)
+
+
 def _oracle_ffn_full_size(X, dY, W, rows, J):
     """The oracle's chain on every token (G, U, Z, dZ, dG, dU in fp64), then: Y and dX on the token rows `rows`, and
     each weight gradient restricted to the rank indices J (column j of dA and row j of dB depend on the pair only
