@@ -37,7 +37,15 @@ def profiled_traffic(workload, kernel):
     else:
         pat = re.compile(re.escape(kernel.split("<")[0]))
     here = os.path.dirname(os.path.abspath(__file__))
-    for path in sorted(glob.glob(os.path.join(here, "profiles", "bench_%s_*.txt" % workload))):
+    # the summary of the plain command first (the same workload with other flags has files of its own)
+    plain = {"c2": "bench_c2_lowrank_gemm_kernels.txt", "c3": "bench_c3_ffn_kernels.txt",
+             "c4": "bench_c4_int8_qlinear_kernels.txt", "c5": "bench_c5_int4_qlinear_kernels.txt"}
+    paths = sorted(glob.glob(os.path.join(here, "profiles", "bench_%s_*.txt" % workload)))
+    first = os.path.join(here, "profiles", plain.get(workload, ""))
+    if first in paths:
+        paths.remove(first)
+        paths.insert(0, first)
+    for path in paths:
         in_table = False
         for line in open(path):
             if line.startswith("== "):

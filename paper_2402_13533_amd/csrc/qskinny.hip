@@ -280,8 +280,11 @@ __device__ __forceinline__ void finish_block(unsigned char* smem, int rb, const 
     };
     // the first tokens' slab values and the first sixteen ranks of B's column are requested before anything waits
     float v[4][8];
+    // (always a row that exists: with fewer than four tokens some threads have no token of their own, and a row
+    // index beyond M would read past the slabs, for one token and a wide weight past the workspace)
+    const int tg_row = tg < M ? tg : 0;
 #pragma unroll
-    for (int u = 0; u < 4; u++) slab_batch(v[u], (tg + 4 * u < M) ? tg + 4 * u : tg, 0);
+    for (int u = 0; u < 4; u++) slab_batch(v[u], (tg + 4 * u < M) ? tg + 4 * u : tg_row, 0);
     float b0[16];
 #pragma unroll
     for (int j = 0; j < 16; j++) {                               // (a row beyond r reads as zero)
