@@ -13,10 +13,13 @@
 // quantised base weight is stored (channel-major: the codes of one output channel are contiguous
 // in k), so a lane loads the 32 codes of its channel once and adds them with no transposition
 // anywhere; code * scale is exact in fp32 and the sum is rounded once.  Along a row the 64 lanes
-// hold 64 consecutive columns: an fp32 store instruction writes 256 contiguous bytes; bf16 moves
-// as 32-bit words of two adjacent columns (neighbouring lanes trade one value each), two rows of
-// 128 bytes per instruction, and a bf16 base weight is loaded the same way.  The base weight of
-// the tile is requested before the r-loop and stays in registers meanwhile.
+// hold 64 consecutive columns: an fp32 store instruction writes 256 contiguous bytes.  bf16 output
+// is packed into 32-bit words of two adjacent columns (neighbouring lanes trade one value each),
+// turned round in a 4 KiB LDS patch per wave and stored 16 bytes per lane, eight rows of 128 bytes
+// per instruction (as 32-bit stores, two rows per instruction, the kernel was bound by the number
+// of stores: a bf16 output took as long as an fp32 one); a bf16 base weight is loaded as 32-bit
+// column pairs.  The base weight of the tile is requested before the r-loop and stays in registers
+// meanwhile.
 #include "merge.h"
 #include "gemm_ring.h"
 #include "profile.h"
@@ -27,7 +30,8 @@ namespace mrg {
 using namespace ring;
 
 constexpr int NT = 256;
-constexpr int TK = 64, TN = 128, BK = 32;     // output tile (rows of W' x columns), rank slice
+constexpr int RB = 1;                         // 32-row blocks per wave (two: no faster for int4, slower for int8)
+constexpr int TK = 64 * RB, TN = 128, BK = 32; // output tile (rows of W' x columns), rank slice
 enum : int { W_NONE = 0, W_BF16 = 1, W_INT8 = 2, W_INT4 = 3 };
 
 struct MergeArgs {
@@ -101,7 +105,8 @@ __device__ __forceinline__ void load_base(BaseRegs<WMODE>& b, const MergeArgs& p
 // out = base_scale * base + scaling * acc for the wave's 32 x 64 block, straight from the accumulators
 // (acc[j]: register v holds row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n_block + 32 j + lane % 32).
 template <int WMODE, bool OUT_F32>
-__device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRegs<WMODE>& b, const MergeArgs& p, int kw, int n, int lane)
+__device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRegs<WMODE>& b, const MergeArgs& p, int kw, int n, int lane,
+                                            unsigned char* patch)
 {
     // rows[q]: row kw + q, lane = column.  One half-wave swap per register pair turns
     // (block 0 | block 1) x (rows of the lower | upper lanes) into (row | row + 4) x 64 columns.
@@ -126,6 +131,11 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
     // bf16 halves of (own, neighbour) words recombined by one byte permute: even lanes keep their low
     // half and take the neighbour's low half on top, odd lanes take the neighbour's high half below their own
     const uint32_t pick = odd ? 0x03020706u : 0x05040100u;
+    // bf16 output: the 32 x 64 block is turned round in a 4 KiB LDS patch of the wave's own ([32 rows][128 bytes],
+    // 16-byte pieces XOR-swizzled by the row) and leaves as 16-byte stores, eight columns per lane and eight rows
+    // per instruction: a quarter of the store instructions the 32-bit pairs took.  (With those the kernel moved a
+    // bf16 output in the time of an fp32 one, twice the bytes: it was bound by the number of stores, not by bytes.)
+    const int prow = odd ? 1 : 0, pword = lane >> 1;             // this lane's word: row q + prow, columns 2 pword, + 1
 #pragma unroll
     for (int q = 0; q < 32; q += 2) {
         float base0 = 0.f, base1 = 0.f;
@@ -147,17 +157,30 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
         }
         const float o0 = rows[q] + base0;
         const float o1 = rows[q + 1] + base1;
-        if (q >= rows_valid) continue;             // uniform: K is a multiple of 8, a row pair is in or out as one
         if constexpr (OUT_F32) {
+            if (q >= rows_valid) continue;         // uniform: K is a multiple of 8, a row pair is in or out as one
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o0), ro, lane_off, q * rowbytes, 0);
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o1), ro, lane_off, (q + 1) * rowbytes, 0);
         } else {
-            // bf16: two columns per 32-bit store.  An even lane stores (n, n + 1) of row q, its odd
-            // neighbour (n - 1, n) of row q + 1: each instruction writes two rows of 128 bytes.
+            // An even lane ends up with columns (n, n + 1) of row q, its odd neighbour with (n - 1, n) of row q + 1.
             const uint32_t own = pack_bf16(o0, o1);                          // (row q, row q + 1) of this column
             const uint32_t nb = swap_with_neighbour(own);                    // the same of the neighbour's column
             const uint32_t word = __builtin_amdgcn_perm(nb, own, pick);
-            __builtin_amdgcn_raw_buffer_store_b32(word, ro, lane_off, q * rowbytes, 0);
+            const int row = q + prow;
+            *reinterpret_cast<uint32_t*>(patch + row * 128 + ((((pword >> 2) ^ row) & 7) << 4) + (pword & 3) * 4) = word;
+        }
+    }
+    if constexpr (!OUT_F32) {
+        // lane -> row lane / 8 (+ 8 per instruction), columns 8 (lane % 8) .. + 7 of the wave's 64
+        const int rr = lane >> 3, rc = lane & 7;
+        const int n8 = n - lane + rc * 8;                                   // first of the lane's eight columns
+        const uint32_t off16 = (n8 < p.N) ? (uint32_t)((kw + rr) * p.N + n8) * 2u : MRG_OOB;   // (N is a multiple of 8)
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            if (8 * k >= rows_valid) break;        // uniform: rows come in groups of eight
+            const int row = rr + 8 * k;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
+            __builtin_amdgcn_raw_buffer_store_b128(v, ro, off16, 8 * k * rowbytes, 0);
         }
     }
 }
@@ -177,31 +200,36 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_k0 = (wave >> 1) * 32;                      // the wave's 32 rows ...
-    const int wave_n0 = (wave & 1) * 64;                       // ... and two blocks of 32 columns
+    const int wave_k0 = (wave >> 1) * (32 * RB);               // the wave's RB blocks of 32 rows ...
+    const int wave_n0 = (wave & 1) * 64;                       // ... by two blocks of 32 columns
     const int tiles_n = (p.N + TN - 1) / TN;
     const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
     const int k0 = tk * TK, n0 = tn * TN;
     const int kw = k0 + wave_k0;                               // first row of the wave
-    // accumulator register v of block j: row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n0 + wave_n0 + 32 j + lane % 32
+    // accumulator register v of block (b, j): row kw + 32 b + 8 (v / 4) + 4 (lane / 32) + v % 4, column n0 + wave_n0 + 32 j + lane % 32
 
-    // ---- base weight of the wave's 32 x 64 block, requested before anything else
+    // ---- base weight of the wave's RB blocks of 32 x 64, requested before anything else
     const int n = n0 + wave_n0 + lane;
-    BaseRegs<WMODE> base;
-    load_base<WMODE>(base, p, kw, n, lane);
+    BaseRegs<WMODE> base[RB];
+#pragma unroll
+    for (int b = 0; b < RB; b++) load_base<WMODE>(base[b], p, kw + 32 * b, n, lane);
 
-    // ---- acc[j] = (A B) block: rows from the A tile, columns from the B tile
-    f32x16 acc[2];
+    // ---- acc[b][j] = (A B) block: rows from the A tile, columns from the B tile
+    f32x16 acc[RB][2];
 #pragma unroll
-    for (int j = 0; j < 2; j++)
+    for (int b = 0; b < RB; b++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) acc[j][v] = 0.f;
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[b][j][v] = 0.f;
     {
         FA fa;
         FB fb;
         fa.init(p.a, k0, p.K, p.r, wave, lane);
         fb.init(p.b, n0, p.N, p.r_rows, wave, lane);
-        const FragAddr aa = TA::make(wave_k0, lane);
+        FragAddr aa[RB];
+#pragma unroll
+        for (int b = 0; b < RB; b++) aa[b] = TA::make(wave_k0 + 32 * b, lane);
         const FragAddr ab = TB::make(wave_n0, lane);
         fa.issue(lds, 0, p.r, wave);
         fb.issue(lds + TILE_A_BYTES, 0, p.r, wave);
@@ -216,11 +244,14 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
             wg_barrier();
 #pragma unroll
             for (int s = 0; s < BK / 16; s++) {
-                const bf16x8 ra = TA::frag(cur, aa, 0, s);
+                bf16x8 rb[2];
 #pragma unroll
-                for (int j = 0; j < 2; j++) {
-                    const bf16x8 rb = TB::frag(cur + TILE_A_BYTES, ab, j, s);
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra, rb, acc[j], 0, 0, 0);
+                for (int j = 0; j < 2; j++) rb[j] = TB::frag(cur + TILE_A_BYTES, ab, j, s);
+#pragma unroll
+                for (int b = 0; b < RB; b++) {
+                    const bf16x8 ra = TA::frag(cur, aa[b], 0, s);
+#pragma unroll
+                    for (int j = 0; j < 2; j++) acc[b][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra, rb[j], acc[b][j], 0, 0, 0);
                 }
             }
             FHPC_WAIT_LGKM0();
@@ -229,8 +260,10 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
         }
         FHPC_WAIT_VM(0);        // the last trip's requests (past the end of the rank: zeros) still land in LDS
     }
+    if constexpr (!OUT_F32) wg_barrier();     // ... every wave's: the stages now serve as the waves' output patches
 
-    store_block<WMODE, OUT_F32>(acc, base, p, kw, n, lane);
+#pragma unroll
+    for (int b = 0; b < RB; b++) store_block<WMODE, OUT_F32>(acc[b], base[b], p, kw + 32 * b, n, lane, lds + wave * 4096);
 }
 
 template <int WMODE, bool OUT_F32>
