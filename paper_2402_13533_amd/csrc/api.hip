@@ -342,7 +342,8 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     const int64_t rp = rank_pad(r);
     const bool bwd = (op == FHPC_OP_LOWRANK_BWD || op == FHPC_OP_QLINEAR_BWD);
-    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && !premerged && many_tokens(op, M, K, N)) s.Wm = c.take(K * N * 2);
+    if ((op == FHPC_OP_QLINEAR_FWD || op == FHPC_OP_QLINEAR_BWD) && !premerged && many_tokens(op, M, K, N))
+        s.Wm = c.take((K + rp) * (N + MERGE_EXT_PAD) * 2);          // (room for the factor pair beside and below it, see rides_along)
     if (rp != r) {
         s.A_p = c.take(K * rp * 2);
         s.B_p = c.take(rp * N * 2);
@@ -431,6 +432,48 @@ int pick_tile(int64_t M, int64_t N, bool allow_skinny)
         }
     }
     return best;
+}
+
+// What pick_tile minimises, for the tile it picks.
+static double tile_cost(int64_t M, int64_t N, int* tile_out)
+{
+    const int tile = pick_tile(M, N, false);
+    int bm, bn;
+    gemm_tile_extent(tile, &bm, &bn);
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    if (tile_out) *tile_out = tile;
+    return (double)((tiles + num_cu() - 1) / num_cu()) * bm * bn;
+}
+
+// The merged-weight products of the finetuning layer can carry a rank-r product along: with the merged weight in the
+// extended layout of merge.h, X times it has H = X A in rp extra output columns, and dY times its transpose has
+// dH = dY B^T there, written by the same launch through its second output (no pass over X or dY of their own, no
+// slabs, no slab sum).  That costs one more column of tiles.  It is taken when that column does not add a round
+// of workgroups (4096 tokens x 5120 channels: 656 tiles of 256 x 128 in the three rounds that 640 take; 4096 x 4096
+// is exactly one round of 256 x 256 tiles and a 17th column would double it), when the request-fed kernels run
+// the product on a tile whose width divides `width`, and for no more than 64 extra columns.
+static bool rides_along(int a_mode, int b_mode, int64_t M, int64_t width, int64_t rp)
+{
+    if (rp > 64) return false;
+    int tile = 0, tile0 = 0;
+    const double with = tile_cost(M, width + rp, &tile), without = tile_cost(M, width, &tile0);
+    if (with > without) return false;
+    int bm, bn;
+    gemm_tile_extent(tile, &bm, &bn);
+    return width % bn == 0 && gemm_pp_supports(a_mode, b_mode, OP_NONE, OUT_BF16, tile);
+}
+
+// C[M][n_main] (ldc) and C2[M][n_all - n_main] (ldc2): one bf16 product whose trailing columns go to a second output.
+static hipError_t gemm_two_outputs(int a_mode, int b_mode, GemmOperand a, GemmOperand b, void* C, int64_t ldc, void* C2, int64_t ldc2,
+                                   int64_t M, int64_t n_main, int64_t n_all, int64_t Kred, Run& run)
+{
+    if (run.dry) return hipSuccess;
+    GemmArgs g = {};
+    g.a = a; g.b = b; g.c = C; g.ldc = ldc;
+    g.c2 = C2; g.ldc2 = ldc2; g.n_split = (int)n_main;
+    g.M = (int)M; g.N = (int)n_all; g.K = (int)Kred; g.K2 = 0;
+    g.alpha = 1.f; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
+    return launch_gemm_bf16(a_mode, b_mode, OP_NONE, OUT_BF16, pick_tile(M, n_all, false), g, run.st);
 }
 
 GemmOperand operand(const void* p, int64_t ld, const void* scales = nullptr, int64_t sld = 0)
@@ -1148,6 +1191,13 @@ static int seq_qlinear_fwd(Run& run, const Scratch& s, const void* X, const void
         // many tokens (or a weight merged by the caller): one plain product with the merged weight; H only if
         // the caller wants it
         const void* Wm = Wq;
+        if (!premerged && H_out && rides_along(OP_KC, OP_XC, M, N, rp)) {
+            // H = X A out of the same product: A stands in rp extra columns of the merged weight
+            FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st, true));
+            FHPC_HIP(gemm_two_outputs(OP_KC, OP_XC, operand(X, K), operand(s.Wm, N + MERGE_EXT_PAD), Y, N, H, rp, M, N, N + rp, K, run));
+            if (rp != r) FHPC_LAUNCH(run, launch_pad2d_u16(H, rp, M, r, H_out, r, M, run.st));
+            return FHPC_OK;
+        }
         if (!premerged) {
             FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st));
             Wm = s.Wm;
@@ -1381,19 +1431,26 @@ static int seq_qlinear_bwd(Run& run, const Scratch& s, const void* X, const void
     const bool merged_dx = premerged || (s.Wm != nullptr && base_scale != 0.f);   // then dX does not need dH
     const bool streamed_dx = dX && s.sk_dxpart && base_scale != 0.f;
     const bool dh_on_the_way = streamed_dx && s.sk_dhpart;                        // the streaming launch forms dH itself
-    if (!dh_on_the_way && (dA || (dX && !merged_dx)))
+    // (many tokens: dH = dY B^T can come out of the dX product itself, B standing in rp extra rows of the merged weight)
+    const bool dh_rides = dX && merged_dx && !premerged && dA && rides_along(OP_KC, OP_KC, M, K, rp);
+    if (!dh_on_the_way && !dh_rides && (dA || (dX && !merged_dx)))
         FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, run));
     if (dX && base_scale == 0.f) {
         FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(s.dH, rp), operand(f.A, rp), dX, K, M, K, rp, run, scaling));
     } else if (dX && merged_dx) {
         // many tokens: dX = dY W'^T with the merged weight W' = base_scale deq(W) + scaling A B
         const void* Wm = Wq;
-        if (!premerged) {
-            const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
-            FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st));
-            Wm = s.Wm;
+        const int w_kind = dense ? 1 : (qscheme == FHPC_Q_INT8_PER_CHANNEL) ? 2 : 3;
+        if (dh_rides) {
+            FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st, true));
+            FHPC_HIP(gemm_two_outputs(OP_KC, OP_KC, operand(dY, N), operand(s.Wm, N + MERGE_EXT_PAD), dX, K, s.dH, rp, M, K, K + rp, N, run));
+        } else {
+            if (!premerged) {
+                FHPC_LAUNCH(run, launch_merge(Wq, scales, w_kind, f.A, rp, f.B, base_scale, scaling, s.Wm, false, K, rp, N, run.st));
+                Wm = s.Wm;
+            }
+            FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, run));
         }
-        FHPC_HIP(gemm_plain(OP_KC, OP_KC, operand(dY, N), operand(Wm, N), dX, K, M, K, N, run));
     } else if (streamed_dx) {
         // a handful of tokens: one pass over the packed weight (slabs; for r <= 16 also dH = dY B^T),
         // then slabs + rank-r branch -> bf16, and dH for dA

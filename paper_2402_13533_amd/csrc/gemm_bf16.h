@@ -67,6 +67,12 @@ struct GemmArgs {
     const void* ga[GEMM_MAX_GROUPS];
     const void* gb[GEMM_MAX_GROUPS];
     void* gc[GEMM_MAX_GROUPS];
+    // n_split > 0 (request-fed kernels, bf16 output, no groups): a second output of the same launch.  Columns
+    // [0, n_split) go to c (ldc) as usual, columns [n_split, N) to c2 (leading dimension ldc2) as its columns
+    // 0 .. N - n_split - 1.  n_split must be a multiple of the tile's width and N - n_split of 8.
+    void* c2;
+    int64_t ldc2;
+    int n_split;
     int dbg;               // kernel choice for tests, 0 in normal use: bit 2 = lockstep kernels only, bit 3 =
                            // four-wave kernel where it exists.  A build with -DFHPC_DIAG also honours bit 0
                            // (request no operand data) and bit 1 (skip the matrix instructions, lockstep only).

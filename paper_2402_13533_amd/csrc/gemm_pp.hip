@@ -317,7 +317,9 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     }
     // (After the loop's last barrier no wave reads the ring any more; with a successor, the requests still
     // in flight are the successor's.)
-    const bool inside = (out_m0 + BM <= p.M) && (out_n0 + BN <= p.N);
+    // A tile at or beyond p.n_split belongs to the launch's second output (c2): it takes the guarded stores.
+    const bool second = p.n_split > 0 && out_n0 >= p.n_split;
+    const bool inside = (out_m0 + BM <= p.M) && (out_n0 + BN <= p.N) && !second;
     chained = chain;
     relaxed = chain && inside && OUT_MODE == OUT_BF16;
 #ifdef FHPC_DIAG
@@ -405,15 +407,19 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
                         __builtin_amdgcn_raw_buffer_store_b128(v, rs_c, lane_off, soff, 0);
                     }
                 } else {
-                    const int col = out_n0 + wave_n0 + rc * 8;
+                    // (edge tiles, and the tiles of a second output: its own base, leading dimension and width)
+                    uint16_t* const eo = reinterpret_cast<uint16_t*>(second ? p.c2 : out_c);
+                    const size_t eld = (size_t)(second ? p.ldc2 : p.ldc);
+                    const int ecols = second ? p.N - p.n_split : (p.n_split > 0 ? p.n_split : p.N);
+                    const int col = out_n0 - (second ? p.n_split : 0) + wave_n0 + rc * 8;
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const int row = rr + 8 * q;
                         u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
                         if (q & 1) v = u32x4{v.z, v.w, v.x, v.y};
                         const int m = out_m0 + wave_m0 + i * 32 + row;
-                        if (m < p.M && col < p.N)
-                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out_c) + (size_t)m * (size_t)p.ldc + (size_t)col) = v;
+                        if (m < p.M && col < ecols)
+                            *reinterpret_cast<u32x4*>(eo + (size_t)m * eld + (size_t)col) = v;
                     }
                 }
             }
@@ -472,6 +478,8 @@ namespace pp {
 template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT>
 static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 {
+    if (a.n_split > 0 && (OUT != OUT_BF16 || a.groups > 1 || a.n_split % BN != 0 || a.n_split >= a.N || (a.N - a.n_split) % 8 != 0 || !a.c2))
+        return hipErrorInvalidValue;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const int total = tiles * (a.splits > 1 ? a.splits : 1) * (a.groups > 1 ? a.groups : 1);
     const int cus = compute_units();

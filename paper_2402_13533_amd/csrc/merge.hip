@@ -43,6 +43,10 @@ struct MergeArgs {
     float base_scale;      // factor on the base weight (1 for the merged weight of Sec. 5.1; alpha for the blend layer)
     int K, N, r;           // r: rank rounded up to a multiple of 8 (the copy of A is zero-padded)
     int r_rows;            // rows of B that exist
+    int ldo;               // row stride of out in elements: N, or N + MERGE_EXT_PAD with `ext`
+    int ext;               // out is [(K + r)][(N + MERGE_EXT_PAD)] bf16: W' in its K x N corner, A in columns N .. N + r - 1 of those
+                           // rows, B in rows K .. K + r - 1 of those columns (the r x r corner zero): one buffer whose
+                           // products with X and with dY also give H = X A and dH = dY B^T as r extra output columns
 };
 
 // value of the lane with the other parity in the same pair (lanes 2 m and 2 m + 1)
@@ -120,14 +124,14 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
         rows[8 * (v / 4) + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[0]);
         rows[8 * (v / 4) + 4 + (v % 4)] = __builtin_bit_cast(float, (uint32_t)sw[1]);
     }
-    const __amdgpu_buffer_rsrc_t ro = matrix_rsrc(p.out, p.K, p.N, OUT_F32 ? 4 : 2);
+    const __amdgpu_buffer_rsrc_t ro = matrix_rsrc(p.out, p.K, p.ldo, OUT_F32 ? 4 : 2);
     const int rows_valid = p.K - kw;               // rows of this block that exist (scalar)
-    const int rowbytes = p.N * (OUT_F32 ? 4 : 2);
+    const int rowbytes = p.ldo * (OUT_F32 ? 4 : 2);
     const bool odd = lane & 1;
     // fp32: the lane's own column, rows q and q + 1 in turn.  bf16: the column pair (n & ~1, + 1) of row
     // q (even lanes) or q + 1 (odd lanes), see below.
-    const uint32_t lane_off = (n < p.N) ? (OUT_F32 ? (uint32_t)(kw * p.N + n) * 4u
-                                                    : (uint32_t)((kw + (odd ? 1 : 0)) * p.N + (n & ~1)) * 2u) : MRG_OOB;
+    const uint32_t lane_off = (n < p.N) ? (OUT_F32 ? (uint32_t)(kw * p.ldo + n) * 4u
+                                                    : (uint32_t)((kw + (odd ? 1 : 0)) * p.ldo + (n & ~1)) * 2u) : MRG_OOB;
     // bf16 halves of (own, neighbour) words recombined by one byte permute: even lanes keep their low
     // half and take the neighbour's low half on top, odd lanes take the neighbour's high half below their own
     const uint32_t pick = odd ? 0x03020706u : 0x05040100u;
@@ -174,7 +178,7 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
         // lane -> row lane / 8 (+ 8 per instruction), columns 8 (lane % 8) .. + 7 of the wave's 64
         const int rr = lane >> 3, rc = lane & 7;
         const int n8 = n - lane + rc * 8;                                   // first of the lane's eight columns
-        const uint32_t off16 = (n8 < p.N) ? (uint32_t)((kw + rr) * p.N + n8) * 2u : MRG_OOB;   // (N is a multiple of 8)
+        const uint32_t off16 = (n8 < p.N) ? (uint32_t)((kw + rr) * p.ldo + n8) * 2u : MRG_OOB;   // (N is a multiple of 8)
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             if (8 * k >= rows_valid) break;        // uniform: rows come in groups of eight
@@ -264,6 +268,35 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
 
 #pragma unroll
     for (int b = 0; b < RB; b++) store_block<WMODE, OUT_F32>(acc[b], base[b], p, kw + 32 * b, n, lane, lds + wave * 4096);
+
+    if constexpr (!OUT_F32) {
+        if (p.ext) {
+            // the factor pair beside and below W' (16-byte pieces; rows of B beyond r_rows and the corner are zero)
+            uint16_t* const out = static_cast<uint16_t*>(p.out);
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            const int pieces = p.r / 8;
+            if (tn == 0) {
+                const uint16_t* const A = static_cast<const uint16_t*>(p.a.ptr);
+                for (int t = tid; t < TK * pieces; t += NT) {
+                    const int k = k0 + t / pieces, c = (t % pieces) * 8;
+                    if (k < p.K)
+                        *reinterpret_cast<u32x4*>(out + (size_t)k * p.ldo + p.N + c) = *reinterpret_cast<const u32x4*>(A + (size_t)k * p.a.ld + c);
+                }
+            }
+            if (tk == 0) {
+                const uint16_t* const B = static_cast<const uint16_t*>(p.b.ptr);
+                for (int t = tid; t < p.r * (TN / 8); t += NT) {
+                    const int j = t / (TN / 8), c = n0 + (t % (TN / 8)) * 8;
+                    if (c < p.N)
+                        *reinterpret_cast<u32x4*>(out + (size_t)(p.K + j) * p.ldo + c) =
+                            (j < p.r_rows) ? *reinterpret_cast<const u32x4*>(B + (size_t)j * p.b.ld + c) : zero;
+                }
+                if (tn == 0)
+                    for (int t = tid; t < p.r * pieces; t += NT)
+                        *reinterpret_cast<u32x4*>(out + (size_t)(p.K + t / pieces) * p.ldo + p.N + (t % pieces) * 8) = zero;
+            }
+        }
+    }
 }
 
 template <int WMODE, bool OUT_F32>
@@ -281,7 +314,8 @@ static hipError_t launch(const MergeArgs& a, double w_bytes, hipStream_t s)
 }  // namespace mrg
 
 hipError_t launch_merge(const void* W, const void* scales, int w_kind, const void* A, int64_t lda, const void* B,
-                        float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s)
+                        float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s,
+                        bool ext)
 {
     using namespace mrg;
     MergeArgs a;
@@ -296,6 +330,9 @@ hipError_t launch_merge(const void* W, const void* scales, int w_kind, const voi
     a.N = (int)N;
     a.r = (int)lda;
     a.r_rows = (int)r;
+    if (ext && out_f32) return hipErrorInvalidValue;
+    a.ext = ext ? 1 : 0;
+    a.ldo = (int)(ext ? N + MERGE_EXT_PAD : N);
     const double kn = (double)K * (double)N;
     const double wbytes[4] = {0.0, 2.0 * kn, kn + 2.0 * N, 0.5 * kn + kn / 32.0};
     if (w_kind < 0 || w_kind > 3) return hipErrorInvalidValue;
