@@ -146,6 +146,18 @@ def test_qlinear_many_tokens(scheme, M, K, r, N):
 
 
 @pytest.mark.parametrize("scheme,M,K,r,N", [
+    (4, 1300, 2048, 12, 2560),    # ragged token count, rank padded to 16: H rides forward (11th tile column), dH backward (9th)
+    (8, 1300, 2560, 40, 2048),    # rank 40: two fifths of the riding tile column are real
+    (4, 2304, 1024, 8, 3584),     # 9 x 14 tiles of 256 x 256 forward; backward K = 1024 is 9 x 8 tiles of 256 x 128
+])
+def test_qlinear_many_tokens_rank_products_ride_along(scheme, M, K, r, N):
+    """Merged-weight route on shapes where the rank-r products ride in the frozen-weight products: H = X A and
+    dH = dY B^T come out of the Y and dX launches as extra output columns (second output of the launch).  Y, H, dX,
+    dA and dB against the oracle as everywhere."""
+    _run_case("ride q%d %s" % (scheme, (M, K, r, N)), scheme, M, K, r, N, 2.0, 8, tensor_base=170)
+
+
+@pytest.mark.parametrize("scheme,M,K,r,N", [
     (8, 2048, 2304, 8, 4224),     # 8 x 33 tiles of 256 x 128: one tile column beyond a full round
     (4, 2048, 2560, 16, 5120),    # 8 x 40 tiles: a quarter round beyond
     (4, 2048, 5120, 16, 2560),    # the same remainder in the backward product (outputs along K = 5120)
