@@ -660,6 +660,30 @@ def quantised_stream(fhpc):
                     rows.append({"config": cfg, "tokens": M, "pass": "fwd" if fwd_only else "fwd+bwd", "launch": launch,
                                  "ms_per_step": mean, "ms_per_step_median": med, "ms_per_step_min": mn, "algorithmic_bytes": io,
                                  "gbs": io / (mean * 1e-3) / 1e9, "frac_hbm_peak": io / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                if cfg == "c5" and fwd_only:
+                    # the same forward as a decoder layer issues it: q, k and v read one X and so do gate and up, each
+                    # group in one call of qlinear_lowrank_fwd_shared_x (four launches per step instead of seven)
+                    shared = []
+                    for cs in sets:
+                        q, k, v, o, gate, up, down = cs
+                        shared.append([SharedXCall(fhpc, [q, k, v]), o, SharedXCall(fhpc, [gate, up]), down])
+                    sstate = {"i": 0}
+
+                    def sstep():
+                        for c in shared[sstate["i"] % copies]:
+                            c.run()
+                        sstate["i"] += 1
+
+                    def sall():
+                        for _ in range(copies):
+                            sstep()
+                    sio = sum(c.io_bytes() for c in shared[0])
+                    mean, med, mn = (t / copies for t in time_steps(sall, 10, 2, graph=True))
+                    rows.append({"config": cfg, "tokens": M, "pass": "fwd, q/k/v and gate/up through the shared-X call",
+                                 "launch": "hip_graph", "ms_per_step": mean, "ms_per_step_median": med, "ms_per_step_min": mn,
+                                 "algorithmic_bytes": sio, "gbs": sio / (mean * 1e-3) / 1e9,
+                                 "frac_hbm_peak": sio / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                    del shared, sstep, sall
                 del sets, step
         rows[-1]["weight_copies"] = copies
         rows[-1]["packed_weight_bytes_all_copies"] = packed
