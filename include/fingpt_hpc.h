@@ -174,7 +174,7 @@ int qlinear_lowrank_bwd(const void* X, const void* Wq, const void* scales, int q
  * qlinear_lowrank_fwd; K, r, the storage scheme and M are shared, N and scaling are per weight.  Each
  * Y is its own dense [M][N] matrix.  Result: exactly what `count` calls of qlinear_lowrank_fwd give up
  * to summation order.  With at most 64 tokens (and up to four weights, r <= 64, K a multiple of 256)
- * all weights go through one pair of launches, which is the point: such a call is bound by launch
+ * all weights go through one launch, which is the point: such a call is bound by launch
  * latency, not by the weight stream.  Otherwise the weights are processed one after another.
  * Workspace: fhpc_workspace_bytes_shared_x (host-only; 0 for invalid arguments). */
 typedef struct {

@@ -1369,7 +1369,7 @@ int qlinear_lowrank_fwd_shared_x(const void* X, const fhpc_qlinear_weight* weigh
     if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (count <= QSKINNY_MAX_JOBS && qskinny_supports(M, K, r, N[0], qscheme)) {
-        // few tokens: every weight in one pair of launches
+        // few tokens: every weight in one launch
         const QskinnyPlan p = qskinny_plan(M, K, r, N, count, num_cu());
         Carver c(workspace);
         uint32_t* header = static_cast<uint32_t*>(c.take(QSKINNY_HEADER_BYTES));

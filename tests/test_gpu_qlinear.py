@@ -303,7 +303,7 @@ def test_few_token_forward(scheme, M, K, r, N):
 @pytest.mark.parametrize("M", [1, 16, 40, 100])
 def test_shared_x_forward(scheme, M):
     """Three projections that read the same X (widths as with grouped key/value heads, one of them not a
-    multiple of 64) in one call: up to 64 tokens they share one pair of launches, at 100 tokens the call
+    multiple of 64) in one call: up to 64 tokens they share one launch, at 100 tokens the call
     runs them one after another.  Every output against the oracle's single layer."""
     fhpc = _fhpc()
     K, r = 1024, 16
