@@ -34,21 +34,35 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
     const int tx = tid & 15, ty = tid >> 4;
     float acc[4][4] = {};
+    // element i of this thread in the A and B tiles: the faster-varying thread index follows the contiguous stride
+    int amm[4], akk[4], bnn[4], bkk[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int e = tid + 256 * i;
+        if (acs == 1) { akk[i] = e & 15; amm[i] = e >> 4; } else { amm[i] = e & 63; akk[i] = e >> 6; }
+        if (brs == 1) { bkk[i] = e & 15; bnn[i] = e >> 4; } else { bnn[i] = e & 63; bkk[i] = e >> 6; }
+    }
+    // the next 16-deep step's operands are requested before the current step's sums, so that a step does not wait
+    // out a round trip to memory (the products of the fp32 configuration are small: the latency was all they took)
+    float ra[4], rb[4];
+    auto fetch = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int m = m0 + amm[i], k = k0 + akk[i];
+            ra[i] = (m < M && k < K) ? A[(int64_t)m * ars + (int64_t)k * acs] : 0.f;
+            const int n = n0 + bnn[i], k2 = k0 + bkk[i];
+            rb[i] = (n < N && k2 < K) ? B[(int64_t)k2 * brs + (int64_t)n * bcs] : 0.f;
+        }
+    };
+    fetch(0);
     for (int k0 = 0; k0 < K; k0 += 16) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const int e = tid + 256 * i;
-            // A tile element (mm, kk): let the faster-varying thread index follow the contiguous stride
-            int mm, kk;
-            if (acs == 1) { kk = e & 15; mm = e >> 4; } else { mm = e & 63; kk = e >> 6; }
-            const int m = m0 + mm, k = k0 + kk;
-            sA[kk][mm] = (m < M && k < K) ? A[(int64_t)m * ars + (int64_t)k * acs] : 0.f;
-            int nn, kb;
-            if (brs == 1) { kb = e & 15; nn = e >> 4; } else { nn = e & 63; kb = e >> 6; }
-            const int n = n0 + nn, k2 = k0 + kb;
-            sB[kb][nn] = (n < N && k2 < K) ? B[(int64_t)k2 * brs + (int64_t)n * bcs] : 0.f;
+            sA[akk[i]][amm[i]] = ra[i];
+            sB[bkk[i]][bnn[i]] = rb[i];
         }
         __syncthreads();
+        if (k0 + 16 < K) fetch(k0 + 16);
 #pragma unroll
         for (int kk = 0; kk < 16; kk++) {
             float a[4], b[4];
