@@ -1615,7 +1615,7 @@ int lowrank_merge(const void* W, const void* scales, int qscheme, int block, con
         FHPC_HIP(launch_pad2d_u16(A, r, K, r, Apad, rp, K, st));
         Ap = Apad;
     }
-    FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, 1.f, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st));
+    FHPC_HIP(launch_merge(W, scales, w_kind, Ap, rp, B, 1.f, scaling, W_out, out_dtype == FHPC_F32, K, r, N, st, false, true));
     return FHPC_OK;
 }
 

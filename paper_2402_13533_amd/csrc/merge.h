@@ -16,8 +16,11 @@ constexpr int MERGE_EXT_PAD = 128;
 // 256-byte aligned: with a row stride of N + 16 every 256-byte request of the products straddled three cache lines
 // and the products ran 8 % slower.  X times that buffer's first K rows is [Y | H]; dY times its first N columns,
 // transposed, is [dX | dH].
+// `stream_out`: the output leaves with non-temporal stores.  Right when nothing reads it soon (the merged weight
+// handed to the caller: the kernel alone is a third faster); wrong inside the layer's own calls, whose product reads
+// the merged weight straight back and wants it in the Infinity Cache (measured: the step gets 3 % slower).
 hipError_t launch_merge(const void* W, const void* scales, int w_kind, const void* A, int64_t lda, const void* B,
                         float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s,
-                        bool ext = false);
+                        bool ext = false, bool stream_out = false);
 
 }  // namespace fhpc

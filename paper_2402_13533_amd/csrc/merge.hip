@@ -108,7 +108,7 @@ __device__ __forceinline__ void load_base(BaseRegs<WMODE>& b, const MergeArgs& p
 
 // out = base_scale * base + scaling * acc for the wave's 32 x 64 block, straight from the accumulators
 // (acc[j]: register v holds row kw + 8 (v / 4) + 4 (lane / 32) + v % 4, column n_block + 32 j + lane % 32).
-template <int WMODE, bool OUT_F32>
+template <int WMODE, bool OUT_F32, bool NT>
 __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRegs<WMODE>& b, const MergeArgs& p, int kw, int n, int lane,
                                             unsigned char* patch)
 {
@@ -163,8 +163,8 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
         const float o1 = rows[q + 1] + base1;
         if constexpr (OUT_F32) {
             if (q >= rows_valid) continue;         // uniform: K is a multiple of 8, a row pair is in or out as one
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o0), ro, lane_off, q * rowbytes, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o1), ro, lane_off, (q + 1) * rowbytes, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o0), ro, lane_off, q * rowbytes, NT ? 2 : 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o1), ro, lane_off, (q + 1) * rowbytes, NT ? 2 : 0);
         } else {
             // An even lane ends up with columns (n, n + 1) of row q, its odd neighbour with (n - 1, n) of row q + 1.
             const uint32_t own = pack_bf16(o0, o1);                          // (row q, row q + 1) of this column
@@ -184,12 +184,12 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[2], const BaseRe
             if (8 * k >= rows_valid) break;        // uniform: rows come in groups of eight
             const int row = rr + 8 * k;
             const u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
-            __builtin_amdgcn_raw_buffer_store_b128(v, ro, off16, 8 * k * rowbytes, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(v, ro, off16, 8 * k * rowbytes, NT ? 2 : 0);
         }
     }
 }
 
-template <int WMODE, bool OUT_F32>
+template <int WMODE, bool OUT_F32, bool STREAM>
 __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
 {
     using FA = Feeder<OP_KC, TK, BK, 4>;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     if constexpr (!OUT_F32) wg_barrier();     // ... every wave's: the stages now serve as the waves' output patches
 
 #pragma unroll
-    for (int b = 0; b < RB; b++) store_block<WMODE, OUT_F32>(acc[b], base[b], p, kw + 32 * b, n, lane, lds + wave * 4096);
+    for (int b = 0; b < RB; b++) store_block<WMODE, OUT_F32, STREAM>(acc[b], base[b], p, kw + 32 * b, n, lane, lds + wave * 4096);
 
     if constexpr (!OUT_F32) {
         if (p.ext) {
@@ -299,14 +299,14 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     }
 }
 
-template <int WMODE, bool OUT_F32>
+template <int WMODE, bool OUT_F32, bool STREAM>
 static hipError_t launch(const MergeArgs& a, double w_bytes, hipStream_t s)
 {
     const int tiles = ((a.K + TK - 1) / TK) * ((a.N + TN - 1) / TN);
     const double bytes = w_bytes + (double)a.K * a.N * (OUT_F32 ? 4.0 : 2.0) + 2.0 * a.r_rows * ((double)a.K + a.N);
     const char* names[4] = {"merge<none>", "merge<bf16>", "merge<int8>", "merge<int4>"};
     const int slot = prof_begin(names[WMODE], 2.0 * a.K * (double)a.N * a.r_rows, bytes, s);
-    hipLaunchKernelGGL((merge_kernel<WMODE, OUT_F32>), dim3((unsigned)tiles), dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((merge_kernel<WMODE, OUT_F32, STREAM>), dim3((unsigned)tiles), dim3(NT), 0, s, a);
     prof_end(slot, s);
     return hipGetLastError();
 }
@@ -315,7 +315,7 @@ static hipError_t launch(const MergeArgs& a, double w_bytes, hipStream_t s)
 
 hipError_t launch_merge(const void* W, const void* scales, int w_kind, const void* A, int64_t lda, const void* B,
                         float base_scale, float scaling, void* out, bool out_f32, int64_t K, int64_t r, int64_t N, hipStream_t s,
-                        bool ext)
+                        bool ext, bool stream_out)
 {
     using namespace mrg;
     MergeArgs a;
@@ -338,7 +338,7 @@ hipError_t launch_merge(const void* W, const void* scales, int w_kind, const voi
     if (w_kind < 0 || w_kind > 3) return hipErrorInvalidValue;
 #define FHPC_MERGE_CASE(KIND, F32)                                                                               \
     if (w_kind == KIND && out_f32 == F32)                                                                        \
-        return launch<KIND, F32>(a, wbytes[KIND], s);
+        return stream_out ? launch<KIND, F32, true>(a, wbytes[KIND], s) : launch<KIND, F32, false>(a, wbytes[KIND], s);
     FHPC_MERGE_CASE(W_NONE, true)
     FHPC_MERGE_CASE(W_NONE, false)
     FHPC_MERGE_CASE(W_BF16, true)
