@@ -207,7 +207,21 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
     const int wave_k0 = (wave >> 1) * (32 * RB);               // the wave's RB blocks of 32 rows ...
     const int wave_n0 = (wave & 1) * 64;                       // ... by two blocks of 32 columns
     const int tiles_n = (p.N + TN - 1) / TN;
-    const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
+    int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
+    if constexpr (STREAM) {
+        // A quantised channel's codes are contiguous along k and a 64-row tile takes 32 (int4) or 64 (int8) bytes of
+        // each 128-byte line: the four tiles that follow one another along k share their lines.  Workgroups go to
+        // the eight XCDs in turn (id % 8), each with an L2 of its own, so the four tiles of a line take four
+        // consecutive slots of one XCD and the line comes from memory once (row-major tile order fetched 78 MB for
+        // a 37.6 MB int4 weight).  With streamed output the kernel is bound by bytes and this pays (40 -> 36 us);
+        // with cached output it is not and it costs 3 % (measured both ways).
+        const int tiles_k = (p.K + TK - 1) / TK;
+        const int xcd = (int)blockIdx.x & 7, slot = (int)blockIdx.x >> 3;
+        const int t = (slot >> 2) * 8 + xcd;                  // (column tile, group of four row tiles)
+        tn = t % tiles_n;
+        tk = 4 * (t / tiles_n) + (slot & 3);
+        if (tk >= tiles_k) return;                             // (the whole workgroup: padding of the last group or block)
+    }
     const int k0 = tk * TK, n0 = tn * TN;
     const int kw = k0 + wave_k0;                               // first row of the wave
     // accumulator register v of block (b, j): row kw + 32 b + 8 (v / 4) + 4 (lane / 32) + v % 4, column n0 + wave_n0 + 32 j + lane % 32
@@ -302,7 +316,12 @@ __global__ __launch_bounds__(NT) void merge_kernel(MergeArgs p)
 template <int WMODE, bool OUT_F32, bool STREAM>
 static hipError_t launch(const MergeArgs& a, double w_bytes, hipStream_t s)
 {
-    const int tiles = ((a.K + TK - 1) / TK) * ((a.N + TN - 1) / TN);
+    int tiles = ((a.K + TK - 1) / TK) * ((a.N + TN - 1) / TN);
+    if (STREAM) {
+        // (column tiles) x (groups of four row tiles), rounded up to whole blocks of 8 groups, four workgroups each
+        const int groups = ((a.K + TK - 1) / TK + 3) / 4 * ((a.N + TN - 1) / TN);
+        tiles = (groups + 7) / 8 * 32;
+    }
     const double bytes = w_bytes + (double)a.K * a.N * (OUT_F32 ? 4.0 : 2.0) + 2.0 * a.r_rows * ((double)a.K + a.N);
     const char* names[4] = {"merge<none>", "merge<bf16>", "merge<int8>", "merge<int4>"};
     const int slot = prof_begin(names[WMODE], 2.0 * a.K * (double)a.N * a.r_rows, bytes, s);
