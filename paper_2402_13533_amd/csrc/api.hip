@@ -655,6 +655,12 @@ int lowrank_fwd_f32(const float* X, const float* A, const float* B, float* Y, fl
 {
     if (run.dry) return FHPC_OK;
     hipStream_t st = run.st;
+    if (lowrank_chain_f32_supports(r)) {
+        // a rank that fits a workgroup's LDS: H = X A never leaves the chip on its way into Y = H B (one launch;
+        // H is stored only if the caller asked for it)
+        FHPC_HIP(launch_lowrank_chain_f32(X, K, A, r, 1, B, N, 1, Y, N, H_out, (int)M, (int)K, (int)r, (int)N, st));
+        return FHPC_OK;
+    }
     float* H = H_out ? H_out : static_cast<float*>(s.H);
     FHPC_HIP(launch_gemm_f32(X, K, 1, A, r, 1, H, r, (int)M, (int)r, (int)K, 1.f, st));
     FHPC_HIP(launch_gemm_f32(H, r, 1, B, N, 1, Y, N, (int)M, (int)N, (int)r, 1.f, st));
@@ -674,10 +680,15 @@ int lowrank_bwd_f32(const float* X, const float* A, const float* B, const float*
         H = Hw;
     }
     float* dH = static_cast<float*>(s.dH);
-    if (dX || dA)   // dH[m][j] = sum_n dY[m][n] B[j][n]
-        FHPC_HIP(launch_gemm_f32(dY, N, 1, B, 1, N, dH, r, (int)M, (int)r, (int)N, 1.f, st));
-    if (dX)         // dX[m][k] = sum_j dH[m][j] A[k][j]
-        FHPC_HIP(launch_gemm_f32(dH, r, 1, A, 1, r, dX, K, (int)M, (int)K, (int)r, 1.f, st));
+    if (dX && lowrank_chain_f32_supports(r)) {
+        // dH = dY B^T stays in LDS on its way into dX = dH A^T (and is stored for dA)
+        FHPC_HIP(launch_lowrank_chain_f32(dY, N, B, 1, N, A, 1, r, dX, K, dA ? dH : nullptr, (int)M, (int)N, (int)r, (int)K, st));
+    } else {
+        if (dX || dA)   // dH[m][j] = sum_n dY[m][n] B[j][n]
+            FHPC_HIP(launch_gemm_f32(dY, N, 1, B, 1, N, dH, r, (int)M, (int)r, (int)N, 1.f, st));
+        if (dX)         // dX[m][k] = sum_j dH[m][j] A[k][j]
+            FHPC_HIP(launch_gemm_f32(dH, r, 1, A, 1, r, dX, K, (int)M, (int)K, (int)r, 1.f, st));
+    }
     if (dA)         // dA[k][j] = sum_m X[m][k] dH[m][j]
         FHPC_HIP(launch_gemm_f32(X, 1, K, dH, r, 1, dA, r, (int)K, (int)r, (int)M, 1.f, st));
     if (dB)         // dB[j][n] = sum_m H[m][j] dY[m][n]

@@ -7,6 +7,12 @@ namespace fhpc {
 
 hipError_t launch_gemm_f32(const float* A, int64_t ars, int64_t acs, const float* B, int64_t brs, int64_t bcs,
                            float* C, int64_t ldc, int M, int N, int K, float alpha, hipStream_t s);
+// Two chained fp32 products with the rank-r intermediate kept in LDS (r <= 64), see kernels_misc.hip:
+// P = L R (M x r, also stored to P_out when given), Out = P S (M x C).
+bool lowrank_chain_f32_supports(int64_t r);
+hipError_t launch_lowrank_chain_f32(const float* L, int64_t ldl, const float* R, int64_t rrs, int64_t rcs,
+                                    const float* S, int64_t srs, int64_t scs, float* Out, int64_t ldo, float* P_out,
+                                    int M, int T, int r, int C, hipStream_t s);
 hipError_t launch_swiglu_fwd(const void* G, const void* U, void* Z, int64_t n, bool bf16, hipStream_t s);
 hipError_t launch_swiglu_bwd(const void* G, const void* U, const void* dZ, void* dG, void* dU, int64_t n,
                              bool bf16, hipStream_t s);

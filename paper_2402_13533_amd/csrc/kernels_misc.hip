@@ -98,6 +98,93 @@ hipError_t launch_gemm_f32(const float* A, int64_t ars, int64_t acs, const float
 }
 
 // ---------------------------------------------------------------------------------
+// Two chained fp32 products through a rank that fits a workgroup's LDS (r <= 64):
+//     P[m][j]   = sum_t L[m][t] R(t, j)          R(t, j) = R[t * rrs + j * rcs]
+//     Out[m][c] = sum_j P[m][j] S(j, c)          S(j, c) = S[j * srs + c * scs]
+// for 16 rows m per workgroup.  Forward of the factorised layer (Sec. 3.2 eq. low_rank_layer): L = X, R = A,
+// S = B gives H = X A and Y = H B; its input gradient: L = dY, R = B (transposed through the strides),
+// S = A gives dH = dY B^T and dX = dH A^T.  The rank-r intermediate stays in LDS between the two
+// products (it is also stored to P_out when the caller wants it: H for the backward pass, dH for dA); each
+// sum runs in index order, in fp32.
+// ---------------------------------------------------------------------------------
+constexpr int CHAIN_ROWS = 16, CHAIN_TC = 64, CHAIN_RMAX = 64;
+
+__global__ __launch_bounds__(256) void lowrank_chain_f32_kernel(const float* __restrict__ L, int64_t ldl,
+                                                                const float* __restrict__ R, int64_t rrs, int64_t rcs,
+                                                                const float* __restrict__ S, int64_t srs, int64_t scs,
+                                                                float* __restrict__ Out, int64_t ldo, float* __restrict__ P_out,
+                                                                int M, int T, int r, int C)
+{
+    __shared__ float sL[CHAIN_ROWS][CHAIN_TC + 1];
+    __shared__ float sR[CHAIN_TC][CHAIN_RMAX + 1];
+    __shared__ float sP[CHAIN_ROWS][CHAIN_RMAX + 1];
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.x * CHAIN_ROWS;
+    const int row = tid >> 4, jg = tid & 15;          // thread: one row, the ranks jg, jg + 16, jg + 32, jg + 48
+    float h[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t0 = 0; t0 < T; t0 += CHAIN_TC) {
+        // the rows' next 64 elements (contiguous along t) ...
+#pragma unroll
+        for (int i = 0; i < CHAIN_ROWS * CHAIN_TC / 256; i++) {
+            const int e = tid + 256 * i, rr = e / CHAIN_TC, tt = e % CHAIN_TC;
+            const int m = m0 + rr, t = t0 + tt;
+            sL[rr][tt] = (m < M && t < T) ? L[(int64_t)m * ldl + t] : 0.f;
+        }
+        // ... and the 64 x r piece of R, read along whichever of its indices is contiguous
+        for (int e = tid; e < CHAIN_TC * r; e += 256) {
+            int tt, j;
+            if (rcs == 1) { tt = e / r; j = e - tt * r; } else { j = e / CHAIN_TC; tt = e - j * CHAIN_TC; }
+            const int t = t0 + tt;
+            sR[tt][j] = (t < T) ? R[(int64_t)t * rrs + (int64_t)j * rcs] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int tt = 0; tt < CHAIN_TC; tt++) {
+            const float x = sL[row][tt];
+#pragma unroll
+            for (int c = 0; c < 4; c++) h[c] = __builtin_fmaf(x, sR[tt][jg + 16 * c], h[c]);     // (ranks beyond r: zero columns of sR are never read back)
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const int j = jg + 16 * c;
+        if (j < r) {
+            sP[row][j] = h[c];
+            if (P_out && m0 + row < M) P_out[(int64_t)(m0 + row) * r + j] = h[c];
+        }
+    }
+    __syncthreads();
+    // second product: a thread owns output columns c = tid, tid + 256, ... for all 16 rows
+    for (int c = tid; c < C; c += 256) {
+        float acc[CHAIN_ROWS];
+#pragma unroll
+        for (int rr = 0; rr < CHAIN_ROWS; rr++) acc[rr] = 0.f;
+        for (int j = 0; j < r; j++) {
+            const float b = S[(int64_t)j * srs + (int64_t)c * scs];
+#pragma unroll
+            for (int rr = 0; rr < CHAIN_ROWS; rr++) acc[rr] = __builtin_fmaf(sP[rr][j], b, acc[rr]);
+        }
+#pragma unroll
+        for (int rr = 0; rr < CHAIN_ROWS; rr++)
+            if (m0 + rr < M) Out[(int64_t)(m0 + rr) * ldo + c] = acc[rr];
+    }
+}
+
+bool lowrank_chain_f32_supports(int64_t r) { return r >= 1 && r <= CHAIN_RMAX; }
+
+hipError_t launch_lowrank_chain_f32(const float* L, int64_t ldl, const float* R, int64_t rrs, int64_t rcs,
+                                    const float* S, int64_t srs, int64_t scs, float* Out, int64_t ldo, float* P_out,
+                                    int M, int T, int r, int C, hipStream_t s)
+{
+    if (M <= 0 || C <= 0) return hipSuccess;
+    if (!lowrank_chain_f32_supports(r)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lowrank_chain_f32_kernel, dim3((unsigned)((M + CHAIN_ROWS - 1) / CHAIN_ROWS)), dim3(256), 0, s,
+                       L, ldl, R, rrs, rcs, S, srs, scs, Out, ldo, P_out, M, T, r, C);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
 // SiLU gate (Sec. 3.1 eq. FFN): fp32 arithmetic on bf16 or fp32 storage.
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }

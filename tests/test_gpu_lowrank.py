@@ -42,6 +42,34 @@ def test_config1_fp32():
 
 
 @pytest.mark.parametrize("M,K,r,N", [
+    (50, 136, 5, 72),        # ragged token count and rank (K and N are multiples of 8 by contract); one launch per chain: H and dH stay in LDS
+    (33, 64, 64, 264),       # the largest rank that fits, a ragged row block, more columns than threads
+    (17, 200, 65, 96),       # one rank beyond: two launches per chain
+    (1, 8, 1, 8),
+])
+def test_fp32_shapes(M, K, r, N):
+    """fp32 storage and arithmetic on shapes other than config 1's (tolerance 1e-5), with H saved, recomputed, and
+    with outputs left out."""
+    import torch
+    fhpc = _fhpc()
+    X, A, B, dY = lowrank_inputs(2, M, K, r, N, bf16=False)
+    Yr, Hr = oracle.lowrank_fwd(X, A, B)
+    ref = (Yr,) + oracle.lowrank_bwd(X, A, B, dY)
+    d = lambda a: torch.from_numpy(a).cuda()
+    Xd, Ad, Bd, dYd = d(X), d(A), d(B), d(dY)
+    Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
+    assert parity_err(from_device(H), Hr, TOL_F32, "H") <= TOL_F32
+    Y2 = fhpc.lowrank_linear_fwd(Xd, Ad, Bd)                          # H not asked for
+    assert torch.equal(Y, Y2)
+    dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H)
+    _check_all("f32 saved-H %s" % ((M, K, r, N),), (Y, dX, dA, dB), ref, TOL_F32)
+    dX, dA, dB = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd)
+    _check_all("f32 recompute %s" % ((M, K, r, N),), (None, dX, dA, dB), ref, TOL_F32)
+    dX3, dA3, dB3 = fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H, need_dA=False)
+    assert dA3 is None and torch.equal(dX3, dX) and torch.equal(dB3, dB)
+
+
+@pytest.mark.parametrize("M,K,r,N", [
     (300, 320, 64, 264),     # ragged in every dimension, several tiles
     (1, 64, 8, 72),          # a single token
     (257, 136, 5, 200),      # rank not a multiple of 8 (padded internally)
