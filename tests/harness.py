@@ -101,3 +101,26 @@ def qlinear_inputs(config: int, M, K, r, N, tensor_base=0):
     B = Bf16.normal(s(2), (r, N), 0.01)
     dY = Bf16.normal(s(3), (M, N), 1.0)
     return W, X, A, B, dY
+
+
+class Guarded:
+    """Output tensors carved out of device buffers that carry 4 KiB of a fill pattern before and after the tensor:
+    check() asserts that a call wrote nothing outside the outputs it was given."""
+    PAD, FILL = 4096, 0xA5
+
+    def __init__(self):
+        self.items = []
+
+    def alloc(self, shape, dtype):
+        import torch
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        body = (n + 255) // 256 * 256
+        buf = torch.full((2 * self.PAD + body,), self.FILL, dtype=torch.uint8, device="cuda")
+        self.items.append((buf, n))
+        return buf[self.PAD:self.PAD + n].view(dtype).reshape(shape)
+
+    def check(self, what=""):
+        for buf, n in self.items:
+            head, tail = buf[:self.PAD], buf[self.PAD + n:]
+            assert bool((head == self.FILL).all()) and bool((tail == self.FILL).all()), (what, "a call wrote outside its output")
+

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, qlinear_inputs, sample_rows, parity_err
+from harness import Guarded, TOL_BF16, Bf16, f16_bits_cuda, from_device, qlinear_inputs, sample_rows, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -88,9 +88,15 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
     Wq, sc = _quantize_host(W, scheme)
     Wd = oracle.dequant(Wq, sc, scheme, 64)
     Wq_d, sc_d = _to_dev(Wq, sc)
+    import torch
     Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
-    Y, H = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, save_H=True)
-    dX, dA, dB = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H)
+    # every output of the first forward and backward sits between guard regions: nothing may be written outside it
+    g = Guarded()
+    bf = torch.bfloat16
+    Y, H = fhpc.qlinear_lowrank_fwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, Y=g.alloc((M, N), bf), H_out=g.alloc((M, r), bf))
+    dX, dA, dB = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd, H_saved=H, dX=g.alloc((M, K), bf),
+                                          dA=g.alloc((K, r), torch.float32), dB=g.alloc((r, N), torch.float32))
+    g.check(tag)
     dX2, dA2, dB2 = fhpc.qlinear_lowrank_bwd(Xd, Wq_d, sc_d, scheme, Ad, Bd, s, dYd)     # recompute H
     if rows is None:
         Yr, Hr = oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, s)

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from harness import TOL_BF16, Bf16, f16_bits_cuda, from_device, parity_err
+from harness import Guarded, TOL_BF16, Bf16, f16_bits_cuda, from_device, parity_err
 
 pytestmark = pytest.mark.gpu
 
@@ -33,9 +33,14 @@ def test_random_shapes(seed):
         Xd, Ad, Bd, dYd = X.cuda(), A.cuda(), B.cuda(), dY.cuda()
         saved = bool(rng.random() < 0.5)
         tag = "%s M=%d K=%d r=%d N=%d saved_H=%s" % (kind, M, K, r, N, saved)
+        # outputs between guard regions: whatever route a shape takes, nothing may be written outside them
+        guard = Guarded()
+        bf = torch.bfloat16
+        fo = dict(Y=guard.alloc((M, N), bf), H_out=guard.alloc((M, r), bf))
+        bo = dict(dX=guard.alloc((M, K), bf), dA=guard.alloc((K, r), torch.float32), dB=guard.alloc((r, N), torch.float32))
         if kind == "lowrank":
-            Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, save_H=True)
-            got = (Y,) + tuple(fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H if saved else None))
+            Y, H = fhpc.lowrank_linear_fwd(Xd, Ad, Bd, **fo)
+            got = (Y,) + tuple(fhpc.lowrank_linear_bwd(Xd, Ad, Bd, dYd, H_saved=H if saved else None, **bo))
             ref = (oracle.lowrank_fwd(X.f64, A.f64, B.f64)[0],) + oracle.lowrank_bwd(X.f64, A.f64, B.f64, dY.f64)
         else:
             if kind == "dense":
@@ -47,15 +52,16 @@ def test_random_shapes(seed):
                 Wq, sc = oracle.quantize_int8_perchannel(Wf) if scheme == 8 else oracle.quantize_int4_block(Wf, 64)
                 Wd, W_dev, sc_dev = oracle.dequant(Wq, sc, scheme, 64), torch.from_numpy(Wq).cuda(), f16_bits_cuda(sc)
             if kind in ("q8", "q4"):
-                Y, H = fhpc.qlinear_lowrank_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, save_H=True)
-                got = (Y,) + tuple(fhpc.qlinear_lowrank_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, dYd, H_saved=H if saved else None))
+                Y, H = fhpc.qlinear_lowrank_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, **fo)
+                got = (Y,) + tuple(fhpc.qlinear_lowrank_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, 2.0, dYd, H_saved=H if saved else None, **bo))
                 ref = (oracle.qlinear_lowrank_fwd(X.f64, Wd, A.f64, B.f64, 2.0)[0],) + oracle.qlinear_lowrank_bwd(X.f64, Wd, A.f64, B.f64, 2.0, dY.f64)
             else:
                 alpha = float(pick([0.0, 0.3, 0.9, 1.0]))
                 tag += " alpha=%.1f" % alpha
-                Y, H = fhpc.qlinear_blend_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, save_H=True)
-                got = (Y,) + tuple(fhpc.qlinear_blend_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, dYd, H_saved=H if saved else None))
+                Y, H = fhpc.qlinear_blend_fwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, **fo)
+                got = (Y,) + tuple(fhpc.qlinear_blend_bwd(Xd, W_dev, sc_dev, scheme, Ad, Bd, alpha, dYd, H_saved=H if saved else None, **bo))
                 ref = (oracle.blend_fwd(X.f64, Wd, A.f64, B.f64, alpha)[0],) + oracle.blend_bwd(X.f64, Wd, A.f64, B.f64, alpha, dY.f64)
+        guard.check(tag)
         for name, g, rf in zip(("Y", "dX", "dA", "dB"), got, ref):
             if np.linalg.norm(rf) > 0:
                 e = parity_err(from_device(g), rf)
