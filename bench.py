@@ -580,6 +580,22 @@ def measured_peaks(fhpc):
         best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     out["hbm_gbs"]["copy_1GiB_read_plus_write"] = best
     del src, dst
+    # One pass over a 4-bit weight of configuration 5 in the few-token kernels' access pattern and nothing else
+    # (rows of K / 2 bytes; eight copies in turn so that the reads come from HBM; 24 passes replayed from a HIP
+    # graph, as the few-token rows are timed): what the read alone costs at that size, launch included.
+    sink = torch.zeros(256, dtype=torch.int32, device=dev)
+    rows = {}
+    for name, (K, N) in {"5120x5120": (5120, 5120), "5120x13824": (5120, 13824), "13824x5120": (13824, 5120)}.items():
+        copies = [torch.empty(N, K // 2, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(8)]
+
+        def passes():
+            for i in range(24):
+                fhpc.probe_read_rows(copies[i % 8], 3 * cus, sink)
+        _, _, best = time_steps(passes, 5, 2, graph=True)
+        n = copies[0].numel()
+        rows[name] = {"weight_MB": n / 1e6, "us_per_pass": best * 1e3 / 24, "gbs": n / (best * 1e-3 / 24) / 1e9}
+        del copies
+    out["hbm_gbs"]["few_token_read_pattern_alone_int4_weights_of_config5"] = rows
     return out
 
 

@@ -314,9 +314,16 @@ int fhpc_profile_get(int index, char* name, int name_len, float* ms, double* flo
  * registers, with no memory traffic; seed (device, 256 x uint32) holds the operand words of a wave (all zero, or
  * random bf16 pairs: the matrix pipes' clock under load depends on the data).  *flops (host) receives the
  * flop count of the launch.  sink (device, workgroups * 256 floats) may be NULL.
- * fhpc_probe_copy: dst[0 .. bytes) = src[0 .. bytes), 16 bytes per lane; bytes a multiple of 16. */
+ * fhpc_probe_copy: dst[0 .. bytes) = src[0 .. bytes), 16 bytes per lane; bytes a multiple of 16.
+ * fhpc_probe_read_rows: one pass over W (device, [N][row_bytes] bytes, 16-byte aligned, row_bytes a multiple of 256,
+ * N * row_bytes < 2^31) in the access pattern of the few-token weight-streaming kernels of Sec. 5.3's inference
+ * path (64 rows x 256 bytes per workgroup and step, the rows cut into as many slices as give one round of
+ * `workgroups` workgroups) with nothing else in the kernel: the time below which no such kernel can get on this
+ * chip at that size.  sink (device, 1 KiB) is never written in practice.  All three return a status code and
+ * only enqueue work on hip_stream. */
 int fhpc_probe_mfma(const void* seed, int workgroups, int iters, float* sink, double* flops, void* hip_stream);
 int fhpc_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
+int fhpc_probe_read_rows(const void* W, int64_t N, int64_t row_bytes, int workgroups, void* sink, void* hip_stream);
 
 /* Host-only test hook (needs no GPU, touches no memory): walks the launch sequence of an entry point for
  * these sizes without launching anything and reports, in bytes, the largest partial-sum area any of its

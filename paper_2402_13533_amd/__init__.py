@@ -26,7 +26,7 @@ EXPORTS = [
     "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
-    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc", "fhpc_probe_mfma", "fhpc_probe_copy",
+    "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc", "fhpc_probe_mfma", "fhpc_probe_copy", "fhpc_probe_read_rows",
 ]
 
 _lib = None
@@ -89,6 +89,7 @@ def load_library():
     lib.fhpc_plan_slab_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32, i32, i32, f32, C.POINTER(i64), C.POINTER(i64)]
     lib.fhpc_probe_mfma.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
     lib.fhpc_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.fhpc_probe_read_rows.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.fhpc_status_string.argtypes = [i32]
     lib.fhpc_status_string.restype = C.c_char_p
     lib.fhpc_version.restype = i32
@@ -137,6 +138,16 @@ def probe_copy(src, dst) -> int:
     if rc:
         raise FhpcError(rc, "fhpc_probe_copy")
     return n
+
+
+def probe_read_rows(W, workgroups: int, sink) -> int:
+    """Enqueue one pass over the byte matrix W ([N][row_bytes], uint8) in the weight-streaming kernels' access
+    pattern and nothing else; returns the bytes read."""
+    N, row_bytes = W.shape
+    rc = load_library().fhpc_probe_read_rows(_ptr(W), N, row_bytes, workgroups, _ptr(sink), _stream())
+    if rc:
+        raise FhpcError(rc, "fhpc_probe_read_rows")
+    return N * row_bytes
 
 
 def status_string(status: int) -> str:

@@ -134,6 +134,19 @@ def test_validation_precedes_launch():
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 16384 + 64 * 8 * 2          # the header, then a padded A
 
 
+def test_read_rows_probe_validates_before_launch():
+    lib = fhpc.load_library()
+    p, odd, nul = C.c_void_p(0x10000), C.c_void_p(0x10004), C.c_void_p(0)
+    f = lib.fhpc_probe_read_rows
+    assert f(nul, 64, 256, 768, p, nul) == 1                   # NULL matrix
+    assert f(p, 64, 256, 768, nul, nul) == 1                   # NULL sink
+    assert f(p, 0, 256, 768, p, nul) == 2                      # no rows
+    assert f(p, 64, 192, 768, p, nul) == 2                     # row_bytes % 256
+    assert f(p, 1 << 20, 4096, 768, p, nul) == 2               # 2^31 bytes and more
+    assert f(p, 64, 256, 0, p, nul) == 2                       # no workgroups
+    assert f(odd, 64, 256, 768, p, nul) == 4                   # alignment
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros((8, 64), dtype=torch.bfloat16)

@@ -72,3 +72,17 @@ def test_four_wave_kernel(a_mode, b_mode, out_mode, splits, M, N, K):
     got, ref = _run(a_mode, b_mode, out_mode, 0, M, N, K, splits=splits, dbg=8, seed=30)
     err = np.linalg.norm(got - ref) / np.linalg.norm(ref)
     assert err <= (TOL_BF16 if out_mode == 0 else 1e-5), err
+
+
+@pytest.mark.parametrize("N,row_bytes,workgroups", [(5120, 2560, 768), (100, 256, 768), (777, 1280, 64), (64, 6912, 4096)])
+def test_read_rows_probe_runs(N, row_bytes, workgroups):
+    """The measurement probe that reads a byte matrix in the few-token kernels' access pattern: it returns the byte
+    count, leaves its sink alone and leaves the matrix as it was (ragged row counts and every slicing case)."""
+    import torch
+    import paper_2402_13533_amd as fhpc
+    W = torch.arange(N * row_bytes, dtype=torch.int64, device="cuda").remainder(251).to(torch.uint8).reshape(N, row_bytes)
+    before = W.clone()
+    sink = torch.zeros(256, dtype=torch.int32, device="cuda")
+    assert fhpc.probe_read_rows(W, workgroups, sink) == N * row_bytes
+    torch.cuda.synchronize()
+    assert torch.equal(W, before) and int(sink.abs().sum()) == 0
