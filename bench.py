@@ -694,11 +694,15 @@ def quantised_stream(fhpc):
                         for _ in range(copies):
                             sstep()
                     sio = sum(c.io_bytes() for c in shared[0])
-                    mean, med, mn = (t / copies for t in time_steps(sall, 10, 2, graph=True))
-                    rows.append({"config": cfg, "tokens": M, "pass": "fwd, q/k/v and gate/up through the shared-X call",
-                                 "launch": "hip_graph", "ms_per_step": mean, "ms_per_step_median": med, "ms_per_step_min": mn,
-                                 "algorithmic_bytes": sio, "gbs": sio / (mean * 1e-3) / 1e9,
-                                 "frac_hbm_peak": sio / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                    for launch in ("eager", "hip_graph"):
+                        if launch == "eager":
+                            mean, med, mn = time_steps(sstep, 40, 8)
+                        else:
+                            mean, med, mn = (t / copies for t in time_steps(sall, 10, 2, graph=True))
+                        rows.append({"config": cfg, "tokens": M, "pass": "fwd, q/k/v and gate/up through the shared-X call",
+                                     "launch": launch, "ms_per_step": mean, "ms_per_step_median": med, "ms_per_step_min": mn,
+                                     "algorithmic_bytes": sio, "gbs": sio / (mean * 1e-3) / 1e9,
+                                     "frac_hbm_peak": sio / (mean * 1e-3) / 1e9 / PEAK_HBM_GBS})
                     del shared, sstep, sall
                 del sets, step
         rows[-1]["weight_copies"] = copies

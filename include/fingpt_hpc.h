@@ -133,6 +133,34 @@ int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* co
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t fhpc_workspace_bytes_lowrank_shared_x(int backward, int64_t M, int64_t K, int64_t r, int64_t N, int g);
 
+/* The FFN's gate and up projections with the gate itself (Sec. 3.1 eq. FFN, every projection a factor pair,
+ * Sec. 4.1 "Method 1"), bf16:
+ *   H_all = X * A_all,   G = H_gate * B_gate,   U = H_up * B_up,   Z = SiLU(G) (.) U   (elementwise)
+ * X [M][K]; A_all [K][2r] = [A_gate | A_up]; B_gate, B_up [r][N]; G_out, U_out, Z_out [M][N] (all three are
+ * written: the backward pass needs G and U); H_all_out [M][2r] or NULL.  All device pointers, 16-byte aligned.
+ * Exactly the results of lowrank_linear_fwd_shared_x with g = 2 followed by swiglu_fwd, bit for bit; when N's
+ * tiles go through the large matrix-core kernel, U's tiles pass the gate in that kernel's epilogue and Z costs
+ * no pass of its own over G and U.  Rules and status codes of lowrank_linear_fwd_shared_x with g = 2.
+ * Workspace: fhpc_workspace_bytes_lowrank_shared_x(0, M, K, r, N, 2). */
+int lowrank_ffn_gate_up_fwd(const void* X, const void* A_all, const void* B_gate, const void* B_up,
+                            void* G_out, void* U_out, void* Z_out, void* H_all_out,
+                            int64_t M, int64_t K, int64_t r, int64_t N,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of the FFN's down projection Y = (Z * A) * B (Sec. 3.1 eq. FFN; Sec. 3.2 eq. low_rank_layer) with
+ * its input gradient taken through the gate, bf16:
+ *   dH = dY * B^T,   dZ = dH * A^T (never stored),   dU = dZ (.) SiLU(G),   dG = dZ (.) U (.) SiLU'(G),
+ *   dA[K,r] = Z^T * dH (fp32),   dB[r,N] = H^T * dY (fp32).
+ * Z [M][K] (the gate's output, this layer's input; K is the FFN's inner width); A [K][r]; B [r][N]; dY [M][N];
+ * H_saved [M][r] or NULL (recomputed); G, U [M][K] as the forward call wrote them; dG_out, dU_out [M][K] bf16;
+ * dA, dB may be NULL.  dZ is rounded to bf16 before the gate, so the results are exactly those of
+ * lowrank_linear_bwd followed by swiglu_bwd.  dU_out may not overlap G or U.  Rules and status codes of
+ * lowrank_linear_bwd.  Workspace: fhpc_workspace_bytes(FHPC_OP_LOWRANK_BWD, M, K, r, N, FHPC_BF16, 0). */
+int lowrank_ffn_down_bwd(const void* Z, const void* A, const void* B, const void* dY, const void* H_saved,
+                         const void* G, const void* U, void* dG_out, void* dU_out, float* dA, float* dB,
+                         int64_t M, int64_t K, int64_t r, int64_t N,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Finetuning layer, forward (Sec. 5.1 eq. new_linear_layer with the frozen weight
  * stored quantised, Sec. 5.2):
  *   Y[M,N] = X[M,K] * deq(Wq, scales)[K,N] + scaling * (X * A[K,r]) * B[r,N].

@@ -24,6 +24,7 @@ FHPC_PLAN_SHARED_FWD, FHPC_PLAN_SHARED_BWD = 16, 17
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose", "qlinear_lowrank_fwd_shared_x", "fhpc_workspace_bytes_shared_x",
     "lowrank_linear_fwd_shared_x", "lowrank_linear_bwd_shared_x", "fhpc_workspace_bytes_lowrank_shared_x",
+    "lowrank_ffn_gate_up_fwd", "lowrank_ffn_down_bwd",
     "fhpc_workspace_bytes", "swiglu_fwd", "swiglu_bwd", "qweight_quantize", "qweight_unpack",
     "qweight_dequant", "fhpc_add", "fhpc_gemm_bf16", "fhpc_profile_start", "fhpc_profile_stop", "fhpc_profile_get",
     "fhpc_status_string", "fhpc_version", "fhpc_plan_slab_bytes", "qlinear_lowrank_fwd_noalloc", "fhpc_probe_mfma", "fhpc_probe_copy", "fhpc_probe_read_rows",
@@ -71,6 +72,8 @@ def load_library():
     pp = C.POINTER(vp)
     lib.lowrank_linear_fwd_shared_x.argtypes = [vp, vp, pp, pp, vp, i64, i64, i64, i64, i32, vp, sz, vp]
     lib.lowrank_linear_bwd_shared_x.argtypes = [vp, vp, pp, pp, vp, vp, vp, pp, i64, i64, i64, i64, i32, vp, sz, vp]
+    lib.lowrank_ffn_gate_up_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp, sz, vp]
+    lib.lowrank_ffn_down_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp, sz, vp]
     lib.fhpc_workspace_bytes_lowrank_shared_x.argtypes = [i32, i64, i64, i64, i64, i32]
     lib.fhpc_workspace_bytes_lowrank_shared_x.restype = sz
     lib.fhpc_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i32, i32]
@@ -315,6 +318,59 @@ def lowrank_linear_fwd_shared_x(X, A_all, Bs, Ys=None, H_all_out=None, save_H: b
     if rc:
         raise FhpcError(rc, "lowrank_linear_fwd_shared_x")
     return (Ys, H_all_out) if H_all_out is not None else Ys
+
+
+def lowrank_ffn_gate_up_fwd(X, A_all, B_gate, B_up, G=None, U=None, Z=None, H_all_out=None, save_H: bool = False, workspace=None):
+    """G = (X A_gate) B_gate, U = (X A_up) B_up, Z = SiLU(G) * U with A_all = [A_gate | A_up] (bf16).
+    Returns (G, U, Z), or (G, U, Z, H_all) when save_H or H_all_out is given."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    M, K = X.shape
+    r, N = B_gate.shape
+    _check(X, "X", None, bf); _check(A_all, "A_all", (K, 2 * r), bf)
+    _check(B_gate, "B_gate", (r, N), bf); _check(B_up, "B_up", (r, N), bf)
+    G = torch.empty((M, N), dtype=bf, device=X.device) if G is None else G
+    U = torch.empty((M, N), dtype=bf, device=X.device) if U is None else U
+    Z = torch.empty((M, N), dtype=bf, device=X.device) if Z is None else Z
+    _check(G, "G", (M, N), bf); _check(U, "U", (M, N), bf); _check(Z, "Z", (M, N), bf)
+    if H_all_out is None and save_H:
+        H_all_out = torch.empty((M, 2 * r), dtype=bf, device=X.device)
+    _check(H_all_out, "H_all_out", (M, 2 * r), bf)
+    ws, wsz = _shared_ws(False, M, K, r, N, 2, X.device, workspace)
+    rc = lib.lowrank_ffn_gate_up_fwd(_ptr(X), _ptr(A_all), _ptr(B_gate), _ptr(B_up), _ptr(G), _ptr(U), _ptr(Z),
+                                     _ptr(H_all_out), M, K, r, N, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_ffn_gate_up_fwd")
+    return (G, U, Z, H_all_out) if H_all_out is not None else (G, U, Z)
+
+
+def lowrank_ffn_down_bwd(Z, A, B, dY, G, U, H_saved=None, need_dA=True, need_dB=True,
+                         dG=None, dU=None, dA=None, dB=None, workspace=None):
+    """Backward of Y = (Z A) B with the input gradient taken through the gate Z = SiLU(G) * U.
+    Returns (dG, dU, dA, dB); dA, dB are fp32."""
+    torch = _torch()
+    lib = load_library()
+    bf = torch.bfloat16
+    M, K = Z.shape
+    r, N = B.shape
+    _check(Z, "Z", None, bf); _check(A, "A", (K, r), bf); _check(B, "B", (r, N), bf)
+    _check(dY, "dY", (M, N), bf); _check(H_saved, "H_saved", (M, r), bf)
+    _check(G, "G", (M, K), bf); _check(U, "U", (M, K), bf)
+    dG = torch.empty((M, K), dtype=bf, device=Z.device) if dG is None else dG
+    dU = torch.empty((M, K), dtype=bf, device=Z.device) if dU is None else dU
+    if dA is None and need_dA:
+        dA = torch.empty((K, r), dtype=torch.float32, device=Z.device)
+    if dB is None and need_dB:
+        dB = torch.empty((r, N), dtype=torch.float32, device=Z.device)
+    _check(dG, "dG", (M, K), bf); _check(dU, "dU", (M, K), bf)
+    _check(dA, "dA", (K, r), torch.float32); _check(dB, "dB", (r, N), torch.float32)
+    ws, wsz = _ws(FHPC_OP_LOWRANK_BWD, M, K, r, N, FHPC_BF16, 0, Z.device, workspace)
+    rc = lib.lowrank_ffn_down_bwd(_ptr(Z), _ptr(A), _ptr(B), _ptr(dY), _ptr(H_saved), _ptr(G), _ptr(U), _ptr(dG), _ptr(dU),
+                                  _ptr(dA), _ptr(dB), M, K, r, N, _ptr(ws), wsz, _stream())
+    if rc:
+        raise FhpcError(rc, "lowrank_ffn_down_bwd")
+    return dG, dU, dA, dB
 
 
 def lowrank_linear_bwd_shared_x(X, A_all, Bs, dYs, H_all_saved=None, need_dX=True, need_dA=True, need_dB=True,

@@ -554,6 +554,28 @@ hipError_t product_bf16(int b_mode, GemmOperand a, GemmOperand b, void* P, int64
     return gemm_plain(OP_KC, b_mode, a, b, P, ldp, M, Nout, Kred, run);
 }
 
+// Whether a dense bf16 product M x Nout runs as one plain launch of the 256 x 256 request-fed kernel, the one
+// whose epilogue can apply the FFN's SiLU gate to the tile it has just produced (GemmArgs::gate).
+static bool gate_rides(int64_t M, int64_t Nout, int64_t Kred)
+{
+    if (large_split_pays(M, Nout, Kred) || split_pays(M, Nout, Kred)) return false;
+    return pick_tile(M, Nout, false) == TILE_256x256;
+}
+
+// P[M][Nout] = a * b^(b_mode) (a with k contiguous) with the gate in the epilogue.  gate 1: P is stored and
+// out1 = SiLU(G) * P; gate 2: P is not stored, out1 = dG and out2 = dU for dZ = P.  All dense, Nout wide.
+static hipError_t gemm_gated(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t M, int64_t Nout, int64_t Kred,
+                             int gate, const void* G, const void* U, void* out1, void* out2, Run& run)
+{
+    if (run.dry) return hipSuccess;
+    GemmArgs g = {};
+    g.a = a; g.b = b; g.c = P; g.ldc = Nout;
+    g.M = (int)M; g.N = (int)Nout; g.K = (int)Kred; g.K2 = 0;
+    g.alpha = 1.f; g.mid_scale = 1.f; g.splits = 1; g.k_chunk = (int)round_up(Kred, 64);
+    g.gate = gate; g.gate_g = G; g.gate_u = U; g.gate_out1 = out1; g.gate_out2 = out2;
+    return launch_gemm_bf16(OP_KC, b_mode, OP_NONE, OUT_BF16, TILE_256x256, g, run.st);
+}
+
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
 // split the long reduction, accumulate in fp32, then round once to bf16.
 hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf, float* part,
@@ -1177,6 +1199,102 @@ int lowrank_linear_bwd_shared_x(const void* X, const void* A_all, const void* co
     run.st = static_cast<hipStream_t>(hip_stream);
     run.part_cap = s.part_bytes;
     return seq_shared_bwd(run, s, X, A_all, B, dY, H_all_saved, dX, dA_all, dB, any_dB, M, K, r, N, g);
+}
+
+// ---- the FFN's gate (Sec. 3.1, eq. FFN) in the epilogue of the product that feeds it ------------------------------
+// Forward: the gate and up projections read one X (the shared-X call with g = 2); U's tiles go through the gate
+// on their way out, against G's finished tiles, so Z costs no pass of its own over G and U.
+static int seq_ffn_gate_up_fwd(Run& run, const SharedScratch& s, const void* X, const void* A_all, const void* B_gate,
+                               const void* B_up, void* G, void* U, void* Z, void* H_all_out,
+                               int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    const int64_t R = 2 * r;
+    void* H = H_all_out ? H_all_out : s.H;
+    FHPC_HIP(narrow_product(OP_XC, operand(X, K), operand(A_all, R), H, R, R, s.Pf, s.part, M, K, run));
+    FHPC_HIP(product_bf16(OP_XC, operand(H, R), operand(B_gate, N), G, N, N, M, r, s.part, run));
+    if (gate_rides(M, N, r)) {
+        FHPC_HIP(gemm_gated(OP_XC, operand(bf16_col(H, r), R), operand(B_up, N), U, M, N, r, 1, G, nullptr, Z, nullptr, run));
+        return FHPC_OK;
+    }
+    FHPC_HIP(product_bf16(OP_XC, operand(bf16_col(H, r), R), operand(B_up, N), U, N, N, M, r, s.part, run));
+    FHPC_LAUNCH(run, launch_swiglu_fwd(G, U, Z, M * N, true, run.st));
+    return FHPC_OK;
+}
+
+// Backward of the down projection Y = (Z A) B with its input gradient taken through the gate: the tiles of
+// dZ = dH A^T leave as dG and dU, and dZ is never stored.  Without the gate epilogue (small or narrow outputs) dZ is
+// written where dU will be and the streaming gate kernel turns it into dG and dU in place.
+static int seq_ffn_down_bwd(Run& run, const Scratch& s, const void* Z, const void* A, const void* B, const void* dY,
+                            const void* H_saved, const void* G, const void* U, void* dG, void* dU, float* dA, float* dB,
+                            int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    const int64_t rp = rank_pad(r);
+    Factors f;
+    int rc = prepare_factors(A, B, K, r, rp, N, s, run, &f);
+    if (rc) return rc;
+    const void* H = nullptr;
+    if (dB) {
+        if (H_saved && rp == r) {
+            H = H_saved;
+        } else if (H_saved) {
+            FHPC_LAUNCH(run, launch_pad2d_u16(H_saved, r, M, r, s.H, rp, M, run.st));
+            H = s.H;
+        } else {
+            FHPC_HIP(rank_product(OP_XC, operand(Z, K), operand(f.A, rp), s.H, rp, s.Hf, s.part, M, K, run));
+            H = s.H;
+        }
+    }
+    FHPC_HIP(rank_product(OP_KC, operand(dY, N), operand(f.B, N), s.dH, rp, s.Hf, s.part, M, N, run));
+    if (gate_rides(M, K, rp)) {
+        FHPC_HIP(gemm_gated(OP_KC, operand(s.dH, rp), operand(f.A, rp), nullptr, M, K, rp, 2, G, U, dG, dU, run));
+    } else {
+        FHPC_HIP(product_bf16(OP_KC, operand(s.dH, rp), operand(f.A, rp), dU, K, K, M, rp, s.part, run));
+        FHPC_LAUNCH(run, launch_swiglu_bwd(G, U, dU, dG, dU, M * K, true, run.st));
+    }
+    return weight_grads(Z, dY, H, s.dH, dA, dB, M, K, r, rp, N, 1.f, s, run);
+}
+
+int lowrank_ffn_gate_up_fwd(const void* X, const void* A_all, const void* B_gate, const void* B_up,
+                            void* G_out, void* U_out, void* Z_out, void* H_all_out,
+                            int64_t M, int64_t K, int64_t r, int64_t N,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!X || !A_all || !B_gate || !B_up || !G_out || !U_out || !Z_out) return FHPC_ERR_NULL;
+    int rc = check_shared(M, K, r, N, 2);
+    if (rc) return rc;
+    if (!aligned(X, 16) || !aligned(A_all, 16) || !aligned(B_gate, 16) || !aligned(B_up, 16) || !aligned(G_out, 16) ||
+        !aligned(U_out, 16) || !aligned(Z_out, 16) || !aligned(H_all_out, 16))
+        return FHPC_ERR_ALIGN;
+    const size_t need = fhpc_workspace_bytes_lowrank_shared_x(0, M, K, r, N, 2);
+    if (need && (!workspace || workspace_bytes < need)) return FHPC_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return FHPC_ERR_ALIGN;
+    Carver c(workspace);
+    const SharedScratch s = carve_shared(c, false, M, K, r, N, 2);
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_ffn_gate_up_fwd(run, s, X, A_all, B_gate, B_up, G_out, U_out, Z_out, H_all_out, M, K, r, N);
+}
+
+int lowrank_ffn_down_bwd(const void* Z, const void* A, const void* B, const void* dY, const void* H_saved,
+                         const void* G, const void* U, void* dG_out, void* dU_out, float* dA, float* dB,
+                         int64_t M, int64_t K, int64_t r, int64_t N,
+                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!Z || !A || !B || !dY || !G || !U || !dG_out || !dU_out) return FHPC_ERR_NULL;
+    int rc = check_common(M, K, r, N);
+    if (rc) return rc;
+    if (!aligned(Z, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(dY, 16) || !aligned(H_saved, 16) || !aligned(G, 16) ||
+        !aligned(U, 16) || !aligned(dG_out, 16) || !aligned(dU_out, 16) || !aligned(dA, 16) || !aligned(dB, 16))
+        return FHPC_ERR_ALIGN;
+    rc = check_workspace(FHPC_OP_LOWRANK_BWD, workspace, workspace_bytes, M, K, r, N, FHPC_BF16);
+    if (rc) return rc;
+    Carver c(workspace);
+    Scratch s = carve(c, FHPC_OP_LOWRANK_BWD, M, K, r, N, FHPC_BF16);
+    Run run;
+    run.st = static_cast<hipStream_t>(hip_stream);
+    run.part_cap = s.part_bytes;
+    return seq_ffn_down_bwd(run, s, Z, A, B, dY, H_saved, G, U, dG_out, dU_out, dA, dB, M, K, r, N);
 }
 
 // Y = base_scale * X deq(W) + scaling * (X A) B

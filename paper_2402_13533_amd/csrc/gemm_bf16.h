@@ -73,6 +73,16 @@ struct GemmArgs {
     void* c2;
     int64_t ldc2;
     int n_split;
+    // gate != 0 (request-fed kernels, 256 x 256 tile, bf16 output, no groups, no second output): the SiLU gate of the
+    // FFN applied to the tile in the epilogue, on C rounded to bf16, with the arithmetic of the streaming gate kernels.
+    // gate == 1: C (the up projection) is stored as usual and gate_out1 = SiLU(gate_g) * C as well.
+    // gate == 2: C (the gradient of the gate's output) is not stored: gate_out1 = d gate_g and gate_out2 = d gate_u.
+    // All four are [M][N] bf16 with C's leading dimension ldc.
+    int gate;
+    const void* gate_g;
+    const void* gate_u;
+    void* gate_out1;
+    void* gate_out2;
     int dbg;               // kernel choice for tests, 0 in normal use: bit 2 = lockstep kernels only, bit 3 =
                            // four-wave kernel where it exists.  A build with -DFHPC_DIAG also honours bit 0
                            // (request no operand data) and bit 1 (skip the matrix instructions, lockstep only).

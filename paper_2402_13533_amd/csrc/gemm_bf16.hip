@@ -826,6 +826,7 @@ hipError_t launch_gemm_bf16(int a_mode, int b_mode, int b2_mode, int out_mode, i
         return launch_gemm_pp(a_mode, b_mode, out_mode, tile, args, stream);
     if (args.groups > 1) return hipErrorInvalidValue;           // grouped products: the request-fed kernels only
     if (args.n_split > 0) return hipErrorInvalidValue;          // a second output: the request-fed kernels only
+    if (args.gate != 0) return hipErrorInvalidValue;           // the gate epilogue: the request-fed kernels only
     const bool skinny = (tile == TILE_256x32 || tile == TILE_32x256);
 #define FHPC_CASE(AM, BMODE, B2, OUT)                                                         \
     if (a_mode == AM && b_mode == BMODE && b2_mode == B2 && out_mode == OUT && !skinny)       \

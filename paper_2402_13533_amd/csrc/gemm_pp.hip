@@ -28,6 +28,7 @@
 // operations complete in order) instead of waiting them out.
 #include "gemm_bf16.h"
 #include "gemm_ring.h"
+#include "gate_math.h"
 #include "profile.h"
 
 #include <stdio.h>
@@ -54,7 +55,7 @@ __device__ unsigned long long g_trace[TRACE_WGS * TRACE_SLOTS];
 #define FHPC_TS(slot) do { } while (0)
 #endif
 
-template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int A_MODE, int B_MODE, int OUT_MODE>
+template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int A_MODE, int B_MODE, int OUT_MODE, int GATE = 0>
 __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 {
     constexpr int TM = 4, TN = 2;                              // every wave: 128 x 64 accumulators
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
     const bool second = p.n_split > 0 && out_n0 >= p.n_split;
     const bool inside = (out_m0 + BM <= p.M) && (out_n0 + BN <= p.N) && !second;
     chained = chain;
-    relaxed = chain && inside && OUT_MODE == OUT_BF16;
+    relaxed = chain && inside && OUT_MODE == OUT_BF16 && GATE == 0;
 #ifdef FHPC_DIAG
     if (p.dbg & 48) relaxed = false;                           // the probes that skip the stores
 #endif
@@ -378,6 +379,23 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
             // (the 8-byte half a lane writes is flipped for rows 8 .. 15 and 24 .. 31, so that the 32 lanes of a
             // half wave spread over both halves of the 16-byte slots; the read-back below swaps them again)
             const uint32_t wr_off = (uint32_t)l32 * 128u + (uint32_t)((hi ^ (l32 >> 3)) & 1) * 8u;        // + swizzled chunk
+            // The SiLU gate on a tile inside the output: the 16-byte pieces of G (and U) that match the pieces this
+            // lane stores, for the 32 rows i, are requested one block of rows ahead (those of block 0 here, those of
+            // block i + 1 while block i is turned round), so that only the first block waits for memory.
+            const uint32_t gate_bytes = (uint32_t)p.M * ldc_b;
+            const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(GATE ? p.gate_g : out_c), 0, (int)gate_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rs_u = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(GATE == 2 ? p.gate_u : out_c), 0, (int)gate_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rs_o1 = __builtin_amdgcn_make_buffer_rsrc(GATE ? p.gate_out1 : out_c, 0, (int)gate_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rs_o2 = __builtin_amdgcn_make_buffer_rsrc(GATE == 2 ? p.gate_out2 : out_c, 0, (int)gate_bytes, 0x00020000);
+            u32x4 gq[2][4], uq[2][4];
+            auto gate_requests = [&](int i, u32x4 (&g4)[4], u32x4 (&u4)[4]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint32_t soff = __builtin_amdgcn_readfirstlane(tile_off + (uint32_t)(i * 32 + 8 * q) * ldc_b);
+                    g4[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_g, lane_off, soff, 0);
+                    if (GATE == 2) u4[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_u, lane_off, soff, 0);
+                }
+            };
 #pragma unroll
             for (int i = 0; i < TM; i++) {
 #pragma unroll
@@ -394,7 +412,38 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 #ifdef FHPC_DIAG
                 if (p.dbg & 16) continue;                      // probe: no read-back, no stores
 #endif
-                if (inside) {
+                if (GATE != 0 && inside) gate_requests(i, gq[i & 1], uq[i & 1]);
+                if (inside && GATE != 0) {
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int row = rr + 8 * q;
+                        u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
+                        if (q & 1) v = u32x4{v.z, v.w, v.x, v.y};
+                        const uint32_t soff = __builtin_amdgcn_readfirstlane(tile_off + (uint32_t)(i * 32 + 8 * q) * ldc_b);
+                        // A 16-byte store reads its data registers for some cycles after it has issued, and the
+                        // arithmetic here would reuse them at once (measured: the first shift of the gate landed in
+                        // the stored word of the lanes read last).  Both results are formed first, the two stores go
+                        // out together, and four idle states follow them; nothing may be scheduled in between.
+                        u32x4 o1, o2;
+                        if (GATE == 1) {
+                            o1 = v;
+#pragma unroll
+                            for (int e = 0; e < 4; e++) o2[e] = gate::fwd_pair(gq[i & 1][q][e], v[e]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                uint32_t a, b;
+                                gate::bwd_pair(gq[i & 1][q][e], uq[i & 1][q][e], v[e], a, b);
+                                o1[e] = a; o2[e] = b;
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        __builtin_amdgcn_raw_buffer_store_b128(o1, GATE == 1 ? rs_c : rs_o1, lane_off, soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(o2, GATE == 1 ? rs_o1 : rs_o2, lane_off, soff, 0);
+                        asm volatile("s_nop 3" ::: "memory");
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else if (inside) {
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const int row = rr + 8 * q;
@@ -418,8 +467,36 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
                         u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * 128 + (((rc ^ row) & 7) << 4));
                         if (q & 1) v = u32x4{v.z, v.w, v.x, v.y};
                         const int m = out_m0 + wave_m0 + i * 32 + row;
-                        if (m < p.M && col < ecols)
-                            *reinterpret_cast<u32x4*>(eo + (size_t)m * eld + (size_t)col) = v;
+                        if (m < p.M && col < ecols) {
+                            const size_t at = (size_t)m * eld + (size_t)col;
+                            if (GATE == 0) {
+                                *reinterpret_cast<u32x4*>(eo + at) = v;
+                            } else {
+                                // (results first, then the stores and the idle states: see the tiles inside the output)
+                                const u32x4 gv = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.gate_g) + at);
+                                u32x4 o1, o2;
+                                if (GATE == 1) {
+                                    o1 = v;
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) o2[e] = gate::fwd_pair(gv[e], v[e]);
+                                } else {
+                                    const u32x4 uv = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.gate_u) + at);
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) {
+                                        uint32_t a, b;
+                                        gate::bwd_pair(gv[e], uv[e], v[e], a, b);
+                                        o1[e] = a; o2[e] = b;
+                                    }
+                                }
+                                uint16_t* const d1 = GATE == 1 ? eo : static_cast<uint16_t*>(p.gate_out1);
+                                uint16_t* const d2 = static_cast<uint16_t*>(GATE == 1 ? p.gate_out1 : p.gate_out2);
+                                __builtin_amdgcn_sched_barrier(0);
+                                *reinterpret_cast<u32x4*>(d1 + at) = o1;
+                                *reinterpret_cast<u32x4*>(d2 + at) = o2;
+                                asm volatile("s_nop 3" ::: "memory");
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
                     }
                 }
             }
@@ -475,10 +552,14 @@ int compute_units()
 
 namespace pp {
 
-template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT>
+template <int BM, int BN, int BK, bool KSPLIT, int NSTAGE, int AM, int BMODE, int OUT, int GATE = 0>
 static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 {
+    if (a.gate != GATE) return hipErrorInvalidValue;
     if (a.n_split > 0 && (OUT != OUT_BF16 || a.groups > 1 || a.n_split % BN != 0 || a.n_split >= a.N || (a.N - a.n_split) % 8 != 0 || !a.c2))
+        return hipErrorInvalidValue;
+    if (a.gate != 0 && (OUT != OUT_BF16 || KSPLIT || a.groups > 1 || a.n_split > 0 || a.gate < 0 || a.gate > 2 || !a.gate_g ||
+                        !a.gate_out1 || (a.gate == 2 && (!a.gate_u || !a.gate_out2)) || (a.N % 8) != 0 || (a.ldc % 8) != 0))
         return hipErrorInvalidValue;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const int total = tiles * (a.splits > 1 ? a.splits : 1) * (a.groups > 1 ? a.groups : 1);
@@ -487,10 +568,10 @@ static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
     int slot = -1;
     if (prof_on()) {
         char name[64];
-        snprintf(name, sizeof(name), "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT);
+        snprintf(name, sizeof(name), GATE ? "gemm_pp<%dx%dx%d,a%d,b%d,o%d,gate%d>" : "gemm_pp<%dx%dx%d,a%d,b%d,o%d>", BM, BN, BK, AM, BMODE, OUT, GATE);
         slot = prof_begin(name, 2.0 * a.M * a.N * (double)a.K * (a.groups > 1 ? a.groups : 1), 0.0, s);
     }
-    hipLaunchKernelGGL((gemm_pp_kernel<BM, BN, BK, KSPLIT, NSTAGE, AM, BMODE, OUT>), grid, dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((gemm_pp_kernel<BM, BN, BK, KSPLIT, NSTAGE, AM, BMODE, OUT, GATE>), grid, dim3(NT), 0, s, a);
     prof_end(slot, s);
     return hipGetLastError();
 }
@@ -498,6 +579,17 @@ static hipError_t launch_pp(const GemmArgs& a, hipStream_t s)
 template <int AM, int BMODE, int OUT>
 static hipError_t launch_pp_tile(int tile, const GemmArgs& a, hipStream_t s)
 {
+    if (a.gate != 0) {
+        // the gate epilogue exists where the FFN uses it: the up projection U = H B (forward) and the input
+        // gradient of the down projection dZ = dH A^T (backward), on the 256 x 256 tile
+        if constexpr (AM == OP_KC && BMODE == OP_XC && OUT == OUT_BF16) {
+            if (tile == TILE_256x256 && a.gate == 1) return launch_pp<256, 256, 32, false, 4, AM, BMODE, OUT, 1>(a, s);
+        }
+        if constexpr (AM == OP_KC && BMODE == OP_KC && OUT == OUT_BF16) {
+            if (tile == TILE_256x256 && a.gate == 2) return launch_pp<256, 256, 32, false, 4, AM, BMODE, OUT, 2>(a, s);
+        }
+        return hipErrorInvalidValue;
+    }
     if (tile == TILE_256x256) return launch_pp<256, 256, 32, false, 4, AM, BMODE, OUT>(a, s);
     if (tile == TILE_256x128) return launch_pp<256, 128, 64, true, 3, AM, BMODE, OUT>(a, s);
     return hipErrorInvalidValue;
@@ -513,6 +605,8 @@ FHPC_PP_INSTANTIATE(OP_XC, OP_XC, OUT_F32)
 FHPC_PP_INSTANTIATE(OP_KC, OP_XC, OUT_F32)      // H = X A, Y = H B with the reduction split (fp32 slabs)
 FHPC_PP_INSTANTIATE(OP_KC, OP_KC, OUT_F32)      // dH = dY B^T, dX = dH A^T likewise
 #undef FHPC_PP_INSTANTIATE
+template __global__ void gemm_pp_kernel<256, 256, 32, false, 4, OP_KC, OP_XC, OUT_BF16, 1>(GemmArgs);   // U = H B with Z = SiLU(G) U
+template __global__ void gemm_pp_kernel<256, 256, 32, false, 4, OP_KC, OP_KC, OUT_BF16, 2>(GemmArgs);   // dZ = dH A^T into dG, dU
 
 }  // namespace pp
 

@@ -1,6 +1,7 @@
 // fp32 GEMM (true fp32 arithmetic), SiLU gate, weight quantise / unpack / dequantise,
 // and the small copy / convert kernels the entry points use around the GEMM core.
 #include "kernels_misc.h"
+#include "gate_math.h"
 #include "profile.h"
 
 namespace fhpc {
@@ -187,7 +188,6 @@ hipError_t launch_lowrank_chain_f32(const float* L, int64_t ldl, const float* R,
 // ---------------------------------------------------------------------------------
 // SiLU gate (Sec. 3.1 eq. FFN): fp32 arithmetic on bf16 or fp32 storage.
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
 
 template <bool BF16>
 __device__ __forceinline__ float load_elem(const void* p, int64_t i)
@@ -228,17 +228,13 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const void* G, const vo
             const u32x4_t g = reinterpret_cast<const u32x4_t*>(G)[i], u = reinterpret_cast<const u32x4_t*>(U)[i];
             u32x4_t z;
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const float g0 = bf16_lo(g[e]), g1 = bf16_hi(g[e]);
-                z[e] = bf16_pack(bf16_lo(u[e]) * g0 * sigmoid_f(g0), bf16_hi(u[e]) * g1 * sigmoid_f(g1));
-            }
+            for (int e = 0; e < 4; e++) z[e] = gate::fwd_pair(g[e], u[e]);
             reinterpret_cast<u32x4_t*>(Z)[i] = z;
         }
         done = n8 * 8;
     }
     for (int64_t i = done + tid; i < n; i += stride) {
-        const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i);
-        store_elem<BF16>(Z, i, u * g * sigmoid_f(g));
+        store_elem<BF16>(Z, i, gate::fwd(load_elem<BF16>(G, i), load_elem<BF16>(U, i)));
     }
 }
 
@@ -257,12 +253,10 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* G, const vo
             u32x4_t og, ou;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                const float g0 = bf16_lo(g[e]), g1 = bf16_hi(g[e]);
-                const float s0 = sigmoid_f(g0), s1 = sigmoid_f(g1);
-                const float d0 = bf16_lo(dz[e]), d1 = bf16_hi(dz[e]);
-                ou[e] = bf16_pack(d0 * g0 * s0, d1 * g1 * s1);
-                og[e] = bf16_pack(d0 * bf16_lo(u[e]) * s0 * (1.f + g0 * (1.f - s0)),
-                                  d1 * bf16_hi(u[e]) * s1 * (1.f + g1 * (1.f - s1)));
+                uint32_t a, b;
+                gate::bwd_pair(g[e], u[e], dz[e], a, b);
+                og[e] = a;
+                ou[e] = b;
             }
             reinterpret_cast<u32x4_t*>(dU)[i] = ou;
             reinterpret_cast<u32x4_t*>(dG)[i] = og;
@@ -270,10 +264,10 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* G, const vo
         done = n8 * 8;
     }
     for (int64_t i = done + tid; i < n; i += stride) {
-        const float g = load_elem<BF16>(G, i), u = load_elem<BF16>(U, i), dz = load_elem<BF16>(dZ, i);
-        const float sg = sigmoid_f(g);
-        store_elem<BF16>(dU, i, dz * g * sg);
-        store_elem<BF16>(dG, i, dz * u * sg * (1.f + g * (1.f - sg)));
+        float dg, du;
+        gate::bwd(load_elem<BF16>(G, i), load_elem<BF16>(U, i), load_elem<BF16>(dZ, i), dg, du);
+        store_elem<BF16>(dU, i, du);
+        store_elem<BF16>(dG, i, dg);
     }
 }
 

@@ -2,8 +2,8 @@
 weight replaced by a factor pair, Sec. 3.2).  Pure sequencing of library calls."""
 from __future__ import annotations
 
-from . import (fhpc_add, lowrank_linear_bwd, lowrank_linear_bwd_shared_x, lowrank_linear_fwd,
-               lowrank_linear_fwd_shared_x, swiglu_bwd, swiglu_fwd)
+from . import (fhpc_add, lowrank_ffn_down_bwd, lowrank_ffn_gate_up_fwd, lowrank_linear_bwd,
+               lowrank_linear_bwd_shared_x, lowrank_linear_fwd, swiglu_bwd, swiglu_fwd)
 
 
 def ffn_fwd(X, Ag, Bg, Au, Bu, Ad, Bd):
@@ -28,18 +28,18 @@ def ffn_bwd(X, Ag, Bg, Au, Bu, Ad, Bd, dY, saved):
 
 def ffn_fwd_shared_x(X, A_gu, Bg, Bu, Ad, Bd):
     """The same FFN with the gate and up factors side by side in A_gu = [Ag | Au] (d x 2r): X is read
-    once for both projections.  Returns (Y, saved)."""
-    (G, U), H_gu = lowrank_linear_fwd_shared_x(X, A_gu, [Bg, Bu], save_H=True)
-    Z = swiglu_fwd(G, U)
+    once for both projections, and the gate is applied where U is produced (lowrank_ffn_gate_up_fwd).
+    Returns (Y, saved)."""
+    G, U, Z, H_gu = lowrank_ffn_gate_up_fwd(X, A_gu, Bg, Bu, save_H=True)
     Y, Hd = lowrank_linear_fwd(Z, Ad, Bd, save_H=True)
     return Y, (G, U, Z, H_gu, Hd)
 
 
 def ffn_bwd_shared_x(X, A_gu, Bg, Bu, Ad, Bd, dY, saved):
-    """Returns dX and (dA_gu, dBg, dBu, dAd, dBd), fp32; dX is one product over [dHg | dHu], so the two
+    """Returns dX and (dA_gu, dBg, dBu, dAd, dBd), fp32.  The down projection's input gradient goes through the
+    gate's backward where it is produced (lowrank_ffn_down_bwd); dX is one product over [dHg | dHu], so the two
     projections' input gradients are summed in the accumulators and rounded once."""
     G, U, Z, H_gu, Hd = saved
-    dZ, dAd, dBd = lowrank_linear_bwd(Z, Ad, Bd, dY, H_saved=Hd)
-    dG, dU = swiglu_bwd(G, U, dZ)
+    dG, dU, dAd, dBd = lowrank_ffn_down_bwd(Z, Ad, Bd, dY, G, U, H_saved=Hd)
     dX, dA_gu, (dBg, dBu) = lowrank_linear_bwd_shared_x(X, A_gu, [Bg, Bu], [dG, dU], H_all_saved=H_gu)
     return dX, (dA_gu, dBg, dBu, dAd, dBd)

@@ -127,6 +127,58 @@ def test_config3_chain_error_spread_over_seeds():
         assert (max(v) - min(v)) <= 0.05 * min(v), (k, v)
 
 
+@pytest.mark.parametrize("M,d,r,f", [(3900, 256, 64, 4040), (300, 256, 32, 520), (4096, 512, 128, 4096), (37, 128, 8, 264)])
+def test_gate_in_the_epilogue_gives_the_bits_of_the_separate_calls(M, d, r, f):
+    """lowrank_ffn_gate_up_fwd and lowrank_ffn_down_bwd against the calls they stand for (shared-X forward with
+    g = 2 + swiglu_fwd; lowrank_linear_bwd + swiglu_bwd): every output bit for bit, on shapes whose tiles pass the
+    gate in the GEMM epilogue (the first and third: 256 x 256 tiles, the first with ragged edges both ways) and on
+    shapes that take the streaming gate kernel inside the call; outputs between guard regions.  And against the
+    oracle directly."""
+    import torch
+    from harness import Guarded
+    fhpc = _fhpc()
+    X, dY, W = _ffn_inputs(M, d, r, f, base=40)
+    Ag, Bg, Au, Bu, Ad, Bd = [w.cuda() for w in W]
+    A_gu = torch.cat([Ag, Au], dim=1).contiguous()
+    Xc, dYc = X.cuda(), dY.cuda()
+    bf = torch.bfloat16
+    # forward
+    (G0, U0), H0 = fhpc.lowrank_linear_fwd_shared_x(Xc, A_gu, [Bg, Bu], save_H=True)
+    Z0 = fhpc.swiglu_fwd(G0, U0)
+    gd = Guarded()
+    G1, U1, Z1, H1 = gd.alloc((M, f), bf), gd.alloc((M, f), bf), gd.alloc((M, f), bf), gd.alloc((M, 2 * r), bf)
+    fhpc.lowrank_ffn_gate_up_fwd(Xc, A_gu, Bg, Bu, G=G1, U=U1, Z=Z1, H_all_out=H1)
+    gd.check("gate/up forward")
+    for name, a, b in (("G", G0, G1), ("U", U0, U1), ("Z", Z0, Z1), ("H", H0, H1)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), name
+    # backward of the down projection
+    Hd = fhpc.lowrank_linear_fwd(Z0, Ad, Bd, save_H=True)[1]
+    dZ0, dAd0, dBd0 = fhpc.lowrank_linear_bwd(Z0, Ad, Bd, dYc, H_saved=Hd)
+    dG0, dU0 = fhpc.swiglu_bwd(G0, U0, dZ0)
+    gd = Guarded()
+    dG1, dU1 = gd.alloc((M, f), bf), gd.alloc((M, f), bf)
+    dAd1, dBd1 = gd.alloc((f, r), torch.float32), gd.alloc((r, d), torch.float32)
+    fhpc.lowrank_ffn_down_bwd(Z0, Ad, Bd, dYc, G0, U0, H_saved=Hd, dG=dG1, dU=dU1, dA=dAd1, dB=dBd1)
+    gd.check("down backward")
+    assert torch.equal(dG0.view(torch.int16), dG1.view(torch.int16)), "dG"
+    assert torch.equal(dU0.view(torch.int16), dU1.view(torch.int16)), "dU"
+    assert torch.equal(dAd0, dAd1) and torch.equal(dBd0, dBd1)
+    # without the saved H (recomputed inside the call)
+    dG2, dU2, dAd2, dBd2 = fhpc.lowrank_ffn_down_bwd(Z0, Ad, Bd, dYc, G0, U0)
+    assert torch.equal(dG0.view(torch.int16), dG2.view(torch.int16)) and torch.equal(dBd0, dBd2)
+    # the oracle on the same inputs (chain in fp64; the gate's inputs as the forward produced them)
+    Wf = [w.f64 for w in W]
+    Gr, _ = oracle.lowrank_fwd(X.f64, Wf[0], Wf[1])
+    Ur, _ = oracle.lowrank_fwd(X.f64, Wf[2], Wf[3])
+    Zr = oracle.swiglu_fwd(Gr, Ur)
+    assert parity_err(from_device(Z1), Zr) <= TOL_BF16
+    Gd, Ud, Zd = from_device(G0), from_device(U0), from_device(Z0)
+    dZr, dAdr, dBdr = oracle.lowrank_bwd(Zd, Wf[4], Wf[5], dY.f64)
+    dGr, dUr = oracle.swiglu_bwd(Gd, Ud, dZr)
+    for name, got, ref in (("dG", dG1, dGr), ("dU", dU1, dUr), ("dAd", dAd1, dAdr), ("dBd", dBd1, dBdr)):
+        assert parity_err(from_device(got), ref) <= TOL_BF16, name
+
+
 def _oracle_ffn_full_size(X, dY, W, rows, J):
     """The oracle's chain on every token (G, U, Z, dZ, dG, dU in fp64), then: Y and dX on the token rows `rows`, and
     each weight gradient restricted to the rank indices J (column j of dA and row j of dB depend on the pair only
