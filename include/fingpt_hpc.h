@@ -359,10 +359,11 @@ int fhpc_probe_read_rows(const void* W, int64_t N, int64_t row_bytes, int workgr
  * The calls themselves refuse, with FHPC_ERR_WORKSPACE, a launch whose slabs would not fit; this hook lets
  * a test show on the CPU that planned <= reserved over a grid of shapes.
  * call: FHPC_OP_LOWRANK_FWD .. FHPC_OP_QLINEAR_BWD, FHPC_OP_DECOMPOSE, FHPC_PLAN_SHARED_FWD / _BWD (the
- * shared-X calls of the factorised layer, g layers).  outputs: bit 0 = dX wanted (forward calls: H_out given),
+ * shared-X calls of the factorised layer, g layers), FHPC_PLAN_FFN_GATE_UP / _DOWN_BWD (lowrank_ffn_gate_up_fwd,
+ * lowrank_ffn_down_bwd).  outputs: bit 0 = dX wanted (forward calls: H_out given),
  * bit 1 = dA, bit 2 = dB, bit 3 = H_saved given.  base_scale: 1 for the finetuning layer, alpha for the blend
  * layer.  dtype, qscheme, g are ignored where the call has no such argument.  Returns a status code. */
-enum { FHPC_PLAN_SHARED_FWD = 16, FHPC_PLAN_SHARED_BWD = 17 };
+enum { FHPC_PLAN_SHARED_FWD = 16, FHPC_PLAN_SHARED_BWD = 17, FHPC_PLAN_FFN_GATE_UP = 18, FHPC_PLAN_FFN_DOWN_BWD = 19 };
 int fhpc_plan_slab_bytes(int call, int64_t M, int64_t K, int64_t r, int64_t N, int dtype, int qscheme, int g,
                          int outputs, float base_scale, int64_t* planned, int64_t* reserved);
 

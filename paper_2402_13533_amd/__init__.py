@@ -19,7 +19,7 @@ FHPC_Q_INT8_PER_CHANNEL, FHPC_Q_INT4_BLOCK = 8, 4
 FHPC_W_BF16 = 16          # blend and merge entry points only: dense bf16 W[K,N] in place of Wq, scales None
 FHPC_W_MERGED = 17        # qlinear_lowrank_fwd/bwd only: Wq is the bf16 [K,N] weight lowrank_merge wrote for the same A, B, scaling
 FHPC_OP_LOWRANK_FWD, FHPC_OP_LOWRANK_BWD, FHPC_OP_QLINEAR_FWD, FHPC_OP_QLINEAR_BWD, FHPC_OP_MERGE, FHPC_OP_DECOMPOSE = 0, 1, 2, 3, 4, 5
-FHPC_PLAN_SHARED_FWD, FHPC_PLAN_SHARED_BWD = 16, 17
+FHPC_PLAN_SHARED_FWD, FHPC_PLAN_SHARED_BWD, FHPC_PLAN_FFN_GATE_UP, FHPC_PLAN_FFN_DOWN_BWD = 16, 17, 18, 19
 
 EXPORTS = [
     "lowrank_linear_fwd", "lowrank_linear_bwd", "qlinear_lowrank_fwd", "qlinear_lowrank_bwd", "qlinear_blend_fwd", "qlinear_blend_bwd", "lowrank_merge", "lowrank_decompose", "qlinear_lowrank_fwd_shared_x", "fhpc_workspace_bytes_shared_x",

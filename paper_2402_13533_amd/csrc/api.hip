@@ -1914,6 +1914,18 @@ int fhpc_plan_slab_bytes(int call, int64_t M, int64_t K, int64_t r, int64_t N, i
         for (int i = 0; i < g; i++) { in[i] = fake; out[i] = fake; dB[i] = o2; }
         rc = bwd ? seq_shared_bwd(run, s, fake, fake, in, in, hs, o0, o1, dB, o2 != nullptr, M, K, r, N, g)
                  : seq_shared_fwd(run, s, fake, fake, in, out, o0, M, K, r, N, g);
+    } else if (call == FHPC_PLAN_FFN_GATE_UP) {
+        rc = check_shared(M, K, r, N, 2);
+        if (rc) return rc;
+        const SharedScratch s = carve_shared(c, false, M, K, r, N, 2);
+        *reserved = s.part_bytes;
+        rc = seq_ffn_gate_up_fwd(run, s, fake, fake, fake, fake, fake, fake, fake, o0, M, K, r, N);
+    } else if (call == FHPC_PLAN_FFN_DOWN_BWD) {
+        rc = check_common(M, K, r, N);
+        if (rc) return rc;
+        const Scratch s = carve(c, FHPC_OP_LOWRANK_BWD, M, K, r, N, FHPC_BF16);
+        *reserved = s.part_bytes;
+        rc = seq_ffn_down_bwd(run, s, fake, fake, fake, fake, hs, fake, fake, fake, fake, o1, o2, M, K, r, N);
     }
     *planned = run.part_need;
     return rc;

@@ -134,6 +134,24 @@ def test_validation_precedes_launch():
     assert fhpc.workspace_bytes(fhpc.FHPC_OP_MERGE, 1, 64, 5, 64) == 16384 + 64 * 8 * 2          # the header, then a padded A
 
 
+def test_ffn_gate_calls_validate_before_launch():
+    lib = fhpc.load_library()
+    p, odd, nul = C.c_void_p(0x10000), C.c_void_p(0x10004), C.c_void_p(0)
+    ws, big = C.c_void_p(0x20000), C.c_size_t(1 << 40)
+    f = lib.lowrank_ffn_gate_up_fwd
+    assert f(p, p, p, p, p, p, nul, nul, 16, 64, 8, 64, ws, big, nul) == 1          # NULL Z_out
+    assert f(p, p, p, p, p, p, p, nul, 16, 60, 8, 64, ws, big, nul) == 2            # K % 8
+    assert f(p, p, p, p, p, p, p, nul, 16, 64, 4, 64, ws, big, nul) == 6            # r % 8: column blocks of A_all
+    assert f(p, p, p, p, p, odd, p, nul, 16, 64, 8, 64, ws, big, nul) == 4          # alignment
+    assert f(p, p, p, p, p, p, p, nul, 16, 64, 8, 64, ws, C.c_size_t(16), nul) == 5  # workspace
+    b = lib.lowrank_ffn_down_bwd
+    assert b(p, p, p, p, nul, nul, p, p, p, nul, nul, 16, 64, 8, 64, ws, big, nul) == 1   # NULL G
+    assert b(p, p, p, p, nul, p, p, p, nul, nul, nul, 16, 64, 8, 64, ws, big, nul) == 1   # NULL dU_out
+    assert b(p, p, p, p, nul, p, p, p, p, nul, nul, 0, 64, 8, 64, ws, big, nul) == 2      # M < 1
+    assert b(p, p, p, p, nul, p, odd, p, p, nul, nul, 16, 64, 8, 64, ws, big, nul) == 4   # alignment
+    assert b(p, p, p, p, nul, p, p, p, p, nul, nul, 16, 64, 8, 64, nul, C.c_size_t(0), nul) == 5
+
+
 def test_read_rows_probe_validates_before_launch():
     lib = fhpc.load_library()
     p, odd, nul = C.c_void_p(0x10000), C.c_void_p(0x10004), C.c_void_p(0)

@@ -50,6 +50,21 @@ def test_shared_x_slabs_fit():
         assert rc == 0 and 0 < planned <= reserved, (M, K, r, N, planned, reserved)
 
 
+def test_ffn_gate_calls_slabs_fit():
+    """lowrank_ffn_gate_up_fwd and lowrank_ffn_down_bwd: the gate in the epilogue of the large tiles, the streaming
+    gate kernel elsewhere, the same workspace layouts as the calls they stand for."""
+    n = 0
+    for M, K, N, r in itertools.product(Ms, KNs, KNs, [8, 16, 32, 40, 64, 128, 512, 1024]):
+        if (M + K + N + r) % 3:
+            continue
+        for outputs in (0, 1):
+            _assert_fits(fhpc.FHPC_PLAN_FFN_GATE_UP, "ffn_gate_up", M=M, K=K, r=r, N=N, outputs=outputs)
+        for outputs in (6, 6 | 8, 2, 4 | 8, 0):
+            _assert_fits(fhpc.FHPC_PLAN_FFN_DOWN_BWD, "ffn_down_bwd", M=M, K=K, r=r, N=N, outputs=outputs)
+        n += 1
+    assert n > 2000
+
+
 @pytest.mark.parametrize("qscheme", [fhpc.FHPC_Q_INT4_BLOCK, fhpc.FHPC_Q_INT8_PER_CHANNEL, fhpc.FHPC_W_BF16, fhpc.FHPC_W_MERGED])
 def test_quantised_layer_slabs_fit(qscheme):
     for M, K, N, r in itertools.product(Ms, [64, 256, 1024, 4096, 5120, 13824], [64, 264, 1024, 4096, 5120, 13824],
