@@ -3,7 +3,7 @@ weight replaced by a factor pair, Sec. 3.2).  Pure sequencing of library calls."
 from __future__ import annotations
 
 from . import (fhpc_add, lowrank_ffn_down_bwd, lowrank_ffn_gate_up_fwd, lowrank_linear_bwd,
-               lowrank_linear_bwd_shared_x, lowrank_linear_fwd, swiglu_bwd, swiglu_fwd)
+               lowrank_linear_bwd_shared_x, lowrank_linear_fwd, swiglu_fwd)
 
 
 def ffn_fwd(X, Ag, Bg, Au, Bu, Ad, Bd):
@@ -18,8 +18,7 @@ def ffn_fwd(X, Ag, Bg, Au, Bu, Ad, Bd):
 def ffn_bwd(X, Ag, Bg, Au, Bu, Ad, Bd, dY, saved):
     """Returns dX and the six weight gradients (fp32)."""
     G, U, Z, Hg, Hu, Hd = saved
-    dZ, dAd, dBd = lowrank_linear_bwd(Z, Ad, Bd, dY, H_saved=Hd)
-    dG, dU = swiglu_bwd(G, U, dZ)
+    dG, dU, dAd, dBd = lowrank_ffn_down_bwd(Z, Ad, Bd, dY, G, U, H_saved=Hd)
     dXg, dAg, dBg = lowrank_linear_bwd(X, Ag, Bg, dG, H_saved=Hg)
     dXu, dAu, dBu = lowrank_linear_bwd(X, Au, Bu, dU, H_saved=Hu)
     dX = fhpc_add(dXg, dXu, out=dXg)
