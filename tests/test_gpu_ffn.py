@@ -127,12 +127,13 @@ def test_config3_chain_error_spread_over_seeds():
         assert (max(v) - min(v)) <= 0.05 * min(v), (k, v)
 
 
-@pytest.mark.parametrize("M,d,r,f", [(3900, 256, 64, 4040), (300, 256, 32, 520), (4096, 512, 128, 4096), (37, 128, 8, 264)])
+@pytest.mark.parametrize("M,d,r,f", [(3900, 256, 64, 4040), (300, 256, 32, 520), (4096, 512, 128, 4096), (37, 128, 8, 264),
+                                     (4096, 256, 24, 4096), (4000, 128, 8, 4352)])
 def test_gate_in_the_epilogue_gives_the_bits_of_the_separate_calls(M, d, r, f):
     """lowrank_ffn_gate_up_fwd and lowrank_ffn_down_bwd against the calls they stand for (shared-X forward with
     g = 2 + swiglu_fwd; lowrank_linear_bwd + swiglu_bwd): every output bit for bit, on shapes whose tiles pass the
-    gate in the GEMM epilogue (the first and third: 256 x 256 tiles, the first with ragged edges both ways) and on
-    shapes that take the streaming gate kernel inside the call; outputs between guard regions.  And against the
+    gate in the GEMM epilogue (256 x 256 tiles; the first with ragged edges both ways, the last two with ranks that are
+    padded to the matrix instruction's depth) and on shapes that take the streaming gate kernel inside the call; outputs between guard regions.  And against the
     oracle directly."""
     import torch
     from harness import Guarded
@@ -163,19 +164,27 @@ def test_gate_in_the_epilogue_gives_the_bits_of_the_separate_calls(M, d, r, f):
     assert torch.equal(dG0.view(torch.int16), dG1.view(torch.int16)), "dG"
     assert torch.equal(dU0.view(torch.int16), dU1.view(torch.int16)), "dU"
     assert torch.equal(dAd0, dAd1) and torch.equal(dBd0, dBd1)
-    # without the saved H (recomputed inside the call)
+    # without the saved H (recomputed inside the call), and with the weight gradients left out
     dG2, dU2, dAd2, dBd2 = fhpc.lowrank_ffn_down_bwd(Z0, Ad, Bd, dYc, G0, U0)
     assert torch.equal(dG0.view(torch.int16), dG2.view(torch.int16)) and torch.equal(dBd0, dBd2)
-    # the oracle on the same inputs (chain in fp64; the gate's inputs as the forward produced them)
+    dG3, dU3, dAd3, dBd3 = fhpc.lowrank_ffn_down_bwd(Z0, Ad, Bd, dYc, G0, U0, need_dA=False, need_dB=False)
+    assert dAd3 is None and dBd3 is None
+    assert torch.equal(dG0.view(torch.int16), dG3.view(torch.int16)) and torch.equal(dU0.view(torch.int16), dU3.view(torch.int16))
+    # the oracle: the gate on the very tensors it was applied to (G, U and the bf16 dZ of the separate call, decoded
+    # exactly), so that one bf16 rounding of an fp32 result is all that separates the two: 2^-9 relative per element;
+    # the products around it against the fp64 chain
     Wf = [w.f64 for w in W]
+    Gd, Ud, Zd, dZd = from_device(G0), from_device(U0), from_device(Z0), from_device(dZ0)
+    dGr, dUr = oracle.swiglu_bwd(Gd, Ud, dZd)
+    for name, got, ref in (("Z", Z1, oracle.swiglu_fwd(Gd, Ud)), ("dG", dG1, dGr), ("dU", dU1, dUr)):
+        g = from_device(got)
+        assert np.all(np.isfinite(g)), name
+        assert np.all(np.abs(g - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30), name
     Gr, _ = oracle.lowrank_fwd(X.f64, Wf[0], Wf[1])
     Ur, _ = oracle.lowrank_fwd(X.f64, Wf[2], Wf[3])
-    Zr = oracle.swiglu_fwd(Gr, Ur)
-    assert parity_err(from_device(Z1), Zr) <= TOL_BF16
-    Gd, Ud, Zd = from_device(G0), from_device(U0), from_device(Z0)
-    dZr, dAdr, dBdr = oracle.lowrank_bwd(Zd, Wf[4], Wf[5], dY.f64)
-    dGr, dUr = oracle.swiglu_bwd(Gd, Ud, dZr)
-    for name, got, ref in (("dG", dG1, dGr), ("dU", dU1, dUr), ("dAd", dAd1, dAdr), ("dBd", dBd1, dBdr)):
+    assert parity_err(from_device(G1), Gr) <= TOL_BF16 and parity_err(from_device(U1), Ur) <= TOL_BF16
+    _, dAdr, dBdr = oracle.lowrank_bwd(Zd, Wf[4], Wf[5], dY.f64)
+    for name, got, ref in (("dAd", dAd1, dAdr), ("dBd", dBd1, dBdr)):
         assert parity_err(from_device(got), ref) <= TOL_BF16, name
 
 
