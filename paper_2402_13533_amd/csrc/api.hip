@@ -116,11 +116,13 @@ struct SplitPlan {
     int tile, splits, k_chunk;
 };
 
-SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
+// `g` > 1: that many products of this shape share the launch (a grouped launch): their tiles fill the chip together,
+// and every slice adds a slab per product.
+SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred, int g = 1)
 {
     SplitPlan sp;
     sp.tile = tile;
-    const int64_t tiles = tile_count(sp.tile, M, N);
+    const int64_t tiles = tile_count(sp.tile, M, N) * g;
     const int64_t ksteps = (Kred + 63) / 64;
     // the eight-wave tiles occupy a compute unit alone; 128x128 runs two at a time.  The skinny tiles could
     // too, but their products are bound by streaming the long operand, and one workgroup per compute
@@ -140,7 +142,7 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
         // Units: 64-deep steps of a 256 x 256 tile (about 1.5 microseconds each).
         const double tile_steps = (sp.tile == TILE_256x256) ? 1.0 : 0.5;
         const double fixed_steps = 5.0;                                     // per round
-        const double slab_steps = (double)M * (double)N * 8.0 / 4.0e12 / 1.5e-6;   // one slab written and read at 4 TB/s
+        const double slab_steps = (double)g * (double)M * (double)N * 8.0 / 4.0e12 / 1.5e-6;   // one slab (per product) written and read at 4 TB/s
         double best = -1.0;
         for (int64_t c = 1; c <= 64 && c <= ksteps / 8; c++) {
             const int64_t rounds = (tiles * c + target - 1) / target;
@@ -159,7 +161,7 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred)
 }
 
 // `rows32`: 32-row tiles whatever M is (the only fp32-output shape of the products X A, H B, dY B^T, dH A^T)
-SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred, bool rows32 = false)
+SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred, bool rows32 = false, int g = 1)
 {
     int tile;
     if (N <= 32) tile = TILE_256x32;
@@ -168,12 +170,12 @@ SplitPlan plan_split(int64_t M, int64_t N, int64_t Kred, bool rows32 = false)
     else if (M > 128) tile = TILE_256x128;
     else if (N > 128) tile = TILE_128x256;
     else tile = TILE_128x128;
-    SplitPlan sp = plan_split_on(tile, M, N, Kred);
+    SplitPlan sp = plan_split_on(tile, M, N, Kred, g);
     if (tile == TILE_256x256 && sp.splits >= 8) {
         // Many slices mean many partial-sum slabs to write and re-read.  The 256x128 shape needs
         // half as many; measured, it wins from eight slices on (config 2: 4096x512 outputs over
         // 16384 tokens) and loses below (config 3: the 256x256 kernel is 25 % faster there).
-        const SplitPlan alt = plan_split_on(TILE_256x128, M, N, Kred);
+        const SplitPlan alt = plan_split_on(TILE_256x128, M, N, Kred, g);
         if (alt.splits < sp.splits) sp = alt;
     }
     return sp;
@@ -1075,7 +1077,7 @@ static bool groupable_f32(int64_t M, int64_t N, int64_t Kred, int g)
 static hipError_t grouped_split_f32(const GemmOperand* a, const GemmOperand* b, float* const* C, int64_t M, int64_t N,
                                     int64_t Kred, float* part, int g, Run& run)
 {
-    const SplitPlan sp = plan_split(M, N, Kred);
+    const SplitPlan sp = plan_split(M, N, Kred, false, g);
     const int64_t slab_area = sp.splits > 1 ? (int64_t)sp.splits * M * N : 0;      // floats per product
     if (!run.claim((int64_t)g * slab_area * 4)) return hipErrorOutOfMemory;
     if (run.dry) return hipSuccess;
