@@ -133,12 +133,14 @@ SplitPlan plan_split_on(int tile, int64_t M, int64_t N, int64_t Kred, int g = 1)
     if (s > ksteps) s = ksteps;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
-    if ((sp.tile == TILE_256x256 || sp.tile == TILE_256x128) && tiles < target && ksteps >= 16) {
+    if ((sp.tile == TILE_256x256 || sp.tile == TILE_256x128) && (tiles < target || (g > 1 && tiles % target != 0)) && ksteps >= 16) {
         // The eight-wave tiles run one workgroup per compute unit, so what a launch takes is the number of
         // rounds its tiles x slices need times the depth of a slice, plus a fixed part per round (ring fill,
         // fp32 epilogue) and the slabs it writes and the slab sum reads.  The rule above can leave a second
         // round nearly empty (96 tiles in 3 slices: 288 items, 235 microseconds for 4096 x 1536 over 16384
         // tokens; in 5 slices two full rounds of shorter slices); take the cheapest count instead.
+        // (A grouped launch with more tiles than units is searched too: 344 tiles leave two thirds of the second
+        // round empty, in two slices they are 2.7 rounds of half the depth.)
         // Units: 64-deep steps of a 256 x 256 tile (about 1.5 microseconds each).
         const double tile_steps = (sp.tile == TILE_256x256) ? 1.0 : 0.5;
         const double fixed_steps = 5.0;                                     // per round
@@ -1001,7 +1003,12 @@ static SharedScratch carve_shared(Carver& c, bool bwd, int64_t M, int64_t K, int
         else if (g == 1) upto(product_part_bytes(M, r, N));
         upto(split_bytes(K, R, R, M));                 // dA_all = X^T dH_all
         // dB_i = H_i^T dY_i: one product's slabs, or all g products' when they go out in one launch
-        upto((groupable_f32(r, N, M, g) ? g : 1) * split_bytes(r, N, N, M));
+        if (groupable_f32(r, N, M, g)) {
+            const SplitPlan gp = plan_split(r, N, M, false, g);
+            upto(gp.splits > 1 ? (int64_t)g * gp.splits * r * N * 4 : 0);
+        } else {
+            upto(split_bytes(r, N, N, M));
+        }
     }
     s.part = static_cast<float*>(c.take(part));
     s.part_bytes = part;
