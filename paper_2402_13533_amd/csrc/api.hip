@@ -99,6 +99,29 @@ int64_t rank_pad(int64_t r) { return round_up(r, 8); }
 // from the big product as well (W' x = W x + s B A x, Sec. 5.1).  288 GB of HBM make room for it.
 // The forward and the backward call each merge for themselves; measured on 4096 x 4096 int8 and on a
 // 13B decoder layer in int4, a whole step is faster this way from about 1152 tokens on.
+// More than 16 tokens on one weight through the weight-streaming forward: the token rows in blocks of 16, every block a
+// job of its own on the same weight (the 16-token kernel holds three workgroups per compute unit and its finishers
+// gather a quarter of the slab rows each).  The plan of that launch.
+static int token_blocks(int64_t M) { return (int)((M + 15) / 16); }
+static QskinnyPlan qskinny_plan_token_blocks(int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    int64_t Ns[QSKINNY_MAX_JOBS];
+    const int tb = token_blocks(M);
+    for (int t = 0; t < tb; t++) Ns[t] = N;
+    return qskinny_plan(16, K, r, Ns, tb, num_cu());
+}
+// It pays while every (token block, 64-channel block) pair can still have three slices of the reduction in the one
+// round of resident workgroups (measured at 64 tokens, forward, per call: 4096 x 4096 int8 29 -> 24 microseconds, at 32
+// tokens 20 -> 18; 5120 x 5120 int4 the same either way; with more channel blocks than that the slices get so
+// long that the blocks lose: 5120 x 13824 int4 59 -> 90 microseconds).
+static bool token_blocks_pay(int64_t M, int64_t K, int64_t r, int64_t N)
+{
+    (void)K; (void)r;
+    if (M <= 16 || token_blocks(M) > QSKINNY_MAX_JOBS) return false;
+    const int64_t blocks = (N + 63) / 64 * token_blocks(M);
+    return 3 * blocks <= 3 * (int64_t)num_cu();
+}
+
 bool many_tokens(int op, int64_t M, int64_t K, int64_t N);
 
 
@@ -339,7 +362,12 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     }
     if (op == FHPC_OP_QLINEAR_FWD && quantised && qskinny_supports(M, K, r, N, FHPC_Q_INT4_BLOCK)) {
         // a handful of tokens: the weight-streaming kernels need only their own slabs
-        const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
+        QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
+        if (M > 16) {                                  // (the same tokens in blocks of 16: whichever plan needs more)
+            const QskinnyPlan pb = qskinny_plan_token_blocks(M, K, r, N);
+            if (pb.part_bytes > p.part_bytes) p.part_bytes = pb.part_bytes;
+            if (pb.hpart_bytes > p.hpart_bytes) p.hpart_bytes = pb.hpart_bytes;
+        }
         s.sk_part = static_cast<float*>(c.take(p.part_bytes));
         s.sk_hpart = static_cast<float*>(c.take(p.hpart_bytes));
         return s;
@@ -1313,6 +1341,18 @@ static int seq_qlinear_fwd(Run& run, const Scratch& s, const void* X, const void
 {
     const bool premerged = (qscheme == FHPC_W_MERGED);
     const bool dense = (qscheme == FHPC_W_BF16) || premerged;
+    if (s.sk_part && token_blocks_pay(M, K, r, N)) {
+        const QskinnyPlan p = qskinny_plan_token_blocks(M, K, r, N);
+        const int tb = token_blocks(M);
+        QskinnyJob jobs[QSKINNY_MAX_JOBS];
+        for (int t = 0; t < tb; t++) {
+            jobs[t] = QskinnyJob{Wq, scales, A, B, static_cast<uint16_t*>(Y) + (int64_t)16 * t * N,
+                                 H_out ? static_cast<uint16_t*>(H_out) + (int64_t)16 * t * r : nullptr, N, base_scale, scaling,
+                                 static_cast<const uint16_t*>(X) + (int64_t)16 * t * K, (M - 16 * t < 16) ? M - 16 * t : 16};
+        }
+        FHPC_LAUNCH(run, launch_qskinny_fwd(X, jobs, tb, qscheme, 16, K, r, p, s.sk_part, s.sk_hpart, s.header, run.st));
+        return FHPC_OK;
+    }
     if (s.sk_part) {
         const QskinnyPlan p = qskinny_plan(M, K, r, &N, 1, num_cu());
         const QskinnyJob job = {Wq, scales, A, B, Y, H_out, N, base_scale, scaling};

@@ -27,6 +27,10 @@ struct QskinnyJob {
     void* H_out;
     int64_t N;
     float base_scale, scaling;
+    // A job may have token rows of its own (a block of the rows of a larger X goes through the launch as a job of the
+    // same weight): X_own [M_own][K], M_own <= the launch's M.  NULL: the launch's X and M.
+    const void* X_own = nullptr;
+    int64_t M_own = 0;
 };
 
 // M <= 64 tokens, r <= 64, K a multiple of 256, scheme 4 (block 64) or 8.

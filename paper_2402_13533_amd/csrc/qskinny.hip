@@ -71,6 +71,8 @@ struct SkinnyJobs {
     const void* B[QSKINNY_MAX_JOBS];
     void* Y[QSKINNY_MAX_JOBS];
     void* H_out[QSKINNY_MAX_JOBS];
+    const void* X[QSKINNY_MAX_JOBS];        // token rows of the job and how many (at most the launch's M, which stays
+    int M[QSKINNY_MAX_JOBS];                // the row count of every job's scratch areas)
     int N[QSKINNY_MAX_JOBS];
     int rb0[QSKINNY_MAX_JOBS + 1];
     float base_scale[QSKINNY_MAX_JOBS];
@@ -252,7 +254,7 @@ __device__ __forceinline__ uint32_t arrive(uint32_t* counter, uint32_t* s_ticket
 // registers, so that this tail does not lower the occupancy the streaming loop was planned for.
 __device__ __forceinline__ void finish_block(unsigned char* smem, int rb, const SkinnyJobs& jb, const float* __restrict__ part,
                                              int splits, const float* __restrict__ hsum_all, const uint32_t* hready, int poll_limit,
-                                             const uint16_t* __restrict__ X, int K, int M, int r)
+                                             const uint16_t* __restrict__ X, int K, int M, int Mstride, int r)
 {
     float* Hs = reinterpret_cast<float*>(smem);                 // [M][r], at most 64 x 64 floats
     const int job = job_of_block(jb, rb);
@@ -260,7 +262,7 @@ __device__ __forceinline__ void finish_block(unsigned char* smem, int rb, const 
     const uint16_t* const B = static_cast<const uint16_t*>(pick(jb.B, job));
     uint16_t* const Y = static_cast<uint16_t*>(pick(jb.Y, job));
     const float base_scale = pick(jb.base_scale, job), scaling = pick(jb.scaling, job);
-    const float* const hsum = hsum_all + (int64_t)job * M * r;
+    const float* const hsum = hsum_all + (int64_t)job * Mstride * r;
     const int ld_part = jb.rb0[jb.count] * ROWS_WG;
     const int c = threadIdx.x & 63, tg = threadIdx.x >> 6;
     const int ncomb = rb * ROWS_WG + c;
@@ -411,7 +413,9 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         }
     };
     auto finish = [&](int rb) __attribute__((always_inline)) {
-        finish_block(smem, rb, jb, part, splits, hsum, tickets + HREADY, poll_limit, static_cast<const uint16_t*>(X), K, M, r);
+        const int fj = job_of_block(jb, rb);
+        finish_block(smem, rb, jb, part, splits, hsum, tickets + HREADY, poll_limit, static_cast<const uint16_t*>(pick(jb.X, fj)), K,
+                     pick(jb.M, fj), M, r);
         if (threadIdx.x == 0) {
             __hip_atomic_store(tickets + rb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             done();
@@ -422,21 +426,22 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
         // the H = X A chunks: kchunks workgroups per weight, at the head of the grid so that they start first
         const int idx = (int)blockIdx.x, hj = idx / kchunks, kc = idx - hj * kchunks;
         float* const hp = hpart + (int64_t)hj * kchunks * M * r;
-        hpart_body<TOKS>(smem, kc, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(pick(jb.A, hj)), hp, M, K, r);
+        const int Mj = pick(jb.M, hj);                              // the job's own token count (scratch strides: M)
+        hpart_body<TOKS>(smem, kc, static_cast<const uint16_t*>(pick(jb.X, hj)), static_cast<const uint16_t*>(pick(jb.A, hj)), hp, Mj, K, r);
         QTS(1);
         if (arrive(tickets + HCOUNT + hj, &s_ticket) != (uint32_t)(kchunks - 1)) return;
         QTS(2);
         // the last chunk of this weight: H = the sum of the chunks, in chunk order (the same order every run)
         uint16_t* const H_out = static_cast<uint16_t*>(pick(jb.H_out, hj));
         float* const hs = hsum + (int64_t)hj * M * r;
-        for (int i = threadIdx.x; i < M * r; i += NT) {
+        for (int i = threadIdx.x; i < Mj * r; i += NT) {
             float t = 0.f;
             for (int c0 = 0; c0 < kchunks; c0 += 48) {         // 48 loads in flight, added in chunk order
                 float v[48];
 #pragma unroll
                 for (int q = 0; q < 48; q++) {
                     const int c = c0 + q;
-                    const float x = shared_load(hp + (int64_t)(c < kchunks ? c : c0) * M * r + i);
+                    const float x = shared_load(hp + (int64_t)(c < kchunks ? c : c0) * Mj * r + i);
                     v[q] = (c < kchunks) ? x : 0.f;
                 }
 #pragma unroll
@@ -467,6 +472,8 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
     const int rb = wg % row_blocks, split = wg / row_blocks;
     const int job = job_of_block(jb, rb);
     const int N = pick(jb.N, job);
+    const int Mj = pick(jb.M, job);                                // this job's token rows
+    const void* const Xj = pick(jb.X, job);
     const void* const Wq = pick(jb.Wq, job);
     const void* const scales = pick(jb.scales, job);
     const int n0 = (rb - pick_rb0(jb, job)) * ROWS_WG + wave * 16;      // channel within its weight
@@ -479,7 +486,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 
     const int64_t row_bytes = I4 ? K / 2 : K;
     const __amdgpu_buffer_rsrc_t rw = rsrc(Wq, (int64_t)N * row_bytes);
-    const __amdgpu_buffer_rsrc_t rx = rsrc(X, (int64_t)M * K * 2);
+    const __amdgpu_buffer_rsrc_t rx = rsrc(Xj, (int64_t)Mj * K * 2);
     const __amdgpu_buffer_rsrc_t rsc = rsrc(scales, I4 ? (int64_t)N * (K / 64) * 2 : (int64_t)N * 2);
     const bool row_ok = (n0 + lr) < N;
     const uint32_t wrow = row_ok ? (uint32_t)((int64_t)(n0 + lr) * row_bytes) : OOB;
@@ -521,7 +528,7 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 #pragma unroll
     for (int j = 0; j < XL; j++) {
         const int c = tid + NT * j, tok = c / XCH, chunk = c % XCH;
-        xlane[j] = (tok < M) ? (uint32_t)(((int64_t)tok * K + chunk * 8) * 2) : OOB;
+        xlane[j] = (tok < Mj) ? (uint32_t)(((int64_t)tok * K + chunk * 8) * 2) : OOB;
     }
     auto load_x = [&](u32x4 (&x)[XL], int k0) __attribute__((always_inline)) {
 #pragma unroll
@@ -670,13 +677,13 @@ __global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict_
 #pragma unroll
         for (int tt = 0; tt < TT; tt++) {
             const int m = TOK * tt + lr;
-            if (m >= M) continue;
+            if (m >= Mj) continue;
             f32x4 o = acc[tt];
             if constexpr (!I4) {
 #pragma unroll
                 for (int v = 0; v < 4; v++) o[v] = ch_scale[v] * (acc[tt][v] - 128.f * ones_acc[tt][v]);
             }
-            float* const dst = part + ((int64_t)split * M + m) * ld_part + ncomb0 + 4 * g;
+            float* const dst = part + ((int64_t)split * Mj + m) * ld_part + ncomb0 + 4 * g;
 #pragma unroll
             for (int v = 0; v < 4; v++) shared_store(dst + v, o[v]);
         }
@@ -748,6 +755,9 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
         const QskinnyJob& q = jobs[j < count ? j : 0];          // unused slots repeat the first weight
         jb.Wq[j] = q.Wq; jb.scales[j] = q.scales; jb.A[j] = q.A; jb.B[j] = q.B; jb.Y[j] = q.Y; jb.H_out[j] = q.H_out;
         jb.N[j] = (int)q.N; jb.base_scale[j] = q.base_scale; jb.scaling[j] = q.scaling;
+        jb.X[j] = q.X_own ? q.X_own : X;
+        jb.M[j] = q.X_own ? (int)q.M_own : (int)M;
+        if (jb.M[j] < 1 || jb.M[j] > (int)M) return hipErrorInvalidValue;
         jb.rb0[j] = rb;
         if (j < count) {
             rb += (int)((q.N + ROWS_WG - 1) / ROWS_WG);

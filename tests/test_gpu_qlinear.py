@@ -286,10 +286,14 @@ def test_config5_full_size():
     (5, 768, 16, 200),         # K a multiple of 256 only: the 256-deep step
     (20, 1280, 8, 136),
     (64, 2816, 16, 72),
+    (40, 512, 16, 5632),       # more than 16 tokens and too many channel blocks for the route in token blocks:
+    (64, 256, 8, 4160),        # the kernels that take two and four token tiles per pass over the weight
 ])
 def test_few_token_forward(scheme, M, K, r, N):
     """M <= 64 tokens and K a multiple of 256 take the weight-streaming forward (codes turned
-    into exact small bf16 integers, offset and scale applied to the fp32 sums)."""
+    into exact small bf16 integers, offset and scale applied to the fp32 sums).  More than 16 tokens on a weight
+    of at most 256 / ceil(M / 16) channel blocks go through the launch in blocks of 16 tokens, each block a job of its
+    own on the same weight (the narrow shapes above with M > 16); wider weights take several token tiles per pass."""
     fhpc = _fhpc()
     W, X, A, B, _ = qlinear_inputs(8, M, K, r, N, 60)
     Wq, sc = _quantize_host(W, scheme)
