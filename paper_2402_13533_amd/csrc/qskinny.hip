@@ -382,7 +382,7 @@ constexpr int HCOUNT = TICKETS, HREADY = TICKETS + QSKINNY_MAX_JOBS, DONE = TICK
 static_assert((DONE + 1) * 4 <= QSKINNY_HEADER_BYTES, "header words");
 
 template <int SCHEME, int TT, int SD>
-__global__ __launch_bounds__(NT) void qskinny_fwd_kernel(const void* __restrict__ X, SkinnyJobs jb, float* __restrict__ part,
+__global__ __launch_bounds__(NT) void qskinny_fwd_kernel(SkinnyJobs jb, float* __restrict__ part,
                                                          int M, int K, int k_chunk, float* __restrict__ hpart, int r,
                                                          int kchunks, int head_grid, int splits, uint32_t* __restrict__ tickets,
                                                          float* __restrict__ hsum, int poll_limit)
@@ -761,7 +761,9 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
         jb.rb0[j] = rb;
         if (j < count) {
             rb += (int)((q.N + ROWS_WG - 1) / ROWS_WG);
-            wbytes += (scheme == 4) ? (double)q.N * K / 2 + (double)q.N * (K / 64) * 2 : (double)q.N * K + (double)q.N * 2;
+            bool seen = false;                                  // (token blocks of one weight: its bytes count once)
+            for (int i = 0; i < j; i++) seen = seen || jobs[i].Wq == q.Wq;
+            if (!seen) wbytes += (scheme == 4) ? (double)q.N * K / 2 + (double)q.N * (K / 64) * 2 : (double)q.N * K + (double)q.N * 2;
             nsum += (double)q.N;
         }
     }
@@ -777,7 +779,7 @@ hipError_t launch_qskinny_fwd(const void* X, const QskinnyJob* jobs, int count, 
     const int slot = prof_begin(scheme == 4 ? "qskinny_fwd<int4>" : "qskinny_fwd<int8>", 2.0 * M * K * nsum,
                                 wbytes + 2.0 * M * K + 4.0 * p.splits * M * nsum + 2.0 * M * nsum, st);
 #define FHPC_MAIN(SCHEME, TT, SD)                                                                                   \
-    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT, SD>), grid, dim3(NT), 0, st, X, jb, part, (int)M, (int)K,    \
+    hipLaunchKernelGGL((qskinny_fwd_kernel<SCHEME, TT, SD>), grid, dim3(NT), 0, st, jb, part, (int)M, (int)K,       \
                        p.k_chunk, hpart, (int)r, p.kchunks, head_grid, p.splits, tickets, hsum, poll_limit)
     const int tt = (M <= 16) ? 1 : (M <= 32) ? 2 : 4;
     const bool deep = step_depth(tt, K) == 512;
