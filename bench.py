@@ -30,10 +30,13 @@ def profiled_traffic(workload, kernel):
     import glob
     import os
     import re
-    m = re.match(r"gemm_pp<(\d+)x(\d+)x(\d+),a(\d),b(\d),o(\d)(,p)?>", kernel)
+    m = re.match(r"gemm_pp<(\d+)x(\d+)x(\d+),a(\d),b(\d),o(\d)(?:,gate(\d))?>", kernel)
     if m:
         bm, bn, bk, a, b, o = (int(v) for v in m.groups()[:6])
-        pat = re.compile(r"gemm_pp_kernel<%d, %d, %d, [^>]*?%d, %d, %d>" % (bm, bn, bk, a, b, o))
+        gate = int(m.group(7) or 0)
+        # template arguments as the profiler prints them: tile, k-split flag, ring depth, operand modes, output, gate
+        tail = r"(?:, 0)?>" if gate == 0 else r", %d>" % gate
+        pat = re.compile(r"gemm_pp_kernel<%d, %d, %d, (?:true|false), \d+, %d, %d, %d%s" % (bm, bn, bk, a, b, o, tail))
     else:
         pat = re.compile(re.escape(kernel.split("<")[0]))
     here = os.path.dirname(os.path.abspath(__file__))
