@@ -380,14 +380,15 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
             // half wave spread over both halves of the 16-byte slots; the read-back below swaps them again)
             const uint32_t wr_off = (uint32_t)l32 * 128u + (uint32_t)((hi ^ (l32 >> 3)) & 1) * 8u;        // + swizzled chunk
             // The SiLU gate on a tile inside the output: the 16-byte pieces of G (and U) that match the pieces this
-            // lane stores, for the 32 rows i, are requested one block of rows ahead (those of block 0 here, those of
-            // block i + 1 while block i is turned round), so that only the first block waits for memory.
+            // lane stores for a block of 32 rows are requested once the block's accumulators have gone to the patch,
+            // and are on their way while the block is read back.  (Requesting one block ahead was measured: the 16 to
+            // 32 registers it needs while all accumulators are live end in spills, and the launch gets slower.)
             const uint32_t gate_bytes = (uint32_t)p.M * ldc_b;
             const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(GATE ? p.gate_g : out_c), 0, (int)gate_bytes, 0x00020000);
             const __amdgpu_buffer_rsrc_t rs_u = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(GATE == 2 ? p.gate_u : out_c), 0, (int)gate_bytes, 0x00020000);
             const __amdgpu_buffer_rsrc_t rs_o1 = __builtin_amdgcn_make_buffer_rsrc(GATE ? p.gate_out1 : out_c, 0, (int)gate_bytes, 0x00020000);
             const __amdgpu_buffer_rsrc_t rs_o2 = __builtin_amdgcn_make_buffer_rsrc(GATE == 2 ? p.gate_out2 : out_c, 0, (int)gate_bytes, 0x00020000);
-            u32x4 gq[2][4], uq[2][4];
+            u32x4 gq[4], uq[4];
             auto gate_requests = [&](int i, u32x4 (&g4)[4], u32x4 (&u4)[4]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
 #ifdef FHPC_DIAG
                 if (p.dbg & 16) continue;                      // probe: no read-back, no stores
 #endif
-                if (GATE != 0 && inside) gate_requests(i, gq[i & 1], uq[i & 1]);
+                if (GATE != 0 && inside) gate_requests(i, gq, uq);
                 if (inside && GATE != 0) {
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
@@ -428,12 +429,12 @@ __global__ __launch_bounds__(NT) void gemm_pp_kernel(GemmArgs p)
                         if (GATE == 1) {
                             o1 = v;
 #pragma unroll
-                            for (int e = 0; e < 4; e++) o2[e] = gate::fwd_pair(gq[i & 1][q][e], v[e]);
+                            for (int e = 0; e < 4; e++) o2[e] = gate::fwd_pair(gq[q][e], v[e]);
                         } else {
 #pragma unroll
                             for (int e = 0; e < 4; e++) {
                                 uint32_t a, b;
-                                gate::bwd_pair(gq[i & 1][q][e], uq[i & 1][q][e], v[e], a, b);
+                                gate::bwd_pair(gq[q][e], uq[q][e], v[e], a, b);
                                 o1[e] = a; o2[e] = b;
                             }
                         }
