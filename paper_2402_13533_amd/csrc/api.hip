@@ -413,8 +413,7 @@ Scratch carve(Carver& c, int op, int64_t M, int64_t K, int64_t r, int64_t N, int
     if (op == FHPC_OP_LOWRANK_FWD) upto(product_part_bytes(M, N, rp));     // Y  = H B
     if (op == FHPC_OP_LOWRANK_BWD) upto(product_part_bytes(M, K, rp));     // dX = dH A^T
     if (bwd) {
-        upto(split_bytes(K, rp, rp, M));               // dA = X^T dH
-        upto(split_bytes(rp, N, N, M));                // dB = H^T dY
+        upto(split_bytes(K, rp, rp, M) + split_bytes(rp, N, N, M));   // dA = X^T dH and dB = H^T dY, slabs side by side
     }
     s.part = static_cast<float*>(c.take(part));
     s.part_bytes = part;
@@ -678,6 +677,34 @@ int weight_grads(const void* X, const void* dY, const void* H, const void* dH, f
     if ((dA || dB) && token_outer_supports(M) && (M <= 32 || rp * (K + N) <= ((int64_t)8 << 20))) {
         FHPC_LAUNCH(run, launch_token_outer_grads(X, dH, dA, H, dY, dB, M, K, r, rp, N, alpha, st));
         return FHPC_OK;
+    }
+    if (dA && dB) {
+        // both reductions in slices, both sums small: the two slab sets sit side by side and one launch adds both
+        const SplitPlan pa = plan_split(K, rp, M), pb = plan_split(rp, N, M);
+        const int64_t na = K * rp, nb = rp * N;
+        if (pa.splits > 1 && pb.splits > 1 && sum_slabs_is_small(na, pa.splits) && sum_slabs_is_small(nb, pb.splits) &&
+            run.claim(((int64_t)pa.splits * na + (int64_t)pb.splits * nb) * 4)) {
+            float* const da = (rp == r) ? dA : s.dA_t;
+            float* const db = (rp == r) ? dB : s.dB_t;
+            float* const part_b = s.part + (int64_t)pa.splits * na;
+            if (!run.dry) {
+                GemmArgs g = {};
+                g.a = operand(X, K); g.b = operand(dH, rp); g.c = s.part; g.ldc = rp;
+                g.M = (int)K; g.N = (int)rp; g.K = (int)M; g.alpha = alpha; g.mid_scale = 1.f;
+                g.splits = pa.splits; g.k_chunk = pa.k_chunk; g.split_stride = na;
+                FHPC_HIP(launch_gemm_bf16(OP_XC, OP_XC, OP_NONE, OUT_F32, pa.tile, g, st));
+                g.a = operand(H, rp); g.b = operand(dY, N); g.c = part_b; g.ldc = N;
+                g.M = (int)rp; g.N = (int)N;
+                g.splits = pb.splits; g.k_chunk = pb.k_chunk; g.split_stride = nb;
+                FHPC_HIP(launch_gemm_bf16(OP_XC, OP_XC, OP_NONE, OUT_F32, pb.tile, g, st));
+                FHPC_HIP(launch_sum_slabs_pair(s.part, na, pa.splits, da, part_b, nb, pb.splits, db, st));
+                if (rp != r) {
+                    FHPC_HIP(launch_compact_f32(s.dA_t, rp, dA, r, K, r, 1.f, false, st));
+                    FHPC_HIP(launch_compact_f32(s.dB_t, N, dB, N, r, N, 1.f, false, st));
+                }
+            }
+            return FHPC_OK;
+        }
     }
     if (dA) {
         float* dst = (rp == r) ? dA : s.dA_t;

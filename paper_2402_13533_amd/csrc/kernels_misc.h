@@ -29,6 +29,11 @@ hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64
                               float scale, bool to_bf16, hipStream_t s);
 // out: fp32, or bf16 when to_bf16 (n a multiple of 4)
 hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out, bool to_bf16, hipStream_t s);
+// Two fp32 slab sums in one launch, bit for bit the sums launch_sum_slabs forms; for sums launch_sum_slabs would not
+// hand to its wide kernel (sum_slabs_is_small).
+bool sum_slabs_is_small(int64_t n, int nslab);
+hipError_t launch_sum_slabs_pair(const float* slabs0, int64_t n0, int nslab0, float* out0,
+                                 const float* slabs1, int64_t n1, int nslab1, float* out1, hipStream_t s);
 // C = A' B in fp32 on the matrix cores, A' = A or A^T; dimensions multiples of 4, rows 16-byte aligned
 hipError_t launch_mm_f32(const float* A, bool transpose_a, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                          int64_t M, int64_t N, int64_t K, hipStream_t s);

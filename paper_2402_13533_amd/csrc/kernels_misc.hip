@@ -670,6 +670,43 @@ __global__ __launch_bounds__(256) void sum_slabs_kernel(const float* __restrict_
     }
 }
 
+// Two small slab sums in one launch (the two rank-r weight gradients of a layer: a launch each would cost more in
+// launch latency than in work).  Block b < blocks[0] belongs to the first sum, the others to the second; within a sum
+// the arithmetic and its order are those of sum_slabs_kernel<false>.
+struct SlabSumPair {
+    const float* slabs[2];
+    float* out[2];
+    int64_t slab[2], n4[2];
+    int nslab[2];
+    int blocks[2];
+};
+__global__ __launch_bounds__(256) void sum_slabs_pair_kernel(SlabSumPair p)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    __shared__ f32x4 red[3][64];
+    const int which = ((int)blockIdx.x < p.blocks[0]) ? 0 : 1;
+    const float* const slabs = which ? p.slabs[1] : p.slabs[0];
+    float* const out = which ? p.out[1] : p.out[0];
+    const int64_t slab = which ? p.slab[1] : p.slab[0], n4 = which ? p.n4[1] : p.n4[0];
+    const int nslab = which ? p.nslab[1] : p.nslab[0];
+    const int nblocks = which ? p.blocks[1] : p.blocks[0];
+    const int block = (int)blockIdx.x - (which ? p.blocks[0] : 0);
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int64_t base = (int64_t)block * 64; base < n4; base += (int64_t)nblocks * 64) {
+        const int64_t i = base + lane;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+        if (i < n4)
+            for (int s = g; s < nslab; s += 4) a += reinterpret_cast<const f32x4*>(slabs + (int64_t)s * slab)[i];
+        if (g > 0) red[g - 1][lane] = a;
+        __syncthreads();
+        if (g == 0 && i < n4) {
+            a = ((a + red[0][lane]) + red[1][lane]) + red[2][lane];
+            reinterpret_cast<f32x4*>(out)[i] = a;
+        }
+        __syncthreads();
+    }
+}
+
 // Large outputs with few slabs: one thread per float4 output adds its slabs in order.
 __global__ __launch_bounds__(256) void sum_slabs_wide_kernel(const float* __restrict__ slabs, int64_t slab, int nslab,
                                                              float* __restrict__ out, int64_t n4)
@@ -697,6 +734,30 @@ hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out,
     if (blocks > 16384) blocks = 16384;
     if (to_bf16) hipLaunchKernelGGL(sum_slabs_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
     else hipLaunchKernelGGL(sum_slabs_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
+    return hipGetLastError();
+}
+
+bool sum_slabs_is_small(int64_t n, int nslab)
+{
+    return !(nslab <= 8 && n / 4 >= 65536);
+}
+
+hipError_t launch_sum_slabs_pair(const float* slabs0, int64_t n0, int nslab0, float* out0,
+                                 const float* slabs1, int64_t n1, int nslab1, float* out1, hipStream_t s)
+{
+    SlabSumPair p;
+    const float* sl[2] = {slabs0, slabs1};
+    float* o[2] = {out0, out1};
+    const int64_t n[2] = {n0, n1};
+    const int ns[2] = {nslab0, nslab1};
+    for (int i = 0; i < 2; i++) {
+        p.slabs[i] = sl[i]; p.out[i] = o[i]; p.slab[i] = n[i]; p.n4[i] = n[i] / 4; p.nslab[i] = ns[i];
+        int64_t blocks = (p.n4[i] + 63) / 64;
+        if (blocks > 8192) blocks = 8192;
+        if (blocks < 1) blocks = 1;
+        p.blocks[i] = (int)blocks;
+    }
+    hipLaunchKernelGGL(sum_slabs_pair_kernel, dim3((unsigned)(p.blocks[0] + p.blocks[1])), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
