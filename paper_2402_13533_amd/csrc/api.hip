@@ -607,11 +607,22 @@ static hipError_t gemm_gated(int b_mode, GemmOperand a, GemmOperand b, void* P, 
     return launch_gemm_bf16(OP_KC, b_mode, OP_NONE, OUT_BF16, TILE_256x256, g, run.st);
 }
 
+// A rank-r output of many rows whose operands both have the reduction contiguous (dH = dY B^T) goes out as one launch
+// of 16-row workgroups that own the whole reduction, without slabs and their sum, once there are rows enough for
+// half the compute units (C4's backward: 11.6 + 4.5 microseconds of product and slab sum become one launch, the step
+// 1.262 -> 1.253 ms).
+static bool tall_skinny_pays(int64_t M) { return M >= 8 * (int64_t)num_cu(); }
+
 // Rank-r product P[M][rp] (bf16) = L * R where the output is only rp <= 32 wide:
 // split the long reduction, accumulate in fp32, then round once to bf16.
 hipError_t rank_product(int b_mode, GemmOperand a, GemmOperand b, void* P, int64_t rp, float* Pf, float* part,
                         int64_t M, int64_t Kred, Run& run)
 {
+    if (rp <= 32 && b_mode == OP_KC && (Kred % 32) == 0 && tall_skinny_pays(M)) {
+        // many rows, both operands with the reduction contiguous (dH = dY B^T): one launch that owns the whole reduction
+        if (run.dry) return hipSuccess;
+        return launch_tall_skinny_kc(a.ptr, a.ld, b.ptr, b.ld, P, M, rp, Kred, run.st);
+    }
     if (rp <= 32) {
         bool done = false;
         hipError_t e = gemm_split_f32(OP_KC, b_mode, a, b, Pf, rp, M, rp, Kred, 1.f, part, run, P, &done);

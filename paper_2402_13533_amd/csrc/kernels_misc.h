@@ -31,6 +31,10 @@ hipError_t launch_compact_f32(const float* src, int64_t ld_src, void* dst, int64
 hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out, bool to_bf16, hipStream_t s);
 // Two fp32 slab sums in one launch, bit for bit the sums launch_sum_slabs forms; for sums launch_sum_slabs would not
 // hand to its wide kernel (sum_slabs_is_small).
+// P[M][rp] bf16 = L[M][Kred] (row stride ldl) * R[rp][Kred]^T (row stride ldr), rp <= 32, Kred a multiple of 32, the strides multiples of 8,
+// 16-byte aligned rows: one launch without partial-sum slabs, for outputs of many rows.
+hipError_t launch_tall_skinny_kc(const void* L, int64_t ldl, const void* R, int64_t ldr, void* P, int64_t M, int64_t rp,
+                                 int64_t Kred, hipStream_t s);
 bool sum_slabs_is_small(int64_t n, int nslab);
 hipError_t launch_sum_slabs_pair(const float* slabs0, int64_t n0, int nslab0, float* out0,
                                  const float* slabs1, int64_t n1, int nslab1, float* out1, hipStream_t s);

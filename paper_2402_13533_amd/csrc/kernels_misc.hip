@@ -4,6 +4,8 @@
 #include "gate_math.h"
 #include "profile.h"
 
+#include <type_traits>
+
 namespace fhpc {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -707,6 +709,77 @@ __global__ __launch_bounds__(256) void sum_slabs_pair_kernel(SlabSumPair p)
     }
 }
 
+// P[M][rp] (bf16) = L[M][Kred] * R[rp][Kred]^T for a rank-r output of many rows (rp <= 32, both operands with the
+// reduction index contiguous: dH = dY B^T).  The output is too narrow for the GEMM tiles, which have to cut the
+// reduction into slices and add slabs afterwards; here a workgroup owns 16 rows and the whole reduction: its eight
+// waves take an eighth of it each, both operands of v_mfma_f32_16x16x32_bf16 come straight from memory as the 16
+// bytes a lane needs (eight consecutive k of its row), and the partial tiles meet in LDS.  One launch, no slabs.
+typedef __attribute__((ext_vector_type(8))) __bf16 ts_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float ts_f32x4;
+constexpr int TS_UNROLL = 8, TS_WAVES = 8;
+__global__ __launch_bounds__(64 * TS_WAVES) void tall_skinny_kc_kernel(const uint16_t* __restrict__ L, int64_t ldl, const uint16_t* __restrict__ R,
+                                                             int64_t ldr, uint16_t* __restrict__ P, int M, int rp, int Kred)
+{
+    __shared__ ts_f32x4 red[TS_WAVES - 1][2][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 15, g = lane >> 4;
+    const int row0 = (int)blockIdx.x * 16;
+    const int steps = Kred / 32;                         // 32-deep steps of the whole reduction (Kred is a multiple of 32)
+    const int per = (steps + TS_WAVES - 1) / TS_WAVES;
+    const int s0 = wave * per, s1 = (s0 + per < steps) ? s0 + per : steps;
+    const bool row_ok = row0 + lr < M;
+    const bool r0_ok = lr < rp, r1_ok = 16 + lr < rp;
+    const bool two = rp > 16;
+    // Rows that do not exist read as zero through the buffer bounds; the position along k travels in the scalar
+    // offset.  (A select behind every load would make the compiler wait for each load in turn.)
+    constexpr uint32_t OOB = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(L), 0, (int)((int64_t)M * ldl * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(R), 0, (int)((int64_t)rp * ldr * 2), 0x00020000);
+    const uint32_t la = row_ok ? (uint32_t)((int64_t)(row0 + lr) * ldl * 2) + 16u * g : OOB;
+    const uint32_t lb0 = r0_ok ? (uint32_t)((int64_t)lr * ldr * 2) + 16u * g : OOB;
+    const uint32_t lb1 = r1_ok ? (uint32_t)((int64_t)(16 + lr) * ldr * 2) + 16u * g : OOB;
+    ts_f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    auto batch = [&](int sb, auto NU) __attribute__((always_inline)) {
+        constexpr int nu = decltype(NU)::value;
+        u32x4_t a[nu], b0[nu], b1[nu];
+#pragma unroll
+        for (int u = 0; u < nu; u++) {
+            const int kb = (sb + u) * 64;                // byte position of the 32-deep step in a row
+            a[u] = __builtin_amdgcn_raw_buffer_load_b128(rl, la, kb, 0);
+            b0[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, lb0, kb, 0);
+            if (two) b1[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, lb1, kb, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < nu; u++) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(ts_bf16x8, a[u]), __builtin_bit_cast(ts_bf16x8, b0[u]), acc0, 0, 0, 0);
+            if (two) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(ts_bf16x8, a[u]), __builtin_bit_cast(ts_bf16x8, b1[u]), acc1, 0, 0, 0);
+        }
+    };
+    int sb = s0;
+    for (; sb + TS_UNROLL <= s1; sb += TS_UNROLL) batch(sb, std::integral_constant<int, TS_UNROLL>{});
+    for (; sb < s1; sb++) batch(sb, std::integral_constant<int, 1>{});
+    if (wave > 0) {
+        red[wave - 1][0][lane] = acc0;
+        red[wave - 1][1][lane] = acc1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // lane holds rows row0 + 4 g + v (from the row operand), rank lr (+ 16): the waves' shares added in wave order
+#pragma unroll
+        for (int w = 0; w < TS_WAVES - 1; w++) {
+            acc0 += red[w][0][lane];
+            acc1 += red[w][1][lane];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+            const int m = row0 + 4 * g + v;
+            if (m < M) {
+                if (r0_ok) P[(int64_t)m * rp + lr] = float_to_bf16_bits(acc0[v]);
+                if (r1_ok) P[(int64_t)m * rp + 16 + lr] = float_to_bf16_bits(acc1[v]);
+            }
+        }
+    }
+}
+
 // Large outputs with few slabs: one thread per float4 output adds its slabs in order.
 __global__ __launch_bounds__(256) void sum_slabs_wide_kernel(const float* __restrict__ slabs, int64_t slab, int nslab,
                                                              float* __restrict__ out, int64_t n4)
@@ -734,6 +807,19 @@ hipError_t launch_sum_slabs(const float* slabs, int64_t n, int nslab, void* out,
     if (blocks > 16384) blocks = 16384;
     if (to_bf16) hipLaunchKernelGGL(sum_slabs_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
     else hipLaunchKernelGGL(sum_slabs_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, slabs, n, nslab, out, n4);
+    return hipGetLastError();
+}
+
+hipError_t launch_tall_skinny_kc(const void* L, int64_t ldl, const void* R, int64_t ldr, void* P, int64_t M, int64_t rp,
+                                 int64_t Kred, hipStream_t s)
+{
+    if (M <= 0) return hipSuccess;
+    if (rp < 1 || rp > 32 || (Kred % 32) != 0 || (ldl % 8) != 0 || (ldr % 8) != 0 || M * ldl * 2 >= ((int64_t)1 << 31))
+        return hipErrorInvalidValue;
+    const int slot = prof_begin("tall_skinny<kc>", 2.0 * M * rp * (double)Kred, 0.0, s);
+    hipLaunchKernelGGL(tall_skinny_kc_kernel, dim3((unsigned)((M + 15) / 16)), dim3(64 * TS_WAVES), 0, s, static_cast<const uint16_t*>(L), ldl,
+                       static_cast<const uint16_t*>(R), ldr, static_cast<uint16_t*>(P), (int)M, (int)rp, (int)Kred);
+    prof_end(slot, s);
     return hipGetLastError();
 }
 

@@ -142,6 +142,8 @@ def _run_case(tag, scheme, M, K, r, N, s, config, tensor_base=0, rows=None):
     (2048, 320, 8, 264),
     (2100, 384, 5, 520),      # ragged in every dimension, rank padded internally
     (2300, 576, 40, 136),
+    (2100, 384, 5, 544),      # many rows, a channel count in whole 32-deep steps: dH = dY B^T in one launch that owns the reduction
+    (2070, 256, 24, 1056),    # the same with two rank tiles, the second half empty
 ])
 def test_qlinear_many_tokens(scheme, M, K, r, N):
     """From 1152 tokens on: base_scale deq(W) + scaling A B is written once as bf16 and Y, dX are plain
